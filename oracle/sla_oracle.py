@@ -1,0 +1,125 @@
+"""ctypes wrapper around the fp64 CPU oracle (oracle/sla_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, the smoke check and the benchmark's
+cpu_baseline leg.  It never imports the GPU package and the GPU package never imports it.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sla_oracle.c")
+_LIB = os.path.join(_HERE, "libsla_oracle.so")
+_lib = None
+
+
+class Params(C.Structure):
+    _fields_ = [("B", C.c_int32), ("H", C.c_int32), ("N", C.c_int32), ("D", C.c_int32),
+                ("bq", C.c_int32), ("bk", C.c_int32), ("k_crit", C.c_int32), ("k_neg", C.c_int32),
+                ("dtype", C.c_int32), ("proj_per_head", C.c_int32), ("sm_scale", C.c_double)]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fast-math, no FMA contraction; fma() is explicit)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-ffp-contract=off", "-mfma",
+               "-Wall", "-Wextra", "-Werror", _SRC, "-o", _LIB, "-lm"]
+        subprocess.check_call(cmd)
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        _lib.sla_oracle_threads.restype = C.c_int
+        for f in (_lib.sla_oracle_classify, _lib.sla_oracle_states_head, _lib.sla_oracle_attend):
+            f.restype = C.c_int
+    return _lib
+
+
+def threads() -> int:
+    return int(lib().sla_oracle_threads())
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def counts(crit_frac: float, neg_frac: float, Nkb: int):
+    kc, kn = C.c_int32(), C.c_int32()
+    lib().sla_oracle_counts(C.c_double(crit_frac), C.c_double(neg_frac), C.c_int32(Nkb), C.byref(kc), C.byref(kn))
+    return kc.value, kn.value
+
+
+def make_params(B, H, N, bq, bk, k_crit, k_neg, dtype="bf16", proj_per_head=False, sm_scale=None, D=64):
+    return Params(B, H, N, D, bq, bk, k_crit, k_neg, 0 if dtype == "bf16" else 1,
+                  1 if proj_per_head else 0, (1.0 / np.sqrt(D)) if sm_scale is None else sm_scale)
+
+
+def _chk(x, dt):
+    assert x is None or (x.dtype == dt and x.flags["C_CONTIGUOUS"]), (None if x is None else x.dtype, dt)
+
+
+def classify(p: Params, Q, K, sQ=None, sK=None, want_scores=False, want_pc=False, want_means=False):
+    """Steps 1-4.  Returns dict(labels, scores?, Pc?, qbar?, kbar?)."""
+    dt = np.uint16 if p.dtype == 0 else np.uint8
+    _chk(Q, dt), _chk(K, dt), _chk(sQ, np.float32), _chk(sK, np.float32)
+    Nqb, Nkb = -(-p.N // p.bq), -(-p.N // p.bk)
+    shp = (p.B, p.H, Nqb, Nkb)
+    out = {"labels": np.zeros(shp, np.int8)}
+    out["scores"] = np.zeros(shp, np.float64) if want_scores else None
+    out["Pc"] = np.zeros(shp, np.float64) if want_pc else None
+    out["qbar"] = np.zeros((p.B, p.H, Nqb, 64)) if want_means else None
+    out["kbar"] = np.zeros((p.B, p.H, Nkb, 64)) if want_means else None
+    rc = lib().sla_oracle_classify(C.byref(p), _p(Q), _p(K), _p(sQ), _p(sK), _p(out["labels"]),
+                                   _p(out["scores"]), _p(out["Pc"]), _p(out["qbar"]), _p(out["kbar"]))
+    assert rc == 0, rc
+    return out
+
+
+def states_head(p: Params, K, V, sK, sV, bh: int):
+    """Step 6a for one (b,h): h [Nkb,64,64] (h[j][d][e]), z [Nkb,64]."""
+    Nkb = -(-p.N // p.bk)
+    h = np.zeros((Nkb, 64, 64)); z = np.zeros((Nkb, 64))
+    rc = lib().sla_oracle_states_head(C.byref(p), _p(K), _p(V), _p(sK), _p(sV), C.c_int32(bh), _p(h), _p(z))
+    assert rc == 0, rc
+    return h, z
+
+
+def attend(p: Params, Q, K, V, W, labels, sel=None, sQ=None, sK=None, sV=None, want_parts=False):
+    """Steps 5-7 on the query blocks in `sel` (list of (bh, i)); None = all blocks.
+
+    Returns dict(O [n_sel,bq,64], O_sparse?, O_lin?, sel)."""
+    dt = np.uint16 if p.dtype == 0 else np.uint8
+    _chk(Q, dt), _chk(K, dt), _chk(V, dt), _chk(W, np.uint16), _chk(labels, np.int8)
+    Nqb = -(-p.N // p.bq)
+    if sel is None:
+        sel = [(bh, i) for bh in range(p.B * p.H) for i in range(Nqb)]
+    sel_bh = np.ascontiguousarray([s[0] for s in sel], dtype=np.int32)
+    sel_i = np.ascontiguousarray([s[1] for s in sel], dtype=np.int32)
+    n = len(sel)
+    O = np.zeros((n, p.bq, 64))
+    Osp = np.zeros((n, p.bq, 64)) if want_parts else None
+    Olin = np.zeros((n, p.bq, 64)) if want_parts else None
+    rc = lib().sla_oracle_attend(C.byref(p), _p(Q), _p(K), _p(V), _p(sQ), _p(sK), _p(sV), _p(W), _p(labels),
+                                 C.c_int32(n), _p(sel_bh), _p(sel_i), _p(O), _p(Osp), _p(Olin))
+    assert rc == 0, rc
+    return {"O": O, "O_sparse": Osp, "O_lin": Olin, "sel": sel}
+
+
+def forward(p: Params, Q, K, V, W, sQ=None, sK=None, sV=None, sel=None, want_parts=False):
+    """Whole SLA forward: classify, then attend.  With sel=None, O is scattered to [B,H,N,64]."""
+    c = classify(p, Q, K, sQ, sK)
+    a = attend(p, Q, K, V, W, c["labels"], sel, sQ, sK, sV, want_parts)
+    a["labels"] = c["labels"]
+    if sel is None:
+        Nqb = -(-p.N // p.bq)
+        for k in ("O", "O_sparse", "O_lin"):
+            if a[k] is not None:
+                a[k] = a[k].reshape(p.B, p.H, Nqb * p.bq, 64)[:, :, :p.N, :]
+    return a

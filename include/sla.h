@@ -1,0 +1,147 @@
+/*
+ * sla.h -- C ABI of the MI355X (gfx950) Sparse Linear Attention forward.
+ *
+ * The operator (paper eq. (1), App. A, Alg. 1):
+ *     O = A_sparse(Q,K,V) + Proj(A_lin(Q,K,V))
+ * evaluated at block granularity, the way the SLA module the paper adopts works:
+ *   1. Q and K are mean-pooled over blocks of bq / bk tokens; the pooled logits
+ *      s_ij = qbar_i . kbar_j (Alg. 1 step 2 on block means) rank the key blocks of every
+ *      query block; the top k_crit are "critical", the bottom k_neg "negligible", the rest
+ *      "marginal" (Alg. 1 step 3, TopKMask, at block level).
+ *   2. Sparse branch (Alg. 1 steps 4-5): softmax(Q K^T * sm_scale) V restricted to the
+ *      tokens of the critical blocks (masked-out keys are excluded from the softmax).
+ *   3. Linear branch (Alg. 1 steps 6-9) with phi = softmax over the head dimension:
+ *      h_j = phi(K_j)^T V_j, z_j = sum_t phi(K_j,t) per key block, summed over the marginal
+ *      blocks of a query block: O_lin = phi(Q) H_i / (phi(Q) . Z_i); 0 if there is none.
+ *   4. Combine (Alg. 1 step 10): O = O_sparse + O_lin W_proj.
+ * Negligible blocks contribute to neither branch.
+ *
+ * Conventions common to every entry point
+ *   - All tensor pointers are DEVICE pointers unless the comment says "host".  Tensors are
+ *     dense, row-major, last index fastest: Q, K, V, O are [B, H, N, D] with D = 64.
+ *   - bf16 tensors are raw 16-bit patterns; fp8 tensors are OCP E4M3 ("e4m3fn", max 448,
+ *     App. B.1) codes with one fp32 scale per (b, h, token block): value = code * scale.
+ *     Scale blocks are the pooling blocks: bq tokens for Q, bk tokens for K and V.
+ *   - The caller owns all memory, including the workspace.  The library never allocates,
+ *     frees or synchronises; every kernel is enqueued on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream).  Inputs are read-only; outputs and workspace must
+ *     not alias inputs or each other.  Pointers must be 16-byte aligned (256 for workspace).
+ *   - Every function returns a status; parameter errors are detected on the host before any
+ *     launch.  No C++ exception crosses the boundary.  sla_last_error() returns a
+ *     thread-local description of the most recent failure on the calling thread.
+ *   - Calls on distinct streams with distinct workspaces may run concurrently.
+ *
+ * Block labels (int8): 2 = critical, 1 = marginal, 0 = negligible.  One total order per
+ * row decides them: pooled logit descending, then key-block index ascending; critical =
+ * first k_crit entries, negligible = last k_neg entries.
+ */
+#ifndef SLA_H_
+#define SLA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SLA_OK = 0,
+    SLA_ERR_INVALID_ARG = -1,   /* null pointer, bad shape, fraction out of range, misaligned pointer */
+    SLA_ERR_UNSUPPORTED = -2,   /* valid request this build does not implement (D != 64, bk != 64, ...) */
+    SLA_ERR_WORKSPACE = -3,     /* workspace too small or misaligned */
+    SLA_ERR_HIP = -4            /* a HIP launch failed */
+} sla_status_t;
+
+typedef enum { SLA_BF16 = 0, SLA_FP8_E4M3 = 1 } sla_dtype_t;
+typedef enum { SLA_PHI_SOFTMAX = 0 } sla_phi_t;   /* feature map of Alg. 1 step 6: softmax over D */
+
+typedef struct {
+    int32_t B, H, N, D;          /* batch, heads, tokens per (b,h), head dim (must be 64) */
+    int32_t bq, bk;              /* query block (64 or 128) and key block (64) sizes */
+    double  crit_frac, neg_frac; /* fractions of key blocks per query block, in [0,1], sum <= 1 */
+    int32_t k_crit, k_neg;       /* explicit block counts; -1 = derive from the fractions:
+                                    k_crit = crit_frac > 0 ? max(1, floor(crit_frac*Nkb + 0.5)) : 0,
+                                    k_neg  = min(Nkb - k_crit, floor(neg_frac*Nkb + 0.5)) */
+    int32_t dtype;               /* sla_dtype_t of Q, K, V */
+    int32_t phi;                 /* sla_phi_t */
+    int32_t proj_per_head;       /* 0: W_proj is [D, D]; 1: [H, D, D] */
+    float   sm_scale;            /* softmax scale of the sparse branch; 0 = 1/sqrt(D) (section 3.3) */
+} sla_params_t;
+
+/* Derived sizes: Nqb = ceil(N/bq), Nkb = ceil(N/bk). */
+
+/* Host only.  Resolves the block counts the other calls will use (see k_crit / k_neg above). */
+sla_status_t sla_resolve_counts(const sla_params_t *p, int32_t *k_crit, int32_t *k_neg);
+
+/* Host only.  Bytes of workspace sla_forward (and every staged call) needs for these params. */
+sla_status_t sla_workspace_bytes(const sla_params_t *p, size_t *bytes);
+
+/*
+ * Whole forward, eq. (1): steps 1-4 above.
+ *   Q, K, V   in   [B,H,N,D] bf16 or E4M3
+ *   sQ,sK,sV  in   fp32 [B,H,Nqb], [B,H,Nkb], [B,H,Nkb]; required for E4M3, NULL for bf16
+ *   W_proj    in   bf16 [D_in, D_out] or [H, D_in, D_out] (right-multiplied, no bias)
+ *   O         out  bf16 [B,H,N,D]
+ *   labels    out  optional int8 [B,H,Nqb,Nkb]; NULL to skip
+ */
+sla_status_t sla_forward(const sla_params_t *p,
+                         const void *Q, const void *K, const void *V,
+                         const float *sQ, const float *sK, const float *sV,
+                         const void *W_proj, void *O, int8_t *labels,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Step 1 alone: block mean-pool, pooled logits, classifier (Alg. 1 steps 2-3 at block level).
+ *   labels    out  int8 [B,H,Nqb,Nkb]                                   (required)
+ *   crit_idx  out  optional int32 [B,H,Nqb,k_crit], ascending key-block indices
+ *   Pc        out  optional fp32 [B,H,Nqb,Nkb], softmax_j(s_ij * sm_scale) (compressed block scores)
+ *   qbar,kbar out  optional fp64 [B,H,Nqb,D], [B,H,Nkb,D] block means
+ *   scores    out  optional fp64 [B,H,Nqb,Nkb] pooled logits (unscaled)
+ * Means are exact block sums (ascending token order, fp64) times 1/count; a logit is the
+ * 64-step fp64 fused-multiply-add chain over the channel index, so labels are reproducible
+ * bit for bit.
+ */
+sla_status_t sla_pool_classify(const sla_params_t *p, const void *Q, const void *K,
+                               const float *sQ, const float *sK,
+                               int8_t *labels, int32_t *crit_idx, float *Pc,
+                               double *qbar, double *kbar, double *scores,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Step 3a alone: per-key-block linear states (Alg. 1 steps 6-8 restricted to one block).
+ *   hT  out  bf16 [B,H,Nkb,65,D]: rows e = 0..63 hold h_j transposed, hT[e][d] = sum_t phi(K_t)[d] V_t[e];
+ *            row 64 holds z_j[d] = sum_t phi(K_t)[d].  Tokens past N contribute nothing.
+ */
+sla_status_t sla_linear_states(const sla_params_t *p, const void *K, const void *V,
+                               const float *sK, const float *sV, void *hT, void *stream);
+
+/*
+ * Step 3b alone: sum of the states over the marginal blocks of each query block.
+ *   labels in   int8 [B,H,Nqb,Nkb]
+ *   hT     in   bf16 [B,H,Nkb,65,D] (from sla_linear_states)
+ *   Hq     out  bf16 [B,H,Nqb,65,D], same row layout as hT
+ */
+sla_status_t sla_marginal_aggregate(const sla_params_t *p, const int8_t *labels, const void *hT,
+                                    void *Hq, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Steps 2, 3c and 4: block-sparse attention over the critical blocks of `labels`, linear
+ * output from Hq, projection and sum.
+ *   labels in   int8 [B,H,Nqb,Nkb]; every row must hold exactly k_crit entries equal to 2
+ *   Hq     in   bf16 [B,H,Nqb,65,D], or NULL: then O = O_sparse only (W_proj may be NULL too)
+ *   O      out  bf16 [B,H,N,D]
+ */
+sla_status_t sla_sparse_combine(const sla_params_t *p,
+                                const void *Q, const void *K, const void *V,
+                                const float *sQ, const float *sK, const float *sV,
+                                const void *W_proj, const int8_t *labels, const void *Hq, void *O,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+const char *sla_strerror(sla_status_t status);
+const char *sla_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLA_H_ */

@@ -1,0 +1,330 @@
+// Block-sparse flash attention over the critical key blocks of each query block, fused with
+// the linear-branch output, the projection and the sum (Alg. 1 steps 4-5, 9, 10; eq. (1)):
+//     O_i = softmax_{t' in critical blocks}(Q_i K_t'^T * scale) V_t'
+//           + [ phi(Q_i) H_i / (phi(Q_i) . Z_i) ] W_proj
+//
+// Work decomposition.  One workgroup per (b, h, query block); each wavefront owns 32 query
+// rows and keeps everything transposed so that a lane owns ONE query row:
+//     S^T[t'][q]  = K_tile (A operand, LDS rows)  x  Q^T (B operand, registers)
+//     O^T[e][q]  += V^T_tile (A operand, LDS)     x  P^T (B operand = the S^T accumulators,
+//                                                   re-used in place: no LDS round trip)
+// With v_mfma_f32_32x32x16_bf16 a lane holds column q = lane%32 of the 32x32 result, rows
+// 8a + 4g + b (g = lane/32; register 4a+b), so the online-softmax row statistics are 31
+// in-lane operations plus one exchange with lane^32.  The B operand of the second product
+// takes accumulator registers 8u..8u+7, i.e. keys 16s + 8a' + 4g + b; the V^T rows are read
+// from LDS with exactly that key permutation (two 8-byte reads), which is why V is staged
+// transposed ([e][t']).  K and V tiles of a critical block are fetched once per workgroup
+// (register prefetch of the next tile while the current one is consumed).
+//
+// Epilogue (per wave, all MFMA): O_lin^T = Hq^T-tile x phi(Q)^T, scaled by 1/(phi(Q).Z),
+// then O^T += W^T x O_lin^T accumulated onto the normalised sparse output, stored as bf16.
+#include "sla_common.hpp"
+#include "sla_kernels.hpp"
+
+namespace sla {
+
+constexpr int kRow = 72;   // bf16 per LDS row (64 + 8 pad)
+constexpr float kLog2e = 1.4426950408889634f;
+
+template <int NW>
+struct TileRegs {
+    static constexpr int T = 64 * NW;
+    static constexpr int KCH = 512 / T;     // 16-byte K chunks per thread
+    static constexpr int VUN = 256 / T;     // V transpose units (2 channels x 8 tokens) per thread
+    uint4 k[KCH];
+    uint32_t v[VUN][8];
+};
+
+template <int NW>
+__device__ __forceinline__ void load_tile_bf16(TileRegs<NW> &r, const uint16_t *Kg, const uint16_t *Vg, int valid, int tid)
+{
+#pragma unroll
+    for (int x = 0; x < TileRegs<NW>::KCH; ++x) {
+        const int c = tid + TileRegs<NW>::T * x, t = c >> 3, col = (c & 7) * 8;
+        r.k[x] = make_uint4(0, 0, 0, 0);
+        if (t < valid) r.k[x] = *(const uint4 *)(Kg + (size_t)t * kD + col);
+    }
+#pragma unroll
+    for (int x = 0; x < TileRegs<NW>::VUN; ++x) {
+        const int u = tid + TileRegs<NW>::T * x, ep = u & 31, tg = u >> 5;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int t = tg * 8 + k;
+            r.v[x][k] = t < valid ? *(const uint32_t *)(Vg + (size_t)t * kD + 2 * ep) : 0u;
+        }
+    }
+}
+
+template <int NW>
+__device__ __forceinline__ void store_tile_bf16(const TileRegs<NW> &r, uint16_t *Ks, uint16_t *Vt, int tid)
+{
+#pragma unroll
+    for (int x = 0; x < TileRegs<NW>::KCH; ++x) {
+        const int c = tid + TileRegs<NW>::T * x, t = c >> 3, col = (c & 7) * 8;
+        *(uint4 *)(Ks + t * kRow + col) = r.k[x];
+    }
+#pragma unroll
+    for (int x = 0; x < TileRegs<NW>::VUN; ++x) {
+        const int u = tid + TileRegs<NW>::T * x, ep = u & 31, tg = u >> 5;
+        const uint32_t *w = r.v[x];
+        uint4 lo, hi;
+        lo.x = __builtin_amdgcn_perm(w[1], w[0], 0x05040100); hi.x = __builtin_amdgcn_perm(w[1], w[0], 0x07060302);
+        lo.y = __builtin_amdgcn_perm(w[3], w[2], 0x05040100); hi.y = __builtin_amdgcn_perm(w[3], w[2], 0x07060302);
+        lo.z = __builtin_amdgcn_perm(w[5], w[4], 0x05040100); hi.z = __builtin_amdgcn_perm(w[5], w[4], 0x07060302);
+        lo.w = __builtin_amdgcn_perm(w[7], w[6], 0x05040100); hi.w = __builtin_amdgcn_perm(w[7], w[6], 0x07060302);
+        *(uint4 *)(Vt + (2 * ep) * kRow + tg * 8) = lo;
+        *(uint4 *)(Vt + (2 * ep + 1) * kRow + tg * 8) = hi;
+    }
+}
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base)
+{
+    uint4 o;
+    o.x = pack_bf16(a[base + 0], a[base + 1]); o.y = pack_bf16(a[base + 2], a[base + 3]);
+    o.z = pack_bf16(a[base + 4], a[base + 5]); o.w = pack_bf16(a[base + 6], a[base + 7]);
+    return __builtin_bit_cast(bf16x8, o);
+}
+
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(
+    const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
+    const int32_t *__restrict__ crit_idx, int k_c, const uint16_t *__restrict__ Hq, const uint16_t *__restrict__ WT,
+    int proj_per_head, int H, int N, int Nqb, int Nkb, long total, float c_exp, uint16_t *__restrict__ O)
+{
+    constexpr int BQ = 32 * NW;
+    __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * kRow];
+    __shared__ __attribute__((aligned(16))) uint16_t Vt[64 * kRow];
+    const long work = xcd_remap(blockIdx.x, total);
+    if (work >= total) return;                        // the whole workgroup leaves together
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    const long bh = work / Nqb;
+    const int i = (int)(work - bh * Nqb);
+    const int q = i * BQ + 32 * wave + l32;           // this lane's query row
+    const bool qok = q < N;
+    const size_t head = (size_t)bh * N * kD;
+
+    bf16x8 qf[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        uint4 w = make_uint4(0, 0, 0, 0);
+        if (qok) w = *(const uint4 *)(Q + head + (size_t)q * kD + 16 * s + 8 * g);
+        qf[s] = __builtin_bit_cast(bf16x8, w);
+    }
+
+    f32x16 oacc[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+        for (int x = 0; x < 16; ++x) oacc[e][x] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int32_t *ci = crit_idx + work * (long)k_c;
+    TileRegs<NW> regs;
+    int jn = k_c > 0 ? ci[0] : -1;
+    if (jn >= Nkb) jn = -1;                          // never trust an index list blindly
+    if (jn >= 0) load_tile_bf16<NW>(regs, K + head + (size_t)jn * kBK * kD, V + head + (size_t)jn * kBK * kD, min(kBK, N - jn * kBK), tid);
+
+    for (int c = 0; c < k_c; ++c) {
+        const int j = jn;
+        __syncthreads();                               // previous tile consumed by every wave
+        store_tile_bf16<NW>(regs, Ks, Vt, tid);
+        __syncthreads();
+        jn = c + 1 < k_c ? ci[c + 1] : -1;
+        if (jn >= Nkb) jn = -1;
+        if (jn >= 0) load_tile_bf16<NW>(regs, K + head + (size_t)jn * kBK * kD, V + head + (size_t)jn * kBK * kD, min(kBK, N - jn * kBK), tid);
+        if (j < 0) continue;
+        const int valid = min(kBK, N - j * kBK);
+
+        // ---- S^T = K Q^T
+        f32x16 sacc[2];
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) sacc[h2][x] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2) {
+                const bf16x8 kf = *(const bf16x8 *)(Ks + (32 * h2 + l32) * kRow + 16 * s + 8 * g);
+                sacc[h2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[h2], 0, 0, 0);
+            }
+        if (valid < kBK) {
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+                for (int x = 0; x < 16; ++x) {
+                    const int t = 32 * h2 + 8 * (x >> 2) + 4 * g + (x & 3);
+                    if (t >= valid) sacc[h2][x] = -INFINITY;
+                }
+        }
+
+        // ---- online softmax, one query row per lane (shared with lane^32)
+        float mx = sacc[0][0];
+#pragma unroll
+        for (int x = 1; x < 16; ++x) mx = fmaxf(mx, sacc[0][x]);
+#pragma unroll
+        for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sacc[1][x]);
+        mx = fmaxf(mx, xchg32(mx));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = fast_exp2((m_run - m_new) * c_exp);
+        const float mc = m_new * c_exp;
+        float psum = 0.f;
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) {
+                sacc[h2][x] = fast_exp2(fmaf(sacc[h2][x], c_exp, -mc));
+                psum += sacc[h2][x];
+            }
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) oacc[e][x] *= alpha;
+
+        // ---- O^T += V^T P^T
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const bf16x8 pf = pack8(sacc[s >> 1], 8 * (s & 1));
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const uint16_t *vr = Vt + (32 * e + l32) * kRow + 16 * s + 4 * g;
+                const uint2 v0 = *(const uint2 *)vr, v1 = *(const uint2 *)(vr + 8);
+                const bf16x8 vf = __builtin_bit_cast(bf16x8, make_uint4(v0.x, v0.y, v1.x, v1.y));
+                oacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[e], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- normalise the sparse output
+    const float l_tot = l_run + xchg32(l_run);
+    const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+        for (int x = 0; x < 16; ++x) oacc[e][x] *= inv_l;
+
+    if (Hq != nullptr) {
+        // ---- phi(Q): softmax over the 64 channels of the row (this lane holds 32, lane^32 the rest)
+        float x[32];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const uint4 w = __builtin_bit_cast(uint4, qf[s]);
+            x[8 * s + 0] = bf16_lo(w.x); x[8 * s + 1] = bf16_hi(w.x);
+            x[8 * s + 2] = bf16_lo(w.y); x[8 * s + 3] = bf16_hi(w.y);
+            x[8 * s + 4] = bf16_lo(w.z); x[8 * s + 5] = bf16_hi(w.z);
+            x[8 * s + 6] = bf16_lo(w.w); x[8 * s + 7] = bf16_hi(w.w);
+        }
+        float mx = x[0];
+#pragma unroll
+        for (int d = 1; d < 32; ++d) mx = fmaxf(mx, x[d]);
+        mx = fmaxf(mx, xchg32(mx));
+        float sum = 0.f;
+#pragma unroll
+        for (int d = 0; d < 32; ++d) { x[d] = fast_exp2((x[d] - mx) * kLog2e); sum += x[d]; }
+        sum += xchg32(sum);
+        const float inv = 1.0f / sum;
+        const uint16_t *Hi = Hq + (size_t)work * kStateElems;
+        bf16x8 fq[4];
+        float den = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            uint4 o;
+            o.x = pack_bf16(x[8 * s + 0] * inv, x[8 * s + 1] * inv); o.y = pack_bf16(x[8 * s + 2] * inv, x[8 * s + 3] * inv);
+            o.z = pack_bf16(x[8 * s + 4] * inv, x[8 * s + 5] * inv); o.w = pack_bf16(x[8 * s + 6] * inv, x[8 * s + 7] * inv);
+            fq[s] = __builtin_bit_cast(bf16x8, o);
+            const uint4 z = *(const uint4 *)(Hi + 64 * kD + 16 * s + 8 * g);
+            den += bf16_lo(o.x) * bf16_lo(z.x) + bf16_hi(o.x) * bf16_hi(z.x) + bf16_lo(o.y) * bf16_lo(z.y) + bf16_hi(o.y) * bf16_hi(z.y)
+                 + bf16_lo(o.z) * bf16_lo(z.z) + bf16_hi(o.z) * bf16_hi(z.z) + bf16_lo(o.w) * bf16_lo(z.w) + bf16_hi(o.w) * bf16_hi(z.w);
+        }
+        den += xchg32(den);
+        const float inv_den = den > 0.f ? 1.0f / den : 0.f;     // no marginal block: H = Z = 0 and O_lin = 0
+
+        // ---- O_lin^T = Hq^T phi(Q)^T
+        f32x16 lacc[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int y = 0; y < 16; ++y) lacc[e][y] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const bf16x8 hf = *(const bf16x8 *)(Hi + (32 * e + l32) * kD + 16 * s + 8 * g);
+                lacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hf, fq[s], lacc[e], 0, 0, 0);
+            }
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int y = 0; y < 16; ++y) lacc[e][y] *= inv_den;
+
+        // ---- O^T += W^T O_lin^T
+        const uint16_t *Wh = WT + (proj_per_head ? (size_t)(bh % H) * kD * kD : 0);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const bf16x8 pf = pack8(lacc[s >> 1], 8 * (s & 1));
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const uint16_t *wr = Wh + (32 * e + l32) * kD + 16 * s + 4 * g;
+                const uint2 w0 = *(const uint2 *)wr, w1 = *(const uint2 *)(wr + 8);
+                const bf16x8 wf = __builtin_bit_cast(bf16x8, make_uint4(w0.x, w0.y, w1.x, w1.y));
+                oacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, pf, oacc[e], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- store: register 4a+b of oacc[e] is channel 32e + 8a + 4g + b of row q
+    if (qok) {
+        uint16_t *orow = O + head + (size_t)q * kD;
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                uint2 o;
+                o.x = pack_bf16(oacc[e][4 * a + 0], oacc[e][4 * a + 1]);
+                o.y = pack_bf16(oacc[e][4 * a + 2], oacc[e][4 * a + 3]);
+                *(uint2 *)(orow + 32 * e + 8 * a + 4 * g) = o;
+            }
+    }
+}
+
+// W [nW][e_in][e_out] -> WT [nW][e_out][e_in]
+__global__ __launch_bounds__(256) void transpose_w_kernel(const uint16_t *__restrict__ W, uint16_t *__restrict__ WT)
+{
+    const uint16_t *w = W + (size_t)blockIdx.x * kD * kD;
+    uint16_t *o = WT + (size_t)blockIdx.x * kD * kD;
+    for (int idx = threadIdx.x; idx < kD * kD; idx += 256) {
+        const int eo = idx >> 6, ei = idx & 63;
+        o[idx] = w[ei * kD + eo];
+    }
+}
+
+hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st)
+{
+    transpose_w_kernel<<<nW, 256, 0, st>>>((const uint16_t *)W, (uint16_t *)WT);
+    return hipGetLastError();
+}
+
+hipError_t launch_attend(const void *Q, const void *K, const void *V,
+                         const float *sQ, const float *sK, const float *sV, bool fp8,
+                         const int32_t *crit_idx, int k_c, const void *Hq, const void *WT,
+                         int proj_per_head, int B, int H, int N, int bq, float sm_scale,
+                         void *O, hipStream_t st)
+{
+    (void)sQ; (void)sK; (void)sV;
+    if (fp8) return hipErrorNotSupported;
+    const int Nqb = (N + bq - 1) / bq, Nkb = (N + kBK - 1) / kBK;
+    const long total = (long)B * H * Nqb;
+    const unsigned grid = (unsigned)xcd_grid(total);
+    const float c_exp = sm_scale * kLog2e;
+    if (bq == 128)
+        attend_bf16_kernel<4><<<grid, 256, 0, st>>>((const uint16_t *)Q, (const uint16_t *)K, (const uint16_t *)V, crit_idx, k_c,
+                                                    (const uint16_t *)Hq, (const uint16_t *)WT, proj_per_head, H, N, Nqb, Nkb, total, c_exp, (uint16_t *)O);
+    else
+        attend_bf16_kernel<2><<<grid, 128, 0, st>>>((const uint16_t *)Q, (const uint16_t *)K, (const uint16_t *)V, crit_idx, k_c,
+                                                    (const uint16_t *)Hq, (const uint16_t *)WT, proj_per_head, H, N, Nqb, Nkb, total, c_exp, (uint16_t *)O);
+    return hipGetLastError();
+}
+
+}  // namespace sla

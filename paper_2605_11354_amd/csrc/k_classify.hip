@@ -1,0 +1,388 @@
+// Block mean-pool, pooled logits and the three-way block classifier
+// (Alg. 1 steps 2-3 of the paper, evaluated on block means).
+//
+// Reproducibility contract (labels must equal a CPU evaluation bit for bit):
+//   * a block mean is the fp64 sum over the block's tokens in ascending token order times
+//     the fp64 value 1/count -- one thread owns a (block, channel) sum and adds serially;
+//   * a pooled logit is the 64-step fp64 fma chain over the channel index from 0.0;
+//   * the classifier works on the total order (logit descending, index ascending).
+#include "sla_common.hpp"
+#include "sla_kernels.hpp"
+
+namespace sla {
+
+// ------------------------------------------------------------------------------------- pool
+// 8 threads per token block, each owning 8 consecutive channels (16 B of bf16 / 8 B of e4m3
+// per token), serial over the tokens of the block.  Bound: HBM (one streaming read of X).
+template <bool FP8>
+__global__ __launch_bounds__(256) void pool_kernel(const void *__restrict__ X, const float *__restrict__ scales,
+                                                   int N, int blk, int nblk, long units, double *__restrict__ mean)
+{
+    const long u = (long)blockIdx.x * 256 + threadIdx.x;
+    if (u >= units) return;
+    const int c = (int)(u & 7);
+    const long blkid = u >> 3;
+    const long bh = blkid / nblk;
+    const int j = (int)(blkid - bh * nblk);
+    const int t0 = j * blk;
+    const int cnt = min(N - t0, blk);
+    double acc[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc[k] = 0.0;
+    if (FP8) {
+        const uint8_t *x = (const uint8_t *)X + ((size_t)bh * N + t0) * kD + c * 8;
+        const double s = (double)scales[blkid];
+#pragma unroll 8
+        for (int t = 0; t < cnt; ++t) {
+            const uint2 w = *(const uint2 *)(x + (size_t)t * kD);
+            const f32x2 a0 = __builtin_amdgcn_cvt_pk_f32_fp8(w.x, false), a1 = __builtin_amdgcn_cvt_pk_f32_fp8(w.x, true);
+            const f32x2 a2 = __builtin_amdgcn_cvt_pk_f32_fp8(w.y, false), a3 = __builtin_amdgcn_cvt_pk_f32_fp8(w.y, true);
+            acc[0] += (double)a0[0] * s; acc[1] += (double)a0[1] * s;
+            acc[2] += (double)a1[0] * s; acc[3] += (double)a1[1] * s;
+            acc[4] += (double)a2[0] * s; acc[5] += (double)a2[1] * s;
+            acc[6] += (double)a3[0] * s; acc[7] += (double)a3[1] * s;
+        }
+    } else {
+        const uint16_t *x = (const uint16_t *)X + ((size_t)bh * N + t0) * kD + c * 8;
+#pragma unroll 8
+        for (int t = 0; t < cnt; ++t) {
+            const uint4 w = *(const uint4 *)(x + (size_t)t * kD);
+            acc[0] += (double)bf16_lo(w.x); acc[1] += (double)bf16_hi(w.x);
+            acc[2] += (double)bf16_lo(w.y); acc[3] += (double)bf16_hi(w.y);
+            acc[4] += (double)bf16_lo(w.z); acc[5] += (double)bf16_hi(w.z);
+            acc[6] += (double)bf16_lo(w.w); acc[7] += (double)bf16_hi(w.w);
+        }
+    }
+    const double inv = 1.0 / (double)cnt;
+    double *o = mean + blkid * kD + c * 8;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) o[k] = acc[k] * inv;
+}
+
+hipError_t launch_pool(const void *X, const float *scales, bool fp8, int BH, int N, int blk,
+                       double *mean, hipStream_t st)
+{
+    const int nblk = (N + blk - 1) / blk;
+    const long units = (long)BH * nblk * 8;
+    const unsigned grid = (unsigned)((units + 255) / 256);
+    if (fp8) pool_kernel<true><<<grid, 256, 0, st>>>(X, scales, N, blk, nblk, units, mean);
+    else     pool_kernel<false><<<grid, 256, 0, st>>>(X, scales, N, blk, nblk, units, mean);
+    return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------------- scores
+// fp64 register-tiled product: workgroup tile 64(i) x 64(j), thread tile 4 x 4, the channel
+// loop runs in ascending order so every (i,j) accumulator is the canonical fma chain.
+// Bound: fp64 vector FMA (2*Nqb*Nkb*64 flops per head).
+__global__ __launch_bounds__(256) void scores_kernel(const double *__restrict__ qbar, const double *__restrict__ kbar,
+                                                     int Nqb, int Nkb, int pitch, double *__restrict__ S)
+{
+    __shared__ double qs[32][66];
+    __shared__ double ks[32][66];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int j0 = blockIdx.x * 64, i0 = blockIdx.y * 64;
+    const long bh = blockIdx.z;
+    const double *qh = qbar + bh * (long)Nqb * kD;
+    const double *kh = kbar + bh * (long)Nkb * kD;
+    double acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
+
+    for (int dh = 0; dh < 2; ++dh) {
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int idx = tid + 256 * r, row = idx >> 5, d = idx & 31;
+            const int gi = i0 + row, gj = j0 + row;
+            qs[d][row] = gi < Nqb ? qh[(long)gi * kD + dh * 32 + d] : 0.0;
+            ks[d][row] = gj < Nkb ? kh[(long)gj * kD + dh * 32 + d] : 0.0;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int d = 0; d < 32; ++d) {
+            double qv[4], kv[4];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) { qv[a] = qs[d][ty * 4 + a]; kv[a] = ks[d][tx * 4 + a]; }
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc[a][b] = fma(qv[a], kv[b], acc[a][b]);
+        }
+    }
+    double *Sh = S + bh * (long)Nqb * pitch;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const int gi = i0 + ty * 4 + a;
+        if (gi >= Nqb) continue;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int gj = j0 + tx * 4 + b;
+            if (gj < Nkb) Sh[(long)gi * pitch + gj] = acc[a][b];
+        }
+    }
+}
+
+hipError_t launch_scores(const double *qbar, const double *kbar, int BH, int Nqb, int Nkb,
+                         int pitch, double *S, hipStream_t st)
+{
+    dim3 grid((Nkb + 63) / 64, (Nqb + 63) / 64, BH);
+    scores_kernel<<<grid, 256, 0, st>>>(qbar, kbar, Nqb, Nkb, pitch, S);
+    return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------------- select
+// One wavefront per score row; lane l holds the keys of blocks j = m*64 + l.  A key is the
+// bit pattern of the logit mapped so that unsigned ascending order == logit descending
+// order; k-th smallest keys are found with an 8-bit-digit radix select on an LDS histogram
+// (keys are first shifted to the row's [min,max] range so two or three passes suffice), and
+// exact ties are resolved by ascending block index.
+
+__device__ __forceinline__ uint64_t wave_min_u64(uint64_t v)
+{
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t lo = __shfl_xor((uint32_t)v, o, 64), hi = __shfl_xor((uint32_t)(v >> 32), o, 64);
+        const uint64_t w = ((uint64_t)hi << 32) | lo;
+        v = w < v ? w : v;
+    }
+    return v;
+}
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v)
+{
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t lo = __shfl_xor((uint32_t)v, o, 64), hi = __shfl_xor((uint32_t)(v >> 32), o, 64);
+        const uint64_t w = ((uint64_t)hi << 32) | lo;
+        v = w > v ? w : v;
+    }
+    return v;
+}
+__device__ __forceinline__ uint64_t bcast_u64(uint64_t v, int src)
+{
+    const uint32_t lo = __shfl((uint32_t)v, src, 64), hi = __shfl((uint32_t)(v >> 32), src, 64);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// logit -> key with (key ascending) == (logit descending); -0.0 is folded onto +0.0
+__device__ __forceinline__ uint64_t desc_key(double s)
+{
+    uint64_t u = (uint64_t)__double_as_longlong(s == 0.0 ? 0.0 : s);
+    u = (u >> 63) ? ~u : (u | 0x8000000000000000ull);   // ascending with the value
+    return ~u;
+}
+__device__ __forceinline__ double key_to_logit(uint64_t key)
+{
+    uint64_t u = ~key;
+    u = (u >> 63) ? (u & 0x7FFFFFFFFFFFFFFFull) : ~u;
+    return __longlong_as_double((long long)u);
+}
+
+// Finds (T, r): the k smallest (key, index) pairs of the row are exactly the keys < T plus the
+// r lowest-index keys == T.  Requires 1 <= k <= Nkb.  Uniform across the wave.
+template <int KPL>
+__device__ void radix_select(const uint64_t (&key)[KPL], int Nkb, int k, uint32_t *hist, uint64_t &T, int &r)
+{
+    const int lane = threadIdx.x;
+    uint64_t prefix = 0;
+    int kk = k, shift = 56, nb = 0;
+    for (;;) {
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < 4; ++b) hist[lane * 4 + b] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int m = 0; m < KPL; ++m) {
+            const bool cand = (m * 64 + lane < Nkb) && (shift == 56 || (key[m] >> (shift + 8)) == prefix);
+            if (cand) atomicAdd(&hist[(uint32_t)(key[m] >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        uint32_t c[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) c[b] = hist[lane * 4 + b];
+        const uint32_t mine = c[0] + c[1] + c[2] + c[3];
+        uint32_t incl = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t v = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += v;
+        }
+        const uint32_t excl = incl - mine;
+        const bool here = excl < (uint32_t)kk && (uint32_t)kk <= incl;
+        const uint64_t bal = __ballot(here);
+        const int src = __ffsll((long long)bal) - 1;          // exactly one lane
+        uint32_t before = excl, digit = 0, cnt = 0;
+        if (here) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                if (cnt == 0) {
+                    if (before + c[b] >= (uint32_t)kk) { digit = lane * 4 + b; cnt = c[b]; }
+                    else before += c[b];
+                }
+            }
+        }
+        digit = __shfl(digit, src, 64);
+        before = __shfl(before, src, 64);
+        nb = (int)__shfl(cnt, src, 64);
+        prefix = (prefix << 8) | digit;
+        kk -= (int)before;
+        if (nb == 1 || shift == 0) break;
+        shift -= 8;
+    }
+    if (shift == 0) { T = prefix; r = kk; return; }
+    // a single key carries this prefix: fetch it
+    uint64_t found = 0;
+    bool have = false;
+#pragma unroll
+    for (int m = 0; m < KPL; ++m)
+        if ((m * 64 + lane < Nkb) && (key[m] >> shift) == prefix) { found = key[m]; have = true; }
+    const int src = __ffsll((long long)__ballot(have)) - 1;
+    T = bcast_u64(found, src);
+    r = 1;
+}
+
+template <int KPL>
+__global__ __launch_bounds__(64) void select_kernel(const double *__restrict__ S, int pitch, int Nkb, int k_c, int k_n,
+                                                    int8_t *__restrict__ lab_pad, int lab_pitch,
+                                                    int8_t *__restrict__ lab_dense, int32_t *__restrict__ crit_idx,
+                                                    float *__restrict__ Pc, double *__restrict__ S_dense, float sm_scale)
+{
+    __shared__ uint32_t hist[256];
+    const long row = blockIdx.x;
+    const int lane = threadIdx.x;
+    const double *s = S + row * pitch;
+    uint64_t key[KPL];
+    uint64_t kmin = ~0ull, kmax = 0;
+#pragma unroll
+    for (int m = 0; m < KPL; ++m) {
+        const int j = m * 64 + lane;
+        key[m] = ~0ull;
+        if (j < Nkb) {
+            const double v = s[j];
+            if (S_dense) S_dense[row * Nkb + j] = v;
+            key[m] = desc_key(v);
+            kmin = key[m] < kmin ? key[m] : kmin;
+            kmax = key[m] > kmax ? key[m] : kmax;
+        }
+    }
+    kmin = wave_min_u64(kmin);
+    kmax = wave_max_u64(kmax);
+
+    if (Pc) {   // compressed block-score softmax (fp32 output), max logit == smallest key
+        const double smax = key_to_logit(kmin);
+        float e[KPL], sum = 0.f;
+#pragma unroll
+        for (int m = 0; m < KPL; ++m) {
+            e[m] = 0.f;
+            if (m * 64 + lane < Nkb) { e[m] = __expf((float)((key_to_logit(key[m]) - smax) * (double)sm_scale)); sum += e[m]; }
+        }
+        sum = wave_sum(sum);
+        const float inv = 1.f / sum;
+#pragma unroll
+        for (int m = 0; m < KPL; ++m)
+            if (m * 64 + lane < Nkb) Pc[row * Nkb + m * 64 + lane] = e[m] * inv;
+    }
+
+    // shift keys into the row's range so the leading radix digits discriminate
+    const uint64_t range = kmax - kmin;
+    const int sh = range ? __clzll((long long)range) : 0;
+#pragma unroll
+    for (int m = 0; m < KPL; ++m) key[m] = (key[m] - kmin) << sh;   // invalid slots are never read
+
+    const int k_keep = Nkb - k_n;          // first k_keep of the order are not negligible
+    uint64_t Tc = 0, Tn = 0;
+    int rc = 0, rn = 0;
+    if (k_c > 0 && k_c < Nkb) radix_select<KPL>(key, Nkb, k_c, hist, Tc, rc);
+    if (k_keep > 0 && k_keep < Nkb) radix_select<KPL>(key, Nkb, k_keep, hist, Tn, rn);
+
+    int tie_c = 0, tie_n = 0, ncrit = 0;
+    const uint64_t lt = (1ull << lane) - 1;
+#pragma unroll
+    for (int m = 0; m < KPL; ++m) {
+        const int j = m * 64 + lane;
+        const bool valid = j < Nkb;
+        bool selc, seln;
+        if (k_c <= 0) selc = false;
+        else if (k_c >= Nkb) selc = valid;
+        else {
+            const bool eq = valid && key[m] == Tc;
+            const uint64_t b = __ballot(eq);
+            selc = valid && (key[m] < Tc || (eq && tie_c + (int)__popcll(b & lt) < rc));
+            tie_c += __popcll(b);
+        }
+        if (k_keep <= 0) seln = false;
+        else if (k_keep >= Nkb) seln = valid;
+        else {
+            const bool eq = valid && key[m] == Tn;
+            const uint64_t b = __ballot(eq);
+            seln = valid && (key[m] < Tn || (eq && tie_n + (int)__popcll(b & lt) < rn));
+            tie_n += __popcll(b);
+        }
+        const int8_t lab = selc ? 2 : (seln ? 1 : 0);
+        if (j < lab_pitch) lab_pad[row * lab_pitch + j] = lab;
+        if (lab_dense && valid) lab_dense[row * Nkb + j] = lab;
+        if (crit_idx) {
+            const uint64_t b = __ballot(selc);
+            const int pos = ncrit + (int)__popcll(b & lt);
+            if (selc && pos < k_c) crit_idx[row * k_c + pos] = j;
+            ncrit += __popcll(b);
+        }
+    }
+}
+
+template <int KPL>
+static hipError_t launch_select_t(const double *S, int pitch, long rows, int Nkb, int k_c, int k_n, int8_t *lab_pad,
+                                  int lab_pitch, int8_t *lab_dense, int32_t *crit_idx, float *Pc, double *S_dense,
+                                  float sm_scale, hipStream_t st)
+{
+    select_kernel<KPL><<<(unsigned)rows, 64, 0, st>>>(S, pitch, Nkb, k_c, k_n, lab_pad, lab_pitch, lab_dense, crit_idx,
+                                                      Pc, S_dense, sm_scale);
+    return hipGetLastError();
+}
+
+hipError_t launch_select(const double *S, int pitch, long rows, int Nkb, int k_c, int k_n,
+                         int8_t *lab_pad, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx,
+                         float *Pc, double *S_dense, float sm_scale, hipStream_t st)
+{
+#define SLA_SEL(K) return launch_select_t<K>(S, pitch, rows, Nkb, k_c, k_n, lab_pad, lab_pitch, lab_dense, crit_idx, Pc, S_dense, sm_scale, st)
+    if (lab_pitch <= 64) SLA_SEL(1);
+    if (lab_pitch <= 128) SLA_SEL(2);
+    if (lab_pitch <= 256) SLA_SEL(4);
+    if (lab_pitch <= 512) SLA_SEL(8);
+    if (lab_pitch <= 1024) SLA_SEL(16);
+    if (lab_pitch <= 2048) SLA_SEL(32);
+    if (lab_pitch <= 4096) SLA_SEL(64);
+#undef SLA_SEL
+    return hipErrorInvalidValue;
+}
+
+// --------------------------------------------------------------------------- labels_prepare
+// dense labels -> padded copy + ascending critical index list per row (one wavefront per row;
+// slots beyond the number of critical blocks found are set to -1, surplus ones are dropped).
+__global__ __launch_bounds__(64) void labels_prepare_kernel(const int8_t *__restrict__ lab_dense, int Nkb, int k_c,
+                                                            int8_t *__restrict__ lab_pad, int lab_pitch,
+                                                            int32_t *__restrict__ crit_idx)
+{
+    const long row = blockIdx.x;
+    const int lane = threadIdx.x;
+    const uint64_t lt = (1ull << lane) - 1;
+    int n = 0;
+    for (int j0 = 0; j0 < lab_pitch; j0 += 64) {
+        const int j = j0 + lane;
+        const int8_t v = j < Nkb ? lab_dense[row * Nkb + j] : (int8_t)0;
+        lab_pad[row * lab_pitch + j] = v;
+        const uint64_t b = __ballot(v == 2);
+        const int pos = n + __popcll(b & lt);
+        if (v == 2 && pos < k_c) crit_idx[row * k_c + pos] = j;
+        n += __popcll(b);
+    }
+    for (int pos = n + lane; pos < k_c; pos += 64) crit_idx[row * k_c + pos] = -1;
+}
+
+hipError_t launch_labels_prepare(const int8_t *lab_dense, long rows, int Nkb, int k_c,
+                                 int8_t *lab_pad, int lab_pitch, int32_t *crit_idx, hipStream_t st)
+{
+    labels_prepare_kernel<<<(unsigned)rows, 64, 0, st>>>(lab_dense, Nkb, k_c, lab_pad, lab_pitch, crit_idx);
+    return hipGetLastError();
+}
+
+}  // namespace sla

@@ -1,0 +1,267 @@
+// C ABI of the SLA forward: parameter validation, workspace carving and kernel sequencing.
+// Host code only; every device operation is a kernel launch on the caller's stream.
+#include "../../include/sla.h"
+#include "sla_common.hpp"
+#include "sla_kernels.hpp"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+sla_status_t fail(sla_status_t st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+struct Plan {
+    int BH, Nqb, Nkb, k_c, k_n, lab_pitch, s_pitch, nW;
+    float sm_scale;
+    bool fp8, empty;
+    size_t off_qbar, off_kbar, off_scores, off_lab, off_crit, off_hT, off_Hq, off_WT, total;
+};
+
+// Validates the parameter block and derives every size used downstream.
+sla_status_t make_plan(const sla_params_t *p, Plan &pl)
+{
+    if (!p) return fail(SLA_ERR_INVALID_ARG, "params is NULL");
+    if (p->B < 0 || p->H < 0 || p->N < 0) return fail(SLA_ERR_INVALID_ARG, "B, H, N must be >= 0 (got %d, %d, %d)", p->B, p->H, p->N);
+    if (p->D != 64) return fail(SLA_ERR_UNSUPPORTED, "head dim D = %d; only 64 is implemented", p->D);
+    if (p->bk != 64) return fail(SLA_ERR_UNSUPPORTED, "key block bk = %d; only 64 is implemented", p->bk);
+    if (p->bq != 64 && p->bq != 128) return fail(SLA_ERR_UNSUPPORTED, "query block bq = %d; only 64 and 128 are implemented", p->bq);
+    if (p->dtype != SLA_BF16 && p->dtype != SLA_FP8_E4M3) return fail(SLA_ERR_INVALID_ARG, "unknown dtype %d", p->dtype);
+    if (p->phi != SLA_PHI_SOFTMAX) return fail(SLA_ERR_UNSUPPORTED, "feature map %d; only softmax over D is implemented", p->phi);
+    if (p->proj_per_head != 0 && p->proj_per_head != 1) return fail(SLA_ERR_INVALID_ARG, "proj_per_head must be 0 or 1");
+    if (!(p->sm_scale >= 0.f) || !std::isfinite(p->sm_scale)) return fail(SLA_ERR_INVALID_ARG, "sm_scale must be finite and >= 0");
+    memset(&pl, 0, sizeof pl);
+    pl.empty = p->B == 0 || p->H == 0 || p->N == 0;
+    if ((long)p->B * p->H > 65535) return fail(SLA_ERR_UNSUPPORTED, "B*H = %ld exceeds 65535", (long)p->B * p->H);
+    pl.BH = p->B * p->H;
+    pl.Nqb = (p->N + p->bq - 1) / p->bq;
+    pl.Nkb = (p->N + p->bk - 1) / p->bk;
+    if (pl.Nkb > 4096) return fail(SLA_ERR_UNSUPPORTED, "N = %d gives %d key blocks; at most 4096 are supported", p->N, pl.Nkb);
+    if ((long)pl.BH * pl.Nqb > 0x7FFFFFF0L) return fail(SLA_ERR_UNSUPPORTED, "too many query blocks");
+    pl.sm_scale = p->sm_scale > 0.f ? p->sm_scale : 0.125f;   // 1/sqrt(64)
+    pl.fp8 = p->dtype == SLA_FP8_E4M3;
+    pl.nW = p->proj_per_head ? p->H : 1;
+
+    if (p->k_crit >= 0 || p->k_neg >= 0) {
+        if (p->k_crit < 0 || p->k_neg < 0) return fail(SLA_ERR_INVALID_ARG, "k_crit and k_neg must both be given or both be -1");
+        if (p->k_crit + p->k_neg > pl.Nkb && !pl.empty)
+            return fail(SLA_ERR_INVALID_ARG, "k_crit + k_neg = %d exceeds the %d key blocks", p->k_crit + p->k_neg, pl.Nkb);
+        pl.k_c = p->k_crit;
+        pl.k_n = p->k_neg;
+    } else {
+        const double fc = p->crit_frac, fn = p->neg_frac;
+        if (!(fc >= 0.0 && fc <= 1.0) || !(fn >= 0.0 && fn <= 1.0)) return fail(SLA_ERR_INVALID_ARG, "fractions must lie in [0,1]");
+        if (fc + fn > 1.0 + 1e-12) return fail(SLA_ERR_INVALID_ARG, "crit_frac + neg_frac = %g exceeds 1", fc + fn);
+        int kc = 0;
+        if (fc > 0.0) { kc = (int)std::floor(fc * pl.Nkb + 0.5); kc = kc < 1 ? 1 : kc; kc = kc > pl.Nkb ? pl.Nkb : kc; }
+        int kn = (int)std::floor(fn * pl.Nkb + 0.5);
+        kn = kn > pl.Nkb - kc ? pl.Nkb - kc : kn;
+        pl.k_c = kc;
+        pl.k_n = kn < 0 ? 0 : kn;
+    }
+
+    pl.lab_pitch = (int)align_up((size_t)pl.Nkb, 64);
+    pl.s_pitch = (int)align_up((size_t)pl.Nkb, 8);
+    size_t off = 0;
+    auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    const size_t BH = (size_t)pl.BH;
+    pl.off_qbar = carve(BH * pl.Nqb * 64 * sizeof(double));
+    pl.off_kbar = carve(BH * pl.Nkb * 64 * sizeof(double));
+    pl.off_scores = carve(BH * pl.Nqb * pl.s_pitch * sizeof(double));
+    pl.off_lab = carve(BH * pl.Nqb * pl.lab_pitch);
+    pl.off_crit = carve(BH * pl.Nqb * (size_t)(pl.k_c > 0 ? pl.k_c : 1) * sizeof(int32_t));
+    pl.off_hT = carve(BH * pl.Nkb * sla::kStateElems * 2);
+    pl.off_Hq = carve(BH * pl.Nqb * sla::kStateElems * 2);
+    pl.off_WT = carve((size_t)pl.nW * 64 * 64 * 2);
+    pl.total = off;
+    return SLA_OK;
+}
+
+sla_status_t check_ws(const Plan &pl, const void *ws, size_t bytes)
+{
+    if (!ws) return fail(SLA_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", pl.total);
+    if (!aligned(ws, 256)) return fail(SLA_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    if (bytes < pl.total) return fail(SLA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", bytes, pl.total);
+    return SLA_OK;
+}
+
+#define SLA_REQ_PTR(ptr)                                                                              \
+    do {                                                                                              \
+        if (!(ptr)) return fail(SLA_ERR_INVALID_ARG, #ptr " is NULL");                                \
+        if (!aligned((ptr), 16)) return fail(SLA_ERR_INVALID_ARG, #ptr " must be 16-byte aligned");   \
+    } while (0)
+#define SLA_OPT_PTR(ptr)                                                                              \
+    do {                                                                                              \
+        if ((ptr) && !aligned((ptr), 16)) return fail(SLA_ERR_INVALID_ARG, #ptr " must be 16-byte aligned"); \
+    } while (0)
+#define SLA_HIP(call)                                                                                 \
+    do {                                                                                              \
+        hipError_t e_ = (call);                                                                       \
+        if (e_ != hipSuccess) return fail(SLA_ERR_HIP, "%s failed: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+template <class T> T *at(void *ws, size_t off) { return (T *)((char *)ws + off); }
+
+// steps a1-a3: pool, logits, classifier.  Leaves padded labels and critical lists in the workspace.
+sla_status_t run_classify(const sla_params_t *p, const Plan &pl, const void *Q, const void *K, const float *sQ,
+                          const float *sK, int8_t *labels, int32_t *crit_out, float *Pc, double *qbar_out,
+                          double *kbar_out, double *scores_out, void *ws, hipStream_t st)
+{
+    double *qbar = qbar_out ? qbar_out : at<double>(ws, pl.off_qbar);
+    double *kbar = kbar_out ? kbar_out : at<double>(ws, pl.off_kbar);
+    SLA_HIP(sla::launch_pool(Q, sQ, pl.fp8, pl.BH, p->N, p->bq, qbar, st));
+    SLA_HIP(sla::launch_pool(K, sK, pl.fp8, pl.BH, p->N, p->bk, kbar, st));
+    SLA_HIP(sla::launch_scores(qbar, kbar, pl.BH, pl.Nqb, pl.Nkb, pl.s_pitch, at<double>(ws, pl.off_scores), st));
+    int32_t *crit = crit_out ? crit_out : at<int32_t>(ws, pl.off_crit);
+    SLA_HIP(sla::launch_select(at<double>(ws, pl.off_scores), pl.s_pitch, (long)pl.BH * pl.Nqb, pl.Nkb, pl.k_c, pl.k_n,
+                               at<int8_t>(ws, pl.off_lab), pl.lab_pitch, labels, pl.k_c > 0 ? crit : nullptr, Pc,
+                               scores_out, pl.sm_scale, st));
+    return SLA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *sla_strerror(sla_status_t s)
+{
+    switch (s) {
+    case SLA_OK: return "ok";
+    case SLA_ERR_INVALID_ARG: return "invalid argument";
+    case SLA_ERR_UNSUPPORTED: return "unsupported configuration";
+    case SLA_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case SLA_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+const char *sla_last_error(void) { return g_err; }
+
+sla_status_t sla_resolve_counts(const sla_params_t *p, int32_t *k_crit, int32_t *k_neg)
+{
+    Plan pl;
+    sla_status_t s = make_plan(p, pl);
+    if (s != SLA_OK) return s;
+    if (!k_crit || !k_neg) return fail(SLA_ERR_INVALID_ARG, "output pointer is NULL");
+    *k_crit = pl.k_c;
+    *k_neg = pl.k_n;
+    return SLA_OK;
+}
+
+sla_status_t sla_workspace_bytes(const sla_params_t *p, size_t *bytes)
+{
+    Plan pl;
+    sla_status_t s = make_plan(p, pl);
+    if (s != SLA_OK) return s;
+    if (!bytes) return fail(SLA_ERR_INVALID_ARG, "bytes is NULL");
+    *bytes = pl.total;
+    return SLA_OK;
+}
+
+sla_status_t sla_pool_classify(const sla_params_t *p, const void *Q, const void *K, const float *sQ, const float *sK,
+                               int8_t *labels, int32_t *crit_idx, float *Pc, double *qbar, double *kbar, double *scores,
+                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    Plan pl;
+    sla_status_t s = make_plan(p, pl);
+    if (s != SLA_OK) return s;
+    if (pl.empty) return SLA_OK;
+    SLA_REQ_PTR(Q); SLA_REQ_PTR(K);
+    if (!labels) return fail(SLA_ERR_INVALID_ARG, "labels is NULL");
+    if (pl.fp8) { SLA_REQ_PTR(sQ); SLA_REQ_PTR(sK); }
+    SLA_OPT_PTR(qbar); SLA_OPT_PTR(kbar); SLA_OPT_PTR(scores);
+    if ((s = check_ws(pl, workspace, workspace_bytes)) != SLA_OK) return s;
+    return run_classify(p, pl, Q, K, sQ, sK, labels, crit_idx, Pc, qbar, kbar, scores, workspace, (hipStream_t)stream);
+}
+
+sla_status_t sla_linear_states(const sla_params_t *p, const void *K, const void *V, const float *sK, const float *sV,
+                               void *hT, void *stream)
+{
+    Plan pl;
+    sla_status_t s = make_plan(p, pl);
+    if (s != SLA_OK) return s;
+    if (pl.empty) return SLA_OK;
+    SLA_REQ_PTR(K); SLA_REQ_PTR(V); SLA_REQ_PTR(hT);
+    if (pl.fp8) { SLA_REQ_PTR(sK); SLA_REQ_PTR(sV); }
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, hT, (hipStream_t)stream));
+    return SLA_OK;
+}
+
+sla_status_t sla_marginal_aggregate(const sla_params_t *p, const int8_t *labels, const void *hT, void *Hq,
+                                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    Plan pl;
+    sla_status_t s = make_plan(p, pl);
+    if (s != SLA_OK) return s;
+    if (pl.empty) return SLA_OK;
+    if (!labels) return fail(SLA_ERR_INVALID_ARG, "labels is NULL");
+    SLA_REQ_PTR(hT); SLA_REQ_PTR(Hq);
+    if ((s = check_ws(pl, workspace, workspace_bytes)) != SLA_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    SLA_HIP(sla::launch_labels_prepare(labels, (long)pl.BH * pl.Nqb, pl.Nkb, pl.k_c > 0 ? pl.k_c : 1,
+                                       at<int8_t>(workspace, pl.off_lab), pl.lab_pitch, at<int32_t>(workspace, pl.off_crit), st));
+    SLA_HIP(sla::launch_aggregate(at<int8_t>(workspace, pl.off_lab), pl.lab_pitch, hT, pl.BH, pl.Nqb, pl.Nkb, Hq, st));
+    return SLA_OK;
+}
+
+sla_status_t sla_sparse_combine(const sla_params_t *p, const void *Q, const void *K, const void *V, const float *sQ,
+                                const float *sK, const float *sV, const void *W_proj, const int8_t *labels, const void *Hq,
+                                void *O, void *workspace, size_t workspace_bytes, void *stream)
+{
+    Plan pl;
+    sla_status_t s = make_plan(p, pl);
+    if (s != SLA_OK) return s;
+    if (pl.empty) return SLA_OK;
+    SLA_REQ_PTR(Q); SLA_REQ_PTR(K); SLA_REQ_PTR(V); SLA_REQ_PTR(O);
+    if (!labels) return fail(SLA_ERR_INVALID_ARG, "labels is NULL");
+    if (pl.fp8) { SLA_REQ_PTR(sQ); SLA_REQ_PTR(sK); SLA_REQ_PTR(sV); }
+    SLA_OPT_PTR(Hq);
+    if (Hq) SLA_REQ_PTR(W_proj);
+    if ((s = check_ws(pl, workspace, workspace_bytes)) != SLA_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    SLA_HIP(sla::launch_labels_prepare(labels, (long)pl.BH * pl.Nqb, pl.Nkb, pl.k_c > 0 ? pl.k_c : 1,
+                                       at<int8_t>(workspace, pl.off_lab), pl.lab_pitch, at<int32_t>(workspace, pl.off_crit), st));
+    if (Hq) SLA_HIP(sla::launch_transpose_w(W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
+    SLA_HIP(sla::launch_attend(Q, K, V, sQ, sK, sV, pl.fp8, at<int32_t>(workspace, pl.off_crit), pl.k_c, Hq,
+                               at<void>(workspace, pl.off_WT), p->proj_per_head, p->B, p->H, p->N, p->bq, pl.sm_scale, O, st));
+    return SLA_OK;
+}
+
+sla_status_t sla_forward(const sla_params_t *p, const void *Q, const void *K, const void *V, const float *sQ,
+                         const float *sK, const float *sV, const void *W_proj, void *O, int8_t *labels,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    Plan pl;
+    sla_status_t s = make_plan(p, pl);
+    if (s != SLA_OK) return s;
+    if (pl.empty) return SLA_OK;
+    SLA_REQ_PTR(Q); SLA_REQ_PTR(K); SLA_REQ_PTR(V); SLA_REQ_PTR(W_proj); SLA_REQ_PTR(O);
+    if (pl.fp8) { SLA_REQ_PTR(sQ); SLA_REQ_PTR(sK); SLA_REQ_PTR(sV); }
+    if ((s = check_ws(pl, workspace, workspace_bytes)) != SLA_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    if ((s = run_classify(p, pl, Q, K, sQ, sK, labels, nullptr, nullptr, nullptr, nullptr, nullptr, workspace, st)) != SLA_OK) return s;
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), st));
+    SLA_HIP(sla::launch_aggregate(at<int8_t>(workspace, pl.off_lab), pl.lab_pitch, at<void>(workspace, pl.off_hT), pl.BH, pl.Nqb,
+                                  pl.Nkb, at<void>(workspace, pl.off_Hq), st));
+    SLA_HIP(sla::launch_transpose_w(W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
+    SLA_HIP(sla::launch_attend(Q, K, V, sQ, sK, sV, pl.fp8, at<int32_t>(workspace, pl.off_crit), pl.k_c,
+                               at<void>(workspace, pl.off_Hq), at<void>(workspace, pl.off_WT), p->proj_per_head, p->B, p->H,
+                               p->N, p->bq, pl.sm_scale, O, st));
+    return SLA_OK;
+}
+
+}  // extern "C"

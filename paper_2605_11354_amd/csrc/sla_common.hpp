@@ -1,0 +1,76 @@
+// Shared device-side helpers of the gfx950 SLA kernels (types, bf16/fp8 conversions,
+// wave-level primitives).  Wavefront size is 64 throughout.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sla {
+
+constexpr int kD = 64;          // head dimension
+constexpr int kBK = 64;         // key block size
+constexpr int kStateRows = 65;  // rows of a block state: 64 rows of h^T plus one row of z
+constexpr int kStateElems = kStateRows * kD;   // 4160
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(2))) int i32x2;
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// two bf16 packed in a dword -> two floats
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// round-to-nearest-even pack of two floats into one dword of bf16 (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    bf16x2 r;
+    r[0] = (__bf16)lo;
+    r[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+__device__ __forceinline__ float bf16_round(float x) { return (float)(__bf16)x; }
+
+// exp2 on the hardware transcendental unit (v_exp_f32); exp2(-inf) = 0
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// value held by the lane 32 positions away (lanes l and l^32 exchange)
+__device__ __forceinline__ float xchg32(float v) { return __shfl_xor(v, 32, 64); }
+
+__device__ __forceinline__ float wave_max(float v)
+{
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// Orders LDS traffic between the lanes of one wavefront (LDS operations of a wave execute in
+// program order; this only stops the compiler from moving accesses across the point).
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// blockIdx -> work item so that each of the 8 XCDs (workgroups are dealt round-robin to them)
+// walks a contiguous range of items and therefore keeps one head's K/V in its own L2.
+__device__ __forceinline__ long xcd_remap(long bid, long total)
+{
+    const long chunk = (total + 7) / 8;
+    return (bid & 7) * chunk + (bid >> 3);
+}
+inline long xcd_grid(long total) { return ((total + 7) / 8) * 8; }
+
+}  // namespace sla

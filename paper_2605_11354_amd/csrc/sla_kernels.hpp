@@ -1,0 +1,46 @@
+// Host-side launch functions of the SLA kernels (internal to the library).
+// Each returns the hipError_t of its launch; none allocates or synchronises.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sla {
+
+// block mean-pool: X [BH,N,64] (bf16 or e4m3 + scales [BH,nblk]) -> mean fp64 [BH,nblk,64]
+hipError_t launch_pool(const void *X, const float *scales, bool fp8, int BH, int N, int blk,
+                       double *mean, hipStream_t st);
+
+// pooled logits: S[bh][i][j] = fma-chain_d(qbar[bh][i][d], kbar[bh][j][d]); row pitch `pitch`
+hipError_t launch_scores(const double *qbar, const double *kbar, int BH, int Nqb, int Nkb,
+                         int pitch, double *S, hipStream_t st);
+
+// three-way classifier on every score row.  lab_pad has row pitch lab_pitch (multiple of 64,
+// pad entries written 0); lab_dense ([.,Nkb]), crit_idx ([.,k_c]), Pc ([.,Nkb]), S_dense
+// ([.,Nkb]) are optional.
+hipError_t launch_select(const double *S, int pitch, long rows, int Nkb, int k_c, int k_n,
+                         int8_t *lab_pad, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx,
+                         float *Pc, double *S_dense, float sm_scale, hipStream_t st);
+
+// dense labels -> padded labels + critical index lists (unfilled slots = -1)
+hipError_t launch_labels_prepare(const int8_t *lab_dense, long rows, int Nkb, int k_c,
+                                 int8_t *lab_pad, int lab_pitch, int32_t *crit_idx, hipStream_t st);
+
+// per-key-block states: hT [BH,Nkb,65,64] bf16
+hipError_t launch_states(const void *K, const void *V, const float *sK, const float *sV, bool fp8,
+                         int BH, int N, void *hT, hipStream_t st);
+
+// Hq[bh][i][:] = sum over j with lab_pad[bh][i][j] == 1 of hT[bh][j][:]   (bf16 MFMA, fp32 accumulate)
+hipError_t launch_aggregate(const int8_t *lab_pad, int lab_pitch, const void *hT, int BH, int Nqb,
+                            int Nkb, void *Hq, hipStream_t st);
+
+// W [nW,64,64] bf16 -> WT[nW][e_out][e_in]
+hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st);
+
+// block-sparse attention over critical blocks + linear output + projection + sum
+hipError_t launch_attend(const void *Q, const void *K, const void *V,
+                         const float *sQ, const float *sK, const float *sV, bool fp8,
+                         const int32_t *crit_idx, int k_c, const void *Hq, const void *WT,
+                         int proj_per_head, int B, int H, int N, int bq, float sm_scale,
+                         void *O, hipStream_t st);
+
+}  // namespace sla

@@ -1,0 +1,169 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle on the same seeded inputs.
+
+Bars: block labels, critical index lists, block means and pooled logits bit-exact; outputs
+within max-abs <= 2e-2 * RMS(oracle output) for bf16 inputs and 6e-2 for fp8 inputs.
+Intermediate bf16 tensors (block states, aggregated states) are compared with a tolerance
+of a few bf16 ulps of their largest entry (they are rounded once to bf16 on the device).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_11354_amd import synth
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+C0 = synth.CONFIGS[0]
+SMALL = [
+    ("c0", C0, -1, -1),
+    ("c0_tail150", C0.with_(N=150), 1, 1),
+    ("c0_bq128_tail", C0.with_(N=700, bq=128, proj_per_head=True), 2, 5),
+    ("c0_one_token", C0.with_(N=1), 1, 0),
+    ("c0_one_block", C0.with_(N=64), 1, 0),
+    ("c3_small", synth.CONFIGS[3].with_(B=3, H=2), -1, -1),
+    ("c1_small", synth.CONFIGS[1].with_(H=2, N=2 * 1374), -1, -1),
+    ("c2_small", synth.CONFIGS[2].with_(H=2, N=3 * 1374), -1, -1),
+]
+
+
+def _case(name):
+    for n, cfg, kc, kn in SMALL:
+        if n == name:
+            return G.Case(cfg, k_crit=kc, k_neg=kn)
+    raise KeyError(name)
+
+
+@pytest.mark.parametrize("name", [s[0] for s in SMALL])
+def test_pool_classify_bit_exact(oracle, name):
+    case = _case(name)
+    got = case.classify()
+    ref = case.oracle_classify(oracle, want_scores=True, want_pc=True, want_means=True)
+    assert np.array_equal(got["qbar"], ref["qbar"]), "query block means differ"
+    assert np.array_equal(got["kbar"], ref["kbar"]), "key block means differ"
+    assert np.array_equal(got["scores"], ref["scores"]), "pooled logits differ"
+    assert np.array_equal(got["labels"], ref["labels"]), "labels differ"
+    np.testing.assert_allclose(got["Pc"], ref["Pc"], rtol=2e-5, atol=1e-9)
+    if case.k_c > 0:
+        for idx in np.ndindex(got["labels"].shape[:3]):
+            assert np.array_equal(got["crit_idx"][idx], np.nonzero(ref["labels"][idx] == 2)[0])
+
+
+@pytest.mark.parametrize("kc,kn", [(0, 0), (8, 0), (0, 8), (3, 5), (1, 7), (4, 0)])
+def test_classifier_ties_and_degenerate_counts(oracle, kc, kn):
+    """Q == 0 makes every logit tie: the index order alone decides; plus all-critical etc."""
+    d = synth.make_inputs(C0)
+    for zero_q in (False, True):
+        dd = dict(d)
+        if zero_q:
+            dd["Q"] = np.zeros_like(d["Q"])
+        case = G.Case(C0, dd, k_crit=kc, k_neg=kn)
+        got = case.classify(want=())
+        ref = case.oracle_classify(oracle)
+        assert np.array_equal(got["labels"], ref["labels"])
+
+
+def test_classifier_duplicate_blocks_tie_exactly(oracle):
+    cfg = C0.with_(N=22 * 64)
+    d = synth.make_inputs(cfg)
+    d["K"][:, :, 7 * 64:8 * 64] = d["K"][:, :, 3 * 64:4 * 64]
+    d["K"][:, :, 20 * 64:21 * 64] = d["K"][:, :, 3 * 64:4 * 64]
+    for kc, kn in [(2, 13), (4, 4), (1, 20)]:
+        case = G.Case(cfg, d, k_crit=kc, k_neg=kn)
+        got = case.classify(want=("scores",))
+        ref = case.oracle_classify(oracle, want_scores=True)
+        assert np.array_equal(got["scores"][..., 3], got["scores"][..., 7])
+        assert np.array_equal(got["labels"], ref["labels"])
+
+
+@pytest.mark.parametrize("name", ["c0", "c0_tail150", "c1_small"])
+def test_linear_states(oracle, name):
+    case = _case(name)
+    hT = G.bf16_tensor_to_f64(case.states())
+    p = case.oracle_params(oracle)
+    for bh in range(case.cfg.B * case.cfg.H):
+        h, z = oracle.states_head(p, case.d["K"], case.d["V"], case.d["sK"], case.d["sV"], bh)
+        got = hT[bh // case.cfg.H, bh % case.cfg.H]
+        tol = 2.0 ** -7 * max(np.abs(h).max(), 1e-30)
+        assert np.abs(got[:, :64, :] - h.transpose(0, 2, 1)).max() <= tol
+        assert np.abs(got[:, 64, :] - z).max() <= 2.0 ** -7 * np.abs(z).max()
+
+
+@pytest.mark.parametrize("name", ["c0", "c0_bq128_tail", "c1_small"])
+def test_marginal_aggregate(oracle, name):
+    case = _case(name)
+    lab = case.oracle_classify(oracle)["labels"]
+    hT = case.states()
+    Hq = G.bf16_tensor_to_f64(case.aggregate(torch.from_numpy(lab).cuda(), hT))
+    p = case.oracle_params(oracle)
+    for bh in range(case.cfg.B * case.cfg.H):
+        b, hh = bh // case.cfg.H, bh % case.cfg.H
+        h, z = oracle.states_head(p, case.d["K"], case.d["V"], case.d["sK"], case.d["sV"], bh)
+        m = (lab[b, hh] == 1).astype(np.float64)                      # [Nqb, Nkb]
+        Href = np.einsum("ij,jde->ied", m, h)                          # transposed like the device layout
+        Zref = m @ z
+        tol = 2.0 ** -6 * max(np.abs(Href).max(), 1e-30)
+        assert np.abs(Hq[b, hh, :, :64, :] - Href).max() <= tol
+        assert np.abs(Hq[b, hh, :, 64, :] - Zref).max() <= 2.0 ** -6 * max(np.abs(Zref).max(), 1e-30)
+
+
+@pytest.mark.parametrize("name", ["c0", "c0_tail150", "c0_bq128_tail", "c1_small"])
+def test_sparse_branch_alone(oracle, name):
+    case = _case(name)
+    lab = case.oracle_classify(oracle)["labels"]
+    ref = case.oracle_attend(oracle, lab, want_parts=True)
+    O = G.bf16_tensor_to_f64(case.sparse_combine(torch.from_numpy(lab).cuda(), None))
+    sel = ref["sel"]
+    got = G.gather_blocks(O, sel, case.cfg.bq, case.cfg.H)
+    G.assert_output(got, ref["O_sparse"], "bf16", name + " sparse branch")
+
+
+@pytest.mark.parametrize("name", [s[0] for s in SMALL])
+def test_forward_small(oracle, name):
+    case = _case(name)
+    O, lab = case.forward()
+    refc = case.oracle_classify(oracle)
+    assert np.array_equal(lab.cpu().numpy(), refc["labels"])
+    ref = case.oracle_attend(oracle, refc["labels"])
+    got = G.gather_blocks(G.bf16_tensor_to_f64(O), ref["sel"], case.cfg.bq, case.cfg.H)
+    G.assert_output(got, ref["O"], case.cfg.dtype, name)
+    O2, _ = case.forward(want_labels=False)                 # same launch twice: bitwise identical (no races)
+    assert torch.equal(O.view(torch.int16), O2.view(torch.int16))
+
+
+@pytest.mark.parametrize("kc,kn", [(8, 0), (0, 0), (0, 8), (3, 0), (0, 3)])
+def test_forward_degenerate_counts(oracle, kc, kn):
+    """All critical (dense attention), all marginal (pure linear attention), all negligible (zeros), ..."""
+    case = G.Case(C0, k_crit=kc, k_neg=kn)
+    O, lab = case.forward()
+    refc = case.oracle_classify(oracle)
+    assert np.array_equal(lab.cpu().numpy(), refc["labels"])
+    ref = case.oracle_attend(oracle, refc["labels"])
+    got = G.gather_blocks(G.bf16_tensor_to_f64(O), ref["sel"], 64, C0.H)
+    if kc == 0 and kn == 8:
+        assert np.abs(got).max() == 0.0 and np.abs(ref["O"]).max() == 0.0
+    else:
+        G.assert_output(got, ref["O"], "bf16", f"k_crit={kc} k_neg={kn}")
+
+
+def test_v_ones_closed_form_on_device():
+    """V == 1 gives O = 1 + column sums of W for every row (eq. 1), independent of the oracle."""
+    d = dict(synth.make_inputs(C0))
+    d["V"] = np.full_like(d["V"], 0x3F80)
+    case = G.Case(C0, d)
+    O, _ = case.forward()
+    W = (d["W"].astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    expect = 1.0 + W.sum(axis=0)
+    assert np.abs(G.bf16_tensor_to_f64(O) - expect).max() <= 2e-2
+
+
+def test_errors_are_reported_not_launched():
+    from paper_2605_11354_amd import binding as B
+    case = G.Case(C0)
+    O = torch.empty((1, 2, 512, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.SlaError) as e:
+        B.sla_forward(case.p, case.Q, case.K, case.V, case.W, O, None, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == B.SLA_ERR_WORKSPACE
+    with pytest.raises(B.SlaError) as e:
+        B.sla_forward(case.p, case.Q, None, case.V, case.W, O, None, workspace=case.ws)
+    assert e.value.status == B.SLA_ERR_INVALID_ARG

@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the SLA forward on one MI355X.
+
+A "step" is one sla_forward call (all kernels of the hot path) on one of the benchmark
+configurations, with seeded synthetic inputs already resident in HBM.  Prints ONE JSON line:
+ms per layer, dense-equivalent TFLOP/s (4*B*H*N^2*D / t), the roofline position of the
+dominant kernel (block-sparse attention, MFMA bound, algorithmic flops only) and of the
+HBM-bound kernels, and the fp64 CPU oracle timed on the host cores beside it.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "fp8": 5000.0}     # MI355X dense MFMA peaks
+PEAK_HBM_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=1, help="index into the benchmark configurations (default 1)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards over batch x heads with no "
+              "communication; no multi-GPU figure is produced). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2605_11354_amd import binding as B
+    from paper_2605_11354_amd import build as libbuild
+    from paper_2605_11354_amd import synth
+
+    if not os.path.exists(B.LIB_PATH):
+        libbuild.build()
+    B.lib()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the SLA forward has no CPU path", file=sys.stderr)
+        return 2
+
+    cfg = synth.CONFIGS[args.config]
+    t0 = time.time()
+    d = synth.make_inputs(cfg)
+    gen_s = time.time() - t0
+    fp8 = cfg.dtype == "fp8"
+    p = B.make_params(cfg.B, cfg.H, cfg.N, cfg.bq, cfg.bk, cfg.crit_frac, cfg.neg_frac, -1, -1, cfg.dtype, cfg.proj_per_head)
+    k_c, k_n = B.sla_resolve_counts(p)
+    Nqb, Nkb = -(-cfg.N // cfg.bq), -(-cfg.N // cfg.bk)
+
+    def up16(a):
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+
+    up = (lambda a: torch.from_numpy(a).cuda()) if fp8 else up16
+    Q, K, V = up(d["Q"]), up(d["K"]), up(d["V"])
+    sQ, sK, sV = ((torch.from_numpy(d[k]).cuda() for k in ("sQ", "sK", "sV")) if fp8 else (None, None, None))
+    W = up16(d["W"])
+    O = torch.empty((cfg.B, cfg.H, cfg.N, 64), dtype=torch.bfloat16, device="cuda")
+    labels = torch.empty((cfg.B, cfg.H, Nqb, Nkb), dtype=torch.int8, device="cuda")
+    ws = B.alloc_workspace(p)
+
+    def step():
+        B.sla_forward(p, Q, K, V, W, O, labels, sQ, sK, sV, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-kernel durations: HIP events around every kernel on the launch stream, same K steps
+    stage = {}
+    for _ in range(args.steps):
+        for k, v in B.sla_forward_profiled(p, Q, K, V, W, O, labels, sQ, sK, sV, ws).items():
+            stage[k] = stage.get(k, 0.0) + v / args.steps
+
+    BH, N, D = cfg.B * cfg.H, cfg.N, 64
+    dense_flops = 4.0 * BH * N * N * D
+    elem = 1 if fp8 else 2
+    qkv_bytes = BH * N * D * elem
+    bytes_pool_q = qkv_bytes + BH * Nqb * D * 8
+    bytes_pool_k = qkv_bytes + BH * Nkb * D * 8
+    bytes_states = 2 * qkv_bytes + BH * Nkb * 65 * D * 2
+
+    # algorithmic flops of the critical-block attention: 4*D per (valid query row, valid critical key)
+    lab_host = labels.cpu().numpy()
+    tail = cfg.N - (Nkb - 1) * cfg.bk
+    rows_per_qb = np.minimum(cfg.bq, cfg.N - np.arange(Nqb) * cfg.bq)      # valid rows of each query block
+    crit_tokens = (lab_host == 2).sum(-1) * cfg.bk - (lab_host[..., Nkb - 1] == 2) * (cfg.bk - tail)
+    attend_flops = 4.0 * D * float((crit_tokens * rows_per_qb[None, None, :]).sum())
+
+    def hbm(name, nbytes):
+        ms = stage[name]
+        gbs = nbytes / ms / 1e6 if ms > 0 else 0.0
+        return {"ms": round(ms, 5), "bound": "hbm", "algorithmic_bytes": int(nbytes), "achieved_GBs": round(gbs, 1),
+                "frac": round(gbs / PEAK_HBM_GBS, 4)}
+
+    attend_tflops = attend_flops / stage["attend"] / 1e9 if stage["attend"] > 0 else 0.0
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tfile):
+        traffic = json.load(open(tfile)).get(cfg.name, {}).get("attend")
+    roofline = {"kernel": "attend (block-sparse attention over critical blocks + fused linear/proj epilogue)",
+                "bound": "mfma", "achieved": round(attend_tflops, 2), "peak": PEAK_TFLOPS[cfg.dtype], "unit": "TFLOP/s",
+                "frac": round(attend_tflops / PEAK_TFLOPS[cfg.dtype], 4), "traffic": traffic,
+                "algorithmic_flops": attend_flops, "ms": round(stage["attend"], 5)}
+    kernels = {"pool_q": hbm("pool_q", bytes_pool_q), "pool_k": hbm("pool_k", bytes_pool_k),
+               "states": hbm("states", bytes_states)}
+    for k in ("scores", "select", "aggregate", "transpose_w"):
+        kernels[k] = {"ms": round(stage[k], 5)}
+    agg_flops = 2.0 * BH * Nqb * Nkb * 65 * D
+    kernels["aggregate"].update({"bound": "mfma", "achieved_TFLOPs": round(agg_flops / stage["aggregate"] / 1e9, 2),
+                                 "frac": round(agg_flops / stage["aggregate"] / 1e9 / PEAK_TFLOPS["bf16"], 4)})
+    kernels["scores"].update({"bound": "alu_fp64", "achieved_TFLOPs": round(2.0 * BH * Nqb * Nkb * D / stage["scores"] / 1e9, 3),
+                              "frac": round(2.0 * BH * Nqb * Nkb * D / stage["scores"] / 1e9 / 78.6, 4)})
+
+    out = {
+        "metric": "SLA forward dense-equivalent TFLOP/s (ms/layer = ms_per_step; % MFMA peak = roofline.frac)",
+        "value": round(dense_flops / ms_per_step / 1e9, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if not fp8 else "fp8_e4m3", "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "H": cfg.H, "N": cfg.N, "D": 64, "bq": cfg.bq, "bk": cfg.bk,
+                   "k_crit": k_c, "k_neg": k_n, "k_marg": Nkb - k_c - k_n, "input_gen_s": round(gen_s, 1)},
+        "roofline": roofline, "kernels": kernels,
+        "sum_kernel_ms": round(sum(stage.values()), 5),
+    }
+
+    if not args.no_check or not args.no_cpu_baseline:
+        from oracle import sla_oracle as orc
+        po = orc.make_params(cfg.B, cfg.H, cfg.N, cfg.bq, cfg.bk, k_c, k_n, cfg.dtype, cfg.proj_per_head)
+        rng = np.random.default_rng(0)
+        t0 = time.perf_counter()
+        oc = orc.classify(po, d["Q"], d["K"], d["sQ"], d["sK"])
+        t_classify = time.perf_counter() - t0
+        # bounded sample of query blocks for the attention part: whole heads, so the per-head
+        # state computation is amortised the way the full workload amortises it
+        heads = [0] if BH * Nqb > 4096 else list(range(BH))
+        per_head = Nqb if len(heads) > 1 else min(Nqb, 128)
+        sel = [(bh, int(i)) for bh in heads for i in (range(Nqb) if per_head == Nqb else sorted(rng.choice(Nqb, per_head, replace=False)))]
+        t0 = time.perf_counter()
+        oa = orc.attend(po, d["Q"], d["K"], d["V"], d["W"], oc["labels"], sel, d["sQ"], d["sK"], d["sV"])
+        t_attend = time.perf_counter() - t0
+        frac = len(sel) / float(BH * Nqb)
+        t_full_est = t_classify + t_attend / frac
+        if not args.no_cpu_baseline:
+          out["cpu_baseline"] = {"value": round(dense_flops / t_full_est / 1e12, 4), "unit": "TFLOP/s",
+                               "cores": orc.threads(), "kind": "oracle",
+                               "ms_per_layer_extrapolated": round(t_full_est * 1e3, 1),
+                               "sample": f"classifier on the full workload ({t_classify:.2f} s) + attention/linear/combine on "
+                                         f"{len(sel)} of {BH * Nqb} query blocks ({t_attend:.2f} s), scaled by 1/{frac:.4f}"}
+        if not args.no_check:
+            Oh = O.float().cpu().numpy().astype(np.float64)
+            got = np.zeros_like(oa["O"])
+            for s, (bh, i) in enumerate(sel):
+                rows = min(N, (i + 1) * cfg.bq) - i * cfg.bq
+                got[s, :rows] = Oh[bh // cfg.H, bh % cfg.H, i * cfg.bq:i * cfg.bq + rows]
+            rms = float(np.sqrt(np.mean(oa["O"] ** 2)))
+            out["parity"] = {"label_mismatches": int((lab_host != oc["labels"]).sum()),
+                             "max_abs_over_rms_sampled": round(float(np.abs(got - oa["O"]).max() / rms), 5),
+                             "sampled_query_blocks": len(sel)}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

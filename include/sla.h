@@ -92,6 +92,22 @@ sla_status_t sla_forward(const sla_params_t *p,
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Measurement variant of sla_forward: identical kernels and results, but every kernel is
+ * bracketed by HIP events on `stream`; the call then WAITS for the stream and writes the
+ * duration of each kernel in milliseconds to stage_ms[SLA_NUM_STAGES] (host memory).
+ * It creates and destroys its events, so unlike every other entry point it touches the HIP
+ * runtime beyond launches and synchronises.  sla_stage_name(i) names stage i.
+ */
+#define SLA_NUM_STAGES 8
+sla_status_t sla_forward_profiled(const sla_params_t *p,
+                                  const void *Q, const void *K, const void *V,
+                                  const float *sQ, const float *sK, const float *sV,
+                                  const void *W_proj, void *O, int8_t *labels,
+                                  void *workspace, size_t workspace_bytes, void *stream,
+                                  float *stage_ms);
+const char *sla_stage_name(int stage);
+
+/*
  * Step 1 alone: block mean-pool, pooled logits, classifier (Alg. 1 steps 2-3 at block level).
  *   labels    out  int8 [B,H,Nqb,Nkb]                                   (required)
  *   crit_idx  out  optional int32 [B,H,Nqb,k_crit], ascending key-block indices

@@ -19,7 +19,9 @@ SLA_OK, SLA_ERR_INVALID_ARG, SLA_ERR_UNSUPPORTED, SLA_ERR_WORKSPACE, SLA_ERR_HIP
 SLA_BF16, SLA_FP8_E4M3 = 0, 1
 STATE_ROWS = 65          # rows of one block state: 64 rows of h^T and one row of z
 EXPORTS = ["sla_resolve_counts", "sla_workspace_bytes", "sla_forward", "sla_pool_classify", "sla_linear_states",
-           "sla_marginal_aggregate", "sla_sparse_combine", "sla_strerror", "sla_last_error"]
+           "sla_marginal_aggregate", "sla_sparse_combine", "sla_forward_profiled", "sla_strerror", "sla_last_error",
+           "sla_stage_name"]
+NUM_STAGES = 8
 
 
 class SlaParams(C.Structure):
@@ -52,7 +54,8 @@ def lib() -> C.CDLL:
             getattr(_lib, name)                      # raises AttributeError on a missing export
         _lib.sla_strerror.restype = C.c_char_p
         _lib.sla_last_error.restype = C.c_char_p
-        for name in EXPORTS[:7]:
+        _lib.sla_stage_name.restype = C.c_char_p
+        for name in EXPORTS[:8]:
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -100,6 +103,16 @@ def sla_forward(p, Q, K, V, W_proj, O, labels=None, sQ=None, sK=None, sV=None, w
     _check(lib().sla_forward(C.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(sQ), _ptr(sK), _ptr(sV), _ptr(W_proj),
                              _ptr(O), _ptr(labels), _ptr(ws), C.c_size_t(ws.numel()), _stream()), "sla_forward")
     return O
+
+
+def sla_forward_profiled(p, Q, K, V, W_proj, O, labels=None, sQ=None, sK=None, sV=None, workspace=None):
+    """Returns {stage name: milliseconds} for one forward (synchronises the stream)."""
+    ws = workspace if workspace is not None else alloc_workspace(p, Q.device)
+    ms = (C.c_float * NUM_STAGES)()
+    _check(lib().sla_forward_profiled(C.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(sQ), _ptr(sK), _ptr(sV), _ptr(W_proj),
+                                      _ptr(O), _ptr(labels), _ptr(ws), C.c_size_t(ws.numel()), _stream(), ms),
+           "sla_forward_profiled")
+    return {lib().sla_stage_name(i).decode(): float(ms[i]) for i in range(NUM_STAGES)}
 
 
 def sla_pool_classify(p, Q, K, labels, crit_idx=None, Pc=None, qbar=None, kbar=None, scores=None,

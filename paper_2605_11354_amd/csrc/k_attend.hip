@@ -117,6 +117,7 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(
 #pragma unroll
         for (int x = 0; x < 16; ++x) oacc[e][x] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u));
 
     const int32_t *ci = crit_idx + work * (long)k_c;
     TileRegs<NW> regs;
@@ -168,25 +169,27 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(
         const float m_new = fmaxf(m_run, mx);
         const float alpha = fast_exp2((m_run - m_new) * c_exp);
         const float mc = m_new * c_exp;
-        float psum = 0.f;
 #pragma unroll
         for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
-            for (int x = 0; x < 16; ++x) {
-                sacc[h2][x] = fast_exp2(fmaf(sacc[h2][x], c_exp, -mc));
-                psum += sacc[h2][x];
-            }
-        l_run = l_run * alpha + psum;
+            for (int x = 0; x < 16; ++x) sacc[h2][x] = fast_exp2(fmaf(sacc[h2][x], c_exp, -mc));
         m_run = m_new;
+        if (__ballot(alpha != 1.0f)) {                 // the running maximum moved for some row of this wave
 #pragma unroll
-        for (int e = 0; e < 2; ++e)
+            for (int e = 0; e < 2; ++e)
 #pragma unroll
-            for (int x = 0; x < 16; ++x) oacc[e][x] *= alpha;
+                for (int x = 0; x < 16; ++x) oacc[e][x] *= alpha;
+        }
 
-        // ---- O^T += V^T P^T
+        // ---- O^T += V^T P^T, and the row sums as ones^T P^T on the same bf16-rounded P, so that
+        // numerator and denominator of the softmax see identical weights
+        f32x16 lsum;
+#pragma unroll
+        for (int x = 0; x < 16; ++x) lsum[x] = 0.f;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const bf16x8 pf = pack8(sacc[s >> 1], 8 * (s & 1));
+            lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf, lsum, 0, 0, 0);
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
                 const uint16_t *vr = Vt + (32 * e + l32) * kRow + 16 * s + 4 * g;
@@ -195,10 +198,11 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(
                 oacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[e], 0, 0, 0);
             }
         }
+        l_run = l_run * alpha + lsum[0];               // every row of ones^T P^T is the full 64-key sum
     }
 
     // ---- normalise the sparse output
-    const float l_tot = l_run + xchg32(l_run);
+    const float l_tot = l_run;
     const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;
 #pragma unroll
     for (int e = 0; e < 2; ++e)

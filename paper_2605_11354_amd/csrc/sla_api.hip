@@ -119,14 +119,19 @@ template <class T> T *at(void *ws, size_t off) { return (T *)((char *)ws + off);
 // steps a1-a3: pool, logits, classifier.  Leaves padded labels and critical lists in the workspace.
 sla_status_t run_classify(const sla_params_t *p, const Plan &pl, const void *Q, const void *K, const float *sQ,
                           const float *sK, int8_t *labels, int32_t *crit_out, float *Pc, double *qbar_out,
-                          double *kbar_out, double *scores_out, void *ws, hipStream_t st)
+                          double *kbar_out, double *scores_out, void *ws, hipStream_t st, hipEvent_t *ev = nullptr)
 {
+    auto mark = [&](int i) { return ev ? hipEventRecord(ev[i], st) : hipSuccess; };
     double *qbar = qbar_out ? qbar_out : at<double>(ws, pl.off_qbar);
     double *kbar = kbar_out ? kbar_out : at<double>(ws, pl.off_kbar);
+    SLA_HIP(mark(0));
     SLA_HIP(sla::launch_pool(Q, sQ, pl.fp8, pl.BH, p->N, p->bq, qbar, st));
+    SLA_HIP(mark(1));
     SLA_HIP(sla::launch_pool(K, sK, pl.fp8, pl.BH, p->N, p->bk, kbar, st));
+    SLA_HIP(mark(2));
     SLA_HIP(sla::launch_scores(qbar, kbar, pl.BH, pl.Nqb, pl.Nkb, pl.s_pitch, at<double>(ws, pl.off_scores), st));
     int32_t *crit = crit_out ? crit_out : at<int32_t>(ws, pl.off_crit);
+    SLA_HIP(mark(3));
     SLA_HIP(sla::launch_select(at<double>(ws, pl.off_scores), pl.s_pitch, (long)pl.BH * pl.Nqb, pl.Nkb, pl.k_c, pl.k_n,
                                at<int8_t>(ws, pl.off_lab), pl.lab_pitch, labels, pl.k_c > 0 ? crit : nullptr, Pc,
                                scores_out, pl.sm_scale, st));
@@ -241,9 +246,9 @@ sla_status_t sla_sparse_combine(const sla_params_t *p, const void *Q, const void
     return SLA_OK;
 }
 
-sla_status_t sla_forward(const sla_params_t *p, const void *Q, const void *K, const void *V, const float *sQ,
-                         const float *sK, const float *sV, const void *W_proj, void *O, int8_t *labels,
-                         void *workspace, size_t workspace_bytes, void *stream)
+static sla_status_t forward_impl(const sla_params_t *p, const void *Q, const void *K, const void *V, const float *sQ,
+                                 const float *sK, const float *sV, const void *W_proj, void *O, int8_t *labels,
+                                 void *workspace, size_t workspace_bytes, void *stream, hipEvent_t *ev, bool *launched)
 {
     Plan pl;
     sla_status_t s = make_plan(p, pl);
@@ -253,15 +258,57 @@ sla_status_t sla_forward(const sla_params_t *p, const void *Q, const void *K, co
     if (pl.fp8) { SLA_REQ_PTR(sQ); SLA_REQ_PTR(sK); SLA_REQ_PTR(sV); }
     if ((s = check_ws(pl, workspace, workspace_bytes)) != SLA_OK) return s;
     hipStream_t st = (hipStream_t)stream;
-    if ((s = run_classify(p, pl, Q, K, sQ, sK, labels, nullptr, nullptr, nullptr, nullptr, nullptr, workspace, st)) != SLA_OK) return s;
+    auto mark = [&](int i) { return ev ? hipEventRecord(ev[i], st) : hipSuccess; };
+    if (launched) *launched = true;
+    if ((s = run_classify(p, pl, Q, K, sQ, sK, labels, nullptr, nullptr, nullptr, nullptr, nullptr, workspace, st, ev)) != SLA_OK) return s;
+    SLA_HIP(mark(4));
     SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), st));
+    SLA_HIP(mark(5));
     SLA_HIP(sla::launch_aggregate(at<int8_t>(workspace, pl.off_lab), pl.lab_pitch, at<void>(workspace, pl.off_hT), pl.BH, pl.Nqb,
                                   pl.Nkb, at<void>(workspace, pl.off_Hq), st));
+    SLA_HIP(mark(6));
     SLA_HIP(sla::launch_transpose_w(W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
+    SLA_HIP(mark(7));
     SLA_HIP(sla::launch_attend(Q, K, V, sQ, sK, sV, pl.fp8, at<int32_t>(workspace, pl.off_crit), pl.k_c,
                                at<void>(workspace, pl.off_Hq), at<void>(workspace, pl.off_WT), p->proj_per_head, p->B, p->H,
                                p->N, p->bq, pl.sm_scale, O, st));
+    SLA_HIP(mark(8));
     return SLA_OK;
+}
+
+sla_status_t sla_forward(const sla_params_t *p, const void *Q, const void *K, const void *V, const float *sQ,
+                         const float *sK, const float *sV, const void *W_proj, void *O, int8_t *labels,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    return forward_impl(p, Q, K, V, sQ, sK, sV, W_proj, O, labels, workspace, workspace_bytes, stream, nullptr, nullptr);
+}
+
+const char *sla_stage_name(int stage)
+{
+    static const char *names[SLA_NUM_STAGES] = {"pool_q", "pool_k", "scores", "select", "states", "aggregate", "transpose_w", "attend"};
+    return stage >= 0 && stage < SLA_NUM_STAGES ? names[stage] : "?";
+}
+
+sla_status_t sla_forward_profiled(const sla_params_t *p, const void *Q, const void *K, const void *V, const float *sQ,
+                                  const float *sK, const float *sV, const void *W_proj, void *O, int8_t *labels,
+                                  void *workspace, size_t workspace_bytes, void *stream, float *stage_ms)
+{
+    if (!stage_ms) return fail(SLA_ERR_INVALID_ARG, "stage_ms is NULL");
+    hipEvent_t ev[SLA_NUM_STAGES + 1];
+    int made = 0;
+    sla_status_t s = SLA_OK;
+    for (; made <= SLA_NUM_STAGES; ++made)
+        if (hipEventCreate(&ev[made]) != hipSuccess) { s = fail(SLA_ERR_HIP, "hipEventCreate failed"); break; }
+    bool launched = false;
+    if (s == SLA_OK) s = forward_impl(p, Q, K, V, sQ, sK, sV, W_proj, O, labels, workspace, workspace_bytes, stream, ev, &launched);
+    for (int i = 0; i < SLA_NUM_STAGES; ++i) stage_ms[i] = 0.f;
+    if (s == SLA_OK && launched) {
+        if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) s = fail(SLA_ERR_HIP, "hipStreamSynchronize failed");
+        for (int i = 0; s == SLA_OK && i < SLA_NUM_STAGES; ++i)
+            if (hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]) != hipSuccess) s = fail(SLA_ERR_HIP, "hipEventElapsedTime failed");
+    }
+    for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+    return s;
 }
 
 }  // extern "C"

@@ -16,6 +16,14 @@
 // transposed ([e][t']).  K and V tiles of a critical block are fetched once per workgroup
 // (register prefetch of the next tile while the current one is consumed).
 //
+// E4M3 inputs.  S^T is one v_mfma_f32_32x32x64_f8f6f4 per 32 keys (the whole head dimension
+// is the K dimension of the instruction; products of two E4M3 numbers are exact in the fp32
+// accumulator), with the per-block scales folded into the exp2 constant.  P is NOT cast to
+// E4M3: three mantissa bits on the softmax weights put the output error at several percent
+// of its RMS, above the 6e-2 bar, so P stays bf16 and V is widened to bf16 (exactly) while it
+// is staged; the second product runs on the bf16 MFMA.  The V block scale is folded into the
+// exponent of the weights, so no operand of that product is rounded twice.
+//
 // Epilogue (per wave, all MFMA): O_lin^T = Hq^T-tile x phi(Q)^T, scaled by 1/(phi(Q).Z),
 // then O^T += W^T x O_lin^T accumulated onto the normalised sparse output, stored as bf16.
 #include "sla_common.hpp"
@@ -23,57 +31,111 @@
 
 namespace sla {
 
-constexpr int kRow = 72;   // bf16 per LDS row (64 + 8 pad)
+constexpr int kRow = 72;    // bf16 per LDS row (64 + 8 pad: 144 B stride)
+constexpr int kRow8 = 80;   // bytes per LDS row of an E4M3 K tile (64 + 16 pad)
 constexpr float kLog2e = 1.4426950408889634f;
 
-template <int NW>
+// Registers that carry the next K/V tile from global memory to LDS.
+template <int NW, bool FP8>
 struct TileRegs {
     static constexpr int T = 64 * NW;
-    static constexpr int KCH = 512 / T;     // 16-byte K chunks per thread
-    static constexpr int VUN = 256 / T;     // V transpose units (2 channels x 8 tokens) per thread
+    static constexpr int KCH = (FP8 ? 256 : 512) / T;   // 16-byte K chunks per thread
+    static constexpr int VUN = 256 / T;                 // V transpose units per thread
+    static constexpr int VW = FP8 ? 4 : 8;              // dwords per unit
     uint4 k[KCH];
-    uint32_t v[VUN][8];
+    uint32_t v[VUN][VW];
 };
 
-template <int NW>
-__device__ __forceinline__ void load_tile_bf16(TileRegs<NW> &r, const uint16_t *Kg, const uint16_t *Vg, int valid, int tid)
+// bf16: K chunk c -> row c/8, 8 channels; V unit u -> 2 channels (pair u%32) x 8 tokens (group u/32)
+// e4m3: K chunk c -> row c/4, 16 channels; V unit u -> 4 channels (quad u%16) x 4 tokens (group u/16)
+template <int NW, bool FP8>
+__device__ __forceinline__ void load_tile(TileRegs<NW, FP8> &r, const void *Kp, const void *Vp, int valid, int tid)
 {
+    using R = TileRegs<NW, FP8>;
+    if (FP8) {
+        const uint8_t *Kg = (const uint8_t *)Kp, *Vg = (const uint8_t *)Vp;
 #pragma unroll
-    for (int x = 0; x < TileRegs<NW>::KCH; ++x) {
-        const int c = tid + TileRegs<NW>::T * x, t = c >> 3, col = (c & 7) * 8;
-        r.k[x] = make_uint4(0, 0, 0, 0);
-        if (t < valid) r.k[x] = *(const uint4 *)(Kg + (size_t)t * kD + col);
-    }
+        for (int x = 0; x < R::KCH; ++x) {
+            const int c = tid + R::T * x, t = c >> 2, col = (c & 3) * 16;
+            r.k[x] = make_uint4(0, 0, 0, 0);
+            if (t < valid) r.k[x] = *(const uint4 *)(Kg + (size_t)t * kD + col);
+        }
 #pragma unroll
-    for (int x = 0; x < TileRegs<NW>::VUN; ++x) {
-        const int u = tid + TileRegs<NW>::T * x, ep = u & 31, tg = u >> 5;
+        for (int x = 0; x < R::VUN; ++x) {
+            const int u = tid + R::T * x, eq = u & 15, tg = u >> 4;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int t = tg * 8 + k;
-            r.v[x][k] = t < valid ? *(const uint32_t *)(Vg + (size_t)t * kD + 2 * ep) : 0u;
+            for (int k = 0; k < R::VW; ++k) {
+                const int t = tg * 4 + k;
+                r.v[x][k] = t < valid ? *(const uint32_t *)(Vg + (size_t)t * kD + 4 * eq) : 0u;
+            }
+        }
+    } else {
+        const uint16_t *Kg = (const uint16_t *)Kp, *Vg = (const uint16_t *)Vp;
+#pragma unroll
+        for (int x = 0; x < R::KCH; ++x) {
+            const int c = tid + R::T * x, t = c >> 3, col = (c & 7) * 8;
+            r.k[x] = make_uint4(0, 0, 0, 0);
+            if (t < valid) r.k[x] = *(const uint4 *)(Kg + (size_t)t * kD + col);
+        }
+#pragma unroll
+        for (int x = 0; x < R::VUN; ++x) {
+            const int u = tid + R::T * x, ep = u & 31, tg = u >> 5;
+#pragma unroll
+            for (int k = 0; k < R::VW; ++k) {
+                const int t = tg * 8 + k;
+                r.v[x][k] = t < valid ? *(const uint32_t *)(Vg + (size_t)t * kD + 2 * ep) : 0u;
+            }
         }
     }
 }
 
-template <int NW>
-__device__ __forceinline__ void store_tile_bf16(const TileRegs<NW> &r, uint16_t *Ks, uint16_t *Vt, int tid)
+// Writes the staged tile to LDS: K row-major as loaded, V transposed to [channel][token] bf16.
+// An E4M3 V tile is widened to bf16 exactly; its block scale is applied to the softmax weights instead.
+template <int NW, bool FP8>
+__device__ __forceinline__ void store_tile(const TileRegs<NW, FP8> &r, uint8_t *Ks, uint16_t *Vt, int tid)
 {
+    using R = TileRegs<NW, FP8>;
+    if (FP8) {
 #pragma unroll
-    for (int x = 0; x < TileRegs<NW>::KCH; ++x) {
-        const int c = tid + TileRegs<NW>::T * x, t = c >> 3, col = (c & 7) * 8;
-        *(uint4 *)(Ks + t * kRow + col) = r.k[x];
-    }
+        for (int x = 0; x < R::KCH; ++x) {
+            const int c = tid + R::T * x, t = c >> 2, col = (c & 3) * 16;
+            *(uint4 *)(Ks + t * kRow8 + col) = r.k[x];
+        }
 #pragma unroll
-    for (int x = 0; x < TileRegs<NW>::VUN; ++x) {
-        const int u = tid + TileRegs<NW>::T * x, ep = u & 31, tg = u >> 5;
-        const uint32_t *w = r.v[x];
-        uint4 lo, hi;
-        lo.x = __builtin_amdgcn_perm(w[1], w[0], 0x05040100); hi.x = __builtin_amdgcn_perm(w[1], w[0], 0x07060302);
-        lo.y = __builtin_amdgcn_perm(w[3], w[2], 0x05040100); hi.y = __builtin_amdgcn_perm(w[3], w[2], 0x07060302);
-        lo.z = __builtin_amdgcn_perm(w[5], w[4], 0x05040100); hi.z = __builtin_amdgcn_perm(w[5], w[4], 0x07060302);
-        lo.w = __builtin_amdgcn_perm(w[7], w[6], 0x05040100); hi.w = __builtin_amdgcn_perm(w[7], w[6], 0x07060302);
-        *(uint4 *)(Vt + (2 * ep) * kRow + tg * 8) = lo;
-        *(uint4 *)(Vt + (2 * ep + 1) * kRow + tg * 8) = hi;
+        for (int x = 0; x < R::VUN; ++x) {
+            const int u = tid + R::T * x, eq = u & 15, tg = u >> 4;
+            float f[4][4];      // [token][channel]
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(r.v[x][k], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(r.v[x][k], true);
+                f[k][0] = lo[0]; f[k][1] = lo[1]; f[k][2] = hi[0]; f[k][3] = hi[1];
+            }
+#pragma unroll
+            for (int ch = 0; ch < 4; ++ch) {
+                uint2 o;
+                o.x = pack_bf16(f[0][ch], f[1][ch]);
+                o.y = pack_bf16(f[2][ch], f[3][ch]);
+                *(uint2 *)(Vt + (4 * eq + ch) * kRow + tg * 4) = o;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int x = 0; x < R::KCH; ++x) {
+            const int c = tid + R::T * x, t = c >> 3, col = (c & 7) * 8;
+            *(uint4 *)(Ks + (t * kRow + col) * 2) = r.k[x];
+        }
+#pragma unroll
+        for (int x = 0; x < R::VUN; ++x) {
+            const int u = tid + R::T * x, ep = u & 31, tg = u >> 5;
+            const uint32_t *w = r.v[x];
+            uint4 lo, hi;
+            lo.x = __builtin_amdgcn_perm(w[1], w[0], 0x05040100); hi.x = __builtin_amdgcn_perm(w[1], w[0], 0x07060302);
+            lo.y = __builtin_amdgcn_perm(w[3], w[2], 0x05040100); hi.y = __builtin_amdgcn_perm(w[3], w[2], 0x07060302);
+            lo.z = __builtin_amdgcn_perm(w[5], w[4], 0x05040100); hi.z = __builtin_amdgcn_perm(w[5], w[4], 0x07060302);
+            lo.w = __builtin_amdgcn_perm(w[7], w[6], 0x05040100); hi.w = __builtin_amdgcn_perm(w[7], w[6], 0x07060302);
+            *(uint4 *)(Vt + (2 * ep) * kRow + tg * 8) = lo;
+            *(uint4 *)(Vt + (2 * ep + 1) * kRow + tg * 8) = hi;
+        }
     }
 }
 
@@ -85,14 +147,16 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base)
     return __builtin_bit_cast(bf16x8, o);
 }
 
-template <int NW>
-__global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(
-    const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
+template <int NW, bool FP8>
+__global__ __launch_bounds__(64 * NW) void attend_kernel(
+    const void *__restrict__ Qp, const void *__restrict__ Kp, const void *__restrict__ Vp,
+    const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV,
     const int32_t *__restrict__ crit_idx, int k_c, const uint16_t *__restrict__ Hq, const uint16_t *__restrict__ WT,
     int proj_per_head, int H, int N, int Nqb, int Nkb, long total, float c_exp, uint16_t *__restrict__ O)
 {
     constexpr int BQ = 32 * NW;
-    __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * kRow];
+    constexpr int ES = FP8 ? 1 : 2;                     // bytes per input element
+    __shared__ __attribute__((aligned(16))) uint8_t Ks[FP8 ? 64 * kRow8 : 64 * kRow * 2];
     __shared__ __attribute__((aligned(16))) uint16_t Vt[64 * kRow];
     const long work = xcd_remap(blockIdx.x, total);
     if (work >= total) return;                        // the whole workgroup leaves together
@@ -101,40 +165,60 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(
     const int i = (int)(work - bh * Nqb);
     const int q = i * BQ + 32 * wave + l32;           // this lane's query row
     const bool qok = q < N;
-    const size_t head = (size_t)bh * N * kD;
+    const size_t head = (size_t)bh * N * kD;          // element offset of this (b,h)
+    const uint8_t *Kh = (const uint8_t *)Kp + head * ES, *Vh = (const uint8_t *)Vp + head * ES;
 
+    // Q as the B operand of S^T: bf16 -> 4 K-steps of 8 channels (16s + 8g ..), e4m3 -> 32 channels (32g ..)
     bf16x8 qf[4];
+    i32x8 q8;
+    if (FP8) {
+        uint4 w0 = make_uint4(0, 0, 0, 0), w1 = w0;
+        if (qok) {
+            const uint8_t *qr = (const uint8_t *)Qp + head + (size_t)q * kD + 32 * g;
+            w0 = *(const uint4 *)qr;
+            w1 = *(const uint4 *)(qr + 16);
+        }
+        q8[0] = w0.x; q8[1] = w0.y; q8[2] = w0.z; q8[3] = w0.w; q8[4] = w1.x; q8[5] = w1.y; q8[6] = w1.z; q8[7] = w1.w;
+    } else {
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        uint4 w = make_uint4(0, 0, 0, 0);
-        if (qok) w = *(const uint4 *)(Q + head + (size_t)q * kD + 16 * s + 8 * g);
-        qf[s] = __builtin_bit_cast(bf16x8, w);
+        for (int s = 0; s < 4; ++s) {
+            uint4 w = make_uint4(0, 0, 0, 0);
+            if (qok) w = *(const uint4 *)((const uint16_t *)Qp + head + (size_t)q * kD + 16 * s + 8 * g);
+            qf[s] = __builtin_bit_cast(bf16x8, w);
+        }
     }
+    const float qscale = FP8 ? sQ[work] : 1.0f;       // scale blocks of Q are the query blocks
 
     f32x16 oacc[2];
 #pragma unroll
     for (int e = 0; e < 2; ++e)
 #pragma unroll
         for (int x = 0; x < 16; ++x) oacc[e][x] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;             // running maximum in the log2 domain, running sum
     const bf16x8 ones = __builtin_bit_cast(bf16x8, make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u));
 
     const int32_t *ci = crit_idx + work * (long)k_c;
-    TileRegs<NW> regs;
+    TileRegs<NW, FP8> regs;
     int jn = k_c > 0 ? ci[0] : -1;
     if (jn >= Nkb) jn = -1;                          // never trust an index list blindly
-    if (jn >= 0) load_tile_bf16<NW>(regs, K + head + (size_t)jn * kBK * kD, V + head + (size_t)jn * kBK * kD, min(kBK, N - jn * kBK), tid);
+    if (jn >= 0) load_tile<NW, FP8>(regs, Kh + (size_t)jn * kBK * kD * ES, Vh + (size_t)jn * kBK * kD * ES, min(kBK, N - jn * kBK), tid);
 
     for (int c = 0; c < k_c; ++c) {
         const int j = jn;
         __syncthreads();                               // previous tile consumed by every wave
-        store_tile_bf16<NW>(regs, Ks, Vt, tid);
+        store_tile<NW, FP8>(regs, Ks, Vt, tid);
         __syncthreads();
         jn = c + 1 < k_c ? ci[c + 1] : -1;
         if (jn >= Nkb) jn = -1;
-        if (jn >= 0) load_tile_bf16<NW>(regs, K + head + (size_t)jn * kBK * kD, V + head + (size_t)jn * kBK * kD, min(kBK, N - jn * kBK), tid);
+        if (jn >= 0) load_tile<NW, FP8>(regs, Kh + (size_t)jn * kBK * kD * ES, Vh + (size_t)jn * kBK * kD * ES, min(kBK, N - jn * kBK), tid);
         if (j < 0) continue;
         const int valid = min(kBK, N - j * kBK);
+        // exp2 constant of this tile: softmax scale * log2(e) (* Q and K block scales for e4m3)
+        const float cj = FP8 ? fmaxf(c_exp * qscale * sK[bh * Nkb + j], 1e-30f) : c_exp;
+        // E4M3: the V block scale rides on the weights, P' = P * sV_j (an offset in the exponent); the
+        // row sum of P' is divided by sV_j again, so numerator and denominator stay consistent.
+        const float svj = FP8 ? fmaxf(sV[bh * Nkb + j], 1e-30f) : 1.0f;
+        const float lsv = FP8 ? __log2f(svj) : 0.0f;
 
         // ---- S^T = K Q^T
         f32x16 sacc[2];
@@ -142,13 +226,24 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(
         for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
             for (int x = 0; x < 16; ++x) sacc[h2][x] = 0.f;
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
+        if (FP8) {
 #pragma unroll
             for (int h2 = 0; h2 < 2; ++h2) {
-                const bf16x8 kf = *(const bf16x8 *)(Ks + (32 * h2 + l32) * kRow + 16 * s + 8 * g);
-                sacc[h2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[h2], 0, 0, 0);
+                const uint8_t *kr = Ks + (32 * h2 + l32) * kRow8 + 32 * g;
+                const uint4 w0 = *(const uint4 *)kr, w1 = *(const uint4 *)(kr + 16);
+                i32x8 k8;
+                k8[0] = w0.x; k8[1] = w0.y; k8[2] = w0.z; k8[3] = w0.w; k8[4] = w1.x; k8[5] = w1.y; k8[6] = w1.z; k8[7] = w1.w;
+                sacc[h2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(k8, q8, sacc[h2], 0, 0, 0, 0, 0, 0);
             }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) {
+                    const bf16x8 kf = *(const bf16x8 *)(Ks + ((32 * h2 + l32) * kRow + 16 * s + 8 * g) * 2);
+                    sacc[h2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[h2], 0, 0, 0);
+                }
+        }
         if (valid < kBK) {
 #pragma unroll
             for (int h2 = 0; h2 < 2; ++h2)
@@ -166,13 +261,13 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(
 #pragma unroll
         for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sacc[1][x]);
         mx = fmaxf(mx, xchg32(mx));
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = fast_exp2((m_run - m_new) * c_exp);
-        const float mc = m_new * c_exp;
+        const float m_new = fmaxf(m_run, mx * cj);
+        const float alpha = fast_exp2(m_run - m_new);
+        const float moff = lsv - m_new;
 #pragma unroll
         for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
-            for (int x = 0; x < 16; ++x) sacc[h2][x] = fast_exp2(fmaf(sacc[h2][x], c_exp, -mc));
+            for (int x = 0; x < 16; ++x) sacc[h2][x] = fast_exp2(fmaf(sacc[h2][x], cj, moff));
         m_run = m_new;
         if (__ballot(alpha != 1.0f)) {                 // the running maximum moved for some row of this wave
 #pragma unroll
@@ -198,27 +293,35 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(
                 oacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[e], 0, 0, 0);
             }
         }
-        l_run = l_run * alpha + lsum[0];               // every row of ones^T P^T is the full 64-key sum
+        l_run = l_run * alpha + (FP8 ? lsum[0] / svj : lsum[0]);   // every row of ones^T P^T is the full 64-key sum
     }
 
     // ---- normalise the sparse output
-    const float l_tot = l_run;
-    const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    const float inv_l = l_run > 0.f ? 1.0f / l_run : 0.f;
 #pragma unroll
     for (int e = 0; e < 2; ++e)
 #pragma unroll
         for (int x = 0; x < 16; ++x) oacc[e][x] *= inv_l;
 
     if (Hq != nullptr) {
-        // ---- phi(Q): softmax over the 64 channels of the row (this lane holds 32, lane^32 the rest)
+        // ---- phi(Q): softmax over the 64 channels of the row (this lane holds 32, lane^32 the rest).
+        // x[8s + c] is channel dcol(s) + c, the channel slot c of K-step s carries in the product below.
         float x[32];
+        if (FP8) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const uint4 w = __builtin_bit_cast(uint4, qf[s]);
-            x[8 * s + 0] = bf16_lo(w.x); x[8 * s + 1] = bf16_hi(w.x);
-            x[8 * s + 2] = bf16_lo(w.y); x[8 * s + 3] = bf16_hi(w.y);
-            x[8 * s + 4] = bf16_lo(w.z); x[8 * s + 5] = bf16_hi(w.z);
-            x[8 * s + 6] = bf16_lo(w.w); x[8 * s + 7] = bf16_hi(w.w);
+            for (int w = 0; w < 8; ++w) {
+                const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(q8[w], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(q8[w], true);
+                x[4 * w + 0] = lo[0] * qscale; x[4 * w + 1] = lo[1] * qscale; x[4 * w + 2] = hi[0] * qscale; x[4 * w + 3] = hi[1] * qscale;
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const uint4 w = __builtin_bit_cast(uint4, qf[s]);
+                x[8 * s + 0] = bf16_lo(w.x); x[8 * s + 1] = bf16_hi(w.x);
+                x[8 * s + 2] = bf16_lo(w.y); x[8 * s + 3] = bf16_hi(w.y);
+                x[8 * s + 4] = bf16_lo(w.z); x[8 * s + 5] = bf16_hi(w.z);
+                x[8 * s + 6] = bf16_lo(w.w); x[8 * s + 7] = bf16_hi(w.w);
+            }
         }
         float mx = x[0];
 #pragma unroll
@@ -234,11 +337,12 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(
         float den = 0.f;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
+            const int dcol = FP8 ? 32 * g + 8 * s : 16 * s + 8 * g;
             uint4 o;
             o.x = pack_bf16(x[8 * s + 0] * inv, x[8 * s + 1] * inv); o.y = pack_bf16(x[8 * s + 2] * inv, x[8 * s + 3] * inv);
             o.z = pack_bf16(x[8 * s + 4] * inv, x[8 * s + 5] * inv); o.w = pack_bf16(x[8 * s + 6] * inv, x[8 * s + 7] * inv);
             fq[s] = __builtin_bit_cast(bf16x8, o);
-            const uint4 z = *(const uint4 *)(Hi + 64 * kD + 16 * s + 8 * g);
+            const uint4 z = *(const uint4 *)(Hi + 64 * kD + dcol);
             den += bf16_lo(o.x) * bf16_lo(z.x) + bf16_hi(o.x) * bf16_hi(z.x) + bf16_lo(o.y) * bf16_lo(z.y) + bf16_hi(o.y) * bf16_hi(z.y)
                  + bf16_lo(o.z) * bf16_lo(z.z) + bf16_hi(o.z) * bf16_hi(z.z) + bf16_lo(o.w) * bf16_lo(z.w) + bf16_hi(o.w) * bf16_hi(z.w);
         }
@@ -252,12 +356,14 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(
 #pragma unroll
             for (int y = 0; y < 16; ++y) lacc[e][y] = 0.f;
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int s = 0; s < 4; ++s) {
+            const int dcol = FP8 ? 32 * g + 8 * s : 16 * s + 8 * g;
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                const bf16x8 hf = *(const bf16x8 *)(Hi + (32 * e + l32) * kD + 16 * s + 8 * g);
+                const bf16x8 hf = *(const bf16x8 *)(Hi + (32 * e + l32) * kD + dcol);
                 lacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hf, fq[s], lacc[e], 0, 0, 0);
             }
+        }
 #pragma unroll
         for (int e = 0; e < 2; ++e)
 #pragma unroll
@@ -310,25 +416,31 @@ hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st)
     return hipGetLastError();
 }
 
+template <int NW, bool FP8>
+static hipError_t launch_attend_t(const void *Q, const void *K, const void *V, const float *sQ, const float *sK, const float *sV,
+                                  const int32_t *crit_idx, int k_c, const void *Hq, const void *WT, int proj_per_head,
+                                  int H, int N, int Nqb, int Nkb, long total, float c_exp, void *O, hipStream_t st)
+{
+    attend_kernel<NW, FP8><<<(unsigned)xcd_grid(total), 64 * NW, 0, st>>>(Q, K, V, sQ, sK, sV, crit_idx, k_c, (const uint16_t *)Hq,
+                                                                          (const uint16_t *)WT, proj_per_head, H, N, Nqb, Nkb,
+                                                                          total, c_exp, (uint16_t *)O);
+    return hipGetLastError();
+}
+
 hipError_t launch_attend(const void *Q, const void *K, const void *V,
                          const float *sQ, const float *sK, const float *sV, bool fp8,
                          const int32_t *crit_idx, int k_c, const void *Hq, const void *WT,
                          int proj_per_head, int B, int H, int N, int bq, float sm_scale,
                          void *O, hipStream_t st)
 {
-    (void)sQ; (void)sK; (void)sV;
-    if (fp8) return hipErrorNotSupported;
     const int Nqb = (N + bq - 1) / bq, Nkb = (N + kBK - 1) / kBK;
     const long total = (long)B * H * Nqb;
-    const unsigned grid = (unsigned)xcd_grid(total);
     const float c_exp = sm_scale * kLog2e;
-    if (bq == 128)
-        attend_bf16_kernel<4><<<grid, 256, 0, st>>>((const uint16_t *)Q, (const uint16_t *)K, (const uint16_t *)V, crit_idx, k_c,
-                                                    (const uint16_t *)Hq, (const uint16_t *)WT, proj_per_head, H, N, Nqb, Nkb, total, c_exp, (uint16_t *)O);
-    else
-        attend_bf16_kernel<2><<<grid, 128, 0, st>>>((const uint16_t *)Q, (const uint16_t *)K, (const uint16_t *)V, crit_idx, k_c,
-                                                    (const uint16_t *)Hq, (const uint16_t *)WT, proj_per_head, H, N, Nqb, Nkb, total, c_exp, (uint16_t *)O);
-    return hipGetLastError();
+#define SLA_ATT(NW, F8) return launch_attend_t<NW, F8>(Q, K, V, sQ, sK, sV, crit_idx, k_c, Hq, WT, proj_per_head, H, N, Nqb, Nkb, total, c_exp, O, st)
+    if (bq == 128) { if (fp8) SLA_ATT(4, true); else SLA_ATT(4, false); }
+    if (fp8) SLA_ATT(2, true);
+    SLA_ATT(2, false);
+#undef SLA_ATT
 }
 
 }  // namespace sla

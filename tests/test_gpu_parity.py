@@ -24,6 +24,8 @@ SMALL = [
     ("c3_small", synth.CONFIGS[3].with_(B=3, H=2), -1, -1),
     ("c1_small", synth.CONFIGS[1].with_(H=2, N=2 * 1374), -1, -1),
     ("c2_small", synth.CONFIGS[2].with_(H=2, N=3 * 1374), -1, -1),
+    ("c4_small", synth.CONFIGS[4].with_(H=2, N=3 * 1374), -1, -1),
+    ("c4_bq64_tail", synth.CONFIGS[4].with_(H=2, N=1000, bq=64), 3, 5),
 ]
 
 
@@ -76,7 +78,7 @@ def test_classifier_duplicate_blocks_tie_exactly(oracle):
         assert np.array_equal(got["labels"], ref["labels"])
 
 
-@pytest.mark.parametrize("name", ["c0", "c0_tail150", "c1_small"])
+@pytest.mark.parametrize("name", ["c0", "c0_tail150", "c1_small", "c4_small"])
 def test_linear_states(oracle, name):
     case = _case(name)
     hT = G.bf16_tensor_to_f64(case.states())
@@ -89,7 +91,7 @@ def test_linear_states(oracle, name):
         assert np.abs(got[:, 64, :] - z).max() <= 2.0 ** -7 * np.abs(z).max()
 
 
-@pytest.mark.parametrize("name", ["c0", "c0_bq128_tail", "c1_small"])
+@pytest.mark.parametrize("name", ["c0", "c0_bq128_tail", "c1_small", "c4_small"])
 def test_marginal_aggregate(oracle, name):
     case = _case(name)
     lab = case.oracle_classify(oracle)["labels"]
@@ -107,7 +109,7 @@ def test_marginal_aggregate(oracle, name):
         assert np.abs(Hq[b, hh, :, 64, :] - Zref).max() <= 2.0 ** -6 * max(np.abs(Zref).max(), 1e-30)
 
 
-@pytest.mark.parametrize("name", ["c0", "c0_tail150", "c0_bq128_tail", "c1_small"])
+@pytest.mark.parametrize("name", ["c0", "c0_tail150", "c0_bq128_tail", "c1_small", "c4_small", "c4_bq64_tail"])
 def test_sparse_branch_alone(oracle, name):
     case = _case(name)
     lab = case.oracle_classify(oracle)["labels"]
@@ -115,7 +117,7 @@ def test_sparse_branch_alone(oracle, name):
     O = G.bf16_tensor_to_f64(case.sparse_combine(torch.from_numpy(lab).cuda(), None))
     sel = ref["sel"]
     got = G.gather_blocks(O, sel, case.cfg.bq, case.cfg.H)
-    G.assert_output(got, ref["O_sparse"], "bf16", name + " sparse branch")
+    G.assert_output(got, ref["O_sparse"], case.cfg.dtype, name + " sparse branch")
 
 
 @pytest.mark.parametrize("name", [s[0] for s in SMALL])

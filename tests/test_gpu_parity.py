@@ -169,3 +169,36 @@ def test_errors_are_reported_not_launched():
     with pytest.raises(B.SlaError) as e:
         B.sla_forward(case.p, case.Q, None, case.V, case.W, O, None, workspace=case.ws)
     assert e.value.status == B.SLA_ERR_INVALID_ARG
+
+
+# ------------------------------------------------------------------ full-size configurations
+# The five benchmark configurations at their real shapes, in the launch configuration bench.py
+# times.  Labels are compared on the whole tensor; outputs on query blocks the oracle can
+# evaluate one by one (all of them for configuration 1, a seeded sample elsewhere that always
+# contains the first and the ragged last query block of some head).
+def _sample_blocks(case, n, seed=0):
+    rng = np.random.default_rng(seed)
+    BH = case.cfg.B * case.cfg.H
+    heads = sorted(rng.choice(BH, size=min(BH, max(3, 2 * n // case.Nqb + 1)), replace=False).tolist())
+    n = min(n, len(heads) * case.Nqb)
+    sel = {(heads[0], 0), (heads[0], case.Nqb - 1), (heads[-1], case.Nqb - 1)}
+    while len(sel) < n:
+        sel.add((int(rng.choice(heads)), int(rng.integers(case.Nqb))))
+    return sorted(sel)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("idx,nsample", [(1, None), (2, 48), (3, 96), (4, 24)])
+def test_full_size_configuration(oracle, idx, nsample):
+    cfg = synth.CONFIGS[idx]
+    case = G.Case(cfg)
+    O, lab = case.forward()
+    refc = case.oracle_classify(oracle)
+    mism = int((lab.cpu().numpy() != refc["labels"]).sum())
+    assert mism == 0, f"{mism} block labels differ"
+    assert ((refc["labels"] == 2).sum(-1) == case.k_c).all() and ((refc["labels"] == 0).sum(-1) == case.k_n).all()
+    sel = None if nsample is None else _sample_blocks(case, nsample)
+    ref = case.oracle_attend(oracle, refc["labels"], sel)
+    got = G.gather_blocks(G.bf16_tensor_to_f64(O), ref["sel"], cfg.bq, cfg.H)
+    G.assert_output(got, ref["O"], cfg.dtype, f"{cfg.name} ({len(ref['sel'])} query blocks)")
+    assert torch.isfinite(O.float()).all()

@@ -329,6 +329,197 @@ __global__ __launch_bounds__(64) void select_kernel(const double *__restrict__ S
     }
 }
 
+// ---- workgroup-per-row variant for long rows (Nkb > 256) ------------------------------------
+// 256 threads, thread t owns the KPT consecutive blocks j = t*KPT .. t*KPT+KPT-1, so index order
+// is (thread, slot) order and every ordered step (tie ranks, index-list compaction) is one
+// workgroup-wide exclusive scan of per-thread counts.
+
+struct SelShared {
+    uint32_t hist[256];
+    uint32_t wsum[4];
+    uint32_t bc[4];
+    uint64_t red[8];
+};
+
+// exclusive prefix over the 256 threads of per-thread value v; *total receives the sum
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, SelShared &sh, uint32_t *total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t u = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += u;
+    }
+    __syncthreads();                                   // wsum may still be read by a previous scan
+    if (lane == 63) sh.wsum[wave] = incl;
+    __syncthreads();
+    uint32_t base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) { const uint32_t x = sh.wsum[w]; if (w < wave) base += x; tot += x; }
+    if (total) *total = tot;
+    return base + incl - v;
+}
+
+template <int KPT>
+__device__ void block_radix_select(const uint64_t (&key)[KPT], int j0, int Nkb, int k, SelShared &sh, uint64_t &T, int &r)
+{
+    const int tid = threadIdx.x;
+    uint64_t prefix = 0;
+    int kk = k, shift = 56, nb = 0;
+    for (;;) {
+        __syncthreads();
+        sh.hist[tid] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int m = 0; m < KPT; ++m) {
+            const bool cand = (j0 + m < Nkb) && (shift == 56 || (key[m] >> (shift + 8)) == prefix);
+            if (cand) atomicAdd(&sh.hist[(uint32_t)(key[m] >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        const uint32_t c = sh.hist[tid];
+        const uint32_t excl = block_excl_scan(c, sh, nullptr);
+        if (excl < (uint32_t)kk && (uint32_t)kk <= excl + c) { sh.bc[0] = tid; sh.bc[1] = excl; sh.bc[2] = c; }
+        __syncthreads();
+        prefix = (prefix << 8) | sh.bc[0];
+        kk -= (int)sh.bc[1];
+        nb = (int)sh.bc[2];
+        if (nb == 1 || shift == 0) break;
+        shift -= 8;
+    }
+    if (shift == 0) { T = prefix; r = kk; return; }
+    __syncthreads();
+#pragma unroll
+    for (int m = 0; m < KPT; ++m)
+        if ((j0 + m < Nkb) && (key[m] >> shift) == prefix) sh.red[0] = key[m];   // exactly one thread
+    __syncthreads();
+    T = sh.red[0];
+    r = 1;
+}
+
+template <int KPT>
+__global__ __launch_bounds__(256) void select_block_kernel(const double *__restrict__ S, int pitch, int Nkb, int k_c, int k_n,
+                                                           int8_t *__restrict__ lab_pad, int lab_pitch,
+                                                           int8_t *__restrict__ lab_dense, int32_t *__restrict__ crit_idx,
+                                                           float *__restrict__ Pc, double *__restrict__ S_dense, float sm_scale)
+{
+    __shared__ SelShared sh;
+    const long row = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j0 = tid * KPT;
+    const double *s = S + row * pitch;
+    uint64_t key[KPT];
+    uint64_t kmin = ~0ull, kmax = 0;
+#pragma unroll
+    for (int m = 0; m < KPT; ++m) {
+        const int j = j0 + m;
+        key[m] = ~0ull;
+        if (j < Nkb) {
+            const double v = s[j];
+            if (S_dense) S_dense[row * Nkb + j] = v;
+            key[m] = desc_key(v);
+            kmin = key[m] < kmin ? key[m] : kmin;
+            kmax = key[m] > kmax ? key[m] : kmax;
+        }
+    }
+    kmin = wave_min_u64(kmin);
+    kmax = wave_max_u64(kmax);
+    if (lane == 0) { sh.red[wave] = kmin; sh.red[4 + wave] = kmax; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        kmin = sh.red[w] < kmin ? sh.red[w] : kmin;
+        kmax = sh.red[4 + w] > kmax ? sh.red[4 + w] : kmax;
+    }
+    __syncthreads();
+
+    if (Pc) {
+        const double smax = key_to_logit(kmin);
+        float e[KPT], sum = 0.f;
+#pragma unroll
+        for (int m = 0; m < KPT; ++m) {
+            e[m] = 0.f;
+            if (j0 + m < Nkb) { e[m] = __expf((float)((key_to_logit(key[m]) - smax) * (double)sm_scale)); sum += e[m]; }
+        }
+        sum = wave_sum(sum);
+        float *fs = (float *)sh.wsum;
+        if (lane == 0) fs[wave] = sum;
+        __syncthreads();
+        const float inv = 1.f / (fs[0] + fs[1] + fs[2] + fs[3]);
+        __syncthreads();
+#pragma unroll
+        for (int m = 0; m < KPT; ++m)
+            if (j0 + m < Nkb) Pc[row * Nkb + j0 + m] = e[m] * inv;
+    }
+
+    const uint64_t range = kmax - kmin;
+    const int shn = range ? __clzll((long long)range) : 0;
+#pragma unroll
+    for (int m = 0; m < KPT; ++m) key[m] = (key[m] - kmin) << shn;
+
+    const int k_keep = Nkb - k_n;
+    uint64_t Tc = 0, Tn = 0;
+    int rc = 0, rn = 0;
+    const bool do_c = k_c > 0 && k_c < Nkb, do_n = k_keep > 0 && k_keep < Nkb;
+    if (do_c) block_radix_select<KPT>(key, j0, Nkb, k_c, sh, Tc, rc);
+    if (do_n) block_radix_select<KPT>(key, j0, Nkb, k_keep, sh, Tn, rn);
+
+    // ranks among exact ties of each threshold, in index order
+    uint32_t eqc = 0, eqn = 0;
+#pragma unroll
+    for (int m = 0; m < KPT; ++m) {
+        const bool valid = j0 + m < Nkb;
+        eqc += (do_c && valid && key[m] == Tc) ? 1u : 0u;
+        eqn += (do_n && valid && key[m] == Tn) ? 1u : 0u;
+    }
+    uint32_t tie_c = do_c ? block_excl_scan(eqc, sh, nullptr) : 0u;
+    uint32_t tie_n = do_n ? block_excl_scan(eqn, sh, nullptr) : 0u;
+
+    int8_t lab[KPT];
+    uint32_t ncrit = 0;
+#pragma unroll
+    for (int m = 0; m < KPT; ++m) {
+        const bool valid = j0 + m < Nkb;
+        bool selc, seln;
+        if (!do_c) selc = k_c > 0 && valid;            // k_c >= Nkb: everything critical; k_c == 0: nothing
+        else {
+            const bool eq = valid && key[m] == Tc;
+            selc = valid && (key[m] < Tc || (eq && (int)tie_c < rc));
+            tie_c += eq ? 1u : 0u;
+        }
+        if (!do_n) seln = k_keep > 0 && valid;
+        else {
+            const bool eq = valid && key[m] == Tn;
+            seln = valid && (key[m] < Tn || (eq && (int)tie_n < rn));
+            tie_n += eq ? 1u : 0u;
+        }
+        lab[m] = selc ? 2 : (seln ? 1 : 0);
+        ncrit += selc ? 1u : 0u;
+    }
+#pragma unroll
+    for (int m = 0; m < KPT; ++m) {
+        const int j = j0 + m;
+        if (j < lab_pitch) lab_pad[row * lab_pitch + j] = lab[m];
+        if (lab_dense && j < Nkb) lab_dense[row * Nkb + j] = lab[m];
+    }
+    if (crit_idx) {
+        uint32_t pos = block_excl_scan(ncrit, sh, nullptr);
+#pragma unroll
+        for (int m = 0; m < KPT; ++m)
+            if (lab[m] == 2) { if ((int)pos < k_c) crit_idx[row * k_c + pos] = j0 + m; ++pos; }
+    }
+}
+
+template <int KPT>
+static hipError_t launch_select_block_t(const double *S, int pitch, long rows, int Nkb, int k_c, int k_n, int8_t *lab_pad,
+                                        int lab_pitch, int8_t *lab_dense, int32_t *crit_idx, float *Pc, double *S_dense,
+                                        float sm_scale, hipStream_t st)
+{
+    select_block_kernel<KPT><<<(unsigned)rows, 256, 0, st>>>(S, pitch, Nkb, k_c, k_n, lab_pad, lab_pitch, lab_dense,
+                                                            crit_idx, Pc, S_dense, sm_scale);
+    return hipGetLastError();
+}
+
 template <int KPL>
 static hipError_t launch_select_t(const double *S, int pitch, long rows, int Nkb, int k_c, int k_n, int8_t *lab_pad,
                                   int lab_pitch, int8_t *lab_dense, int32_t *crit_idx, float *Pc, double *S_dense,
@@ -347,11 +538,16 @@ hipError_t launch_select(const double *S, int pitch, long rows, int Nkb, int k_c
     if (lab_pitch <= 64) SLA_SEL(1);
     if (lab_pitch <= 128) SLA_SEL(2);
     if (lab_pitch <= 256) SLA_SEL(4);
-    if (lab_pitch <= 512) SLA_SEL(8);
-    if (lab_pitch <= 1024) SLA_SEL(16);
-    if (lab_pitch <= 2048) SLA_SEL(32);
-    if (lab_pitch <= 4096) SLA_SEL(64);
 #undef SLA_SEL
+#define SLA_SELB(K) return launch_select_block_t<K>(S, pitch, rows, Nkb, k_c, k_n, lab_pad, lab_pitch, lab_dense, crit_idx, Pc, S_dense, sm_scale, st)
+    if (lab_pitch <= 512) SLA_SELB(2);
+    if (lab_pitch <= 1024) SLA_SELB(4);
+    if (lab_pitch <= 1536) SLA_SELB(6);
+    if (lab_pitch <= 2048) SLA_SELB(8);
+    if (lab_pitch <= 2560) SLA_SELB(10);
+    if (lab_pitch <= 3072) SLA_SELB(12);
+    if (lab_pitch <= 4096) SLA_SELB(16);
+#undef SLA_SELB
     return hipErrorInvalidValue;
 }
 

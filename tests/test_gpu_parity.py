@@ -78,6 +78,29 @@ def test_classifier_duplicate_blocks_tie_exactly(oracle):
         assert np.array_equal(got["labels"], ref["labels"])
 
 
+@pytest.mark.parametrize("nkb,kc,kn", [(300, 15, 200), (300, 1, 299), (300, 299, 1), (300, 0, 150), (700, 35, 560), (1100, 3, 1000)])
+def test_classifier_long_rows(oracle, nkb, kc, kn):
+    """Rows longer than 256 key blocks take the workgroup-per-row classifier; include exact ties."""
+    cfg = C0.with_(H=1, N=nkb * 64 - 17, n_clusters=256)
+    d = synth.make_inputs(cfg)
+    for variant in ("plain", "dup", "allties"):
+        dd = dict(d)
+        if variant == "dup":
+            dd["K"] = d["K"].copy()
+            for dst in (5, 77, 250, 298 if nkb <= 300 else 650):
+                dd["K"][:, :, dst * 64:(dst + 1) * 64] = d["K"][:, :, 3 * 64:4 * 64]
+        if variant == "allties":
+            dd["Q"] = np.zeros_like(d["Q"])
+        case = G.Case(cfg, dd, k_crit=kc, k_neg=kn)
+        got = case.classify(want=("crit_idx", "Pc"))
+        ref = case.oracle_classify(oracle, want_pc=True)
+        assert np.array_equal(got["labels"], ref["labels"]), variant
+        np.testing.assert_allclose(got["Pc"], ref["Pc"], rtol=2e-5, atol=1e-9)
+        if kc > 0:
+            for i in range(case.Nqb):
+                assert np.array_equal(got["crit_idx"][0, 0, i], np.nonzero(ref["labels"][0, 0, i] == 2)[0])
+
+
 @pytest.mark.parametrize("name", ["c0", "c0_tail150", "c1_small", "c4_small"])
 def test_linear_states(oracle, name):
     case = _case(name)

@@ -12,16 +12,24 @@
 // 8a + 4g + b (g = lane/32; register 4a+b), so the online-softmax row statistics are 31
 // in-lane operations plus one exchange with lane^32.  The B operand of the second product
 // takes accumulator registers 8u..8u+7, i.e. keys 16s + 8a' + 4g + b; the V^T rows are read
-// from LDS with exactly that key permutation (two 8-byte reads), which is why V is staged
-// transposed ([e][t']).  K and V tiles of a critical block are fetched once per workgroup
-// (register prefetch of the next tile while the current one is consumed).
+// with exactly that key permutation: the states kernel leaves V^T of every key block in that
+// order (bf16), so a V^T fragment is one 16-byte LDS read like a K fragment.
+//
+// Memory pipeline.  K and V^T tiles go from global memory straight into LDS
+// (global_load_lds_dwordx4, no staging registers) into a ring of three stages; the tile of
+// iteration c+2 is requested while tile c is consumed, and a single workgroup barrier per
+// iteration both publishes tile c and frees the stage of tile c-1.  Rows are stored unpadded
+// with the 16-byte chunk index XOR-ed by row bits (applied on the global side of the copy),
+// which keeps the fragment reads free of bank conflicts.  Every wave issues the same number of
+// copies per tile (rows past a ragged end are clamped, absent list entries copy block 0), so
+// s_waitcnt vmcnt(n) with a compile-time n identifies "tile c has landed".
 //
 // E4M3 inputs.  S^T is one v_mfma_f32_32x32x64_f8f6f4 per 32 keys (the whole head dimension
 // is the K dimension of the instruction; products of two E4M3 numbers are exact in the fp32
 // accumulator), with the per-block scales folded into the exp2 constant.  P is NOT cast to
 // E4M3: three mantissa bits on the softmax weights put the output error at several percent
-// of its RMS, above the 6e-2 bar, so P stays bf16 and V is widened to bf16 (exactly) while it
-// is staged; the second product runs on the bf16 MFMA.  The V block scale is folded into the
+// of its RMS, above the 6e-2 bar, so P stays bf16, V^T arrives widened to bf16 (exactly) from
+// the states kernel, and the second product runs on the bf16 MFMA.  The V block scale is folded into the
 // exponent of the weights, so no operand of that product is rounded twice.
 //
 // Epilogue (per wave, all MFMA): O_lin^T = Hq^T-tile x phi(Q)^T, scaled by 1/(phi(Q).Z),
@@ -31,111 +39,60 @@
 
 namespace sla {
 
-constexpr int kRow = 72;    // bf16 per LDS row (64 + 8 pad: 144 B stride)
-constexpr int kRow8 = 80;   // bytes per LDS row of an E4M3 K tile (64 + 16 pad)
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kStages = 3;
+constexpr float kLazyMax = 8.0f;   // the running maximum is only raised when a row exceeds it by 2^8
 
-// Registers that carry the next K/V tile from global memory to LDS.
-template <int NW, bool FP8>
-struct TileRegs {
-    static constexpr int T = 64 * NW;
-    static constexpr int KCH = (FP8 ? 256 : 512) / T;   // 16-byte K chunks per thread
-    static constexpr int VUN = 256 / T;                 // V transpose units per thread
-    static constexpr int VW = FP8 ? 4 : 8;              // dwords per unit
-    uint4 k[KCH];
-    uint32_t v[VUN][VW];
-};
+typedef __attribute__((address_space(3))) void *lds_void_p;
+typedef __attribute__((address_space(1))) const void *glb_void_p;
 
-// bf16: K chunk c -> row c/8, 8 channels; V unit u -> 2 channels (pair u%32) x 8 tokens (group u/32)
-// e4m3: K chunk c -> row c/4, 16 channels; V unit u -> 4 channels (quad u%16) x 4 tokens (group u/16)
-template <int NW, bool FP8>
-__device__ __forceinline__ void load_tile(TileRegs<NW, FP8> &r, const void *Kp, const void *Vp, int valid, int tid)
+// XOR swizzle of 16-byte chunks: 8 chunks per 128-byte row / 4 chunks per 64-byte row
+__device__ __forceinline__ int swz8(int row) { return (row >> 1) & 7; }
+__device__ __forceinline__ int swz4(int row) { return (row >> 2) & 3; }
+
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+template <int N> __device__ __forceinline__ void wait_vmcnt()
 {
-    using R = TileRegs<NW, FP8>;
-    if (FP8) {
-        const uint8_t *Kg = (const uint8_t *)Kp, *Vg = (const uint8_t *)Vp;
-#pragma unroll
-        for (int x = 0; x < R::KCH; ++x) {
-            const int c = tid + R::T * x, t = c >> 2, col = (c & 3) * 16;
-            r.k[x] = make_uint4(0, 0, 0, 0);
-            if (t < valid) r.k[x] = *(const uint4 *)(Kg + (size_t)t * kD + col);
-        }
-#pragma unroll
-        for (int x = 0; x < R::VUN; ++x) {
-            const int u = tid + R::T * x, eq = u & 15, tg = u >> 4;
-#pragma unroll
-            for (int k = 0; k < R::VW; ++k) {
-                const int t = tg * 4 + k;
-                r.v[x][k] = t < valid ? *(const uint32_t *)(Vg + (size_t)t * kD + 4 * eq) : 0u;
-            }
-        }
-    } else {
-        const uint16_t *Kg = (const uint16_t *)Kp, *Vg = (const uint16_t *)Vp;
-#pragma unroll
-        for (int x = 0; x < R::KCH; ++x) {
-            const int c = tid + R::T * x, t = c >> 3, col = (c & 7) * 8;
-            r.k[x] = make_uint4(0, 0, 0, 0);
-            if (t < valid) r.k[x] = *(const uint4 *)(Kg + (size_t)t * kD + col);
-        }
-#pragma unroll
-        for (int x = 0; x < R::VUN; ++x) {
-            const int u = tid + R::T * x, ep = u & 31, tg = u >> 5;
-#pragma unroll
-            for (int k = 0; k < R::VW; ++k) {
-                const int t = tg * 8 + k;
-                r.v[x][k] = t < valid ? *(const uint32_t *)(Vg + (size_t)t * kD + 2 * ep) : 0u;
-            }
-        }
-    }
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-// Writes the staged tile to LDS: K row-major as loaded, V transposed to [channel][token] bf16.
-// An E4M3 V tile is widened to bf16 exactly; its block scale is applied to the softmax weights instead.
 template <int NW, bool FP8>
-__device__ __forceinline__ void store_tile(const TileRegs<NW, FP8> &r, uint8_t *Ks, uint16_t *Vt, int tid)
+struct Tile {
+    static constexpr int KBYTES = FP8 ? 64 * 64 : 64 * 128;     // K tile (e4m3 / bf16)
+    static constexpr int VBYTES = 64 * 128;                     // V^T tile (always bf16)
+    static constexpr int STAGE = KBYTES + VBYTES;
+    static constexpr int KINS = KBYTES / 1024 / NW;             // 1 KB copy instructions per wave
+    static constexpr int VINS = VBYTES / 1024 / NW;
+    static constexpr int LOADS = KINS + VINS;                   // per wave per tile
+};
+
+// Requests one K tile and one V^T tile into an LDS stage.  kt / vt: first byte of the tiles in
+// global memory; valid: number of real rows of the K tile (rows past it are clamped to the last).
+template <int NW, bool FP8>
+__device__ __forceinline__ void issue_tile(uint8_t *stage, const uint8_t *kt, const uint8_t *vt, int valid, int wave, int lane)
 {
-    using R = TileRegs<NW, FP8>;
-    if (FP8) {
+    using T = Tile<NW, FP8>;
 #pragma unroll
-        for (int x = 0; x < R::KCH; ++x) {
-            const int c = tid + R::T * x, t = c >> 2, col = (c & 3) * 16;
-            *(uint4 *)(Ks + t * kRow8 + col) = r.k[x];
+    for (int x = 0; x < T::KINS; ++x) {
+        const int ins = wave * T::KINS + x;
+        if (FP8) {
+            const int r = ins * 16 + (lane >> 2), chunk = (lane & 3) ^ swz4(r);
+            const uint8_t *src = kt + (size_t)min(r, valid - 1) * 64 + chunk * 16;
+            __builtin_amdgcn_global_load_lds((glb_void_p)src, (lds_void_p)(stage + ins * 1024), 16, 0, 0);
+        } else {
+            const int r = ins * 8 + (lane >> 3), chunk = (lane & 7) ^ swz8(r);
+            const uint8_t *src = kt + (size_t)min(r, valid - 1) * 128 + chunk * 16;
+            __builtin_amdgcn_global_load_lds((glb_void_p)src, (lds_void_p)(stage + ins * 1024), 16, 0, 0);
         }
+    }
 #pragma unroll
-        for (int x = 0; x < R::VUN; ++x) {
-            const int u = tid + R::T * x, eq = u & 15, tg = u >> 4;
-            float f[4][4];      // [token][channel]
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(r.v[x][k], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(r.v[x][k], true);
-                f[k][0] = lo[0]; f[k][1] = lo[1]; f[k][2] = hi[0]; f[k][3] = hi[1];
-            }
-#pragma unroll
-            for (int ch = 0; ch < 4; ++ch) {
-                uint2 o;
-                o.x = pack_bf16(f[0][ch], f[1][ch]);
-                o.y = pack_bf16(f[2][ch], f[3][ch]);
-                *(uint2 *)(Vt + (4 * eq + ch) * kRow + tg * 4) = o;
-            }
-        }
-    } else {
-#pragma unroll
-        for (int x = 0; x < R::KCH; ++x) {
-            const int c = tid + R::T * x, t = c >> 3, col = (c & 7) * 8;
-            *(uint4 *)(Ks + (t * kRow + col) * 2) = r.k[x];
-        }
-#pragma unroll
-        for (int x = 0; x < R::VUN; ++x) {
-            const int u = tid + R::T * x, ep = u & 31, tg = u >> 5;
-            const uint32_t *w = r.v[x];
-            uint4 lo, hi;
-            lo.x = __builtin_amdgcn_perm(w[1], w[0], 0x05040100); hi.x = __builtin_amdgcn_perm(w[1], w[0], 0x07060302);
-            lo.y = __builtin_amdgcn_perm(w[3], w[2], 0x05040100); hi.y = __builtin_amdgcn_perm(w[3], w[2], 0x07060302);
-            lo.z = __builtin_amdgcn_perm(w[5], w[4], 0x05040100); hi.z = __builtin_amdgcn_perm(w[5], w[4], 0x07060302);
-            lo.w = __builtin_amdgcn_perm(w[7], w[6], 0x05040100); hi.w = __builtin_amdgcn_perm(w[7], w[6], 0x07060302);
-            *(uint4 *)(Vt + (2 * ep) * kRow + tg * 8) = lo;
-            *(uint4 *)(Vt + (2 * ep + 1) * kRow + tg * 8) = hi;
-        }
+    for (int x = 0; x < T::VINS; ++x) {
+        const int ins = wave * T::VINS + x;
+        const int r = ins * 8 + (lane >> 3), chunk = (lane & 7) ^ swz8(r);
+        const uint8_t *src = vt + (size_t)r * 128 + chunk * 16;
+        __builtin_amdgcn_global_load_lds((glb_void_p)src, (lds_void_p)(stage + T::KBYTES + ins * 1024), 16, 0, 0);
     }
 }
 
@@ -149,15 +106,15 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base)
 
 template <int NW, bool FP8>
 __global__ __launch_bounds__(64 * NW) void attend_kernel(
-    const void *__restrict__ Qp, const void *__restrict__ Kp, const void *__restrict__ Vp,
+    const void *__restrict__ Qp, const void *__restrict__ Kp, const uint16_t *__restrict__ Vp,
     const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV,
     const int32_t *__restrict__ crit_idx, int k_c, const uint16_t *__restrict__ Hq, const uint16_t *__restrict__ WT,
     int proj_per_head, int H, int N, int Nqb, int Nkb, long total, float c_exp, uint16_t *__restrict__ O)
 {
+    using T = Tile<NW, FP8>;
     constexpr int BQ = 32 * NW;
     constexpr int ES = FP8 ? 1 : 2;                     // bytes per input element
-    __shared__ __attribute__((aligned(16))) uint8_t Ks[FP8 ? 64 * kRow8 : 64 * kRow * 2];
-    __shared__ __attribute__((aligned(16))) uint16_t Vt[64 * kRow];
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[kStages * T::STAGE];
     const long work = xcd_remap(blockIdx.x, total);
     if (work >= total) return;                        // the whole workgroup leaves together
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
@@ -166,7 +123,8 @@ __global__ __launch_bounds__(64 * NW) void attend_kernel(
     const int q = i * BQ + 32 * wave + l32;           // this lane's query row
     const bool qok = q < N;
     const size_t head = (size_t)bh * N * kD;          // element offset of this (b,h)
-    const uint8_t *Kh = (const uint8_t *)Kp + head * ES, *Vh = (const uint8_t *)Vp + head * ES;
+    const uint8_t *Kh = (const uint8_t *)Kp + head * ES;
+    const uint8_t *Vh = (const uint8_t *)(Vp + (size_t)bh * Nkb * kBK * kD);
 
     // Q as the B operand of S^T: bf16 -> 4 K-steps of 8 channels (16s + 8g ..), e4m3 -> 32 channels (32g ..)
     bf16x8 qf[4];
@@ -189,29 +147,47 @@ __global__ __launch_bounds__(64 * NW) void attend_kernel(
     }
     const float qscale = FP8 ? sQ[work] : 1.0f;       // scale blocks of Q are the query blocks
 
-    f32x16 oacc[2];
+    // per-lane LDS byte offsets of the fragments (row l32, chunk 2s+g, swizzled); the second
+    // 32-row half of a tile is a fixed 32 rows further
+    int koff[4], voff[4];
 #pragma unroll
-    for (int e = 0; e < 2; ++e)
+    for (int s = 0; s < 4; ++s) {
+        voff[s] = T::KBYTES + l32 * 128 + (((2 * s + g) ^ swz8(l32)) << 4);
+        koff[s] = FP8 ? l32 * 64 + ((((2 * g + (s & 1)) ^ swz4(l32))) << 4) : l32 * 128 + (((2 * s + g) ^ swz8(l32)) << 4);
+    }
+
+    f32x16 zero16;
 #pragma unroll
-        for (int x = 0; x < 16; ++x) oacc[e][x] = 0.f;
+    for (int x = 0; x < 16; ++x) zero16[x] = 0.f;
+    f32x16 oacc[2] = {zero16, zero16};
     float m_run = -INFINITY, l_run = 0.f;             // running maximum in the log2 domain, running sum
     const bf16x8 ones = __builtin_bit_cast(bf16x8, make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u));
 
     const int32_t *ci = crit_idx + work * (long)k_c;
-    TileRegs<NW, FP8> regs;
-    int jn = k_c > 0 ? ci[0] : -1;
-    if (jn >= Nkb) jn = -1;                          // never trust an index list blindly
-    if (jn >= 0) load_tile<NW, FP8>(regs, Kh + (size_t)jn * kBK * kD * ES, Vh + (size_t)jn * kBK * kD * ES, min(kBK, N - jn * kBK), tid);
+    auto tile_index = [&](int c) {                     // -1: no such tile (list exhausted or entry absent)
+        int j = c < k_c ? ci[c] : -1;
+        return (j < 0 || j >= Nkb) ? -1 : j;
+    };
+    auto request = [&](int c, int j) {
+        const int jj = j < 0 ? 0 : j;                  // absent entries still copy (block 0) so the copy count is uniform
+        issue_tile<NW, FP8>(lds + (c % kStages) * T::STAGE, Kh + (size_t)jj * kBK * kD * ES, Vh + (size_t)jj * kBK * kD * 2,
+                            min(kBK, N - jj * kBK), wave, lane);
+    };
+    int j0 = tile_index(0), j1 = tile_index(1);
+    if (k_c > 0) request(0, j0);
+    if (k_c > 1) request(1, j1);
 
     for (int c = 0; c < k_c; ++c) {
-        const int j = jn;
-        __syncthreads();                               // previous tile consumed by every wave
-        store_tile<NW, FP8>(regs, Ks, Vt, tid);
-        __syncthreads();
-        jn = c + 1 < k_c ? ci[c + 1] : -1;
-        if (jn >= Nkb) jn = -1;
-        if (jn >= 0) load_tile<NW, FP8>(regs, Kh + (size_t)jn * kBK * kD * ES, Vh + (size_t)jn * kBK * kD * ES, min(kBK, N - jn * kBK), tid);
+        const int j = j0;
+        // copies of tiles 0..c+1 have been requested; tile c has landed once only those of tile c+1 remain
+        if (c + 1 < k_c) wait_vmcnt<T::LOADS>();
+        else wait_vmcnt<0>();
+        lds_barrier();                                 // tile c visible to all waves; stage of tile c-1 free
+        j0 = j1;
+        j1 = tile_index(c + 2);
+        if (c + 2 < k_c) request(c + 2, j1);
         if (j < 0) continue;
+        const uint8_t *st = lds + (c % kStages) * T::STAGE;
         const int valid = min(kBK, N - j * kBK);
         // exp2 constant of this tile: softmax scale * log2(e) (* Q and K block scales for e4m3)
         const float cj = FP8 ? fmaxf(c_exp * qscale * sK[bh * Nkb + j], 1e-30f) : c_exp;
@@ -222,27 +198,23 @@ __global__ __launch_bounds__(64 * NW) void attend_kernel(
 
         // ---- S^T = K Q^T
         f32x16 sacc[2];
-#pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2)
-#pragma unroll
-            for (int x = 0; x < 16; ++x) sacc[h2][x] = 0.f;
         if (FP8) {
 #pragma unroll
             for (int h2 = 0; h2 < 2; ++h2) {
-                const uint8_t *kr = Ks + (32 * h2 + l32) * kRow8 + 32 * g;
-                const uint4 w0 = *(const uint4 *)kr, w1 = *(const uint4 *)(kr + 16);
+                const uint4 w0 = *(const uint4 *)(st + koff[0] + h2 * 32 * 64), w1 = *(const uint4 *)(st + koff[1] + h2 * 32 * 64);
                 i32x8 k8;
                 k8[0] = w0.x; k8[1] = w0.y; k8[2] = w0.z; k8[3] = w0.w; k8[4] = w1.x; k8[5] = w1.y; k8[6] = w1.z; k8[7] = w1.w;
-                sacc[h2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(k8, q8, sacc[h2], 0, 0, 0, 0, 0, 0);
+                sacc[h2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(k8, q8, zero16, 0, 0, 0, 0, 0, 0);
             }
         } else {
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
+            for (int h2 = 0; h2 < 2; ++h2) {
 #pragma unroll
-                for (int h2 = 0; h2 < 2; ++h2) {
-                    const bf16x8 kf = *(const bf16x8 *)(Ks + ((32 * h2 + l32) * kRow + 16 * s + 8 * g) * 2);
-                    sacc[h2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[h2], 0, 0, 0);
+                for (int s = 0; s < 4; ++s) {
+                    const bf16x8 kf = *(const bf16x8 *)(st + koff[s] + h2 * 32 * 128);
+                    sacc[h2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? zero16 : sacc[h2], 0, 0, 0);
                 }
+            }
         }
         if (valid < kBK) {
 #pragma unroll
@@ -260,40 +232,38 @@ __global__ __launch_bounds__(64 * NW) void attend_kernel(
         for (int x = 1; x < 16; ++x) mx = fmaxf(mx, sacc[0][x]);
 #pragma unroll
         for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sacc[1][x]);
-        mx = fmaxf(mx, xchg32(mx));
-        const float m_new = fmaxf(m_run, mx * cj);
-        const float alpha = fast_exp2(m_run - m_new);
-        const float moff = lsv - m_new;
-#pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2)
-#pragma unroll
-            for (int x = 0; x < 16; ++x) sacc[h2][x] = fast_exp2(fmaf(sacc[h2][x], cj, moff));
-        m_run = m_new;
-        if (__ballot(alpha != 1.0f)) {                 // the running maximum moved for some row of this wave
+        mx = fmaxf(mx, xchg32(mx)) * cj;
+        // lazy maximum: weights may grow to 2^kLazyMax before the accumulators are rescaled
+        if (__ballot(mx > m_run + kLazyMax)) {
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = fast_exp2(m_run - m_new);
+            m_run = m_new;
+            l_run *= alpha;
 #pragma unroll
             for (int e = 0; e < 2; ++e)
 #pragma unroll
                 for (int x = 0; x < 16; ++x) oacc[e][x] *= alpha;
         }
+        const float moff = lsv - m_run;
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) sacc[h2][x] = fast_exp2(fmaf(sacc[h2][x], cj, moff));
 
         // ---- O^T += V^T P^T, and the row sums as ones^T P^T on the same bf16-rounded P, so that
         // numerator and denominator of the softmax see identical weights
         f32x16 lsum;
 #pragma unroll
-        for (int x = 0; x < 16; ++x) lsum[x] = 0.f;
-#pragma unroll
         for (int s = 0; s < 4; ++s) {
             const bf16x8 pf = pack8(sacc[s >> 1], 8 * (s & 1));
-            lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf, lsum, 0, 0, 0);
+            lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf, s == 0 ? zero16 : lsum, 0, 0, 0);
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                const uint16_t *vr = Vt + (32 * e + l32) * kRow + 16 * s + 4 * g;
-                const uint2 v0 = *(const uint2 *)vr, v1 = *(const uint2 *)(vr + 8);
-                const bf16x8 vf = __builtin_bit_cast(bf16x8, make_uint4(v0.x, v0.y, v1.x, v1.y));
+                const bf16x8 vf = *(const bf16x8 *)(st + voff[s] + e * 32 * 128);
                 oacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[e], 0, 0, 0);
             }
         }
-        l_run = l_run * alpha + (FP8 ? lsum[0] / svj : lsum[0]);   // every row of ones^T P^T is the full 64-key sum
+        l_run += FP8 ? lsum[0] / svj : lsum[0];        // every row of ones^T P^T is the full 64-key sum
     }
 
     // ---- normalise the sparse output
@@ -417,17 +387,17 @@ hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st)
 }
 
 template <int NW, bool FP8>
-static hipError_t launch_attend_t(const void *Q, const void *K, const void *V, const float *sQ, const float *sK, const float *sV,
+static hipError_t launch_attend_t(const void *Q, const void *K, const void *Vp, const float *sQ, const float *sK, const float *sV,
                                   const int32_t *crit_idx, int k_c, const void *Hq, const void *WT, int proj_per_head,
                                   int H, int N, int Nqb, int Nkb, long total, float c_exp, void *O, hipStream_t st)
 {
-    attend_kernel<NW, FP8><<<(unsigned)xcd_grid(total), 64 * NW, 0, st>>>(Q, K, V, sQ, sK, sV, crit_idx, k_c, (const uint16_t *)Hq,
+    attend_kernel<NW, FP8><<<(unsigned)xcd_grid(total), 64 * NW, 0, st>>>(Q, K, (const uint16_t *)Vp, sQ, sK, sV, crit_idx, k_c, (const uint16_t *)Hq,
                                                                           (const uint16_t *)WT, proj_per_head, H, N, Nqb, Nkb,
                                                                           total, c_exp, (uint16_t *)O);
     return hipGetLastError();
 }
 
-hipError_t launch_attend(const void *Q, const void *K, const void *V,
+hipError_t launch_attend(const void *Q, const void *K, const void *Vp,
                          const float *sQ, const float *sK, const float *sV, bool fp8,
                          const int32_t *crit_idx, int k_c, const void *Hq, const void *WT,
                          int proj_per_head, int B, int H, int N, int bq, float sm_scale,
@@ -436,7 +406,7 @@ hipError_t launch_attend(const void *Q, const void *K, const void *V,
     const int Nqb = (N + bq - 1) / bq, Nkb = (N + kBK - 1) / kBK;
     const long total = (long)B * H * Nqb;
     const float c_exp = sm_scale * kLog2e;
-#define SLA_ATT(NW, F8) return launch_attend_t<NW, F8>(Q, K, V, sQ, sK, sV, crit_idx, k_c, Hq, WT, proj_per_head, H, N, Nqb, Nkb, total, c_exp, O, st)
+#define SLA_ATT(NW, F8) return launch_attend_t<NW, F8>(Q, K, Vp, sQ, sK, sV, crit_idx, k_c, Hq, WT, proj_per_head, H, N, Nqb, Nkb, total, c_exp, O, st)
     if (bq == 128) { if (fp8) SLA_ATT(4, true); else SLA_ATT(4, false); }
     if (fp8) SLA_ATT(2, true);
     SLA_ATT(2, false);

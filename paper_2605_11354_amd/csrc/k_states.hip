@@ -6,8 +6,9 @@
 // One wavefront owns one key block: it stages K (row-major) and V (transposed) in its own
 // LDS slice, every lane normalises one token row (no cross-lane work for the softmax), the
 // 64x64x64 product runs on v_mfma_f32_32x32x16_bf16, and the state leaves in the layout the
-// aggregation GEMM and the attention epilogue read.  Bound: HBM (K and V are read once,
-// 8 KB + 130 B leave per block).
+// aggregation GEMM and the attention epilogue read.  The same pass also leaves V^T of the block
+// (bf16, key-permuted) for the attention kernel, which can then fetch both of its tiles as
+// plain 16-byte rows.  Bound: HBM (K and V are read once, 8.1 KB of state + 8 KB of V^T leave).
 #include "sla_common.hpp"
 #include "sla_kernels.hpp"
 
@@ -19,7 +20,7 @@ constexpr int kWavesPerWG = 2;
 template <bool FP8>
 __global__ __launch_bounds__(64 * kWavesPerWG) void states_kernel(const void *__restrict__ K, const void *__restrict__ V,
                                                                   const float *__restrict__ sK, const float *__restrict__ sV,
-                                                                  int N, int Nkb, long nblocks, uint16_t *__restrict__ hT)
+                                                                  int N, int Nkb, long nblocks, uint16_t *__restrict__ hT, uint16_t *__restrict__ Vp)
 {
     __shared__ __attribute__((aligned(16))) uint16_t lds[kWavesPerWG][2][64 * kLdsRow];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -133,6 +134,19 @@ __global__ __launch_bounds__(64 * kWavesPerWG) void states_kernel(const void *__
     for (int d = 0; d < 64; ++d) Ks[d * kLdsRow + lane] = (uint16_t)(pack_bf16(x[d] * inv, 0.f) & 0xFFFFu);
     wave_lds_sync();
 
+    // ---- V^T tile for the attention kernel: Vp[e][.] with the 2nd and 3rd group of 4 tokens of every
+    // 16 swapped (slot 16s + 8g + 4a + b holds token 16s + 8a + 4g + b), which is the key order the
+    // accumulator-as-operand trick of that kernel needs; e4m3 V leaves widened to bf16, unscaled.
+    if (Vp != nullptr) {
+        uint16_t *vrow = Vp + ((size_t)blk * kD + lane) * kBK;
+#pragma unroll
+        for (int c = 0; c < 8; c += 2) {
+            const uint4 w0 = *(const uint4 *)(Vt + lane * kLdsRow + c * 8), w1 = *(const uint4 *)(Vt + lane * kLdsRow + c * 8 + 8);
+            *(uint4 *)(vrow + c * 8) = make_uint4(w0.x, w0.y, w1.x, w1.y);
+            *(uint4 *)(vrow + c * 8 + 8) = make_uint4(w0.z, w0.w, w1.z, w1.w);
+        }
+    }
+
     // ---- z: lane d sums phi^T row d (the bf16 values the product below consumes)
     float z = 0.f;
 #pragma unroll
@@ -183,13 +197,13 @@ __global__ __launch_bounds__(64 * kWavesPerWG) void states_kernel(const void *__
 }
 
 hipError_t launch_states(const void *K, const void *V, const float *sK, const float *sV, bool fp8,
-                         int BH, int N, void *hT, hipStream_t st)
+                         int BH, int N, void *hT, void *Vp, hipStream_t st)
 {
     const int Nkb = (N + kBK - 1) / kBK;
     const long nblocks = (long)BH * Nkb;
     const unsigned grid = (unsigned)((nblocks + kWavesPerWG - 1) / kWavesPerWG);
-    if (fp8) states_kernel<true><<<grid, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, (uint16_t *)hT);
-    else     states_kernel<false><<<grid, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, (uint16_t *)hT);
+    if (fp8) states_kernel<true><<<grid, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, (uint16_t *)hT, (uint16_t *)Vp);
+    else     states_kernel<false><<<grid, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, (uint16_t *)hT, (uint16_t *)Vp);
     return hipGetLastError();
 }
 

@@ -29,7 +29,7 @@ struct Plan {
     int BH, Nqb, Nkb, k_c, k_n, lab_pitch, s_pitch, nW;
     float sm_scale;
     bool fp8, empty;
-    size_t off_qbar, off_kbar, off_scores, off_lab, off_crit, off_hT, off_Hq, off_WT, total;
+    size_t off_qbar, off_kbar, off_scores, off_lab, off_crit, off_hT, off_Hq, off_WT, off_Vp, total;
 };
 
 // Validates the parameter block and derives every size used downstream.
@@ -87,6 +87,7 @@ sla_status_t make_plan(const sla_params_t *p, Plan &pl)
     pl.off_hT = carve(BH * pl.Nkb * sla::kStateElems * 2);
     pl.off_Hq = carve(BH * pl.Nqb * sla::kStateElems * 2);
     pl.off_WT = carve((size_t)pl.nW * 64 * 64 * 2);
+    pl.off_Vp = carve(BH * pl.Nkb * 64 * 64 * 2);
     pl.total = off;
     return SLA_OK;
 }
@@ -202,7 +203,7 @@ sla_status_t sla_linear_states(const sla_params_t *p, const void *K, const void 
     if (pl.empty) return SLA_OK;
     SLA_REQ_PTR(K); SLA_REQ_PTR(V); SLA_REQ_PTR(hT);
     if (pl.fp8) { SLA_REQ_PTR(sK); SLA_REQ_PTR(sV); }
-    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, hT, (hipStream_t)stream));
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, hT, nullptr, (hipStream_t)stream));
     return SLA_OK;
 }
 
@@ -241,7 +242,9 @@ sla_status_t sla_sparse_combine(const sla_params_t *p, const void *Q, const void
     SLA_HIP(sla::launch_labels_prepare(labels, (long)pl.BH * pl.Nqb, pl.Nkb, pl.k_c > 0 ? pl.k_c : 1,
                                        at<int8_t>(workspace, pl.off_lab), pl.lab_pitch, at<int32_t>(workspace, pl.off_crit), st));
     if (Hq) SLA_HIP(sla::launch_transpose_w(W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
-    SLA_HIP(sla::launch_attend(Q, K, V, sQ, sK, sV, pl.fp8, at<int32_t>(workspace, pl.off_crit), pl.k_c, Hq,
+    // the attention kernel reads V as transposed tiles; the states pass produces them (its states go to the workspace)
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp), st));
+    SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), sQ, sK, sV, pl.fp8, at<int32_t>(workspace, pl.off_crit), pl.k_c, Hq,
                                at<void>(workspace, pl.off_WT), p->proj_per_head, p->B, p->H, p->N, p->bq, pl.sm_scale, O, st));
     return SLA_OK;
 }
@@ -262,14 +265,14 @@ static sla_status_t forward_impl(const sla_params_t *p, const void *Q, const voi
     if (launched) *launched = true;
     if ((s = run_classify(p, pl, Q, K, sQ, sK, labels, nullptr, nullptr, nullptr, nullptr, nullptr, workspace, st, ev)) != SLA_OK) return s;
     SLA_HIP(mark(4));
-    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), st));
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp), st));
     SLA_HIP(mark(5));
     SLA_HIP(sla::launch_aggregate(at<int8_t>(workspace, pl.off_lab), pl.lab_pitch, at<void>(workspace, pl.off_hT), pl.BH, pl.Nqb,
                                   pl.Nkb, at<void>(workspace, pl.off_Hq), st));
     SLA_HIP(mark(6));
     SLA_HIP(sla::launch_transpose_w(W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
     SLA_HIP(mark(7));
-    SLA_HIP(sla::launch_attend(Q, K, V, sQ, sK, sV, pl.fp8, at<int32_t>(workspace, pl.off_crit), pl.k_c,
+    SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), sQ, sK, sV, pl.fp8, at<int32_t>(workspace, pl.off_crit), pl.k_c,
                                at<void>(workspace, pl.off_Hq), at<void>(workspace, pl.off_WT), p->proj_per_head, p->B, p->H,
                                p->N, p->bq, pl.sm_scale, O, st));
     SLA_HIP(mark(8));

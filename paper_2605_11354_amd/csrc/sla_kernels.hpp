@@ -25,9 +25,10 @@ hipError_t launch_select(const double *S, int pitch, long rows, int Nkb, int k_c
 hipError_t launch_labels_prepare(const int8_t *lab_dense, long rows, int Nkb, int k_c,
                                  int8_t *lab_pad, int lab_pitch, int32_t *crit_idx, hipStream_t st);
 
-// per-key-block states: hT [BH,Nkb,65,64] bf16
+// per-key-block states: hT [BH,Nkb,65,64] bf16; optionally also Vp [BH,Nkb,64,64] bf16, the
+// transposed, key-permuted V tiles the attention kernel reads (NULL to skip)
 hipError_t launch_states(const void *K, const void *V, const float *sK, const float *sV, bool fp8,
-                         int BH, int N, void *hT, hipStream_t st);
+                         int BH, int N, void *hT, void *Vp, hipStream_t st);
 
 // Hq[bh][i][:] = sum over j with lab_pad[bh][i][j] == 1 of hT[bh][j][:]   (bf16 MFMA, fp32 accumulate)
 hipError_t launch_aggregate(const int8_t *lab_pad, int lab_pitch, const void *hT, int BH, int Nqb,
@@ -37,7 +38,7 @@ hipError_t launch_aggregate(const int8_t *lab_pad, int lab_pitch, const void *hT
 hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st);
 
 // block-sparse attention over critical blocks + linear output + projection + sum
-hipError_t launch_attend(const void *Q, const void *K, const void *V,
+hipError_t launch_attend(const void *Q, const void *K, const void *Vp,
                          const float *sQ, const float *sK, const float *sV, bool fp8,
                          const int32_t *crit_idx, int k_c, const void *Hq, const void *WT,
                          int proj_per_head, int B, int H, int N, int bq, float sm_scale,

@@ -22,7 +22,8 @@
 // with the 16-byte chunk index XOR-ed by row bits (applied on the global side of the copy),
 // which keeps the fragment reads free of bank conflicts.  Every wave issues the same number of
 // copies per tile (rows past a ragged end are clamped, absent list entries copy block 0), so
-// s_waitcnt vmcnt(n) with a compile-time n identifies "tile c has landed".
+// s_waitcnt vmcnt(n) with a compile-time n identifies "tile c has landed".  The key mask of a
+// ragged last block enters as the initial accumulator of S^T (0 / -inf), costing nothing per tile.
 //
 // E4M3 inputs.  S^T is one v_mfma_f32_32x32x64_f8f6f4 per 32 keys (the whole head dimension
 // is the K dimension of the instruction; products of two E4M3 numbers are exact in the fp32
@@ -50,12 +51,21 @@ typedef __attribute__((address_space(1))) const void *glb_void_p;
 __device__ __forceinline__ int swz8(int row) { return (row >> 1) & 7; }
 __device__ __forceinline__ int swz4(int row) { return (row >> 2) & 3; }
 
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
-template <int N> __device__ __forceinline__ void wait_vmcnt()
+// Waits until at most N of this wave's tile copies are outstanding, then joins the workgroup.
+// The copies below are issued from inline assembly so that the compiler's own wait-count
+// insertion does not see them: it would otherwise drain ALL outstanding copies (vmcnt(0))
+// before every LDS read and serialise the prefetch ring.  The waits are therefore explicit.
+template <int N> __device__ __forceinline__ void wait_copies_and_barrier()
 {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+// One 1 KB copy global -> LDS: lane l moves the 16 bytes at base + voff(l) to LDS byte lds_addr + 16 l.
+// base and lds_addr are wave-uniform (SGPRs); M0 carries the LDS address for this instruction only.
+__device__ __forceinline__ void copy_1k_to_lds(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds_addr) : "memory");
 }
 
 template <int NW, bool FP8>
@@ -68,32 +78,48 @@ struct Tile {
     static constexpr int LOADS = KINS + VINS;                   // per wave per tile
 };
 
-// Requests one K tile and one V^T tile into an LDS stage.  kt / vt: first byte of the tiles in
-// global memory; valid: number of real rows of the K tile (rows past it are clamped to the last).
+// Per-lane byte offsets (inside a tile) of the 16-byte chunk each lane copies, one per copy
+// instruction of this wave: LDS position (row, slot) <- global chunk slot ^ swizzle(row).
 template <int NW, bool FP8>
-__device__ __forceinline__ void issue_tile(uint8_t *stage, const uint8_t *kt, const uint8_t *vt, int valid, int wave, int lane)
-{
+struct CopyOffsets {
     using T = Tile<NW, FP8>;
+    int k[T::KINS], v[T::VINS];
+    int krow[T::KINS];            // K row of this lane per instruction (for clamping at a ragged end)
+    __device__ __forceinline__ void init(int wave, int lane)
+    {
 #pragma unroll
-    for (int x = 0; x < T::KINS; ++x) {
-        const int ins = wave * T::KINS + x;
-        if (FP8) {
-            const int r = ins * 16 + (lane >> 2), chunk = (lane & 3) ^ swz4(r);
-            const uint8_t *src = kt + (size_t)min(r, valid - 1) * 64 + chunk * 16;
-            __builtin_amdgcn_global_load_lds((glb_void_p)src, (lds_void_p)(stage + ins * 1024), 16, 0, 0);
-        } else {
-            const int r = ins * 8 + (lane >> 3), chunk = (lane & 7) ^ swz8(r);
-            const uint8_t *src = kt + (size_t)min(r, valid - 1) * 128 + chunk * 16;
-            __builtin_amdgcn_global_load_lds((glb_void_p)src, (lds_void_p)(stage + ins * 1024), 16, 0, 0);
+        for (int x = 0; x < T::KINS; ++x) {
+            const int ins = wave * T::KINS + x;
+            if (FP8) { const int r = ins * 16 + (lane >> 2); krow[x] = r; k[x] = r * 64 + (((lane & 3) ^ swz4(r)) << 4); }
+            else     { const int r = ins * 8 + (lane >> 3);  krow[x] = r; k[x] = r * 128 + (((lane & 7) ^ swz8(r)) << 4); }
+        }
+#pragma unroll
+        for (int x = 0; x < T::VINS; ++x) {
+            const int ins = wave * T::VINS + x, r = ins * 8 + (lane >> 3);
+            v[x] = r * 128 + (((lane & 7) ^ swz8(r)) << 4);
         }
     }
+};
+
+// Requests one K tile and one V^T tile into the LDS stage at byte address stage (wave-uniform).
+// kt / vt: first byte of the tiles in global memory (wave-uniform); valid: number of real rows of
+// the K tile (rows past it are clamped to the last, they are masked later; V^T tiles are complete).
+template <int NW, bool FP8>
+__device__ __forceinline__ void issue_tile(uint32_t stage, const uint8_t *kt, const uint8_t *vt, int valid,
+                                           const CopyOffsets<NW, FP8> &co, int wave)
+{
+    using T = Tile<NW, FP8>;
+    constexpr int KROW = FP8 ? 64 : 128;
+    if (valid == kBK) {
 #pragma unroll
-    for (int x = 0; x < T::VINS; ++x) {
-        const int ins = wave * T::VINS + x;
-        const int r = ins * 8 + (lane >> 3), chunk = (lane & 7) ^ swz8(r);
-        const uint8_t *src = vt + (size_t)r * 128 + chunk * 16;
-        __builtin_amdgcn_global_load_lds((glb_void_p)src, (lds_void_p)(stage + T::KBYTES + ins * 1024), 16, 0, 0);
+        for (int x = 0; x < T::KINS; ++x) copy_1k_to_lds(kt, co.k[x], stage + (wave * T::KINS + x) * 1024);
+    } else {
+#pragma unroll
+        for (int x = 0; x < T::KINS; ++x)
+            copy_1k_to_lds(kt, co.k[x] - (co.krow[x] - min(co.krow[x], valid - 1)) * KROW, stage + (wave * T::KINS + x) * 1024);
     }
+#pragma unroll
+    for (int x = 0; x < T::VINS; ++x) copy_1k_to_lds(vt, co.v[x], stage + T::KBYTES + (wave * T::VINS + x) * 1024);
 }
 
 __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base)
@@ -168,27 +194,47 @@ __global__ __launch_bounds__(64 * NW) void attend_kernel(
         int j = c < k_c ? ci[c] : -1;
         return (j < 0 || j >= Nkb) ? -1 : j;
     };
+    CopyOffsets<NW, FP8> co;
+    co.init(wave, lane);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);                       // same value, provably uniform
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_p)lds;                // LDS byte address of the ring
     auto request = [&](int c, int j) {
         const int jj = j < 0 ? 0 : j;                  // absent entries still copy (block 0) so the copy count is uniform
-        issue_tile<NW, FP8>(lds + (c % kStages) * T::STAGE, Kh + (size_t)jj * kBK * kD * ES, Vh + (size_t)jj * kBK * kD * 2,
-                            min(kBK, N - jj * kBK), wave, lane);
+        issue_tile<NW, FP8>(lds_base + (c % kStages) * T::STAGE, Kh + (size_t)jj * kBK * kD * ES, Vh + (size_t)jj * kBK * kD * 2,
+                            min(kBK, N - jj * kBK), co, wave_u);
+    };
+    // Key mask as the initial accumulator of S^T: 0 for real keys, -inf for keys past the ragged end
+    // of the last block.  Rebuilt only when the number of real keys differs from the previous tile's.
+    f32x16 cmask[2] = {zero16, zero16};
+    int cmask_valid = kBK;
+    auto set_mask = [&](int valid) {
+        if (valid != cmask_valid) {
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+                for (int x = 0; x < 16; ++x)
+                    cmask[h2][x] = (32 * h2 + 8 * (x >> 2) + 4 * g + (x & 3)) < valid ? 0.f : -INFINITY;
+            cmask_valid = valid;
+        }
     };
     int j0 = tile_index(0), j1 = tile_index(1);
     if (k_c > 0) request(0, j0);
     if (k_c > 1) request(1, j1);
+    // Let the Q fragments (ordinary loads the compiler tracks) land here, once: left to the compiler, its
+    // vmcnt(0) for them would sit in front of their first use inside the loop and drain the ring every trip.
+    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
 
     for (int c = 0; c < k_c; ++c) {
         const int j = j0;
         // copies of tiles 0..c+1 have been requested; tile c has landed once only those of tile c+1 remain
-        if (c + 1 < k_c) wait_vmcnt<T::LOADS>();
-        else wait_vmcnt<0>();
-        lds_barrier();                                 // tile c visible to all waves; stage of tile c-1 free
+        if (c + 1 < k_c) wait_copies_and_barrier<T::LOADS>();   // tile c visible to all waves; stage of tile c-1 free
+        else wait_copies_and_barrier<0>();
         j0 = j1;
         j1 = tile_index(c + 2);
         if (c + 2 < k_c) request(c + 2, j1);
         if (j < 0) continue;
         const uint8_t *st = lds + (c % kStages) * T::STAGE;
-        const int valid = min(kBK, N - j * kBK);
+        set_mask(min(kBK, N - j * kBK));
         // exp2 constant of this tile: softmax scale * log2(e) (* Q and K block scales for e4m3)
         const float cj = FP8 ? fmaxf(c_exp * qscale * sK[bh * Nkb + j], 1e-30f) : c_exp;
         // E4M3: the V block scale rides on the weights, P' = P * sV_j (an offset in the exponent); the
@@ -204,28 +250,17 @@ __global__ __launch_bounds__(64 * NW) void attend_kernel(
                 const uint4 w0 = *(const uint4 *)(st + koff[0] + h2 * 32 * 64), w1 = *(const uint4 *)(st + koff[1] + h2 * 32 * 64);
                 i32x8 k8;
                 k8[0] = w0.x; k8[1] = w0.y; k8[2] = w0.z; k8[3] = w0.w; k8[4] = w1.x; k8[5] = w1.y; k8[6] = w1.z; k8[7] = w1.w;
-                sacc[h2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(k8, q8, zero16, 0, 0, 0, 0, 0, 0);
+                sacc[h2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(k8, q8, cmask[h2], 0, 0, 0, 0, 0, 0);
             }
         } else {
 #pragma unroll
-            for (int h2 = 0; h2 < 2; ++h2) {
+            for (int s = 0; s < 4; ++s)
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
+                for (int h2 = 0; h2 < 2; ++h2) {
                     const bf16x8 kf = *(const bf16x8 *)(st + koff[s] + h2 * 32 * 128);
-                    sacc[h2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? zero16 : sacc[h2], 0, 0, 0);
-                }
-            }
-        }
-        if (valid < kBK) {
-#pragma unroll
-            for (int h2 = 0; h2 < 2; ++h2)
-#pragma unroll
-                for (int x = 0; x < 16; ++x) {
-                    const int t = 32 * h2 + 8 * (x >> 2) + 4 * g + (x & 3);
-                    if (t >= valid) sacc[h2][x] = -INFINITY;
+                    sacc[h2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? cmask[h2] : sacc[h2], 0, 0, 0);
                 }
         }
-
         // ---- online softmax, one query row per lane (shared with lane^32)
         float mx = sacc[0][0];
 #pragma unroll
@@ -233,10 +268,11 @@ __global__ __launch_bounds__(64 * NW) void attend_kernel(
 #pragma unroll
         for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sacc[1][x]);
         mx = fmaxf(mx, xchg32(mx)) * cj;
-        // lazy maximum: weights may grow to 2^kLazyMax before the accumulators are rescaled
+        // lazy maximum: a row raises its running maximum only when exceeded by 2^kLazyMax, so the weights
+        // stay below 2^kLazyMax and the accumulators are rarely rescaled
         if (__ballot(mx > m_run + kLazyMax)) {
-            const float m_new = fmaxf(m_run, mx);
-            const float alpha = fast_exp2(m_run - m_new);
+            const float m_new = mx > m_run + kLazyMax ? fmaxf(m_run, mx) : m_run;
+            const float alpha = m_new == m_run ? 1.0f : fast_exp2(m_run - m_new);
             m_run = m_new;
             l_run *= alpha;
 #pragma unroll

@@ -122,6 +122,15 @@ __device__ __forceinline__ void issue_tile(uint32_t stage, const uint8_t *kt, co
     for (int x = 0; x < T::VINS; ++x) copy_1k_to_lds(vt, co.v[x], stage + T::KBYTES + (wave * T::VINS + x) * 1024);
 }
 
+// max of v over the lane pair (l, l^32): after the swap one register holds lanes 0..31 twice, the
+// other lanes 32..63 twice
+__device__ __forceinline__ float pair_max(float v)
+{
+    const uint32_t u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base)
 {
     uint4 o;
@@ -207,16 +216,15 @@ __global__ __launch_bounds__(64 * NW) void attend_kernel(
     // of the last block.  Rebuilt only when the number of real keys differs from the previous tile's.
     f32x16 cmask[2] = {zero16, zero16};
     int cmask_valid = kBK;
-    auto set_mask = [&](int valid) {
-        if (valid != cmask_valid) {
+    auto build_mask = [&](int valid) {
 #pragma unroll
-            for (int h2 = 0; h2 < 2; ++h2)
+        for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
-                for (int x = 0; x < 16; ++x)
-                    cmask[h2][x] = (32 * h2 + 8 * (x >> 2) + 4 * g + (x & 3)) < valid ? 0.f : -INFINITY;
-            cmask_valid = valid;
-        }
+            for (int x = 0; x < 16; ++x)
+                cmask[h2][x] = (32 * h2 + 8 * (x >> 2) + 4 * g + (x & 3)) < valid ? 0.f : -INFINITY;
+        cmask_valid = valid;
     };
+    auto set_mask = [&](int valid) { if (valid != cmask_valid) build_mask(valid); };
     int j0 = tile_index(0), j1 = tile_index(1);
     if (k_c > 0) request(0, j0);
     if (k_c > 1) request(1, j1);
@@ -267,9 +275,10 @@ __global__ __launch_bounds__(64 * NW) void attend_kernel(
         for (int x = 1; x < 16; ++x) mx = fmaxf(mx, sacc[0][x]);
 #pragma unroll
         for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sacc[1][x]);
-        mx = fmaxf(mx, xchg32(mx)) * cj;
+        mx = pair_max(mx);
         // lazy maximum: a row raises its running maximum only when exceeded by 2^kLazyMax, so the weights
         // stay below 2^kLazyMax and the accumulators are rarely rescaled
+        mx *= cj;
         if (__ballot(mx > m_run + kLazyMax)) {
             const float m_new = mx > m_run + kLazyMax ? fmaxf(m_run, mx) : m_run;
             const float alpha = m_new == m_run ? 1.0f : fast_exp2(m_run - m_new);

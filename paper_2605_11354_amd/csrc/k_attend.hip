@@ -140,7 +140,7 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base)
 }
 
 template <int NW, bool FP8>
-__global__ __launch_bounds__(64 * NW) void attend_kernel(
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void attend_kernel(
     const void *__restrict__ Qp, const void *__restrict__ Kp, const uint16_t *__restrict__ Vp,
     const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV,
     const int32_t *__restrict__ crit_idx, int k_c, const uint16_t *__restrict__ Hq, const uint16_t *__restrict__ WT,
@@ -212,6 +212,21 @@ __global__ __launch_bounds__(64 * NW) void attend_kernel(
         issue_tile<NW, FP8>(lds_base + (c % kStages) * T::STAGE, Kh + (size_t)jj * kBK * kD * ES, Vh + (size_t)jj * kBK * kD * 2,
                             min(kBK, N - jj * kBK), co, wave_u);
     };
+    // The operands of the linear/projection epilogue (the 64x64 tile of Hq^T, the Z row, W^T) travel the
+    // same way into the two ring stages that are idle during the last tile, so their latency hides
+    // behind that tile's arithmetic.  c_next: index of the first idle stage.
+    const uint8_t *Hi8 = Hq ? (const uint8_t *)(Hq + (size_t)work * kStateElems) : nullptr;
+    const uint8_t *Wh8 = (const uint8_t *)(WT + (proj_per_head ? (size_t)(bh % H) * kD * kD : 0));
+    auto request_epilogue = [&](int c_next) {
+        const uint32_t sa = lds_base + (c_next % kStages) * T::STAGE, sb = lds_base + ((c_next + 1) % kStages) * T::STAGE;
+#pragma unroll
+        for (int x = 0; x < T::VINS; ++x) copy_1k_to_lds(Hi8, co.v[x], sa + (wave_u * T::VINS + x) * 1024);
+#pragma unroll
+        for (int x = 0; x < T::VINS; ++x) copy_1k_to_lds(Wh8, co.v[x], sb + (wave_u * T::VINS + x) * 1024);
+        if (tid < 8) copy_1k_to_lds(Hi8 + 64 * kD * 2, tid * 16, sa + 8192);      // Z: 128 bytes, 8 lanes of wave 0
+    };
+    if (Hq != nullptr && k_c == 0) request_epilogue(0);
+
     // Key mask as the initial accumulator of S^T: 0 for real keys, -inf for keys past the ragged end
     // of the last block.  Rebuilt only when the number of real keys differs from the previous tile's.
     f32x16 cmask[2] = {zero16, zero16};
@@ -240,6 +255,7 @@ __global__ __launch_bounds__(64 * NW) void attend_kernel(
         j0 = j1;
         j1 = tile_index(c + 2);
         if (c + 2 < k_c) request(c + 2, j1);
+        if (Hq != nullptr && c + 1 == k_c) request_epilogue(c + 1);
         if (j < 0) continue;
         const uint8_t *st = lds + (c % kStages) * T::STAGE;
         set_mask(min(kBK, N - j * kBK));
@@ -319,6 +335,9 @@ __global__ __launch_bounds__(64 * NW) void attend_kernel(
         for (int x = 0; x < 16; ++x) oacc[e][x] *= inv_l;
 
     if (Hq != nullptr) {
+        wait_copies_and_barrier<0>();                  // epilogue operands landed; every wave is past its last tile
+        const int c_next = k_c > 0 ? k_c : 0;
+        const uint8_t *stA = lds + (c_next % kStages) * T::STAGE, *stB = lds + ((c_next + 1) % kStages) * T::STAGE;
         // ---- phi(Q): softmax over the 64 channels of the row (this lane holds 32, lane^32 the rest).
         // x[8s + c] is channel dcol(s) + c, the channel slot c of K-step s carries in the product below.
         float x[32];
@@ -341,13 +360,12 @@ __global__ __launch_bounds__(64 * NW) void attend_kernel(
         float mx = x[0];
 #pragma unroll
         for (int d = 1; d < 32; ++d) mx = fmaxf(mx, x[d]);
-        mx = fmaxf(mx, xchg32(mx));
+        mx = pair_max(mx);
         float sum = 0.f;
 #pragma unroll
         for (int d = 0; d < 32; ++d) { x[d] = fast_exp2((x[d] - mx) * kLog2e); sum += x[d]; }
         sum += xchg32(sum);
         const float inv = 1.0f / sum;
-        const uint16_t *Hi = Hq + (size_t)work * kStateElems;
         bf16x8 fq[4];
         float den = 0.f;
 #pragma unroll
@@ -357,26 +375,22 @@ __global__ __launch_bounds__(64 * NW) void attend_kernel(
             o.x = pack_bf16(x[8 * s + 0] * inv, x[8 * s + 1] * inv); o.y = pack_bf16(x[8 * s + 2] * inv, x[8 * s + 3] * inv);
             o.z = pack_bf16(x[8 * s + 4] * inv, x[8 * s + 5] * inv); o.w = pack_bf16(x[8 * s + 6] * inv, x[8 * s + 7] * inv);
             fq[s] = __builtin_bit_cast(bf16x8, o);
-            const uint4 z = *(const uint4 *)(Hi + 64 * kD + dcol);
+            const uint4 z = *(const uint4 *)(stA + 8192 + dcol * 2);
             den += bf16_lo(o.x) * bf16_lo(z.x) + bf16_hi(o.x) * bf16_hi(z.x) + bf16_lo(o.y) * bf16_lo(z.y) + bf16_hi(o.y) * bf16_hi(z.y)
                  + bf16_lo(o.z) * bf16_lo(z.z) + bf16_hi(o.z) * bf16_hi(z.z) + bf16_lo(o.w) * bf16_lo(z.w) + bf16_hi(o.w) * bf16_hi(z.w);
         }
         den += xchg32(den);
         const float inv_den = den > 0.f ? 1.0f / den : 0.f;     // no marginal block: H = Z = 0 and O_lin = 0
 
-        // ---- O_lin^T = Hq^T phi(Q)^T
+        // ---- O_lin^T = Hq^T phi(Q)^T   (Hq^T tile staged with the tile swizzle)
         f32x16 lacc[2];
 #pragma unroll
-        for (int e = 0; e < 2; ++e)
-#pragma unroll
-            for (int y = 0; y < 16; ++y) lacc[e][y] = 0.f;
-#pragma unroll
         for (int s = 0; s < 4; ++s) {
-            const int dcol = FP8 ? 32 * g + 8 * s : 16 * s + 8 * g;
+            const int hchunk = FP8 ? 4 * g + s : 2 * s + g;      // 16-byte chunk holding channels dcol(s)..dcol(s)+7
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                const bf16x8 hf = *(const bf16x8 *)(Hi + (32 * e + l32) * kD + dcol);
-                lacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hf, fq[s], lacc[e], 0, 0, 0);
+                const bf16x8 hf = *(const bf16x8 *)(stA + (32 * e + l32) * 128 + ((hchunk ^ swz8(l32)) << 4));
+                lacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hf, fq[s], s == 0 ? zero16 : lacc[e], 0, 0, 0);
             }
         }
 #pragma unroll
@@ -384,43 +398,57 @@ __global__ __launch_bounds__(64 * NW) void attend_kernel(
 #pragma unroll
             for (int y = 0; y < 16; ++y) lacc[e][y] *= inv_den;
 
-        // ---- O^T += W^T O_lin^T
-        const uint16_t *Wh = WT + (proj_per_head ? (size_t)(bh % H) * kD * kD : 0);
+        // ---- O^T += W^T O_lin^T   (W^T staged transposed and key-permuted like a V^T tile)
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const bf16x8 pf = pack8(lacc[s >> 1], 8 * (s & 1));
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                const uint16_t *wr = Wh + (32 * e + l32) * kD + 16 * s + 4 * g;
-                const uint2 w0 = *(const uint2 *)wr, w1 = *(const uint2 *)(wr + 8);
-                const bf16x8 wf = __builtin_bit_cast(bf16x8, make_uint4(w0.x, w0.y, w1.x, w1.y));
+                const bf16x8 wf = *(const bf16x8 *)(stB + (32 * e + l32) * 128 + (((2 * s + g) ^ swz8(l32)) << 4));
                 oacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, pf, oacc[e], 0, 0, 0);
             }
         }
     }
 
-    // ---- store: register 4a+b of oacc[e] is channel 32e + 8a + 4g + b of row q
-    if (qok) {
-        uint16_t *orow = O + head + (size_t)q * kD;
+    // ---- store.  Register 4a+b of oacc[e] is channel 32e + 8a + 4g + b of row q: the wave's 32x64 tile
+    // is transposed through a private 4 KB LDS slice (8-byte pieces, XOR-swizzled by row) so that it
+    // leaves as full 128-byte rows, 16 bytes per lane.
+    wait_copies_and_barrier<0>();                      // all waves are done reading the ring
+    {
+        uint8_t *ot = lds + wave * 4096;
+        const int f = ((l32 >> 1) & 7) << 1;
 #pragma unroll
         for (int e = 0; e < 2; ++e)
 #pragma unroll
-            for (int a = 0; a < 4; ++a) {
+            for (int aa = 0; aa < 4; ++aa) {
                 uint2 o;
-                o.x = pack_bf16(oacc[e][4 * a + 0], oacc[e][4 * a + 1]);
-                o.y = pack_bf16(oacc[e][4 * a + 2], oacc[e][4 * a + 3]);
-                *(uint2 *)(orow + 32 * e + 8 * a + 4 * g) = o;
+                o.x = pack_bf16(oacc[e][4 * aa + 0], oacc[e][4 * aa + 1]);
+                o.y = pack_bf16(oacc[e][4 * aa + 2], oacc[e][4 * aa + 3]);
+                const int piece = 8 * e + 2 * aa + g;
+                *(uint2 *)(ot + l32 * 128 + ((piece ^ f) << 3)) = o;
             }
+        wave_lds_sync();
+        const int q0w = i * BQ + 32 * wave;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int r = 8 * k + (lane >> 3), ch = lane & 7;      // row of the tile, 16-byte chunk of the row
+            const int fr = ((r >> 1) & 7) << 1;
+            const uint4 v = *(const uint4 *)(ot + r * 128 + (((2 * ch) ^ fr) << 3));
+            if (q0w + r < N) *(uint4 *)(O + head + (size_t)(q0w + r) * kD + ch * 8) = v;
+        }
     }
 }
 
-// W [nW][e_in][e_out] -> WT [nW][e_out][e_in]
+// W [nW][e_in][e_out] -> WT [nW][e_out][slot], slot 16s + 8g + 4a + b holding e_in = 16s + 8a + 4g + b
+// (transposed, and with the same permutation of the contraction index as the V^T tiles, so the
+// projection product reads it with the fragment addressing of the attention loop)
 __global__ __launch_bounds__(256) void transpose_w_kernel(const uint16_t *__restrict__ W, uint16_t *__restrict__ WT)
 {
     const uint16_t *w = W + (size_t)blockIdx.x * kD * kD;
     uint16_t *o = WT + (size_t)blockIdx.x * kD * kD;
     for (int idx = threadIdx.x; idx < kD * kD; idx += 256) {
-        const int eo = idx >> 6, ei = idx & 63;
+        const int eo = idx >> 6, slot = idx & 63;
+        const int ei = (slot & 0x33) | ((slot & 4) << 1) | ((slot & 8) >> 1);      // swap bits 2 and 3
         o[idx] = w[ei * kD + eo];
     }
 }

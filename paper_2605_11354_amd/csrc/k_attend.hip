@@ -42,7 +42,10 @@ namespace sla {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kStages = 3;
-constexpr float kLazyMax = 8.0f;   // the running maximum is only raised when a row exceeds it by 2^8
+// Slack allowed before a row raises its running maximum.  0 = exact running maximum: the dominant weight of a
+// row is then exactly 1.0 and survives the bf16 rounding of P untouched; a slack of 8 (rescaling the
+// accumulators far less often) was measured 6 % faster but doubled the output error of peaked rows.
+constexpr float kLazyMax = 0.0f;
 
 typedef __attribute__((address_space(3))) void *lds_void_p;
 typedef __attribute__((address_space(1))) const void *glb_void_p;
@@ -292,8 +295,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void attend_kernel(
 #pragma unroll
         for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sacc[1][x]);
         mx = pair_max(mx);
-        // lazy maximum: a row raises its running maximum only when exceeded by 2^kLazyMax, so the weights
-        // stay below 2^kLazyMax and the accumulators are rarely rescaled
+        // the accumulators are rescaled only in iterations where some row of the wave raised its maximum
         mx *= cj;
         if (__ballot(mx > m_run + kLazyMax)) {
             const float m_new = mx > m_run + kLazyMax ? fmaxf(m_run, mx) : m_run;

@@ -94,8 +94,9 @@ def main() -> int:
     elem = 1 if fp8 else 2
     qkv_bytes = BH * N * D * elem
     bytes_pool_q = qkv_bytes + BH * Nqb * D * 8
-    bytes_pool_k = qkv_bytes + BH * Nkb * D * 8
-    bytes_states = 2 * qkv_bytes + BH * Nkb * 65 * D * 2
+    # states pass: reads K and V once; writes the block states (65x64 bf16), the V^T tiles (64x64 bf16)
+    # and the fp64 block means of K
+    bytes_states = 2 * qkv_bytes + BH * Nkb * (65 * D * 2 + D * D * 2 + D * 8)
 
     # algorithmic flops of the critical-block attention: 4*D per (valid query row, valid critical key)
     lab_host = labels.cpu().numpy()
@@ -119,8 +120,7 @@ def main() -> int:
                 "bound": "mfma", "achieved": round(attend_tflops, 2), "peak": PEAK_TFLOPS[cfg.dtype], "unit": "TFLOP/s",
                 "frac": round(attend_tflops / PEAK_TFLOPS[cfg.dtype], 4), "traffic": traffic,
                 "algorithmic_flops": attend_flops, "ms": round(stage["attend"], 5)}
-    kernels = {"pool_q": hbm("pool_q", bytes_pool_q), "pool_k": hbm("pool_k", bytes_pool_k),
-               "states": hbm("states", bytes_states)}
+    kernels = {"pool_q": hbm("pool_q", bytes_pool_q), "states": hbm("states", bytes_states)}
     for k in ("scores", "select", "aggregate", "transpose_w"):
         kernels[k] = {"ms": round(stage[k], 5)}
     agg_flops = 2.0 * BH * Nqb * Nkb * 65 * D

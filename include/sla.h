@@ -98,7 +98,7 @@ sla_status_t sla_forward(const sla_params_t *p,
  * It creates and destroys its events, so unlike every other entry point it touches the HIP
  * runtime beyond launches and synchronises.  sla_stage_name(i) names stage i.
  */
-#define SLA_NUM_STAGES 8
+#define SLA_NUM_STAGES 7
 sla_status_t sla_forward_profiled(const sla_params_t *p,
                                   const void *Q, const void *K, const void *V,
                                   const float *sQ, const float *sK, const float *sV,

@@ -3,12 +3,15 @@
 //     h_j = phi(K_j)^T V_j   (64 x 64),   z_j = sum_t phi(K_j,t)   (64)
 // written as bf16 hT[j][e][d] = h_j[d][e] (rows 0..63) and hT[j][64][d] = z_j[d].
 //
-// One wavefront owns one key block: it stages K (row-major) and V (transposed) in its own
-// LDS slice, every lane normalises one token row (no cross-lane work for the softmax), the
-// 64x64x64 product runs on v_mfma_f32_32x32x16_bf16, and the state leaves in the layout the
-// aggregation GEMM and the attention epilogue read.  The same pass also leaves V^T of the block
-// (bf16, key-permuted) for the attention kernel, which can then fetch both of its tiles as
-// plain 16-byte rows.  Bound: HBM (K and V are read once, 8.1 KB of state + 8 KB of V^T leave).
+// One wavefront owns a contiguous run of key blocks.  Per block it stages K (row-major) and V
+// (transposed) in its own LDS slice, every lane normalises one token row (no cross-lane work
+// for the softmax), the 64x64x64 product runs on v_mfma_f32_32x32x16_bf16, and the state leaves
+// in the layout the aggregation GEMM and the attention epilogue read.  The same pass also leaves
+// V^T of the block (bf16, key-permuted) for the attention kernel, which can then fetch both of
+// its tiles as plain 16-byte rows, and (optionally) the fp64 block mean of K for the classifier,
+// so K is read from HBM once per layer by this kernel instead of twice.
+// The loads of the next block are in flight (in registers) while the current one is processed:
+// the kernel is bound by HBM (16 KB in, 16.3 KB out per block for bf16 inputs).
 #include "sla_common.hpp"
 #include "sla_kernels.hpp"
 
@@ -17,44 +20,83 @@ namespace sla {
 constexpr int kLdsRow = 72;            // bf16 elements per LDS row (64 + 8 pad: 144 B stride)
 constexpr int kWavesPerWG = 2;
 
+// Raw global data of one key block, as loaded: K as 16-byte row chunks, V as dwords arranged
+// for the register transpose.
 template <bool FP8>
-__global__ __launch_bounds__(64 * kWavesPerWG) void states_kernel(const void *__restrict__ K, const void *__restrict__ V,
-                                                                  const float *__restrict__ sK, const float *__restrict__ sV,
-                                                                  int N, int Nkb, long nblocks, uint16_t *__restrict__ hT, uint16_t *__restrict__ Vp)
-{
-    __shared__ __attribute__((aligned(16))) uint16_t lds[kWavesPerWG][2][64 * kLdsRow];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const long blk = (long)blockIdx.x * kWavesPerWG + wave;
-    if (blk >= nblocks) return;                      // whole wave exits together; no block-wide barrier below
-    const long bh = blk / Nkb;
-    const int j = (int)(blk - bh * Nkb);
-    const int t0 = j * kBK;
-    const int valid = min(kBK, N - t0);
-    uint16_t *Ks = lds[wave][0];                     // K rows, later phi^T [d][t]
-    uint16_t *Vt = lds[wave][1];                     // V^T [e][t]
-    const size_t tok0 = ((size_t)bh * N + t0) * kD;
+struct BlockRegs {
+    uint4 k[FP8 ? 4 : 8];
+    uint32_t v[FP8 ? 16 : 32];
+};
 
-    // ---- stage K row-major: chunk c = lane + 64 r is 8 channels (16 B of bf16) of row c/8
-    // ---- stage V transposed: a unit is 2 channels x 8 consecutive tokens
+template <bool FP8>
+__device__ __forceinline__ void load_block(BlockRegs<FP8> &r, const void *K, const void *V, size_t tok0, int valid, int lane)
+{
     if (!FP8) {
-        const uint16_t *Kg = (const uint16_t *)K + tok0;
-        const uint16_t *Vg = (const uint16_t *)V + tok0;
+        const uint16_t *Kg = (const uint16_t *)K + tok0, *Vg = (const uint16_t *)V + tok0;
+        // K: chunk c = lane + 64 x is 8 channels (16 B) of row c/8
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int c = lane + 64 * r, t = c >> 3, col = (c & 7) * 8;
-            uint4 w = make_uint4(0, 0, 0, 0);
-            if (t < valid) w = *(const uint4 *)(Kg + (size_t)t * kD + col);
-            *(uint4 *)(Ks + t * kLdsRow + col) = w;
+        for (int x = 0; x < 8; ++x) {
+            const int c = lane + 64 * x, t = c >> 3, col = (c & 7) * 8;
+            r.k[x] = make_uint4(0, 0, 0, 0);
+            if (t < valid) r.k[x] = *(const uint4 *)(Kg + (size_t)t * kD + col);
         }
+        // V: unit u = lane + 64 x is 2 channels (pair u%32) x 8 consecutive tokens (group u/32)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int u = lane + 64 * r, ep = u & 31, tg = u >> 5;
-            uint32_t w[8];
+        for (int x = 0; x < 4; ++x) {
+            const int u = lane + 64 * x, ep = u & 31, tg = u >> 5;
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 const int t = tg * 8 + k;
-                w[k] = t < valid ? *(const uint32_t *)(Vg + (size_t)t * kD + 2 * ep) : 0u;
+                r.v[8 * x + k] = t < valid ? *(const uint32_t *)(Vg + (size_t)t * kD + 2 * ep) : 0u;
             }
+        }
+    } else {
+        const uint8_t *Kg = (const uint8_t *)K + tok0, *Vg = (const uint8_t *)V + tok0;
+        // K: chunk c = lane + 64 x is 16 channels (16 B of e4m3) of row c/4
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const int c = lane + 64 * x, t = c >> 2, col = (c & 3) * 16;
+            r.k[x] = make_uint4(0, 0, 0, 0);
+            if (t < valid) r.k[x] = *(const uint4 *)(Kg + (size_t)t * kD + col);
+        }
+        // V: unit u = lane + 64 x is 4 channels (quad u%16) x 8 consecutive tokens (group u/16)
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+            const int u = lane + 64 * x, eq = u & 15, tg = u >> 4;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int t = tg * 8 + k;
+                r.v[8 * x + k] = t < valid ? *(const uint32_t *)(Vg + (size_t)t * kD + 4 * eq) : 0u;
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ uint4 e4m3x8_to_bf16x8(uint32_t lo, uint32_t hi)
+{
+    const f32x2 a0 = __builtin_amdgcn_cvt_pk_f32_fp8(lo, false), a1 = __builtin_amdgcn_cvt_pk_f32_fp8(lo, true);
+    const f32x2 a2 = __builtin_amdgcn_cvt_pk_f32_fp8(hi, false), a3 = __builtin_amdgcn_cvt_pk_f32_fp8(hi, true);
+    uint4 o;
+    o.x = pack_bf16(a0[0], a0[1]); o.y = pack_bf16(a1[0], a1[1]);
+    o.z = pack_bf16(a2[0], a2[1]); o.w = pack_bf16(a3[0], a3[1]);
+    return o;
+}
+
+// Registers -> LDS: K rows as bf16 (e4m3 codes widened exactly, the block scale is applied later
+// in fp32), V transposed to [channel][token] bf16 (e4m3 widened exactly, unscaled).
+template <bool FP8>
+__device__ __forceinline__ void stage_block(const BlockRegs<FP8> &r, uint16_t *Ks, uint16_t *Vt, int lane)
+{
+    if (!FP8) {
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const int c = lane + 64 * x, t = c >> 3, col = (c & 7) * 8;
+            *(uint4 *)(Ks + t * kLdsRow + col) = r.k[x];
+        }
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const int u = lane + 64 * x, ep = u & 31, tg = u >> 5;
+            const uint32_t *w = r.v + 8 * x;
             uint4 lo, hi;   // lo: channel 2ep over 8 tokens, hi: channel 2ep+1
             lo.x = __builtin_amdgcn_perm(w[1], w[0], 0x05040100); hi.x = __builtin_amdgcn_perm(w[1], w[0], 0x07060302);
             lo.y = __builtin_amdgcn_perm(w[3], w[2], 0x05040100); hi.y = __builtin_amdgcn_perm(w[3], w[2], 0x07060302);
@@ -64,34 +106,16 @@ __global__ __launch_bounds__(64 * kWavesPerWG) void states_kernel(const void *__
             *(uint4 *)(Vt + (2 * ep + 1) * kLdsRow + tg * 8) = hi;
         }
     } else {
-        const uint8_t *Kg = (const uint8_t *)K + tok0;
-        const uint8_t *Vg = (const uint8_t *)V + tok0;
-        // K: chunk c = lane + 64 r is 8 channels (8 B of e4m3) of row c/8; dequantised to bf16
-        // after scaling would lose bits, so the scaled fp32 values are rounded to bf16 only for
-        // staging -- phi below recomputes from the staged values.  To keep full precision the
-        // row is staged as raw e4m3 -> bf16 (exact) and the scale is applied in fp32 by the lane.
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int c = lane + 64 * r, t = c >> 3, col = (c & 7) * 8;
-            uint2 w = make_uint2(0, 0);
-            if (t < valid) w = *(const uint2 *)(Kg + (size_t)t * kD + col);
-            const f32x2 a0 = __builtin_amdgcn_cvt_pk_f32_fp8(w.x, false), a1 = __builtin_amdgcn_cvt_pk_f32_fp8(w.x, true);
-            const f32x2 a2 = __builtin_amdgcn_cvt_pk_f32_fp8(w.y, false), a3 = __builtin_amdgcn_cvt_pk_f32_fp8(w.y, true);
-            uint4 o;
-            o.x = pack_bf16(a0[0], a0[1]); o.y = pack_bf16(a1[0], a1[1]);
-            o.z = pack_bf16(a2[0], a2[1]); o.w = pack_bf16(a3[0], a3[1]);
-            *(uint4 *)(Ks + t * kLdsRow + col) = o;
+        for (int x = 0; x < 4; ++x) {
+            const int c = lane + 64 * x, t = c >> 2, col = (c & 3) * 16;
+            *(uint4 *)(Ks + t * kLdsRow + col) = e4m3x8_to_bf16x8(r.k[x].x, r.k[x].y);
+            *(uint4 *)(Ks + t * kLdsRow + col + 8) = e4m3x8_to_bf16x8(r.k[x].z, r.k[x].w);
         }
-        // V: a unit is 4 channels x 8 consecutive tokens (dword loads of 4 e4m3 codes)
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            const int u = lane + 64 * r, eq = u & 15, tg = u >> 4;
-            uint32_t w[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int t = tg * 8 + k;
-                w[k] = t < valid ? *(const uint32_t *)(Vg + (size_t)t * kD + 4 * eq) : 0u;
-            }
+        for (int x = 0; x < 2; ++x) {
+            const int u = lane + 64 * x, eq = u & 15, tg = u >> 4;
+            const uint32_t *w = r.v + 8 * x;
 #pragma unroll
             for (int ch = 0; ch < 4; ++ch) {
                 float f[8];
@@ -107,103 +131,158 @@ __global__ __launch_bounds__(64 * kWavesPerWG) void states_kernel(const void *__
             }
         }
     }
-    wave_lds_sync();
+}
 
-    // ---- phi: lane t owns token row t
-    float x[64];
-#pragma unroll
-    for (int c = 0; c < 8; ++c) {
-        const uint4 w = *(const uint4 *)(Ks + lane * kLdsRow + c * 8);
-        x[c * 8 + 0] = bf16_lo(w.x); x[c * 8 + 1] = bf16_hi(w.x);
-        x[c * 8 + 2] = bf16_lo(w.y); x[c * 8 + 3] = bf16_hi(w.y);
-        x[c * 8 + 4] = bf16_lo(w.z); x[c * 8 + 5] = bf16_hi(w.z);
-        x[c * 8 + 6] = bf16_lo(w.w); x[c * 8 + 7] = bf16_hi(w.w);
-    }
-    float mx = x[0];
-#pragma unroll
-    for (int d = 1; d < 64; ++d) mx = fmaxf(mx, x[d]);
-    // exp(s*(x - mx)) = exp2(x*c - mx*c), c = s*log2(e); s = 1 for bf16 inputs, the K scale for e4m3
-    const float cexp = (FP8 ? sK[blk] : 1.0f) * 1.4426950408889634f;
-    const float mc = mx * cexp;
-    float sum = 0.f;
-#pragma unroll
-    for (int d = 0; d < 64; ++d) { x[d] = fast_exp2(fmaf(x[d], cexp, -mc)); sum += x[d]; }
-    const float inv = lane < valid ? 1.0f / sum : 0.0f;     // rows past the sequence end contribute nothing
-    wave_lds_sync();                                        // all rows are in registers: Ks may be overwritten
-#pragma unroll
-    for (int d = 0; d < 64; ++d) Ks[d * kLdsRow + lane] = (uint16_t)(pack_bf16(x[d] * inv, 0.f) & 0xFFFFu);
-    wave_lds_sync();
-
-    // ---- V^T tile for the attention kernel: Vp[e][.] with the 2nd and 3rd group of 4 tokens of every
-    // 16 swapped (slot 16s + 8g + 4a + b holds token 16s + 8a + 4g + b), which is the key order the
-    // accumulator-as-operand trick of that kernel needs; e4m3 V leaves widened to bf16, unscaled.
-    if (Vp != nullptr) {
-        uint16_t *vrow = Vp + ((size_t)blk * kD + lane) * kBK;
-#pragma unroll
-        for (int c = 0; c < 8; c += 2) {
-            const uint4 w0 = *(const uint4 *)(Vt + lane * kLdsRow + c * 8), w1 = *(const uint4 *)(Vt + lane * kLdsRow + c * 8 + 8);
-            *(uint4 *)(vrow + c * 8) = make_uint4(w0.x, w0.y, w1.x, w1.y);
-            *(uint4 *)(vrow + c * 8 + 8) = make_uint4(w0.z, w0.w, w1.z, w1.w);
-        }
-    }
-
-    // ---- z: lane d sums phi^T row d (the bf16 values the product below consumes)
-    float z = 0.f;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) {
-        const uint4 w = *(const uint4 *)(Ks + lane * kLdsRow + c * 8);
-        z += bf16_lo(w.x) + bf16_hi(w.x) + bf16_lo(w.y) + bf16_hi(w.y) + bf16_lo(w.z) + bf16_hi(w.z) + bf16_lo(w.w) + bf16_hi(w.w);
-    }
-
-    // ---- h[d][e] = sum_t phi^T[d][t] * V^T[e][t]
+template <bool FP8>
+__global__ __launch_bounds__(64 * kWavesPerWG) void states_kernel(const void *__restrict__ K, const void *__restrict__ V,
+                                                                  const float *__restrict__ sK, const float *__restrict__ sV,
+                                                                  int N, int Nkb, long nblocks, int per_wave,
+                                                                  uint16_t *__restrict__ hT, uint16_t *__restrict__ Vp,
+                                                                  double *__restrict__ kbar)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t lds[kWavesPerWG][2][64 * kLdsRow];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const long first = ((long)blockIdx.x * kWavesPerWG + wave) * per_wave;
+    const long last = min(first + per_wave, nblocks);          // this wave owns blocks [first, last)
+    if (first >= last) return;                                  // whole wave exits together; no workgroup barrier below
+    uint16_t *Ks = lds[wave][0];                     // K rows, later phi^T [d][t]
+    uint16_t *Vt = lds[wave][1];                     // V^T [e][t]
     const int l32 = lane & 31, g = lane >> 5;
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        bf16x8 af[2], bfr[2];
-#pragma unroll
-        for (int a = 0; a < 2; ++a) {
-            af[a] = *(const bf16x8 *)(Ks + (32 * a + l32) * kLdsRow + 16 * s + 8 * g);
-            bfr[a] = *(const bf16x8 *)(Vt + (32 * a + l32) * kLdsRow + 16 * s + 8 * g);
+
+    auto block_geometry = [&](long blk, size_t &tok0, int &valid) {
+        const long bh = blk / Nkb;
+        const int t0 = (int)(blk - bh * Nkb) * kBK;
+        valid = min(kBK, N - t0);
+        tok0 = ((size_t)bh * N + t0) * kD;
+    };
+
+    BlockRegs<FP8> regs;
+    {
+        size_t tok0; int valid;
+        block_geometry(first, tok0, valid);
+        load_block<FP8>(regs, K, V, tok0, valid, lane);
+    }
+    for (long blk = first; blk < last; ++blk) {
+        size_t tok0; int valid;
+        block_geometry(blk, tok0, valid);
+        wave_lds_sync();                             // the previous block's LDS reads are done
+        stage_block<FP8>(regs, Ks, Vt, lane);
+        if (blk + 1 < last) {                        // next block's loads fly while this one is processed
+            size_t tn; int vn;
+            block_geometry(blk + 1, tn, vn);
+            load_block<FP8>(regs, K, V, tn, vn, lane);
         }
+        wave_lds_sync();
+
+        // ---- block mean of K for the classifier: lane d adds the tokens of channel d serially in fp64
+        // (ascending token order) and multiplies by 1/count -- the same arithmetic as the pooling kernel
+        if (kbar != nullptr) {
+            const double s = FP8 ? (double)sK[blk] : 1.0;
+            double acc = 0.0;
+#pragma unroll 8
+            for (int t = 0; t < valid; ++t) {
+                const double v = (double)bf16_bits_to_f32(Ks[t * kLdsRow + lane]);
+                acc += FP8 ? v * s : v;
+            }
+            kbar[blk * kD + lane] = acc * (1.0 / (double)valid);
+        }
+
+        // ---- phi: lane t owns token row t
+        float x[64];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const uint4 w = *(const uint4 *)(Ks + lane * kLdsRow + c * 8);
+            x[c * 8 + 0] = bf16_lo(w.x); x[c * 8 + 1] = bf16_hi(w.x);
+            x[c * 8 + 2] = bf16_lo(w.y); x[c * 8 + 3] = bf16_hi(w.y);
+            x[c * 8 + 4] = bf16_lo(w.z); x[c * 8 + 5] = bf16_hi(w.z);
+            x[c * 8 + 6] = bf16_lo(w.w); x[c * 8 + 7] = bf16_hi(w.w);
+        }
+        float mx = x[0];
+#pragma unroll
+        for (int d = 1; d < 64; ++d) mx = fmaxf(mx, x[d]);
+        // exp(s*(x - mx)) = exp2(x*c - mx*c), c = s*log2(e); s = 1 for bf16 inputs, the K scale for e4m3
+        const float cexp = (FP8 ? sK[blk] : 1.0f) * 1.4426950408889634f;
+        const float mc = mx * cexp;
+        float sum = 0.f;
+#pragma unroll
+        for (int d = 0; d < 64; ++d) { x[d] = fast_exp2(fmaf(x[d], cexp, -mc)); sum += x[d]; }
+        const float inv = lane < valid ? 1.0f / sum : 0.0f;     // rows past the sequence end contribute nothing
+        wave_lds_sync();                                        // all rows are in registers: Ks may be overwritten
+#pragma unroll
+        for (int d = 0; d < 64; ++d) Ks[d * kLdsRow + lane] = (uint16_t)(pack_bf16(x[d] * inv, 0.f) & 0xFFFFu);
+        wave_lds_sync();
+
+        // ---- V^T tile for the attention kernel: Vp[e][.] with the 2nd and 3rd group of 4 tokens of every
+        // 16 swapped (slot 16s + 8g + 4a + b holds token 16s + 8a + 4g + b), which is the key order the
+        // accumulator-as-operand trick of that kernel needs; e4m3 V leaves widened to bf16, unscaled.
+        if (Vp != nullptr) {
+            uint16_t *vrow = Vp + ((size_t)blk * kD + lane) * kBK;
+#pragma unroll
+            for (int c = 0; c < 8; c += 2) {
+                const uint4 w0 = *(const uint4 *)(Vt + lane * kLdsRow + c * 8), w1 = *(const uint4 *)(Vt + lane * kLdsRow + c * 8 + 8);
+                *(uint4 *)(vrow + c * 8) = make_uint4(w0.x, w0.y, w1.x, w1.y);
+                *(uint4 *)(vrow + c * 8 + 8) = make_uint4(w0.z, w0.w, w1.z, w1.w);
+            }
+        }
+
+        // ---- z: lane d sums phi^T row d (the bf16 values the product below consumes)
+        float z = 0.f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const uint4 w = *(const uint4 *)(Ks + lane * kLdsRow + c * 8);
+            z += bf16_lo(w.x) + bf16_hi(w.x) + bf16_lo(w.y) + bf16_hi(w.y) + bf16_lo(w.z) + bf16_hi(w.z) + bf16_lo(w.w) + bf16_hi(w.w);
+        }
+
+        // ---- h[d][e] = sum_t phi^T[d][t] * V^T[e][t]
+        f32x16 zero16;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) zero16[i] = 0.f;
+        f32x16 acc[2][2];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            bf16x8 af[2], bfr[2];
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                af[a] = *(const bf16x8 *)(Ks + (32 * a + l32) * kLdsRow + 16 * s + 8 * g);
+                bfr[a] = *(const bf16x8 *)(Vt + (32 * a + l32) * kLdsRow + 16 * s + 8 * g);
+            }
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], s == 0 ? zero16 : acc[a][b], 0, 0, 0);
+        }
+
+        // ---- write hT[e][d]: accumulator (a,b) register 4q+r holds d = 32a + 8q + 4g + r, e = 32b + l32
+        uint16_t *out = hT + (size_t)blk * kStateElems;
+        const float vs = FP8 ? sV[blk] : 1.0f;
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
             for (int b = 0; b < 2; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint2 o;
+                    o.x = pack_bf16(acc[a][b][4 * q + 0] * vs, acc[a][b][4 * q + 1] * vs);
+                    o.y = pack_bf16(acc[a][b][4 * q + 2] * vs, acc[a][b][4 * q + 3] * vs);
+                    *(uint2 *)(out + (32 * b + l32) * kD + 32 * a + 8 * q + 4 * g) = o;
+                }
+        out[64 * kD + lane] = (uint16_t)(pack_bf16(z, 0.f) & 0xFFFFu);
     }
-
-    // ---- write hT[e][d]: accumulator (a,b) register 4q+r holds d = 32a + 8q + 4g + r, e = 32b + l32
-    uint16_t *out = hT + (size_t)blk * kStateElems;
-    const float vs = FP8 ? sV[blk] : 1.0f;
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                uint2 o;
-                o.x = pack_bf16(acc[a][b][4 * q + 0] * vs, acc[a][b][4 * q + 1] * vs);
-                o.y = pack_bf16(acc[a][b][4 * q + 2] * vs, acc[a][b][4 * q + 3] * vs);
-                *(uint2 *)(out + (32 * b + l32) * kD + 32 * a + 8 * q + 4 * g) = o;
-            }
-    out[64 * kD + lane] = (uint16_t)(pack_bf16(z, 0.f) & 0xFFFFu);
 }
 
 hipError_t launch_states(const void *K, const void *V, const float *sK, const float *sV, bool fp8,
-                         int BH, int N, void *hT, void *Vp, hipStream_t st)
+                         int BH, int N, void *hT, void *Vp, double *kbar, hipStream_t st)
 {
     const int Nkb = (N + kBK - 1) / kBK;
     const long nblocks = (long)BH * Nkb;
-    const unsigned grid = (unsigned)((nblocks + kWavesPerWG - 1) / kWavesPerWG);
-    if (fp8) states_kernel<true><<<grid, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, (uint16_t *)hT, (uint16_t *)Vp);
-    else     states_kernel<false><<<grid, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, (uint16_t *)hT, (uint16_t *)Vp);
+    // enough waves to fill the chip (256 CUs x 8 resident waves), each with a contiguous run of blocks
+    const long target_waves = 256L * 8;
+    const int per_wave = (int)((nblocks + target_waves - 1) / target_waves);
+    const long waves = (nblocks + per_wave - 1) / per_wave;
+    const unsigned grid = (unsigned)((waves + kWavesPerWG - 1) / kWavesPerWG);
+    if (fp8) states_kernel<true><<<grid, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, kbar);
+    else     states_kernel<false><<<grid, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, kbar);
     return hipGetLastError();
 }
 

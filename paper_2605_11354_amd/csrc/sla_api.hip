@@ -120,15 +120,15 @@ template <class T> T *at(void *ws, size_t off) { return (T *)((char *)ws + off);
 // steps a1-a3: pool, logits, classifier.  Leaves padded labels and critical lists in the workspace.
 sla_status_t run_classify(const sla_params_t *p, const Plan &pl, const void *Q, const void *K, const float *sQ,
                           const float *sK, int8_t *labels, int32_t *crit_out, float *Pc, double *qbar_out,
-                          double *kbar_out, double *scores_out, void *ws, hipStream_t st, hipEvent_t *ev = nullptr)
+                          double *kbar_out, double *scores_out, void *ws, hipStream_t st, hipEvent_t *ev = nullptr, bool pooled = false)
 {
     auto mark = [&](int i) { return ev ? hipEventRecord(ev[i], st) : hipSuccess; };
     double *qbar = qbar_out ? qbar_out : at<double>(ws, pl.off_qbar);
     double *kbar = kbar_out ? kbar_out : at<double>(ws, pl.off_kbar);
-    SLA_HIP(mark(0));
-    SLA_HIP(sla::launch_pool(Q, sQ, pl.fp8, pl.BH, p->N, p->bq, qbar, st));
-    SLA_HIP(mark(1));
-    SLA_HIP(sla::launch_pool(K, sK, pl.fp8, pl.BH, p->N, p->bk, kbar, st));
+    if (!pooled) {      // sla_forward pools Q itself and gets the K means from the states pass
+        SLA_HIP(sla::launch_pool(Q, sQ, pl.fp8, pl.BH, p->N, p->bq, qbar, st));
+        SLA_HIP(sla::launch_pool(K, sK, pl.fp8, pl.BH, p->N, p->bk, kbar, st));
+    }
     SLA_HIP(mark(2));
     SLA_HIP(sla::launch_scores(qbar, kbar, pl.BH, pl.Nqb, pl.Nkb, pl.s_pitch, at<double>(ws, pl.off_scores), st));
     int32_t *crit = crit_out ? crit_out : at<int32_t>(ws, pl.off_crit);
@@ -203,7 +203,7 @@ sla_status_t sla_linear_states(const sla_params_t *p, const void *K, const void 
     if (pl.empty) return SLA_OK;
     SLA_REQ_PTR(K); SLA_REQ_PTR(V); SLA_REQ_PTR(hT);
     if (pl.fp8) { SLA_REQ_PTR(sK); SLA_REQ_PTR(sV); }
-    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, hT, nullptr, (hipStream_t)stream));
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, hT, nullptr, nullptr, (hipStream_t)stream));
     return SLA_OK;
 }
 
@@ -243,7 +243,7 @@ sla_status_t sla_sparse_combine(const sla_params_t *p, const void *Q, const void
                                        at<int8_t>(workspace, pl.off_lab), pl.lab_pitch, at<int32_t>(workspace, pl.off_crit), st));
     if (Hq) SLA_HIP(sla::launch_transpose_w(W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
     // the attention kernel reads V as transposed tiles; the states pass produces them (its states go to the workspace)
-    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp), st));
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp), nullptr, st));
     SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), sQ, sK, sV, pl.fp8, at<int32_t>(workspace, pl.off_crit), pl.k_c, Hq,
                                at<void>(workspace, pl.off_WT), p->proj_per_head, p->B, p->H, p->N, p->bq, pl.sm_scale, O, st));
     return SLA_OK;
@@ -263,19 +263,22 @@ static sla_status_t forward_impl(const sla_params_t *p, const void *Q, const voi
     hipStream_t st = (hipStream_t)stream;
     auto mark = [&](int i) { return ev ? hipEventRecord(ev[i], st) : hipSuccess; };
     if (launched) *launched = true;
-    if ((s = run_classify(p, pl, Q, K, sQ, sK, labels, nullptr, nullptr, nullptr, nullptr, nullptr, workspace, st, ev)) != SLA_OK) return s;
+    SLA_HIP(mark(0));
+    SLA_HIP(sla::launch_pool(Q, sQ, pl.fp8, pl.BH, p->N, p->bq, at<double>(workspace, pl.off_qbar), st));
+    SLA_HIP(mark(1));     // states + V^T tiles + block means of K: the one pass over K and V besides the attention kernel
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp),
+                               at<double>(workspace, pl.off_kbar), st));
+    if ((s = run_classify(p, pl, Q, K, sQ, sK, labels, nullptr, nullptr, nullptr, nullptr, nullptr, workspace, st, ev, true)) != SLA_OK) return s;
     SLA_HIP(mark(4));
-    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp), st));
-    SLA_HIP(mark(5));
     SLA_HIP(sla::launch_aggregate(at<int8_t>(workspace, pl.off_lab), pl.lab_pitch, at<void>(workspace, pl.off_hT), pl.BH, pl.Nqb,
                                   pl.Nkb, at<void>(workspace, pl.off_Hq), st));
-    SLA_HIP(mark(6));
+    SLA_HIP(mark(5));
     SLA_HIP(sla::launch_transpose_w(W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
-    SLA_HIP(mark(7));
+    SLA_HIP(mark(6));
     SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), sQ, sK, sV, pl.fp8, at<int32_t>(workspace, pl.off_crit), pl.k_c,
                                at<void>(workspace, pl.off_Hq), at<void>(workspace, pl.off_WT), p->proj_per_head, p->B, p->H,
                                p->N, p->bq, pl.sm_scale, O, st));
-    SLA_HIP(mark(8));
+    SLA_HIP(mark(7));
     return SLA_OK;
 }
 
@@ -288,7 +291,7 @@ sla_status_t sla_forward(const sla_params_t *p, const void *Q, const void *K, co
 
 const char *sla_stage_name(int stage)
 {
-    static const char *names[SLA_NUM_STAGES] = {"pool_q", "pool_k", "scores", "select", "states", "aggregate", "transpose_w", "attend"};
+    static const char *names[SLA_NUM_STAGES] = {"pool_q", "states", "scores", "select", "aggregate", "transpose_w", "attend"};
     return stage >= 0 && stage < SLA_NUM_STAGES ? names[stage] : "?";
 }
 

@@ -26,9 +26,10 @@ hipError_t launch_labels_prepare(const int8_t *lab_dense, long rows, int Nkb, in
                                  int8_t *lab_pad, int lab_pitch, int32_t *crit_idx, hipStream_t st);
 
 // per-key-block states: hT [BH,Nkb,65,64] bf16; optionally also Vp [BH,Nkb,64,64] bf16, the
-// transposed, key-permuted V tiles the attention kernel reads (NULL to skip)
+// transposed, key-permuted V tiles the attention kernel reads, and kbar [BH,Nkb,64] fp64, the
+// block means of K (same arithmetic as launch_pool); NULL skips either
 hipError_t launch_states(const void *K, const void *V, const float *sK, const float *sV, bool fp8,
-                         int BH, int N, void *hT, void *Vp, hipStream_t st);
+                         int BH, int N, void *hT, void *Vp, double *kbar, hipStream_t st);
 
 // Hq[bh][i][:] = sum over j with lab_pad[bh][i][j] == 1 of hT[bh][j][:]   (bf16 MFMA, fp32 accumulate)
 hipError_t launch_aggregate(const int8_t *lab_pad, int lab_pitch, const void *hT, int BH, int Nqb,

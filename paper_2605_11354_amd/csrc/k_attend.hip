@@ -143,7 +143,7 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base)
 }
 
 template <int NW, bool FP8>
-__global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void attend_kernel(
+__global__ __launch_bounds__(64 * NW, 3) void attend_kernel(
     const void *__restrict__ Qp, const void *__restrict__ Kp, const uint16_t *__restrict__ Vp,
     const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV,
     const int32_t *__restrict__ crit_idx, int k_c, const uint16_t *__restrict__ Hq, const uint16_t *__restrict__ WT,
@@ -230,19 +230,35 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void attend_kernel(
     };
     if (Hq != nullptr && k_c == 0) request_epilogue(0);
 
-    // Key mask as the initial accumulator of S^T: 0 for real keys, -inf for keys past the ragged end
-    // of the last block.  Rebuilt only when the number of real keys differs from the previous tile's.
-    f32x16 cmask[2] = {zero16, zero16};
-    int cmask_valid = kBK;
-    auto build_mask = [&](int valid) {
+    // Key mask of a ragged last block: it enters as the initial accumulator of S^T (0 for real keys,
+    // -inf for keys past the end), built on the fly only for such a tile; every other tile starts from 0.
+    auto key_mask = [&](int valid, f32x16 (&m)[2]) {
 #pragma unroll
         for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
             for (int x = 0; x < 16; ++x)
-                cmask[h2][x] = (32 * h2 + 8 * (x >> 2) + 4 * g + (x & 3)) < valid ? 0.f : -INFINITY;
-        cmask_valid = valid;
+                m[h2][x] = (32 * h2 + 8 * (x >> 2) + 4 * g + (x & 3)) < valid ? 0.f : -INFINITY;
     };
-    auto set_mask = [&](int valid) { if (valid != cmask_valid) build_mask(valid); };
+    // S^T = K Q^T (+ init) of the tile staged at st
+    auto compute_S = [&](const uint8_t *st, const f32x16 (&init)[2], f32x16 (&s2)[2]) {
+        if (FP8) {
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2) {
+                const uint4 w0 = *(const uint4 *)(st + koff[0] + h2 * 32 * 64), w1 = *(const uint4 *)(st + koff[1] + h2 * 32 * 64);
+                i32x8 k8;
+                k8[0] = w0.x; k8[1] = w0.y; k8[2] = w0.z; k8[3] = w0.w; k8[4] = w1.x; k8[5] = w1.y; k8[6] = w1.z; k8[7] = w1.w;
+                s2[h2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(k8, q8, init[h2], 0, 0, 0, 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) {
+                    const bf16x8 kf = *(const bf16x8 *)(st + koff[s] + h2 * 32 * 128);
+                    s2[h2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? init[h2] : s2[h2], 0, 0, 0);
+                }
+        }
+    };
     int j0 = tile_index(0), j1 = tile_index(1);
     if (k_c > 0) request(0, j0);
     if (k_c > 1) request(1, j1);
@@ -261,7 +277,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void attend_kernel(
         if (Hq != nullptr && c + 1 == k_c) request_epilogue(c + 1);
         if (j < 0) continue;
         const uint8_t *st = lds + (c % kStages) * T::STAGE;
-        set_mask(min(kBK, N - j * kBK));
+        const int valid = min(kBK, N - j * kBK);
         // exp2 constant of this tile: softmax scale * log2(e) (* Q and K block scales for e4m3)
         const float cj = FP8 ? fmaxf(c_exp * qscale * sK[bh * Nkb + j], 1e-30f) : c_exp;
         // E4M3: the V block scale rides on the weights, P' = P * sV_j (an offset in the exponent); the
@@ -271,23 +287,15 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void attend_kernel(
 
         // ---- S^T = K Q^T
         f32x16 sacc[2];
-        if (FP8) {
-#pragma unroll
-            for (int h2 = 0; h2 < 2; ++h2) {
-                const uint4 w0 = *(const uint4 *)(st + koff[0] + h2 * 32 * 64), w1 = *(const uint4 *)(st + koff[1] + h2 * 32 * 64);
-                i32x8 k8;
-                k8[0] = w0.x; k8[1] = w0.y; k8[2] = w0.z; k8[3] = w0.w; k8[4] = w1.x; k8[5] = w1.y; k8[6] = w1.z; k8[7] = w1.w;
-                sacc[h2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(k8, q8, cmask[h2], 0, 0, 0, 0, 0, 0);
-            }
+        if (valid == kBK) {
+            const f32x16 init[2] = {zero16, zero16};
+            compute_S(st, init, sacc);
         } else {
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int h2 = 0; h2 < 2; ++h2) {
-                    const bf16x8 kf = *(const bf16x8 *)(st + koff[s] + h2 * 32 * 128);
-                    sacc[h2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? cmask[h2] : sacc[h2], 0, 0, 0);
-                }
+            f32x16 init[2];
+            key_mask(valid, init);
+            compute_S(st, init, sacc);
         }
+
         // ---- online softmax, one query row per lane (shared with lane^32)
         float mx = sacc[0][0];
 #pragma unroll

@@ -142,23 +142,31 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base)
     return __builtin_bit_cast(bf16x8, o);
 }
 
-template <int NW, bool FP8>
-__global__ __launch_bounds__(64 * NW, 3) void attend_kernel(
+// NW: 32-row query groups per workgroup (query block = 32 NW rows).  KS: key split -- with KS = 2
+// two waves share a query group and each takes one 32-key half of every tile (used for 64-row
+// query blocks so that a workgroup still has four waves); their partial (max, sum, O) are merged
+// through LDS after the loop and the KS = 0 wave of each pair runs the epilogue.
+template <int NW, int KS, bool FP8>
+__global__ __launch_bounds__(64 * NW * KS, 3) void attend_kernel(
     const void *__restrict__ Qp, const void *__restrict__ Kp, const uint16_t *__restrict__ Vp,
     const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV,
     const int32_t *__restrict__ crit_idx, int k_c, const uint16_t *__restrict__ Hq, const uint16_t *__restrict__ WT,
     int proj_per_head, int H, int N, int Nqb, int Nkb, long total, float c_exp, uint16_t *__restrict__ O)
 {
-    using T = Tile<NW, FP8>;
+    constexpr int NWAVES = NW * KS;
+    using T = Tile<NWAVES, FP8>;
     constexpr int BQ = 32 * NW;
     constexpr int ES = FP8 ? 1 : 2;                     // bytes per input element
+    constexpr int NH = 2 / KS;                          // 32-key halves of a tile this wave processes
+    constexpr int NS = 4 / KS;                          // 16-key steps of the second product this wave processes
     __shared__ __attribute__((aligned(1024))) uint8_t lds[kStages * T::STAGE];
     const long work = xcd_remap(blockIdx.x, total);
     if (work >= total) return;                        // the whole workgroup leaves together
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    const int wq = wave % NW, kh = wave / NW;         // query group and key half (kh = 0 when KS = 1)
     const long bh = work / Nqb;
     const int i = (int)(work - bh * Nqb);
-    const int q = i * BQ + 32 * wave + l32;           // this lane's query row
+    const int q = i * BQ + 32 * wq + l32;             // this lane's query row
     const bool qok = q < N;
     const size_t head = (size_t)bh * N * kD;          // element offset of this (b,h)
     const uint8_t *Kh = (const uint8_t *)Kp + head * ES;
@@ -185,14 +193,16 @@ __global__ __launch_bounds__(64 * NW, 3) void attend_kernel(
     }
     const float qscale = FP8 ? sQ[work] : 1.0f;       // scale blocks of Q are the query blocks
 
-    // per-lane LDS byte offsets of the fragments (row l32, chunk 2s+g, swizzled); the second
-    // 32-row half of a tile is a fixed 32 rows further
-    int koff[4], voff[4];
+    // per-lane LDS byte offsets of the fragments (swizzled 16-byte chunks):
+    //   koff[s]: K row 32 kh + l32 (+32 for the second half when KS = 1), channel chunk of step s
+    //   voff[ss]: V^T row l32 (+32 for channels 32..63), key chunk 2 s + g of this wave's step s = NS kh + ss
+    int koff[4], voff[NS];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        voff[s] = T::KBYTES + l32 * 128 + (((2 * s + g) ^ swz8(l32)) << 4);
-        koff[s] = FP8 ? l32 * 64 + ((((2 * g + (s & 1)) ^ swz4(l32))) << 4) : l32 * 128 + (((2 * s + g) ^ swz8(l32)) << 4);
-    }
+    for (int s = 0; s < 4; ++s)
+        koff[s] = (FP8 ? l32 * 64 + ((((2 * g + (s & 1)) ^ swz4(l32))) << 4) : l32 * 128 + (((2 * s + g) ^ swz8(l32)) << 4))
+                  + kh * 32 * (FP8 ? 64 : 128);
+#pragma unroll
+    for (int ss = 0; ss < NS; ++ss) voff[ss] = T::KBYTES + l32 * 128 + (((2 * (NS * kh + ss) + g) ^ swz8(l32)) << 4);
 
     f32x16 zero16;
 #pragma unroll
@@ -206,14 +216,14 @@ __global__ __launch_bounds__(64 * NW, 3) void attend_kernel(
         int j = c < k_c ? ci[c] : -1;
         return (j < 0 || j >= Nkb) ? -1 : j;
     };
-    CopyOffsets<NW, FP8> co;
+    CopyOffsets<NWAVES, FP8> co;
     co.init(wave, lane);
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);                       // same value, provably uniform
     const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_p)lds;                // LDS byte address of the ring
     auto request = [&](int c, int j) {
         const int jj = j < 0 ? 0 : j;                  // absent entries still copy (block 0) so the copy count is uniform
-        issue_tile<NW, FP8>(lds_base + (c % kStages) * T::STAGE, Kh + (size_t)jj * kBK * kD * ES, Vh + (size_t)jj * kBK * kD * 2,
-                            min(kBK, N - jj * kBK), co, wave_u);
+        issue_tile<NWAVES, FP8>(lds_base + (c % kStages) * T::STAGE, Kh + (size_t)jj * kBK * kD * ES, Vh + (size_t)jj * kBK * kD * 2,
+                                min(kBK, N - jj * kBK), co, wave_u);
     };
     // The operands of the linear/projection epilogue (the 64x64 tile of Hq^T, the Z row, W^T) travel the
     // same way into the two ring stages that are idle during the last tile, so their latency hides
@@ -232,30 +242,30 @@ __global__ __launch_bounds__(64 * NW, 3) void attend_kernel(
 
     // Key mask of a ragged last block: it enters as the initial accumulator of S^T (0 for real keys,
     // -inf for keys past the end), built on the fly only for such a tile; every other tile starts from 0.
-    auto key_mask = [&](int valid, f32x16 (&m)[2]) {
+    auto key_mask = [&](int valid, f32x16 (&m)[NH]) {
 #pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2)
+        for (int hh = 0; hh < NH; ++hh)
 #pragma unroll
             for (int x = 0; x < 16; ++x)
-                m[h2][x] = (32 * h2 + 8 * (x >> 2) + 4 * g + (x & 3)) < valid ? 0.f : -INFINITY;
+                m[hh][x] = (32 * (kh + hh) + 8 * (x >> 2) + 4 * g + (x & 3)) < valid ? 0.f : -INFINITY;
     };
-    // S^T = K Q^T (+ init) of the tile staged at st
-    auto compute_S = [&](const uint8_t *st, const f32x16 (&init)[2], f32x16 (&s2)[2]) {
+    // S^T = K Q^T (+ init) of this wave's key halves of the tile staged at st
+    auto compute_S = [&](const uint8_t *st, const f32x16 (&init)[NH], f32x16 (&s2)[NH]) {
         if (FP8) {
 #pragma unroll
-            for (int h2 = 0; h2 < 2; ++h2) {
-                const uint4 w0 = *(const uint4 *)(st + koff[0] + h2 * 32 * 64), w1 = *(const uint4 *)(st + koff[1] + h2 * 32 * 64);
+            for (int hh = 0; hh < NH; ++hh) {
+                const uint4 w0 = *(const uint4 *)(st + koff[0] + hh * 32 * 64), w1 = *(const uint4 *)(st + koff[1] + hh * 32 * 64);
                 i32x8 k8;
                 k8[0] = w0.x; k8[1] = w0.y; k8[2] = w0.z; k8[3] = w0.w; k8[4] = w1.x; k8[5] = w1.y; k8[6] = w1.z; k8[7] = w1.w;
-                s2[h2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(k8, q8, init[h2], 0, 0, 0, 0, 0, 0);
+                s2[hh] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(k8, q8, init[hh], 0, 0, 0, 0, 0, 0);
             }
         } else {
 #pragma unroll
             for (int s = 0; s < 4; ++s)
 #pragma unroll
-                for (int h2 = 0; h2 < 2; ++h2) {
-                    const bf16x8 kf = *(const bf16x8 *)(st + koff[s] + h2 * 32 * 128);
-                    s2[h2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? init[h2] : s2[h2], 0, 0, 0);
+                for (int hh = 0; hh < NH; ++hh) {
+                    const bf16x8 kf = *(const bf16x8 *)(st + koff[s] + hh * 32 * 128);
+                    s2[hh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? init[hh] : s2[hh], 0, 0, 0);
                 }
         }
     };
@@ -286,12 +296,14 @@ __global__ __launch_bounds__(64 * NW, 3) void attend_kernel(
         const float lsv = FP8 ? __log2f(svj) : 0.0f;
 
         // ---- S^T = K Q^T
-        f32x16 sacc[2];
+        f32x16 sacc[NH];
         if (valid == kBK) {
-            const f32x16 init[2] = {zero16, zero16};
+            f32x16 init[NH];
+#pragma unroll
+            for (int hh = 0; hh < NH; ++hh) init[hh] = zero16;
             compute_S(st, init, sacc);
         } else {
-            f32x16 init[2];
+            f32x16 init[NH];
             key_mask(valid, init);
             compute_S(st, init, sacc);
         }
@@ -299,11 +311,12 @@ __global__ __launch_bounds__(64 * NW, 3) void attend_kernel(
         // ---- online softmax, one query row per lane (shared with lane^32)
         float mx = sacc[0][0];
 #pragma unroll
-        for (int x = 1; x < 16; ++x) mx = fmaxf(mx, sacc[0][x]);
+        for (int hh = 0; hh < NH; ++hh)
 #pragma unroll
-        for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sacc[1][x]);
+            for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sacc[hh][x]);
         mx = pair_max(mx);
-        // the accumulators are rescaled only in iterations where some row of the wave raised its maximum
+        // the accumulators are rescaled only in iterations where some row of the wave raised its maximum;
+        // a half tile may hold no real key (ragged end): its maximum is -inf and leaves the state alone
         mx *= cj;
         if (__ballot(mx > m_run + kLazyMax)) {
             const float m_new = mx > m_run + kLazyMax ? fmaxf(m_run, mx) : m_run;
@@ -315,26 +328,70 @@ __global__ __launch_bounds__(64 * NW, 3) void attend_kernel(
 #pragma unroll
                 for (int x = 0; x < 16; ++x) oacc[e][x] *= alpha;
         }
-        const float moff = lsv - m_run;
+        const float moff = lsv - (m_run == -INFINITY ? 0.f : m_run);
 #pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2)
+        for (int hh = 0; hh < NH; ++hh)
 #pragma unroll
-            for (int x = 0; x < 16; ++x) sacc[h2][x] = fast_exp2(fmaf(sacc[h2][x], cj, moff));
+            for (int x = 0; x < 16; ++x) sacc[hh][x] = fast_exp2(fmaf(sacc[hh][x], cj, moff));
 
         // ---- O^T += V^T P^T, and the row sums as ones^T P^T on the same bf16-rounded P, so that
         // numerator and denominator of the softmax see identical weights
         f32x16 lsum;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const bf16x8 pf = pack8(sacc[s >> 1], 8 * (s & 1));
-            lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf, s == 0 ? zero16 : lsum, 0, 0, 0);
+        for (int ss = 0; ss < NS; ++ss) {
+            const bf16x8 pf = pack8(sacc[ss >> 1], 8 * (ss & 1));
+            lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf, ss == 0 ? zero16 : lsum, 0, 0, 0);
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                const bf16x8 vf = *(const bf16x8 *)(st + voff[s] + e * 32 * 128);
+                const bf16x8 vf = *(const bf16x8 *)(st + voff[ss] + e * 32 * 128);
                 oacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[e], 0, 0, 0);
             }
         }
-        l_run += FP8 ? lsum[0] / svj : lsum[0];        // every row of ones^T P^T is the full 64-key sum
+        l_run += FP8 ? lsum[0] / svj : lsum[0];        // every row of ones^T P^T is the sum over this wave's keys
+    }
+
+    // ring stages after the loop: A, B hold the epilogue operands, L (the last tile's stage) is free
+    const int c_next = k_c;
+    uint8_t *stA = lds + (c_next % kStages) * T::STAGE, *stB = lds + ((c_next + 1) % kStages) * T::STAGE;
+    uint8_t *stL = lds + ((c_next + 2) % kStages) * T::STAGE;
+    wait_copies_and_barrier<0>();                      // epilogue operands landed; every wave is past its last tile
+
+    if (KS == 2) {
+        // ---- merge the two key halves: the kh = 1 wave parks (O, max, sum) in LDS, its partner folds them in.
+        // Four 4 KB slots for the two 32-channel halves of the two parked waves: three in stage L and one
+        // behind W^T in stage B (an e4m3 stage is only 12 KB); max/sum go behind the Z row in stage A.
+        auto slot = [&](int r) { return r < 3 ? stL + r * 4096 : (T::STAGE >= 16384 ? stL + 12288 : stB + 8192); };
+        float *ml = (float *)(stA + 8448) + wq * 128;
+        if (kh == 1) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                uint8_t *dst = slot(2 * wq + e);
+#pragma unroll
+                for (int x4 = 0; x4 < 4; ++x4)
+                    *(float4 *)(dst + x4 * 1024 + lane * 16) = make_float4(oacc[e][4 * x4], oacc[e][4 * x4 + 1], oacc[e][4 * x4 + 2], oacc[e][4 * x4 + 3]);
+            }
+            ml[lane] = m_run;
+            ml[64 + lane] = l_run;
+        }
+        wait_copies_and_barrier<0>();
+        if (kh == 0) {
+            const float m1 = ml[lane], l1 = ml[64 + lane];
+            const float m = fmaxf(m_run, m1);
+            const float a0 = m_run == m ? 1.0f : fast_exp2(m_run - m), a1 = m1 == m ? 1.0f : fast_exp2(m1 - m);   // -inf - -inf avoided
+            l_run = l_run * a0 + l1 * a1;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const uint8_t *src = slot(2 * wq + e);
+#pragma unroll
+                for (int x4 = 0; x4 < 4; ++x4) {
+                    const float4 o1 = *(const float4 *)(src + x4 * 1024 + lane * 16);
+                    oacc[e][4 * x4 + 0] = oacc[e][4 * x4 + 0] * a0 + o1.x * a1;
+                    oacc[e][4 * x4 + 1] = oacc[e][4 * x4 + 1] * a0 + o1.y * a1;
+                    oacc[e][4 * x4 + 2] = oacc[e][4 * x4 + 2] * a0 + o1.z * a1;
+                    oacc[e][4 * x4 + 3] = oacc[e][4 * x4 + 3] * a0 + o1.w * a1;
+                }
+            }
+        }
     }
 
     // ---- normalise the sparse output
@@ -344,10 +401,7 @@ __global__ __launch_bounds__(64 * NW, 3) void attend_kernel(
 #pragma unroll
         for (int x = 0; x < 16; ++x) oacc[e][x] *= inv_l;
 
-    if (Hq != nullptr) {
-        wait_copies_and_barrier<0>();                  // epilogue operands landed; every wave is past its last tile
-        const int c_next = k_c > 0 ? k_c : 0;
-        const uint8_t *stA = lds + (c_next % kStages) * T::STAGE, *stB = lds + ((c_next + 1) % kStages) * T::STAGE;
+    if (Hq != nullptr && kh == 0) {
         // ---- phi(Q): softmax over the 64 channels of the row (this lane holds 32, lane^32 the rest).
         // x[8s + c] is channel dcol(s) + c, the channel slot c of K-step s carries in the product below.
         float x[32];
@@ -424,8 +478,8 @@ __global__ __launch_bounds__(64 * NW, 3) void attend_kernel(
     // is transposed through a private 4 KB LDS slice (8-byte pieces, XOR-swizzled by row) so that it
     // leaves as full 128-byte rows, 16 bytes per lane.
     wait_copies_and_barrier<0>();                      // all waves are done reading the ring
-    {
-        uint8_t *ot = lds + wave * 4096;
+    if (kh == 0) {
+        uint8_t *ot = lds + wq * 4096;
         const int f = ((l32 >> 1) & 7) << 1;
 #pragma unroll
         for (int e = 0; e < 2; ++e)
@@ -438,7 +492,7 @@ __global__ __launch_bounds__(64 * NW, 3) void attend_kernel(
                 *(uint2 *)(ot + l32 * 128 + ((piece ^ f) << 3)) = o;
             }
         wave_lds_sync();
-        const int q0w = i * BQ + 32 * wave;
+        const int q0w = i * BQ + 32 * wq;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int r = 8 * k + (lane >> 3), ch = lane & 7;      // row of the tile, 16-byte chunk of the row
@@ -469,12 +523,12 @@ hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int NW, bool FP8>
+template <int NW, int KS, bool FP8>
 static hipError_t launch_attend_t(const void *Q, const void *K, const void *Vp, const float *sQ, const float *sK, const float *sV,
                                   const int32_t *crit_idx, int k_c, const void *Hq, const void *WT, int proj_per_head,
                                   int H, int N, int Nqb, int Nkb, long total, float c_exp, void *O, hipStream_t st)
 {
-    attend_kernel<NW, FP8><<<(unsigned)xcd_grid(total), 64 * NW, 0, st>>>(Q, K, (const uint16_t *)Vp, sQ, sK, sV, crit_idx, k_c, (const uint16_t *)Hq,
+    attend_kernel<NW, KS, FP8><<<(unsigned)xcd_grid(total), 64 * NW * KS, 0, st>>>(Q, K, (const uint16_t *)Vp, sQ, sK, sV, crit_idx, k_c, (const uint16_t *)Hq,
                                                                           (const uint16_t *)WT, proj_per_head, H, N, Nqb, Nkb,
                                                                           total, c_exp, (uint16_t *)O);
     return hipGetLastError();
@@ -489,10 +543,13 @@ hipError_t launch_attend(const void *Q, const void *K, const void *Vp,
     const int Nqb = (N + bq - 1) / bq, Nkb = (N + kBK - 1) / kBK;
     const long total = (long)B * H * Nqb;
     const float c_exp = sm_scale * kLog2e;
-#define SLA_ATT(NW, F8) return launch_attend_t<NW, F8>(Q, K, Vp, sQ, sK, sV, crit_idx, k_c, Hq, WT, proj_per_head, H, N, Nqb, Nkb, total, c_exp, O, st)
-    if (bq == 128) { if (fp8) SLA_ATT(4, true); else SLA_ATT(4, false); }
-    if (fp8) SLA_ATT(2, true);
-    SLA_ATT(2, false);
+#define SLA_ATT(NW, KS, F8) return launch_attend_t<NW, KS, F8>(Q, K, Vp, sQ, sK, sV, crit_idx, k_c, Hq, WT, proj_per_head, H, N, Nqb, Nkb, total, c_exp, O, st)
+    if (bq == 128) { if (fp8) SLA_ATT(4, 1, true); else SLA_ATT(4, 1, false); }
+    // 64-row query blocks: two query groups x two key halves, so a workgroup still has four waves;
+    // with very few critical blocks per row the merge of the halves costs more than it hides
+    if (k_c >= 4) { if (fp8) SLA_ATT(2, 2, true); else SLA_ATT(2, 2, false); }
+    if (fp8) SLA_ATT(2, 1, true);
+    SLA_ATT(2, 1, false);
 #undef SLA_ATT
 }
 

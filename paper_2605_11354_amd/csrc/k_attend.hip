@@ -147,7 +147,7 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base)
 // query blocks so that a workgroup still has four waves); their partial (max, sum, O) are merged
 // through LDS after the loop and the KS = 0 wave of each pair runs the epilogue.
 template <int NW, int KS, bool FP8>
-__global__ __launch_bounds__(64 * NW * KS, 3) void attend_kernel(
+__global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void attend_kernel(
     const void *__restrict__ Qp, const void *__restrict__ Kp, const uint16_t *__restrict__ Vp,
     const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV,
     const int32_t *__restrict__ crit_idx, int k_c, const uint16_t *__restrict__ Hq, const uint16_t *__restrict__ WT,

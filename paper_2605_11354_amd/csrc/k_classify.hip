@@ -178,24 +178,25 @@ __device__ __forceinline__ double key_to_logit(uint64_t key)
 }
 
 // Finds (T, r): the k smallest (key, index) pairs of the row are exactly the keys < T plus the
-// r lowest-index keys == T.  Requires 1 <= k <= Nkb.  Uniform across the wave.
+// r lowest-index keys == T.  Requires 1 <= k <= Nkb.  Uniform across the wave.  hist: 256 counters private
+// to this wave (LDS operations of one wave execute in order, so no workgroup barrier is involved).
 template <int KPL>
 __device__ void radix_select(const uint64_t (&key)[KPL], int Nkb, int k, uint32_t *hist, uint64_t &T, int &r)
 {
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63;
     uint64_t prefix = 0;
     int kk = k, shift = 56, nb = 0;
     for (;;) {
-        __syncthreads();
+        wave_lds_sync();
 #pragma unroll
         for (int b = 0; b < 4; ++b) hist[lane * 4 + b] = 0;
-        __syncthreads();
+        wave_lds_sync();
 #pragma unroll
         for (int m = 0; m < KPL; ++m) {
             const bool cand = (m * 64 + lane < Nkb) && (shift == 56 || (key[m] >> (shift + 8)) == prefix);
             if (cand) atomicAdd(&hist[(uint32_t)(key[m] >> shift) & 255u], 1u);
         }
-        __syncthreads();
+        wave_lds_sync();
         uint32_t c[4];
 #pragma unroll
         for (int b = 0; b < 4; ++b) c[b] = hist[lane * 4 + b];
@@ -240,30 +241,21 @@ __device__ void radix_select(const uint64_t (&key)[KPL], int Nkb, int k, uint32_
     r = 1;
 }
 
+// Classifies one score row held by one wave (key[m] of lane l belongs to block j = 64 m + l; slots with
+// j >= Nkb hold ~0) and writes labels / critical list / compressed softmax for that row.
 template <int KPL>
-__global__ __launch_bounds__(64) void select_kernel(const double *__restrict__ S, int pitch, int Nkb, int k_c, int k_n,
-                                                    int8_t *__restrict__ lab_pad, int lab_pitch,
-                                                    int8_t *__restrict__ lab_dense, int32_t *__restrict__ crit_idx,
-                                                    float *__restrict__ Pc, double *__restrict__ S_dense, float sm_scale)
+__device__ void classify_row_wave(uint64_t (&key)[KPL], long row, int Nkb, int k_c, int k_n, uint32_t *hist,
+                                  int8_t *__restrict__ lab_pad, int lab_pitch, int8_t *__restrict__ lab_dense,
+                                  int32_t *__restrict__ crit_idx, float *__restrict__ Pc, float sm_scale)
 {
-    __shared__ uint32_t hist[256];
-    const long row = blockIdx.x;
-    const int lane = threadIdx.x;
-    const double *s = S + row * pitch;
-    uint64_t key[KPL];
+    const int lane = threadIdx.x & 63;
     uint64_t kmin = ~0ull, kmax = 0;
 #pragma unroll
-    for (int m = 0; m < KPL; ++m) {
-        const int j = m * 64 + lane;
-        key[m] = ~0ull;
-        if (j < Nkb) {
-            const double v = s[j];
-            if (S_dense) S_dense[row * Nkb + j] = v;
-            key[m] = desc_key(v);
+    for (int m = 0; m < KPL; ++m)
+        if (m * 64 + lane < Nkb) {
             kmin = key[m] < kmin ? key[m] : kmin;
             kmax = key[m] > kmax ? key[m] : kmax;
         }
-    }
     kmin = wave_min_u64(kmin);
     kmax = wave_max_u64(kmax);
 
@@ -327,6 +319,96 @@ __global__ __launch_bounds__(64) void select_kernel(const double *__restrict__ S
             ncrit += __popcll(b);
         }
     }
+}
+
+template <int KPL>
+__global__ __launch_bounds__(64) void select_kernel(const double *__restrict__ S, int pitch, int Nkb, int k_c, int k_n,
+                                                    int8_t *__restrict__ lab_pad, int lab_pitch,
+                                                    int8_t *__restrict__ lab_dense, int32_t *__restrict__ crit_idx,
+                                                    float *__restrict__ Pc, double *__restrict__ S_dense, float sm_scale)
+{
+    __shared__ uint32_t hist[256];
+    const long row = blockIdx.x;
+    const int lane = threadIdx.x;
+    const double *s = S + row * pitch;
+    uint64_t key[KPL];
+#pragma unroll
+    for (int m = 0; m < KPL; ++m) {
+        const int j = m * 64 + lane;
+        key[m] = ~0ull;
+        if (j < Nkb) {
+            const double v = s[j];
+            if (S_dense) S_dense[row * Nkb + j] = v;
+            key[m] = desc_key(v);
+        }
+    }
+    classify_row_wave<KPL>(key, row, Nkb, k_c, k_n, hist, lab_pad, lab_pitch, lab_dense, crit_idx, Pc, sm_scale);
+}
+
+// Fused classifier for short rows (Nkb <= 64 KPL <= 256): block mean of Q, pooled logits and
+// classification in one launch.  A workgroup of four waves takes four consecutive query blocks of one
+// (b, h): lane d of wave w first forms channel d of the block mean (serial fp64 sum over the block's
+// tokens, times 1/count); then, chunk of 64 key blocks by chunk, the K means are staged in LDS and lane
+// l of wave w runs the 64-step fma chain of (query block w, key block l); the logits never leave registers.
+template <int KPL, bool FP8>
+__global__ __launch_bounds__(256) void classify_fused_kernel(const void *__restrict__ Q, const float *__restrict__ sQ,
+                                                             const double *__restrict__ kbar, int N, int bq, int Nqb, int Nkb,
+                                                             int k_c, int k_n, int8_t *__restrict__ lab_pad, int lab_pitch,
+                                                             int8_t *__restrict__ lab_dense, int32_t *__restrict__ crit_idx,
+                                                             float *__restrict__ Pc, double *__restrict__ S_dense,
+                                                             double *__restrict__ qbar_out, float sm_scale)
+{
+    __shared__ double ks[64][65];          // 65: rows land on different banks when lane l reads row l
+    __shared__ double qs[4][kD];
+    __shared__ uint32_t hist[4][256];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const long bh = blockIdx.y;
+    const int i = blockIdx.x * 4 + wave;
+    const bool rowok = i < Nqb;
+    const long row = bh * Nqb + i;
+
+    double mean = 0.0;
+    if (rowok) {
+        const int t0 = i * bq, cnt = min(bq, N - t0);
+        double acc = 0.0;
+        if (FP8) {
+            const uint8_t *x = (const uint8_t *)Q + ((size_t)bh * N + t0) * kD + lane;
+            const double sc = (double)sQ[row];
+#pragma unroll 16
+            for (int t = 0; t < cnt; ++t) acc += (double)__builtin_amdgcn_cvt_f32_fp8((int)x[(size_t)t * kD], 0) * sc;
+        } else {
+            const uint16_t *x = (const uint16_t *)Q + ((size_t)bh * N + t0) * kD + lane;
+#pragma unroll 16
+            for (int t = 0; t < cnt; ++t) acc += (double)bf16_bits_to_f32(x[(size_t)t * kD]);
+        }
+        mean = acc * (1.0 / (double)cnt);
+        if (qbar_out) qbar_out[row * kD + lane] = mean;
+    }
+    qs[wave][lane] = mean;
+
+    uint64_t key[KPL];
+    const double *kh = kbar + bh * (long)Nkb * kD;
+#pragma unroll
+    for (int m = 0; m < KPL; ++m) {
+        __syncthreads();                   // previous chunk consumed (first trip: qs written)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int idx = tid + 256 * r, jj = idx >> 6, d = idx & 63, j = m * 64 + jj;
+            ks[jj][d] = j < Nkb ? kh[(long)j * kD + d] : 0.0;
+        }
+        __syncthreads();
+        double s = 0.0;
+#pragma unroll 16
+        for (int d = 0; d < kD; ++d) s = fma(qs[wave][d], ks[lane][d], s);
+        const int j = m * 64 + lane;
+        key[m] = ~0ull;
+        if (rowok && j < Nkb) {
+            if (S_dense) S_dense[row * Nkb + j] = s;
+            key[m] = desc_key(s);
+        }
+    }
+    if (rowok)
+        classify_row_wave<KPL>(key, row, Nkb, k_c, k_n, hist[wave], lab_pad, lab_pitch, lab_dense, crit_idx, Pc, sm_scale);
 }
 
 // ---- workgroup-per-row variant for long rows (Nkb > 256) ------------------------------------
@@ -548,6 +630,31 @@ hipError_t launch_select(const double *S, int pitch, long rows, int Nkb, int k_c
     if (lab_pitch <= 3072) SLA_SELB(12);
     if (lab_pitch <= 4096) SLA_SELB(16);
 #undef SLA_SELB
+    return hipErrorInvalidValue;
+}
+
+template <int KPL>
+static hipError_t launch_classify_fused_t(const void *Q, const float *sQ, bool fp8, const double *kbar, int BH, int N, int bq,
+                                          int Nqb, int Nkb, int k_c, int k_n, int8_t *lab_pad, int lab_pitch, int8_t *lab_dense,
+                                          int32_t *crit_idx, float *Pc, double *S_dense, double *qbar_out, float sm_scale,
+                                          hipStream_t st)
+{
+    dim3 grid((Nqb + 3) / 4, BH);
+    if (fp8) classify_fused_kernel<KPL, true><<<grid, 256, 0, st>>>(Q, sQ, kbar, N, bq, Nqb, Nkb, k_c, k_n, lab_pad, lab_pitch, lab_dense, crit_idx, Pc, S_dense, qbar_out, sm_scale);
+    else     classify_fused_kernel<KPL, false><<<grid, 256, 0, st>>>(Q, sQ, kbar, N, bq, Nqb, Nkb, k_c, k_n, lab_pad, lab_pitch, lab_dense, crit_idx, Pc, S_dense, qbar_out, sm_scale);
+    return hipGetLastError();
+}
+
+hipError_t launch_classify_fused(const void *Q, const float *sQ, bool fp8, const double *kbar, int BH, int N, int bq, int Nkb,
+                                 int k_c, int k_n, int8_t *lab_pad, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx,
+                                 float *Pc, double *S_dense, double *qbar_out, float sm_scale, hipStream_t st)
+{
+    const int Nqb = (N + bq - 1) / bq;
+#define SLA_CF(K) return launch_classify_fused_t<K>(Q, sQ, fp8, kbar, BH, N, bq, Nqb, Nkb, k_c, k_n, lab_pad, lab_pitch, lab_dense, crit_idx, Pc, S_dense, qbar_out, sm_scale, st)
+    if (Nkb <= 64) SLA_CF(1);
+    if (Nkb <= 128) SLA_CF(2);
+    if (Nkb <= 256) SLA_CF(4);
+#undef SLA_CF
     return hipErrorInvalidValue;
 }
 

@@ -125,13 +125,21 @@ sla_status_t run_classify(const sla_params_t *p, const Plan &pl, const void *Q, 
     auto mark = [&](int i) { return ev ? hipEventRecord(ev[i], st) : hipSuccess; };
     double *qbar = qbar_out ? qbar_out : at<double>(ws, pl.off_qbar);
     double *kbar = kbar_out ? kbar_out : at<double>(ws, pl.off_kbar);
-    if (!pooled) {      // sla_forward pools Q itself and gets the K means from the states pass
-        SLA_HIP(sla::launch_pool(Q, sQ, pl.fp8, pl.BH, p->N, p->bq, qbar, st));
+    int32_t *crit = crit_out ? crit_out : at<int32_t>(ws, pl.off_crit);
+    const bool fused = pl.Nkb <= 256;   // short rows: Q means, logits and classification in one launch
+    if (!pooled) {                      // sla_forward gets the K means from the states pass (and pools Q itself if needed)
+        if (!fused) SLA_HIP(sla::launch_pool(Q, sQ, pl.fp8, pl.BH, p->N, p->bq, qbar, st));
         SLA_HIP(sla::launch_pool(K, sK, pl.fp8, pl.BH, p->N, p->bk, kbar, st));
     }
     SLA_HIP(mark(2));
+    if (fused) {
+        SLA_HIP(sla::launch_classify_fused(Q, sQ, pl.fp8, kbar, pl.BH, p->N, p->bq, pl.Nkb, pl.k_c, pl.k_n, at<int8_t>(ws, pl.off_lab),
+                                           pl.lab_pitch, labels, pl.k_c > 0 ? crit : nullptr, Pc, scores_out,
+                                           qbar_out ? qbar_out : nullptr, pl.sm_scale, st));
+        SLA_HIP(mark(3));
+        return SLA_OK;
+    }
     SLA_HIP(sla::launch_scores(qbar, kbar, pl.BH, pl.Nqb, pl.Nkb, pl.s_pitch, at<double>(ws, pl.off_scores), st));
-    int32_t *crit = crit_out ? crit_out : at<int32_t>(ws, pl.off_crit);
     SLA_HIP(mark(3));
     SLA_HIP(sla::launch_select(at<double>(ws, pl.off_scores), pl.s_pitch, (long)pl.BH * pl.Nqb, pl.Nkb, pl.k_c, pl.k_n,
                                at<int8_t>(ws, pl.off_lab), pl.lab_pitch, labels, pl.k_c > 0 ? crit : nullptr, Pc,
@@ -264,7 +272,7 @@ static sla_status_t forward_impl(const sla_params_t *p, const void *Q, const voi
     auto mark = [&](int i) { return ev ? hipEventRecord(ev[i], st) : hipSuccess; };
     if (launched) *launched = true;
     SLA_HIP(mark(0));
-    SLA_HIP(sla::launch_pool(Q, sQ, pl.fp8, pl.BH, p->N, p->bq, at<double>(workspace, pl.off_qbar), st));
+    if (pl.Nkb > 256) SLA_HIP(sla::launch_pool(Q, sQ, pl.fp8, pl.BH, p->N, p->bq, at<double>(workspace, pl.off_qbar), st));
     SLA_HIP(mark(1));     // states + V^T tiles + block means of K: the one pass over K and V besides the attention kernel
     SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp),
                                at<double>(workspace, pl.off_kbar), st));

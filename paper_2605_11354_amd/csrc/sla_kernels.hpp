@@ -21,6 +21,12 @@ hipError_t launch_select(const double *S, int pitch, long rows, int Nkb, int k_c
                          int8_t *lab_pad, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx,
                          float *Pc, double *S_dense, float sm_scale, hipStream_t st);
 
+// short rows (Nkb <= 256): block mean of Q + pooled logits + classifier in one launch; kbar holds the
+// block means of K.  Outputs as launch_select; qbar_out (optional) receives the block means of Q.
+hipError_t launch_classify_fused(const void *Q, const float *sQ, bool fp8, const double *kbar, int BH, int N, int bq, int Nkb,
+                                 int k_c, int k_n, int8_t *lab_pad, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx,
+                                 float *Pc, double *S_dense, double *qbar_out, float sm_scale, hipStream_t st);
+
 // dense labels -> padded labels + critical index lists (unfilled slots = -1)
 hipError_t launch_labels_prepare(const int8_t *lab_dense, long rows, int Nkb, int k_c,
                                  int8_t *lab_pad, int lab_pitch, int32_t *crit_idx, hipStream_t st);

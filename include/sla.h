@@ -96,7 +96,9 @@ sla_status_t sla_forward(const sla_params_t *p,
  * bracketed by HIP events on `stream`; the call then WAITS for the stream and writes the
  * duration of each kernel in milliseconds to stage_ms[SLA_NUM_STAGES] (host memory).
  * It creates and destroys its events, so unlike every other entry point it touches the HIP
- * runtime beyond launches and synchronises.  sla_stage_name(i) names stage i.
+ * runtime beyond launches and synchronises.  sla_stage_name(i) names stage i.  Rows of at most
+ * 256 key blocks take the fused classifier, reported as "scores"; "pool_q" and "select" are
+ * then empty (their figure is the cost of an event pair).
  */
 #define SLA_NUM_STAGES 7
 sla_status_t sla_forward_profiled(const sla_params_t *p,

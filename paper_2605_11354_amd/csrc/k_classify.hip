@@ -347,9 +347,11 @@ __global__ __launch_bounds__(64) void select_kernel(const double *__restrict__ S
 
 // Fused classifier for short rows (Nkb <= 64 KPL <= 256): block mean of Q, pooled logits and
 // classification in one launch.  A workgroup of four waves takes four consecutive query blocks of one
-// (b, h): lane d of wave w first forms channel d of the block mean (serial fp64 sum over the block's
-// tokens, times 1/count); then, chunk of 64 key blocks by chunk, the K means are staged in LDS and lane
-// l of wave w runs the 64-step fma chain of (query block w, key block l); the logits never leave registers.
+// (b, h).  Lane d of wave w first forms channel d of the block mean of query block w (serial fp64 sum
+// over the tokens in ascending order, times 1/count).  Chunk of 64 key blocks by chunk, the K means are staged in LDS
+// (the next chunk already on its way in registers) and lane l of wave w runs the 64-step fma chain of
+// (query block w, key block l), reading its K mean two channels per LDS access and channel d of the
+// Q mean out of lane d; the logits never leave registers.
 template <int KPL, bool FP8>
 __global__ __launch_bounds__(256) void classify_fused_kernel(const void *__restrict__ Q, const float *__restrict__ sQ,
                                                              const double *__restrict__ kbar, int N, int bq, int Nqb, int Nkb,
@@ -358,17 +360,29 @@ __global__ __launch_bounds__(256) void classify_fused_kernel(const void *__restr
                                                              float *__restrict__ Pc, double *__restrict__ S_dense,
                                                              double *__restrict__ qbar_out, float sm_scale)
 {
-    __shared__ double ks[64][65];          // 65: rows land on different banks when lane l reads row l
-    __shared__ double qs[4][kD];
+    constexpr int kPitch = 66;             // doubles per row of the K-mean buffer: 16-byte aligned rows, and the
+                                           // sixteen lanes of one 16-byte access pass cover all 64 banks once
+    __shared__ __align__(16) double ks[64 * kPitch];
     __shared__ uint32_t hist[4][256];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const long bh = blockIdx.y;
     const int i = blockIdx.x * 4 + wave;
     const bool rowok = i < Nqb;
     const long row = bh * Nqb + i;
+    const double *kh = kbar + bh * (long)Nkb * kD;
+
+    double2 nx[8];                         // the chunk of K means on its way to LDS (two channels per lane and load)
+    auto load_chunk = [&](int m) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int idx = tid + 256 * r, j = m * 64 + (idx >> 5);
+            nx[r] = j < Nkb ? *(const double2 *)(kh + (long)j * kD + (idx & 31) * 2) : double2{0.0, 0.0};
+        }
+    };
+    load_chunk(0);
 
     double mean = 0.0;
-    if (rowok) {
+    if (rowok) {                           // 2-byte (1-byte) loads straight from global memory: LDS is the busy unit here
         const int t0 = i * bq, cnt = min(bq, N - t0);
         double acc = 0.0;
         if (FP8) {
@@ -384,22 +398,28 @@ __global__ __launch_bounds__(256) void classify_fused_kernel(const void *__restr
         mean = acc * (1.0 / (double)cnt);
         if (qbar_out) qbar_out[row * kD + lane] = mean;
     }
-    qs[wave][lane] = mean;
+    const int mlo = __double2loint(mean), mhi = __double2hiint(mean);
 
     uint64_t key[KPL];
-    const double *kh = kbar + bh * (long)Nkb * kD;
 #pragma unroll
     for (int m = 0; m < KPL; ++m) {
-        __syncthreads();                   // previous chunk consumed (first trip: qs written)
+        __syncthreads();                   // previous chunk consumed
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int idx = tid + 256 * r, jj = idx >> 6, d = idx & 63, j = m * 64 + jj;
-            ks[jj][d] = j < Nkb ? kh[(long)j * kD + d] : 0.0;
+        for (int r = 0; r < 8; ++r) {
+            const int idx = tid + 256 * r;
+            *(double2 *)(ks + (idx >> 5) * kPitch + (idx & 31) * 2) = nx[r];
         }
         __syncthreads();
+        if (m + 1 < KPL) load_chunk(m + 1);
         double s = 0.0;
-#pragma unroll 16
-        for (int d = 0; d < kD; ++d) s = fma(qs[wave][d], ks[lane][d], s);
+#pragma unroll
+        for (int d = 0; d < kD; d += 2) {
+            const double2 kv = *(const double2 *)(ks + lane * kPitch + d);
+            const double q0 = __hiloint2double(__builtin_amdgcn_readlane(mhi, d), __builtin_amdgcn_readlane(mlo, d));
+            const double q1 = __hiloint2double(__builtin_amdgcn_readlane(mhi, d + 1), __builtin_amdgcn_readlane(mlo, d + 1));
+            s = fma(q0, kv.x, s);
+            s = fma(q1, kv.y, s);
+        }
         const int j = m * 64 + lane;
         key[m] = ~0ull;
         if (rowok && j < Nkb) {
@@ -653,6 +673,7 @@ hipError_t launch_classify_fused(const void *Q, const float *sQ, bool fp8, const
 #define SLA_CF(K) return launch_classify_fused_t<K>(Q, sQ, fp8, kbar, BH, N, bq, Nqb, Nkb, k_c, k_n, lab_pad, lab_pitch, lab_dense, crit_idx, Pc, S_dense, qbar_out, sm_scale, st)
     if (Nkb <= 64) SLA_CF(1);
     if (Nkb <= 128) SLA_CF(2);
+    if (Nkb <= 192) SLA_CF(3);
     if (Nkb <= 256) SLA_CF(4);
 #undef SLA_CF
     return hipErrorInvalidValue;

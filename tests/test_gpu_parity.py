@@ -182,6 +182,36 @@ def test_v_ones_closed_form_on_device():
     assert np.abs(G.bf16_tensor_to_f64(O) - expect).max() <= 2e-2
 
 
+@pytest.mark.parametrize("name", ["c1_small", "c3_small", "c2_small"])
+def test_forward_back_to_back_and_profiled_variant(name):
+    """Calls queued on one stream without host waits, sharing one workspace, must not disturb each
+    other (short rows fork onto the library's helper stream), and the measurement variant, which
+    runs the same kernels serially, must give the same bytes."""
+    from paper_2605_11354_amd import binding as B
+    a = _case(name)
+    d2 = dict(a.d)
+    d2["Q"], d2["K"] = a.d["K"].copy(), a.d["Q"].copy()        # a second problem of the same shape
+    b = G.Case(a.cfg, d2, k_crit=a.k_c, k_neg=a.k_n)
+    b.ws = a.ws
+    ref_a, lab_a = a.forward()
+    ref_b, lab_b = b.forward()
+    c = a.cfg
+    outs = [torch.zeros((c.B, c.H, c.N, 64), dtype=torch.bfloat16, device="cuda") for _ in range(6)]
+    labs = [torch.zeros((c.B, c.H, a.Nqb, a.Nkb), dtype=torch.int8, device="cuda") for _ in range(6)]
+    for r in range(6):
+        x = a if r % 2 == 0 else b
+        B.sla_forward(x.p, x.Q, x.K, x.V, x.W, outs[r], labs[r], x.sQ, x.sK, x.sV, a.ws)
+    torch.cuda.synchronize()
+    for r in range(6):
+        assert torch.equal(outs[r].view(torch.int16), (ref_a if r % 2 == 0 else ref_b).view(torch.int16)), r
+        assert torch.equal(labs[r], lab_a if r % 2 == 0 else lab_b), r
+    O = torch.zeros_like(outs[0])
+    lab = torch.zeros_like(labs[0])
+    stages = B.sla_forward_profiled(a.p, a.Q, a.K, a.V, a.W, O, lab, a.sQ, a.sK, a.sV, a.ws)
+    assert set(stages) == {B.lib().sla_stage_name(i).decode() for i in range(B.NUM_STAGES)}
+    assert torch.equal(O.view(torch.int16), ref_a.view(torch.int16)) and torch.equal(lab, lab_a)
+
+
 def test_errors_are_reported_not_launched():
     from paper_2605_11354_amd import binding as B
     case = G.Case(C0)

@@ -20,44 +20,27 @@ namespace sla {
 constexpr int kLdsRow = 72;            // bf16 elements per LDS row (64 + 8 pad: 144 B stride)
 constexpr int kWavesPerWG = 2;
 
-// Raw global data of one key block, as loaded: K as 16-byte row chunks, V as dwords arranged
-// for the register transpose.
+// Raw global data of one key block, as loaded: K as 16-byte row chunks, V as 8-byte (bf16) or
+// 4-byte (e4m3) pieces of four channels arranged for the register transpose.
 template <bool FP8>
 struct BlockRegs {
     uint4 k[FP8 ? 4 : 8];
     uint32_t v[FP8 ? 16 : 32];
 };
 
+// Rows past the end of the sequence (ragged last block of a head) repeat the last valid row: their
+// phi is multiplied by zero below, and finite stand-in values keep every product finite.
 template <bool FP8>
 __device__ __forceinline__ void load_block(BlockRegs<FP8> &r, const void *K, const void *V, size_t tok0, int valid, int lane)
 {
+    const int last = valid - 1;
     if (!FP8) {
         const uint16_t *Kg = (const uint16_t *)K + tok0, *Vg = (const uint16_t *)V + tok0;
         // K: chunk c = lane + 64 x is 8 channels (16 B) of row c/8
 #pragma unroll
         for (int x = 0; x < 8; ++x) {
-            const int c = lane + 64 * x, t = c >> 3, col = (c & 7) * 8;
-            r.k[x] = make_uint4(0, 0, 0, 0);
-            if (t < valid) r.k[x] = *(const uint4 *)(Kg + (size_t)t * kD + col);
-        }
-        // V: unit u = lane + 64 x is 2 channels (pair u%32) x 8 consecutive tokens (group u/32)
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            const int u = lane + 64 * x, ep = u & 31, tg = u >> 5;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int t = tg * 8 + k;
-                r.v[8 * x + k] = t < valid ? *(const uint32_t *)(Vg + (size_t)t * kD + 2 * ep) : 0u;
-            }
-        }
-    } else {
-        const uint8_t *Kg = (const uint8_t *)K + tok0, *Vg = (const uint8_t *)V + tok0;
-        // K: chunk c = lane + 64 x is 16 channels (16 B of e4m3) of row c/4
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            const int c = lane + 64 * x, t = c >> 2, col = (c & 3) * 16;
-            r.k[x] = make_uint4(0, 0, 0, 0);
-            if (t < valid) r.k[x] = *(const uint4 *)(Kg + (size_t)t * kD + col);
+            const int c = lane + 64 * x, t = min(c >> 3, last), col = (c & 7) * 8;
+            r.k[x] = *(const uint4 *)(Kg + (size_t)t * kD + col);
         }
         // V: unit u = lane + 64 x is 4 channels (quad u%16) x 8 consecutive tokens (group u/16)
 #pragma unroll
@@ -65,8 +48,28 @@ __device__ __forceinline__ void load_block(BlockRegs<FP8> &r, const void *K, con
             const int u = lane + 64 * x, eq = u & 15, tg = u >> 4;
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
-                const int t = tg * 8 + k;
-                r.v[8 * x + k] = t < valid ? *(const uint32_t *)(Vg + (size_t)t * kD + 4 * eq) : 0u;
+                const int t = min(tg * 8 + k, last);
+                const uint2 w = *(const uint2 *)(Vg + (size_t)t * kD + 4 * eq);
+                r.v[16 * x + 2 * k] = w.x;
+                r.v[16 * x + 2 * k + 1] = w.y;
+            }
+        }
+    } else {
+        const uint8_t *Kg = (const uint8_t *)K + tok0, *Vg = (const uint8_t *)V + tok0;
+        // K: chunk c = lane + 64 x is 16 channels (16 B of e4m3) of row c/4
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const int c = lane + 64 * x, t = min(c >> 2, last), col = (c & 3) * 16;
+            r.k[x] = *(const uint4 *)(Kg + (size_t)t * kD + col);
+        }
+        // V: unit u = lane + 64 x is 4 channels (quad u%16) x 8 consecutive tokens (group u/16)
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+            const int u = lane + 64 * x, eq = u & 15, tg = u >> 4;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int t = min(tg * 8 + k, last);
+                r.v[8 * x + k] = *(const uint32_t *)(Vg + (size_t)t * kD + 4 * eq);
             }
         }
     }
@@ -94,16 +97,23 @@ __device__ __forceinline__ void stage_block(const BlockRegs<FP8> &r, uint16_t *K
             *(uint4 *)(Ks + t * kLdsRow + col) = r.k[x];
         }
 #pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            const int u = lane + 64 * x, ep = u & 31, tg = u >> 5;
-            const uint32_t *w = r.v + 8 * x;
-            uint4 lo, hi;   // lo: channel 2ep over 8 tokens, hi: channel 2ep+1
-            lo.x = __builtin_amdgcn_perm(w[1], w[0], 0x05040100); hi.x = __builtin_amdgcn_perm(w[1], w[0], 0x07060302);
-            lo.y = __builtin_amdgcn_perm(w[3], w[2], 0x05040100); hi.y = __builtin_amdgcn_perm(w[3], w[2], 0x07060302);
-            lo.z = __builtin_amdgcn_perm(w[5], w[4], 0x05040100); hi.z = __builtin_amdgcn_perm(w[5], w[4], 0x07060302);
-            lo.w = __builtin_amdgcn_perm(w[7], w[6], 0x05040100); hi.w = __builtin_amdgcn_perm(w[7], w[6], 0x07060302);
-            *(uint4 *)(Vt + (2 * ep) * kLdsRow + tg * 8) = lo;
-            *(uint4 *)(Vt + (2 * ep + 1) * kLdsRow + tg * 8) = hi;
+        for (int x = 0; x < 2; ++x) {
+            const int u = lane + 64 * x, eq = u & 15, tg = u >> 4;
+            const uint32_t *w = r.v + 16 * x;      // w[2k], w[2k+1]: channels 4eq..4eq+3 of token 8 tg + k
+            uint4 c0, c1, c2, c3;                  // channel 4eq + c over the 8 tokens
+            c0.x = __builtin_amdgcn_perm(w[2], w[0], 0x05040100);   c1.x = __builtin_amdgcn_perm(w[2], w[0], 0x07060302);
+            c2.x = __builtin_amdgcn_perm(w[3], w[1], 0x05040100);   c3.x = __builtin_amdgcn_perm(w[3], w[1], 0x07060302);
+            c0.y = __builtin_amdgcn_perm(w[6], w[4], 0x05040100);   c1.y = __builtin_amdgcn_perm(w[6], w[4], 0x07060302);
+            c2.y = __builtin_amdgcn_perm(w[7], w[5], 0x05040100);   c3.y = __builtin_amdgcn_perm(w[7], w[5], 0x07060302);
+            c0.z = __builtin_amdgcn_perm(w[10], w[8], 0x05040100);  c1.z = __builtin_amdgcn_perm(w[10], w[8], 0x07060302);
+            c2.z = __builtin_amdgcn_perm(w[11], w[9], 0x05040100);  c3.z = __builtin_amdgcn_perm(w[11], w[9], 0x07060302);
+            c0.w = __builtin_amdgcn_perm(w[14], w[12], 0x05040100); c1.w = __builtin_amdgcn_perm(w[14], w[12], 0x07060302);
+            c2.w = __builtin_amdgcn_perm(w[15], w[13], 0x05040100); c3.w = __builtin_amdgcn_perm(w[15], w[13], 0x07060302);
+            uint16_t *dst = Vt + (4 * eq) * kLdsRow + tg * 8;
+            *(uint4 *)(dst) = c0;
+            *(uint4 *)(dst + kLdsRow) = c1;
+            *(uint4 *)(dst + 2 * kLdsRow) = c2;
+            *(uint4 *)(dst + 3 * kLdsRow) = c3;
         }
     } else {
 #pragma unroll
@@ -134,7 +144,7 @@ __device__ __forceinline__ void stage_block(const BlockRegs<FP8> &r, uint16_t *K
 }
 
 template <bool FP8>
-__global__ __launch_bounds__(64 * kWavesPerWG) void states_kernel(const void *__restrict__ K, const void *__restrict__ V,
+__global__ __launch_bounds__(64 * kWavesPerWG) __attribute__((amdgpu_waves_per_eu(2, 2))) void states_kernel(const void *__restrict__ K, const void *__restrict__ V,
                                                                   const float *__restrict__ sK, const float *__restrict__ sV,
                                                                   int N, int Nkb, long nblocks, int per_wave,
                                                                   uint16_t *__restrict__ hT, uint16_t *__restrict__ Vp,
@@ -216,12 +226,13 @@ __global__ __launch_bounds__(64 * kWavesPerWG) void states_kernel(const void *__
         // 16 swapped (slot 16s + 8g + 4a + b holds token 16s + 8a + 4g + b), which is the key order the
         // accumulator-as-operand trick of that kernel needs; e4m3 V leaves widened to bf16, unscaled.
         if (Vp != nullptr) {
-            uint16_t *vrow = Vp + ((size_t)blk * kD + lane) * kBK;
+            uint16_t *vt = Vp + (size_t)blk * kD * kBK;
+            const int c = lane & 7, src = 16 * (c >> 1) + 4 * (c & 1);   // 16-byte piece c of a row: tokens src..src+3, src+8..src+11
 #pragma unroll
-            for (int c = 0; c < 8; c += 2) {
-                const uint4 w0 = *(const uint4 *)(Vt + lane * kLdsRow + c * 8), w1 = *(const uint4 *)(Vt + lane * kLdsRow + c * 8 + 8);
-                *(uint4 *)(vrow + c * 8) = make_uint4(w0.x, w0.y, w1.x, w1.y);
-                *(uint4 *)(vrow + c * 8 + 8) = make_uint4(w0.z, w0.w, w1.z, w1.w);
+            for (int x = 0; x < 8; ++x) {                                // a wave-wide store covers 8 whole rows (1 KB)
+                const int e = 8 * x + (lane >> 3);
+                const uint2 lo = *(const uint2 *)(Vt + e * kLdsRow + src), hi = *(const uint2 *)(Vt + e * kLdsRow + src + 8);
+                *(uint4 *)(vt + e * kBK + 8 * c) = make_uint4(lo.x, lo.y, hi.x, hi.y);
             }
         }
 
@@ -253,9 +264,11 @@ __global__ __launch_bounds__(64 * kWavesPerWG) void states_kernel(const void *__
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], s == 0 ? zero16 : acc[a][b], 0, 0, 0);
         }
 
-        // ---- write hT[e][d]: accumulator (a,b) register 4q+r holds d = 32a + 8q + 4g + r, e = 32b + l32
+        // ---- write hT[e][d]: accumulator (a,b) register 4q+r holds d = 32a + 8q + 4g + r, e = 32b + l32.
+        // The tile goes through LDS (phi^T is consumed) so that it leaves as whole rows, 1 KB per wave-wide store.
         uint16_t *out = hT + (size_t)blk * kStateElems;
         const float vs = FP8 ? sV[blk] : 1.0f;
+        wave_lds_sync();                                        // the operand reads of phi^T are done
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -265,8 +278,14 @@ __global__ __launch_bounds__(64 * kWavesPerWG) void states_kernel(const void *__
                     uint2 o;
                     o.x = pack_bf16(acc[a][b][4 * q + 0] * vs, acc[a][b][4 * q + 1] * vs);
                     o.y = pack_bf16(acc[a][b][4 * q + 2] * vs, acc[a][b][4 * q + 3] * vs);
-                    *(uint2 *)(out + (32 * b + l32) * kD + 32 * a + 8 * q + 4 * g) = o;
+                    *(uint2 *)(Ks + (32 * b + l32) * kLdsRow + 32 * a + 8 * q + 4 * g) = o;
                 }
+        wave_lds_sync();
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const int e = 8 * x + (lane >> 3), c = lane & 7;
+            *(uint4 *)(out + e * kD + 8 * c) = *(const uint4 *)(Ks + e * kLdsRow + 8 * c);
+        }
         out[64 * kD + lane] = (uint16_t)(pack_bf16(z, 0.f) & 0xFFFFu);
     }
 }

@@ -2,126 +2,236 @@
 //     Hq[i][:] = sum_{j : label(i,j) == marginal} hT[j][:]          (4160 values per block)
 // evaluated per head as the product  M[Nqb x Nkb] * Hf[Nkb x 4160]  with M the 0/1 marginal
 // mask, on v_mfma_f32_32x32x16_bf16 with fp32 accumulation.  A gather would move
-// Nqb*k_m*8.3 KB per head; the product re-uses every state tile across 128 query blocks.
+// Nqb*k_m*8.3 KB per head; the product re-uses every state tile across all query blocks of a
+// workgroup tile.
 //
-// Workgroup tile 128 (query blocks) x 128 (state columns), K step 32 key blocks, 4 waves in
-// a 2x2 arrangement of 64x64 wave tiles.  The mask operand is built on the fly from the
-// int8 labels; the state operand is transposed in registers while it is staged so both MFMA
-// operands are read from LDS as 16-byte rows.
+// The kernel computes the transposed tile  D^T[n][i] = sum_j Hf[j][n] M[i][j]:  the state slab is
+// the MFMA A operand and goes through LDS (transposed in registers on its way in, so the operand
+// is read as 16-byte rows); the mask is the B operand and never touches LDS: a lane's eight mask
+// values of one MFMA are eight consecutive bits of the row's marginal bit mask, expanded in
+// registers to bf16 2.0 / 0.0 (a bf16 power of two has a single bit set; the accumulators are
+// halved at the end, which is exact).  A lane's four consecutive accumulator registers are four
+// consecutive state columns of one query block and leave through LDS as 16-byte stores.
+//
+// Workgroup: 4 waves, tile 128 state columns x BM query blocks.  Long heads: BM = 256, every wave
+// takes all 128 columns (TA = 4 sub-tiles of 32) and 64 query blocks (TB = 2), so the state slab,
+// which dominates the L2 traffic, is read once per 256 query blocks and one expanded mask operand
+// feeds four MFMAs.  Short heads: BM = 64, waves as 2 x 2 with TA = 2, TB = 1.  K step 64
+// key blocks; global loads run kAggAhead K steps ahead of their use in register sets, LDS is
+// double buffered: one barrier per K step.
 #include "sla_common.hpp"
 #include "sla_kernels.hpp"
 
 namespace sla {
 
-constexpr int kAggRow = 40;   // bf16 per LDS row: 32 K-values + 8 pad (80 B stride)
+namespace {
+constexpr int kAggK = 64;             // key blocks per K step (one 64-bit mask word)
+constexpr int kAggRow = kAggK + 8;    // bf16 per state-operand row in LDS: 144 B, consecutive rows start 9 16-byte slots apart
+constexpr int kAggOutRow = 128 + 8;   // bf16 per row of the output staging tile (272 B)
+constexpr int kAggAhead = 3;          // K steps between a global load and its use
+constexpr int kAggBuf = 128 * kAggRow;
+}  // namespace
 
-__global__ __launch_bounds__(256) void aggregate_kernel(const int8_t *__restrict__ lab, int lab_pitch,
-                                                        const uint16_t *__restrict__ hT, int Nqb, int Nkb,
-                                                        uint16_t *__restrict__ Hq)
+template <int TA, int TB>
+__global__ __launch_bounds__(256) void aggregate_kernel(const uint2 *__restrict__ mbits, int nkw,
+                                                        const uint16_t *__restrict__ hT, int Nqb, int Nkb, int n_it,
+                                                        long total, uint16_t *__restrict__ Hq)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t As[128 * kAggRow];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[128 * kAggRow];
+    constexpr int kWN = 4 / TA;                   // waves along the columns (TA 32-column sub-tiles each)
+    constexpr int kWI = 4 / kWN;                  // waves along the query blocks (TB 32-block sub-tiles each)
+    constexpr int BM = 32 * TB * kWI;             // query blocks per workgroup tile
+    constexpr int kStage = BM * kAggOutRow > 2 * kAggBuf ? BM * kAggOutRow : 2 * kAggBuf;
+    __shared__ __attribute__((aligned(16))) uint16_t smem[kStage];
+
+    const long item = xcd_remap(blockIdx.x, total);      // (head, column tile, query tile), query tile fastest:
+    if (item >= total) return;                           // neighbours on one XCD share a state slab in its L2
+    const int it = (int)(item % n_it);
+    const long rest = item / n_it;
+    constexpr int kNT = (kStateElems + 127) / 128;
+    const int nt = (int)(rest % kNT);
+    const long bh = rest / kNT;
+    const int n0 = nt * 128, i0 = it * BM;
+
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, g = lane >> 5;
-    const int n0 = blockIdx.x * 128, i0 = blockIdx.y * 128;
-    const long bh = blockIdx.z;
-    const int8_t *labh = lab + bh * (long)Nqb * lab_pitch;
+    const int l32 = lane & 31, g = lane >> 5;
+    const int wn = (wave / kWI) * (32 * TA), wi = (wave % kWI) * (32 * TB);   // wave's first column / query block within the tile
     const uint16_t *Hf = hT + bh * (long)Nkb * kStateElems;
 
-    // A loader: thread -> (row i = tid/2, 16 labels at k = 16*(tid&1))
-    const int ai = tid >> 1, ak = (tid & 1) * 16;
-    const bool a_ok = i0 + ai < Nqb;
-    // B loader: thread -> (column pair 2p, 2p+1; 8 consecutive key blocks 8*kg..)
-    const int bp = tid & 63, bkg = tid >> 6;
-    const bool b_ok = n0 + 2 * bp < kStateElems;      // kStateElems is even: the pair is in or out together
+    // state loader: thread -> 4 columns (4 n4 ..) x 8 key blocks (8 jg ..).  Lane bits 0-1 and 4-6 select the
+    // column group, bits 2-3 and 7 the key-block group: a load instruction covers whole 128-byte lines and the
+    // sixteen lanes of one LDS write pass land on sixteen different 16-byte slots.
+    // The loads of the main loop are unconditional (indices are clamped instead: key blocks past the end repeat
+    // the last one and meet mask bits that are zero, columns and query blocks past the end give results nobody
+    // stores), so the compiler can count the loads in flight and wait for exactly the set it needs.
+    const int n4 = (tid & 3) | ((tid >> 2) & 0x1C), jg = ((tid >> 2) & 3) | ((tid >> 5) & 4);
+    const uint16_t *hcol = Hf + (n0 + 4 * n4 < kStateElems ? n0 + 4 * n4 : 0);   // kStateElems % 4 == 0: a group is in or out as a whole
+    // mask rows of this lane: query block i0 + wi + 32 b + l32, one 64-bit word per K step
+    const uint2 *mrow[TB];
+#pragma unroll
+    for (int b = 0; b < TB; ++b) {
+        const int i = i0 + wi + 32 * b + l32;
+        mrow[b] = mbits + (bh * (long)Nqb + (i < Nqb ? i : 0)) * nkw;
+    }
+    const int ksteps = (Nkb + kAggK - 1) / kAggK;            // == nkw
 
-    f32x16 acc[2][2];
+    uint2 hreg[kAggAhead][8];
+    uint2 mreg[kAggAhead][TB];
+    auto load_tile = [&](int ks, uint2 (&h)[8], uint2 (&m)[TB]) {          // main loop: ks < ksteps
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-
-    uint4 areg = make_uint4(0, 0, 0, 0);
-    uint32_t breg[8];
-    auto load_tile = [&](int k0) {
-        areg = make_uint4(0, 0, 0, 0);
-        if (a_ok && k0 + ak < lab_pitch) areg = *(const uint4 *)(labh + (long)(i0 + ai) * lab_pitch + k0 + ak);
+        for (int b = 0; b < TB; ++b) m[b] = mrow[b][ks];
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            const int j = k0 + bkg * 8 + r;
-            breg[r] = (b_ok && j < Nkb) ? *(const uint32_t *)(Hf + (long)j * kStateElems + n0 + 2 * bp) : 0u;
+            const int j = min(ks * kAggK + jg * 8 + r, Nkb - 1);
+            h[r] = *(const uint2 *)(hcol + (long)j * kStateElems);
         }
     };
-    auto store_tile = [&]() {
-        // 16 labels -> 16 bf16 mask values (1.0 where the label is "marginal")
-        uint32_t w[4] = {areg.x, areg.y, areg.z, areg.w};
-        uint32_t o[8];
+    // first and last steps: the same tile, but key blocks past the end are skipped instead of repeated (short
+    // heads have K steps that are mostly padding)
+    auto load_tile_edge = [&](int ks, uint2 (&h)[8], uint2 (&m)[TB]) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const uint32_t b0 = (w[q] & 0xFFu) == 1u, b1 = ((w[q] >> 8) & 0xFFu) == 1u;
-            const uint32_t b2 = ((w[q] >> 16) & 0xFFu) == 1u, b3 = (w[q] >> 24) == 1u;
-            o[2 * q] = (b0 ? 0x3F80u : 0u) | (b1 ? 0x3F800000u : 0u);
-            o[2 * q + 1] = (b2 ? 0x3F80u : 0u) | (b3 ? 0x3F800000u : 0u);
+        for (int b = 0; b < TB; ++b) m[b] = mrow[b][ks];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int j = ks * kAggK + jg * 8 + r;
+            h[r] = j < Nkb ? *(const uint2 *)(hcol + (long)j * kStateElems) : make_uint2(0u, 0u);
         }
-        *(uint4 *)(As + ai * kAggRow + ak) = make_uint4(o[0], o[1], o[2], o[3]);
-        *(uint4 *)(As + ai * kAggRow + ak + 8) = make_uint4(o[4], o[5], o[6], o[7]);
-        uint4 lo, hi;
-        lo.x = __builtin_amdgcn_perm(breg[1], breg[0], 0x05040100); hi.x = __builtin_amdgcn_perm(breg[1], breg[0], 0x07060302);
-        lo.y = __builtin_amdgcn_perm(breg[3], breg[2], 0x05040100); hi.y = __builtin_amdgcn_perm(breg[3], breg[2], 0x07060302);
-        lo.z = __builtin_amdgcn_perm(breg[5], breg[4], 0x05040100); hi.z = __builtin_amdgcn_perm(breg[5], breg[4], 0x07060302);
-        lo.w = __builtin_amdgcn_perm(breg[7], breg[6], 0x05040100); hi.w = __builtin_amdgcn_perm(breg[7], breg[6], 0x07060302);
-        *(uint4 *)(Bs + (2 * bp) * kAggRow + bkg * 8) = lo;
-        *(uint4 *)(Bs + (2 * bp + 1) * kAggRow + bkg * 8) = hi;
+    };
+    auto store_tile = [&](uint16_t *As, const uint2 (&h)[8]) {
+        // column c of the 8x4 piece -> one 16-byte row segment (8 key blocks of one column)
+        uint4 c0, c1, c2, c3;
+        c0.x = __builtin_amdgcn_perm(h[1].x, h[0].x, 0x05040100); c1.x = __builtin_amdgcn_perm(h[1].x, h[0].x, 0x07060302);
+        c2.x = __builtin_amdgcn_perm(h[1].y, h[0].y, 0x05040100); c3.x = __builtin_amdgcn_perm(h[1].y, h[0].y, 0x07060302);
+        c0.y = __builtin_amdgcn_perm(h[3].x, h[2].x, 0x05040100); c1.y = __builtin_amdgcn_perm(h[3].x, h[2].x, 0x07060302);
+        c2.y = __builtin_amdgcn_perm(h[3].y, h[2].y, 0x05040100); c3.y = __builtin_amdgcn_perm(h[3].y, h[2].y, 0x07060302);
+        c0.z = __builtin_amdgcn_perm(h[5].x, h[4].x, 0x05040100); c1.z = __builtin_amdgcn_perm(h[5].x, h[4].x, 0x07060302);
+        c2.z = __builtin_amdgcn_perm(h[5].y, h[4].y, 0x05040100); c3.z = __builtin_amdgcn_perm(h[5].y, h[4].y, 0x07060302);
+        c0.w = __builtin_amdgcn_perm(h[7].x, h[6].x, 0x05040100); c1.w = __builtin_amdgcn_perm(h[7].x, h[6].x, 0x07060302);
+        c2.w = __builtin_amdgcn_perm(h[7].y, h[6].y, 0x05040100); c3.w = __builtin_amdgcn_perm(h[7].y, h[6].y, 0x07060302);
+        uint16_t *a = As + (4 * n4) * kAggRow + jg * 8;
+        *(uint4 *)(a) = c0;
+        *(uint4 *)(a + kAggRow) = c1;
+        *(uint4 *)(a + 2 * kAggRow) = c2;
+        *(uint4 *)(a + 3 * kAggRow) = c3;
+    };
+    // eight mask bits (key blocks 16 s + 8 g .. + 7 of the K step) -> the B operand of one MFMA: bf16 2.0 where set.
+    // x * 0x8001 puts a second copy of the byte 15 bits up, so that one shift brings bit 2d to bit 14 and bit 2d+1 to
+    // bit 30 of the same dword: the two bf16 exponent bits of 2.0.
+    auto mask_frag = [&](const uint2 &w, int s) {
+        const uint32_t x = ((s < 2 ? w.x : w.y) >> (16 * (s & 1) + 8 * g)) & 0xFFu;
+        const uint32_t m = x * 0x8001u;
+        union { uint32_t u[4]; bf16x8 v; } f;
+        f.u[0] = (m << 14) & 0x40004000u;
+        f.u[1] = (m << 12) & 0x40004000u;
+        f.u[2] = (m << 10) & 0x40004000u;
+        f.u[3] = (m << 8) & 0x40004000u;
+        return f.v;
     };
 
-    const int ksteps = (Nkb + 31) / 32;
-    load_tile(0);
-    for (int ks = 0; ks < ksteps; ++ks) {
-        __syncthreads();               // previous tile fully consumed
-        store_tile();
-        __syncthreads();
-        if (ks + 1 < ksteps) load_tile((ks + 1) * 32);
+    f32x16 acc[TA][TB];
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            bf16x8 af[2], bfr[2];
+    for (int a = 0; a < TA; ++a)
 #pragma unroll
-            for (int a = 0; a < 2; ++a) {
-                af[a] = *(const bf16x8 *)(As + (64 * wm + 32 * a + l32) * kAggRow + 16 * s + 8 * g);
-                bfr[a] = *(const bf16x8 *)(Bs + (64 * wn + 32 * a + l32) * kAggRow + 16 * s + 8 * g);
+        for (int b = 0; b < TB; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+
+    // one K step: the operand tile of step ks is in LDS buffer ks & 1, its mask words in mw
+    auto mma_step = [&](int ks, const uint2 (&mw)[TB]) {
+        const uint16_t *As = smem + (ks & 1) * kAggBuf;
+#pragma unroll
+        for (int s = 0; s < kAggK / 16; ++s) {
+            bf16x8 af[TA];
+#pragma unroll
+            for (int a = 0; a < TA; ++a) af[a] = *(const bf16x8 *)(As + (wn + 32 * a + l32) * kAggRow + 16 * s + 8 * g);
+#pragma unroll
+            for (int b = 0; b < TB; ++b) {
+                const bf16x8 mf = mask_frag(mw[b], s);
+#pragma unroll
+                for (int a = 0; a < TA; ++a)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], mf, acc[a][b], 0, 0, 0);
             }
+        }
+    };
+
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+    for (int u = 0; u < kAggAhead; ++u)
+        if (u < ksteps) load_tile_edge(u, hreg[u], mreg[u]);
+    store_tile(smem, hreg[0]);
+    lds_barrier();
+
+    // main part: groups of kAggAhead steps whose look-ahead loads are all real, as straight-line code (register
+    // set u holds step ks0 + u); the compiler waits for one set at a time and leaves the later ones in flight
+    int ks0 = 0;
+    for (; ks0 + 2 * kAggAhead <= ksteps; ks0 += kAggAhead) {
 #pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
+        for (int u = 0; u < kAggAhead; ++u) {
+            const int ks = ks0 + u;
+            uint2 mw[TB];
+#pragma unroll
+            for (int b = 0; b < TB; ++b) mw[b] = mreg[u][b];
+            load_tile(ks + kAggAhead, hreg[u], mreg[u]);      // set u: its states went to LDS one step ago, its mask words are copied
+            mma_step(ks, mw);
+            store_tile(smem + ((ks + 1) & 1) * kAggBuf, hreg[(u + 1) % kAggAhead]);
+            lds_barrier();                                     // not __syncthreads(): the loads of later steps stay in flight
+        }
+    }
+    // the remaining steps (fewer than 2 kAggAhead), with the loads that are still due issued under a condition
+    for (; ks0 < ksteps; ks0 += kAggAhead) {
+#pragma unroll
+        for (int u = 0; u < kAggAhead; ++u) {
+            const int ks = ks0 + u;
+            if (ks < ksteps) {                                 // uniform over the workgroup
+                uint2 mw[TB];
+#pragma unroll
+                for (int b = 0; b < TB; ++b) mw[b] = mreg[u][b];
+                if (ks + kAggAhead < ksteps) load_tile_edge(ks + kAggAhead, hreg[u], mreg[u]);
+                mma_step(ks, mw);
+                if (ks + 1 < ksteps) store_tile(smem + ((ks + 1) & 1) * kAggBuf, hreg[(u + 1) % kAggAhead]);
+                lds_barrier();
+            }
         }
     }
 
-    // accumulator (a,b) register 4q+r: row i = i0 + 64wm + 32a + 8q + 4g + r, column n = n0 + 64wn + 32b + l32
+    // accumulator (a,b) register 4q+r of lane (l32, g): column n0 + wn + 32a + 8q + 4g + r, query block i0 + wi + 32b + l32.
+    // Staged as [query block][column] so that a query block's 128 columns leave as 16-byte stores; the factor 0.5
+    // undoes the mask value 2.0.
+#pragma unroll
+    for (int a = 0; a < TA; ++a)
+#pragma unroll
+        for (int b = 0; b < TB; ++b)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint2 o;
+                o.x = pack_bf16(0.5f * acc[a][b][4 * q], 0.5f * acc[a][b][4 * q + 1]);
+                o.y = pack_bf16(0.5f * acc[a][b][4 * q + 2], 0.5f * acc[a][b][4 * q + 3]);
+                *(uint2 *)(smem + (wi + 32 * b + l32) * kAggOutRow + wn + 32 * a + 8 * q + 4 * g) = o;
+            }
+    __syncthreads();
     uint16_t *out = Hq + bh * (long)Nqb * kStateElems;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int n = n0 + 64 * wn + 32 * b + l32;
-            if (n >= kStateElems) continue;
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int i = i0 + 64 * wm + 32 * a + 8 * q + 4 * g + r;
-                    if (i < Nqb) out[(long)i * kStateElems + n] = (uint16_t)(pack_bf16(acc[a][b][4 * q + r], 0.f) & 0xFFFFu);
-                }
-        }
+    for (int t = 0; t < BM * 16 / 256; ++t) {
+        const int idx = tid + 256 * t, r = idx >> 4, seg = idx & 15;
+        if (i0 + r < Nqb && n0 + 8 * seg < kStateElems)       // kStateElems % 8 == 0: the segment is in or out as a whole
+            *(uint4 *)(out + (long)(i0 + r) * kStateElems + n0 + 8 * seg) = *(const uint4 *)(smem + r * kAggOutRow + 8 * seg);
+    }
 }
 
-hipError_t launch_aggregate(const int8_t *lab_pad, int lab_pitch, const void *hT, int BH, int Nqb,
+hipError_t launch_aggregate(const uint64_t *mbits, int lab_pitch, const void *hT, int BH, int Nqb,
                             int Nkb, void *Hq, hipStream_t st)
 {
-    dim3 grid((kStateElems + 127) / 128, (Nqb + 127) / 128, BH);
-    aggregate_kernel<<<grid, 256, 0, st>>>(lab_pad, lab_pitch, (const uint16_t *)hT, Nqb, Nkb, (uint16_t *)Hq);
+    constexpr int kNT = (kStateElems + 127) / 128;
+    const int nkw = lab_pitch / 64;
+    if (Nqb <= 192) {    // short heads: 64-query-block tiles waste less of the matrix unit and give more workgroups
+        const int n_it = (Nqb + 63) / 64;
+        const long total = (long)BH * kNT * n_it;
+        aggregate_kernel<2, 1><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint2 *)mbits, nkw, (const uint16_t *)hT, Nqb, Nkb,
+                                                                        n_it, total, (uint16_t *)Hq);
+    } else {
+        const int n_it = (Nqb + 255) / 256;
+        const long total = (long)BH * kNT * n_it;
+        aggregate_kernel<4, 2><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint2 *)mbits, nkw, (const uint16_t *)hT, Nqb, Nkb,
+                                                                        n_it, total, (uint16_t *)Hq);
+    }
     return hipGetLastError();
 }
 

@@ -245,7 +245,7 @@ __device__ void radix_select(const uint64_t (&key)[KPL], int Nkb, int k, uint32_
 // j >= Nkb hold ~0) and writes labels / critical list / compressed softmax for that row.
 template <int KPL>
 __device__ void classify_row_wave(uint64_t (&key)[KPL], long row, int Nkb, int k_c, int k_n, uint32_t *hist,
-                                  int8_t *__restrict__ lab_pad, int lab_pitch, int8_t *__restrict__ lab_dense,
+                                  uint64_t *__restrict__ mbits, int lab_pitch, int8_t *__restrict__ lab_dense,
                                   int32_t *__restrict__ crit_idx, float *__restrict__ Pc, float sm_scale)
 {
     const int lane = threadIdx.x & 63;
@@ -310,7 +310,8 @@ __device__ void classify_row_wave(uint64_t (&key)[KPL], long row, int Nkb, int k
             tie_n += __popcll(b);
         }
         const int8_t lab = selc ? 2 : (seln ? 1 : 0);
-        if (j < lab_pitch) lab_pad[row * lab_pitch + j] = lab;
+        const uint64_t mb = __ballot(lab == 1);                 // marginal mask of this chunk, bit = lane
+        if (lane == 0 && m * 64 < lab_pitch) mbits[row * (lab_pitch >> 6) + m] = mb;
         if (lab_dense && valid) lab_dense[row * Nkb + j] = lab;
         if (crit_idx) {
             const uint64_t b = __ballot(selc);
@@ -323,7 +324,7 @@ __device__ void classify_row_wave(uint64_t (&key)[KPL], long row, int Nkb, int k
 
 template <int KPL>
 __global__ __launch_bounds__(64) void select_kernel(const double *__restrict__ S, int pitch, int Nkb, int k_c, int k_n,
-                                                    int8_t *__restrict__ lab_pad, int lab_pitch,
+                                                    uint64_t *__restrict__ mbits, int lab_pitch,
                                                     int8_t *__restrict__ lab_dense, int32_t *__restrict__ crit_idx,
                                                     float *__restrict__ Pc, double *__restrict__ S_dense, float sm_scale)
 {
@@ -342,7 +343,7 @@ __global__ __launch_bounds__(64) void select_kernel(const double *__restrict__ S
             key[m] = desc_key(v);
         }
     }
-    classify_row_wave<KPL>(key, row, Nkb, k_c, k_n, hist, lab_pad, lab_pitch, lab_dense, crit_idx, Pc, sm_scale);
+    classify_row_wave<KPL>(key, row, Nkb, k_c, k_n, hist, mbits, lab_pitch, lab_dense, crit_idx, Pc, sm_scale);
 }
 
 // Fused classifier for short rows (Nkb <= 64 KPL <= 256): block mean of Q, pooled logits and
@@ -355,7 +356,7 @@ __global__ __launch_bounds__(64) void select_kernel(const double *__restrict__ S
 template <int KPL, bool FP8>
 __global__ __launch_bounds__(256) void classify_fused_kernel(const void *__restrict__ Q, const float *__restrict__ sQ,
                                                              const double *__restrict__ kbar, int N, int bq, int Nqb, int Nkb,
-                                                             int k_c, int k_n, int8_t *__restrict__ lab_pad, int lab_pitch,
+                                                             int k_c, int k_n, uint64_t *__restrict__ mbits, int lab_pitch,
                                                              int8_t *__restrict__ lab_dense, int32_t *__restrict__ crit_idx,
                                                              float *__restrict__ Pc, double *__restrict__ S_dense,
                                                              double *__restrict__ qbar_out, float sm_scale)
@@ -428,7 +429,7 @@ __global__ __launch_bounds__(256) void classify_fused_kernel(const void *__restr
         }
     }
     if (rowok)
-        classify_row_wave<KPL>(key, row, Nkb, k_c, k_n, hist[wave], lab_pad, lab_pitch, lab_dense, crit_idx, Pc, sm_scale);
+        classify_row_wave<KPL>(key, row, Nkb, k_c, k_n, hist[wave], mbits, lab_pitch, lab_dense, crit_idx, Pc, sm_scale);
 }
 
 // ---- workgroup-per-row variant for long rows (Nkb > 256) ------------------------------------
@@ -437,6 +438,7 @@ __global__ __launch_bounds__(256) void classify_fused_kernel(const void *__restr
 // workgroup-wide exclusive scan of per-thread counts.
 
 struct SelShared {
+    uint32_t mb[128];      // marginal mask of the row, one bit per key block
     uint32_t hist[256];
     uint32_t wsum[4];
     uint32_t bc[4];
@@ -501,7 +503,7 @@ __device__ void block_radix_select(const uint64_t (&key)[KPT], int j0, int Nkb, 
 
 template <int KPT>
 __global__ __launch_bounds__(256) void select_block_kernel(const double *__restrict__ S, int pitch, int Nkb, int k_c, int k_n,
-                                                           int8_t *__restrict__ lab_pad, int lab_pitch,
+                                                           uint64_t *__restrict__ mbits, int lab_pitch,
                                                            int8_t *__restrict__ lab_dense, int32_t *__restrict__ crit_idx,
                                                            float *__restrict__ Pc, double *__restrict__ S_dense, float sm_scale)
 {
@@ -510,6 +512,7 @@ __global__ __launch_bounds__(256) void select_block_kernel(const double *__restr
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j0 = tid * KPT;
     const double *s = S + row * pitch;
+    if (tid < 128) sh.mb[tid] = 0;          // ordered before its use by the barriers of the selection below
     uint64_t key[KPT];
     uint64_t kmin = ~0ull, kmax = 0;
 #pragma unroll
@@ -598,11 +601,21 @@ __global__ __launch_bounds__(256) void select_block_kernel(const double *__restr
         lab[m] = selc ? 2 : (seln ? 1 : 0);
         ncrit += selc ? 1u : 0u;
     }
+    uint32_t mine = 0;                                          // marginal bits of this thread's KPT blocks
 #pragma unroll
     for (int m = 0; m < KPT; ++m) {
         const int j = j0 + m;
-        if (j < lab_pitch) lab_pad[row * lab_pitch + j] = lab[m];
+        mine |= (lab[m] == 1 ? 1u : 0u) << m;
         if (lab_dense && j < Nkb) lab_dense[row * Nkb + j] = lab[m];
+    }
+    {   // assemble the row's marginal mask in LDS (cleared at kernel entry) and write it as whole dwords
+        const int w = j0 >> 5, off = j0 & 31;
+        if (mine) {
+            atomicOr(&sh.mb[w], mine << off);
+            if (off + KPT > 32 && (mine >> (32 - off))) atomicOr(&sh.mb[w + 1], mine >> (32 - off));
+        }
+        __syncthreads();
+        if (tid < (lab_pitch >> 5)) ((uint32_t *)mbits)[row * (lab_pitch >> 5) + tid] = sh.mb[tid];
     }
     if (crit_idx) {
         uint32_t pos = block_excl_scan(ncrit, sh, nullptr);
@@ -613,35 +626,35 @@ __global__ __launch_bounds__(256) void select_block_kernel(const double *__restr
 }
 
 template <int KPT>
-static hipError_t launch_select_block_t(const double *S, int pitch, long rows, int Nkb, int k_c, int k_n, int8_t *lab_pad,
+static hipError_t launch_select_block_t(const double *S, int pitch, long rows, int Nkb, int k_c, int k_n, uint64_t *mbits,
                                         int lab_pitch, int8_t *lab_dense, int32_t *crit_idx, float *Pc, double *S_dense,
                                         float sm_scale, hipStream_t st)
 {
-    select_block_kernel<KPT><<<(unsigned)rows, 256, 0, st>>>(S, pitch, Nkb, k_c, k_n, lab_pad, lab_pitch, lab_dense,
+    select_block_kernel<KPT><<<(unsigned)rows, 256, 0, st>>>(S, pitch, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense,
                                                             crit_idx, Pc, S_dense, sm_scale);
     return hipGetLastError();
 }
 
 template <int KPL>
-static hipError_t launch_select_t(const double *S, int pitch, long rows, int Nkb, int k_c, int k_n, int8_t *lab_pad,
+static hipError_t launch_select_t(const double *S, int pitch, long rows, int Nkb, int k_c, int k_n, uint64_t *mbits,
                                   int lab_pitch, int8_t *lab_dense, int32_t *crit_idx, float *Pc, double *S_dense,
                                   float sm_scale, hipStream_t st)
 {
-    select_kernel<KPL><<<(unsigned)rows, 64, 0, st>>>(S, pitch, Nkb, k_c, k_n, lab_pad, lab_pitch, lab_dense, crit_idx,
+    select_kernel<KPL><<<(unsigned)rows, 64, 0, st>>>(S, pitch, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx,
                                                       Pc, S_dense, sm_scale);
     return hipGetLastError();
 }
 
 hipError_t launch_select(const double *S, int pitch, long rows, int Nkb, int k_c, int k_n,
-                         int8_t *lab_pad, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx,
+                         uint64_t *mbits, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx,
                          float *Pc, double *S_dense, float sm_scale, hipStream_t st)
 {
-#define SLA_SEL(K) return launch_select_t<K>(S, pitch, rows, Nkb, k_c, k_n, lab_pad, lab_pitch, lab_dense, crit_idx, Pc, S_dense, sm_scale, st)
+#define SLA_SEL(K) return launch_select_t<K>(S, pitch, rows, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx, Pc, S_dense, sm_scale, st)
     if (lab_pitch <= 64) SLA_SEL(1);
     if (lab_pitch <= 128) SLA_SEL(2);
     if (lab_pitch <= 256) SLA_SEL(4);
 #undef SLA_SEL
-#define SLA_SELB(K) return launch_select_block_t<K>(S, pitch, rows, Nkb, k_c, k_n, lab_pad, lab_pitch, lab_dense, crit_idx, Pc, S_dense, sm_scale, st)
+#define SLA_SELB(K) return launch_select_block_t<K>(S, pitch, rows, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx, Pc, S_dense, sm_scale, st)
     if (lab_pitch <= 512) SLA_SELB(2);
     if (lab_pitch <= 1024) SLA_SELB(4);
     if (lab_pitch <= 1536) SLA_SELB(6);
@@ -655,22 +668,22 @@ hipError_t launch_select(const double *S, int pitch, long rows, int Nkb, int k_c
 
 template <int KPL>
 static hipError_t launch_classify_fused_t(const void *Q, const float *sQ, bool fp8, const double *kbar, int BH, int N, int bq,
-                                          int Nqb, int Nkb, int k_c, int k_n, int8_t *lab_pad, int lab_pitch, int8_t *lab_dense,
+                                          int Nqb, int Nkb, int k_c, int k_n, uint64_t *mbits, int lab_pitch, int8_t *lab_dense,
                                           int32_t *crit_idx, float *Pc, double *S_dense, double *qbar_out, float sm_scale,
                                           hipStream_t st)
 {
     dim3 grid((Nqb + 3) / 4, BH);
-    if (fp8) classify_fused_kernel<KPL, true><<<grid, 256, 0, st>>>(Q, sQ, kbar, N, bq, Nqb, Nkb, k_c, k_n, lab_pad, lab_pitch, lab_dense, crit_idx, Pc, S_dense, qbar_out, sm_scale);
-    else     classify_fused_kernel<KPL, false><<<grid, 256, 0, st>>>(Q, sQ, kbar, N, bq, Nqb, Nkb, k_c, k_n, lab_pad, lab_pitch, lab_dense, crit_idx, Pc, S_dense, qbar_out, sm_scale);
+    if (fp8) classify_fused_kernel<KPL, true><<<grid, 256, 0, st>>>(Q, sQ, kbar, N, bq, Nqb, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx, Pc, S_dense, qbar_out, sm_scale);
+    else     classify_fused_kernel<KPL, false><<<grid, 256, 0, st>>>(Q, sQ, kbar, N, bq, Nqb, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx, Pc, S_dense, qbar_out, sm_scale);
     return hipGetLastError();
 }
 
 hipError_t launch_classify_fused(const void *Q, const float *sQ, bool fp8, const double *kbar, int BH, int N, int bq, int Nkb,
-                                 int k_c, int k_n, int8_t *lab_pad, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx,
+                                 int k_c, int k_n, uint64_t *mbits, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx,
                                  float *Pc, double *S_dense, double *qbar_out, float sm_scale, hipStream_t st)
 {
     const int Nqb = (N + bq - 1) / bq;
-#define SLA_CF(K) return launch_classify_fused_t<K>(Q, sQ, fp8, kbar, BH, N, bq, Nqb, Nkb, k_c, k_n, lab_pad, lab_pitch, lab_dense, crit_idx, Pc, S_dense, qbar_out, sm_scale, st)
+#define SLA_CF(K) return launch_classify_fused_t<K>(Q, sQ, fp8, kbar, BH, N, bq, Nqb, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx, Pc, S_dense, qbar_out, sm_scale, st)
     if (Nkb <= 64) SLA_CF(1);
     if (Nkb <= 128) SLA_CF(2);
     if (Nkb <= 192) SLA_CF(3);
@@ -680,10 +693,10 @@ hipError_t launch_classify_fused(const void *Q, const float *sQ, bool fp8, const
 }
 
 // --------------------------------------------------------------------------- labels_prepare
-// dense labels -> padded copy + ascending critical index list per row (one wavefront per row;
+// dense labels -> marginal bit mask + ascending critical index list per row (one wavefront per row;
 // slots beyond the number of critical blocks found are set to -1, surplus ones are dropped).
 __global__ __launch_bounds__(64) void labels_prepare_kernel(const int8_t *__restrict__ lab_dense, int Nkb, int k_c,
-                                                            int8_t *__restrict__ lab_pad, int lab_pitch,
+                                                            uint64_t *__restrict__ mbits, int lab_pitch,
                                                             int32_t *__restrict__ crit_idx)
 {
     const long row = blockIdx.x;
@@ -693,7 +706,8 @@ __global__ __launch_bounds__(64) void labels_prepare_kernel(const int8_t *__rest
     for (int j0 = 0; j0 < lab_pitch; j0 += 64) {
         const int j = j0 + lane;
         const int8_t v = j < Nkb ? lab_dense[row * Nkb + j] : (int8_t)0;
-        lab_pad[row * lab_pitch + j] = v;
+        const uint64_t mb = __ballot(v == 1);
+        if (lane == 0) mbits[row * (lab_pitch >> 6) + (j0 >> 6)] = mb;
         const uint64_t b = __ballot(v == 2);
         const int pos = n + __popcll(b & lt);
         if (v == 2 && pos < k_c) crit_idx[row * k_c + pos] = j;
@@ -703,9 +717,9 @@ __global__ __launch_bounds__(64) void labels_prepare_kernel(const int8_t *__rest
 }
 
 hipError_t launch_labels_prepare(const int8_t *lab_dense, long rows, int Nkb, int k_c,
-                                 int8_t *lab_pad, int lab_pitch, int32_t *crit_idx, hipStream_t st)
+                                 uint64_t *mbits, int lab_pitch, int32_t *crit_idx, hipStream_t st)
 {
-    labels_prepare_kernel<<<(unsigned)rows, 64, 0, st>>>(lab_dense, Nkb, k_c, lab_pad, lab_pitch, crit_idx);
+    labels_prepare_kernel<<<(unsigned)rows, 64, 0, st>>>(lab_dense, Nkb, k_c, mbits, lab_pitch, crit_idx);
     return hipGetLastError();
 }
 

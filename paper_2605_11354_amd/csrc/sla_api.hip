@@ -82,7 +82,7 @@ sla_status_t make_plan(const sla_params_t *p, Plan &pl)
     pl.off_qbar = carve(BH * pl.Nqb * 64 * sizeof(double));
     pl.off_kbar = carve(BH * pl.Nkb * 64 * sizeof(double));
     pl.off_scores = carve(BH * pl.Nqb * pl.s_pitch * sizeof(double));
-    pl.off_lab = carve(BH * pl.Nqb * pl.lab_pitch);
+    pl.off_lab = carve(BH * pl.Nqb * (size_t)(pl.lab_pitch / 8));   // marginal masks, one bit per (query block, key block)
     pl.off_crit = carve(BH * pl.Nqb * (size_t)(pl.k_c > 0 ? pl.k_c : 1) * sizeof(int32_t));
     pl.off_hT = carve(BH * pl.Nkb * sla::kStateElems * 2);
     pl.off_Hq = carve(BH * pl.Nqb * sla::kStateElems * 2);
@@ -133,7 +133,7 @@ sla_status_t run_classify(const sla_params_t *p, const Plan &pl, const void *Q, 
     }
     SLA_HIP(mark(2));
     if (fused) {
-        SLA_HIP(sla::launch_classify_fused(Q, sQ, pl.fp8, kbar, pl.BH, p->N, p->bq, pl.Nkb, pl.k_c, pl.k_n, at<int8_t>(ws, pl.off_lab),
+        SLA_HIP(sla::launch_classify_fused(Q, sQ, pl.fp8, kbar, pl.BH, p->N, p->bq, pl.Nkb, pl.k_c, pl.k_n, at<uint64_t>(ws, pl.off_lab),
                                            pl.lab_pitch, labels, pl.k_c > 0 ? crit : nullptr, Pc, scores_out,
                                            qbar_out ? qbar_out : nullptr, pl.sm_scale, st));
         SLA_HIP(mark(3));
@@ -142,7 +142,7 @@ sla_status_t run_classify(const sla_params_t *p, const Plan &pl, const void *Q, 
     SLA_HIP(sla::launch_scores(qbar, kbar, pl.BH, pl.Nqb, pl.Nkb, pl.s_pitch, at<double>(ws, pl.off_scores), st));
     SLA_HIP(mark(3));
     SLA_HIP(sla::launch_select(at<double>(ws, pl.off_scores), pl.s_pitch, (long)pl.BH * pl.Nqb, pl.Nkb, pl.k_c, pl.k_n,
-                               at<int8_t>(ws, pl.off_lab), pl.lab_pitch, labels, pl.k_c > 0 ? crit : nullptr, Pc,
+                               at<uint64_t>(ws, pl.off_lab), pl.lab_pitch, labels, pl.k_c > 0 ? crit : nullptr, Pc,
                                scores_out, pl.sm_scale, st));
     return SLA_OK;
 }
@@ -227,8 +227,8 @@ sla_status_t sla_marginal_aggregate(const sla_params_t *p, const int8_t *labels,
     if ((s = check_ws(pl, workspace, workspace_bytes)) != SLA_OK) return s;
     hipStream_t st = (hipStream_t)stream;
     SLA_HIP(sla::launch_labels_prepare(labels, (long)pl.BH * pl.Nqb, pl.Nkb, pl.k_c > 0 ? pl.k_c : 1,
-                                       at<int8_t>(workspace, pl.off_lab), pl.lab_pitch, at<int32_t>(workspace, pl.off_crit), st));
-    SLA_HIP(sla::launch_aggregate(at<int8_t>(workspace, pl.off_lab), pl.lab_pitch, hT, pl.BH, pl.Nqb, pl.Nkb, Hq, st));
+                                       at<uint64_t>(workspace, pl.off_lab), pl.lab_pitch, at<int32_t>(workspace, pl.off_crit), st));
+    SLA_HIP(sla::launch_aggregate(at<uint64_t>(workspace, pl.off_lab), pl.lab_pitch, hT, pl.BH, pl.Nqb, pl.Nkb, Hq, st));
     return SLA_OK;
 }
 
@@ -248,7 +248,7 @@ sla_status_t sla_sparse_combine(const sla_params_t *p, const void *Q, const void
     if ((s = check_ws(pl, workspace, workspace_bytes)) != SLA_OK) return s;
     hipStream_t st = (hipStream_t)stream;
     SLA_HIP(sla::launch_labels_prepare(labels, (long)pl.BH * pl.Nqb, pl.Nkb, pl.k_c > 0 ? pl.k_c : 1,
-                                       at<int8_t>(workspace, pl.off_lab), pl.lab_pitch, at<int32_t>(workspace, pl.off_crit), st));
+                                       at<uint64_t>(workspace, pl.off_lab), pl.lab_pitch, at<int32_t>(workspace, pl.off_crit), st));
     if (Hq) SLA_HIP(sla::launch_transpose_w(W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
     // the attention kernel reads V as transposed tiles; the states pass produces them (its states go to the workspace)
     SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp), nullptr, st));
@@ -278,7 +278,7 @@ static sla_status_t forward_impl(const sla_params_t *p, const void *Q, const voi
                                at<double>(workspace, pl.off_kbar), st));
     if ((s = run_classify(p, pl, Q, K, sQ, sK, labels, nullptr, nullptr, nullptr, nullptr, nullptr, workspace, st, ev, true)) != SLA_OK) return s;
     SLA_HIP(mark(4));
-    SLA_HIP(sla::launch_aggregate(at<int8_t>(workspace, pl.off_lab), pl.lab_pitch, at<void>(workspace, pl.off_hT), pl.BH, pl.Nqb,
+    SLA_HIP(sla::launch_aggregate(at<uint64_t>(workspace, pl.off_lab), pl.lab_pitch, at<void>(workspace, pl.off_hT), pl.BH, pl.Nqb,
                                   pl.Nkb, at<void>(workspace, pl.off_Hq), st));
     SLA_HIP(mark(5));
     SLA_HIP(sla::launch_transpose_w(W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));

@@ -64,6 +64,14 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Workgroup barrier that orders LDS traffic only: the wave waits for its own LDS operations and then
+// for the other waves, but not for global loads still in flight to registers, which __syncthreads()
+// would drain (its fence covers global memory) and with them any prefetch distance beyond one step.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // blockIdx -> work item so that each of the 8 XCDs (workgroups are dealt round-robin to them)
 // walks a contiguous range of items and therefore keeps one head's K/V in its own L2.
 __device__ __forceinline__ long xcd_remap(long bid, long total)

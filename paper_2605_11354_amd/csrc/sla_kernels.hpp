@@ -14,22 +14,22 @@ hipError_t launch_pool(const void *X, const float *scales, bool fp8, int BH, int
 hipError_t launch_scores(const double *qbar, const double *kbar, int BH, int Nqb, int Nkb,
                          int pitch, double *S, hipStream_t st);
 
-// three-way classifier on every score row.  lab_pad has row pitch lab_pitch (multiple of 64,
-// pad entries written 0); lab_dense ([.,Nkb]), crit_idx ([.,k_c]), Pc ([.,Nkb]), S_dense
-// ([.,Nkb]) are optional.
+// three-way classifier on every score row.  mbits receives the marginal mask of every row, one bit
+// per key block (bit j%64 of word j/64, lab_pitch/64 words per row, lab_pitch a multiple of 64, pad
+// bits 0); lab_dense ([.,Nkb]), crit_idx ([.,k_c]), Pc ([.,Nkb]), S_dense ([.,Nkb]) are optional.
 hipError_t launch_select(const double *S, int pitch, long rows, int Nkb, int k_c, int k_n,
-                         int8_t *lab_pad, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx,
+                         uint64_t *mbits, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx,
                          float *Pc, double *S_dense, float sm_scale, hipStream_t st);
 
 // short rows (Nkb <= 256): block mean of Q + pooled logits + classifier in one launch; kbar holds the
 // block means of K.  Outputs as launch_select; qbar_out (optional) receives the block means of Q.
 hipError_t launch_classify_fused(const void *Q, const float *sQ, bool fp8, const double *kbar, int BH, int N, int bq, int Nkb,
-                                 int k_c, int k_n, int8_t *lab_pad, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx,
+                                 int k_c, int k_n, uint64_t *mbits, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx,
                                  float *Pc, double *S_dense, double *qbar_out, float sm_scale, hipStream_t st);
 
-// dense labels -> padded labels + critical index lists (unfilled slots = -1)
+// dense labels -> marginal masks + critical index lists (unfilled slots = -1)
 hipError_t launch_labels_prepare(const int8_t *lab_dense, long rows, int Nkb, int k_c,
-                                 int8_t *lab_pad, int lab_pitch, int32_t *crit_idx, hipStream_t st);
+                                 uint64_t *mbits, int lab_pitch, int32_t *crit_idx, hipStream_t st);
 
 // per-key-block states: hT [BH,Nkb,65,64] bf16; optionally also Vp [BH,Nkb,64,64] bf16, the
 // transposed, key-permuted V tiles the attention kernel reads, and kbar [BH,Nkb,64] fp64, the
@@ -38,7 +38,7 @@ hipError_t launch_states(const void *K, const void *V, const float *sK, const fl
                          int BH, int N, void *hT, void *Vp, double *kbar, hipStream_t st);
 
 // Hq[bh][i][:] = sum over j with lab_pad[bh][i][j] == 1 of hT[bh][j][:]   (bf16 MFMA, fp32 accumulate)
-hipError_t launch_aggregate(const int8_t *lab_pad, int lab_pitch, const void *hT, int BH, int Nqb,
+hipError_t launch_aggregate(const uint64_t *mbits, int lab_pitch, const void *hT, int BH, int Nqb,
                             int Nkb, void *Hq, hipStream_t st);
 
 // W [nW,64,64] bf16 -> WT[nW][e_out][e_in]

@@ -24,7 +24,7 @@ constexpr int kWavesPerWG = 2;
 // 4-byte (e4m3) pieces of four channels arranged for the register transpose.
 template <bool FP8>
 struct BlockRegs {
-    uint4 k[FP8 ? 4 : 8];
+    uint32_t k[FP8 ? 16 : 32];    // plain dwords: arrays of vectors are not reliably kept in registers
     uint32_t v[FP8 ? 16 : 32];
 };
 
@@ -40,7 +40,8 @@ __device__ __forceinline__ void load_block(BlockRegs<FP8> &r, const void *K, con
 #pragma unroll
         for (int x = 0; x < 8; ++x) {
             const int c = lane + 64 * x, t = min(c >> 3, last), col = (c & 7) * 8;
-            r.k[x] = *(const uint4 *)(Kg + (size_t)t * kD + col);
+            const uint4 w = *(const uint4 *)(Kg + (size_t)t * kD + col);
+            r.k[4 * x] = w.x; r.k[4 * x + 1] = w.y; r.k[4 * x + 2] = w.z; r.k[4 * x + 3] = w.w;
         }
         // V: unit u = lane + 64 x is 4 channels (quad u%16) x 8 consecutive tokens (group u/16)
 #pragma unroll
@@ -60,7 +61,8 @@ __device__ __forceinline__ void load_block(BlockRegs<FP8> &r, const void *K, con
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
             const int c = lane + 64 * x, t = min(c >> 2, last), col = (c & 3) * 16;
-            r.k[x] = *(const uint4 *)(Kg + (size_t)t * kD + col);
+            const uint4 w = *(const uint4 *)(Kg + (size_t)t * kD + col);
+            r.k[4 * x] = w.x; r.k[4 * x + 1] = w.y; r.k[4 * x + 2] = w.z; r.k[4 * x + 3] = w.w;
         }
         // V: unit u = lane + 64 x is 4 channels (quad u%16) x 8 consecutive tokens (group u/16)
 #pragma unroll
@@ -94,7 +96,7 @@ __device__ __forceinline__ void stage_block(const BlockRegs<FP8> &r, uint16_t *K
 #pragma unroll
         for (int x = 0; x < 8; ++x) {
             const int c = lane + 64 * x, t = c >> 3, col = (c & 7) * 8;
-            *(uint4 *)(Ks + t * kLdsRow + col) = r.k[x];
+            *(uint4 *)(Ks + t * kLdsRow + col) = make_uint4(r.k[4 * x], r.k[4 * x + 1], r.k[4 * x + 2], r.k[4 * x + 3]);
         }
 #pragma unroll
         for (int x = 0; x < 2; ++x) {
@@ -119,8 +121,8 @@ __device__ __forceinline__ void stage_block(const BlockRegs<FP8> &r, uint16_t *K
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
             const int c = lane + 64 * x, t = c >> 2, col = (c & 3) * 16;
-            *(uint4 *)(Ks + t * kLdsRow + col) = e4m3x8_to_bf16x8(r.k[x].x, r.k[x].y);
-            *(uint4 *)(Ks + t * kLdsRow + col + 8) = e4m3x8_to_bf16x8(r.k[x].z, r.k[x].w);
+            *(uint4 *)(Ks + t * kLdsRow + col) = e4m3x8_to_bf16x8(r.k[4 * x], r.k[4 * x + 1]);
+            *(uint4 *)(Ks + t * kLdsRow + col + 8) = e4m3x8_to_bf16x8(r.k[4 * x + 2], r.k[4 * x + 3]);
         }
 #pragma unroll
         for (int x = 0; x < 2; ++x) {

@@ -433,7 +433,7 @@ __global__ __launch_bounds__(256) void classify_fused_kernel(const void *__restr
 }
 
 // ---- workgroup-per-row variant for long rows (Nkb > 256) ------------------------------------
-// 256 threads, thread t owns the KPT consecutive blocks j = t*KPT .. t*KPT+KPT-1, so index order
+// NT threads (128 or 256), thread t owns the KPT consecutive blocks j = t*KPT .. t*KPT+KPT-1, so index order
 // is (thread, slot) order and every ordered step (tie ranks, index-list compaction) is one
 // workgroup-wide exclusive scan of per-thread counts.
 
@@ -445,7 +445,8 @@ struct SelShared {
     uint64_t red[8];
 };
 
-// exclusive prefix over the 256 threads of per-thread value v; *total receives the sum
+// exclusive prefix over the NT threads of per-thread value v; *total receives the sum
+template <int NT>
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, SelShared &sh, uint32_t *total)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -460,20 +461,22 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, SelShared &sh, u
     __syncthreads();
     uint32_t base = 0, tot = 0;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) { const uint32_t x = sh.wsum[w]; if (w < wave) base += x; tot += x; }
+    for (int w = 0; w < NT / 64; ++w) { const uint32_t x = sh.wsum[w]; if (w < wave) base += x; tot += x; }
     if (total) *total = tot;
     return base + incl - v;
 }
 
-template <int KPT>
+template <int KPT, int NT>
 __device__ void block_radix_select(const uint64_t (&key)[KPT], int j0, int Nkb, int k, SelShared &sh, uint64_t &T, int &r)
 {
+    constexpr int BPT = 256 / NT;                 // histogram bins per thread
     const int tid = threadIdx.x;
     uint64_t prefix = 0;
     int kk = k, shift = 56, nb = 0;
     for (;;) {
         __syncthreads();
-        sh.hist[tid] = 0;
+#pragma unroll
+        for (int b = 0; b < BPT; ++b) sh.hist[tid * BPT + b] = 0;
         __syncthreads();
 #pragma unroll
         for (int m = 0; m < KPT; ++m) {
@@ -481,9 +484,17 @@ __device__ void block_radix_select(const uint64_t (&key)[KPT], int j0, int Nkb, 
             if (cand) atomicAdd(&sh.hist[(uint32_t)(key[m] >> shift) & 255u], 1u);
         }
         __syncthreads();
-        const uint32_t c = sh.hist[tid];
-        const uint32_t excl = block_excl_scan(c, sh, nullptr);
-        if (excl < (uint32_t)kk && (uint32_t)kk <= excl + c) { sh.bc[0] = tid; sh.bc[1] = excl; sh.bc[2] = c; }
+        uint32_t c[BPT], mine = 0;
+#pragma unroll
+        for (int b = 0; b < BPT; ++b) { c[b] = sh.hist[tid * BPT + b]; mine += c[b]; }
+        uint32_t before = block_excl_scan<NT>(mine, sh, nullptr);
+        if (before < (uint32_t)kk && (uint32_t)kk <= before + mine) {       // exactly one thread
+#pragma unroll
+            for (int b = 0; b < BPT; ++b) {
+                if (before + c[b] >= (uint32_t)kk) { sh.bc[0] = tid * BPT + b; sh.bc[1] = before; sh.bc[2] = c[b]; break; }
+                before += c[b];
+            }
+        }
         __syncthreads();
         prefix = (prefix << 8) | sh.bc[0];
         kk -= (int)sh.bc[1];
@@ -501,8 +512,8 @@ __device__ void block_radix_select(const uint64_t (&key)[KPT], int j0, int Nkb, 
     r = 1;
 }
 
-template <int KPT>
-__global__ __launch_bounds__(256) void select_block_kernel(const double *__restrict__ S, int pitch, int Nkb, int k_c, int k_n,
+template <int KPT, int NT>
+__global__ __launch_bounds__(NT) void select_block_kernel(const double *__restrict__ S, int pitch, int Nkb, int k_c, int k_n,
                                                            uint64_t *__restrict__ mbits, int lab_pitch,
                                                            int8_t *__restrict__ lab_dense, int32_t *__restrict__ crit_idx,
                                                            float *__restrict__ Pc, double *__restrict__ S_dense, float sm_scale)
@@ -512,7 +523,7 @@ __global__ __launch_bounds__(256) void select_block_kernel(const double *__restr
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j0 = tid * KPT;
     const double *s = S + row * pitch;
-    if (tid < 128) sh.mb[tid] = 0;          // ordered before its use by the barriers of the selection below
+    if (tid < 128) sh.mb[tid] = 0;          // ordered before its use by the barriers of the selection below (NT >= 128)
     uint64_t key[KPT];
     uint64_t kmin = ~0ull, kmax = 0;
 #pragma unroll
@@ -532,7 +543,7 @@ __global__ __launch_bounds__(256) void select_block_kernel(const double *__restr
     if (lane == 0) { sh.red[wave] = kmin; sh.red[4 + wave] = kmax; }
     __syncthreads();
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NT / 64; ++w) {
         kmin = sh.red[w] < kmin ? sh.red[w] : kmin;
         kmax = sh.red[4 + w] > kmax ? sh.red[4 + w] : kmax;
     }
@@ -550,7 +561,10 @@ __global__ __launch_bounds__(256) void select_block_kernel(const double *__restr
         float *fs = (float *)sh.wsum;
         if (lane == 0) fs[wave] = sum;
         __syncthreads();
-        const float inv = 1.f / (fs[0] + fs[1] + fs[2] + fs[3]);
+        float tot = 0.f;
+#pragma unroll
+        for (int w = 0; w < NT / 64; ++w) tot += fs[w];
+        const float inv = 1.f / tot;
         __syncthreads();
 #pragma unroll
         for (int m = 0; m < KPT; ++m)
@@ -566,8 +580,8 @@ __global__ __launch_bounds__(256) void select_block_kernel(const double *__restr
     uint64_t Tc = 0, Tn = 0;
     int rc = 0, rn = 0;
     const bool do_c = k_c > 0 && k_c < Nkb, do_n = k_keep > 0 && k_keep < Nkb;
-    if (do_c) block_radix_select<KPT>(key, j0, Nkb, k_c, sh, Tc, rc);
-    if (do_n) block_radix_select<KPT>(key, j0, Nkb, k_keep, sh, Tn, rn);
+    if (do_c) block_radix_select<KPT, NT>(key, j0, Nkb, k_c, sh, Tc, rc);
+    if (do_n) block_radix_select<KPT, NT>(key, j0, Nkb, k_keep, sh, Tn, rn);
 
     // ranks among exact ties of each threshold, in index order
     uint32_t eqc = 0, eqn = 0;
@@ -577,8 +591,8 @@ __global__ __launch_bounds__(256) void select_block_kernel(const double *__restr
         eqc += (do_c && valid && key[m] == Tc) ? 1u : 0u;
         eqn += (do_n && valid && key[m] == Tn) ? 1u : 0u;
     }
-    uint32_t tie_c = do_c ? block_excl_scan(eqc, sh, nullptr) : 0u;
-    uint32_t tie_n = do_n ? block_excl_scan(eqn, sh, nullptr) : 0u;
+    uint32_t tie_c = do_c ? block_excl_scan<NT>(eqc, sh, nullptr) : 0u;
+    uint32_t tie_n = do_n ? block_excl_scan<NT>(eqn, sh, nullptr) : 0u;
 
     int8_t lab[KPT];
     uint32_t ncrit = 0;
@@ -618,20 +632,20 @@ __global__ __launch_bounds__(256) void select_block_kernel(const double *__restr
         if (tid < (lab_pitch >> 5)) ((uint32_t *)mbits)[row * (lab_pitch >> 5) + tid] = sh.mb[tid];
     }
     if (crit_idx) {
-        uint32_t pos = block_excl_scan(ncrit, sh, nullptr);
+        uint32_t pos = block_excl_scan<NT>(ncrit, sh, nullptr);
 #pragma unroll
         for (int m = 0; m < KPT; ++m)
             if (lab[m] == 2) { if ((int)pos < k_c) crit_idx[row * k_c + pos] = j0 + m; ++pos; }
     }
 }
 
-template <int KPT>
+template <int KPT, int NT>
 static hipError_t launch_select_block_t(const double *S, int pitch, long rows, int Nkb, int k_c, int k_n, uint64_t *mbits,
                                         int lab_pitch, int8_t *lab_dense, int32_t *crit_idx, float *Pc, double *S_dense,
                                         float sm_scale, hipStream_t st)
 {
-    select_block_kernel<KPT><<<(unsigned)rows, 256, 0, st>>>(S, pitch, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense,
-                                                            crit_idx, Pc, S_dense, sm_scale);
+    select_block_kernel<KPT, NT><<<(unsigned)rows, NT, 0, st>>>(S, pitch, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense,
+                                                                crit_idx, Pc, S_dense, sm_scale);
     return hipGetLastError();
 }
 
@@ -653,11 +667,14 @@ hipError_t launch_select(const double *S, int pitch, long rows, int Nkb, int k_c
     if (lab_pitch <= 64) SLA_SEL(1);
     if (lab_pitch <= 128) SLA_SEL(2);
     if (lab_pitch <= 256) SLA_SEL(4);
+    // one wave per row as long as the row's keys fit its registers (up to 24 per lane): no workgroup barriers
+    // and 32 rows in flight per CU; 36 keys per lane spill, so longer rows take a workgroup per row
+    if (lab_pitch <= 512) SLA_SEL(8);
+    if (lab_pitch <= 768) SLA_SEL(12);
+    if (lab_pitch <= 1024) SLA_SEL(16);
+    if (lab_pitch <= 1536) SLA_SEL(24);
 #undef SLA_SEL
-#define SLA_SELB(K) return launch_select_block_t<K>(S, pitch, rows, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx, Pc, S_dense, sm_scale, st)
-    if (lab_pitch <= 512) SLA_SELB(2);
-    if (lab_pitch <= 1024) SLA_SELB(4);
-    if (lab_pitch <= 1536) SLA_SELB(6);
+#define SLA_SELB(K) return launch_select_block_t<K, 256>(S, pitch, rows, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx, Pc, S_dense, sm_scale, st)
     if (lab_pitch <= 2048) SLA_SELB(8);
     if (lab_pitch <= 2560) SLA_SELB(10);
     if (lab_pitch <= 3072) SLA_SELB(12);

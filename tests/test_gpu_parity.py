@@ -78,7 +78,7 @@ def test_classifier_duplicate_blocks_tie_exactly(oracle):
         assert np.array_equal(got["labels"], ref["labels"])
 
 
-@pytest.mark.parametrize("nkb,kc,kn", [(300, 15, 200), (300, 1, 299), (300, 299, 1), (300, 0, 150), (700, 35, 560), (1100, 3, 1000)])
+@pytest.mark.parametrize("nkb,kc,kn", [(300, 15, 200), (300, 1, 299), (300, 299, 1), (300, 0, 150), (700, 35, 560), (1000, 50, 800), (1100, 3, 1000), (1700, 40, 1500), (2500, 100, 2000)])
 def test_classifier_long_rows(oracle, nkb, kc, kn):
     """Rows longer than 256 key blocks take the workgroup-per-row classifier; include exact ties."""
     cfg = C0.with_(H=1, N=nkb * 64 - 17, n_clusters=256)

@@ -100,7 +100,7 @@ sla_status_t sla_forward(const sla_params_t *p,
  * 256 key blocks take the fused classifier, reported as "scores"; "pool_q" and "select" are
  * then empty (their figure is the cost of an event pair).
  */
-#define SLA_NUM_STAGES 7
+#define SLA_NUM_STAGES 6
 sla_status_t sla_forward_profiled(const sla_params_t *p,
                                   const void *Q, const void *K, const void *V,
                                   const float *sQ, const float *sK, const float *sV,

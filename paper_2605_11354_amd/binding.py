@@ -21,7 +21,7 @@ STATE_ROWS = 65          # rows of one block state: 64 rows of h^T and one row o
 EXPORTS = ["sla_resolve_counts", "sla_workspace_bytes", "sla_forward", "sla_pool_classify", "sla_linear_states",
            "sla_marginal_aggregate", "sla_sparse_combine", "sla_forward_profiled", "sla_strerror", "sla_last_error",
            "sla_stage_name"]
-NUM_STAGES = 7
+NUM_STAGES = 6
 
 
 class SlaParams(C.Structure):

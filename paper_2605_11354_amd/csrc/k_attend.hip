@@ -503,18 +503,10 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
     }
 }
 
-// W [nW][e_in][e_out] -> WT [nW][e_out][slot], slot 16s + 8g + 4a + b holding e_in = 16s + 8a + 4g + b
-// (transposed, and with the same permutation of the contraction index as the V^T tiles, so the
-// projection product reads it with the fragment addressing of the attention loop)
+// W [nW][e_in][e_out] -> WT [nW][e_out][slot] as its own launch (the whole forward folds this into the states pass)
 __global__ __launch_bounds__(256) void transpose_w_kernel(const uint16_t *__restrict__ W, uint16_t *__restrict__ WT)
 {
-    const uint16_t *w = W + (size_t)blockIdx.x * kD * kD;
-    uint16_t *o = WT + (size_t)blockIdx.x * kD * kD;
-    for (int idx = threadIdx.x; idx < kD * kD; idx += 256) {
-        const int eo = idx >> 6, slot = idx & 63;
-        const int ei = (slot & 0x33) | ((slot & 4) << 1) | ((slot & 8) >> 1);      // swap bits 2 and 3
-        o[idx] = w[ei * kD + eo];
-    }
+    transpose_w_tile(W + (size_t)blockIdx.x * kD * kD, WT + (size_t)blockIdx.x * kD * kD, 256);
 }
 
 hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st)

@@ -150,8 +150,14 @@ __global__ __launch_bounds__(64 * kWavesPerWG) __attribute__((amdgpu_waves_per_e
                                                                   const float *__restrict__ sK, const float *__restrict__ sV,
                                                                   int N, int Nkb, long nblocks, int per_wave,
                                                                   uint16_t *__restrict__ hT, uint16_t *__restrict__ Vp,
-                                                                  double *__restrict__ kbar)
+                                                                  double *__restrict__ kbar, unsigned state_wgs,
+                                                                  const uint16_t *__restrict__ W, uint16_t *__restrict__ WT)
 {
+    if (blockIdx.x >= state_wgs) {     // workgroups past the states grid each lay out one projection matrix for the attention kernel
+        const size_t m = (size_t)(blockIdx.x - state_wgs) * kD * kD;
+        transpose_w_tile(W + m, WT + m, 64 * kWavesPerWG);
+        return;
+    }
     __shared__ __attribute__((aligned(16))) uint16_t lds[kWavesPerWG][2][64 * kLdsRow];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const long first = ((long)blockIdx.x * kWavesPerWG + wave) * per_wave;
@@ -293,7 +299,7 @@ __global__ __launch_bounds__(64 * kWavesPerWG) __attribute__((amdgpu_waves_per_e
 }
 
 hipError_t launch_states(const void *K, const void *V, const float *sK, const float *sV, bool fp8,
-                         int BH, int N, void *hT, void *Vp, double *kbar, hipStream_t st)
+                         int BH, int N, void *hT, void *Vp, double *kbar, const void *W, int nW, void *WT, hipStream_t st)
 {
     const int Nkb = (N + kBK - 1) / kBK;
     const long nblocks = (long)BH * Nkb;
@@ -302,8 +308,9 @@ hipError_t launch_states(const void *K, const void *V, const float *sK, const fl
     const int per_wave = (int)((nblocks + target_waves - 1) / target_waves);
     const long waves = (nblocks + per_wave - 1) / per_wave;
     const unsigned grid = (unsigned)((waves + kWavesPerWG - 1) / kWavesPerWG);
-    if (fp8) states_kernel<true><<<grid, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, kbar);
-    else     states_kernel<false><<<grid, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, kbar);
+    const unsigned extra = W != nullptr ? (unsigned)nW : 0u;
+    if (fp8) states_kernel<true><<<grid + extra, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, kbar, grid, (const uint16_t *)W, (uint16_t *)WT);
+    else     states_kernel<false><<<grid + extra, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, kbar, grid, (const uint16_t *)W, (uint16_t *)WT);
     return hipGetLastError();
 }
 

@@ -211,7 +211,7 @@ sla_status_t sla_linear_states(const sla_params_t *p, const void *K, const void 
     if (pl.empty) return SLA_OK;
     SLA_REQ_PTR(K); SLA_REQ_PTR(V); SLA_REQ_PTR(hT);
     if (pl.fp8) { SLA_REQ_PTR(sK); SLA_REQ_PTR(sV); }
-    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, hT, nullptr, nullptr, (hipStream_t)stream));
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, hT, nullptr, nullptr, nullptr, 0, nullptr, (hipStream_t)stream));
     return SLA_OK;
 }
 
@@ -251,7 +251,7 @@ sla_status_t sla_sparse_combine(const sla_params_t *p, const void *Q, const void
                                        at<uint64_t>(workspace, pl.off_lab), pl.lab_pitch, at<int32_t>(workspace, pl.off_crit), st));
     if (Hq) SLA_HIP(sla::launch_transpose_w(W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
     // the attention kernel reads V as transposed tiles; the states pass produces them (its states go to the workspace)
-    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp), nullptr, st));
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp), nullptr, nullptr, 0, nullptr, st));
     SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), sQ, sK, sV, pl.fp8, at<int32_t>(workspace, pl.off_crit), pl.k_c, Hq,
                                at<void>(workspace, pl.off_WT), p->proj_per_head, p->B, p->H, p->N, p->bq, pl.sm_scale, O, st));
     return SLA_OK;
@@ -273,20 +273,19 @@ static sla_status_t forward_impl(const sla_params_t *p, const void *Q, const voi
     if (launched) *launched = true;
     SLA_HIP(mark(0));
     if (pl.Nkb > 256) SLA_HIP(sla::launch_pool(Q, sQ, pl.fp8, pl.BH, p->N, p->bq, at<double>(workspace, pl.off_qbar), st));
-    SLA_HIP(mark(1));     // states + V^T tiles + block means of K: the one pass over K and V besides the attention kernel
+    SLA_HIP(mark(1));     // states + V^T tiles + block means of K: the one pass over K and V besides the attention kernel;
+                          // a few extra workgroups of the same launch lay out W_proj for the attention epilogue
     SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp),
-                               at<double>(workspace, pl.off_kbar), st));
+                               at<double>(workspace, pl.off_kbar), W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
     if ((s = run_classify(p, pl, Q, K, sQ, sK, labels, nullptr, nullptr, nullptr, nullptr, nullptr, workspace, st, ev, true)) != SLA_OK) return s;
     SLA_HIP(mark(4));
     SLA_HIP(sla::launch_aggregate(at<uint64_t>(workspace, pl.off_lab), pl.lab_pitch, at<void>(workspace, pl.off_hT), pl.BH, pl.Nqb,
                                   pl.Nkb, at<void>(workspace, pl.off_Hq), st));
     SLA_HIP(mark(5));
-    SLA_HIP(sla::launch_transpose_w(W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
-    SLA_HIP(mark(6));
     SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), sQ, sK, sV, pl.fp8, at<int32_t>(workspace, pl.off_crit), pl.k_c,
                                at<void>(workspace, pl.off_Hq), at<void>(workspace, pl.off_WT), p->proj_per_head, p->B, p->H,
                                p->N, p->bq, pl.sm_scale, O, st));
-    SLA_HIP(mark(7));
+    SLA_HIP(mark(6));
     return SLA_OK;
 }
 
@@ -299,7 +298,7 @@ sla_status_t sla_forward(const sla_params_t *p, const void *Q, const void *K, co
 
 const char *sla_stage_name(int stage)
 {
-    static const char *names[SLA_NUM_STAGES] = {"pool_q", "states", "scores", "select", "aggregate", "transpose_w", "attend"};
+    static const char *names[SLA_NUM_STAGES] = {"pool_q", "states", "scores", "select", "aggregate", "attend"};
     return stage >= 0 && stage < SLA_NUM_STAGES ? names[stage] : "?";
 }
 

@@ -72,6 +72,19 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// One projection matrix W [e_in][e_out] -> WT [e_out][slot], slot 16s + 8g + 4a + b holding e_in = 16s + 8a + 4g + b
+// (transposed, and with the same permutation of the contraction index as the V^T tiles, so the projection
+// product of the attention kernel reads it with the fragment addressing of its main loop).  One workgroup of
+// nthreads threads per matrix.
+__device__ __forceinline__ void transpose_w_tile(const uint16_t *__restrict__ w, uint16_t *__restrict__ o, int nthreads)
+{
+    for (int idx = threadIdx.x; idx < kD * kD; idx += nthreads) {
+        const int eo = idx >> 6, slot = idx & 63;
+        const int ei = (slot & 0x33) | ((slot & 4) << 1) | ((slot & 8) >> 1);      // swap bits 2 and 3
+        o[idx] = w[ei * kD + eo];
+    }
+}
+
 // blockIdx -> work item so that each of the 8 XCDs (workgroups are dealt round-robin to them)
 // walks a contiguous range of items and therefore keeps one head's K/V in its own L2.
 __device__ __forceinline__ long xcd_remap(long bid, long total)

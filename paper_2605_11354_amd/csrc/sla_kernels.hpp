@@ -33,9 +33,10 @@ hipError_t launch_labels_prepare(const int8_t *lab_dense, long rows, int Nkb, in
 
 // per-key-block states: hT [BH,Nkb,65,64] bf16; optionally also Vp [BH,Nkb,64,64] bf16, the
 // transposed, key-permuted V tiles the attention kernel reads, and kbar [BH,Nkb,64] fp64, the
-// block means of K (same arithmetic as launch_pool); NULL skips either
+// block means of K (same arithmetic as launch_pool); NULL skips either.  With W != NULL the launch also
+// does the work of launch_transpose_w(W, nW, WT) in nW extra workgroups.
 hipError_t launch_states(const void *K, const void *V, const float *sK, const float *sV, bool fp8,
-                         int BH, int N, void *hT, void *Vp, double *kbar, hipStream_t st);
+                         int BH, int N, void *hT, void *Vp, double *kbar, const void *W, int nW, void *WT, hipStream_t st);
 
 // Hq[bh][i][:] = sum over j with lab_pad[bh][i][j] == 1 of hT[bh][j][:]   (bf16 MFMA, fp32 accumulate)
 hipError_t launch_aggregate(const uint64_t *mbits, int lab_pitch, const void *hT, int BH, int Nqb,

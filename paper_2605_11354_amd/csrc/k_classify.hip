@@ -139,28 +139,56 @@ hipError_t launch_scores(const double *qbar, const double *kbar, int BH, int Nqb
 // (keys are first shifted to the row's [min,max] range so two or three passes suffice), and
 // exact ties are resolved by ascending block index.
 
-__device__ __forceinline__ uint64_t wave_min_u64(uint64_t v)
+// Cross-lane steps as DPP moves (row shifts, then the two row broadcasts that carry a row's last lane into
+// the following rows) instead of LDS permutes: a wave-wide scan or reduction is six short VALU steps.
+//   kShr1/2/4/8: lane l reads lane l-n of its row of 16;  kBc15: rows 1 and 3 read lane 15 of the row before;
+//   kBc31: rows 2 and 3 read lane 31.  A lane without a source receives `old`.
+constexpr int kShr1 = 0x111, kShr2 = 0x112, kShr4 = 0x114, kShr8 = 0x118, kBc15 = 0x142, kBc31 = 0x143;
+template <int CTRL, int ROWS>
+__device__ __forceinline__ uint32_t dpp_get(uint32_t old, uint32_t src)
 {
-    for (int o = 32; o > 0; o >>= 1) {
-        const uint32_t lo = __shfl_xor((uint32_t)v, o, 64), hi = __shfl_xor((uint32_t)(v >> 32), o, 64);
-        const uint64_t w = ((uint64_t)hi << 32) | lo;
-        v = w < v ? w : v;
-    }
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)old, (int)src, CTRL, ROWS, 0xf, false);
+}
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
+{
+    v += dpp_get<kShr1, 0xf>(0u, v);
+    v += dpp_get<kShr2, 0xf>(0u, v);
+    v += dpp_get<kShr4, 0xf>(0u, v);
+    v += dpp_get<kShr8, 0xf>(0u, v);
+    v += dpp_get<kBc15, 0xa>(0u, v);
+    v += dpp_get<kBc31, 0xc>(0u, v);
     return v;
 }
-__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v)
+template <bool MAX, int CTRL, int ROWS>
+__device__ __forceinline__ uint64_t dpp_minmax_step(uint64_t v)
 {
-    for (int o = 32; o > 0; o >>= 1) {
-        const uint32_t lo = __shfl_xor((uint32_t)v, o, 64), hi = __shfl_xor((uint32_t)(v >> 32), o, 64);
-        const uint64_t w = ((uint64_t)hi << 32) | lo;
-        v = w > v ? w : v;
-    }
-    return v;
+    const uint32_t lo = dpp_get<CTRL, ROWS>((uint32_t)v, (uint32_t)v), hi = dpp_get<CTRL, ROWS>((uint32_t)(v >> 32), (uint32_t)(v >> 32));
+    const uint64_t w = ((uint64_t)hi << 32) | lo;      // a lane without a source sees its own value
+    return MAX ? (w > v ? w : v) : (w < v ? w : v);
+}
+template <bool MAX>
+__device__ __forceinline__ uint64_t wave_minmax_u64(uint64_t v)
+{
+    v = dpp_minmax_step<MAX, kShr1, 0xf>(v);
+    v = dpp_minmax_step<MAX, kShr2, 0xf>(v);
+    v = dpp_minmax_step<MAX, kShr4, 0xf>(v);
+    v = dpp_minmax_step<MAX, kShr8, 0xf>(v);
+    v = dpp_minmax_step<MAX, kBc15, 0xa>(v);
+    v = dpp_minmax_step<MAX, kBc31, 0xc>(v);           // lane 63 now holds the result over all lanes
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, 63), hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), 63);
+    return ((uint64_t)hi << 32) | lo;
+}
+__device__ __forceinline__ uint64_t wave_min_u64(uint64_t v) { return wave_minmax_u64<false>(v); }
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) { return wave_minmax_u64<true>(v); }
+// value of lane src (uniform) in every lane
+__device__ __forceinline__ uint32_t bcast_u32(uint32_t v, int src)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, __builtin_amdgcn_readfirstlane(src));
 }
 __device__ __forceinline__ uint64_t bcast_u64(uint64_t v, int src)
 {
-    const uint32_t lo = __shfl((uint32_t)v, src, 64), hi = __shfl((uint32_t)(v >> 32), src, 64);
-    return ((uint64_t)hi << 32) | lo;
+    return ((uint64_t)bcast_u32((uint32_t)(v >> 32), src) << 32) | bcast_u32((uint32_t)v, src);
 }
 
 // logit -> key with (key ascending) == (logit descending); -0.0 is folded onto +0.0
@@ -201,12 +229,7 @@ __device__ void radix_select(const uint64_t (&key)[KPL], int Nkb, int k, uint32_
 #pragma unroll
         for (int b = 0; b < 4; ++b) c[b] = hist[lane * 4 + b];
         const uint32_t mine = c[0] + c[1] + c[2] + c[3];
-        uint32_t incl = mine;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t v = __shfl_up(incl, o, 64);
-            if (lane >= o) incl += v;
-        }
+        const uint32_t incl = wave_incl_scan(mine);
         const uint32_t excl = incl - mine;
         const bool here = excl < (uint32_t)kk && (uint32_t)kk <= incl;
         const uint64_t bal = __ballot(here);
@@ -221,9 +244,9 @@ __device__ void radix_select(const uint64_t (&key)[KPL], int Nkb, int k, uint32_
                 }
             }
         }
-        digit = __shfl(digit, src, 64);
-        before = __shfl(before, src, 64);
-        nb = (int)__shfl(cnt, src, 64);
+        digit = bcast_u32(digit, src);
+        before = bcast_u32(before, src);
+        nb = (int)bcast_u32(cnt, src);
         prefix = (prefix << 8) | digit;
         kk -= (int)before;
         if (nb == 1 || shift == 0) break;
@@ -450,12 +473,7 @@ template <int NT>
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, SelShared &sh, uint32_t *total)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t incl = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t u = __shfl_up(incl, o, 64);
-        if (lane >= o) incl += u;
-    }
+    const uint32_t incl = wave_incl_scan(v);
     __syncthreads();                                   // wsum may still be read by a previous scan
     if (lane == 63) sh.wsum[wave] = incl;
     __syncthreads();

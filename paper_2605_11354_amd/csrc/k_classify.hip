@@ -90,16 +90,27 @@ __global__ __launch_bounds__(256) void scores_kernel(const double *__restrict__ 
 #pragma unroll
         for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
 
-    for (int dh = 0; dh < 2; ++dh) {
-        __syncthreads();
+    // both channel halves are requested up front (row indices clamped, so the loads are unconditional and the
+    // second half stays in flight while the first is staged and consumed)
+    double qr[2][8], kr[2][8];
+#pragma unroll
+    for (int dh = 0; dh < 2; ++dh)
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const int idx = tid + 256 * r, row = idx >> 5, d = idx & 31;
-            const int gi = i0 + row, gj = j0 + row;
-            qs[d][row] = gi < Nqb ? qh[(long)gi * kD + dh * 32 + d] : 0.0;
-            ks[d][row] = gj < Nkb ? kh[(long)gj * kD + dh * 32 + d] : 0.0;
+            qr[dh][r] = qh[(long)min(i0 + row, Nqb - 1) * kD + dh * 32 + d];
+            kr[dh][r] = kh[(long)min(j0 + row, Nkb - 1) * kD + dh * 32 + d];
         }
-        __syncthreads();
+#pragma unroll
+    for (int dh = 0; dh < 2; ++dh) {
+        if (dh) lds_barrier();             // first half consumed; the loads of the second stay in flight
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int idx = tid + 256 * r, row = idx >> 5, d = idx & 31;
+            qs[d][row] = qr[dh][r];        // rows past the end repeat the last one; their results are not stored
+            ks[d][row] = kr[dh][r];
+        }
+        lds_barrier();
 #pragma unroll 4
         for (int d = 0; d < 32; ++d) {
             double qv[4], kv[4];
@@ -111,15 +122,17 @@ __global__ __launch_bounds__(256) void scores_kernel(const double *__restrict__ 
                 for (int b = 0; b < 4; ++b) acc[a][b] = fma(qv[a], kv[b], acc[a][b]);
         }
     }
+    // a thread's four logits of a row are 32 contiguous bytes; the row pitch is a multiple of 8 entries, so the
+    // group is inside the row's allocation as a whole (entries in [Nkb, pitch) are padding nobody reads)
     double *Sh = S + bh * (long)Nqb * pitch;
+    const int gj = j0 + tx * 4;
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
         const int gi = i0 + ty * 4 + a;
-        if (gi >= Nqb) continue;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int gj = j0 + tx * 4 + b;
-            if (gj < Nkb) Sh[(long)gi * pitch + gj] = acc[a][b];
+        if (gi < Nqb && gj < pitch) {
+            double2 *dst = (double2 *)(Sh + (long)gi * pitch + gj);
+            dst[0] = double2{acc[a][0], acc[a][1]};
+            dst[1] = double2{acc[a][2], acc[a][3]};
         }
     }
 }

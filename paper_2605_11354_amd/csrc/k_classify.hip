@@ -32,16 +32,23 @@ __global__ __launch_bounds__(256) void pool_kernel(const void *__restrict__ X, c
     if (FP8) {
         const uint8_t *x = (const uint8_t *)X + ((size_t)bh * N + t0) * kD + c * 8;
         const double s = (double)scales[blkid];
-#pragma unroll 8
-        for (int t = 0; t < cnt; ++t) {
-            const uint2 w = *(const uint2 *)(x + (size_t)t * kD);
+        auto add_row = [&](uint2 w) {
             const f32x2 a0 = __builtin_amdgcn_cvt_pk_f32_fp8(w.x, false), a1 = __builtin_amdgcn_cvt_pk_f32_fp8(w.x, true);
             const f32x2 a2 = __builtin_amdgcn_cvt_pk_f32_fp8(w.y, false), a3 = __builtin_amdgcn_cvt_pk_f32_fp8(w.y, true);
             acc[0] += (double)a0[0] * s; acc[1] += (double)a0[1] * s;
             acc[2] += (double)a1[0] * s; acc[3] += (double)a1[1] * s;
             acc[4] += (double)a2[0] * s; acc[5] += (double)a2[1] * s;
             acc[6] += (double)a3[0] * s; acc[7] += (double)a3[1] * s;
+        };
+        int t = 0;
+        for (; t + 16 <= cnt; t += 16) {       // sixteen rows requested before the first is consumed
+            uint2 w[16];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) w[k] = *(const uint2 *)(x + (size_t)(t + k) * kD);
+#pragma unroll
+            for (int k = 0; k < 16; ++k) add_row(w[k]);
         }
+        for (; t < cnt; ++t) add_row(*(const uint2 *)(x + (size_t)t * kD));
     } else {
         const uint16_t *x = (const uint16_t *)X + ((size_t)bh * N + t0) * kD + c * 8;
 #pragma unroll 8

@@ -26,6 +26,12 @@ SMALL = [
     ("c2_small", synth.CONFIGS[2].with_(H=2, N=3 * 1374), -1, -1),
     ("c4_small", synth.CONFIGS[4].with_(H=2, N=3 * 1374), -1, -1),
     ("c4_bq64_tail", synth.CONFIGS[4].with_(H=2, N=1000, bq=64), 3, 5),
+    # around the switches between kernel variants: 192 / 193 query blocks (aggregation tile shape),
+    # 256 / 257 key blocks (fused classifier / separate logits + selection)
+    ("nqb192", C0.with_(H=1, N=192 * 64), 4, 150),
+    ("nqb193", C0.with_(H=1, N=193 * 64 - 5), 4, 150),
+    ("nkb256", C0.with_(H=1, N=256 * 64 - 1), 6, 200),
+    ("nkb257_bq128", C0.with_(H=1, N=257 * 64 - 63, bq=128), 6, 200),
 ]
 
 
@@ -114,7 +120,7 @@ def test_linear_states(oracle, name):
         assert np.abs(got[:, 64, :] - z).max() <= 2.0 ** -7 * np.abs(z).max()
 
 
-@pytest.mark.parametrize("name", ["c0", "c0_bq128_tail", "c1_small", "c4_small"])
+@pytest.mark.parametrize("name", ["c0", "c0_bq128_tail", "c1_small", "c4_small", "nqb192", "nqb193", "nkb257_bq128"])
 def test_marginal_aggregate(oracle, name):
     case = _case(name)
     lab = case.oracle_classify(oracle)["labels"]

@@ -111,10 +111,12 @@ def main() -> int:
                 "frac": round(gbs / PEAK_HBM_GBS, 4)}
 
     attend_tflops = attend_flops / stage["attend"] / 1e9 if stage["attend"] > 0 else 0.0
-    traffic = None
-    tfile = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    traffic = None     # HBM bytes per launch of the attention kernel, from the committed FETCH_SIZE / WRITE_SIZE summary
+    tfile = os.path.join(ROOT, "profiles", f"{cfg.name}_hbm_counters.txt")
     if os.path.exists(tfile):
-        traffic = json.load(open(tfile)).get(cfg.name, {}).get("attend")
+        for line in open(tfile):
+            if line.startswith("attend_kernel HBM bytes per launch:"):
+                traffic = int(line.split(":")[1])
     roofline = {"kernel": "attend (block-sparse attention over critical blocks + fused linear/proj epilogue)",
                 "bound": "mfma", "achieved": round(attend_tflops, 2), "peak": PEAK_TFLOPS[cfg.dtype], "unit": "TFLOP/s",
                 "frac": round(attend_tflops / PEAK_TFLOPS[cfg.dtype], 4), "traffic": traffic,

@@ -177,6 +177,22 @@ def test_forward_degenerate_counts(oracle, kc, kn):
         G.assert_output(got, ref["O"], "bf16", f"k_crit={kc} k_neg={kn}")
 
 
+@pytest.mark.parametrize("name,scale", [("c0", 0.25), ("c0_tail150", 0.03), ("c4_bq64_tail", 0.2)])
+def test_forward_softmax_scale_override(oracle, name, scale):
+    """sm_scale other than 1/sqrt(D) (section 3.3 fixes the default only) reaches the sparse branch and P_c."""
+    for n, cfg, kc, kn in SMALL:
+        if n == name:
+            case = G.Case(cfg, k_crit=kc, k_neg=kn, sm_scale=scale)
+    O, lab = case.forward()
+    oc = case.oracle_classify(oracle, want_pc=True)
+    assert np.array_equal(lab.cpu().numpy(), oc["labels"])
+    ref = case.oracle_attend(oracle, oc["labels"])
+    got = G.gather_blocks(G.bf16_tensor_to_f64(O), ref["sel"], case.cfg.bq, case.cfg.H)
+    G.assert_output(got, ref["O"], case.cfg.dtype, f"{name} sm_scale={scale}")
+    pc = case.classify(want=("Pc",))["Pc"]
+    np.testing.assert_allclose(pc, oc["Pc"], rtol=2e-5, atol=1e-9)
+
+
 def test_v_ones_closed_form_on_device():
     """V == 1 gives O = 1 + column sums of W for every row (eq. 1), independent of the oracle."""
     d = dict(synth.make_inputs(C0))

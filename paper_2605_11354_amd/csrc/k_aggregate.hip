@@ -16,9 +16,10 @@
 // Workgroup: 4 waves, tile 128 state columns x BM query blocks.  Long heads: BM = 256, every wave
 // takes all 128 columns (TA = 4 sub-tiles of 32) and 64 query blocks (TB = 2), so the state slab,
 // which dominates the L2 traffic, is read once per 256 query blocks and one expanded mask operand
-// feeds four MFMAs.  Short heads: BM = 64, waves as 2 x 2 with TA = 2, TB = 1.  K step 64
-// key blocks; global loads run kAggAhead K steps ahead of their use in register sets, LDS is
-// double buffered: one barrier per K step.
+// feeds four MFMAs.  Short heads: BM = 64, waves as 2 x 2 with TA = 2, TB = 1; frame-sized heads (at most 32
+// query blocks): BM = 32, four waves side by side along the columns, TA = TB = 1.  K step 64
+// key blocks; global loads run AHEAD (three, or one for very short heads) K steps ahead of their use in
+// register sets, LDS is double buffered: one barrier per K step.
 #include "sla_common.hpp"
 #include "sla_kernels.hpp"
 
@@ -28,11 +29,13 @@ namespace {
 constexpr int kAggK = 64;             // key blocks per K step (one 64-bit mask word)
 constexpr int kAggRow = kAggK + 8;    // bf16 per state-operand row in LDS: 144 B, consecutive rows start 9 16-byte slots apart
 constexpr int kAggOutRow = 128 + 8;   // bf16 per row of the output staging tile (272 B)
-constexpr int kAggAhead = 3;          // K steps between a global load and its use
 constexpr int kAggBuf = 128 * kAggRow;
 }  // namespace
 
-template <int TA, int TB>
+// AHEAD: K steps between a global load and its use (register sets); 1 for heads of one or two K steps, where
+// deeper sets would only cost registers and with them resident workgroups
+// NBUF: LDS operand buffers, 2 in general, 1 for heads of a single K step (more workgroups per CU)
+template <int TA, int TB, int AHEAD, int NBUF>
 __global__ __launch_bounds__(256) void aggregate_kernel(const uint2 *__restrict__ mbits, int nkw,
                                                         const uint16_t *__restrict__ hT, int Nqb, int Nkb, int n_it,
                                                         long total, uint16_t *__restrict__ Hq)
@@ -40,7 +43,7 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const uint2 *__restrict_
     constexpr int kWN = 4 / TA;                   // waves along the columns (TA 32-column sub-tiles each)
     constexpr int kWI = 4 / kWN;                  // waves along the query blocks (TB 32-block sub-tiles each)
     constexpr int BM = 32 * TB * kWI;             // query blocks per workgroup tile
-    constexpr int kStage = BM * kAggOutRow > 2 * kAggBuf ? BM * kAggOutRow : 2 * kAggBuf;
+    constexpr int kStage = BM * kAggOutRow > NBUF * kAggBuf ? BM * kAggOutRow : NBUF * kAggBuf;
     __shared__ __attribute__((aligned(16))) uint16_t smem[kStage];
 
     const long item = xcd_remap(blockIdx.x, total);      // (head, column tile, query tile), query tile fastest:
@@ -74,8 +77,8 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const uint2 *__restrict_
     }
     const int ksteps = (Nkb + kAggK - 1) / kAggK;            // == nkw
 
-    uint2 hreg[kAggAhead][8];
-    uint2 mreg[kAggAhead][TB];
+    uint2 hreg[AHEAD][8];
+    uint2 mreg[AHEAD][TB];
     auto load_tile = [&](int ks, uint2 (&h)[8], uint2 (&m)[TB]) {          // main loop: ks < ksteps
 #pragma unroll
         for (int b = 0; b < TB; ++b) m[b] = mrow[b][ks];
@@ -137,7 +140,7 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const uint2 *__restrict_
 
     // one K step: the operand tile of step ks is in LDS buffer ks & 1, its mask words in mw
     auto mma_step = [&](int ks, const uint2 (&mw)[TB]) {
-        const uint16_t *As = smem + (ks & 1) * kAggBuf;
+        const uint16_t *As = smem + (ks & (NBUF - 1)) * kAggBuf;
 #pragma unroll
         for (int s = 0; s < kAggK / 16; ++s) {
             bf16x8 af[TA];
@@ -154,39 +157,39 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const uint2 *__restrict_
     };
 
 #pragma unroll
-    for (int u = 0; u < kAggAhead; ++u)
+    for (int u = 0; u < AHEAD; ++u)
         if (u < ksteps) load_tile_edge(u, hreg[u], mreg[u]);
     store_tile(smem, hreg[0]);
     lds_barrier();
 
-    // main part: groups of kAggAhead steps whose look-ahead loads are all real, as straight-line code (register
+    // main part: groups of AHEAD steps whose look-ahead loads are all real, as straight-line code (register
     // set u holds step ks0 + u); the compiler waits for one set at a time and leaves the later ones in flight
     int ks0 = 0;
-    for (; ks0 + 2 * kAggAhead <= ksteps; ks0 += kAggAhead) {
+    for (; ks0 + 2 * AHEAD <= ksteps; ks0 += AHEAD) {
 #pragma unroll
-        for (int u = 0; u < kAggAhead; ++u) {
+        for (int u = 0; u < AHEAD; ++u) {
             const int ks = ks0 + u;
             uint2 mw[TB];
 #pragma unroll
             for (int b = 0; b < TB; ++b) mw[b] = mreg[u][b];
-            load_tile(ks + kAggAhead, hreg[u], mreg[u]);      // set u: its states went to LDS one step ago, its mask words are copied
+            load_tile(ks + AHEAD, hreg[u], mreg[u]);      // set u: its states went to LDS one step ago, its mask words are copied
             mma_step(ks, mw);
-            store_tile(smem + ((ks + 1) & 1) * kAggBuf, hreg[(u + 1) % kAggAhead]);
+            store_tile(smem + ((ks + 1) & (NBUF - 1)) * kAggBuf, hreg[(u + 1) % AHEAD]);
             lds_barrier();                                     // not __syncthreads(): the loads of later steps stay in flight
         }
     }
-    // the remaining steps (fewer than 2 kAggAhead), with the loads that are still due issued under a condition
-    for (; ks0 < ksteps; ks0 += kAggAhead) {
+    // the remaining steps (fewer than 2 AHEAD), with the loads that are still due issued under a condition
+    for (; ks0 < ksteps; ks0 += AHEAD) {
 #pragma unroll
-        for (int u = 0; u < kAggAhead; ++u) {
+        for (int u = 0; u < AHEAD; ++u) {
             const int ks = ks0 + u;
             if (ks < ksteps) {                                 // uniform over the workgroup
                 uint2 mw[TB];
 #pragma unroll
                 for (int b = 0; b < TB; ++b) mw[b] = mreg[u][b];
-                if (ks + kAggAhead < ksteps) load_tile_edge(ks + kAggAhead, hreg[u], mreg[u]);
+                if (ks + AHEAD < ksteps) load_tile_edge(ks + AHEAD, hreg[u], mreg[u]);
                 mma_step(ks, mw);
-                if (ks + 1 < ksteps) store_tile(smem + ((ks + 1) & 1) * kAggBuf, hreg[(u + 1) % kAggAhead]);
+                if (ks + 1 < ksteps) store_tile(smem + ((ks + 1) & (NBUF - 1)) * kAggBuf, hreg[(u + 1) % AHEAD]);
                 lds_barrier();
             }
         }
@@ -221,15 +224,23 @@ hipError_t launch_aggregate(const uint64_t *mbits, int lab_pitch, const void *hT
 {
     constexpr int kNT = (kStateElems + 127) / 128;
     const int nkw = lab_pitch / 64;
-    if (Nqb <= 192) {    // short heads: 64-query-block tiles waste less of the matrix unit and give more workgroups
+    if (Nqb <= 32 && Nkb <= kAggK) {   // frame-sized heads (one K step): 32-query-block tiles, 32 x 32 per wave, one LDS buffer
+        const long total = (long)BH * kNT;
+        aggregate_kernel<1, 1, 1, 1><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint2 *)mbits, nkw, (const uint16_t *)hT, Nqb, Nkb,
+                                                                              1, total, (uint16_t *)Hq);
+    } else if (Nqb <= 192) {    // short heads: 64-query-block tiles waste less of the matrix unit and give more workgroups
         const int n_it = (Nqb + 63) / 64;
         const long total = (long)BH * kNT * n_it;
-        aggregate_kernel<2, 1><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint2 *)mbits, nkw, (const uint16_t *)hT, Nqb, Nkb,
-                                                                        n_it, total, (uint16_t *)Hq);
+        if (Nkb <= 128)
+            aggregate_kernel<2, 1, 1, 2><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint2 *)mbits, nkw, (const uint16_t *)hT, Nqb, Nkb,
+                                                                               n_it, total, (uint16_t *)Hq);
+        else
+            aggregate_kernel<2, 1, 3, 2><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint2 *)mbits, nkw, (const uint16_t *)hT, Nqb, Nkb,
+                                                                               n_it, total, (uint16_t *)Hq);
     } else {
         const int n_it = (Nqb + 255) / 256;
         const long total = (long)BH * kNT * n_it;
-        aggregate_kernel<4, 2><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint2 *)mbits, nkw, (const uint16_t *)hT, Nqb, Nkb,
+        aggregate_kernel<4, 2, 3, 2><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint2 *)mbits, nkw, (const uint16_t *)hT, Nqb, Nkb,
                                                                         n_it, total, (uint16_t *)Hq);
     }
     return hipGetLastError();

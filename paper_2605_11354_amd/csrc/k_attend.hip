@@ -41,7 +41,7 @@
 namespace sla {
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kStages = 3;
+constexpr int kStages = 3;           // ring depth of the general kernel (STG below)
 // Slack allowed before a row raises its running maximum.  0 = exact running maximum: the dominant weight of a
 // row is then exactly 1.0 and survives the bf16 rounding of P untouched; a slack of 8 (rescaling the
 // accumulators far less often) was measured 6 % faster but doubled the output error of peaked rows.
@@ -146,7 +146,11 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base)
 // two waves share a query group and each takes one 32-key half of every tile (used for 64-row
 // query blocks so that a workgroup still has four waves); their partial (max, sum, O) are merged
 // through LDS after the loop and the KS = 0 wave of each pair runs the epilogue.
-template <int NW, int KS, bool FP8>
+// STG: stages of the tile ring.  3 in general (copies run two tiles ahead).  2 for lists of at most two critical
+// blocks (bf16, no key split): both tiles are requested at the start, the epilogue operands share the stage the
+// first tile leaves free, and the smaller LDS footprint lets five workgroups instead of three share a CU, which is
+// what a loop this short needs.
+template <int NW, int KS, bool FP8, int STG>
 __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void attend_kernel(
     const void *__restrict__ Qp, const void *__restrict__ Kp, const uint16_t *__restrict__ Vp,
     const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV,
@@ -159,7 +163,9 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
     constexpr int ES = FP8 ? 1 : 2;                     // bytes per input element
     constexpr int NH = 2 / KS;                          // 32-key halves of a tile this wave processes
     constexpr int NS = 4 / KS;                          // 16-key steps of the second product this wave processes
-    __shared__ __attribute__((aligned(1024))) uint8_t lds[kStages * T::STAGE];
+    static_assert(STG == 3 || (STG == 2 && KS == 1 && !FP8), "the two-stage ring is for unsplit bf16 lists of at most two tiles");
+    constexpr int kZBytes = STG == 2 ? 256 : 0;         // two-stage ring: the Z row gets its own slot behind the ring
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[STG * T::STAGE + kZBytes];
     const long work = xcd_remap(blockIdx.x, total);
     if (work >= total) return;                        // the whole workgroup leaves together
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
@@ -222,7 +228,7 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
     const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_p)lds;                // LDS byte address of the ring
     auto request = [&](int c, int j) {
         const int jj = j < 0 ? 0 : j;                  // absent entries still copy (block 0) so the copy count is uniform
-        issue_tile<NWAVES, FP8>(lds_base + (c % kStages) * T::STAGE, Kh + (size_t)jj * kBK * kD * ES, Vh + (size_t)jj * kBK * kD * 2,
+        issue_tile<NWAVES, FP8>(lds_base + (c % STG) * T::STAGE, Kh + (size_t)jj * kBK * kD * ES, Vh + (size_t)jj * kBK * kD * 2,
                                 min(kBK, N - jj * kBK), co, wave_u);
     };
     // The operands of the linear/projection epilogue (the 64x64 tile of Hq^T, the Z row, W^T) travel the
@@ -231,12 +237,14 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
     const uint8_t *Hi8 = Hq ? (const uint8_t *)(Hq + (size_t)work * kStateElems) : nullptr;
     const uint8_t *Wh8 = (const uint8_t *)(WT + (proj_per_head ? (size_t)(bh % H) * kD * kD : 0));
     auto request_epilogue = [&](int c_next) {
-        const uint32_t sa = lds_base + (c_next % kStages) * T::STAGE, sb = lds_base + ((c_next + 1) % kStages) * T::STAGE;
+        const uint32_t sa = lds_base + (c_next % STG) * T::STAGE;
+        const uint32_t sb = STG == 2 ? sa + 8192 : lds_base + ((c_next + 1) % STG) * T::STAGE;
+        const uint32_t sz = STG == 2 ? lds_base + STG * T::STAGE : sa + 8192;
 #pragma unroll
         for (int x = 0; x < T::VINS; ++x) copy_1k_to_lds(Hi8, co.v[x], sa + (wave_u * T::VINS + x) * 1024);
 #pragma unroll
         for (int x = 0; x < T::VINS; ++x) copy_1k_to_lds(Wh8, co.v[x], sb + (wave_u * T::VINS + x) * 1024);
-        if (tid < 8) copy_1k_to_lds(Hi8 + 64 * kD * 2, tid * 16, sa + 8192);      // Z: 128 bytes, 8 lanes of wave 0
+        if (tid < 8) copy_1k_to_lds(Hi8 + 64 * kD * 2, tid * 16, sz);             // Z: 128 bytes, 8 lanes of wave 0
     };
     if (Hq != nullptr && k_c == 0) request_epilogue(0);
 
@@ -286,7 +294,7 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
         if (c + 2 < k_c) request(c + 2, j1);
         if (Hq != nullptr && c + 1 == k_c) request_epilogue(c + 1);
         if (j < 0) continue;
-        const uint8_t *st = lds + (c % kStages) * T::STAGE;
+        const uint8_t *st = lds + (c % STG) * T::STAGE;
         const int valid = min(kBK, N - j * kBK);
         // exp2 constant of this tile: softmax scale * log2(e) (* Q and K block scales for e4m3)
         const float cj = FP8 ? fmaxf(c_exp * qscale * sK[bh * Nkb + j], 1e-30f) : c_exp;
@@ -352,8 +360,9 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
 
     // ring stages after the loop: A, B hold the epilogue operands, L (the last tile's stage) is free
     const int c_next = k_c;
-    uint8_t *stA = lds + (c_next % kStages) * T::STAGE, *stB = lds + ((c_next + 1) % kStages) * T::STAGE;
-    uint8_t *stL = lds + ((c_next + 2) % kStages) * T::STAGE;
+    uint8_t *stA = lds + (c_next % STG) * T::STAGE, *stB = STG == 2 ? stA + 8192 : lds + ((c_next + 1) % STG) * T::STAGE;
+    uint8_t *stL = lds + ((c_next + 2) % STG) * T::STAGE;            // used by the key-split merge only (STG == 3)
+    const uint8_t *zrow = STG == 2 ? lds + STG * T::STAGE : stA + 8192;
     wait_copies_and_barrier<0>();                      // epilogue operands landed; every wave is past its last tile
 
     if (KS == 2) {
@@ -439,7 +448,7 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
             o.x = pack_bf16(x[8 * s + 0] * inv, x[8 * s + 1] * inv); o.y = pack_bf16(x[8 * s + 2] * inv, x[8 * s + 3] * inv);
             o.z = pack_bf16(x[8 * s + 4] * inv, x[8 * s + 5] * inv); o.w = pack_bf16(x[8 * s + 6] * inv, x[8 * s + 7] * inv);
             fq[s] = __builtin_bit_cast(bf16x8, o);
-            const uint4 z = *(const uint4 *)(stA + 8192 + dcol * 2);
+            const uint4 z = *(const uint4 *)(zrow + dcol * 2);
             den += bf16_lo(o.x) * bf16_lo(z.x) + bf16_hi(o.x) * bf16_hi(z.x) + bf16_lo(o.y) * bf16_lo(z.y) + bf16_hi(o.y) * bf16_hi(z.y)
                  + bf16_lo(o.z) * bf16_lo(z.z) + bf16_hi(o.z) * bf16_hi(z.z) + bf16_lo(o.w) * bf16_lo(z.w) + bf16_hi(o.w) * bf16_hi(z.w);
         }
@@ -515,12 +524,12 @@ hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int NW, int KS, bool FP8>
+template <int NW, int KS, bool FP8, int STG>
 static hipError_t launch_attend_t(const void *Q, const void *K, const void *Vp, const float *sQ, const float *sK, const float *sV,
                                   const int32_t *crit_idx, int k_c, const void *Hq, const void *WT, int proj_per_head,
                                   int H, int N, int Nqb, int Nkb, long total, float c_exp, void *O, hipStream_t st)
 {
-    attend_kernel<NW, KS, FP8><<<(unsigned)xcd_grid(total), 64 * NW * KS, 0, st>>>(Q, K, (const uint16_t *)Vp, sQ, sK, sV, crit_idx, k_c, (const uint16_t *)Hq,
+    attend_kernel<NW, KS, FP8, STG><<<(unsigned)xcd_grid(total), 64 * NW * KS, 0, st>>>(Q, K, (const uint16_t *)Vp, sQ, sK, sV, crit_idx, k_c, (const uint16_t *)Hq,
                                                                           (const uint16_t *)WT, proj_per_head, H, N, Nqb, Nkb,
                                                                           total, c_exp, (uint16_t *)O);
     return hipGetLastError();
@@ -535,13 +544,14 @@ hipError_t launch_attend(const void *Q, const void *K, const void *Vp,
     const int Nqb = (N + bq - 1) / bq, Nkb = (N + kBK - 1) / kBK;
     const long total = (long)B * H * Nqb;
     const float c_exp = sm_scale * kLog2e;
-#define SLA_ATT(NW, KS, F8) return launch_attend_t<NW, KS, F8>(Q, K, Vp, sQ, sK, sV, crit_idx, k_c, Hq, WT, proj_per_head, H, N, Nqb, Nkb, total, c_exp, O, st)
-    if (bq == 128) { if (fp8) SLA_ATT(4, 1, true); else SLA_ATT(4, 1, false); }
+#define SLA_ATT(NW, KS, F8, STG) return launch_attend_t<NW, KS, F8, STG>(Q, K, Vp, sQ, sK, sV, crit_idx, k_c, Hq, WT, proj_per_head, H, N, Nqb, Nkb, total, c_exp, O, st)
+    if (bq == 128) { if (fp8) SLA_ATT(4, 1, true, 3); else SLA_ATT(4, 1, false, 3); }
     // 64-row query blocks: two query groups x two key halves, so a workgroup still has four waves;
     // with very few critical blocks per row the merge of the halves costs more than it hides
-    if (k_c >= 4) { if (fp8) SLA_ATT(2, 2, true); else SLA_ATT(2, 2, false); }
-    if (fp8) SLA_ATT(2, 1, true);
-    SLA_ATT(2, 1, false);
+    if (k_c >= 4) { if (fp8) SLA_ATT(2, 2, true, 3); else SLA_ATT(2, 2, false, 3); }
+    if (fp8) SLA_ATT(2, 1, true, 3);
+    if (k_c <= 2) SLA_ATT(2, 1, false, 2);
+    SLA_ATT(2, 1, false, 3);
 #undef SLA_ATT
 }
 

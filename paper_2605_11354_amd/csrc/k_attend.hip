@@ -14,9 +14,13 @@
 // takes accumulator registers 8u..8u+7, i.e. keys 16s + 8a' + 4g + b; the V^T rows are read
 // with exactly that key permutation: the states kernel leaves V^T of every key block in that
 // order (bf16), so a V^T fragment is one 16-byte LDS read like a K fragment.
+// Template parameters: NW query groups of 32 rows (2 for 64-row, 4 for 128-row query blocks); KS = 2 splits the
+// critical list of a 64-row block between two wave pairs (alternate tiles) whose (maximum, sum, O) are merged
+// through LDS before the epilogue, so that short lists still give a workgroup four waves of work.
 //
 // Memory pipeline.  K and V^T tiles go from global memory straight into LDS
-// (global_load_lds_dwordx4, no staging registers) into a ring of three stages; the tile of
+// (global_load_lds_dwordx4, no staging registers) into a ring of three stages (two for lists of at most two
+// tiles, see STG below); the tile of
 // iteration c+2 is requested while tile c is consumed, and a single workgroup barrier per
 // iteration both publishes tile c and frees the stage of tile c-1.  Rows are stored unpadded
 // with the 16-byte chunk index XOR-ed by row bits (applied on the global side of the copy),

@@ -10,8 +10,10 @@
 // V^T of the block (bf16, key-permuted) for the attention kernel, which can then fetch both of
 // its tiles as plain 16-byte rows, and (optionally) the fp64 block mean of K for the classifier,
 // so K is read from HBM once per layer by this kernel instead of twice.
-// The loads of the next block are in flight (in registers) while the current one is processed:
-// the kernel is bound by HBM (16 KB in, 16.3 KB out per block for bf16 inputs).
+// The loads of the next block are in flight (in registers) while the current one is processed, and the
+// state and V^T tiles leave through LDS so that every store instruction writes 1 KB of whole rows:
+// the kernel is bound by HBM (16 KB in, 16.6 KB out per block for bf16 inputs).  A few workgroups past
+// the states grid lay out the projection matrices for the attention epilogue (one launch fewer).
 #include "sla_common.hpp"
 #include "sla_kernels.hpp"
 

@@ -123,3 +123,25 @@ def forward(p: Params, Q, K, V, W, sQ=None, sK=None, sV=None, sel=None, want_par
             if a[k] is not None:
                 a[k] = a[k].reshape(p.B, p.H, Nqb * p.bq, 64)[:, :, :p.N, :]
     return a
+
+
+def grad_wproj(p: Params, Q, K, V, labels, dO, sQ=None, sK=None, sV=None):
+    """Gradient of L = sum(O * dO) with respect to the projection of the linear branch.
+
+    Alg. 1 step 10 / eq. (1): O = O_sparse + O_lin W_O, and W_O is the only parameter the method
+    trains (section 3.3), so dL/dW_O = sum over the tokens (and over every (b,h) that uses the matrix)
+    of O_lin[t]^T dO[t], with O_lin the normalised linear output before the projection.  No gradient
+    flows through the block masks or into Q, K, V.
+
+    dO: float64 [B,H,N,64].  Returns dW float64 [nW,64,64] ([D_in, D_out]), nW = H if the projection
+    is per head, else 1."""
+    _chk(labels, np.int8)
+    dO = np.ascontiguousarray(dO, dtype=np.float64)
+    assert dO.shape == (p.B, p.H, p.N, 64), dO.shape
+    Wzero = np.zeros((p.H if p.proj_per_head else 1, 64, 64), np.uint16)      # the projection itself does not enter
+    parts = attend(p, Q, K, V, Wzero, labels, None, sQ, sK, sV, want_parts=True)
+    Nqb = -(-p.N // p.bq)
+    olin = parts["O_lin"].reshape(p.B, p.H, Nqb * p.bq, 64)[:, :, :p.N, :]
+    if p.proj_per_head:
+        return np.einsum("bhtd,bhte->hde", olin, dO)
+    return np.einsum("bhtd,bhte->de", olin, dO)[None]

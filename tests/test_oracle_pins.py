@@ -295,3 +295,51 @@ def test_fp8_inputs_all_critical_equals_dense_on_dequantised(oracle):
         deq = [vals[d[k][0, h]] * np.repeat(d["s" + k][0, h].astype(np.float64), b)[:300, None]
                for k, b in (("Q", 128), ("K", 64), ("V", 64))]
         np.testing.assert_allclose(r["O"][0, h], bf.dense_attention(*deq, 0.125), rtol=0, atol=1e-12)
+
+
+def test_wproj_gradient_matches_difference_quotient_of_the_forward(oracle):
+    """O is linear in W_O (Alg. 1 step 10), so the difference quotient of L = sum(O * G) between two projections
+    that differ in one entry IS dL/dW for that entry; this fixes the orientation ([D_in, D_out], right-multiplied),
+    the use of the normalised O_lin, and the sum over heads of a shared projection."""
+    for per_head in (False, True):
+        cfg = synth.CONFIGS[0].with_(N=200, proj_per_head=per_head)
+        d = synth.make_inputs(cfg)
+        po = oracle.make_params(cfg.B, cfg.H, cfg.N, cfg.bq, cfg.bk, 1, 1, cfg.dtype, cfg.proj_per_head)
+        labels = oracle.classify(po, d["Q"], d["K"])["labels"]
+        rng = np.random.default_rng(5)
+        G = rng.standard_normal((cfg.B, cfg.H, cfg.N, 64))
+        dW = oracle.grad_wproj(po, d["Q"], d["K"], d["V"], labels, G)
+        assert dW.shape == ((cfg.H if per_head else 1), 64, 64)
+        base = oracle.forward(po, d["Q"], d["K"], d["V"], d["W"])["O"]
+        L0 = float((base * G).sum())
+        W = d["W"].reshape(-1, 64, 64)
+        for (w, e_in, e_out) in [(0, 3, 17), (W.shape[0] - 1, 63, 0), (0, 40, 40)]:
+            W2 = W.copy()
+            bf = lambda bits: float((np.array([bits], np.uint32) << 16).view(np.float32)[0])     # bf16 bits -> value
+            old = bf(int(W2[w, e_in, e_out]))
+            W2[w, e_in, e_out] = synth.to_bf16_bits(np.array([old + 0.5], np.float32))[0]      # another bf16 value
+            delta = bf(int(W2[w, e_in, e_out])) - old
+            assert delta != 0.0
+            O2 = oracle.forward(po, d["Q"], d["K"], d["V"], W2.reshape(d["W"].shape))["O"]
+            quotient = (float((O2 * G).sum()) - L0) / delta
+            assert abs(quotient - dW[w, e_in, e_out]) <= 1e-9 * max(1.0, abs(dW[w, e_in, e_out])), (per_head, w, e_in, e_out)
+
+
+def test_wproj_gradient_closed_form_for_constant_values(oracle):
+    """V == 1 makes O_lin the all-ones row for every token whose query block has a marginal block (a weighted
+    mean of ones), so every row of dL/dW_O is the column sum of dO over those tokens."""
+    cfg = synth.CONFIGS[0]
+    d = dict(synth.make_inputs(cfg))
+    d["V"] = np.full_like(d["V"], 0x3F80)
+    po = oracle.make_params(cfg.B, cfg.H, cfg.N, cfg.bq, cfg.bk, 1, 4, cfg.dtype, cfg.proj_per_head)
+    labels = oracle.classify(po, d["Q"], d["K"])["labels"]
+    assert (labels == 1).any(axis=-1).all()                      # every query block has marginal blocks here
+    G = np.random.default_rng(6).standard_normal((cfg.B, cfg.H, cfg.N, 64))
+    dW = oracle.grad_wproj(po, d["Q"], d["K"], d["V"], labels, G)
+    expect = np.broadcast_to(G.sum(axis=(0, 1, 2)), (64, 64))
+    np.testing.assert_allclose(dW[0], expect, rtol=1e-12, atol=1e-10)
+    # and no marginal block at all: no gradient
+    po0 = oracle.make_params(cfg.B, cfg.H, cfg.N, cfg.bq, cfg.bk, 4, 4, cfg.dtype, cfg.proj_per_head)
+    lab0 = oracle.classify(po0, d["Q"], d["K"])["labels"]
+    assert not (lab0 == 1).any()
+    assert np.all(oracle.grad_wproj(po0, d["Q"], d["K"], d["V"], lab0, G) == 0.0)

@@ -32,6 +32,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=1, help="index into the benchmark configurations (default 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--with-grad", action="store_true", help="also time sla_wproj_grad (gradient of W_proj) after the forward")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards over batch x heads with no "
@@ -153,6 +154,25 @@ def main() -> int:
         "roofline": roofline, "kernels": kernels,
         "sum_kernel_ms": round(stage["attend"] + sum(k["ms"] for k in kernels.values()), 5),
     }
+
+    if args.with_grad:
+        # gradient of the projection (next row of the scope table): reads Q, dO and the aggregated states once
+        nW = cfg.H if cfg.proj_per_head else 1
+        dO = torch.randn((cfg.B, cfg.H, cfg.N, 64), device="cuda").to(torch.bfloat16)
+        dW = torch.empty((nW, 64, 64), dtype=torch.float32, device="cuda")
+        for _ in range(args.warmup):
+            B.sla_wproj_grad(p, Q, dO, dW, ws, sQ)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            B.sla_wproj_grad(p, Q, dO, dW, ws, sQ)
+        e1.record()
+        torch.cuda.synchronize()
+        gms = e0.elapsed_time(e1) / args.steps
+        gbytes = qkv_bytes + BH * N * D * 2 + BH * Nqb * 65 * D * 2 + nW * D * D * 4
+        out["wproj_grad"] = {"ms": round(gms, 5), "bound": "hbm", "algorithmic_bytes": int(gbytes),
+                             "achieved_GBs": round(gbytes / gms / 1e6, 1), "frac": round(gbytes / gms / 1e6 / PEAK_HBM_GBS, 4),
+                             "note": "two launches (partials + fixed-order reduction), HIP events on the launch stream"}
 
     if not args.no_check or not args.no_cpu_baseline:
         from oracle import sla_oracle as orc

@@ -92,6 +92,24 @@ sla_status_t sla_forward(const sla_params_t *p,
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Gradient with respect to W_proj, the only parameter the method trains (section 3.3; Alg. 1 step 10:
+ * O = O_sparse + O_lin W_O):
+ *     dW[w][d_in][d_out] = sum over the (b,h) that use matrix w and over their tokens t of
+ *                          O_lin[b,h,t][d_in] * dO[b,h,t][d_out]
+ * with O_lin the normalised output of the linear branch before the projection.  No gradient flows through the
+ * block masks or into Q, K, V.  O_lin is recomputed from Q and the aggregated states that a preceding
+ * sla_forward with the same params and the same Q, K, V left in `workspace`: pass that workspace,
+ * untouched since that call.
+ *   Q, sQ   in   as in sla_forward
+ *   dO      in   bf16 [B,H,N,D], the gradient of the loss with respect to O
+ *   dW      out  fp32 [D_in, D_out] or [H, D_in, D_out] (written, not accumulated into)
+ * The sum is formed in a fixed order (no atomics): the same inputs give the same bits.
+ * With B, H or N zero, dW is set to zero with hipMemsetAsync: do not capture that case into a HIP graph.
+ */
+sla_status_t sla_wproj_grad(const sla_params_t *p, const void *Q, const float *sQ, const void *dO, float *dW,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Measurement variant of sla_forward: identical kernels and results, but every kernel is
  * bracketed by HIP events on `stream`; the call then WAITS for the stream and writes the
  * duration of each kernel in milliseconds to stage_ms[SLA_NUM_STAGES] (host memory).

@@ -19,8 +19,8 @@ SLA_OK, SLA_ERR_INVALID_ARG, SLA_ERR_UNSUPPORTED, SLA_ERR_WORKSPACE, SLA_ERR_HIP
 SLA_BF16, SLA_FP8_E4M3 = 0, 1
 STATE_ROWS = 65          # rows of one block state: 64 rows of h^T and one row of z
 EXPORTS = ["sla_resolve_counts", "sla_workspace_bytes", "sla_forward", "sla_pool_classify", "sla_linear_states",
-           "sla_marginal_aggregate", "sla_sparse_combine", "sla_forward_profiled", "sla_strerror", "sla_last_error",
-           "sla_stage_name"]
+           "sla_marginal_aggregate", "sla_sparse_combine", "sla_forward_profiled", "sla_wproj_grad", "sla_strerror",
+           "sla_last_error", "sla_stage_name"]
 NUM_STAGES = 6
 
 
@@ -55,7 +55,7 @@ def lib() -> C.CDLL:
         _lib.sla_strerror.restype = C.c_char_p
         _lib.sla_last_error.restype = C.c_char_p
         _lib.sla_stage_name.restype = C.c_char_p
-        for name in EXPORTS[:8]:
+        for name in EXPORTS[:9]:
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -135,6 +135,13 @@ def sla_marginal_aggregate(p, labels, hT, Hq, workspace=None):
     _check(lib().sla_marginal_aggregate(C.byref(p), _ptr(labels), _ptr(hT), _ptr(Hq), _ptr(ws), C.c_size_t(ws.numel()),
                                         _stream()), "sla_marginal_aggregate")
     return Hq
+
+
+def sla_wproj_grad(p, Q, dO, dW, workspace, sQ=None):
+    """dW (fp32 [nW,64,64]) <- gradient of sum(O * dO) w.r.t. W_proj; `workspace` is the one sla_forward just used."""
+    _check(lib().sla_wproj_grad(C.byref(p), _ptr(Q), _ptr(sQ), _ptr(dO), _ptr(dW), _ptr(workspace),
+                                C.c_size_t(workspace.numel()), _stream()), "sla_wproj_grad")
+    return dW
 
 
 def sla_sparse_combine(p, Q, K, V, W_proj, labels, Hq, O, sQ=None, sK=None, sV=None, workspace=None):

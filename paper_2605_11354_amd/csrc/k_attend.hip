@@ -45,7 +45,6 @@
 namespace sla {
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kStages = 3;           // ring depth of the general kernel (STG below)
 // Slack allowed before a row raises its running maximum.  0 = exact running maximum: the dominant weight of a
 // row is then exactly 1.0 and survives the bf16 rounding of P untouched; a slack of 8 (rescaling the
 // accumulators far less often) was measured 6 % faster but doubled the output error of peaked rows.
@@ -127,23 +126,6 @@ __device__ __forceinline__ void issue_tile(uint32_t stage, const uint8_t *kt, co
     }
 #pragma unroll
     for (int x = 0; x < T::VINS; ++x) copy_1k_to_lds(vt, co.v[x], stage + T::KBYTES + (wave * T::VINS + x) * 1024);
-}
-
-// max of v over the lane pair (l, l^32): after the swap one register holds lanes 0..31 twice, the
-// other lanes 32..63 twice
-__device__ __forceinline__ float pair_max(float v)
-{
-    const uint32_t u = __float_as_uint(v);
-    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-
-__device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base)
-{
-    uint4 o;
-    o.x = pack_bf16(a[base + 0], a[base + 1]); o.y = pack_bf16(a[base + 2], a[base + 3]);
-    o.z = pack_bf16(a[base + 4], a[base + 5]); o.w = pack_bf16(a[base + 6], a[base + 7]);
-    return __builtin_bit_cast(bf16x8, o);
 }
 
 // NW: 32-row query groups per workgroup (query block = 32 NW rows).  KS: key split -- with KS = 2

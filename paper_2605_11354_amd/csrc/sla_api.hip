@@ -29,7 +29,7 @@ struct Plan {
     int BH, Nqb, Nkb, k_c, k_n, lab_pitch, s_pitch, nW;
     float sm_scale;
     bool fp8, empty;
-    size_t off_qbar, off_kbar, off_scores, off_lab, off_crit, off_hT, off_Hq, off_WT, off_Vp, total;
+    size_t off_qbar, off_kbar, off_scores, off_lab, off_crit, off_hT, off_Hq, off_WT, off_Vp, off_dWpart, total;
 };
 
 // Validates the parameter block and derives every size used downstream.
@@ -88,6 +88,7 @@ sla_status_t make_plan(const sla_params_t *p, Plan &pl)
     pl.off_Hq = carve(BH * pl.Nqb * sla::kStateElems * 2);
     pl.off_WT = carve((size_t)pl.nW * 64 * 64 * 2);
     pl.off_Vp = carve(BH * pl.Nkb * 64 * 64 * 2);
+    pl.off_dWpart = carve(pl.empty ? 0 : BH * (size_t)sla::wproj_grad_groups(pl.BH, p->N) * 64 * 64 * sizeof(float));
     pl.total = off;
     return SLA_OK;
 }
@@ -294,6 +295,26 @@ sla_status_t sla_forward(const sla_params_t *p, const void *Q, const void *K, co
                          void *workspace, size_t workspace_bytes, void *stream)
 {
     return forward_impl(p, Q, K, V, sQ, sK, sV, W_proj, O, labels, workspace, workspace_bytes, stream, nullptr, nullptr);
+}
+
+sla_status_t sla_wproj_grad(const sla_params_t *p, const void *Q, const float *sQ, const void *dO, float *dW,
+                            void *workspace, size_t workspace_bytes, void *stream)
+{
+    Plan pl;
+    sla_status_t s = make_plan(p, pl);
+    if (s != SLA_OK) return s;
+    SLA_REQ_PTR(dW);
+    hipStream_t st = (hipStream_t)stream;
+    if (pl.empty) {                      // no tokens: the gradient is zero
+        SLA_HIP(hipMemsetAsync(dW, 0, (size_t)pl.nW * 64 * 64 * sizeof(float), st));
+        return SLA_OK;
+    }
+    SLA_REQ_PTR(Q); SLA_REQ_PTR(dO);
+    if (pl.fp8) SLA_REQ_PTR(sQ);
+    if ((s = check_ws(pl, workspace, workspace_bytes)) != SLA_OK) return s;
+    SLA_HIP(sla::launch_wproj_grad(Q, sQ, pl.fp8, dO, at<void>(workspace, pl.off_Hq), p->B, p->H, p->N, p->bq, p->proj_per_head,
+                                   at<float>(workspace, pl.off_dWpart), dW, st));
+    return SLA_OK;
 }
 
 const char *sla_stage_name(int stage)

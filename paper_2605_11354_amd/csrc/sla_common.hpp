@@ -55,6 +55,23 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// max of v over the lane pair (l, l^32): after the swap one register holds lanes 0..31 twice, the
+// other lanes 32..63 twice
+__device__ __forceinline__ float pair_max(float v)
+{
+    const uint32_t u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base)
+{
+    uint4 o;
+    o.x = pack_bf16(a[base + 0], a[base + 1]); o.y = pack_bf16(a[base + 2], a[base + 3]);
+    o.z = pack_bf16(a[base + 4], a[base + 5]); o.w = pack_bf16(a[base + 6], a[base + 7]);
+    return __builtin_bit_cast(bf16x8, o);
+}
+
 // Orders LDS traffic between the lanes of one wavefront (LDS operations of a wave execute in
 // program order; this only stops the compiler from moving accesses across the point).
 __device__ __forceinline__ void wave_lds_sync()

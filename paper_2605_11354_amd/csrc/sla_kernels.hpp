@@ -52,4 +52,10 @@ hipError_t launch_attend(const void *Q, const void *K, const void *Vp,
                          int proj_per_head, int B, int H, int N, int bq, float sm_scale,
                          void *O, hipStream_t st);
 
+// dW[w] = sum over the (b,h) that use projection matrix w and their tokens of O_lin^T dO, O_lin recomputed from Q and
+// the aggregated states Hq; part is scratch of wproj_grad_groups(BH, N) * BH * 64 * 64 floats
+int wproj_grad_groups(int BH, int N);
+hipError_t launch_wproj_grad(const void *Q, const float *sQ, bool fp8, const void *dO, const void *Hq, int B, int H, int N, int bq,
+                             int proj_per_head, float *part, float *dW, hipStream_t st);
+
 }  // namespace sla

@@ -193,6 +193,51 @@ def test_forward_softmax_scale_override(oracle, name, scale):
     np.testing.assert_allclose(pc, oc["Pc"], rtol=2e-5, atol=1e-9)
 
 
+# max-abs error of dW relative to RMS(dW): the device forms O_lin from bf16 states (one rounding per key block, one
+# for the aggregate) and rounds phi(Q) and O_lin to bf16 as MFMA operands, 2^-9 relative each; measured 0.7-1.3e-2
+GRAD_TOL = 3e-2
+
+
+@pytest.mark.parametrize("name", ["c0", "c0_tail150", "c0_bq128_tail", "c3_small", "c1_small", "c4_small", "c4_bq64_tail"])
+def test_wproj_gradient(oracle, name):
+    """dL/dW_proj (Alg. 1 step 10; the only trained parameter, section 3.3) after a forward, against the oracle.
+    The device rounds phi(Q) and O_lin to bf16 like its forward does; the sum runs over all tokens of the heads
+    that share a matrix, so the error is compared with the RMS of the gradient."""
+    from paper_2605_11354_amd import binding as B
+    case = _case(name)
+    c = case.cfg
+    O, lab = case.forward()
+    g_bits = synth.to_bf16_bits(np.random.default_rng(11).standard_normal((c.B, c.H, c.N, 64)).astype(np.float32))
+    dO = G.dev_bf16(g_bits)
+    nW = c.H if c.proj_per_head else 1
+    dW = torch.full((nW, 64, 64), float("nan"), dtype=torch.float32, device="cuda")
+    B.sla_wproj_grad(case.p, case.Q, dO, dW, case.ws, case.sQ)
+    torch.cuda.synchronize()
+    dW2 = torch.empty_like(dW)
+    B.sla_wproj_grad(case.p, case.Q, dO, dW2, case.ws, case.sQ)
+    torch.cuda.synchronize()
+    assert torch.equal(dW, dW2)                                   # fixed summation order
+    g64 = (g_bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    d = case.d
+    ref = oracle.grad_wproj(case.oracle_params(oracle), d["Q"], d["K"], d["V"], lab.cpu().numpy(), g64, d["sQ"], d["sK"], d["sV"])
+    got = dW.cpu().numpy().astype(np.float64)
+    rms = float(np.sqrt(np.mean(ref ** 2)))
+    err = float(np.abs(got - ref).max())
+    print(f"{name}: max|dW - ref| = {err:.3e}, RMS(ref) = {rms:.3e}, ratio {err / max(rms, 1e-30):.3e}")
+    assert err <= GRAD_TOL * rms if rms > 0 else err == 0.0
+
+
+def test_wproj_gradient_without_marginal_blocks_is_zero():
+    from paper_2605_11354_amd import binding as B
+    case = G.Case(C0, k_crit=4, k_neg=4)
+    case.forward()
+    dO = torch.ones((1, 2, 512, 64), dtype=torch.bfloat16, device="cuda")
+    dW = torch.full((1, 64, 64), float("nan"), dtype=torch.float32, device="cuda")
+    B.sla_wproj_grad(case.p, case.Q, dO, dW, case.ws)
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(dW).item() == 0
+
+
 def test_v_ones_closed_form_on_device():
     """V == 1 gives O = 1 + column sums of W for every row (eq. 1), independent of the oracle."""
     d = dict(synth.make_inputs(C0))
@@ -277,3 +322,25 @@ def test_full_size_configuration(oracle, idx, nsample):
     got = G.gather_blocks(G.bf16_tensor_to_f64(O), ref["sel"], cfg.bq, cfg.H)
     G.assert_output(got, ref["O"], cfg.dtype, f"{cfg.name} ({len(ref['sel'])} query blocks)")
     assert torch.isfinite(O.float()).all()
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("idx", [1, 3])
+def test_wproj_gradient_full_size(oracle, idx):
+    """The gradient at the real shapes of configurations 1 and 3 (the oracle evaluates every query block)."""
+    from paper_2605_11354_amd import binding as B
+    case = G.Case(synth.CONFIGS[idx])
+    c = case.cfg
+    O, lab = case.forward()
+    g_bits = synth.to_bf16_bits(np.random.default_rng(12).standard_normal((c.B, c.H, c.N, 64)).astype(np.float32))
+    dW = torch.empty((c.H if c.proj_per_head else 1, 64, 64), dtype=torch.float32, device="cuda")
+    B.sla_wproj_grad(case.p, case.Q, G.dev_bf16(g_bits), dW, case.ws, case.sQ)
+    torch.cuda.synchronize()
+    g64 = (g_bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    d = case.d
+    ref = oracle.grad_wproj(case.oracle_params(oracle), d["Q"], d["K"], d["V"], lab.cpu().numpy(), g64)
+    got = dW.cpu().numpy().astype(np.float64)
+    rms = float(np.sqrt(np.mean(ref ** 2)))
+    err = float(np.abs(got - ref).max())
+    print(f"config {idx}: max|dW - ref| = {err:.3e}, RMS(ref) = {rms:.3e}, ratio {err / rms:.3e}")
+    assert err <= GRAD_TOL * rms

@@ -79,3 +79,17 @@ def test_workspace_size_covers_every_slice(lib):
         nqb, nkb = -(-N // bq), -(-N // 64)
         need = 16 * (nqb * 64 * 8 + nkb * 64 * 8 + nqb * nkb * 8 + nqb * nkb + (nqb + nkb) * 65 * 64 * 2)
         assert B.sla_workspace_bytes(p) >= need
+
+
+def test_wproj_grad_rejects_bad_pointers_before_any_launch(lib):
+    p = B.make_params(1, 2, 640, 64, 64, 0.1, 0.5)
+    null = C.c_void_p(0)
+    rc = lib.sla_wproj_grad(C.byref(p), C.c_void_p(16), null, C.c_void_p(16), null, C.c_void_p(256), C.c_size_t(1 << 30), null)
+    assert rc == B.SLA_ERR_INVALID_ARG and b"dW" in lib.sla_last_error()
+    rc = lib.sla_wproj_grad(C.byref(p), null, null, C.c_void_p(16), C.c_void_p(16), C.c_void_p(256), C.c_size_t(1 << 30), null)
+    assert rc == B.SLA_ERR_INVALID_ARG
+    rc = lib.sla_wproj_grad(C.byref(p), C.c_void_p(16), null, C.c_void_p(16), C.c_void_p(16), C.c_void_p(256), C.c_size_t(64), null)
+    assert rc == B.SLA_ERR_WORKSPACE
+    fp8 = B.make_params(1, 2, 640, 64, 64, 0.1, 0.5, dtype="fp8")
+    rc = lib.sla_wproj_grad(C.byref(fp8), C.c_void_p(16), null, C.c_void_p(16), C.c_void_p(16), C.c_void_p(256), C.c_size_t(1 << 30), null)
+    assert rc == B.SLA_ERR_INVALID_ARG                      # e4m3 Q needs its scales

@@ -54,33 +54,70 @@ __global__ __launch_bounds__(256) void wproj_grad_kernel(const void *__restrict_
 #pragma unroll
             for (int x = 0; x < 16; ++x) acc[a][b][x] = 0.f;
 
-    const int u1 = min((grp + 1) * upw, units);
-    for (int u = grp * upw + wave; u < u1; u += 4) {
-        const int t0 = 32 * u, i = t0 / bq;
-        const int q = t0 + l32;
-        const bool qok = q < N;
-        wave_lds_sync();                                             // the previous rows' LDS reads are done
-
-        // ---- state tile of query block i (rows 0..63 of Hq[i]) and its Z row -> LDS
+    // Raw global data of one 32-row unit, held in registers while the previous unit is processed (plain dwords:
+    // arrays of vectors are not reliably kept in registers).
+    struct Unit {
+        uint32_t h[32];      // state tile: 8 pieces of 16 bytes
+        uint32_t z[4];       // Z row: 16 bytes in each of the first eight lanes
+        uint32_t d[16];      // dO: 8 tokens x 4 channels
+        uint32_t q[FP8 ? 8 : 16];
+        float qscale;
+    };
+    auto load_unit = [&](int u, Unit &r) {
+        const int t0 = 32 * u, i = t0 / bq, q = t0 + l32;
         const uint16_t *Hi = Hq + ((size_t)bh * Nqb + i) * kStateElems;
 #pragma unroll
         for (int x = 0; x < 8; ++x) {
             const int c = lane + 64 * x, row = c >> 3, col = (c & 7) * 8;
-            *(uint4 *)(Hs + row * kGRow + col) = *(const uint4 *)(Hi + row * kD + col);
+            const uint4 v = *(const uint4 *)(Hi + row * kD + col);
+            r.h[4 * x] = v.x; r.h[4 * x + 1] = v.y; r.h[4 * x + 2] = v.z; r.h[4 * x + 3] = v.w;
         }
-        if (lane < 8) *(uint4 *)(Zs + lane * 8) = *(const uint4 *)(Hi + 64 * kD + lane * 8);
-        // ---- dO rows t0..t0+31 -> dO^T in LDS (8 tokens x 4 channels per lane and step, transposed in registers);
-        // rows past the end of the sequence are zero
+        {
+            const uint4 v = *(const uint4 *)(Hi + 64 * kD + (lane & 7) * 8);      // every lane reads it; eight store it
+            r.z[0] = v.x; r.z[1] = v.y; r.z[2] = v.z; r.z[3] = v.w;
+        }
+        const int eq = lane & 15, tg = lane >> 4;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int t = t0 + 8 * tg + k;
+            const uint2 v = *(const uint2 *)(dO + head + (size_t)min(t, N - 1) * kD + 4 * eq);
+            r.d[2 * k] = t < N ? v.x : 0u;                                        // rows past the end of the sequence are zero
+            r.d[2 * k + 1] = t < N ? v.y : 0u;
+        }
+        const int qc = min(q, N - 1);                                             // such rows are switched off through 1/(phi.Z) = 0
+        if constexpr (FP8) {
+            const uint8_t *qr = (const uint8_t *)Qp + head + (size_t)qc * kD + 32 * g;
+            const uint4 w0 = *(const uint4 *)qr, w1 = *(const uint4 *)(qr + 16);
+            r.q[0] = w0.x; r.q[1] = w0.y; r.q[2] = w0.z; r.q[3] = w0.w; r.q[4] = w1.x; r.q[5] = w1.y; r.q[6] = w1.z; r.q[7] = w1.w;
+            r.qscale = sQ[bh * Nqb + i];
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const uint4 w = *(const uint4 *)((const uint16_t *)Qp + head + (size_t)qc * kD + 16 * s + 8 * g);
+                r.q[4 * s] = w.x; r.q[4 * s + 1] = w.y; r.q[4 * s + 2] = w.z; r.q[4 * s + 3] = w.w;
+            }
+            r.qscale = 1.0f;
+        }
+    };
+
+    const int u1 = min((grp + 1) * upw, units);
+    Unit cur;
+    if (grp * upw + wave < u1) load_unit(grp * upw + wave, cur);
+    for (int u = grp * upw + wave; u < u1; u += 4) {
+        const int t0 = 32 * u;
+        const bool qok = t0 + l32 < N;
+        wave_lds_sync();                                             // the previous rows' LDS reads are done
+
+        // ---- state tile and Z row -> LDS; dO rows -> dO^T in LDS (8 tokens x 4 channels per lane, transposed in registers)
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const int c = lane + 64 * x, row = c >> 3, col = (c & 7) * 8;
+            *(uint4 *)(Hs + row * kGRow + col) = make_uint4(cur.h[4 * x], cur.h[4 * x + 1], cur.h[4 * x + 2], cur.h[4 * x + 3]);
+        }
+        if (lane < 8) *(uint4 *)(Zs + lane * 8) = make_uint4(cur.z[0], cur.z[1], cur.z[2], cur.z[3]);
         {
             const int eq = lane & 15, tg = lane >> 4;
-            uint32_t w[16];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int t = t0 + 8 * tg + k;
-                uint2 v = make_uint2(0u, 0u);
-                if (t < N) v = *(const uint2 *)(dO + head + (size_t)t * kD + 4 * eq);
-                w[2 * k] = v.x; w[2 * k + 1] = v.y;
-            }
+            const uint32_t *w = cur.d;
             uint4 c0, c1, c2, c3;                                    // channel 4 eq + c over the 8 tokens
             c0.x = __builtin_amdgcn_perm(w[2], w[0], 0x05040100);   c1.x = __builtin_amdgcn_perm(w[2], w[0], 0x07060302);
             c2.x = __builtin_amdgcn_perm(w[3], w[1], 0x05040100);   c3.x = __builtin_amdgcn_perm(w[3], w[1], 0x07060302);
@@ -100,31 +137,17 @@ __global__ __launch_bounds__(256) void wproj_grad_kernel(const void *__restrict_
         // ---- phi(Q): softmax over the 64 channels of the row (this lane holds 32, lane^32 the rest).
         // x[8s + c] is channel dcol(s) + c, the channel slot c of K-step s carries in the product below.
         float x[32];
-        if (FP8) {
-            uint4 w0 = make_uint4(0, 0, 0, 0), w1 = w0;
-            if (qok) {
-                const uint8_t *qr = (const uint8_t *)Qp + head + (size_t)q * kD + 32 * g;
-                w0 = *(const uint4 *)qr;
-                w1 = *(const uint4 *)(qr + 16);
-            }
-            const uint32_t q8[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-            const float qscale = sQ[bh * Nqb + i];
+        if constexpr (FP8) {
 #pragma unroll
             for (int w = 0; w < 8; ++w) {
-                const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(q8[w], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(q8[w], true);
-                x[4 * w + 0] = lo[0] * qscale; x[4 * w + 1] = lo[1] * qscale; x[4 * w + 2] = hi[0] * qscale; x[4 * w + 3] = hi[1] * qscale;
+                const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(cur.q[w], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(cur.q[w], true);
+                x[4 * w + 0] = lo[0] * cur.qscale; x[4 * w + 1] = lo[1] * cur.qscale; x[4 * w + 2] = hi[0] * cur.qscale; x[4 * w + 3] = hi[1] * cur.qscale;
             }
         } else {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                uint4 w = make_uint4(0, 0, 0, 0);
-                if (qok) w = *(const uint4 *)((const uint16_t *)Qp + head + (size_t)q * kD + 16 * s + 8 * g);
-                x[8 * s + 0] = bf16_lo(w.x); x[8 * s + 1] = bf16_hi(w.x);
-                x[8 * s + 2] = bf16_lo(w.y); x[8 * s + 3] = bf16_hi(w.y);
-                x[8 * s + 4] = bf16_lo(w.z); x[8 * s + 5] = bf16_hi(w.z);
-                x[8 * s + 6] = bf16_lo(w.w); x[8 * s + 7] = bf16_hi(w.w);
-            }
+            for (int w = 0; w < 16; ++w) { x[2 * w] = bf16_lo(cur.q[w]); x[2 * w + 1] = bf16_hi(cur.q[w]); }
         }
+        if (u + 4 < u1) load_unit(u + 4, cur);                       // the next unit's loads fly while this one is processed
         float mx = x[0];
 #pragma unroll
         for (int d = 1; d < 32; ++d) mx = fmaxf(mx, x[d]);

@@ -16,7 +16,8 @@
  * Q/K, giving three classes (critical / marginal / negligible); the sparse branch
  * (steps 4-5) runs over the tokens of critical blocks, the linear branch (steps 7-9) over
  * the tokens of marginal blocks, negligible blocks are skipped.  phi is the softmax over
- * the head dimension (the benchmark configurations fix this instead of ELU+1).
+ * the head dimension (the benchmark configurations fix this) or, selectable, the ELU(x)+1 of
+ * Alg. 1 step 6.
  *
  * Readings where the paper is silent (all listed in the design notes):
  *   - masked entries are excluded from the softmax (-inf), not multiplied by 0;
@@ -48,6 +49,7 @@ typedef struct {
     int32_t dtype;             /* 0: bf16 bit patterns (uint16); 1: E4M3 codes (uint8) + fp32 block scales */
     int32_t proj_per_head;     /* 0: W [D,D]; 1: W [H,D,D] */
     double  sm_scale;          /* 1/sqrt(D) normally */
+    int32_t phi;               /* feature map of the linear branch: 0 softmax over the channels, 1 ELU(x)+1 (Alg. 1 step 6) */
 } sla_oracle_params;
 
 #define DH 64
@@ -158,13 +160,19 @@ static void classify_row(const double *s, int Nkb, int k_c, int k_n, int8_t *lab
     free(o);
 }
 
-/* ---- feature map (Alg. 1 step 6 with phi = softmax over the 64 channels) --------------- */
+/* ---- feature map (Alg. 1 step 6): softmax over the 64 channels (the benchmark configurations),
+ * or ELU(x)+1 elementwise as the algorithm prints it: x+1 for x > 0, exp(x) otherwise ------------ */
 static void phi_softmax(const double *x, double *out)
 {
     double m = x[0], sum = 0.0;
     for (int d = 1; d < DH; ++d) if (x[d] > m) m = x[d];
     for (int d = 0; d < DH; ++d) { out[d] = exp(x[d] - m); sum += out[d]; }
     for (int d = 0; d < DH; ++d) out[d] /= sum;
+}
+static void phi_map(int kind, const double *x, double *out)
+{
+    if (kind == 0) { phi_softmax(x, out); return; }
+    for (int d = 0; d < DH; ++d) out[d] = x[d] > 0.0 ? x[d] + 1.0 : exp(x[d]);
 }
 
 /* ---- step 5: sparse branch for one query row (Alg. 1 steps 2, 4, 5 over critical tokens) */
@@ -201,13 +209,13 @@ static void sparse_row(const double *q, const double *K, const double *V, int N,
 }
 
 /* ---- step 6a: per-key-block linear states (Alg. 1 steps 7-8 restricted to one block) --- */
-static void block_state(const double *K, const double *V, int t0, int t1, double *h /*[64][64]*/, double *z /*[64]*/)
+static void block_state(int phi, const double *K, const double *V, int t0, int t1, double *h /*[64][64]*/, double *z /*[64]*/)
 {
     double f[DH];
     memset(h, 0, sizeof(double) * DH * DH);
     memset(z, 0, sizeof(double) * DH);
     for (int t = t0; t < t1; ++t) {
-        phi_softmax(K + (size_t)t * DH, f);
+        phi_map(phi, K + (size_t)t * DH, f);
         for (int d = 0; d < DH; ++d) {
             z[d] += f[d];
             for (int e = 0; e < DH; ++e) h[d * DH + e] += f[d] * V[(size_t)t * DH + e];
@@ -262,7 +270,7 @@ int sla_oracle_states_head(const sla_oracle_params *p, const void *K, const void
     #pragma omp parallel for schedule(dynamic, 4)
     for (int j = 0; j < Nkb; ++j) {
         int t1 = (j + 1) * p->bk < N ? (j + 1) * p->bk : N;
-        block_state(Kd, Vd, j * p->bk, t1, h + (size_t)j * DH * DH, z + (size_t)j * DH);
+        block_state(p->phi, Kd, Vd, j * p->bk, t1, h + (size_t)j * DH * DH, z + (size_t)j * DH);
     }
     free(Kd); free(Vd);
     return 0;
@@ -297,7 +305,7 @@ int sla_oracle_attend(const sla_oracle_params *p, const void *Q, const void *K, 
         #pragma omp parallel for schedule(dynamic, 4)
         for (int j = 0; j < Nkb; ++j) {
             int t1 = (j + 1) * bk < N ? (j + 1) * bk : N;
-            block_state(Kd, Vd, j * bk, t1, h + (size_t)j * DH * DH, z + (size_t)j * DH);
+            block_state(p->phi, Kd, Vd, j * bk, t1, h + (size_t)j * DH * DH, z + (size_t)j * DH);
         }
         #pragma omp parallel for schedule(dynamic, 1)
         for (int s = 0; s < n_sel; ++s) {
@@ -324,7 +332,7 @@ int sla_oracle_attend(const sla_oracle_params *p, const void *Q, const void *K, 
                 for (int e = 0; e < DH; ++e) olin[e] = 0.0;
                 if (n_marg > 0) {
                     double den = 0.0;
-                    phi_softmax(q, f);
+                    phi_map(p->phi, q, f);
                     for (int d = 0; d < DH; ++d) {
                         den += f[d] * Zi[d];
                         for (int e = 0; e < DH; ++e) olin[e] += f[d] * Hi[d * DH + e];

@@ -19,7 +19,7 @@ _lib = None
 class Params(C.Structure):
     _fields_ = [("B", C.c_int32), ("H", C.c_int32), ("N", C.c_int32), ("D", C.c_int32),
                 ("bq", C.c_int32), ("bk", C.c_int32), ("k_crit", C.c_int32), ("k_neg", C.c_int32),
-                ("dtype", C.c_int32), ("proj_per_head", C.c_int32), ("sm_scale", C.c_double)]
+                ("dtype", C.c_int32), ("proj_per_head", C.c_int32), ("sm_scale", C.c_double), ("phi", C.c_int32)]
 
 
 def build(force: bool = False) -> str:
@@ -56,9 +56,11 @@ def counts(crit_frac: float, neg_frac: float, Nkb: int):
     return kc.value, kn.value
 
 
-def make_params(B, H, N, bq, bk, k_crit, k_neg, dtype="bf16", proj_per_head=False, sm_scale=None, D=64):
+def make_params(B, H, N, bq, bk, k_crit, k_neg, dtype="bf16", proj_per_head=False, sm_scale=None, D=64, phi="softmax"):
+    """phi: feature map of the linear branch, "softmax" (over the channels) or "elu1" (ELU(x)+1, Alg. 1 step 6)."""
     return Params(B, H, N, D, bq, bk, k_crit, k_neg, 0 if dtype == "bf16" else 1,
-                  1 if proj_per_head else 0, (1.0 / np.sqrt(D)) if sm_scale is None else sm_scale)
+                  1 if proj_per_head else 0, (1.0 / np.sqrt(D)) if sm_scale is None else sm_scale,
+                  {"softmax": 0, "elu1": 1}[phi])
 
 
 def _chk(x, dt):

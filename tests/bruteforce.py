@@ -24,9 +24,17 @@ def phi_softmax(X):
     return E / E.sum(axis=-1, keepdims=True)
 
 
-def linear_attention(Q, K, V, W):
-    """Alg. 1 steps 6-10 with O_sparse = 0 and phi = softmax over channels, one head."""
-    fq, fk = phi_softmax(Q), phi_softmax(K)
+def phi_elu1(X):
+    """ELU(x) + 1 as Alg. 1 step 6 prints it: x + 1 where x > 0, exp(x) elsewhere."""
+    return np.where(X > 0, X + 1.0, np.exp(np.minimum(X, 0.0)))
+
+
+PHI = {"softmax": phi_softmax, "elu1": phi_elu1}
+
+
+def linear_attention(Q, K, V, W, phi="softmax"):
+    """Alg. 1 steps 6-10 with O_sparse = 0, one head."""
+    fq, fk = PHI[phi](Q), PHI[phi](K)
     T = fk.T @ V                      # [D, D]
     z = fk.sum(axis=0)                # [D]
     return ((fq @ T) / (fq @ z)[:, None]) @ W
@@ -42,7 +50,7 @@ def rank_labels(s_row, k_c, k_n):
     return lab
 
 
-def sla_tokenlevel(Q, K, V, W, labels_row_of_block, bq, bk, scale):
+def sla_tokenlevel(Q, K, V, W, labels_row_of_block, bq, bk, scale, phi="softmax"):
     """SLA for one head from given labels [Nqb, Nkb], written with dense token masks."""
     N = Q.shape[0]
     qb = np.arange(N) // bq
@@ -57,7 +65,7 @@ def sla_tokenlevel(Q, K, V, W, labels_row_of_block, bq, bk, scale):
     P = np.where(crit, np.exp(Sm - m[:, None]), 0.0)
     den = P.sum(axis=1)
     out[has] = (P[has] / den[has, None]) @ V
-    fq, fk = phi_softmax(Q), phi_softmax(K)
+    fq, fk = PHI[phi](Q), PHI[phi](K)
     A = np.where(L == 1, fq @ fk.T, 0.0)        # phi(q).phi(k) on marginal pairs
     dl = A.sum(axis=1)
     hasm = (L == 1).any(axis=1)

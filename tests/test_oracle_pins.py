@@ -343,3 +343,32 @@ def test_wproj_gradient_closed_form_for_constant_values(oracle):
     lab0 = oracle.classify(po0, d["Q"], d["K"])["labels"]
     assert not (lab0 == 1).any()
     assert np.all(oracle.grad_wproj(po0, d["Q"], d["K"], d["V"], lab0, G) == 0.0)
+
+
+@pytest.mark.parametrize("N,bq,bk,kc,kn", [(512, 64, 64, 0, 0), (700, 128, 64, 2, 5), (333, 64, 64, 3, 0)])
+def test_elu_feature_map_matches_tokenlevel_form(oracle, N, bq, bk, kc, kn):
+    """phi = ELU(x)+1 as Alg. 1 step 6 prints it: all-marginal equals token-level linear attention (steps 6-10),
+    mixed labels equal the dense-mask token-level form; the sparse branch does not depend on phi."""
+    rng = np.random.default_rng(7)
+    Q, K, V, W = _small(rng, N=N)
+    p = oracle.make_params(1, 2, N, bq, bk, kc, kn, proj_per_head=True, phi="elu1")
+    ps = oracle.make_params(1, 2, N, bq, bk, kc, kn, proj_per_head=True)
+    r = oracle.forward(p, Q, K, V, W, want_parts=True)
+    rs = oracle.forward(ps, Q, K, V, W, want_parts=True)
+    assert np.array_equal(r["labels"], rs["labels"]) and np.array_equal(r["O_sparse"], rs["O_sparse"])
+    if kc == 0 and kn == 0:
+        assert np.abs(r["O_lin"] - rs["O_lin"]).max() > 1e-3          # the two feature maps do differ
+    for h in range(2):
+        q, k, v = (bf.bf16_bits_to_f64(x[0, h]) for x in (Q, K, V))
+        Wd = bf.bf16_bits_to_f64(W[h])
+        O, Osp, Olin = bf.sla_tokenlevel(q, k, v, Wd, r["labels"][0, h], bq, bk, 0.125, phi="elu1")
+        np.testing.assert_allclose(r["O_lin"][0, h], Olin, rtol=0, atol=1e-11)
+        np.testing.assert_allclose(r["O"][0, h], O, rtol=0, atol=1e-11)
+        if kc == 0 and kn == 0:
+            np.testing.assert_allclose(r["O"][0, h], bf.linear_attention(q, k, v, Wd, phi="elu1"), rtol=0, atol=1e-11)
+
+
+def test_elu_feature_map_values():
+    """ELU(x)+1: 1 at 0, x+1 above, exp(x) below (continuous, positive)."""
+    x = np.array([-30.0, -1.0, -0.0, 0.0, 0.5, 3.0])
+    np.testing.assert_allclose(bf.phi_elu1(x), [np.exp(-30.0), np.exp(-1.0), 1.0, 1.0, 1.5, 4.0], rtol=1e-15)

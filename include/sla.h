@@ -10,7 +10,7 @@
  *      "marginal" (Alg. 1 step 3, TopKMask, at block level).
  *   2. Sparse branch (Alg. 1 steps 4-5): softmax(Q K^T * sm_scale) V restricted to the
  *      tokens of the critical blocks (masked-out keys are excluded from the softmax).
- *   3. Linear branch (Alg. 1 steps 6-9) with phi = softmax over the head dimension:
+ *   3. Linear branch (Alg. 1 steps 6-9) with the feature map phi (sla_phi_t below):
  *      h_j = phi(K_j)^T V_j, z_j = sum_t phi(K_j,t) per key block, summed over the marginal
  *      blocks of a query block: O_lin = phi(Q) H_i / (phi(Q) . Z_i); 0 if there is none.
  *   4. Combine (Alg. 1 step 10): O = O_sparse + O_lin W_proj.
@@ -54,7 +54,9 @@ typedef enum {
 } sla_status_t;
 
 typedef enum { SLA_BF16 = 0, SLA_FP8_E4M3 = 1 } sla_dtype_t;
-typedef enum { SLA_PHI_SOFTMAX = 0 } sla_phi_t;   /* feature map of Alg. 1 step 6: softmax over D */
+/* feature map phi of the linear branch (Alg. 1 step 6): softmax over the D channels of the row (the benchmark
+ * configurations), or ELU(x)+1 elementwise as the algorithm prints it (x+1 for x > 0, exp(x) otherwise) */
+typedef enum { SLA_PHI_SOFTMAX = 0, SLA_PHI_ELU1 = 1 } sla_phi_t;
 
 typedef struct {
     int32_t B, H, N, D;          /* batch, heads, tokens per (b,h), head dim (must be 64) */

@@ -61,9 +61,10 @@ def lib() -> C.CDLL:
 
 
 def make_params(B, H, N, bq, bk, crit_frac=0.0, neg_frac=0.0, k_crit=-1, k_neg=-1, dtype="bf16",
-                proj_per_head=False, sm_scale=0.0, D=64) -> SlaParams:
+                proj_per_head=False, sm_scale=0.0, D=64, phi="softmax") -> SlaParams:
     return SlaParams(B, H, N, D, bq, bk, crit_frac, neg_frac, k_crit, k_neg,
-                     SLA_BF16 if dtype == "bf16" else SLA_FP8_E4M3, 0, 1 if proj_per_head else 0, sm_scale)
+                     SLA_BF16 if dtype == "bf16" else SLA_FP8_E4M3, {"softmax": 0, "elu1": 1}[phi],
+                     1 if proj_per_head else 0, sm_scale)
 
 
 def _check(status: int, where: str):

@@ -141,7 +141,7 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
     const void *__restrict__ Qp, const void *__restrict__ Kp, const uint16_t *__restrict__ Vp,
     const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV,
     const int32_t *__restrict__ crit_idx, int k_c, const uint16_t *__restrict__ Hq, const uint16_t *__restrict__ WT,
-    int proj_per_head, int H, int N, int Nqb, int Nkb, long total, float c_exp, uint16_t *__restrict__ O)
+    int proj_per_head, int phi, int H, int N, int Nqb, int Nkb, long total, float c_exp, uint16_t *__restrict__ O)
 {
     constexpr int NWAVES = NW * KS;
     using T = Tile<NWAVES, FP8>;
@@ -416,15 +416,21 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
                 x[8 * s + 6] = bf16_lo(w.w); x[8 * s + 7] = bf16_hi(w.w);
             }
         }
-        float mx = x[0];
+        float inv = 1.0f;
+        if (phi == 0) {
+            float mx = x[0];
 #pragma unroll
-        for (int d = 1; d < 32; ++d) mx = fmaxf(mx, x[d]);
-        mx = pair_max(mx);
-        float sum = 0.f;
+            for (int d = 1; d < 32; ++d) mx = fmaxf(mx, x[d]);
+            mx = pair_max(mx);
+            float sum = 0.f;
 #pragma unroll
-        for (int d = 0; d < 32; ++d) { x[d] = fast_exp2((x[d] - mx) * kLog2e); sum += x[d]; }
-        sum += xchg32(sum);
-        const float inv = 1.0f / sum;
+            for (int d = 0; d < 32; ++d) { x[d] = fast_exp2((x[d] - mx) * kLog2e); sum += x[d]; }
+            sum += xchg32(sum);
+            inv = 1.0f / sum;
+        } else {                                               // ELU(x)+1, elementwise
+#pragma unroll
+            for (int d = 0; d < 32; ++d) x[d] = x[d] > 0.f ? x[d] + 1.0f : fast_exp2(x[d] * kLog2e);
+        }
         bf16x8 fq[4];
         float den = 0.f;
 #pragma unroll
@@ -512,11 +518,11 @@ hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st)
 
 template <int NW, int KS, bool FP8, int STG>
 static hipError_t launch_attend_t(const void *Q, const void *K, const void *Vp, const float *sQ, const float *sK, const float *sV,
-                                  const int32_t *crit_idx, int k_c, const void *Hq, const void *WT, int proj_per_head,
+                                  const int32_t *crit_idx, int k_c, const void *Hq, const void *WT, int proj_per_head, int phi,
                                   int H, int N, int Nqb, int Nkb, long total, float c_exp, void *O, hipStream_t st)
 {
     attend_kernel<NW, KS, FP8, STG><<<(unsigned)xcd_grid(total), 64 * NW * KS, 0, st>>>(Q, K, (const uint16_t *)Vp, sQ, sK, sV, crit_idx, k_c, (const uint16_t *)Hq,
-                                                                          (const uint16_t *)WT, proj_per_head, H, N, Nqb, Nkb,
+                                                                          (const uint16_t *)WT, proj_per_head, phi, H, N, Nqb, Nkb,
                                                                           total, c_exp, (uint16_t *)O);
     return hipGetLastError();
 }
@@ -524,13 +530,13 @@ static hipError_t launch_attend_t(const void *Q, const void *K, const void *Vp, 
 hipError_t launch_attend(const void *Q, const void *K, const void *Vp,
                          const float *sQ, const float *sK, const float *sV, bool fp8,
                          const int32_t *crit_idx, int k_c, const void *Hq, const void *WT,
-                         int proj_per_head, int B, int H, int N, int bq, float sm_scale,
+                         int proj_per_head, int phi, int B, int H, int N, int bq, float sm_scale,
                          void *O, hipStream_t st)
 {
     const int Nqb = (N + bq - 1) / bq, Nkb = (N + kBK - 1) / kBK;
     const long total = (long)B * H * Nqb;
     const float c_exp = sm_scale * kLog2e;
-#define SLA_ATT(NW, KS, F8, STG) return launch_attend_t<NW, KS, F8, STG>(Q, K, Vp, sQ, sK, sV, crit_idx, k_c, Hq, WT, proj_per_head, H, N, Nqb, Nkb, total, c_exp, O, st)
+#define SLA_ATT(NW, KS, F8, STG) return launch_attend_t<NW, KS, F8, STG>(Q, K, Vp, sQ, sK, sV, crit_idx, k_c, Hq, WT, proj_per_head, phi, H, N, Nqb, Nkb, total, c_exp, O, st)
     if (bq == 128) { if (fp8) SLA_ATT(4, 1, true, 3); else SLA_ATT(4, 1, false, 3); }
     // 64-row query blocks: two query groups x two key halves, so a workgroup still has four waves;
     // with very few critical blocks per row the merge of the halves costs more than it hides

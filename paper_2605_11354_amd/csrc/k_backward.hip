@@ -31,7 +31,7 @@ constexpr float kLog2eB = 1.4426950408889634f;
 template <bool FP8>
 __global__ __launch_bounds__(256) void wproj_grad_kernel(const void *__restrict__ Qp, const float *__restrict__ sQ,
                                                          const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Hq,
-                                                         int N, int bq, int Nqb, int units, int upw, int groups,
+                                                         int N, int bq, int Nqb, int units, int upw, int groups, int phi,
                                                          float *__restrict__ part)
 {
     static_assert(3 * 16384 <= 4 * kWaveLds, "three parked accumulators must fit the workgroup's LDS");
@@ -148,15 +148,21 @@ __global__ __launch_bounds__(256) void wproj_grad_kernel(const void *__restrict_
             for (int w = 0; w < 16; ++w) { x[2 * w] = bf16_lo(cur.q[w]); x[2 * w + 1] = bf16_hi(cur.q[w]); }
         }
         if (u + 4 < u1) load_unit(u + 4, cur);                       // the next unit's loads fly while this one is processed
-        float mx = x[0];
+        float inv = 1.0f;
+        if (phi == 0) {
+            float mx = x[0];
 #pragma unroll
-        for (int d = 1; d < 32; ++d) mx = fmaxf(mx, x[d]);
-        mx = pair_max(mx);
-        float sum = 0.f;
+            for (int d = 1; d < 32; ++d) mx = fmaxf(mx, x[d]);
+            mx = pair_max(mx);
+            float sum = 0.f;
 #pragma unroll
-        for (int d = 0; d < 32; ++d) { x[d] = fast_exp2((x[d] - mx) * kLog2eB); sum += x[d]; }
-        sum += xchg32(sum);
-        const float inv = 1.0f / sum;
+            for (int d = 0; d < 32; ++d) { x[d] = fast_exp2((x[d] - mx) * kLog2eB); sum += x[d]; }
+            sum += xchg32(sum);
+            inv = 1.0f / sum;
+        } else {                                                     // ELU(x)+1, elementwise
+#pragma unroll
+            for (int d = 0; d < 32; ++d) x[d] = x[d] > 0.f ? x[d] + 1.0f : fast_exp2(x[d] * kLog2eB);
+        }
         wave_lds_sync();                                             // the tiles staged above are visible
         bf16x8 fq[4];
         float den = 0.f;
@@ -277,13 +283,13 @@ int wproj_grad_groups(int BH, int N)
 }
 
 hipError_t launch_wproj_grad(const void *Q, const float *sQ, bool fp8, const void *dO, const void *Hq, int B, int H, int N, int bq,
-                             int proj_per_head, float *part, float *dW, hipStream_t st)
+                             int proj_per_head, int phi, float *part, float *dW, hipStream_t st)
 {
     const int BH = B * H, Nqb = (N + bq - 1) / bq, units = (N + 31) / 32;
     const int groups = wproj_grad_groups(BH, N), upw = (units + groups - 1) / groups;
     const unsigned grid = (unsigned)BH * groups;
-    if (fp8) wproj_grad_kernel<true><<<grid, 256, 0, st>>>(Q, sQ, (const uint16_t *)dO, (const uint16_t *)Hq, N, bq, Nqb, units, upw, groups, part);
-    else     wproj_grad_kernel<false><<<grid, 256, 0, st>>>(Q, sQ, (const uint16_t *)dO, (const uint16_t *)Hq, N, bq, Nqb, units, upw, groups, part);
+    if (fp8) wproj_grad_kernel<true><<<grid, 256, 0, st>>>(Q, sQ, (const uint16_t *)dO, (const uint16_t *)Hq, N, bq, Nqb, units, upw, groups, phi, part);
+    else     wproj_grad_kernel<false><<<grid, 256, 0, st>>>(Q, sQ, (const uint16_t *)dO, (const uint16_t *)Hq, N, bq, Nqb, units, upw, groups, phi, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     wproj_grad_reduce_kernel<<<dim3(kD * kD / 256, proj_per_head ? H : 1), 256, 0, st>>>(part, B, H, groups, proj_per_head, dW);

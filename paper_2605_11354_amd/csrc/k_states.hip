@@ -1,5 +1,5 @@
 // Per-key-block linear-attention states (Alg. 1 steps 6-8 of the paper restricted to one
-// key block, phi = softmax over the head dimension):
+// key block; phi = softmax over the head dimension, or the ELU(x)+1 the algorithm prints):
 //     h_j = phi(K_j)^T V_j   (64 x 64),   z_j = sum_t phi(K_j,t)   (64)
 // written as bf16 hT[j][e][d] = h_j[d][e] (rows 0..63) and hT[j][64][d] = z_j[d].
 //
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(64 * kWavesPerWG) __attribute__((amdgpu_waves_per_e
                                                                   const float *__restrict__ sK, const float *__restrict__ sV,
                                                                   int N, int Nkb, long nblocks, int per_wave,
                                                                   uint16_t *__restrict__ hT, uint16_t *__restrict__ Vp,
-                                                                  double *__restrict__ kbar, unsigned state_wgs,
+                                                                  double *__restrict__ kbar, int phi, unsigned state_wgs,
                                                                   const uint16_t *__restrict__ W, uint16_t *__restrict__ WT)
 {
     if (blockIdx.x >= state_wgs) {     // workgroups past the states grid each lay out one projection matrix for the attention kernel
@@ -217,16 +217,26 @@ __global__ __launch_bounds__(64 * kWavesPerWG) __attribute__((amdgpu_waves_per_e
             x[c * 8 + 4] = bf16_lo(w.z); x[c * 8 + 5] = bf16_hi(w.z);
             x[c * 8 + 6] = bf16_lo(w.w); x[c * 8 + 7] = bf16_hi(w.w);
         }
-        float mx = x[0];
-#pragma unroll
-        for (int d = 1; d < 64; ++d) mx = fmaxf(mx, x[d]);
-        // exp(s*(x - mx)) = exp2(x*c - mx*c), c = s*log2(e); s = 1 for bf16 inputs, the K scale for e4m3
+        // phi = 0: softmax over the 64 channels; phi = 1: ELU(x)+1 elementwise (x+1 above 0, exp(x) below).
+        // s is 1 for bf16 inputs and the K block scale for e4m3.
         const float cexp = (FP8 ? sK[blk] : 1.0f) * 1.4426950408889634f;
-        const float mc = mx * cexp;
-        float sum = 0.f;
+        float inv;
+        if (phi == 0) {
+            float mx = x[0];
 #pragma unroll
-        for (int d = 0; d < 64; ++d) { x[d] = fast_exp2(fmaf(x[d], cexp, -mc)); sum += x[d]; }
-        const float inv = lane < valid ? 1.0f / sum : 0.0f;     // rows past the sequence end contribute nothing
+            for (int d = 1; d < 64; ++d) mx = fmaxf(mx, x[d]);
+            // exp(s*(x - mx)) = exp2(x*c - mx*c), c = s*log2(e)
+            const float mc = mx * cexp;
+            float sum = 0.f;
+#pragma unroll
+            for (int d = 0; d < 64; ++d) { x[d] = fast_exp2(fmaf(x[d], cexp, -mc)); sum += x[d]; }
+            inv = lane < valid ? 1.0f / sum : 0.0f;             // rows past the sequence end contribute nothing
+        } else {
+            const float sc = FP8 ? sK[blk] : 1.0f;
+#pragma unroll
+            for (int d = 0; d < 64; ++d) x[d] = x[d] > 0.f ? fmaf(x[d], sc, 1.0f) : fast_exp2(x[d] * cexp);
+            inv = lane < valid ? 1.0f : 0.0f;
+        }
         wave_lds_sync();                                        // all rows are in registers: Ks may be overwritten
 #pragma unroll
         for (int d = 0; d < 64; ++d) Ks[d * kLdsRow + lane] = (uint16_t)(pack_bf16(x[d] * inv, 0.f) & 0xFFFFu);
@@ -301,7 +311,7 @@ __global__ __launch_bounds__(64 * kWavesPerWG) __attribute__((amdgpu_waves_per_e
 }
 
 hipError_t launch_states(const void *K, const void *V, const float *sK, const float *sV, bool fp8,
-                         int BH, int N, void *hT, void *Vp, double *kbar, const void *W, int nW, void *WT, hipStream_t st)
+                         int BH, int N, void *hT, void *Vp, double *kbar, int phi, const void *W, int nW, void *WT, hipStream_t st)
 {
     const int Nkb = (N + kBK - 1) / kBK;
     const long nblocks = (long)BH * Nkb;
@@ -311,8 +321,8 @@ hipError_t launch_states(const void *K, const void *V, const float *sK, const fl
     const long waves = (nblocks + per_wave - 1) / per_wave;
     const unsigned grid = (unsigned)((waves + kWavesPerWG - 1) / kWavesPerWG);
     const unsigned extra = W != nullptr ? (unsigned)nW : 0u;
-    if (fp8) states_kernel<true><<<grid + extra, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, kbar, grid, (const uint16_t *)W, (uint16_t *)WT);
-    else     states_kernel<false><<<grid + extra, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, kbar, grid, (const uint16_t *)W, (uint16_t *)WT);
+    if (fp8) states_kernel<true><<<grid + extra, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, kbar, phi, grid, (const uint16_t *)W, (uint16_t *)WT);
+    else     states_kernel<false><<<grid + extra, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, kbar, phi, grid, (const uint16_t *)W, (uint16_t *)WT);
     return hipGetLastError();
 }
 

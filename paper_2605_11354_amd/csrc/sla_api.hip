@@ -41,7 +41,7 @@ sla_status_t make_plan(const sla_params_t *p, Plan &pl)
     if (p->bk != 64) return fail(SLA_ERR_UNSUPPORTED, "key block bk = %d; only 64 is implemented", p->bk);
     if (p->bq != 64 && p->bq != 128) return fail(SLA_ERR_UNSUPPORTED, "query block bq = %d; only 64 and 128 are implemented", p->bq);
     if (p->dtype != SLA_BF16 && p->dtype != SLA_FP8_E4M3) return fail(SLA_ERR_INVALID_ARG, "unknown dtype %d", p->dtype);
-    if (p->phi != SLA_PHI_SOFTMAX) return fail(SLA_ERR_UNSUPPORTED, "feature map %d; only softmax over D is implemented", p->phi);
+    if (p->phi != SLA_PHI_SOFTMAX && p->phi != SLA_PHI_ELU1) return fail(SLA_ERR_INVALID_ARG, "unknown feature map %d", p->phi);
     if (p->proj_per_head != 0 && p->proj_per_head != 1) return fail(SLA_ERR_INVALID_ARG, "proj_per_head must be 0 or 1");
     if (!(p->sm_scale >= 0.f) || !std::isfinite(p->sm_scale)) return fail(SLA_ERR_INVALID_ARG, "sm_scale must be finite and >= 0");
     memset(&pl, 0, sizeof pl);
@@ -212,7 +212,7 @@ sla_status_t sla_linear_states(const sla_params_t *p, const void *K, const void 
     if (pl.empty) return SLA_OK;
     SLA_REQ_PTR(K); SLA_REQ_PTR(V); SLA_REQ_PTR(hT);
     if (pl.fp8) { SLA_REQ_PTR(sK); SLA_REQ_PTR(sV); }
-    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, hT, nullptr, nullptr, nullptr, 0, nullptr, (hipStream_t)stream));
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, hT, nullptr, nullptr, p->phi, nullptr, 0, nullptr, (hipStream_t)stream));
     return SLA_OK;
 }
 
@@ -252,9 +252,9 @@ sla_status_t sla_sparse_combine(const sla_params_t *p, const void *Q, const void
                                        at<uint64_t>(workspace, pl.off_lab), pl.lab_pitch, at<int32_t>(workspace, pl.off_crit), st));
     if (Hq) SLA_HIP(sla::launch_transpose_w(W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
     // the attention kernel reads V as transposed tiles; the states pass produces them (its states go to the workspace)
-    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp), nullptr, nullptr, 0, nullptr, st));
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp), nullptr, p->phi, nullptr, 0, nullptr, st));
     SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), sQ, sK, sV, pl.fp8, at<int32_t>(workspace, pl.off_crit), pl.k_c, Hq,
-                               at<void>(workspace, pl.off_WT), p->proj_per_head, p->B, p->H, p->N, p->bq, pl.sm_scale, O, st));
+                               at<void>(workspace, pl.off_WT), p->proj_per_head, p->phi, p->B, p->H, p->N, p->bq, pl.sm_scale, O, st));
     return SLA_OK;
 }
 
@@ -277,14 +277,14 @@ static sla_status_t forward_impl(const sla_params_t *p, const void *Q, const voi
     SLA_HIP(mark(1));     // states + V^T tiles + block means of K: the one pass over K and V besides the attention kernel;
                           // a few extra workgroups of the same launch lay out W_proj for the attention epilogue
     SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp),
-                               at<double>(workspace, pl.off_kbar), W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
+                               at<double>(workspace, pl.off_kbar), p->phi, W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
     if ((s = run_classify(p, pl, Q, K, sQ, sK, labels, nullptr, nullptr, nullptr, nullptr, nullptr, workspace, st, ev, true)) != SLA_OK) return s;
     SLA_HIP(mark(4));
     SLA_HIP(sla::launch_aggregate(at<uint64_t>(workspace, pl.off_lab), pl.lab_pitch, at<void>(workspace, pl.off_hT), pl.BH, pl.Nqb,
                                   pl.Nkb, at<void>(workspace, pl.off_Hq), st));
     SLA_HIP(mark(5));
     SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), sQ, sK, sV, pl.fp8, at<int32_t>(workspace, pl.off_crit), pl.k_c,
-                               at<void>(workspace, pl.off_Hq), at<void>(workspace, pl.off_WT), p->proj_per_head, p->B, p->H,
+                               at<void>(workspace, pl.off_Hq), at<void>(workspace, pl.off_WT), p->proj_per_head, p->phi, p->B, p->H,
                                p->N, p->bq, pl.sm_scale, O, st));
     SLA_HIP(mark(6));
     return SLA_OK;
@@ -312,7 +312,7 @@ sla_status_t sla_wproj_grad(const sla_params_t *p, const void *Q, const float *s
     SLA_REQ_PTR(Q); SLA_REQ_PTR(dO);
     if (pl.fp8) SLA_REQ_PTR(sQ);
     if ((s = check_ws(pl, workspace, workspace_bytes)) != SLA_OK) return s;
-    SLA_HIP(sla::launch_wproj_grad(Q, sQ, pl.fp8, dO, at<void>(workspace, pl.off_Hq), p->B, p->H, p->N, p->bq, p->proj_per_head,
+    SLA_HIP(sla::launch_wproj_grad(Q, sQ, pl.fp8, dO, at<void>(workspace, pl.off_Hq), p->B, p->H, p->N, p->bq, p->proj_per_head, p->phi,
                                    at<float>(workspace, pl.off_dWpart), dW, st));
     return SLA_OK;
 }

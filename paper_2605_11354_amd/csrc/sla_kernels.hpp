@@ -31,12 +31,13 @@ hipError_t launch_classify_fused(const void *Q, const float *sQ, bool fp8, const
 hipError_t launch_labels_prepare(const int8_t *lab_dense, long rows, int Nkb, int k_c,
                                  uint64_t *mbits, int lab_pitch, int32_t *crit_idx, hipStream_t st);
 
+// phi (here and below): feature map of the linear branch, 0 = softmax over the channels, 1 = ELU(x)+1.
 // per-key-block states: hT [BH,Nkb,65,64] bf16; optionally also Vp [BH,Nkb,64,64] bf16, the
 // transposed, key-permuted V tiles the attention kernel reads, and kbar [BH,Nkb,64] fp64, the
 // block means of K (same arithmetic as launch_pool); NULL skips either.  With W != NULL the launch also
 // does the work of launch_transpose_w(W, nW, WT) in nW extra workgroups.
 hipError_t launch_states(const void *K, const void *V, const float *sK, const float *sV, bool fp8,
-                         int BH, int N, void *hT, void *Vp, double *kbar, const void *W, int nW, void *WT, hipStream_t st);
+                         int BH, int N, void *hT, void *Vp, double *kbar, int phi, const void *W, int nW, void *WT, hipStream_t st);
 
 // Hq[bh][i][:] = sum over j with lab_pad[bh][i][j] == 1 of hT[bh][j][:]   (bf16 MFMA, fp32 accumulate)
 hipError_t launch_aggregate(const uint64_t *mbits, int lab_pitch, const void *hT, int BH, int Nqb,
@@ -49,13 +50,13 @@ hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st);
 hipError_t launch_attend(const void *Q, const void *K, const void *Vp,
                          const float *sQ, const float *sK, const float *sV, bool fp8,
                          const int32_t *crit_idx, int k_c, const void *Hq, const void *WT,
-                         int proj_per_head, int B, int H, int N, int bq, float sm_scale,
+                         int proj_per_head, int phi, int B, int H, int N, int bq, float sm_scale,
                          void *O, hipStream_t st);
 
 // dW[w] = sum over the (b,h) that use projection matrix w and their tokens of O_lin^T dO, O_lin recomputed from Q and
 // the aggregated states Hq; part is scratch of wproj_grad_groups(BH, N) * BH * 64 * 64 floats
 int wproj_grad_groups(int BH, int N);
 hipError_t launch_wproj_grad(const void *Q, const float *sQ, bool fp8, const void *dO, const void *Hq, int B, int H, int N, int bq,
-                             int proj_per_head, float *part, float *dW, hipStream_t st);
+                             int proj_per_head, int phi, float *part, float *dW, hipStream_t st);
 
 }  // namespace sla

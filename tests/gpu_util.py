@@ -30,7 +30,7 @@ def bf16_tensor_to_f64(t: torch.Tensor) -> np.ndarray:
 class Case:
     """One workload: host arrays (for the oracle) and device tensors (for the library)."""
 
-    def __init__(self, cfg: synth.SLAConfig, inputs: dict | None = None, k_crit=-1, k_neg=-1, sm_scale=0.0):
+    def __init__(self, cfg: synth.SLAConfig, inputs: dict | None = None, k_crit=-1, k_neg=-1, sm_scale=0.0, phi="softmax"):
         self.cfg = cfg
         self.d = inputs if inputs is not None else synth.make_inputs(cfg)
         self.fp8 = cfg.dtype == "fp8"
@@ -38,7 +38,8 @@ class Case:
         self.Nkb = -(-cfg.N // cfg.bk)
         self.sm_scale = sm_scale                      # 0: the default 1/sqrt(D) on both sides
         self.p = B.make_params(cfg.B, cfg.H, cfg.N, cfg.bq, cfg.bk, cfg.crit_frac, cfg.neg_frac, k_crit, k_neg,
-                               cfg.dtype, cfg.proj_per_head, sm_scale)
+                               cfg.dtype, cfg.proj_per_head, sm_scale, phi=phi)
+        self.phi = phi
         self.k_c, self.k_n = B.sla_resolve_counts(self.p)
         up = dev_u8 if self.fp8 else dev_bf16
         self.Q, self.K, self.V = up(self.d["Q"]), up(self.d["K"]), up(self.d["V"])
@@ -49,7 +50,7 @@ class Case:
     def oracle_params(self, oracle):
         c = self.cfg
         return oracle.make_params(c.B, c.H, c.N, c.bq, c.bk, self.k_c, self.k_n, c.dtype, c.proj_per_head,
-                                  self.sm_scale if self.sm_scale > 0 else None)
+                                  self.sm_scale if self.sm_scale > 0 else None, phi=self.phi)
 
     # ---- library calls
     def forward(self, want_labels=True):

@@ -238,6 +238,39 @@ def test_wproj_gradient_without_marginal_blocks_is_zero():
     assert torch.count_nonzero(dW).item() == 0
 
 
+@pytest.mark.parametrize("name", ["c0", "c0_tail150", "c0_bq128_tail", "c1_small", "c4_small", "c4_bq64_tail"])
+def test_elu_feature_map(oracle, name):
+    """phi = ELU(x)+1, the feature map Alg. 1 step 6 prints: block states, whole forward and the gradient of the
+    projection against the oracle in the same mode (same labels: the classifier does not depend on phi)."""
+    from paper_2605_11354_amd import binding as B
+    for n, cfg, kc, kn in SMALL:
+        if n == name:
+            case = G.Case(cfg, k_crit=kc, k_neg=kn, phi="elu1")
+    c, d = case.cfg, case.d
+    hT = G.bf16_tensor_to_f64(case.states())
+    for bh in (0, c.B * c.H - 1):
+        h, z = oracle.states_head(case.oracle_params(oracle), d["K"], d["V"], d["sK"], d["sV"], bh)
+        got = hT[bh // c.H, bh % c.H]
+        assert np.abs(got[:, :64, :] - h.transpose(0, 2, 1)).max() <= 2.0 ** -7 * max(np.abs(h).max(), 1e-30)
+        assert np.abs(got[:, 64, :] - z).max() <= 2.0 ** -7 * np.abs(z).max()
+    O, lab = case.forward()
+    oc = case.oracle_classify(oracle)
+    assert np.array_equal(lab.cpu().numpy(), oc["labels"])
+    ref = case.oracle_attend(oracle, oc["labels"])
+    got = G.gather_blocks(G.bf16_tensor_to_f64(O), ref["sel"], c.bq, c.H)
+    G.assert_output(got, ref["O"], c.dtype, f"{name} phi=elu1")
+    g_bits = synth.to_bf16_bits(np.random.default_rng(13).standard_normal((c.B, c.H, c.N, 64)).astype(np.float32))
+    dW = torch.empty((c.H if c.proj_per_head else 1, 64, 64), dtype=torch.float32, device="cuda")
+    B.sla_wproj_grad(case.p, case.Q, G.dev_bf16(g_bits), dW, case.ws, case.sQ)
+    torch.cuda.synchronize()
+    g64 = (g_bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    dref = oracle.grad_wproj(case.oracle_params(oracle), d["Q"], d["K"], d["V"], oc["labels"], g64, d["sQ"], d["sK"], d["sV"])
+    err = float(np.abs(dW.cpu().numpy() - dref).max())
+    rms = float(np.sqrt(np.mean(dref ** 2)))
+    print(f"{name} phi=elu1: dW error {err / rms:.3e} of RMS")
+    assert err <= GRAD_TOL * rms
+
+
 def test_v_ones_closed_form_on_device():
     """V == 1 gives O = 1 + column sums of W for every row (eq. 1), independent of the oracle."""
     d = dict(synth.make_inputs(C0))

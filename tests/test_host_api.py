@@ -43,13 +43,17 @@ def test_count_rule_matches_golden_table(lib):
     (dict(D=32), B.SLA_ERR_UNSUPPORTED), (dict(bk=32), B.SLA_ERR_UNSUPPORTED), (dict(bq=96), B.SLA_ERR_UNSUPPORTED),
     (dict(crit_frac=0.7, neg_frac=0.5), B.SLA_ERR_INVALID_ARG), (dict(crit_frac=-0.1), B.SLA_ERR_INVALID_ARG),
     (dict(k_crit=5, k_neg=-1), B.SLA_ERR_INVALID_ARG), (dict(k_crit=9, k_neg=9), B.SLA_ERR_INVALID_ARG),
-    (dict(N=64 * 5000), B.SLA_ERR_UNSUPPORTED), (dict(B=-1), B.SLA_ERR_INVALID_ARG), (dict(sm_scale=-1.0), B.SLA_ERR_INVALID_ARG),
+    (dict(N=64 * 5000), B.SLA_ERR_UNSUPPORTED), (dict(B=-1), B.SLA_ERR_INVALID_ARG), (dict(sm_scale=-1.0), B.SLA_ERR_INVALID_ARG), (dict(phi=2), B.SLA_ERR_INVALID_ARG),
 ])
 def test_invalid_parameters_are_rejected_on_the_host(lib, kw, status):
     base = dict(B=1, H=2, N=640, bq=64, bk=64, crit_frac=0.1, neg_frac=0.5)
     base.update(kw)
+    phi = base.pop("phi", None)
+    p = B.make_params(**base)
+    if phi is not None:
+        p.phi = phi                                         # a value outside sla_phi_t
     with pytest.raises(B.SlaError) as e:
-        B.sla_workspace_bytes(B.make_params(**base))
+        B.sla_workspace_bytes(p)
     assert e.value.status == status
     assert len(lib.sla_last_error()) > 0 and lib.sla_strerror(status)
 

@@ -268,7 +268,8 @@ __global__ __launch_bounds__(256) void wproj_grad_reduce_kernel(const float *__r
     for (int b = 0; b < B; ++b)
         for (int h = per_head ? w : 0; h < (per_head ? w + 1 : H); ++h) {
             const float *p = part + ((size_t)(b * H + h) * groups) * kD * kD + x;
-            for (int gidx = 0; gidx < groups; ++gidx) s += p[(size_t)gidx * kD * kD];
+#pragma unroll 8
+            for (int gidx = 0; gidx < groups; ++gidx) s += p[(size_t)gidx * kD * kD];      // loads batch, adds stay in order
         }
     dW[(size_t)w * kD * kD + x] = s;
 }

@@ -204,8 +204,15 @@ def main() -> int:
                 rows = min(N, (i + 1) * cfg.bq) - i * cfg.bq
                 got[s, :rows] = Oh[bh // cfg.H, bh % cfg.H, i * cfg.bq:i * cfg.bq + rows]
             rms = float(np.sqrt(np.mean(oa["O"] ** 2)))
+            diff = np.abs(got - oa["O"])
+            ax = np.abs(oa["O"])
+            half_ulp = np.where(ax > 0, 2.0 ** (np.floor(np.log2(np.where(ax > 0, ax, 1.0))) - 8), 0.0)   # of the bf16 output format
             out["parity"] = {"label_mismatches": int((lab_host != oc["labels"]).sum()),
-                             "max_abs_over_rms_sampled": round(float(np.abs(got - oa["O"]).max() / rms), 5),
+                             "max_abs_over_rms_sampled": round(float(diff.max() / rms), 5),
+                             "beyond_bf16_store_over_rms": round(float(np.maximum(diff - half_ulp, 0.0).max() / rms), 5),
+                             "bar": 6e-2 if fp8 else 2e-2,
+                             "note": "the first figure includes the rounding of the exact result to the bf16 output format "
+                                     "(up to 2^-8 |O| on heavy-tailed rows); the tests assert the second",
                              "sampled_query_blocks": len(sel)}
     print(json.dumps(out))
     return 0

@@ -312,6 +312,44 @@ def test_forward_back_to_back_and_profiled_variant(name):
     assert torch.equal(O.view(torch.int16), ref_a.view(torch.int16)) and torch.equal(lab, lab_a)
 
 
+@pytest.mark.parametrize("name", ["c1_small", "c2_small", "c4_small"])
+def test_forward_replays_from_a_hip_graph(name):
+    """sla_forward only launches kernels on the caller's stream (no allocation, no host wait, no memset), so it can
+    be captured into a HIP graph; every replay, with eager work and synchronisations in between, must reproduce the
+    eager result bit for bit, also after the inputs have been overwritten in place."""
+    from paper_2605_11354_amd import binding as B
+    case = _case(name)
+    c = case.cfg
+    ref, lab_ref = case.forward()
+    O = torch.zeros_like(ref)
+    lab = torch.zeros_like(lab_ref)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                             # warm-up on the capture stream, as torch asks
+        B.sla_forward(case.p, case.Q, case.K, case.V, case.W, O, lab, case.sQ, case.sK, case.sV, case.ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.sla_forward(case.p, case.Q, case.K, case.V, case.W, O, lab, case.sQ, case.sK, case.sV, case.ws)
+    Q0 = case.Q.clone()
+    for r in range(4):
+        O.zero_(); lab.zero_()
+        if r == 2:                                            # other inputs through the same graph ...
+            case.Q.copy_(case.K)
+        if r == 3:                                            # ... and back
+            case.Q.copy_(Q0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        if r == 2:
+            assert not torch.equal(O.view(torch.int16), ref.view(torch.int16))
+        else:
+            assert torch.equal(O.view(torch.int16), ref.view(torch.int16)), r
+            assert torch.equal(lab, lab_ref), r
+        _ = (O.float() * 2).sum().item()                      # eager work between replays
+
+
 def test_errors_are_reported_not_launched():
     from paper_2605_11354_amd import binding as B
     case = G.Case(C0)

@@ -147,3 +147,42 @@ def grad_wproj(p: Params, Q, K, V, labels, dO, sQ=None, sK=None, sV=None):
     if p.proj_per_head:
         return np.einsum("bhtd,bhte->hde", olin, dO)
     return np.einsum("bhtd,bhte->de", olin, dO)[None]
+
+
+def quantise_e4m3_blocks(bits, blk: int):
+    """Scaled FP8 quantiser of App. B.2 (eqs. for scale, clamp and cast) applied per block of `blk` consecutive
+    tokens of every (b, h), the granularity configuration 4 uses for Q, K and V:
+        scale = max(amax, 1e-8) / 448        (fp32; the 1e-8 is the paper's epsilon against division by zero)
+        code  = E4M3(clamp(x / scale, -448, 448))   with round-to-nearest-even
+    bits: uint16 bf16 bit patterns [..., N, D].  Returns (codes uint8 [..., N, D], scales fp32 [..., ceil(N/blk)]).
+
+    The cast is written from the format's definition: the 127 non-negative finite E4M3 values (decoded by the C
+    oracle's table routine) are searched for the nearest one; a value exactly half-way between two neighbours goes
+    to the one with an even code."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    x = (bits.astype(np.uint32) << 16).view(np.float32)
+    N = x.shape[-2]
+    nb = -(-N // blk)
+    dec = lib().sla_oracle_decode_e4m3
+    dec.restype = C.c_double
+    grid = np.array([dec(C.c_uint8(c)) for c in range(127)], dtype=np.float64)       # codes 0..126: 0 .. 448, ascending
+    assert np.all(np.diff(grid) > 0) and grid[-1] == 448.0
+    codes = np.empty(x.shape, dtype=np.uint8)
+    scales = np.empty(x.shape[:-2] + (nb,), dtype=np.float32)
+    for j in range(nb):
+        sl = slice(j * blk, min(N, (j + 1) * blk))
+        xb = x[..., sl, :]
+        amax = np.abs(xb).max(axis=(-2, -1)).astype(np.float32)
+        scale = (np.maximum(amax, np.float32(1e-8)) / np.float32(448.0)).astype(np.float32)
+        scales[..., j] = scale
+        y = (xb / scale[..., None, None]).astype(np.float32)                          # fp32 division, correctly rounded
+        y = np.clip(y, np.float32(-448.0), np.float32(448.0))
+        a = np.abs(y).astype(np.float64)
+        hi = np.clip(np.searchsorted(grid, a, side="left"), 0, 126)                   # first grid value >= a
+        lo = np.maximum(hi - 1, 0)
+        dlo, dhi = a - grid[lo], grid[hi] - a
+        pick_hi = (dhi < dlo) | ((dhi == dlo) & (hi % 2 == 0))
+        code = np.where(pick_hi, hi, lo).astype(np.uint8)
+        code |= (np.signbit(y).astype(np.uint8) << 7)
+        codes[..., sl, :] = code
+    return codes, scales

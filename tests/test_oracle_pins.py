@@ -372,3 +372,33 @@ def test_elu_feature_map_values():
     """ELU(x)+1: 1 at 0, x+1 above, exp(x) below (continuous, positive)."""
     x = np.array([-30.0, -1.0, -0.0, 0.0, 0.5, 3.0])
     np.testing.assert_allclose(bf.phi_elu1(x), [np.exp(-30.0), np.exp(-1.0), 1.0, 1.0, 1.5, 4.0], rtol=1e-15)
+
+
+def test_block_quantiser_matches_library_cast_and_host_generator(oracle):
+    """The oracle's quantiser (App. B.2 per token block) against two independent casts: torch's float8_e4m3fn
+    conversion of the same clamped fp32 quotients, and the benchmark generator's own quantiser."""
+    import torch
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((2, 3, 333, 64)).astype(np.float32) * np.exp(rng.uniform(-12, 6, (2, 3, 333, 1))).astype(np.float32)
+    x[0, 0, :64] = 0.0                                              # an all-zero block: scale = 1e-8/448, codes 0
+    x[0, 1, 5, 7] = 3.0e4                                           # a block whose amax is a single outlier
+    bits = synth.to_bf16_bits(x)
+    codes, scales = oracle.quantise_e4m3_blocks(bits, 64)
+    xb = (bits.astype(np.uint32) << 16).view(np.float32)
+    for j in range(6):
+        sl = slice(64 * j, min(333, 64 * j + 64))
+        amax = np.abs(xb[..., sl, :]).max(axis=(-2, -1))
+        sc = np.maximum(amax, np.float32(1e-8)) / np.float32(448.0)
+        assert np.array_equal(scales[..., j], sc.astype(np.float32))
+        y = np.clip(xb[..., sl, :] / sc[..., None, None].astype(np.float32), -448.0, 448.0).astype(np.float32)
+        t = torch.from_numpy(y).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        got = codes[..., sl, :]
+        same = (got == t) | ((got & 0x7F == 0) & (t & 0x7F == 0))   # +0 / -0 may differ in sign conventions only
+        assert same.all()
+    c2, s2 = synth.quantise_e4m3_blocks(bits, 64)
+    assert np.array_equal(s2, scales) and np.array_equal(c2, codes)
+    assert np.all(codes[0, 0, :64] == 0) and scales[0, 0, 0] == np.float32(1e-8) / np.float32(448.0)
+    # exact half-way cases go to the even code: 1.0625 = midpoint of 1.0 (0x38) and 1.125 (0x39) at scale 1
+    tie = np.zeros((1, 1, 64, 64), np.float32); tie[0, 0, 0, 0] = 448.0; tie[0, 0, 0, 1] = 1.0625; tie[0, 0, 0, 2] = 1.1875
+    ct, st = oracle.quantise_e4m3_blocks(synth.to_bf16_bits(tie), 64)
+    assert st[0, 0, 0] == 1.0 and ct[0, 0, 0, 0] == 0x7E and ct[0, 0, 0, 1] == 0x38 and ct[0, 0, 0, 2] == 0x3A

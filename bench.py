@@ -33,6 +33,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--with-grad", action="store_true", help="also time sla_wproj_grad (gradient of W_proj) after the forward")
+    ap.add_argument("--with-quant", action="store_true", help="also time sla_quantise_e4m3 on a bf16 tensor of the workload's shape")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards over batch x heads with no "
@@ -173,6 +174,24 @@ def main() -> int:
         out["wproj_grad"] = {"ms": round(gms, 5), "bound": "hbm", "algorithmic_bytes": int(gbytes),
                              "achieved_GBs": round(gbytes / gms / 1e6, 1), "frac": round(gbytes / gms / 1e6 / PEAK_HBM_GBS, 4),
                              "note": "two launches (partials + fixed-order reduction), HIP events on the launch stream"}
+
+    if args.with_quant:
+        # per-block E4M3 quantiser (App. B.2): 2 bytes in, 1 byte out per element, plus the scales
+        xq = torch.randn((cfg.B, cfg.H, cfg.N, 64), device="cuda").to(torch.bfloat16)
+        cq = torch.empty((cfg.B, cfg.H, cfg.N, 64), dtype=torch.uint8, device="cuda")
+        sq_ = torch.empty((cfg.B, cfg.H, Nkb), dtype=torch.float32, device="cuda")
+        for _ in range(args.warmup):
+            B.sla_quantise_e4m3(xq, cfg.bk, cq, sq_)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            B.sla_quantise_e4m3(xq, cfg.bk, cq, sq_)
+        e1.record()
+        torch.cuda.synchronize()
+        qms = e0.elapsed_time(e1) / args.steps
+        qbytes = BH * N * D * 3 + BH * Nkb * 4
+        out["quantise_e4m3"] = {"ms": round(qms, 5), "bound": "hbm", "algorithmic_bytes": int(qbytes),
+                                "achieved_GBs": round(qbytes / qms / 1e6, 1), "frac": round(qbytes / qms / 1e6 / PEAK_HBM_GBS, 4)}
 
     if not args.no_check or not args.no_cpu_baseline:
         from oracle import sla_oracle as orc

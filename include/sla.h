@@ -112,6 +112,20 @@ sla_status_t sla_wproj_grad(const sla_params_t *p, const void *Q, const float *s
                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Scaled FP8 quantiser (App. B.2: scale = max|x| / 448, clamp, cast to E4M3) applied per block of `blk`
+ * consecutive tokens of every (b, h), which is the form sla_forward takes E4M3 Q, K and V in (blk = bq for Q,
+ * bk for K and V):
+ *     scale = max(amax, 1e-8) / 448 (fp32),   code = E4M3(clamp(x / scale, -448, 448)), round to nearest even
+ *   X       in   bf16 [B,H,N,64]
+ *   blk     64 or 128
+ *   codes   out  uint8 [B,H,N,64]
+ *   scales  out  fp32 [B,H,ceil(N/blk)]
+ * The result is defined bit for bit (fp32 division, one rounding).
+ */
+sla_status_t sla_quantise_e4m3(const void *X, int32_t B, int32_t H, int32_t N, int32_t blk, void *codes, float *scales,
+                               void *stream);
+
+/*
  * Measurement variant of sla_forward: identical kernels and results, but every kernel is
  * bracketed by HIP events on `stream`; the call then WAITS for the stream and writes the
  * duration of each kernel in milliseconds to stage_ms[SLA_NUM_STAGES] (host memory).

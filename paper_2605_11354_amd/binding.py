@@ -19,8 +19,8 @@ SLA_OK, SLA_ERR_INVALID_ARG, SLA_ERR_UNSUPPORTED, SLA_ERR_WORKSPACE, SLA_ERR_HIP
 SLA_BF16, SLA_FP8_E4M3 = 0, 1
 STATE_ROWS = 65          # rows of one block state: 64 rows of h^T and one row of z
 EXPORTS = ["sla_resolve_counts", "sla_workspace_bytes", "sla_forward", "sla_pool_classify", "sla_linear_states",
-           "sla_marginal_aggregate", "sla_sparse_combine", "sla_forward_profiled", "sla_wproj_grad", "sla_strerror",
-           "sla_last_error", "sla_stage_name"]
+           "sla_marginal_aggregate", "sla_sparse_combine", "sla_forward_profiled", "sla_wproj_grad", "sla_quantise_e4m3",
+           "sla_strerror", "sla_last_error", "sla_stage_name"]
 NUM_STAGES = 6
 
 
@@ -55,7 +55,7 @@ def lib() -> C.CDLL:
         _lib.sla_strerror.restype = C.c_char_p
         _lib.sla_last_error.restype = C.c_char_p
         _lib.sla_stage_name.restype = C.c_char_p
-        for name in EXPORTS[:9]:
+        for name in EXPORTS[:10]:
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -136,6 +136,15 @@ def sla_marginal_aggregate(p, labels, hT, Hq, workspace=None):
     _check(lib().sla_marginal_aggregate(C.byref(p), _ptr(labels), _ptr(hT), _ptr(Hq), _ptr(ws), C.c_size_t(ws.numel()),
                                         _stream()), "sla_marginal_aggregate")
     return Hq
+
+
+def sla_quantise_e4m3(X, blk, codes, scales):
+    """X bf16 [B,H,N,64] -> codes uint8 [B,H,N,64], scales fp32 [B,H,ceil(N/blk)] (per-block scaled E4M3)."""
+    Bn, H, N, D = X.shape
+    assert D == 64
+    _check(lib().sla_quantise_e4m3(_ptr(X), C.c_int32(Bn), C.c_int32(H), C.c_int32(N), C.c_int32(blk), _ptr(codes),
+                                   _ptr(scales), _stream()), "sla_quantise_e4m3")
+    return codes, scales
 
 
 def sla_wproj_grad(p, Q, dO, dW, workspace, sQ=None):

@@ -317,6 +317,19 @@ sla_status_t sla_wproj_grad(const sla_params_t *p, const void *Q, const float *s
     return SLA_OK;
 }
 
+sla_status_t sla_quantise_e4m3(const void *X, int32_t B, int32_t H, int32_t N, int32_t blk, void *codes, float *scales,
+                               void *stream)
+{
+    if (B < 0 || H < 0 || N < 0) return fail(SLA_ERR_INVALID_ARG, "negative size (B=%d H=%d N=%d)", B, H, N);
+    if (blk != 64 && blk != 128) return fail(SLA_ERR_UNSUPPORTED, "block of %d tokens; only 64 and 128 are implemented", blk);
+    if ((long)B * H > 0x7FFFFFF0L / 4) return fail(SLA_ERR_UNSUPPORTED, "B*H = %ld is too large", (long)B * H);
+    if (B == 0 || H == 0 || N == 0) return SLA_OK;
+    SLA_REQ_PTR(X); SLA_REQ_PTR(codes);
+    if (!scales) return fail(SLA_ERR_INVALID_ARG, "scales is NULL");
+    SLA_HIP(sla::launch_quantise_e4m3(X, B * H, N, blk, codes, scales, (hipStream_t)stream));
+    return SLA_OK;
+}
+
 const char *sla_stage_name(int stage)
 {
     static const char *names[SLA_NUM_STAGES] = {"pool_q", "states", "scores", "select", "aggregate", "attend"};

@@ -59,4 +59,7 @@ int wproj_grad_groups(int BH, int N);
 hipError_t launch_wproj_grad(const void *Q, const float *sQ, bool fp8, const void *dO, const void *Hq, int B, int H, int N, int bq,
                              int proj_per_head, int phi, float *part, float *dW, hipStream_t st);
 
+// X bf16 [BH,N,64] -> codes e4m3 [BH,N,64] + fp32 scales [BH, ceil(N/blk)], blk = 64 or 128 (App. B.2 per token block)
+hipError_t launch_quantise_e4m3(const void *X, int BH, int N, int blk, void *codes, float *scales, hipStream_t st);
+
 }  // namespace sla

@@ -350,6 +350,49 @@ def test_forward_replays_from_a_hip_graph(name):
         _ = (O.float() * 2).sum().item()                      # eager work between replays
 
 
+@pytest.mark.parametrize("N,blk", [(512, 64), (333, 64), (700, 128), (1, 64), (2748, 128)])
+def test_block_quantiser_is_bit_exact(oracle, N, blk):
+    """Per-block scaled E4M3 quantiser (App. B.2) on the device against the oracle: codes and scales bit for bit,
+    including an all-zero block, an outlier block, half-way cases and a ragged last block."""
+    from paper_2605_11354_amd import binding as B
+    rng = np.random.default_rng(21)
+    x = rng.standard_normal((2, 3, N, 64)).astype(np.float32) * np.exp(rng.uniform(-12, 6, (2, 3, N, 1))).astype(np.float32)
+    if N >= 64:
+        x[0, 0, :blk] = 0.0
+        x[0, 1, 5, 7] = 3.0e4
+        x[1, 0, :blk] = 0.0
+        x[1, 0, 0, 0] = 448.0                                      # scale exactly 1: the block below holds grid midpoints
+        x[1, 0, 1, :] = np.linspace(1.0, 1.0 + 63 / 16, 64)        # multiples of 1/16 = half-way between E4M3 neighbours
+        x[1, 0, 2, :] = -np.linspace(0.0, 63 * 2.0 ** -10, 64)     # the subnormal range, spacing 2^-9, with its midpoints
+    bits = synth.to_bf16_bits(x)
+    codes = torch.full((2, 3, N, 64), 0xAA, dtype=torch.uint8, device="cuda")
+    scales = torch.full((2, 3, -(-N // blk)), -1.0, dtype=torch.float32, device="cuda")
+    B.sla_quantise_e4m3(G.dev_bf16(bits), blk, codes, scales)
+    torch.cuda.synchronize()
+    rc, rs = oracle.quantise_e4m3_blocks(bits, blk)
+    assert np.array_equal(scales.cpu().numpy(), rs)
+    got = codes.cpu().numpy()
+    bad = np.argwhere(got != rc)
+    assert bad.size == 0, (bad[:5], got[tuple(bad[0])], rc[tuple(bad[0])])
+
+
+def test_quantiser_reproduces_the_benchmark_inputs():
+    """Quantising configuration 4's bf16 tensors on the device reproduces the E4M3 codes and scales the benchmark
+    generator makes on the host (and with them everything the E4M3 forward computes from them)."""
+    from paper_2605_11354_amd import binding as B
+    cfg = synth.CONFIGS[4].with_(H=2, N=2 * 1374)
+    d16 = synth.make_inputs(cfg.with_(dtype="bf16"))
+    case = G.Case(cfg)                                            # holds the host-quantised tensors
+    q = torch.empty_like(case.Q); k = torch.empty_like(case.K); v = torch.empty_like(case.V)
+    sq = torch.empty_like(case.sQ); sk = torch.empty_like(case.sK); sv = torch.empty_like(case.sV)
+    B.sla_quantise_e4m3(G.dev_bf16(d16["Q"]), cfg.bq, q, sq)
+    B.sla_quantise_e4m3(G.dev_bf16(d16["K"]), cfg.bk, k, sk)
+    B.sla_quantise_e4m3(G.dev_bf16(d16["V"]), cfg.bk, v, sv)
+    torch.cuda.synchronize()
+    assert torch.equal(q, case.Q) and torch.equal(k, case.K) and torch.equal(v, case.V)
+    assert torch.equal(sq, case.sQ) and torch.equal(sk, case.sK) and torch.equal(sv, case.sV)
+
+
 def test_errors_are_reported_not_launched():
     from paper_2605_11354_amd import binding as B
     case = G.Case(C0)

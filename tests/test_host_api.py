@@ -21,7 +21,7 @@ def lib():
 def test_library_exports_every_declared_symbol(lib):
     header = open(os.path.join(ROOT, "include", "sla.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    names = set(re.findall(r"\b(sla_[a-z_]+)\s*\(", header))
+    names = set(re.findall(r"\b(sla_[a-z0-9_]+)\s*\(", header))
     assert {"sla_forward", "sla_pool_classify", "sla_linear_states", "sla_marginal_aggregate", "sla_sparse_combine",
             "sla_workspace_bytes", "sla_resolve_counts", "sla_strerror", "sla_last_error"} <= names
     for n in names:

@@ -58,6 +58,10 @@ typedef enum { SLA_BF16 = 0, SLA_FP8_E4M3 = 1 } sla_dtype_t;
  * configurations), or ELU(x)+1 elementwise as the algorithm prints it (x+1 for x > 0, exp(x) otherwise) */
 typedef enum { SLA_PHI_SOFTMAX = 0, SLA_PHI_ELU1 = 1 } sla_phi_t;
 
+/* memory layout of Q, K, V, O (and dO): [B,H,N,D], or [B,N,H,D] as a fused qkv projection leaves its heads
+ * (a row of D elements is contiguous either way; block scales, labels and W_proj are not affected) */
+typedef enum { SLA_LAYOUT_BHND = 0, SLA_LAYOUT_BNHD = 1 } sla_layout_t;
+
 typedef struct {
     int32_t B, H, N, D;          /* batch, heads, tokens per (b,h), head dim (must be 64) */
     int32_t bq, bk;              /* query block (64 or 128) and key block (64) sizes */
@@ -69,6 +73,7 @@ typedef struct {
     int32_t phi;                 /* sla_phi_t */
     int32_t proj_per_head;       /* 0: W_proj is [D, D]; 1: [H, D, D] */
     float   sm_scale;            /* softmax scale of the sparse branch; 0 = 1/sqrt(D) (section 3.3) */
+    int32_t layout;              /* sla_layout_t of Q, K, V, O, dO */
 } sla_params_t;
 
 /* Derived sizes: Nqb = ceil(N/bq), Nkb = ceil(N/bk). */
@@ -116,14 +121,14 @@ sla_status_t sla_wproj_grad(const sla_params_t *p, const void *Q, const float *s
  * consecutive tokens of every (b, h), which is the form sla_forward takes E4M3 Q, K and V in (blk = bq for Q,
  * bk for K and V):
  *     scale = max(amax, 1e-8) / 448 (fp32),   code = E4M3(clamp(x / scale, -448, 448)), round to nearest even
- *   X       in   bf16 [B,H,N,64]
+ *   X       in   bf16 [B,H,N,64], or [B,N,H,64] with layout = SLA_LAYOUT_BNHD
  *   blk     64 or 128
- *   codes   out  uint8 [B,H,N,64]
+ *   codes   out  uint8, same layout as X
  *   scales  out  fp32 [B,H,ceil(N/blk)]
  * The result is defined bit for bit (fp32 division, one rounding).
  */
-sla_status_t sla_quantise_e4m3(const void *X, int32_t B, int32_t H, int32_t N, int32_t blk, void *codes, float *scales,
-                               void *stream);
+sla_status_t sla_quantise_e4m3(const void *X, int32_t B, int32_t H, int32_t N, int32_t blk, int32_t layout, void *codes,
+                               float *scales, void *stream);
 
 /*
  * Measurement variant of sla_forward: identical kernels and results, but every kernel is

@@ -30,7 +30,7 @@ class SlaParams(C.Structure):
                 ("crit_frac", C.c_double), ("neg_frac", C.c_double),
                 ("k_crit", C.c_int32), ("k_neg", C.c_int32),
                 ("dtype", C.c_int32), ("phi", C.c_int32), ("proj_per_head", C.c_int32),
-                ("sm_scale", C.c_float)]
+                ("sm_scale", C.c_float), ("layout", C.c_int32)]
 
 
 class SlaError(RuntimeError):
@@ -61,10 +61,11 @@ def lib() -> C.CDLL:
 
 
 def make_params(B, H, N, bq, bk, crit_frac=0.0, neg_frac=0.0, k_crit=-1, k_neg=-1, dtype="bf16",
-                proj_per_head=False, sm_scale=0.0, D=64, phi="softmax") -> SlaParams:
+                proj_per_head=False, sm_scale=0.0, D=64, phi="softmax", layout="bhnd") -> SlaParams:
+    """layout: "bhnd" = Q, K, V, O are [B,H,N,D]; "bnhd" = [B,N,H,D] (rows of a head H*D elements apart)."""
     return SlaParams(B, H, N, D, bq, bk, crit_frac, neg_frac, k_crit, k_neg,
                      SLA_BF16 if dtype == "bf16" else SLA_FP8_E4M3, {"softmax": 0, "elu1": 1}[phi],
-                     1 if proj_per_head else 0, sm_scale)
+                     1 if proj_per_head else 0, sm_scale, {"bhnd": 0, "bnhd": 1}[layout])
 
 
 def _check(status: int, where: str):
@@ -138,12 +139,16 @@ def sla_marginal_aggregate(p, labels, hT, Hq, workspace=None):
     return Hq
 
 
-def sla_quantise_e4m3(X, blk, codes, scales):
-    """X bf16 [B,H,N,64] -> codes uint8 [B,H,N,64], scales fp32 [B,H,ceil(N/blk)] (per-block scaled E4M3)."""
-    Bn, H, N, D = X.shape
+def sla_quantise_e4m3(X, blk, codes, scales, layout="bhnd"):
+    """X bf16 [B,H,N,64] ([B,N,H,64] with layout "bnhd") -> codes uint8 of the same layout, scales fp32 [B,H,ceil(N/blk)]."""
+    if layout == "bhnd":
+        Bn, H, N, D = X.shape
+    else:
+        Bn, N, H, D = X.shape
     assert D == 64
-    _check(lib().sla_quantise_e4m3(_ptr(X), C.c_int32(Bn), C.c_int32(H), C.c_int32(N), C.c_int32(blk), _ptr(codes),
-                                   _ptr(scales), _stream()), "sla_quantise_e4m3")
+    _check(lib().sla_quantise_e4m3(_ptr(X), C.c_int32(Bn), C.c_int32(H), C.c_int32(N), C.c_int32(blk),
+                                   C.c_int32({"bhnd": 0, "bnhd": 1}[layout]), _ptr(codes), _ptr(scales), _stream()),
+           "sla_quantise_e4m3")
     return codes, scales
 
 

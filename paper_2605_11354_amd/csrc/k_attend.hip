@@ -91,13 +91,14 @@ struct CopyOffsets {
     using T = Tile<NW, FP8>;
     int k[T::KINS], v[T::VINS];
     int krow[T::KINS];            // K row of this lane per instruction (for clamping at a ragged end)
-    __device__ __forceinline__ void init(int wave, int lane)
+    // krowb: bytes between consecutive K rows in global memory (64 or 128 when the heads are contiguous)
+    __device__ __forceinline__ void init(int wave, int lane, int krowb)
     {
 #pragma unroll
         for (int x = 0; x < T::KINS; ++x) {
             const int ins = wave * T::KINS + x;
-            if (FP8) { const int r = ins * 16 + (lane >> 2); krow[x] = r; k[x] = r * 64 + (((lane & 3) ^ swz4(r)) << 4); }
-            else     { const int r = ins * 8 + (lane >> 3);  krow[x] = r; k[x] = r * 128 + (((lane & 7) ^ swz8(r)) << 4); }
+            if (FP8) { const int r = ins * 16 + (lane >> 2); krow[x] = r; k[x] = r * krowb + (((lane & 3) ^ swz4(r)) << 4); }
+            else     { const int r = ins * 8 + (lane >> 3);  krow[x] = r; k[x] = r * krowb + (((lane & 7) ^ swz8(r)) << 4); }
         }
 #pragma unroll
         for (int x = 0; x < T::VINS; ++x) {
@@ -111,11 +112,10 @@ struct CopyOffsets {
 // kt / vt: first byte of the tiles in global memory (wave-uniform); valid: number of real rows of
 // the K tile (rows past it are clamped to the last, they are masked later; V^T tiles are complete).
 template <int NW, bool FP8>
-__device__ __forceinline__ void issue_tile(uint32_t stage, const uint8_t *kt, const uint8_t *vt, int valid,
+__device__ __forceinline__ void issue_tile(uint32_t stage, const uint8_t *kt, const uint8_t *vt, int valid, int KROW,
                                            const CopyOffsets<NW, FP8> &co, int wave)
 {
     using T = Tile<NW, FP8>;
-    constexpr int KROW = FP8 ? 64 : 128;
     if (valid == kBK) {
 #pragma unroll
         for (int x = 0; x < T::KINS; ++x) copy_1k_to_lds(kt, co.k[x], stage + (wave * T::KINS + x) * 1024);
@@ -134,12 +134,12 @@ __device__ __forceinline__ void issue_tile(uint32_t stage, const uint8_t *kt, co
 // through LDS after the loop and the KS = 0 wave of each pair runs the epilogue.
 // STG: stages of the tile ring.  3 in general (copies run two tiles ahead).  2 for lists of at most two critical
 // blocks (bf16, no key split): both tiles are requested at the start, the epilogue operands share the stage the
-// first tile leaves free, and the smaller LDS footprint lets five workgroups instead of three share a CU, which is
+// first tile leaves free, and the smaller LDS footprint lets four workgroups instead of three share a CU, which is
 // what a loop this short needs.
 template <int NW, int KS, bool FP8, int STG>
 __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void attend_kernel(
     const void *__restrict__ Qp, const void *__restrict__ Kp, const uint16_t *__restrict__ Vp,
-    const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV,
+    const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV, RowMap rm,
     const int32_t *__restrict__ crit_idx, int k_c, const uint16_t *__restrict__ Hq, const uint16_t *__restrict__ WT,
     int proj_per_head, int phi, int H, int N, int Nqb, int Nkb, long total, float c_exp, uint16_t *__restrict__ O)
 {
@@ -160,7 +160,8 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
     const int i = (int)(work - bh * Nqb);
     const int q = i * BQ + 32 * wq + l32;             // this lane's query row
     const bool qok = q < N;
-    const size_t head = (size_t)bh * N * kD;          // element offset of this (b,h)
+    const size_t head = rm.head(bh);                  // element offset of this (b,h); rows are rm.ts elements apart
+    const int krowb = rm.ts * ES;                     // bytes between consecutive K rows
     const uint8_t *Kh = (const uint8_t *)Kp + head * ES;
     const uint8_t *Vh = (const uint8_t *)(Vp + (size_t)bh * Nkb * kBK * kD);
 
@@ -170,7 +171,7 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
     if (FP8) {
         uint4 w0 = make_uint4(0, 0, 0, 0), w1 = w0;
         if (qok) {
-            const uint8_t *qr = (const uint8_t *)Qp + head + (size_t)q * kD + 32 * g;
+            const uint8_t *qr = (const uint8_t *)Qp + head + (size_t)q * rm.ts + 32 * g;
             w0 = *(const uint4 *)qr;
             w1 = *(const uint4 *)(qr + 16);
         }
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             uint4 w = make_uint4(0, 0, 0, 0);
-            if (qok) w = *(const uint4 *)((const uint16_t *)Qp + head + (size_t)q * kD + 16 * s + 8 * g);
+            if (qok) w = *(const uint4 *)((const uint16_t *)Qp + head + (size_t)q * rm.ts + 16 * s + 8 * g);
             qf[s] = __builtin_bit_cast(bf16x8, w);
         }
     }
@@ -209,13 +210,13 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
         return (j < 0 || j >= Nkb) ? -1 : j;
     };
     CopyOffsets<NWAVES, FP8> co;
-    co.init(wave, lane);
+    co.init(wave, lane, krowb);
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);                       // same value, provably uniform
     const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_p)lds;                // LDS byte address of the ring
     auto request = [&](int c, int j) {
         const int jj = j < 0 ? 0 : j;                  // absent entries still copy (block 0) so the copy count is uniform
-        issue_tile<NWAVES, FP8>(lds_base + (c % STG) * T::STAGE, Kh + (size_t)jj * kBK * kD * ES, Vh + (size_t)jj * kBK * kD * 2,
-                                min(kBK, N - jj * kBK), co, wave_u);
+        issue_tile<NWAVES, FP8>(lds_base + (c % STG) * T::STAGE, Kh + (size_t)jj * kBK * krowb, Vh + (size_t)jj * kBK * kD * 2,
+                                min(kBK, N - jj * kBK), krowb, co, wave_u);
     };
     // The operands of the linear/projection epilogue (the 64x64 tile of Hq^T, the Z row, W^T) travel the
     // same way into the two ring stages that are idle during the last tile, so their latency hides
@@ -499,7 +500,7 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
             const int r = 8 * k + (lane >> 3), ch = lane & 7;      // row of the tile, 16-byte chunk of the row
             const int fr = ((r >> 1) & 7) << 1;
             const uint4 v = *(const uint4 *)(ot + r * 128 + (((2 * ch) ^ fr) << 3));
-            if (q0w + r < N) *(uint4 *)(O + head + (size_t)(q0w + r) * kD + ch * 8) = v;
+            if (q0w + r < N) *(uint4 *)(O + head + (size_t)(q0w + r) * rm.ts + ch * 8) = v;
         }
     }
 }
@@ -517,18 +518,18 @@ hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st)
 }
 
 template <int NW, int KS, bool FP8, int STG>
-static hipError_t launch_attend_t(const void *Q, const void *K, const void *Vp, const float *sQ, const float *sK, const float *sV,
+static hipError_t launch_attend_t(const void *Q, const void *K, const void *Vp, const float *sQ, const float *sK, const float *sV, RowMap rm,
                                   const int32_t *crit_idx, int k_c, const void *Hq, const void *WT, int proj_per_head, int phi,
                                   int H, int N, int Nqb, int Nkb, long total, float c_exp, void *O, hipStream_t st)
 {
-    attend_kernel<NW, KS, FP8, STG><<<(unsigned)xcd_grid(total), 64 * NW * KS, 0, st>>>(Q, K, (const uint16_t *)Vp, sQ, sK, sV, crit_idx, k_c, (const uint16_t *)Hq,
+    attend_kernel<NW, KS, FP8, STG><<<(unsigned)xcd_grid(total), 64 * NW * KS, 0, st>>>(Q, K, (const uint16_t *)Vp, sQ, sK, sV, rm, crit_idx, k_c, (const uint16_t *)Hq,
                                                                           (const uint16_t *)WT, proj_per_head, phi, H, N, Nqb, Nkb,
                                                                           total, c_exp, (uint16_t *)O);
     return hipGetLastError();
 }
 
 hipError_t launch_attend(const void *Q, const void *K, const void *Vp,
-                         const float *sQ, const float *sK, const float *sV, bool fp8,
+                         const float *sQ, const float *sK, const float *sV, bool fp8, RowMap rm,
                          const int32_t *crit_idx, int k_c, const void *Hq, const void *WT,
                          int proj_per_head, int phi, int B, int H, int N, int bq, float sm_scale,
                          void *O, hipStream_t st)
@@ -536,7 +537,7 @@ hipError_t launch_attend(const void *Q, const void *K, const void *Vp,
     const int Nqb = (N + bq - 1) / bq, Nkb = (N + kBK - 1) / kBK;
     const long total = (long)B * H * Nqb;
     const float c_exp = sm_scale * kLog2e;
-#define SLA_ATT(NW, KS, F8, STG) return launch_attend_t<NW, KS, F8, STG>(Q, K, Vp, sQ, sK, sV, crit_idx, k_c, Hq, WT, proj_per_head, phi, H, N, Nqb, Nkb, total, c_exp, O, st)
+#define SLA_ATT(NW, KS, F8, STG) return launch_attend_t<NW, KS, F8, STG>(Q, K, Vp, sQ, sK, sV, rm, crit_idx, k_c, Hq, WT, proj_per_head, phi, H, N, Nqb, Nkb, total, c_exp, O, st)
     if (bq == 128) { if (fp8) SLA_ATT(4, 1, true, 3); else SLA_ATT(4, 1, false, 3); }
     // 64-row query blocks: two query groups x two key halves, so a workgroup still has four waves;
     // with very few critical blocks per row the merge of the halves costs more than it hides

@@ -31,7 +31,7 @@ constexpr float kLog2eB = 1.4426950408889634f;
 template <bool FP8>
 __global__ __launch_bounds__(256) void wproj_grad_kernel(const void *__restrict__ Qp, const float *__restrict__ sQ,
                                                          const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Hq,
-                                                         int N, int bq, int Nqb, int units, int upw, int groups, int phi,
+                                                         RowMap rm, int N, int bq, int Nqb, int units, int upw, int groups, int phi,
                                                          float *__restrict__ part)
 {
     static_assert(3 * 16384 <= 4 * kWaveLds, "three parked accumulators must fit the workgroup's LDS");
@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void wproj_grad_kernel(const void *__restrict_
     uint16_t *Zs = (uint16_t *)(my + kHsBytes);                      // its Z row
     uint16_t *Ts = (uint16_t *)(my + kHsBytes + kZsBytes);           // dO^T of the 32 rows: [d_out][token]
     float *Ds = (float *)(my + kHsBytes + kZsBytes + kTsBytes);      // 1/(phi.Z) per row
-    const size_t head = (size_t)bh * N * kD;
+    const size_t head = rm.head(bh);
 
     f32x16 acc[2][2];                                                // [ot][et]: D[32 ot + ..][32 et + l32]
 #pragma unroll
@@ -80,20 +80,20 @@ __global__ __launch_bounds__(256) void wproj_grad_kernel(const void *__restrict_
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int t = t0 + 8 * tg + k;
-            const uint2 v = *(const uint2 *)(dO + head + (size_t)min(t, N - 1) * kD + 4 * eq);
+            const uint2 v = *(const uint2 *)(dO + head + (size_t)min(t, N - 1) * rm.ts + 4 * eq);
             r.d[2 * k] = t < N ? v.x : 0u;                                        // rows past the end of the sequence are zero
             r.d[2 * k + 1] = t < N ? v.y : 0u;
         }
         const int qc = min(q, N - 1);                                             // such rows are switched off through 1/(phi.Z) = 0
         if constexpr (FP8) {
-            const uint8_t *qr = (const uint8_t *)Qp + head + (size_t)qc * kD + 32 * g;
+            const uint8_t *qr = (const uint8_t *)Qp + head + (size_t)qc * rm.ts + 32 * g;
             const uint4 w0 = *(const uint4 *)qr, w1 = *(const uint4 *)(qr + 16);
             r.q[0] = w0.x; r.q[1] = w0.y; r.q[2] = w0.z; r.q[3] = w0.w; r.q[4] = w1.x; r.q[5] = w1.y; r.q[6] = w1.z; r.q[7] = w1.w;
             r.qscale = sQ[bh * Nqb + i];
         } else {
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                const uint4 w = *(const uint4 *)((const uint16_t *)Qp + head + (size_t)qc * kD + 16 * s + 8 * g);
+                const uint4 w = *(const uint4 *)((const uint16_t *)Qp + head + (size_t)qc * rm.ts + 16 * s + 8 * g);
                 r.q[4 * s] = w.x; r.q[4 * s + 1] = w.y; r.q[4 * s + 2] = w.z; r.q[4 * s + 3] = w.w;
             }
             r.qscale = 1.0f;
@@ -283,14 +283,14 @@ int wproj_grad_groups(int BH, int N)
     return g < 1 ? 1 : g;
 }
 
-hipError_t launch_wproj_grad(const void *Q, const float *sQ, bool fp8, const void *dO, const void *Hq, int B, int H, int N, int bq,
+hipError_t launch_wproj_grad(const void *Q, const float *sQ, bool fp8, RowMap rm, const void *dO, const void *Hq, int B, int H, int N, int bq,
                              int proj_per_head, int phi, float *part, float *dW, hipStream_t st)
 {
     const int BH = B * H, Nqb = (N + bq - 1) / bq, units = (N + 31) / 32;
     const int groups = wproj_grad_groups(BH, N), upw = (units + groups - 1) / groups;
     const unsigned grid = (unsigned)BH * groups;
-    if (fp8) wproj_grad_kernel<true><<<grid, 256, 0, st>>>(Q, sQ, (const uint16_t *)dO, (const uint16_t *)Hq, N, bq, Nqb, units, upw, groups, phi, part);
-    else     wproj_grad_kernel<false><<<grid, 256, 0, st>>>(Q, sQ, (const uint16_t *)dO, (const uint16_t *)Hq, N, bq, Nqb, units, upw, groups, phi, part);
+    if (fp8) wproj_grad_kernel<true><<<grid, 256, 0, st>>>(Q, sQ, (const uint16_t *)dO, (const uint16_t *)Hq, rm, N, bq, Nqb, units, upw, groups, phi, part);
+    else     wproj_grad_kernel<false><<<grid, 256, 0, st>>>(Q, sQ, (const uint16_t *)dO, (const uint16_t *)Hq, rm, N, bq, Nqb, units, upw, groups, phi, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     wproj_grad_reduce_kernel<<<dim3(kD * kD / 256, proj_per_head ? H : 1), 256, 0, st>>>(part, B, H, groups, proj_per_head, dW);

@@ -16,7 +16,7 @@ namespace sla {
 // per token), serial over the tokens of the block.  Bound: HBM (one streaming read of X).
 template <bool FP8>
 __global__ __launch_bounds__(256) void pool_kernel(const void *__restrict__ X, const float *__restrict__ scales,
-                                                   int N, int blk, int nblk, long units, double *__restrict__ mean)
+                                                   RowMap rm, int N, int blk, int nblk, long units, double *__restrict__ mean)
 {
     const long u = (long)blockIdx.x * 256 + threadIdx.x;
     if (u >= units) return;
@@ -30,7 +30,7 @@ __global__ __launch_bounds__(256) void pool_kernel(const void *__restrict__ X, c
 #pragma unroll
     for (int k = 0; k < 8; ++k) acc[k] = 0.0;
     if (FP8) {
-        const uint8_t *x = (const uint8_t *)X + ((size_t)bh * N + t0) * kD + c * 8;
+        const uint8_t *x = (const uint8_t *)X + rm.head(bh) + (size_t)t0 * rm.ts + c * 8;
         const double s = (double)scales[blkid];
         auto add_row = [&](uint2 w) {
             const f32x2 a0 = __builtin_amdgcn_cvt_pk_f32_fp8(w.x, false), a1 = __builtin_amdgcn_cvt_pk_f32_fp8(w.x, true);
@@ -44,21 +44,28 @@ __global__ __launch_bounds__(256) void pool_kernel(const void *__restrict__ X, c
         for (; t + 16 <= cnt; t += 16) {       // sixteen rows requested before the first is consumed
             uint2 w[16];
 #pragma unroll
-            for (int k = 0; k < 16; ++k) w[k] = *(const uint2 *)(x + (size_t)(t + k) * kD);
+            for (int k = 0; k < 16; ++k) w[k] = *(const uint2 *)(x + (size_t)(t + k) * rm.ts);
 #pragma unroll
             for (int k = 0; k < 16; ++k) add_row(w[k]);
         }
-        for (; t < cnt; ++t) add_row(*(const uint2 *)(x + (size_t)t * kD));
+        for (; t < cnt; ++t) add_row(*(const uint2 *)(x + (size_t)t * rm.ts));
     } else {
-        const uint16_t *x = (const uint16_t *)X + ((size_t)bh * N + t0) * kD + c * 8;
-#pragma unroll 8
-        for (int t = 0; t < cnt; ++t) {
-            const uint4 w = *(const uint4 *)(x + (size_t)t * kD);
+        const uint16_t *x = (const uint16_t *)X + rm.head(bh) + (size_t)t0 * rm.ts + c * 8;
+        auto add_row = [&](uint4 w) {
             acc[0] += (double)bf16_lo(w.x); acc[1] += (double)bf16_hi(w.x);
             acc[2] += (double)bf16_lo(w.y); acc[3] += (double)bf16_hi(w.y);
             acc[4] += (double)bf16_lo(w.z); acc[5] += (double)bf16_hi(w.z);
             acc[6] += (double)bf16_lo(w.w); acc[7] += (double)bf16_hi(w.w);
+        };
+        int t = 0;
+        for (; t + 16 <= cnt; t += 16) {        // sixteen rows requested before the first is consumed
+            uint4 w[16];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) w[k] = *(const uint4 *)(x + (size_t)(t + k) * rm.ts);
+#pragma unroll
+            for (int k = 0; k < 16; ++k) add_row(w[k]);
         }
+        for (; t < cnt; ++t) add_row(*(const uint4 *)(x + (size_t)t * rm.ts));
     }
     const double inv = 1.0 / (double)cnt;
     double *o = mean + blkid * kD + c * 8;
@@ -66,14 +73,14 @@ __global__ __launch_bounds__(256) void pool_kernel(const void *__restrict__ X, c
     for (int k = 0; k < 8; ++k) o[k] = acc[k] * inv;
 }
 
-hipError_t launch_pool(const void *X, const float *scales, bool fp8, int BH, int N, int blk,
+hipError_t launch_pool(const void *X, const float *scales, bool fp8, RowMap rm, int BH, int N, int blk,
                        double *mean, hipStream_t st)
 {
     const int nblk = (N + blk - 1) / blk;
     const long units = (long)BH * nblk * 8;
     const unsigned grid = (unsigned)((units + 255) / 256);
-    if (fp8) pool_kernel<true><<<grid, 256, 0, st>>>(X, scales, N, blk, nblk, units, mean);
-    else     pool_kernel<false><<<grid, 256, 0, st>>>(X, scales, N, blk, nblk, units, mean);
+    if (fp8) pool_kernel<true><<<grid, 256, 0, st>>>(X, scales, rm, N, blk, nblk, units, mean);
+    else     pool_kernel<false><<<grid, 256, 0, st>>>(X, scales, rm, N, blk, nblk, units, mean);
     return hipGetLastError();
 }
 
@@ -397,7 +404,7 @@ __global__ __launch_bounds__(64) void select_kernel(const double *__restrict__ S
 // (query block w, key block l), reading its K mean two channels per LDS access and channel d of the
 // Q mean out of lane d; the logits never leave registers.
 template <int KPL, bool FP8>
-__global__ __launch_bounds__(256) void classify_fused_kernel(const void *__restrict__ Q, const float *__restrict__ sQ,
+__global__ __launch_bounds__(256) void classify_fused_kernel(const void *__restrict__ Q, const float *__restrict__ sQ, RowMap rm,
                                                              const double *__restrict__ kbar, int N, int bq, int Nqb, int Nkb,
                                                              int k_c, int k_n, uint64_t *__restrict__ mbits, int lab_pitch,
                                                              int8_t *__restrict__ lab_dense, int32_t *__restrict__ crit_idx,
@@ -430,14 +437,14 @@ __global__ __launch_bounds__(256) void classify_fused_kernel(const void *__restr
         const int t0 = i * bq, cnt = min(bq, N - t0);
         double acc = 0.0;
         if (FP8) {
-            const uint8_t *x = (const uint8_t *)Q + ((size_t)bh * N + t0) * kD + lane;
+            const uint8_t *x = (const uint8_t *)Q + rm.head(bh) + (size_t)t0 * rm.ts + lane;
             const double sc = (double)sQ[row];
 #pragma unroll 16
-            for (int t = 0; t < cnt; ++t) acc += (double)__builtin_amdgcn_cvt_f32_fp8((int)x[(size_t)t * kD], 0) * sc;
+            for (int t = 0; t < cnt; ++t) acc += (double)__builtin_amdgcn_cvt_f32_fp8((int)x[(size_t)t * rm.ts], 0) * sc;
         } else {
-            const uint16_t *x = (const uint16_t *)Q + ((size_t)bh * N + t0) * kD + lane;
+            const uint16_t *x = (const uint16_t *)Q + rm.head(bh) + (size_t)t0 * rm.ts + lane;
 #pragma unroll 16
-            for (int t = 0; t < cnt; ++t) acc += (double)bf16_bits_to_f32(x[(size_t)t * kD]);
+            for (int t = 0; t < cnt; ++t) acc += (double)bf16_bits_to_f32(x[(size_t)t * rm.ts]);
         }
         mean = acc * (1.0 / (double)cnt);
         if (qbar_out) qbar_out[row * kD + lane] = mean;
@@ -722,23 +729,23 @@ hipError_t launch_select(const double *S, int pitch, long rows, int Nkb, int k_c
 }
 
 template <int KPL>
-static hipError_t launch_classify_fused_t(const void *Q, const float *sQ, bool fp8, const double *kbar, int BH, int N, int bq,
+static hipError_t launch_classify_fused_t(const void *Q, const float *sQ, bool fp8, RowMap rm, const double *kbar, int BH, int N, int bq,
                                           int Nqb, int Nkb, int k_c, int k_n, uint64_t *mbits, int lab_pitch, int8_t *lab_dense,
                                           int32_t *crit_idx, float *Pc, double *S_dense, double *qbar_out, float sm_scale,
                                           hipStream_t st)
 {
     dim3 grid((Nqb + 3) / 4, BH);
-    if (fp8) classify_fused_kernel<KPL, true><<<grid, 256, 0, st>>>(Q, sQ, kbar, N, bq, Nqb, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx, Pc, S_dense, qbar_out, sm_scale);
-    else     classify_fused_kernel<KPL, false><<<grid, 256, 0, st>>>(Q, sQ, kbar, N, bq, Nqb, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx, Pc, S_dense, qbar_out, sm_scale);
+    if (fp8) classify_fused_kernel<KPL, true><<<grid, 256, 0, st>>>(Q, sQ, rm, kbar, N, bq, Nqb, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx, Pc, S_dense, qbar_out, sm_scale);
+    else     classify_fused_kernel<KPL, false><<<grid, 256, 0, st>>>(Q, sQ, rm, kbar, N, bq, Nqb, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx, Pc, S_dense, qbar_out, sm_scale);
     return hipGetLastError();
 }
 
-hipError_t launch_classify_fused(const void *Q, const float *sQ, bool fp8, const double *kbar, int BH, int N, int bq, int Nkb,
+hipError_t launch_classify_fused(const void *Q, const float *sQ, bool fp8, RowMap rm, const double *kbar, int BH, int N, int bq, int Nkb,
                                  int k_c, int k_n, uint64_t *mbits, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx,
                                  float *Pc, double *S_dense, double *qbar_out, float sm_scale, hipStream_t st)
 {
     const int Nqb = (N + bq - 1) / bq;
-#define SLA_CF(K) return launch_classify_fused_t<K>(Q, sQ, fp8, kbar, BH, N, bq, Nqb, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx, Pc, S_dense, qbar_out, sm_scale, st)
+#define SLA_CF(K) return launch_classify_fused_t<K>(Q, sQ, fp8, rm, kbar, BH, N, bq, Nqb, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx, Pc, S_dense, qbar_out, sm_scale, st)
     if (Nkb <= 64) SLA_CF(1);
     if (Nkb <= 128) SLA_CF(2);
     if (Nkb <= 192) SLA_CF(3);

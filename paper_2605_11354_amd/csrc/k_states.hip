@@ -33,7 +33,7 @@ struct BlockRegs {
 // Rows past the end of the sequence (ragged last block of a head) repeat the last valid row: their
 // phi is multiplied by zero below, and finite stand-in values keep every product finite.
 template <bool FP8>
-__device__ __forceinline__ void load_block(BlockRegs<FP8> &r, const void *K, const void *V, size_t tok0, int valid, int lane)
+__device__ __forceinline__ void load_block(BlockRegs<FP8> &r, const void *K, const void *V, size_t tok0, int ts, int valid, int lane)
 {
     const int last = valid - 1;
     if (!FP8) {
@@ -42,7 +42,7 @@ __device__ __forceinline__ void load_block(BlockRegs<FP8> &r, const void *K, con
 #pragma unroll
         for (int x = 0; x < 8; ++x) {
             const int c = lane + 64 * x, t = min(c >> 3, last), col = (c & 7) * 8;
-            const uint4 w = *(const uint4 *)(Kg + (size_t)t * kD + col);
+            const uint4 w = *(const uint4 *)(Kg + (size_t)t * ts + col);
             r.k[4 * x] = w.x; r.k[4 * x + 1] = w.y; r.k[4 * x + 2] = w.z; r.k[4 * x + 3] = w.w;
         }
         // V: unit u = lane + 64 x is 4 channels (quad u%16) x 8 consecutive tokens (group u/16)
@@ -52,7 +52,7 @@ __device__ __forceinline__ void load_block(BlockRegs<FP8> &r, const void *K, con
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 const int t = min(tg * 8 + k, last);
-                const uint2 w = *(const uint2 *)(Vg + (size_t)t * kD + 4 * eq);
+                const uint2 w = *(const uint2 *)(Vg + (size_t)t * ts + 4 * eq);
                 r.v[16 * x + 2 * k] = w.x;
                 r.v[16 * x + 2 * k + 1] = w.y;
             }
@@ -63,7 +63,7 @@ __device__ __forceinline__ void load_block(BlockRegs<FP8> &r, const void *K, con
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
             const int c = lane + 64 * x, t = min(c >> 2, last), col = (c & 3) * 16;
-            const uint4 w = *(const uint4 *)(Kg + (size_t)t * kD + col);
+            const uint4 w = *(const uint4 *)(Kg + (size_t)t * ts + col);
             r.k[4 * x] = w.x; r.k[4 * x + 1] = w.y; r.k[4 * x + 2] = w.z; r.k[4 * x + 3] = w.w;
         }
         // V: unit u = lane + 64 x is 4 channels (quad u%16) x 8 consecutive tokens (group u/16)
@@ -73,7 +73,7 @@ __device__ __forceinline__ void load_block(BlockRegs<FP8> &r, const void *K, con
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 const int t = min(tg * 8 + k, last);
-                r.v[8 * x + k] = *(const uint32_t *)(Vg + (size_t)t * kD + 4 * eq);
+                r.v[8 * x + k] = *(const uint32_t *)(Vg + (size_t)t * ts + 4 * eq);
             }
         }
     }
@@ -150,7 +150,7 @@ __device__ __forceinline__ void stage_block(const BlockRegs<FP8> &r, uint16_t *K
 template <bool FP8>
 __global__ __launch_bounds__(64 * kWavesPerWG) __attribute__((amdgpu_waves_per_eu(2, 2))) void states_kernel(const void *__restrict__ K, const void *__restrict__ V,
                                                                   const float *__restrict__ sK, const float *__restrict__ sV,
-                                                                  int N, int Nkb, long nblocks, int per_wave,
+                                                                  RowMap rm, int N, int Nkb, long nblocks, int per_wave,
                                                                   uint16_t *__restrict__ hT, uint16_t *__restrict__ Vp,
                                                                   double *__restrict__ kbar, int phi, unsigned state_wgs,
                                                                   const uint16_t *__restrict__ W, uint16_t *__restrict__ WT)
@@ -173,14 +173,14 @@ __global__ __launch_bounds__(64 * kWavesPerWG) __attribute__((amdgpu_waves_per_e
         const long bh = blk / Nkb;
         const int t0 = (int)(blk - bh * Nkb) * kBK;
         valid = min(kBK, N - t0);
-        tok0 = ((size_t)bh * N + t0) * kD;
+        tok0 = rm.head(bh) + (size_t)t0 * rm.ts;
     };
 
     BlockRegs<FP8> regs;
     {
         size_t tok0; int valid;
         block_geometry(first, tok0, valid);
-        load_block<FP8>(regs, K, V, tok0, valid, lane);
+        load_block<FP8>(regs, K, V, tok0, rm.ts, valid, lane);
     }
     for (long blk = first; blk < last; ++blk) {
         size_t tok0; int valid;
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(64 * kWavesPerWG) __attribute__((amdgpu_waves_per_e
         if (blk + 1 < last) {                        // next block's loads fly while this one is processed
             size_t tn; int vn;
             block_geometry(blk + 1, tn, vn);
-            load_block<FP8>(regs, K, V, tn, vn, lane);
+            load_block<FP8>(regs, K, V, tn, rm.ts, vn, lane);
         }
         wave_lds_sync();
 
@@ -310,7 +310,7 @@ __global__ __launch_bounds__(64 * kWavesPerWG) __attribute__((amdgpu_waves_per_e
     }
 }
 
-hipError_t launch_states(const void *K, const void *V, const float *sK, const float *sV, bool fp8,
+hipError_t launch_states(const void *K, const void *V, const float *sK, const float *sV, bool fp8, RowMap rm,
                          int BH, int N, void *hT, void *Vp, double *kbar, int phi, const void *W, int nW, void *WT, hipStream_t st)
 {
     const int Nkb = (N + kBK - 1) / kBK;
@@ -321,8 +321,8 @@ hipError_t launch_states(const void *K, const void *V, const float *sK, const fl
     const long waves = (nblocks + per_wave - 1) / per_wave;
     const unsigned grid = (unsigned)((waves + kWavesPerWG - 1) / kWavesPerWG);
     const unsigned extra = W != nullptr ? (unsigned)nW : 0u;
-    if (fp8) states_kernel<true><<<grid + extra, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, kbar, phi, grid, (const uint16_t *)W, (uint16_t *)WT);
-    else     states_kernel<false><<<grid + extra, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, kbar, phi, grid, (const uint16_t *)W, (uint16_t *)WT);
+    if (fp8) states_kernel<true><<<grid + extra, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, rm, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, kbar, phi, grid, (const uint16_t *)W, (uint16_t *)WT);
+    else     states_kernel<false><<<grid + extra, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, rm, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, kbar, phi, grid, (const uint16_t *)W, (uint16_t *)WT);
     return hipGetLastError();
 }
 

@@ -27,6 +27,7 @@ bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
 struct Plan {
     int BH, Nqb, Nkb, k_c, k_n, lab_pitch, s_pitch, nW;
+    sla::RowMap rm;      // where the rows of a (b,h) live in Q, K, V, O, dO
     float sm_scale;
     bool fp8, empty;
     size_t off_qbar, off_kbar, off_scores, off_lab, off_crit, off_hT, off_Hq, off_WT, off_Vp, off_dWpart, total;
@@ -43,6 +44,7 @@ sla_status_t make_plan(const sla_params_t *p, Plan &pl)
     if (p->dtype != SLA_BF16 && p->dtype != SLA_FP8_E4M3) return fail(SLA_ERR_INVALID_ARG, "unknown dtype %d", p->dtype);
     if (p->phi != SLA_PHI_SOFTMAX && p->phi != SLA_PHI_ELU1) return fail(SLA_ERR_INVALID_ARG, "unknown feature map %d", p->phi);
     if (p->proj_per_head != 0 && p->proj_per_head != 1) return fail(SLA_ERR_INVALID_ARG, "proj_per_head must be 0 or 1");
+    if (p->layout != SLA_LAYOUT_BHND && p->layout != SLA_LAYOUT_BNHD) return fail(SLA_ERR_INVALID_ARG, "unknown layout %d", p->layout);
     if (!(p->sm_scale >= 0.f) || !std::isfinite(p->sm_scale)) return fail(SLA_ERR_INVALID_ARG, "sm_scale must be finite and >= 0");
     memset(&pl, 0, sizeof pl);
     pl.empty = p->B == 0 || p->H == 0 || p->N == 0;
@@ -55,6 +57,7 @@ sla_status_t make_plan(const sla_params_t *p, Plan &pl)
     pl.sm_scale = p->sm_scale > 0.f ? p->sm_scale : 0.125f;   // 1/sqrt(64)
     pl.fp8 = p->dtype == SLA_FP8_E4M3;
     pl.nW = p->proj_per_head ? p->H : 1;
+    pl.rm = sla::make_rowmap(p->layout == SLA_LAYOUT_BNHD, p->H > 0 ? p->H : 1, p->N);
 
     if (p->k_crit >= 0 || p->k_neg >= 0) {
         if (p->k_crit < 0 || p->k_neg < 0) return fail(SLA_ERR_INVALID_ARG, "k_crit and k_neg must both be given or both be -1");
@@ -129,12 +132,12 @@ sla_status_t run_classify(const sla_params_t *p, const Plan &pl, const void *Q, 
     int32_t *crit = crit_out ? crit_out : at<int32_t>(ws, pl.off_crit);
     const bool fused = pl.Nkb <= 256;   // short rows: Q means, logits and classification in one launch
     if (!pooled) {                      // sla_forward gets the K means from the states pass (and pools Q itself if needed)
-        if (!fused) SLA_HIP(sla::launch_pool(Q, sQ, pl.fp8, pl.BH, p->N, p->bq, qbar, st));
-        SLA_HIP(sla::launch_pool(K, sK, pl.fp8, pl.BH, p->N, p->bk, kbar, st));
+        if (!fused) SLA_HIP(sla::launch_pool(Q, sQ, pl.fp8, pl.rm, pl.BH, p->N, p->bq, qbar, st));
+        SLA_HIP(sla::launch_pool(K, sK, pl.fp8, pl.rm, pl.BH, p->N, p->bk, kbar, st));
     }
     SLA_HIP(mark(2));
     if (fused) {
-        SLA_HIP(sla::launch_classify_fused(Q, sQ, pl.fp8, kbar, pl.BH, p->N, p->bq, pl.Nkb, pl.k_c, pl.k_n, at<uint64_t>(ws, pl.off_lab),
+        SLA_HIP(sla::launch_classify_fused(Q, sQ, pl.fp8, pl.rm, kbar, pl.BH, p->N, p->bq, pl.Nkb, pl.k_c, pl.k_n, at<uint64_t>(ws, pl.off_lab),
                                            pl.lab_pitch, labels, pl.k_c > 0 ? crit : nullptr, Pc, scores_out,
                                            qbar_out ? qbar_out : nullptr, pl.sm_scale, st));
         SLA_HIP(mark(3));
@@ -212,7 +215,7 @@ sla_status_t sla_linear_states(const sla_params_t *p, const void *K, const void 
     if (pl.empty) return SLA_OK;
     SLA_REQ_PTR(K); SLA_REQ_PTR(V); SLA_REQ_PTR(hT);
     if (pl.fp8) { SLA_REQ_PTR(sK); SLA_REQ_PTR(sV); }
-    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, hT, nullptr, nullptr, p->phi, nullptr, 0, nullptr, (hipStream_t)stream));
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.rm, pl.BH, p->N, hT, nullptr, nullptr, p->phi, nullptr, 0, nullptr, (hipStream_t)stream));
     return SLA_OK;
 }
 
@@ -252,8 +255,8 @@ sla_status_t sla_sparse_combine(const sla_params_t *p, const void *Q, const void
                                        at<uint64_t>(workspace, pl.off_lab), pl.lab_pitch, at<int32_t>(workspace, pl.off_crit), st));
     if (Hq) SLA_HIP(sla::launch_transpose_w(W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
     // the attention kernel reads V as transposed tiles; the states pass produces them (its states go to the workspace)
-    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp), nullptr, p->phi, nullptr, 0, nullptr, st));
-    SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), sQ, sK, sV, pl.fp8, at<int32_t>(workspace, pl.off_crit), pl.k_c, Hq,
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.rm, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp), nullptr, p->phi, nullptr, 0, nullptr, st));
+    SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), sQ, sK, sV, pl.fp8, pl.rm, at<int32_t>(workspace, pl.off_crit), pl.k_c, Hq,
                                at<void>(workspace, pl.off_WT), p->proj_per_head, p->phi, p->B, p->H, p->N, p->bq, pl.sm_scale, O, st));
     return SLA_OK;
 }
@@ -273,17 +276,17 @@ static sla_status_t forward_impl(const sla_params_t *p, const void *Q, const voi
     auto mark = [&](int i) { return ev ? hipEventRecord(ev[i], st) : hipSuccess; };
     if (launched) *launched = true;
     SLA_HIP(mark(0));
-    if (pl.Nkb > 256) SLA_HIP(sla::launch_pool(Q, sQ, pl.fp8, pl.BH, p->N, p->bq, at<double>(workspace, pl.off_qbar), st));
+    if (pl.Nkb > 256) SLA_HIP(sla::launch_pool(Q, sQ, pl.fp8, pl.rm, pl.BH, p->N, p->bq, at<double>(workspace, pl.off_qbar), st));
     SLA_HIP(mark(1));     // states + V^T tiles + block means of K: the one pass over K and V besides the attention kernel;
                           // a few extra workgroups of the same launch lay out W_proj for the attention epilogue
-    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp),
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.rm, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp),
                                at<double>(workspace, pl.off_kbar), p->phi, W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
     if ((s = run_classify(p, pl, Q, K, sQ, sK, labels, nullptr, nullptr, nullptr, nullptr, nullptr, workspace, st, ev, true)) != SLA_OK) return s;
     SLA_HIP(mark(4));
     SLA_HIP(sla::launch_aggregate(at<uint64_t>(workspace, pl.off_lab), pl.lab_pitch, at<void>(workspace, pl.off_hT), pl.BH, pl.Nqb,
                                   pl.Nkb, at<void>(workspace, pl.off_Hq), st));
     SLA_HIP(mark(5));
-    SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), sQ, sK, sV, pl.fp8, at<int32_t>(workspace, pl.off_crit), pl.k_c,
+    SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), sQ, sK, sV, pl.fp8, pl.rm, at<int32_t>(workspace, pl.off_crit), pl.k_c,
                                at<void>(workspace, pl.off_Hq), at<void>(workspace, pl.off_WT), p->proj_per_head, p->phi, p->B, p->H,
                                p->N, p->bq, pl.sm_scale, O, st));
     SLA_HIP(mark(6));
@@ -312,21 +315,22 @@ sla_status_t sla_wproj_grad(const sla_params_t *p, const void *Q, const float *s
     SLA_REQ_PTR(Q); SLA_REQ_PTR(dO);
     if (pl.fp8) SLA_REQ_PTR(sQ);
     if ((s = check_ws(pl, workspace, workspace_bytes)) != SLA_OK) return s;
-    SLA_HIP(sla::launch_wproj_grad(Q, sQ, pl.fp8, dO, at<void>(workspace, pl.off_Hq), p->B, p->H, p->N, p->bq, p->proj_per_head, p->phi,
+    SLA_HIP(sla::launch_wproj_grad(Q, sQ, pl.fp8, pl.rm, dO, at<void>(workspace, pl.off_Hq), p->B, p->H, p->N, p->bq, p->proj_per_head, p->phi,
                                    at<float>(workspace, pl.off_dWpart), dW, st));
     return SLA_OK;
 }
 
-sla_status_t sla_quantise_e4m3(const void *X, int32_t B, int32_t H, int32_t N, int32_t blk, void *codes, float *scales,
-                               void *stream)
+sla_status_t sla_quantise_e4m3(const void *X, int32_t B, int32_t H, int32_t N, int32_t blk, int32_t layout, void *codes,
+                               float *scales, void *stream)
 {
+    if (layout != SLA_LAYOUT_BHND && layout != SLA_LAYOUT_BNHD) return fail(SLA_ERR_INVALID_ARG, "unknown layout %d", layout);
     if (B < 0 || H < 0 || N < 0) return fail(SLA_ERR_INVALID_ARG, "negative size (B=%d H=%d N=%d)", B, H, N);
     if (blk != 64 && blk != 128) return fail(SLA_ERR_UNSUPPORTED, "block of %d tokens; only 64 and 128 are implemented", blk);
     if ((long)B * H > 0x7FFFFFF0L / 4) return fail(SLA_ERR_UNSUPPORTED, "B*H = %ld is too large", (long)B * H);
     if (B == 0 || H == 0 || N == 0) return SLA_OK;
     SLA_REQ_PTR(X); SLA_REQ_PTR(codes);
     if (!scales) return fail(SLA_ERR_INVALID_ARG, "scales is NULL");
-    SLA_HIP(sla::launch_quantise_e4m3(X, B * H, N, blk, codes, scales, (hipStream_t)stream));
+    SLA_HIP(sla::launch_quantise_e4m3(X, sla::make_rowmap(layout == SLA_LAYOUT_BNHD, H, N), B * H, N, blk, codes, scales, (hipStream_t)stream));
     return SLA_OK;
 }
 

@@ -11,6 +11,23 @@ constexpr int kBK = 64;         // key block size
 constexpr int kStateRows = 65;  // rows of a block state: 64 rows of h^T plus one row of z
 constexpr int kStateElems = kStateRows * kD;   // 4160
 
+// Where the rows of one (b, h) live inside a Q / K / V / O tensor: element offset of (bh, token t, channel 0) is
+// head(bh) + t * ts.  Head-major [B,H,N,64]: bs = H N 64, hs = N 64, ts = 64; token-major [B,N,H,64] (what a fused
+// qkv projection leaves): bs = N H 64, hs = 64, ts = 64 H.  A row is 64 contiguous elements either way.
+struct RowMap {
+    long bs, hs;
+    int ts, H;
+    __host__ __device__ size_t head(long bh) const { return (size_t)(bh / H) * bs + (size_t)(bh % H) * hs; }
+};
+inline RowMap make_rowmap(int token_major, int H, int N)
+{
+    RowMap m;
+    m.H = H;
+    if (token_major) { m.bs = (long)N * H * 64; m.hs = 64; m.ts = 64 * H; }
+    else             { m.bs = (long)H * N * 64; m.hs = (long)N * 64; m.ts = 64; }
+    return m;
+}
+
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;

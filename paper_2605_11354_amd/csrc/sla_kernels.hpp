@@ -3,11 +3,13 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include "sla_common.hpp"
 
 namespace sla {
 
 // block mean-pool: X [BH,N,64] (bf16 or e4m3 + scales [BH,nblk]) -> mean fp64 [BH,nblk,64]
-hipError_t launch_pool(const void *X, const float *scales, bool fp8, int BH, int N, int blk,
+// rm (here and below): where the rows of a (b,h) live in the Q / K / V / O tensors (head-major or token-major)
+hipError_t launch_pool(const void *X, const float *scales, bool fp8, RowMap rm, int BH, int N, int blk,
                        double *mean, hipStream_t st);
 
 // pooled logits: S[bh][i][j] = fma-chain_d(qbar[bh][i][d], kbar[bh][j][d]); row pitch `pitch`
@@ -23,7 +25,7 @@ hipError_t launch_select(const double *S, int pitch, long rows, int Nkb, int k_c
 
 // short rows (Nkb <= 256): block mean of Q + pooled logits + classifier in one launch; kbar holds the
 // block means of K.  Outputs as launch_select; qbar_out (optional) receives the block means of Q.
-hipError_t launch_classify_fused(const void *Q, const float *sQ, bool fp8, const double *kbar, int BH, int N, int bq, int Nkb,
+hipError_t launch_classify_fused(const void *Q, const float *sQ, bool fp8, RowMap rm, const double *kbar, int BH, int N, int bq, int Nkb,
                                  int k_c, int k_n, uint64_t *mbits, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx,
                                  float *Pc, double *S_dense, double *qbar_out, float sm_scale, hipStream_t st);
 
@@ -36,7 +38,7 @@ hipError_t launch_labels_prepare(const int8_t *lab_dense, long rows, int Nkb, in
 // transposed, key-permuted V tiles the attention kernel reads, and kbar [BH,Nkb,64] fp64, the
 // block means of K (same arithmetic as launch_pool); NULL skips either.  With W != NULL the launch also
 // does the work of launch_transpose_w(W, nW, WT) in nW extra workgroups.
-hipError_t launch_states(const void *K, const void *V, const float *sK, const float *sV, bool fp8,
+hipError_t launch_states(const void *K, const void *V, const float *sK, const float *sV, bool fp8, RowMap rm,
                          int BH, int N, void *hT, void *Vp, double *kbar, int phi, const void *W, int nW, void *WT, hipStream_t st);
 
 // Hq[bh][i][:] = sum over j with lab_pad[bh][i][j] == 1 of hT[bh][j][:]   (bf16 MFMA, fp32 accumulate)
@@ -48,7 +50,7 @@ hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st);
 
 // block-sparse attention over critical blocks + linear output + projection + sum
 hipError_t launch_attend(const void *Q, const void *K, const void *Vp,
-                         const float *sQ, const float *sK, const float *sV, bool fp8,
+                         const float *sQ, const float *sK, const float *sV, bool fp8, RowMap rm,
                          const int32_t *crit_idx, int k_c, const void *Hq, const void *WT,
                          int proj_per_head, int phi, int B, int H, int N, int bq, float sm_scale,
                          void *O, hipStream_t st);
@@ -56,10 +58,10 @@ hipError_t launch_attend(const void *Q, const void *K, const void *Vp,
 // dW[w] = sum over the (b,h) that use projection matrix w and their tokens of O_lin^T dO, O_lin recomputed from Q and
 // the aggregated states Hq; part is scratch of wproj_grad_groups(BH, N) * BH * 64 * 64 floats
 int wproj_grad_groups(int BH, int N);
-hipError_t launch_wproj_grad(const void *Q, const float *sQ, bool fp8, const void *dO, const void *Hq, int B, int H, int N, int bq,
+hipError_t launch_wproj_grad(const void *Q, const float *sQ, bool fp8, RowMap rm, const void *dO, const void *Hq, int B, int H, int N, int bq,
                              int proj_per_head, int phi, float *part, float *dW, hipStream_t st);
 
 // X bf16 [BH,N,64] -> codes e4m3 [BH,N,64] + fp32 scales [BH, ceil(N/blk)], blk = 64 or 128 (App. B.2 per token block)
-hipError_t launch_quantise_e4m3(const void *X, int BH, int N, int blk, void *codes, float *scales, hipStream_t st);
+hipError_t launch_quantise_e4m3(const void *X, RowMap rm, int BH, int N, int blk, void *codes, float *scales, hipStream_t st);
 
 }  // namespace sla

@@ -393,6 +393,47 @@ def test_quantiser_reproduces_the_benchmark_inputs():
     assert torch.equal(sq, case.sQ) and torch.equal(sk, case.sK) and torch.equal(sv, case.sV)
 
 
+@pytest.mark.parametrize("name", ["c0_tail150", "c0_bq128_tail", "c3_small", "c1_small", "c2_small", "c4_small", "c4_bq64_tail"])
+def test_token_major_layout_gives_identical_results(name):
+    """Q, K, V, O, dO as [B,N,H,D] (the heads of a fused qkv projection side by side) instead of [B,H,N,D]: every
+    kernel reads the same rows through a different stride, so outputs, labels and the gradient are the same bits."""
+    from paper_2605_11354_amd import binding as B
+    case = _case(name)
+    c = case.cfg
+    O, lab = case.forward()
+    g = torch.randn((c.B, c.H, c.N, 64), device="cuda").to(torch.bfloat16)
+    nW = c.H if c.proj_per_head else 1
+    dW = torch.empty((nW, 64, 64), dtype=torch.float32, device="cuda")
+    B.sla_wproj_grad(case.p, case.Q, g, dW, case.ws, case.sQ)
+    tm = lambda x: x.permute(0, 2, 1, 3).contiguous()            # [B,H,N,D] -> [B,N,H,D]
+    pt = B.make_params(c.B, c.H, c.N, c.bq, c.bk, c.crit_frac, c.neg_frac, case.k_c, case.k_n, c.dtype, c.proj_per_head,
+                       layout="bnhd")
+    Ot = torch.zeros((c.B, c.N, c.H, 64), dtype=torch.bfloat16, device="cuda")
+    labt = torch.zeros_like(lab)
+    ws = B.alloc_workspace(pt)
+    B.sla_forward(pt, tm(case.Q), tm(case.K), tm(case.V), case.W, Ot, labt, case.sQ, case.sK, case.sV, ws)
+    dWt = torch.empty_like(dW)
+    B.sla_wproj_grad(pt, tm(case.Q), tm(g), dWt, ws, case.sQ)
+    torch.cuda.synchronize()
+    assert torch.equal(labt, lab)
+    assert torch.equal(tm(O).view(torch.int16), Ot.view(torch.int16))
+    assert torch.equal(dWt, dW)
+
+
+def test_quantiser_token_major_layout(oracle):
+    from paper_2605_11354_amd import binding as B
+    x = torch.randn((2, 3, 333, 64), device="cuda").to(torch.bfloat16)
+    codes = torch.empty((2, 3, 333, 64), dtype=torch.uint8, device="cuda")
+    scales = torch.empty((2, 3, 3), dtype=torch.float32, device="cuda")
+    B.sla_quantise_e4m3(x, 128, codes, scales)
+    xt = x.permute(0, 2, 1, 3).contiguous()
+    ct = torch.empty((2, 333, 3, 64), dtype=torch.uint8, device="cuda")
+    st = torch.empty_like(scales)
+    B.sla_quantise_e4m3(xt, 128, ct, st, layout="bnhd")
+    torch.cuda.synchronize()
+    assert torch.equal(ct.permute(0, 2, 1, 3), codes) and torch.equal(st, scales)
+
+
 def test_errors_are_reported_not_launched():
     from paper_2605_11354_amd import binding as B
     case = G.Case(C0)

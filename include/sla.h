@@ -99,6 +99,20 @@ sla_status_t sla_forward(const sla_params_t *p,
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The forward with the block labels given instead of computed: steps 2-4 on the labels of an earlier call
+ * (e.g. the masks of one layer reused by the next, whose Q and K differ little).  Arguments as sla_forward, except
+ *   labels   in   int8 [B,H,Nqb,Nkb], 2 critical / 1 marginal / 0 negligible.  A row may hold any number of marginal
+ *                 blocks; of its critical blocks the first k_crit (ascending index) are attended, so rows taken from
+ *                 sla_forward with the same params are reproduced exactly.
+ * Leaves the workspace in the state sla_forward leaves it in (sla_wproj_grad may follow).
+ */
+sla_status_t sla_forward_with_labels(const sla_params_t *p,
+                                     const void *Q, const void *K, const void *V,
+                                     const float *sQ, const float *sK, const float *sV,
+                                     const void *W_proj, const int8_t *labels, void *O,
+                                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Gradient with respect to W_proj, the only parameter the method trains (section 3.3; Alg. 1 step 10:
  * O = O_sparse + O_lin W_O):
  *     dW[w][d_in][d_out] = sum over the (b,h) that use matrix w and over their tokens t of

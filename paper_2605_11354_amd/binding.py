@@ -20,6 +20,7 @@ SLA_BF16, SLA_FP8_E4M3 = 0, 1
 STATE_ROWS = 65          # rows of one block state: 64 rows of h^T and one row of z
 EXPORTS = ["sla_resolve_counts", "sla_workspace_bytes", "sla_forward", "sla_pool_classify", "sla_linear_states",
            "sla_marginal_aggregate", "sla_sparse_combine", "sla_forward_profiled", "sla_wproj_grad", "sla_quantise_e4m3",
+           "sla_forward_with_labels",
            "sla_strerror", "sla_last_error", "sla_stage_name"]
 NUM_STAGES = 6
 
@@ -55,7 +56,7 @@ def lib() -> C.CDLL:
         _lib.sla_strerror.restype = C.c_char_p
         _lib.sla_last_error.restype = C.c_char_p
         _lib.sla_stage_name.restype = C.c_char_p
-        for name in EXPORTS[:10]:
+        for name in EXPORTS[:11]:
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -137,6 +138,14 @@ def sla_marginal_aggregate(p, labels, hT, Hq, workspace=None):
     _check(lib().sla_marginal_aggregate(C.byref(p), _ptr(labels), _ptr(hT), _ptr(Hq), _ptr(ws), C.c_size_t(ws.numel()),
                                         _stream()), "sla_marginal_aggregate")
     return Hq
+
+
+def sla_forward_with_labels(p, Q, K, V, W_proj, labels, O, sQ=None, sK=None, sV=None, workspace=None):
+    ws = workspace if workspace is not None else alloc_workspace(p, Q.device)
+    _check(lib().sla_forward_with_labels(C.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(sQ), _ptr(sK), _ptr(sV), _ptr(W_proj),
+                                         _ptr(labels), _ptr(O), _ptr(ws), C.c_size_t(ws.numel()), _stream()),
+           "sla_forward_with_labels")
+    return O
 
 
 def sla_quantise_e4m3(X, blk, codes, scales, layout="bhnd"):

@@ -261,6 +261,32 @@ sla_status_t sla_sparse_combine(const sla_params_t *p, const void *Q, const void
     return SLA_OK;
 }
 
+sla_status_t sla_forward_with_labels(const sla_params_t *p, const void *Q, const void *K, const void *V, const float *sQ,
+                                     const float *sK, const float *sV, const void *W_proj, const int8_t *labels, void *O,
+                                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    Plan pl;
+    sla_status_t s = make_plan(p, pl);
+    if (s != SLA_OK) return s;
+    if (pl.empty) return SLA_OK;
+    SLA_REQ_PTR(Q); SLA_REQ_PTR(K); SLA_REQ_PTR(V); SLA_REQ_PTR(W_proj); SLA_REQ_PTR(O);
+    if (!labels) return fail(SLA_ERR_INVALID_ARG, "labels is NULL");
+    if (pl.fp8) { SLA_REQ_PTR(sQ); SLA_REQ_PTR(sK); SLA_REQ_PTR(sV); }
+    if ((s = check_ws(pl, workspace, workspace_bytes)) != SLA_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    // the forward without its classifier: the given labels become the bit masks and critical lists of the workspace
+    SLA_HIP(sla::launch_labels_prepare(labels, (long)pl.BH * pl.Nqb, pl.Nkb, pl.k_c > 0 ? pl.k_c : 1,
+                                       at<uint64_t>(workspace, pl.off_lab), pl.lab_pitch, at<int32_t>(workspace, pl.off_crit), st));
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.rm, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp),
+                               nullptr, p->phi, W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
+    SLA_HIP(sla::launch_aggregate(at<uint64_t>(workspace, pl.off_lab), pl.lab_pitch, at<void>(workspace, pl.off_hT), pl.BH, pl.Nqb, pl.Nkb,
+                                  at<void>(workspace, pl.off_Hq), st));
+    SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), sQ, sK, sV, pl.fp8, pl.rm, at<int32_t>(workspace, pl.off_crit), pl.k_c,
+                               at<void>(workspace, pl.off_Hq), at<void>(workspace, pl.off_WT), p->proj_per_head, p->phi, p->B, p->H,
+                               p->N, p->bq, pl.sm_scale, O, st));
+    return SLA_OK;
+}
+
 static sla_status_t forward_impl(const sla_params_t *p, const void *Q, const void *K, const void *V, const float *sQ,
                                  const float *sK, const float *sV, const void *W_proj, void *O, int8_t *labels,
                                  void *workspace, size_t workspace_bytes, void *stream, hipEvent_t *ev, bool *launched)

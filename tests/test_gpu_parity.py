@@ -434,6 +434,32 @@ def test_quantiser_token_major_layout(oracle):
     assert torch.equal(ct.permute(0, 2, 1, 3), codes) and torch.equal(st, scales)
 
 
+@pytest.mark.parametrize("name", ["c0_tail150", "c3_small", "c1_small", "c2_small", "c4_small"])
+def test_forward_with_given_labels_reproduces_the_forward(oracle, name):
+    """Masks of one call reused by another: the labels sla_forward returns, fed back, give the same output bits and
+    leave the workspace ready for the gradient; other labels (all marginal) are honoured as given."""
+    from paper_2605_11354_amd import binding as B
+    case = _case(name)
+    c = case.cfg
+    O, lab = case.forward()
+    dO = torch.randn((c.B, c.H, c.N, 64), device="cuda").to(torch.bfloat16)
+    dW = torch.empty((c.H if c.proj_per_head else 1, 64, 64), dtype=torch.float32, device="cuda")
+    B.sla_wproj_grad(case.p, case.Q, dO, dW, case.ws, case.sQ)
+    ws2 = B.alloc_workspace(case.p)
+    O2 = torch.zeros_like(O)
+    B.sla_forward_with_labels(case.p, case.Q, case.K, case.V, case.W, lab, O2, case.sQ, case.sK, case.sV, ws2)
+    dW2 = torch.empty_like(dW)
+    B.sla_wproj_grad(case.p, case.Q, dO, dW2, ws2, case.sQ)
+    torch.cuda.synchronize()
+    assert torch.equal(O2.view(torch.int16), O.view(torch.int16)) and torch.equal(dW2, dW)
+    allm = torch.ones_like(lab)                                   # every block marginal: pure linear attention
+    B.sla_forward_with_labels(case.p, case.Q, case.K, case.V, case.W, allm, O2, case.sQ, case.sK, case.sV, ws2)
+    torch.cuda.synchronize()
+    ref = case.oracle_attend(oracle, allm.cpu().numpy())
+    got = G.gather_blocks(G.bf16_tensor_to_f64(O2), ref["sel"], c.bq, c.H)
+    G.assert_output(got, ref["O"], c.dtype, f"{name} all-marginal labels")
+
+
 def test_errors_are_reported_not_launched():
     from paper_2605_11354_amd import binding as B
     case = G.Case(C0)

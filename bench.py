@@ -157,7 +157,7 @@ def main() -> int:
     }
 
     if args.with_grad:
-        # gradient of the projection (next row of the scope table): reads Q, dO and the aggregated states once
+        # gradient of the projection: reads Q, dO and the aggregated states once
         nW = cfg.H if cfg.proj_per_head else 1
         dO = torch.randn((cfg.B, cfg.H, cfg.N, 64), device="cuda").to(torch.bfloat16)
         dW = torch.empty((nW, 64, 64), dtype=torch.float32, device="cuda")

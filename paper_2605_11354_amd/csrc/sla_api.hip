@@ -121,7 +121,7 @@ sla_status_t check_ws(const Plan &pl, const void *ws, size_t bytes)
 
 template <class T> T *at(void *ws, size_t off) { return (T *)((char *)ws + off); }
 
-// steps a1-a3: pool, logits, classifier.  Leaves padded labels and critical lists in the workspace.
+// Pooling, pooled logits and classifier.  Leaves the marginal bit masks and the critical lists in the workspace.
 sla_status_t run_classify(const sla_params_t *p, const Plan &pl, const void *Q, const void *K, const float *sQ,
                           const float *sK, int8_t *labels, int32_t *crit_out, float *Pc, double *qbar_out,
                           double *kbar_out, double *scores_out, void *ws, hipStream_t st, hipEvent_t *ev = nullptr, bool pooled = false)

@@ -41,7 +41,7 @@ hipError_t launch_labels_prepare(const int8_t *lab_dense, long rows, int Nkb, in
 hipError_t launch_states(const void *K, const void *V, const float *sK, const float *sV, bool fp8, RowMap rm,
                          int BH, int N, void *hT, void *Vp, double *kbar, int phi, const void *W, int nW, void *WT, hipStream_t st);
 
-// Hq[bh][i][:] = sum over j with lab_pad[bh][i][j] == 1 of hT[bh][j][:]   (bf16 MFMA, fp32 accumulate)
+// Hq[bh][i][:] = sum over the key blocks j whose bit is set in row (bh,i) of mbits of hT[bh][j][:]   (bf16 MFMA, fp32 accumulate)
 hipError_t launch_aggregate(const uint64_t *mbits, int lab_pitch, const void *hT, int BH, int Nqb,
                             int Nkb, void *Hq, hipStream_t st);
 

@@ -236,7 +236,7 @@ __device__ __forceinline__ double key_to_logit(uint64_t key)
 // r lowest-index keys == T.  Requires 1 <= k <= Nkb.  Uniform across the wave.  hist: 256 counters private
 // to this wave (LDS operations of one wave execute in order, so no workgroup barrier is involved).
 template <int KPL>
-__device__ void radix_select(const uint64_t (&key)[KPL], int Nkb, int k, uint32_t *hist, uint64_t &T, int &r)
+__device__ __forceinline__ void radix_select(const uint64_t (&key)[KPL], int Nkb, int k, uint32_t *hist, uint64_t &T, int &r)
 {
     const int lane = threadIdx.x & 63;
     uint64_t prefix = 0;
@@ -294,7 +294,7 @@ __device__ void radix_select(const uint64_t (&key)[KPL], int Nkb, int k, uint32_
 // Classifies one score row held by one wave (key[m] of lane l belongs to block j = 64 m + l; slots with
 // j >= Nkb hold ~0) and writes labels / critical list / compressed softmax for that row.
 template <int KPL>
-__device__ void classify_row_wave(uint64_t (&key)[KPL], long row, int Nkb, int k_c, int k_n, uint32_t *hist,
+__device__ __forceinline__ void classify_row_wave(uint64_t (&key)[KPL], long row, int Nkb, int k_c, int k_n, uint32_t *hist,
                                   uint64_t *__restrict__ mbits, int lab_pitch, int8_t *__restrict__ lab_dense,
                                   int32_t *__restrict__ crit_idx, float *__restrict__ Pc, float sm_scale)
 {
@@ -512,7 +512,7 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, SelShared &sh, u
 }
 
 template <int KPT, int NT>
-__device__ void block_radix_select(const uint64_t (&key)[KPT], int j0, int Nkb, int k, SelShared &sh, uint64_t &T, int &r)
+__device__ __forceinline__ void block_radix_select(const uint64_t (&key)[KPT], int j0, int Nkb, int k, SelShared &sh, uint64_t &T, int &r)
 {
     constexpr int BPT = 256 / NT;                 // histogram bins per thread
     const int tid = threadIdx.x;
@@ -712,8 +712,8 @@ hipError_t launch_select(const double *S, int pitch, long rows, int Nkb, int k_c
     if (lab_pitch <= 64) SLA_SEL(1);
     if (lab_pitch <= 128) SLA_SEL(2);
     if (lab_pitch <= 256) SLA_SEL(4);
-    // one wave per row as long as the row's keys fit its registers (up to 24 per lane): no workgroup barriers
-    // and 32 rows in flight per CU; 36 keys per lane spill, so longer rows take a workgroup per row
+    // one wave per row up to 24 keys per lane: no workgroup barriers and 16 to 32 rows in flight per CU.  Beyond
+    // that (36 keys per lane: 153 VGPRs, measured 20 % slower on 2147 key blocks) a workgroup takes the row.
     if (lab_pitch <= 512) SLA_SEL(8);
     if (lab_pitch <= 768) SLA_SEL(12);
     if (lab_pitch <= 1024) SLA_SEL(16);

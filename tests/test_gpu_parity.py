@@ -271,6 +271,25 @@ def test_elu_feature_map(oracle, name):
     assert err <= GRAD_TOL * rms
 
 
+@pytest.mark.parametrize("qk_gain,v_gain", [(6.0, 100.0), (1.0 / 64, 1.0 / 256), (3.0, 1.0)])
+def test_forward_with_extreme_magnitudes(oracle, qk_gain, v_gain):
+    """Logits far outside the benchmark's range (softmax rows collapsing onto one key, or flat to rounding) and
+    values of large / tiny magnitude: the running maximum, the exponent offsets and the bf16 states must cope."""
+    d = dict(synth.make_inputs(C0.with_(N=700, proj_per_head=True)))
+    f = lambda bits: (bits.astype(np.uint32) << 16).view(np.float32)
+    d["Q"] = synth.to_bf16_bits(f(d["Q"]) * np.float32(qk_gain))
+    d["K"] = synth.to_bf16_bits(f(d["K"]) * np.float32(qk_gain))
+    d["V"] = synth.to_bf16_bits(f(d["V"]) * np.float32(v_gain))
+    case = G.Case(C0.with_(N=700, proj_per_head=True), d, k_crit=2, k_neg=5)
+    O, lab = case.forward()
+    oc = case.oracle_classify(oracle)
+    assert np.array_equal(lab.cpu().numpy(), oc["labels"])
+    ref = case.oracle_attend(oracle, oc["labels"])
+    got = G.gather_blocks(G.bf16_tensor_to_f64(O), ref["sel"], 64, 2)
+    assert np.isfinite(got).all()
+    G.assert_output(got, ref["O"], "bf16", f"gain {qk_gain} / {v_gain}")
+
+
 def test_v_ones_closed_form_on_device():
     """V == 1 gives O = 1 + column sums of W for every row (eq. 1), independent of the oracle."""
     d = dict(synth.make_inputs(C0))

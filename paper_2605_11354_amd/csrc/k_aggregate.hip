@@ -36,7 +36,7 @@ constexpr int kAggBuf = 128 * kAggRow;
 // deeper sets would only cost registers and with them resident workgroups
 // NBUF: LDS operand buffers, 2 in general, 1 for heads of a single K step (more workgroups per CU)
 template <int TA, int TB, int AHEAD, int NBUF>
-__global__ __launch_bounds__(256) void aggregate_kernel(const uint2 *__restrict__ mbits, int nkw,
+__global__ __launch_bounds__(256, (TA == 2 && AHEAD == 3) ? 4 : 1) void aggregate_kernel(const uint2 *__restrict__ mbits, int nkw,
                                                         const uint16_t *__restrict__ hT, int Nqb, int Nkb, int n_it,
                                                         long total, uint16_t *__restrict__ Hq)
 {

@@ -68,10 +68,12 @@ template <int N> __device__ __forceinline__ void wait_copies_and_barrier()
 }
 
 // One 1 KB copy global -> LDS: lane l moves the 16 bytes at base + voff(l) to LDS byte lds_addr + 16 l.
-// base and lds_addr are wave-uniform (SGPRs); M0 carries the LDS address for this instruction only.
+// base and lds_addr are wave-uniform (SGPRs); M0 carries the LDS address for this instruction only.  The s_nop is
+// the wait state the ISA asks for between a scalar write of M0 and an instruction that moves data into LDS through
+// it (the compiler's hazard recogniser does not look inside inline assembly).
 __device__ __forceinline__ void copy_1k_to_lds(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
 {
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds_addr) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds_addr) : "memory");
 }
 
 template <int NW, bool FP8>

@@ -149,6 +149,28 @@ def grad_wproj(p: Params, Q, K, V, labels, dO, sQ=None, sK=None, sV=None):
     return np.einsum("bhtd,bhte->de", olin, dO)[None]
 
 
+def _e4m3_grid():
+    """The 127 non-negative finite E4M3 values in ascending order (codes 0..126), from the C oracle's decoder."""
+    dec = lib().sla_oracle_decode_e4m3
+    dec.restype = C.c_double
+    grid = np.array([dec(C.c_uint8(c)) for c in range(127)], dtype=np.float64)
+    assert np.all(np.diff(grid) > 0) and grid[-1] == 448.0
+    return grid
+
+
+def _e4m3_cast(y):
+    """fp32 values in [-448, 448] -> E4M3 codes: nearest representable value, a value exactly half-way between two
+    neighbours goes to the one with an even code (round to nearest even on this grid)."""
+    grid = _e4m3_grid()
+    a = np.abs(y).astype(np.float64)
+    hi = np.clip(np.searchsorted(grid, a, side="left"), 0, 126)                       # first grid value >= a
+    lo = np.maximum(hi - 1, 0)
+    dlo, dhi = a - grid[lo], grid[hi] - a
+    pick_hi = (dhi < dlo) | ((dhi == dlo) & (hi % 2 == 0))
+    code = np.where(pick_hi, hi, lo).astype(np.uint8)
+    return code | (np.signbit(y).astype(np.uint8) << 7)
+
+
 def quantise_e4m3_blocks(bits, blk: int):
     """Scaled FP8 quantiser of App. B.2 (eqs. for scale, clamp and cast) applied per block of `blk` consecutive
     tokens of every (b, h), the granularity configuration 4 uses for Q, K and V:
@@ -163,10 +185,6 @@ def quantise_e4m3_blocks(bits, blk: int):
     x = (bits.astype(np.uint32) << 16).view(np.float32)
     N = x.shape[-2]
     nb = -(-N // blk)
-    dec = lib().sla_oracle_decode_e4m3
-    dec.restype = C.c_double
-    grid = np.array([dec(C.c_uint8(c)) for c in range(127)], dtype=np.float64)       # codes 0..126: 0 .. 448, ascending
-    assert np.all(np.diff(grid) > 0) and grid[-1] == 448.0
     codes = np.empty(x.shape, dtype=np.uint8)
     scales = np.empty(x.shape[:-2] + (nb,), dtype=np.float32)
     for j in range(nb):
@@ -177,12 +195,31 @@ def quantise_e4m3_blocks(bits, blk: int):
         scales[..., j] = scale
         y = (xb / scale[..., None, None]).astype(np.float32)                          # fp32 division, correctly rounded
         y = np.clip(y, np.float32(-448.0), np.float32(448.0))
-        a = np.abs(y).astype(np.float64)
-        hi = np.clip(np.searchsorted(grid, a, side="left"), 0, 126)                   # first grid value >= a
-        lo = np.maximum(hi - 1, 0)
-        dlo, dhi = a - grid[lo], grid[hi] - a
-        pick_hi = (dhi < dlo) | ((dhi == dlo) & (hi % 2 == 0))
-        code = np.where(pick_hi, hi, lo).astype(np.uint8)
-        code |= (np.signbit(y).astype(np.uint8) << 7)
+        code = _e4m3_cast(y)
         codes[..., sl, :] = code
     return codes, scales
+
+
+def quantise_e4m3_rows(bits):
+    """Scaled FP8 quantiser of App. B.2 / B.3 with one scale per row (per token for activations, per output channel
+    for weights): bits uint16 bf16 [R, C] -> (codes uint8 [R, C], scales fp32 [R]); scale = max(amax, 1e-8) / 448."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    x = (bits.astype(np.uint32) << 16).view(np.float32)
+    amax = np.abs(x).max(axis=-1).astype(np.float32)
+    scale = (np.maximum(amax, np.float32(1e-8)) / np.float32(448.0)).astype(np.float32)
+    y = np.clip((x / scale[:, None]).astype(np.float32), np.float32(-448.0), np.float32(448.0))
+    return _e4m3_cast(y), scale
+
+
+def fp8_linear(x_bits, W_bits, bias_bits=None):
+    """Forward value of the FP8 fake-quantised linear layer (Alg. 2): activations quantised per token, weights per
+    output channel, y = x_fp8 W_fp8^T + b with x_fp8 = E4M3(clamp(x / scale_x)) * scale_x (likewise W).
+    x [N, d_in], W [d_out, d_in], bias [d_out]: uint16 bf16 bit patterns.  Returns y float64 [N, d_out]."""
+    grid = _e4m3_grid()
+    deq = lambda c, s: np.where(c & 0x80, -1.0, 1.0) * grid[(c & 0x7F).astype(np.int64)] * s.astype(np.float64)[:, None]
+    cx, sx = quantise_e4m3_rows(x_bits)
+    cw, sw = quantise_e4m3_rows(W_bits)
+    y = deq(cx, sx) @ deq(cw, sw).T
+    if bias_bits is not None:
+        y = y + (np.asarray(bias_bits, np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)[None, :]
+    return y

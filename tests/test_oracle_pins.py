@@ -402,3 +402,30 @@ def test_block_quantiser_matches_library_cast_and_host_generator(oracle):
     tie = np.zeros((1, 1, 64, 64), np.float32); tie[0, 0, 0, 0] = 448.0; tie[0, 0, 0, 1] = 1.0625; tie[0, 0, 0, 2] = 1.1875
     ct, st = oracle.quantise_e4m3_blocks(synth.to_bf16_bits(tie), 64)
     assert st[0, 0, 0] == 1.0 and ct[0, 0, 0, 0] == 0x7E and ct[0, 0, 0, 1] == 0x38 and ct[0, 0, 0, 2] == 0x3A
+
+
+def test_fp8_linear_matches_torch_fake_quant(oracle):
+    """Alg. 2 forward (per-token activation scales, per-output-channel weight scales) against the same steps written
+    with torch tensor ops and torch's float8_e4m3fn cast; plus: a power-of-two rescaling of a token leaves its codes
+    unchanged (the scale absorbs it) and scales y by the same factor."""
+    import torch
+    rng = np.random.default_rng(9)
+    x = (rng.standard_normal((37, 192)) * np.exp(rng.uniform(-3, 3, (37, 1)))).astype(np.float32)
+    W = (rng.standard_normal((70, 192)) * 0.05).astype(np.float32)
+    b = rng.standard_normal(70).astype(np.float32)
+    xb, Wb, bb = synth.to_bf16_bits(x), synth.to_bf16_bits(W), synth.to_bf16_bits(b)
+    y = oracle.fp8_linear(xb, Wb, bb)
+    f = lambda bits: torch.from_numpy((bits.astype(np.uint32) << 16).view(np.float32).copy())
+
+    def fq(t):
+        scale = torch.clamp(t.abs().amax(dim=-1, keepdim=True), min=1e-8) / 448.0
+        q = torch.clamp(t / scale, -448.0, 448.0).to(torch.float8_e4m3fn).to(torch.float64)
+        return q * scale.to(torch.float64)
+    ref = fq(f(xb)) @ fq(f(Wb)).T + f(bb).to(torch.float64)
+    np.testing.assert_allclose(y, ref.numpy(), rtol=1e-12, atol=1e-12)
+    x2 = x.copy(); x2[5] *= 8.0
+    c1, s1 = oracle.quantise_e4m3_rows(xb)
+    c2, s2 = oracle.quantise_e4m3_rows(synth.to_bf16_bits(x2))
+    assert np.array_equal(c1, c2) and s2[5] == s1[5] * 8 and np.array_equal(np.delete(s1, 5), np.delete(s2, 5))
+    y2 = oracle.fp8_linear(synth.to_bf16_bits(x2), Wb, None)
+    np.testing.assert_allclose(y2[5], 8.0 * (y[5] - (bb.astype(np.uint32) << 16).view(np.float32)), rtol=1e-12, atol=1e-12)

@@ -33,6 +33,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--with-grad", action="store_true", help="also time sla_wproj_grad (gradient of W_proj) after the forward")
+    ap.add_argument("--with-linear", action="store_true", help="also time sla_fp8_linear on the workload's qkv projection shape")
     ap.add_argument("--with-quant", action="store_true", help="also time sla_quantise_e4m3 on a bf16 tensor of the workload's shape")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -192,6 +193,28 @@ def main() -> int:
         qbytes = BH * N * D * 3 + BH * Nkb * 4
         out["quantise_e4m3"] = {"ms": round(qms, 5), "bound": "hbm", "algorithmic_bytes": int(qbytes),
                                 "achieved_GBs": round(qbytes / qms / 1e6, 1), "frac": round(qbytes / qms / 1e6 / PEAK_HBM_GBS, 4)}
+
+    if args.with_linear:
+        # FP8 fake-quantised linear layer (Alg. 2) at the shape of the qkv projection in front of this attention:
+        # tokens x (H*64) -> 3*H*64; both quantisers and the GEMM are inside the timed call
+        tokens, d_in, d_out = cfg.B * cfg.N, cfg.H * 64, 3 * cfg.H * 64
+        xl = torch.randn((tokens, d_in), device="cuda").to(torch.bfloat16)
+        Wl = (torch.randn((d_out, d_in), device="cuda") / d_in ** 0.5).to(torch.bfloat16)
+        bl = torch.randn((d_out,), device="cuda").to(torch.bfloat16)
+        yl = torch.empty((tokens, d_out), dtype=torch.bfloat16, device="cuda")
+        for _ in range(args.warmup):
+            B.sla_fp8_linear(xl, Wl, bl, yl)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            B.sla_fp8_linear(xl, Wl, bl, yl)
+        e1.record()
+        torch.cuda.synchronize()
+        lms = e0.elapsed_time(e1) / args.steps
+        lflops = 2.0 * tokens * d_in * d_out
+        out["fp8_linear"] = {"ms": round(lms, 5), "shape": [tokens, d_in, d_out], "bound": "mfma", "algorithmic_flops": lflops,
+                             "achieved_TFLOPs": round(lflops / lms / 1e9, 1), "frac": round(lflops / lms / 1e9 / PEAK_TFLOPS["fp8"], 4),
+                             "note": "three launches: token quantiser, weight quantiser, E4M3 GEMM with the scales and bias in its epilogue"}
 
     if not args.no_check or not args.no_cpu_baseline:
         from oracle import sla_oracle as orc

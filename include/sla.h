@@ -145,6 +145,21 @@ sla_status_t sla_quantise_e4m3(const void *X, int32_t B, int32_t H, int32_t N, i
                                float *scales, void *stream);
 
 /*
+ * Forward of the FP8 fake-quantised linear layer (Alg. 2; App. B.2-B.4), e.g. the qkv projection in front of the
+ * attention: activations quantised per token, weights per output channel, both to E4M3 with
+ * scale = max(amax, 1e-8) / 448, then  y = x_fp8 W_fp8^T + b  on the FP8 matrix unit (exact products, fp32
+ * accumulation), scales and bias applied in fp32.
+ *   x     in   bf16 [N, d_in]          d_in a multiple of 128
+ *   W     in   bf16 [d_out, d_in]      d_out a multiple of 8
+ *   bias  in   bf16 [d_out] or NULL
+ *   y     out  bf16 [N, d_out]
+ *   workspace  sla_fp8_linear_workspace_bytes(N, d_in, d_out) bytes, 256-byte aligned (the code matrices and scales)
+ */
+sla_status_t sla_fp8_linear_workspace_bytes(int32_t N, int32_t d_in, int32_t d_out, size_t *bytes);
+sla_status_t sla_fp8_linear(const void *x, const void *W, const void *bias, int32_t N, int32_t d_in, int32_t d_out, void *y,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Measurement variant of sla_forward: identical kernels and results, but every kernel is
  * bracketed by HIP events on `stream`; the call then WAITS for the stream and writes the
  * duration of each kernel in milliseconds to stage_ms[SLA_NUM_STAGES] (host memory).

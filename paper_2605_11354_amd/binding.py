@@ -20,7 +20,7 @@ SLA_BF16, SLA_FP8_E4M3 = 0, 1
 STATE_ROWS = 65          # rows of one block state: 64 rows of h^T and one row of z
 EXPORTS = ["sla_resolve_counts", "sla_workspace_bytes", "sla_forward", "sla_pool_classify", "sla_linear_states",
            "sla_marginal_aggregate", "sla_sparse_combine", "sla_forward_profiled", "sla_wproj_grad", "sla_quantise_e4m3",
-           "sla_forward_with_labels",
+           "sla_forward_with_labels", "sla_fp8_linear_workspace_bytes", "sla_fp8_linear",
            "sla_strerror", "sla_last_error", "sla_stage_name"]
 NUM_STAGES = 6
 
@@ -56,7 +56,7 @@ def lib() -> C.CDLL:
         _lib.sla_strerror.restype = C.c_char_p
         _lib.sla_last_error.restype = C.c_char_p
         _lib.sla_stage_name.restype = C.c_char_p
-        for name in EXPORTS[:11]:
+        for name in EXPORTS[:13]:
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -146,6 +146,19 @@ def sla_forward_with_labels(p, Q, K, V, W_proj, labels, O, sQ=None, sK=None, sV=
                                          _ptr(labels), _ptr(O), _ptr(ws), C.c_size_t(ws.numel()), _stream()),
            "sla_forward_with_labels")
     return O
+
+
+def sla_fp8_linear(x, W, bias, y, workspace=None):
+    """y bf16 [N,d_out] <- FP8 fake-quantised linear layer of x bf16 [N,d_in] with W bf16 [d_out,d_in] and bias (or None)."""
+    import torch
+    N, d_in = x.shape
+    d_out = W.shape[0]
+    n = C.c_size_t(0)
+    _check(lib().sla_fp8_linear_workspace_bytes(C.c_int32(N), C.c_int32(d_in), C.c_int32(d_out), C.byref(n)), "sla_fp8_linear_workspace_bytes")
+    ws = workspace if workspace is not None else torch.empty(max(n.value, 256), dtype=torch.uint8, device=x.device)
+    _check(lib().sla_fp8_linear(_ptr(x), _ptr(W), _ptr(bias), C.c_int32(N), C.c_int32(d_in), C.c_int32(d_out), _ptr(y), _ptr(ws),
+                                C.c_size_t(ws.numel()), _stream()), "sla_fp8_linear")
+    return y
 
 
 def sla_quantise_e4m3(X, blk, codes, scales, layout="bhnd"):

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsla.so")
-SOURCES = ["sla_api.hip", "k_classify.hip", "k_states.hip", "k_aggregate.hip", "k_attend.hip", "k_backward.hip", "k_quant.hip"]
+SOURCES = ["sla_api.hip", "k_classify.hip", "k_states.hip", "k_aggregate.hip", "k_attend.hip", "k_backward.hip", "k_quant.hip", "k_linear.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-ffp-contract=off", "-Wall", "-Wextra",
          "-Wno-unused-parameter", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-mllvm", "-amdgpu-mfma-vgpr-form=1"]   # MFMA accumulators stay in VGPRs: no AGPR copy traffic

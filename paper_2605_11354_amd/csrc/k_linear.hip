@@ -1,0 +1,244 @@
+// Forward of the FP8 fake-quantised linear layer (Alg. 2 of the paper, with the scaled quantiser of App. B.2/B.3):
+//     x_fp8 = E4M3(clamp(x / s_x, +-448)) * s_x   per token,          s_x = max(amax(x_i), 1e-8) / 448
+//     W_fp8 = E4M3(clamp(W / s_W, +-448)) * s_W   per output channel, s_W likewise
+//     y = x_fp8 W_fp8^T + b
+// Two kernels.  quantise_rows_kernel turns a bf16 matrix into E4M3 codes plus one fp32 scale per row (one wavefront
+// per row, two passes over the row: absolute maximum, then divide / clamp / convert; bit for bit the arithmetic of
+// the block quantiser).  fp8_gemm_kernel multiplies the code matrices on v_mfma_f32_32x32x64_f8f6f4 (products of
+// two E4M3 numbers are exact in the fp32 accumulator) and applies s_x[i] s_W[o] and the bias in its epilogue.
+//
+// GEMM tiling: workgroup tile 128 or 256 tokens x 128 output channels, 4 waves as 2 x 2, K step 128 bytes (two
+// MFMA K steps).  Both operands are K-contiguous in memory, so their tiles go to LDS as 16-byte chunks of 128-byte
+// rows (chunk index XOR-ed with row bits against bank conflicts) and an MFMA operand is two 16-byte reads.  The
+// kernel forms the transposed tile D[o][i] (W rows as the A operand), so that a lane's four consecutive accumulator
+// registers are four consecutive output channels of one token and leave through LDS as 16-byte stores.  Global
+// loads run two K steps ahead of their use in registers, LDS is double buffered with an LDS-only barrier.
+#include "sla_common.hpp"
+#include "sla_kernels.hpp"
+
+namespace sla {
+
+__global__ __launch_bounds__(256) void quantise_rows_kernel(const uint16_t *__restrict__ X, long rows, int cols,
+                                                            uint8_t *__restrict__ codes, float *__restrict__ scales)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const long row = (long)blockIdx.x * 4 + wave;
+    if (row >= rows) return;                         // the whole wave leaves; nothing below synchronises across waves
+    const uint16_t *x = X + row * cols;
+    float amax = 0.f;
+    for (int c = lane * 8; c < cols; c += 512) {     // cols is a multiple of 8: whole 16-byte pieces
+        const uint4 v = *(const uint4 *)(x + c);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) amax = fmaxf(amax, fmaxf(fabsf(bf16_lo(w[q])), fabsf(bf16_hi(w[q]))));
+    }
+    amax = wave_max(amax);
+    const float scale = fmaxf(amax, 1e-8f) / 448.0f;
+    if (lane == 0) scales[row] = scale;
+    uint8_t *out = codes + row * cols;
+    for (int c = lane * 8; c < cols; c += 512) {
+        const uint4 v = *(const uint4 *)(x + c);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        float y[8];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            y[2 * q] = fminf(fmaxf(bf16_lo(w[q]) / scale, -448.0f), 448.0f);
+            y[2 * q + 1] = fminf(fmaxf(bf16_hi(w[q]) / scale, -448.0f), 448.0f);
+        }
+        int lo = 0, hi = 0;
+        lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], lo, false);
+        lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], lo, true);
+        hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[4], y[5], hi, false);
+        hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[6], y[7], hi, true);
+        *(uint2 *)(out + c) = make_uint2((uint32_t)lo, (uint32_t)hi);
+    }
+}
+
+namespace {
+constexpr int kLinK = 128;                           // bytes (= E4M3 elements) of K per step
+constexpr int kLinTile = 128 * kLinK;                // bytes of one operand tile in LDS
+constexpr int kLinOutRow = 128 + 8;                  // bf16 per row of the output staging tile
+__device__ __forceinline__ int lin_swz(int row) { return (row >> 1) & 7; }
+}  // namespace
+
+// Y[i][o] = (sum_k A8[i][k] W8[o][k]) * sa[i] * sw[o] + bias[o];  A8 [M,K], W8 [O,K] E4M3 codes, K a multiple of 128.
+// TB: 32-token sub-tiles per wave.  TB = 2: tile 128 tokens x 128 channels, LDS double buffered (one barrier per K
+// step).  TB = 4: tile 256 tokens x 128 channels for large token counts -- a wave's 64 x 128 tile needs six operand
+// reads per eight MFMAs instead of four per four, which takes the LDS read rate off the critical path; one LDS buffer
+// (two barriers per K step) so that two workgroups still share a CU.
+template <int TB>
+__global__ __launch_bounds__(256) void fp8_gemm_kernel(const uint8_t *__restrict__ A8, const float *__restrict__ sa,
+                                                       const uint8_t *__restrict__ W8, const float *__restrict__ sw,
+                                                       const uint16_t *__restrict__ bias, int M, int O, int K, int n_it,
+                                                       long total, uint16_t *__restrict__ Y)
+{
+    constexpr int kTok = 64 * TB;                                                // tokens per workgroup tile
+    constexpr int kBufs = TB == 2 ? 2 : 1;
+    constexpr int kBufBytes = (kTok + 128) * kLinK;                              // token tile, then channel tile
+    constexpr int kStageBytes = kTok * kLinOutRow * 2;
+    constexpr int kSmem = kBufs * kBufBytes > kStageBytes ? kBufs * kBufBytes : kStageBytes;
+    constexpr int kAx = 2 * TB;                                                  // 16-byte chunks of the token tile per thread
+    __shared__ __attribute__((aligned(16))) uint8_t smem[kSmem];
+    const long item = xcd_remap(blockIdx.x, total);  // token tile fastest: neighbours on one XCD share a slab of W in its L2
+    if (item >= total) return;
+    const int it = (int)(item % n_it), ot = (int)(item / n_it);
+    const int i0 = it * kTok, o0 = ot * 128;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    const int wo = (wave >> 1) * 64, wi = (wave & 1) * (32 * TB);                // wave's first channel / token within the tile
+
+    // loader: 16-byte chunk id = tid + 256 x of a tile of 128-byte rows: row id / 8, chunk id % 8 (rows past the end of
+    // the matrix repeat its last row: their results are never stored)
+    uint32_t ga[kAx], gw[4];                       // byte offsets into A8 / W8 (the host checks that both stay below 4 GB)
+    int la[kAx], lw[4];
+#pragma unroll
+    for (int x = 0; x < kAx; ++x) {
+        const int id = tid + 256 * x, row = id >> 3, ch = id & 7;
+        ga[x] = (uint32_t)min(i0 + row, M - 1) * (uint32_t)K + ch * 16;
+        la[x] = row * kLinK + ((ch ^ lin_swz(row)) << 4);
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const int id = tid + 256 * x, row = id >> 3, ch = id & 7;
+        gw[x] = (uint32_t)min(o0 + row, O - 1) * (uint32_t)K + ch * 16;
+        lw[x] = kTok * kLinK + row * kLinK + ((ch ^ lin_swz(row)) << 4);
+    }
+    uint32_t ra[kBufs][4 * kAx], rw[kBufs][16];                                  // register sets (plain dwords)
+    auto load_tile = [&](int ks, uint32_t (&a)[4 * kAx], uint32_t (&w)[16]) {
+#pragma unroll
+        for (int x = 0; x < kAx; ++x) {
+            const uint4 v = *(const uint4 *)(A8 + ga[x] + (uint32_t)ks * kLinK);
+            a[4 * x] = v.x; a[4 * x + 1] = v.y; a[4 * x + 2] = v.z; a[4 * x + 3] = v.w;
+        }
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const uint4 v = *(const uint4 *)(W8 + gw[x] + (uint32_t)ks * kLinK);
+            w[4 * x] = v.x; w[4 * x + 1] = v.y; w[4 * x + 2] = v.z; w[4 * x + 3] = v.w;
+        }
+    };
+    auto store_tile = [&](uint8_t *buf, const uint32_t (&a)[4 * kAx], const uint32_t (&w)[16]) {
+#pragma unroll
+        for (int x = 0; x < kAx; ++x) *(uint4 *)(buf + la[x]) = make_uint4(a[4 * x], a[4 * x + 1], a[4 * x + 2], a[4 * x + 3]);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) *(uint4 *)(buf + lw[x]) = make_uint4(w[4 * x], w[4 * x + 1], w[4 * x + 2], w[4 * x + 3]);
+    };
+    // operand of one MFMA: 32 bytes of K (bytes 64 s + 32 g ..) of row `row` of the tile at `tile`
+    auto frag = [&](const uint8_t *tile, int row, int s) {
+        const int c0 = 4 * s + 2 * g;
+        const uint4 u0 = *(const uint4 *)(tile + row * kLinK + ((c0 ^ lin_swz(row)) << 4));
+        const uint4 u1 = *(const uint4 *)(tile + row * kLinK + (((c0 + 1) ^ lin_swz(row)) << 4));
+        i32x8 f;
+        f[0] = u0.x; f[1] = u0.y; f[2] = u0.z; f[3] = u0.w; f[4] = u1.x; f[5] = u1.y; f[6] = u1.z; f[7] = u1.w;
+        return f;
+    };
+
+    f32x16 acc[2][TB];                                                          // [channel sub-tile][token sub-tile]
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < TB; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+    auto mma_step = [&](const uint8_t *buf) {
+        const uint8_t *At = buf, *Wt = buf + kTok * kLinK;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            i32x8 wf[2], af[TB];
+#pragma unroll
+            for (int a = 0; a < 2; ++a) wf[a] = frag(Wt, wo + 32 * a + l32, s);
+#pragma unroll
+            for (int b = 0; b < TB; ++b) af[b] = frag(At, wi + 32 * b + l32, s);
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < TB; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wf[a], af[b], acc[a][b], 0, 0, 0, 0, 0, 0);
+        }
+    };
+
+    const int ksteps = K / kLinK;
+    if constexpr (kBufs == 2) {
+        load_tile(0, ra[0], rw[0]);
+        load_tile(min(1, ksteps - 1), ra[1], rw[1]);
+        store_tile(smem, ra[0], rw[0]);
+        lds_barrier();
+        for (int ks0 = 0; ks0 < ksteps; ks0 += 2) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int ks = ks0 + u;
+                if (ks < ksteps) {                                              // uniform over the workgroup
+                    load_tile(min(ks + 2, ksteps - 1), ra[u], rw[u]);           // set u went to LDS one step ago; past the end: a repeat nobody uses
+                    mma_step(smem + (ks & 1) * kBufBytes);
+                    store_tile(smem + ((ks + 1) & 1) * kBufBytes, ra[(u + 1) & 1], rw[(u + 1) & 1]);
+                    lds_barrier();
+                }
+            }
+        }
+    } else {
+        load_tile(0, ra[0], rw[0]);
+        for (int ks = 0; ks < ksteps; ++ks) {
+            store_tile(smem, ra[0], rw[0]);
+            lds_barrier();                                                      // tile ks is in LDS
+            load_tile(min(ks + 1, ksteps - 1), ra[0], rw[0]);                   // the next one flies during the products
+            mma_step(smem);
+            lds_barrier();                                                      // every wave has read tile ks
+        }
+    }
+
+    // accumulator (a,b) register 4q+r of lane (l32, g): channel o0 + wo + 32a + 8q + 4g + r, token i0 + wi + 32b + l32.
+    // Scales and bias applied in fp32, staged as [token][channel], stored as 16-byte pieces.
+    uint16_t *stage = (uint16_t *)smem;
+#pragma unroll
+    for (int b = 0; b < TB; ++b) {
+        const int i = i0 + wi + 32 * b + l32;
+        const float si = sa[min(i, M - 1)];
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int o = o0 + wo + 32 * a + 8 * q + 4 * g;
+                float v[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int oc = min(o + r, O - 1);
+                    v[r] = acc[a][b][4 * q + r] * (si * sw[oc]) + (bias ? bf16_bits_to_f32(bias[oc]) : 0.f);
+                }
+                uint2 p;
+                p.x = pack_bf16(v[0], v[1]);
+                p.y = pack_bf16(v[2], v[3]);
+                *(uint2 *)(stage + (wi + 32 * b + l32) * kLinOutRow + wo + 32 * a + 8 * q + 4 * g) = p;
+            }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < kTok / 16; ++t) {
+        const int idx = tid + 256 * t, r = idx >> 4, seg = idx & 15;
+        if (i0 + r < M && o0 + 8 * seg < O)                                      // O is a multiple of 8: a segment is in or out as a whole
+            *(uint4 *)(Y + (size_t)(i0 + r) * O + o0 + 8 * seg) = *(const uint4 *)(stage + r * kLinOutRow + 8 * seg);
+    }
+}
+
+hipError_t launch_quantise_rows(const void *X, long rows, int cols, void *codes, float *scales, hipStream_t st)
+{
+    quantise_rows_kernel<<<(unsigned)((rows + 3) / 4), 256, 0, st>>>((const uint16_t *)X, rows, cols, (uint8_t *)codes, scales);
+    return hipGetLastError();
+}
+
+hipError_t launch_fp8_gemm(const void *A8, const float *sa, const void *W8, const float *sw, const void *bias, int M, int O, int K,
+                           void *Y, hipStream_t st)
+{
+    const int n_ot = (O + 127) / 128;
+    if ((long)((M + 255) / 256) * n_ot >= 512) {        // enough 256-token tiles to fill the chip twice over
+        const int n_it = (M + 255) / 256;
+        const long total = (long)n_it * n_ot;
+        fp8_gemm_kernel<4><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint8_t *)A8, sa, (const uint8_t *)W8, sw, (const uint16_t *)bias, M, O, K,
+                                                                       n_it, total, (uint16_t *)Y);
+    } else {
+        const int n_it = (M + 127) / 128;
+        const long total = (long)n_it * n_ot;
+        fp8_gemm_kernel<2><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint8_t *)A8, sa, (const uint8_t *)W8, sw, (const uint16_t *)bias, M, O, K,
+                                                                       n_it, total, (uint16_t *)Y);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace sla

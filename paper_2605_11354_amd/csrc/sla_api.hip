@@ -360,6 +360,55 @@ sla_status_t sla_quantise_e4m3(const void *X, int32_t B, int32_t H, int32_t N, i
     return SLA_OK;
 }
 
+namespace {
+struct LinPlan { size_t off_cx, off_sx, off_cw, off_sw, total; };
+sla_status_t make_lin_plan(int32_t N, int32_t d_in, int32_t d_out, LinPlan &lp)
+{
+    if (N < 0 || d_in <= 0 || d_out <= 0) return fail(SLA_ERR_INVALID_ARG, "bad sizes (N=%d d_in=%d d_out=%d)", N, d_in, d_out);
+    if (d_in % 128 != 0) return fail(SLA_ERR_UNSUPPORTED, "d_in = %d; only multiples of 128 are implemented", d_in);
+    if (d_out % 8 != 0) return fail(SLA_ERR_UNSUPPORTED, "d_out = %d; only multiples of 8 are implemented", d_out);
+    if ((double)N * d_in >= 4.0e9 || (double)d_out * d_in >= 4.0e9) return fail(SLA_ERR_UNSUPPORTED, "operand of 4 GB or more");
+    size_t off = 0;
+    auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    lp.off_cx = carve((size_t)N * d_in);
+    lp.off_sx = carve((size_t)N * sizeof(float));
+    lp.off_cw = carve((size_t)d_out * d_in);
+    lp.off_sw = carve((size_t)d_out * sizeof(float));
+    lp.total = off;
+    return SLA_OK;
+}
+}  // namespace
+
+sla_status_t sla_fp8_linear_workspace_bytes(int32_t N, int32_t d_in, int32_t d_out, size_t *bytes)
+{
+    LinPlan lp;
+    sla_status_t s = make_lin_plan(N, d_in, d_out, lp);
+    if (s != SLA_OK) return s;
+    if (!bytes) return fail(SLA_ERR_INVALID_ARG, "bytes is NULL");
+    *bytes = lp.total;
+    return SLA_OK;
+}
+
+sla_status_t sla_fp8_linear(const void *x, const void *W, const void *bias, int32_t N, int32_t d_in, int32_t d_out, void *y,
+                            void *workspace, size_t workspace_bytes, void *stream)
+{
+    LinPlan lp;
+    sla_status_t s = make_lin_plan(N, d_in, d_out, lp);
+    if (s != SLA_OK) return s;
+    if (N == 0) return SLA_OK;
+    SLA_REQ_PTR(x); SLA_REQ_PTR(W); SLA_REQ_PTR(y);
+    SLA_OPT_PTR(bias);
+    if (!workspace) return fail(SLA_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", lp.total);
+    if (!aligned(workspace, 256)) return fail(SLA_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    if (workspace_bytes < lp.total) return fail(SLA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, lp.total);
+    hipStream_t st = (hipStream_t)stream;
+    SLA_HIP(sla::launch_quantise_rows(x, N, d_in, at<void>(workspace, lp.off_cx), at<float>(workspace, lp.off_sx), st));
+    SLA_HIP(sla::launch_quantise_rows(W, d_out, d_in, at<void>(workspace, lp.off_cw), at<float>(workspace, lp.off_sw), st));
+    SLA_HIP(sla::launch_fp8_gemm(at<void>(workspace, lp.off_cx), at<float>(workspace, lp.off_sx), at<void>(workspace, lp.off_cw),
+                                 at<float>(workspace, lp.off_sw), bias, N, d_out, d_in, y, st));
+    return SLA_OK;
+}
+
 const char *sla_stage_name(int stage)
 {
     static const char *names[SLA_NUM_STAGES] = {"pool_q", "states", "scores", "select", "aggregate", "attend"};

@@ -64,4 +64,10 @@ hipError_t launch_wproj_grad(const void *Q, const float *sQ, bool fp8, RowMap rm
 // X bf16 [BH,N,64] -> codes e4m3 [BH,N,64] + fp32 scales [BH, ceil(N/blk)], blk = 64 or 128 (App. B.2 per token block)
 hipError_t launch_quantise_e4m3(const void *X, RowMap rm, int BH, int N, int blk, void *codes, float *scales, hipStream_t st);
 
+// X bf16 [rows, cols] (cols a multiple of 8) -> E4M3 codes [rows, cols] + one fp32 scale per row (App. B.2 / B.3)
+hipError_t launch_quantise_rows(const void *X, long rows, int cols, void *codes, float *scales, hipStream_t st);
+// Y bf16 [M,O] = (A8 [M,K] x W8 [O,K]^T) * sa[i] * sw[o] + bias[o]; E4M3 codes, K a multiple of 128, O of 8; bias may be NULL
+hipError_t launch_fp8_gemm(const void *A8, const float *sa, const void *W8, const float *sw, const void *bias, int M, int O, int K,
+                           void *Y, hipStream_t st);
+
 }  // namespace sla

@@ -479,6 +479,31 @@ def test_forward_with_given_labels_reproduces_the_forward(oracle, name):
     G.assert_output(got, ref["O"], c.dtype, f"{name} all-marginal labels")
 
 
+@pytest.mark.parametrize("N,d_in,d_out,with_bias", [(300, 256, 200, True), (128, 128, 128, False), (1, 1024, 8, True),
+                                                    (1374, 1024, 3072, True), (257, 384, 136, False),
+                                                    (8000, 128, 2048, True)])        # the last one takes the 256-token tiles
+def test_fp8_linear_layer(oracle, N, d_in, d_out, with_bias):
+    """Alg. 2 forward on the device against the oracle.  The code matrices and scales are the oracle's bit for bit
+    (same quantiser arithmetic), products of E4M3 numbers are exact in fp32, so what remains is fp32 accumulation
+    order and the bf16 store: the error beyond half a bf16 ulp of the result is asserted to be below 1e-3 RMS."""
+    from paper_2605_11354_amd import binding as B
+    rng = np.random.default_rng(31)
+    x = (rng.standard_normal((N, d_in)) * np.exp(rng.uniform(-2, 2, (N, 1)))).astype(np.float32)
+    W = (rng.standard_normal((d_out, d_in)) / np.sqrt(d_in)).astype(np.float32)
+    b = rng.standard_normal(d_out).astype(np.float32)
+    xb, Wb, bb = synth.to_bf16_bits(x), synth.to_bf16_bits(W), synth.to_bf16_bits(b)
+    y = torch.full((N, d_out), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.sla_fp8_linear(G.dev_bf16(xb), G.dev_bf16(Wb), G.dev_bf16(bb) if with_bias else None, y)
+    torch.cuda.synchronize()
+    ref = oracle.fp8_linear(xb, Wb, bb if with_bias else None)
+    got = G.bf16_tensor_to_f64(y)
+    assert np.isfinite(got).all()
+    rms = float(np.sqrt(np.mean(ref ** 2)))
+    excess = np.maximum(np.abs(got - ref) - G.bf16_half_ulp(ref), 0.0).max() / rms
+    print(f"fp8 linear {N}x{d_in}x{d_out}: max-abs/RMS {np.abs(got - ref).max() / rms:.3e}, beyond the bf16 store {excess:.3e}")
+    assert excess <= 1e-3
+
+
 def test_errors_are_reported_not_launched():
     from paper_2605_11354_amd import binding as B
     case = G.Case(C0)

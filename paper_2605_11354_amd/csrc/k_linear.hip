@@ -79,9 +79,12 @@ __global__ __launch_bounds__(256) void fp8_gemm_kernel(const uint8_t *__restrict
     constexpr int kSmem = kBufs * kBufBytes > kStageBytes ? kBufs * kBufBytes : kStageBytes;
     constexpr int kAx = 2 * TB;                                                  // 16-byte chunks of the token tile per thread
     __shared__ __attribute__((aligned(16))) uint8_t smem[kSmem];
-    const long item = xcd_remap(blockIdx.x, total);  // token tile fastest: neighbours on one XCD share a slab of W in its L2
+    // channel tile fastest: the workgroups that share a token tile run side by side on one XCD, so the activations come
+    // from HBM once; the weight matrix (a few MB) stays in every XCD's L2
+    const long item = xcd_remap(blockIdx.x, total);
     if (item >= total) return;
-    const int it = (int)(item % n_it), ot = (int)(item / n_it);
+    const int n_ot = (int)(total / n_it);
+    const int ot = (int)(item % n_ot), it = (int)(item / n_ot);
     const int i0 = it * kTok, o0 = ot * 128;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
     const int wo = (wave >> 1) * 64, wi = (wave & 1) * (32 * TB);                // wave's first channel / token within the tile

@@ -97,3 +97,22 @@ def test_wproj_grad_rejects_bad_pointers_before_any_launch(lib):
     fp8 = B.make_params(1, 2, 640, 64, 64, 0.1, 0.5, dtype="fp8")
     rc = lib.sla_wproj_grad(C.byref(fp8), C.c_void_p(16), null, C.c_void_p(16), C.c_void_p(16), C.c_void_p(256), C.c_size_t(1 << 30), null)
     assert rc == B.SLA_ERR_INVALID_ARG                      # e4m3 Q needs its scales
+
+
+def test_fp8_linear_and_quantiser_validate_on_the_host(lib):
+    null = C.c_void_p(0)
+    n = C.c_size_t(0)
+    assert lib.sla_fp8_linear_workspace_bytes(C.c_int32(1000), C.c_int32(1024), C.c_int32(3072), C.byref(n)) == B.SLA_OK
+    assert n.value >= 1000 * 1024 + 3072 * 1024 + 4 * (1000 + 3072)
+    assert lib.sla_fp8_linear_workspace_bytes(C.c_int32(1000), C.c_int32(1000), C.c_int32(3072), C.byref(n)) == B.SLA_ERR_UNSUPPORTED
+    assert lib.sla_fp8_linear_workspace_bytes(C.c_int32(1000), C.c_int32(1024), C.c_int32(3070), C.byref(n)) == B.SLA_ERR_UNSUPPORTED
+    assert lib.sla_fp8_linear_workspace_bytes(C.c_int32(-1), C.c_int32(1024), C.c_int32(3072), C.byref(n)) == B.SLA_ERR_INVALID_ARG
+    # no tokens: nothing to do, nothing dereferenced
+    assert lib.sla_fp8_linear(null, null, null, C.c_int32(0), C.c_int32(128), C.c_int32(8), null, null, C.c_size_t(0), null) == B.SLA_OK
+    rc = lib.sla_fp8_linear(C.c_void_p(16), C.c_void_p(16), null, C.c_int32(4), C.c_int32(128), C.c_int32(8), C.c_void_p(16), null, C.c_size_t(0), null)
+    assert rc == B.SLA_ERR_WORKSPACE
+    rc = lib.sla_quantise_e4m3(C.c_void_p(16), C.c_int32(1), C.c_int32(2), C.c_int32(640), C.c_int32(96), C.c_int32(0), C.c_void_p(16), C.c_void_p(16), null)
+    assert rc == B.SLA_ERR_UNSUPPORTED and b"block" in lib.sla_last_error()
+    rc = lib.sla_quantise_e4m3(C.c_void_p(16), C.c_int32(1), C.c_int32(2), C.c_int32(640), C.c_int32(64), C.c_int32(7), C.c_void_p(16), C.c_void_p(16), null)
+    assert rc == B.SLA_ERR_INVALID_ARG
+    assert lib.sla_quantise_e4m3(null, C.c_int32(0), C.c_int32(2), C.c_int32(640), C.c_int32(64), C.c_int32(0), null, null, null) == B.SLA_OK

@@ -8,89 +8,158 @@
 //     S^T[t'][q]  = K_tile (A operand, LDS rows)  x  Q^T (B operand, registers)
 //     O^T[e][q]  += V^T_tile (A operand, LDS)     x  P^T (B operand = the S^T accumulators,
 //                                                   re-used in place: no LDS round trip)
-// With v_mfma_f32_32x32x16_bf16 a lane holds column q = lane%32 of the 32x32 result, rows
-// 8a + 4g + b (g = lane/32; register 4a+b), so the online-softmax row statistics are 31
-// in-lane operations plus one exchange with lane^32.  The B operand of the second product
-// takes accumulator registers 8u..8u+7, i.e. keys 16s + 8a' + 4g + b; the V^T rows are read
-// with exactly that key permutation: the states kernel leaves V^T of every key block in that
-// order (bf16), so a V^T fragment is one 16-byte LDS read like a K fragment.
-// Template parameters: NW query groups of 32 rows (2 for 64-row, 4 for 128-row query blocks); KS = 2 splits the
-// critical list of a 64-row block between two wave pairs (alternate tiles) whose (maximum, sum, O) are merged
+// With the 32x32x16 MFMA a lane holds column q = lane%32 of the 32x32 result, rows
+// 8a + 4g + b (g = lane/32; register 4a+b).  The B operand of the second product takes
+// accumulator registers 8u..8u+7, i.e. keys 16s + 8a' + 4g + b; the V^T rows are read with
+// exactly that key permutation: the states kernel leaves V^T of every key block in that order,
+// so a V^T fragment is one 16-byte LDS read like a K fragment.
+// Template parameters: NW query groups of 32 rows (2 for 64-row, 4 for 128-row query blocks); KS = 2 splits every
+// tile of a 64-row block between two wave pairs (one 32-key half each) whose (maximum, sum, O) are merged
 // through LDS before the epilogue, so that short lists still give a workgroup four waves of work.
 //
-// Memory pipeline.  K and V^T tiles go from global memory straight into LDS
-// (global_load_lds_dwordx4, no staging registers) into a ring of three stages (two for lists of at most two
-// tiles, see STG below); the tile of
-// iteration c+2 is requested while tile c is consumed, and a single workgroup barrier per
-// iteration both publishes tile c and frees the stage of tile c-1.  Rows are stored unpadded
-// with the 16-byte chunk index XOR-ed by row bits (applied on the global side of the copy),
-// which keeps the fragment reads free of bank conflicts.  Every wave issues the same number of
-// copies per tile (rows past a ragged end are clamped, absent list entries copy block 0), so
-// s_waitcnt vmcnt(n) with a compile-time n identifies "tile c has landed".  The key mask of a
-// ragged last block enters as the initial accumulator of S^T (0 / -inf), costing nothing per tile.
+// Arithmetic of the weights.  P is rounded to fp16 (11 significant bits) and V^T arrives as fp16 from the states
+// kernel (bf16 or E4M3 values are exact in fp16 once divided by the power of two the states kernel picks per key
+// block; its base-2 logarithm comes in `lvs` and is added to the exponent of the weights, so the product is
+// unchanged).  The second product runs on the fp16 MFMA at the rate of the bf16 one with an eighth of the rounding
+// error on the weights.  That margin pays for a running maximum that is only raised when a lane sees an exponent
+// above kRaise: the accumulators are rescaled a few times per row instead of once per tile, and the softmax of a
+// 32-key unit needs nothing from other lanes before its exponentials.
 //
-// E4M3 inputs.  S^T is one v_mfma_f32_32x32x64_f8f6f4 per 32 keys (the whole head dimension
-// is the K dimension of the instruction; products of two E4M3 numbers are exact in the fp32
-// accumulator), with the per-block scales folded into the exp2 constant.  P is NOT cast to
-// E4M3: three mantissa bits on the softmax weights put the output error at several percent
-// of its RMS, above the 6e-2 bar, so P stays bf16, V^T arrives widened to bf16 (exactly) from
-// the states kernel, and the second product runs on the bf16 MFMA.  The V block scale is folded into the
-// exponent of the weights, so no operand of that product is rounded twice.
+// Software pipeline.  The work of a wave is a stream of units (32 keys x 32 queries).  In step u the matrix unit
+// runs O += V P of unit u-1 and S of unit u+1 while the vector unit runs the softmax of unit u; the three have no
+// dependency on each other, so the compiler can interleave MFMA and VALU instructions in one basic block
+// (`sched_group_barrier` below asks for exactly that).  Everything with control flow (raising the maximum, the
+// first unit of a row, a ragged key block, a key block whose V scale is far below the first one's) sits between the
+// steps or in the "careful" variant of a step.
+//
+// Memory pipeline.  K and V^T tiles go from global memory straight into LDS (global_load_lds_dwordx4, no staging
+// registers) into two rings of three slots each.  K runs ahead of V^T by the pipeline's skew, so the copies of an
+// iteration are needed two iterations later; one workgroup barrier per tile publishes what has landed and frees
+// the slots that were consumed.  Rows are stored unpadded with the 16-byte chunk index XOR-ed by row bits (applied
+// on the global side of the copy), which keeps the fragment reads free of bank conflicts.  The copies are inline
+// assembly, invisible to the compiler's wait-count insertion, and are awaited by explicit s_waitcnt vmcnt(n).
+//
+// E4M3 inputs.  S^T is one v_mfma_f32_32x32x64_f8f6f4 per 32 keys (the whole head dimension is the K dimension of
+// the instruction; products of two E4M3 numbers are exact in the fp32 accumulator), with the per-block scales
+// folded into the exp2 constant.  P is NOT cast to E4M3: three mantissa bits on the softmax weights put the output
+// error at several percent of its RMS, above the 6e-2 bar; the second product is the fp16 one described above, with
+// the V block scale in the exponent of the weights.
 //
 // Epilogue (per wave, all MFMA): O_lin^T = Hq^T-tile x phi(Q)^T, scaled by 1/(phi(Q).Z),
 // then O^T += W^T x O_lin^T accumulated onto the normalised sparse output, stored as bf16.
 #include "sla_common.hpp"
 #include "sla_kernels.hpp"
 
+#include <type_traits>
+
 namespace sla {
 
 constexpr float kLog2e = 1.4426950408889634f;
-// Slack allowed before a row raises its running maximum.  0 = exact running maximum: the dominant weight of a
-// row is then exactly 1.0 and survives the bf16 rounding of P untouched; a slack of 8 (rescaling the
-// accumulators far less often) was measured 6 % faster but doubled the output error of peaked rows.
-constexpr float kLazyMax = 0.0f;
+// A lane raises the running maximum of its row when a weight of the current unit would exceed 2^kRaise times
+// the largest weight seen when the maximum was last set; fp16 holds 2^kRaise with room to spare (max 65504).
+constexpr float kRaise = 12.0f;
+// A key block whose V scale differs from that of the row's first block by more than 2^kTinyV either way takes the
+// careful step: its weights (or the factor that divides the scale out of the row sums again) would leave the range
+// of fp16, so its row sums are formed in fp32.
+constexpr float kTinyV = 8.0f;
 
 typedef __attribute__((address_space(3))) void *lds_void_p;
-typedef __attribute__((address_space(1))) const void *glb_void_p;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 
 // XOR swizzle of 16-byte chunks: 8 chunks per 128-byte row / 4 chunks per 64-byte row
 __device__ __forceinline__ int swz8(int row) { return (row >> 1) & 7; }
 __device__ __forceinline__ int swz4(int row) { return (row >> 2) & 3; }
 
-// Waits until at most N of this wave's tile copies are outstanding, then joins the workgroup.
-// The copies below are issued from inline assembly so that the compiler's own wait-count
-// insertion does not see them: it would otherwise drain ALL outstanding copies (vmcnt(0))
-// before every LDS read and serialise the prefetch ring.  The waits are therefore explicit.
+// Waits until at most N of this wave's tile copies are outstanding and its LDS reads have returned, then joins
+// the workgroup.  The copies below are issued from inline assembly so that the compiler's own wait-count
+// insertion does not see them: it would otherwise drain ALL outstanding copies (vmcnt(0)) before every LDS read
+// and serialise the prefetch ring.  The waits are therefore explicit.
 template <int N> __device__ __forceinline__ void wait_copies_and_barrier()
 {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+#ifdef SLA_PROBE_NOBARRIER   /* timing probe only (results are wrong): how much of the time is waves waiting for each other */
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_waitcnt lgkmcnt(0)" ::"n"(N) : "memory");
+#else
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+#endif
 }
 
-// One 1 KB copy global -> LDS: lane l moves the 16 bytes at base + voff(l) to LDS byte lds_addr + 16 l.
-// base and lds_addr are wave-uniform (SGPRs); M0 carries the LDS address for this instruction only.  The s_nop is
-// the wait state the ISA asks for between a scalar write of M0 and an instruction that moves data into LDS through
-// it (the compiler's hazard recogniser does not look inside inline assembly).
+// 1 KB copies global -> LDS: lane l moves the 16 bytes at base + voff(l) to LDS byte lds_addr + 16 l.
+// base and lds_addr are wave-uniform (SGPRs); M0 carries the LDS address for the copy and is put back afterwards
+// (the compiler reserves M0 for its own use and does not accept it as a clobber, so the statement leaves it as it
+// found it).  The s_nop is the wait state the ISA asks for between a scalar write of M0 and an instruction that
+// moves data into LDS through it (the compiler's hazard recogniser does not look inside inline assembly).
 __device__ __forceinline__ void copy_1k_to_lds(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
 {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds_addr) : "memory");
+    uint32_t saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0) : "v"(voff), "s"(base), "s"(lds_addr) : "memory");
+}
+// N such copies from the same base to consecutive kilobytes of LDS (per-lane offsets voff[0..N-1]) in one statement
+template <int N> __device__ __forceinline__ void copy_nk_to_lds(const uint8_t *base, const int (&voff)[N], uint32_t lds_addr)
+{
+    static_assert(N == 1 || N == 2 || N == 4, "1, 2 or 4 copies");
+    uint32_t saved_m0;
+    if constexpr (N == 1) {
+        copy_1k_to_lds(base, voff[0], lds_addr);
+    } else if constexpr (N == 2) {
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %4\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %3\n\t"
+                     "s_add_u32 m0, m0, 0x400\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
+                     : "=&s"(saved_m0) : "v"(voff[0]), "v"(voff[1]), "s"(base), "s"(lds_addr) : "memory", "scc");
+    } else {
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %6\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %5\n\t"
+                     "s_add_u32 m0, m0, 0x400\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %5\n\t"
+                     "s_add_u32 m0, m0, 0x400\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %3, %5\n\t"
+                     "s_add_u32 m0, m0, 0x400\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %4, %5\n\ts_mov_b32 m0, %0"
+                     : "=&s"(saved_m0) : "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "v"(voff[3]), "s"(base), "s"(lds_addr) : "memory", "scc");
+    }
 }
 
-template <int NW, bool FP8>
+__device__ __forceinline__ uint32_t pack_f16(float lo, float hi)
+{
+    f16x2 r;
+    r[0] = (_Float16)lo;
+    r[1] = (_Float16)hi;
+    return __builtin_bit_cast(uint32_t, r);
+}
+__device__ __forceinline__ f16x8 pack8_f16(const f32x16 &a, int base)
+{
+    uint4 o;
+    o.x = pack_f16(a[base + 0], a[base + 1]); o.y = pack_f16(a[base + 2], a[base + 3]);
+    o.z = pack_f16(a[base + 4], a[base + 5]); o.w = pack_f16(a[base + 6], a[base + 7]);
+    return __builtin_bit_cast(f16x8, o);
+}
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+// largest of the 16 values a lane holds of one unit of S^T
+__device__ __forceinline__ float max16(const f32x16 &s)
+{
+    const float a = max3(s[0], s[1], s[2]), b = max3(s[3], s[4], s[5]), c = max3(s[6], s[7], s[8]);
+    const float d = max3(s[9], s[10], s[11]), e = max3(s[12], s[13], s[14]);
+    return max3(max3(a, b, c), max3(d, e, s[15]), a);
+}
+
+template <int NWAVES, bool FP8>
 struct Tile {
     static constexpr int KBYTES = FP8 ? 64 * 64 : 64 * 128;     // K tile (e4m3 / bf16)
-    static constexpr int VBYTES = 64 * 128;                     // V^T tile (always bf16)
-    static constexpr int STAGE = KBYTES + VBYTES;
-    static constexpr int KINS = KBYTES / 1024 / NW;             // 1 KB copy instructions per wave
-    static constexpr int VINS = VBYTES / 1024 / NW;
+    static constexpr int VBYTES = 64 * 128;                     // V^T tile (always fp16)
+    static constexpr int KINS = KBYTES / 1024 / NWAVES;         // 1 KB copy instructions per wave
+    static constexpr int VINS = VBYTES / 1024 / NWAVES;
     static constexpr int LOADS = KINS + VINS;                   // per wave per tile
+    static constexpr int SLOTS = 3;                             // slots of the K ring and of the V^T ring
+    static constexpr int VRING = SLOTS * KBYTES;                // the V^T ring follows the K ring
+    // behind the rings: a 256-byte slot for the Z row, and, for E4M3 inputs (whose K ring is too small for both
+    // epilogue operands), 8 KB for W^T
+    static constexpr int ZOFF = SLOTS * (KBYTES + VBYTES);
+    static constexpr int WOFF = ZOFF + 256;
+    static constexpr int LDS = WOFF + (FP8 ? 8192 : 0);
 };
 
 // Per-lane byte offsets (inside a tile) of the 16-byte chunk each lane copies, one per copy
 // instruction of this wave: LDS position (row, slot) <- global chunk slot ^ swizzle(row).
-template <int NW, bool FP8>
+template <int NWAVES, bool FP8>
 struct CopyOffsets {
-    using T = Tile<NW, FP8>;
+    using T = Tile<NWAVES, FP8>;
     int k[T::KINS], v[T::VINS];
     int krow[T::KINS];            // K row of this lane per instruction (for clamping at a ragged end)
     // krowb: bytes between consecutive K rows in global memory (64 or 128 when the heads are contiguous)
@@ -110,38 +179,16 @@ struct CopyOffsets {
     }
 };
 
-// Requests one K tile and one V^T tile into the LDS stage at byte address stage (wave-uniform).
-// kt / vt: first byte of the tiles in global memory (wave-uniform); valid: number of real rows of
-// the K tile (rows past it are clamped to the last, they are masked later; V^T tiles are complete).
-template <int NW, bool FP8>
-__device__ __forceinline__ void issue_tile(uint32_t stage, const uint8_t *kt, const uint8_t *vt, int valid, int KROW,
-                                           const CopyOffsets<NW, FP8> &co, int wave)
-{
-    using T = Tile<NW, FP8>;
-    if (valid == kBK) {
-#pragma unroll
-        for (int x = 0; x < T::KINS; ++x) copy_1k_to_lds(kt, co.k[x], stage + (wave * T::KINS + x) * 1024);
-    } else {
-#pragma unroll
-        for (int x = 0; x < T::KINS; ++x)
-            copy_1k_to_lds(kt, co.k[x] - (co.krow[x] - min(co.krow[x], valid - 1)) * KROW, stage + (wave * T::KINS + x) * 1024);
-    }
-#pragma unroll
-    for (int x = 0; x < T::VINS; ++x) copy_1k_to_lds(vt, co.v[x], stage + T::KBYTES + (wave * T::VINS + x) * 1024);
-}
+template <bool B> using flag = std::integral_constant<bool, B>;
 
 // NW: 32-row query groups per workgroup (query block = 32 NW rows).  KS: key split -- with KS = 2
 // two waves share a query group and each takes one 32-key half of every tile (used for 64-row
 // query blocks so that a workgroup still has four waves); their partial (max, sum, O) are merged
 // through LDS after the loop and the KS = 0 wave of each pair runs the epilogue.
-// STG: stages of the tile ring.  3 in general (copies run two tiles ahead).  2 for lists of at most two critical
-// blocks (bf16, no key split): both tiles are requested at the start, the epilogue operands share the stage the
-// first tile leaves free, and the smaller LDS footprint lets four workgroups instead of three share a CU, which is
-// what a loop this short needs.
-template <int NW, int KS, bool FP8, int STG>
-__global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void attend_kernel(
-    const void *__restrict__ Qp, const void *__restrict__ Kp, const uint16_t *__restrict__ Vp,
-    const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV, RowMap rm,
+template <int NW, int KS, bool FP8>
+__global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
+    const void *__restrict__ Qp, const void *__restrict__ Kp, const uint16_t *__restrict__ Vp, const float *__restrict__ lvs,
+    const float *__restrict__ sQ, const float *__restrict__ sK, RowMap rm,
     const int32_t *__restrict__ crit_idx, int k_c, const uint16_t *__restrict__ Hq, const uint16_t *__restrict__ WT,
     int proj_per_head, int phi, int H, int N, int Nqb, int Nkb, long total, float c_exp, uint16_t *__restrict__ O)
 {
@@ -149,11 +196,9 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
     using T = Tile<NWAVES, FP8>;
     constexpr int BQ = 32 * NW;
     constexpr int ES = FP8 ? 1 : 2;                     // bytes per input element
-    constexpr int NH = 2 / KS;                          // 32-key halves of a tile this wave processes
-    constexpr int NS = 4 / KS;                          // 16-key steps of the second product this wave processes
-    static_assert(STG == 3 || (STG == 2 && KS == 1 && !FP8), "the two-stage ring is for unsplit bf16 lists of at most two tiles");
-    constexpr int kZBytes = STG == 2 ? 256 : 0;         // two-stage ring: the Z row gets its own slot behind the ring
-    __shared__ __attribute__((aligned(1024))) uint8_t lds[STG * T::STAGE + kZBytes];
+    constexpr int NH = 2 / KS;                          // units (32-key halves of a tile) this wave processes per tile
+    constexpr int KROWB = FP8 ? 64 : 128;               // bytes of a K row in LDS
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[T::LDS];
     const long work = xcd_remap(blockIdx.x, total);
     if (work >= total) return;                        // the whole workgroup leaves together
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
@@ -166,6 +211,7 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
     const int krowb = rm.ts * ES;                     // bytes between consecutive K rows
     const uint8_t *Kh = (const uint8_t *)Kp + head * ES;
     const uint8_t *Vh = (const uint8_t *)(Vp + (size_t)bh * Nkb * kBK * kD);
+    const float *lvh = lvs + bh * Nkb;
 
     // Q as the B operand of S^T: bf16 -> 4 K-steps of 8 channels (16s + 8g ..), e4m3 -> 32 channels (32g ..)
     bf16x8 qf[4];
@@ -188,182 +234,412 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
     }
     const float qscale = FP8 ? sQ[work] : 1.0f;       // scale blocks of Q are the query blocks
 
-    // per-lane LDS byte offsets of the fragments (swizzled 16-byte chunks):
-    //   koff[s]: K row 32 kh + l32 (+32 for the second half when KS = 1), channel chunk of step s
-    //   voff[ss]: V^T row l32 (+32 for channels 32..63), key chunk 2 s + g of this wave's step s = NS kh + ss
-    int koff[4], voff[NS];
+    // per-lane LDS byte offsets of the fragments inside a tile (swizzled 16-byte chunks):
+    //   koff[s]: K row l32 of a 32-key half, channel chunk of step s
+    //   voff[st]: V^T row l32 (+32 for channels 32..63), key chunk 2 st + g of 16-key step st of the tile
+    int koff[4], voff[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s)
-        koff[s] = (FP8 ? l32 * 64 + ((((2 * g + (s & 1)) ^ swz4(l32))) << 4) : l32 * 128 + (((2 * s + g) ^ swz8(l32)) << 4))
-                  + kh * 32 * (FP8 ? 64 : 128);
+        koff[s] = FP8 ? l32 * 64 + ((((2 * g + (s & 1)) ^ swz4(l32))) << 4) : l32 * 128 + (((2 * s + g) ^ swz8(l32)) << 4);
 #pragma unroll
-    for (int ss = 0; ss < NS; ++ss) voff[ss] = T::KBYTES + l32 * 128 + (((2 * (NS * kh + ss) + g) ^ swz8(l32)) << 4);
+    for (int st = 0; st < 4; ++st) voff[st] = l32 * 128 + (((2 * st + g) ^ swz8(l32)) << 4);
+    // KS == 2: the two steps of this wave's half (computed, not indexed: a run-time index would put voff[] in memory)
+    const int voffk[2] = {l32 * 128 + (((4 * kh + g) ^ swz8(l32)) << 4), l32 * 128 + (((4 * kh + 2 + g) ^ swz8(l32)) << 4)};
 
     f32x16 zero16;
 #pragma unroll
     for (int x = 0; x < 16; ++x) zero16[x] = 0.f;
     f32x16 oacc[2] = {zero16, zero16};
-    float m_run = -INFINITY, l_run = 0.f;             // running maximum in the log2 domain, running sum
-    const bf16x8 ones = __builtin_bit_cast(bf16x8, make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u));
+    // Running state of the lane's row.  m_run: reference exponent (log2 domain) of the weights; l_part: this lane's
+    // share of the row sum, accumulated from the fp16 weights the second product consumes (divided by the V scale
+    // ratio again); l_full: row sums formed in fp32 by the careful steps (already complete over the lane pair).
+    float m_run = -INFINITY, l_part = 0.f, l_full = 0.f;
 
     const int32_t *ci = crit_idx + work * (long)k_c;
-    auto tile_index = [&](int c) {                     // -1: no such tile (list exhausted or entry absent)
-        int j = c < k_c ? ci[c] : -1;
-        return (j < 0 || j >= Nkb) ? -1 : j;
+    // number of leading valid entries of the critical list (a list taken from given labels may end in -1 entries)
+    int k = 0;
+    for (int base = 0; base < k_c; base += 64) {
+        const int idx = base + lane;
+        const int j = idx < k_c ? ci[idx] : -1;
+        const unsigned long long ok = __ballot(j >= 0 && j < Nkb);
+        if (ok == ~0ull) { k += 64; continue; }
+        k += __builtin_ctzll(~ok);
+        break;
+    }
+    k = __builtin_amdgcn_readfirstlane(k);
+    // The list lives in registers, one entry per lane, as a window of 64 entries starting at wbase (a multiple of 32):
+    // block index, log2 of its V scale and (e4m3) its exp2 constant.  The loop takes what it needs with v_readlane,
+    // so no scalar load (and none of their waits) sits between the steps; the window moves every 32 tiles.
+    const float lv_ref = k > 0 ? lvh[ci[0]] : 0.f;     // log2 of the V scale of the first tile: the reference of the weights
+    int wbase = 0, d_j = 0;
+    float d_lv = 0.f, d_cj = 0.f;
+    auto load_window = [&](int wb) __attribute__((always_inline)) {
+        const int idx = wb + lane;
+        const int j = idx < k ? ci[idx] : 0;
+        d_j = j;
+        d_lv = lvh[j] - lv_ref;
+        // exp2 constant of the tile: softmax scale * log2(e) (* Q and K block scales for e4m3)
+        d_cj = FP8 ? fmaxf(c_exp * qscale * sK[bh * Nkb + j], 1e-30f) : c_exp;
+        asm volatile("" : "+v"(d_j), "+v"(d_lv), "+v"(d_cj));     // the loads complete here, not at some later first use
+        wbase = wb;
     };
+    load_window(0);
+    auto entry_j = [&](int c) { return __builtin_amdgcn_readlane(d_j, c - wbase); };
+
     CopyOffsets<NWAVES, FP8> co;
     co.init(wave, lane, krowb);
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);                       // same value, provably uniform
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_p)lds;                // LDS byte address of the ring
-    auto request = [&](int c, int j) {
-        const int jj = j < 0 ? 0 : j;                  // absent entries still copy (block 0) so the copy count is uniform
-        issue_tile<NWAVES, FP8>(lds_base + (c % STG) * T::STAGE, Kh + (size_t)jj * kBK * krowb, Vh + (size_t)jj * kBK * kD * 2,
-                                min(kBK, N - jj * kBK), krowb, co, wave_u);
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_p)lds;                // LDS byte address of the K ring
+    // Ragged block: only the last key block of the sequence can be short.
+    const int tail_rows = N & (kBK - 1), ragged_j = tail_rows ? Nkb - 1 : -1;
+    const uint32_t ktile_bytes = (uint32_t)kBK * (uint32_t)krowb;                  // bytes from one K block to the next
+    const uint32_t kdst0 = lds_base + wave_u * T::KINS * 1024, vdst0 = lds_base + T::VRING + wave_u * T::VINS * 1024;
+    // slot: byte offset of the ring slot (a multiple of the tile size below 3 tiles)
+    auto request_K = [&](int c, uint32_t slot) __attribute__((always_inline)) {       // K tile of list entry c into the slot at byte offset `slot` of the K ring
+#ifdef SLA_PROBE_NOCOPY
+        return;
+#endif
+        const uint32_t j = (uint32_t)entry_j(c);
+        const uint8_t *kt = Kh + (uint64_t)j * ktile_bytes;
+        if ((int)j != ragged_j) {
+            copy_nk_to_lds<T::KINS>(kt, co.k, kdst0 + slot);
+        } else {                                       // rows past the end are clamped to the last one; they are masked later
+#pragma unroll
+            for (int x = 0; x < T::KINS; ++x)
+                copy_1k_to_lds(kt, co.k[x] - (co.krow[x] - min(co.krow[x], tail_rows - 1)) * krowb, kdst0 + slot + x * 1024);
+        }
     };
-    // The operands of the linear/projection epilogue (the 64x64 tile of Hq^T, the Z row, W^T) travel the
-    // same way into the two ring stages that are idle during the last tile, so their latency hides
-    // behind that tile's arithmetic.  c_next: index of the first idle stage.
+    auto request_V = [&](int c, uint32_t slot) __attribute__((always_inline)) {       // V^T tile of list entry c into the slot at byte offset `slot` of the V^T ring
+#ifdef SLA_PROBE_NOCOPY
+        return;
+#endif
+        const uint8_t *vt = Vh + (uint64_t)(uint32_t)entry_j(c) * (uint32_t)(kBK * kD * 2);
+        copy_nk_to_lds<T::VINS>(vt, co.v, vdst0 + slot);
+    };
+    auto next_slot = [](uint32_t slot, uint32_t bytes) { return slot + bytes == T::SLOTS * bytes ? 0u : slot + bytes; };
+    // The operands of the linear/projection epilogue (the 64x64 tile of Hq^T, the Z row, W^T) travel the same way
+    // into the K ring, which is idle during the last tile, so their latency hides behind that tile's arithmetic.
     const uint8_t *Hi8 = Hq ? (const uint8_t *)(Hq + (size_t)work * kStateElems) : nullptr;
     const uint8_t *Wh8 = (const uint8_t *)(WT + (proj_per_head ? (size_t)(bh % H) * kD * kD : 0));
-    auto request_epilogue = [&](int c_next) {
-        const uint32_t sa = lds_base + (c_next % STG) * T::STAGE;
-        const uint32_t sb = STG == 2 ? sa + 8192 : lds_base + ((c_next + 1) % STG) * T::STAGE;
-        const uint32_t sz = STG == 2 ? lds_base + STG * T::STAGE : sa + 8192;
+    constexpr int kHqOff = 0, kWtOff = FP8 ? T::WOFF : 8192;
+    auto request_epilogue = [&]() __attribute__((always_inline)) {
+        if (Hq == nullptr) return;
 #pragma unroll
-        for (int x = 0; x < T::VINS; ++x) copy_1k_to_lds(Hi8, co.v[x], sa + (wave_u * T::VINS + x) * 1024);
+        for (int x = 0; x < T::VINS; ++x) copy_1k_to_lds(Hi8, co.v[x], lds_base + kHqOff + (wave_u * T::VINS + x) * 1024);
 #pragma unroll
-        for (int x = 0; x < T::VINS; ++x) copy_1k_to_lds(Wh8, co.v[x], sb + (wave_u * T::VINS + x) * 1024);
-        if (tid < 8) copy_1k_to_lds(Hi8 + 64 * kD * 2, tid * 16, sz);             // Z: 128 bytes, 8 lanes of wave 0
+        for (int x = 0; x < T::VINS; ++x) copy_1k_to_lds(Wh8, co.v[x], lds_base + kWtOff + (wave_u * T::VINS + x) * 1024);
+        if (tid < 8) copy_1k_to_lds(Hi8 + 64 * kD * 2, tid * 16, lds_base + T::ZOFF);   // Z: 128 bytes, 8 lanes of wave 0
     };
-    if (Hq != nullptr && k_c == 0) request_epilogue(0);
 
-    // Key mask of a ragged last block: it enters as the initial accumulator of S^T (0 for real keys,
-    // -inf for keys past the end), built on the fly only for such a tile; every other tile starts from 0.
-    auto key_mask = [&](int valid, f32x16 (&m)[NH]) {
-#pragma unroll
-        for (int hh = 0; hh < NH; ++hh)
-#pragma unroll
-            for (int x = 0; x < 16; ++x)
-                m[hh][x] = (32 * (kh + hh) + 8 * (x >> 2) + 4 * g + (x & 3)) < valid ? 0.f : -INFINITY;
+    // ---- per-tile constants (wave-uniform)
+    struct TileInfo { int valid; float cj, lsv, invr; bool tiny; };
+    auto tile_info = [&](int c) __attribute__((always_inline)) {
+        TileInfo t;
+        t.valid = entry_j(c) == ragged_j ? tail_rows : kBK;
+        t.cj = FP8 ? __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(d_cj), c - wbase)) : c_exp;
+        t.lsv = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(d_lv), c - wbase));   // the V scale of the tile rides on the weights: P' = P * 2^lsv
+        t.tiny = fabsf(t.lsv) > kTinyV;
+        t.invr = fast_exp2(-t.lsv);                    // and is divided out of the row sums again
+        return t;
     };
-    // S^T = K Q^T (+ init) of this wave's key halves of the tile staged at st
-    auto compute_S = [&](const uint8_t *st, const f32x16 (&init)[NH], f32x16 (&s2)[NH]) {
+
+    // ---- pieces of a step.  Unit u of a wave is the 32-key half `half` of tile c: u = c * NH + half - (KS == 2 ? kh : 0)
+    // S^T of a unit: K rows 32 half .. 32 half + 31 of the tile in K slot c % 3
+    // kbase / vbase: byte offset of a slot of the K ring / of the V^T ring (wave-uniform); the per-lane part koff / voff
+    // is added once per slot, the half of the tile is an immediate offset of the read (K) or picks the register (V^T)
+    auto k_frag_addr = [&](int kbase, int half, int s) {
+        return lds + half * 32 * KROWB + (kbase + koff[s]);
+    };
+    auto v_frag_addr = [&](int vbase, int half, int ss, int e) {
+        return lds + e * 32 * 128 + (vbase + (KS == 2 ? voffk[ss] : voff[2 * half + ss]));
+    };
+    // key mask of a ragged block as the initial accumulator: 0 for real keys, -inf for keys past the end
+    auto s_init = [&](int valid, int half) {
+        f32x16 m;
+#pragma unroll
+        for (int x = 0; x < 16; ++x) m[x] = (32 * half + 8 * (x >> 2) + 4 * g + (x & 3)) < valid ? 0.f : -INFINITY;
+        return m;
+    };
+    struct KFrag { i32x4 w[FP8 ? 2 : 4]; };
+    struct VFrag { f16x8 f[2][2]; };                   // [16-key step][channel half]
+    auto load_kfrag = [&](int kbase, int half) __attribute__((always_inline)) {
+        KFrag f;
+#ifdef SLA_PROBE_NOLDS
+        for (int s = 0; s < (FP8 ? 2 : 4); ++s) f.w[s] = i32x4{kbase, half, s, 1};
+        return f;
+#endif
+#pragma unroll
+        for (int s = 0; s < (FP8 ? 2 : 4); ++s) f.w[s] = *(const i32x4 *)k_frag_addr(kbase, half, s);
+        return f;
+    };
+    auto load_vfrag = [&](int vbase, int half) __attribute__((always_inline)) {
+        VFrag f;
+#ifdef SLA_PROBE_NOLDS
+        for (int ss = 0; ss < 2; ++ss) for (int e = 0; e < 2; ++e) f.f[ss][e] = __builtin_bit_cast(f16x8, i32x4{vbase, half, ss, e});
+        return f;
+#endif
+#pragma unroll
+        for (int ss = 0; ss < 2; ++ss)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) f.f[ss][e] = *(const f16x8 *)v_frag_addr(vbase, half, ss, e);
+        return f;
+    };
+    auto compute_S = [&](const KFrag &kf, const f32x16 &init) __attribute__((always_inline)) {
+        f32x16 s;
         if (FP8) {
-#pragma unroll
-            for (int hh = 0; hh < NH; ++hh) {
-                const uint4 w0 = *(const uint4 *)(st + koff[0] + hh * 32 * 64), w1 = *(const uint4 *)(st + koff[1] + hh * 32 * 64);
-                i32x8 k8;
-                k8[0] = w0.x; k8[1] = w0.y; k8[2] = w0.z; k8[3] = w0.w; k8[4] = w1.x; k8[5] = w1.y; k8[6] = w1.z; k8[7] = w1.w;
-                s2[hh] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(k8, q8, init[hh], 0, 0, 0, 0, 0, 0);
-            }
+            i32x8 k8;
+            k8[0] = kf.w[0][0]; k8[1] = kf.w[0][1]; k8[2] = kf.w[0][2]; k8[3] = kf.w[0][3];
+            k8[4] = kf.w[1][0]; k8[5] = kf.w[1][1]; k8[6] = kf.w[1][2]; k8[7] = kf.w[1][3];
+            s = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(k8, q8, init, 0, 0, 0, 0, 0, 0);
         } else {
+            s = init;
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
+            for (int st = 0; st < 4; ++st)
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf.w[st]), qf[st], s, 0, 0, 0);
+        }
+        return s;
+    };
+    // O^T += V^T P^T of one unit, and the lane's share of its row sums from the same fp16 weights
+    struct Weights { f16x8 p[2]; float invr; };        // invr = 0: the row sums of this unit were formed elsewhere
+    auto accumulate = [&](const VFrag &vf, const Weights &w) __attribute__((always_inline)) {
+        const f16x2 iv = {(_Float16)w.invr, (_Float16)w.invr};
 #pragma unroll
-                for (int hh = 0; hh < NH; ++hh) {
-                    const bf16x8 kf = *(const bf16x8 *)(st + koff[s] + hh * 32 * 128);
-                    s2[hh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? init[hh] : s2[hh], 0, 0, 0);
-                }
+        for (int ss = 0; ss < 2; ++ss) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e) oacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf.f[ss][e], w.p[ss], oacc[e], 0, 0, 0);
+            const uint4 pw = __builtin_bit_cast(uint4, w.p[ss]);
+            l_part = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, pw.x), iv, l_part, false);
+            l_part = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, pw.y), iv, l_part, false);
+            l_part = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, pw.z), iv, l_part, false);
+            l_part = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, pw.w), iv, l_part, false);
         }
     };
-    int j0 = tile_index(0), j1 = tile_index(1);
-    if (k_c > 0) request(0, j0);
-    if (k_c > 1) request(1, j1);
-    // Let the Q fragments (ordinary loads the compiler tracks) land here, once: left to the compiler, its
-    // vmcnt(0) for them would sit in front of their first use inside the loop and drain the ring every trip.
-    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
-
-    for (int c = 0; c < k_c; ++c) {
-        const int j = j0;
-        // copies of tiles 0..c+1 have been requested; tile c has landed once only those of tile c+1 remain
-        if (c + 1 < k_c) wait_copies_and_barrier<T::LOADS>();   // tile c visible to all waves; stage of tile c-1 free
-        else wait_copies_and_barrier<0>();
-        j0 = j1;
-        j1 = tile_index(c + 2);
-        if (c + 2 < k_c) request(c + 2, j1);
-        if (Hq != nullptr && c + 1 == k_c) request_epilogue(c + 1);
-        if (j < 0) continue;
-        const uint8_t *st = lds + (c % STG) * T::STAGE;
-        const int valid = min(kBK, N - j * kBK);
-        // exp2 constant of this tile: softmax scale * log2(e) (* Q and K block scales for e4m3)
-        const float cj = FP8 ? fmaxf(c_exp * qscale * sK[bh * Nkb + j], 1e-30f) : c_exp;
-        // E4M3: the V block scale rides on the weights, P' = P * sV_j (an offset in the exponent); the
-        // row sum of P' is divided by sV_j again, so numerator and denominator stay consistent.
-        const float svj = FP8 ? fmaxf(sV[bh * Nkb + j], 1e-30f) : 1.0f;
-        const float lsv = FP8 ? __log2f(svj) : 0.0f;
-
-        // ---- S^T = K Q^T
-        f32x16 sacc[NH];
-        if (valid == kBK) {
-            f32x16 init[NH];
+    auto rescale = [&](float alpha) __attribute__((always_inline)) {
+        l_part *= alpha;
+        l_full *= alpha;
 #pragma unroll
-            for (int hh = 0; hh < NH; ++hh) init[hh] = zero16;
-            compute_S(st, init, sacc);
-        } else {
-            f32x16 init[NH];
-            key_mask(valid, init);
-            compute_S(st, init, sacc);
-        }
-
-        // ---- online softmax, one query row per lane (shared with lane^32)
-        float mx = sacc[0][0];
+        for (int e = 0; e < 2; ++e)
 #pragma unroll
-        for (int hh = 0; hh < NH; ++hh)
-#pragma unroll
-            for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sacc[hh][x]);
-        mx = pair_max(mx);
-        // the accumulators are rescaled only in iterations where some row of the wave raised its maximum;
-        // a half tile may hold no real key (ragged end): its maximum is -inf and leaves the state alone
-        mx *= cj;
-        if (__ballot(mx > m_run + kLazyMax)) {
-            const float m_new = mx > m_run + kLazyMax ? fmaxf(m_run, mx) : m_run;
-            const float alpha = m_new == m_run ? 1.0f : fast_exp2(m_run - m_new);
+            for (int x = 0; x < 16; ++x) oacc[e][x] *= alpha;
+    };
+    // Careful form (first unit of a row, ragged or tiny-scale tiles): exact maximum of the unit, row sums in fp32
+    // from weights that do not carry the V scale.
+    auto softmax_careful = [&](f32x16 &s, const TileInfo &t, Weights &w) __attribute__((always_inline)) {
+        const float top = pair_max(max16(s)) * t.cj + t.lsv;        // -inf if the lane's row sees no real key in this unit
+        if (__ballot(top > m_run)) {
+            const float m_new = fmaxf(m_run, top);
+            rescale(m_new == m_run ? 1.0f : fast_exp2(m_run - m_new));
             m_run = m_new;
-            l_run *= alpha;
-#pragma unroll
-            for (int e = 0; e < 2; ++e)
-#pragma unroll
-                for (int x = 0; x < 16; ++x) oacc[e][x] *= alpha;
         }
-        const float moff = lsv - (m_run == -INFINITY ? 0.f : m_run);
+        const float mfin = m_run == -INFINITY ? 0.f : m_run;
+        const float r = fast_exp2(t.lsv);
+        float sum = 0.f;
 #pragma unroll
-        for (int hh = 0; hh < NH; ++hh)
-#pragma unroll
-            for (int x = 0; x < 16; ++x) sacc[hh][x] = fast_exp2(fmaf(sacc[hh][x], cj, moff));
+        for (int x = 0; x < 16; ++x) {
+            const float pu = fast_exp2(fmaf(s[x], t.cj, -mfin));   // weight without the V scale: what the row sum adds up
+            sum += pu;
+            s[x] = pu * r;                                          // weight with it: what multiplies the scaled V^T
+        }
+        l_full += sum + xchg32(sum);
+        w.p[0] = pack8_f16(s, 0);
+        w.p[1] = pack8_f16(s, 8);
+        w.invr = 0.f;
+    };
 
-        // ---- O^T += V^T P^T, and the row sums as ones^T P^T on the same bf16-rounded P, so that
-        // numerator and denominator of the softmax see identical weights
-        f32x16 lsum;
-#pragma unroll
-        for (int ss = 0; ss < NS; ++ss) {
-            const bf16x8 pf = pack8(sacc[ss >> 1], 8 * (ss & 1));
-            lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf, ss == 0 ? zero16 : lsum, 0, 0, 0);
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const bf16x8 vf = *(const bf16x8 *)(st + voff[ss] + e * 32 * 128);
-                oacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[e], 0, 0, 0);
-            }
-        }
-        l_run += FP8 ? lsum[0] / svj : lsum[0];        // every row of ones^T P^T is the sum over this wave's keys
+    // ---- prologue: the first copies, Q, and S^T of unit 0
+    if (k == 0) request_epilogue();
+    if (k > 0) request_K(0, 0);
+    if (k > 1) request_K(1, T::KBYTES);
+    if (k > 2) request_K(2, 2 * T::KBYTES);
+    if (k > 0) request_V(0, 0);
+    if (k > 1) request_V(1, T::VBYTES);
+    // Let the Q fragments (ordinary loads the compiler tracks) and the first tiles land here, once: left to the
+    // compiler, its vmcnt(0) for Q would sit in front of their first use inside the loop and drain the ring every trip.
+    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));      // vmcnt(0), as a builtin so that the compiler's bookkeeping sees it
+    wait_copies_and_barrier<0>();
+
+    // Units of this wave: u = NH c + hh is the 32-key half (KS == 2 ? kh : hh) of tile c.  Step u accumulates unit u-1
+    // (V^T fragments vf_use), forms S^T of unit u+1 (K fragments kf_use) and runs the softmax of unit u; meanwhile the
+    // fragments of step u+1 are read from LDS (vf_pre, kf_pre), so that a slot is done with one step before its
+    // arithmetic and the LDS latency is off the critical path.
+    auto unit_tile = [&](int u) { return NH == 2 ? u >> 1 : u; };
+    auto unit_half = [&](int u) { return NH == 2 ? u & 1 : kh; };
+    f32x16 s_cur = zero16;
+    Weights w_prev;
+    w_prev.p[0] = w_prev.p[1] = __builtin_bit_cast(f16x8, make_uint4(0, 0, 0, 0));
+    w_prev.invr = 0.f;
+    KFrag kf_use, kf_pre;
+    VFrag vf_use, vf_pre;
+    TileInfo t_cur, t_nxt;
+    const int U = k * NH;                              // units of this wave
+    if (k > 0) {
+        t_cur = tile_info(0);
+        s_cur = compute_S(load_kfrag(0, unit_half(0)), t_cur.valid == kBK ? zero16 : s_init(t_cur.valid, unit_half(0)));
+        if (U > 1) kf_use = load_kfrag(unit_tile(1) * T::KBYTES, unit_half(1));     // for S^T of unit 1, formed in step 0
     }
 
-    // ring stages after the loop: A, B hold the epilogue operands, L (the last tile's stage) is free
-    const int c_next = k_c;
-    uint8_t *stA = lds + (c_next % STG) * T::STAGE, *stB = STG == 2 ? stA + 8192 : lds + ((c_next + 1) % STG) * T::STAGE;
-    uint8_t *stL = lds + ((c_next + 2) % STG) * T::STAGE;            // used by the key-split merge only (STG == 3)
-    const uint8_t *zrow = STG == 2 ? lds + STG * T::STAGE : stA + 8192;
-    wait_copies_and_barrier<0>();                      // epilogue operands landed; every wave is past its last tile
+#define SLA_SB() __builtin_amdgcn_sched_barrier(0)
+#define SLA_PIN(...) asm volatile("" : __VA_ARGS__)
+    // Whether some lane's largest exponent in the unit whose S^T is s would exceed kRaise against the lane's running
+    // maximum (stale by that much, or still -inf): such a unit takes the careful step, which raises the maximum exactly.
+    auto overflows = [&](const f32x16 &s, const TileInfo &t) __attribute__((always_inline)) {
+        return __ballot(!(fmaf(max16(s), t.cj, t.lsv - m_run) <= kRaise)) != 0;
+    };
+    bool over_cur = true;                              // the first unit is careful anyway
 
+    // One step of the pipeline (see above), careful form: exact softmax, no particular instruction order.
+    // t: tile of unit u; tn, half_n: tile and half of unit u+1 (key mask of a ragged block); has_pv / has_s: unit u-1 /
+    // u+1 exists; (cv, hv) / (ck, hk): ring slot (byte offset) and half whose V^T / K fragments step u+1 will use.
+    auto careful_step = [&](bool has_pv, bool has_s, const TileInfo &t, const TileInfo &tn, int half_n, int cv, int hv, int ck, int hk)
+                            __attribute__((always_inline)) {
+        f32x16 s_nxt = zero16;
+        Weights w;
+        vf_pre = load_vfrag(cv, hv);                   // always in bounds (a slot of the ring); unused if there is no such step
+        kf_pre = load_kfrag(ck, hk);
+        if (has_pv) accumulate(vf_use, w_prev);
+        if (has_s) s_nxt = compute_S(kf_use, tn.valid == kBK ? zero16 : s_init(tn.valid, half_n));
+        softmax_careful(s_cur, t, w);
+        over_cur = has_s ? overflows(s_nxt, tn) : true;
+        s_cur = s_nxt; w_prev = w; vf_use = vf_pre; kf_use = kf_pre;
+    };
+    // Fast form (a unit in the middle of the list, full tiles, no exponent above kRaise), written out in issue order:
+    // one MFMA, then a share of the vector work (the matrix unit needs 32 cycles per MFMA, the share of vector work
+    // about as long).  The order is held by data dependencies the compiler cannot see through: every share ends in
+    // an empty asm statement that "rewrites" the results of the share and the exponent offset the next one starts
+    // from, so nothing can move from one share into another (the instruction selector would otherwise bunch the MFMAs
+    // that open a new accumulator at the end of the block, and the exponentials behind them), and in a scheduling
+    // barrier for the later passes.  The running maximum stays where it is.  The step ends with the overflow check of
+    // the next unit, while the last MFMA runs.
+    auto fast_step = [&](const TileInfo &t, const TileInfo &tn, int cv, int hv, int ck, int hk) __attribute__((always_inline)) {
+        f32x16 s_nxt = zero16;
+        Weights w;
+        vf_pre = load_vfrag(cv, hv);
+        kf_pre = load_kfrag(ck, hk);
+        const f16x2 iv = {(_Float16)w_prev.invr, (_Float16)w_prev.invr};
+        uint32_t pw[8];
+        float moff = t.lsv - m_run;
+        auto pv = [&](int ss, int e) { oacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf_use.f[ss][e], w_prev.p[ss], oacc[e], 0, 0, 0); };
+        auto sm = [&](int st) {
+            if (FP8) {
+                i32x8 k8;
+                k8[0] = kf_use.w[0][0]; k8[1] = kf_use.w[0][1]; k8[2] = kf_use.w[0][2]; k8[3] = kf_use.w[0][3];
+                k8[4] = kf_use.w[1][0]; k8[5] = kf_use.w[1][1]; k8[6] = kf_use.w[1][2]; k8[7] = kf_use.w[1][3];
+                s_nxt = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(k8, q8, zero16, 0, 0, 0, 0, 0, 0);
+            } else {
+                s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf_use.w[st]), qf[st], s_nxt, 0, 0, 0);
+            }
+        };
+        auto el = [&](int x0, int x1) {
+#pragma unroll
+            for (int x = x0; x <= x1; ++x) s_cur[x] = fast_exp2(fmaf(s_cur[x], t.cj, moff));
+        };
+        auto cv2 = [&](int pr) { pw[pr] = pack_f16(s_cur[2 * pr], s_cur[2 * pr + 1]); };
+        auto dots = [&](int ss) {
+            const uint4 q4 = __builtin_bit_cast(uint4, w_prev.p[ss]);
+            l_part = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, q4.x), iv, l_part, false);
+            l_part = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, q4.y), iv, l_part, false);
+            l_part = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, q4.z), iv, l_part, false);
+            l_part = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, q4.w), iv, l_part, false);
+        };
+        SLA_SB();
+        if (!FP8) {
+            sm(0);    el(0, 1);   cv2(0);
+            SLA_PIN("+v"(s_nxt), "+v"(moff), "+v"(pw[0])); SLA_SB();
+            pv(0, 0); el(2, 3);   cv2(1);
+            SLA_PIN("+v"(oacc[0]), "+v"(moff), "+v"(pw[1])); SLA_SB();
+            sm(1);    el(4, 5);   cv2(2);
+            SLA_PIN("+v"(s_nxt), "+v"(moff), "+v"(pw[2])); SLA_SB();
+            pv(0, 1); el(6, 7);   cv2(3);
+            SLA_PIN("+v"(oacc[1]), "+v"(moff), "+v"(pw[3])); SLA_SB();
+            sm(2);    el(8, 9);   cv2(4);
+            SLA_PIN("+v"(s_nxt), "+v"(moff), "+v"(pw[4])); SLA_SB();
+            pv(1, 0); el(10, 11); cv2(5);
+            SLA_PIN("+v"(oacc[0]), "+v"(moff), "+v"(pw[5])); SLA_SB();
+            sm(3);    el(12, 13); cv2(6); dots(0);
+            SLA_PIN("+v"(s_nxt), "+v"(moff), "+v"(pw[6]), "+v"(l_part)); SLA_SB();
+            pv(1, 1); el(14, 15); cv2(7); dots(1);
+            SLA_PIN("+v"(oacc[1]), "+v"(pw[7]), "+v"(l_part)); SLA_SB();
+        } else {
+            sm(0);    el(0, 4);   cv2(0); cv2(1);                            // the e4m3 MFMA takes twice as long
+            SLA_PIN("+v"(s_nxt), "+v"(moff), "+v"(pw[0]), "+v"(pw[1])); SLA_SB();
+            pv(0, 0); el(5, 7);   cv2(2); cv2(3);
+            SLA_PIN("+v"(oacc[0]), "+v"(moff), "+v"(pw[2]), "+v"(pw[3])); SLA_SB();
+            pv(0, 1); el(8, 10);  cv2(4);
+            SLA_PIN("+v"(oacc[1]), "+v"(moff), "+v"(pw[4])); SLA_SB();
+            pv(1, 0); el(11, 13); cv2(5); cv2(6); dots(0);
+            SLA_PIN("+v"(oacc[0]), "+v"(moff), "+v"(pw[5]), "+v"(pw[6]), "+v"(l_part)); SLA_SB();
+            pv(1, 1); el(14, 15); cv2(7); dots(1);
+            SLA_PIN("+v"(oacc[1]), "+v"(pw[7]), "+v"(l_part)); SLA_SB();
+        }
+        w.p[0] = __builtin_bit_cast(f16x8, make_uint4(pw[0], pw[1], pw[2], pw[3]));
+        w.p[1] = __builtin_bit_cast(f16x8, make_uint4(pw[4], pw[5], pw[6], pw[7]));
+        w.invr = t.invr;
+        over_cur = overflows(s_nxt, tn);
+        // the fragments requested at the top of this step have long arrived: say so here, so that the wait the
+        // compiler places in front of their first use in the next step does not also cover that step's own reads
+        __builtin_amdgcn_s_waitcnt(0xC07F);        // lgkmcnt(0) only
+        s_cur = s_nxt; w_prev = w; vf_use = vf_pre; kf_use = kf_pre;
+    };
+#undef SLA_PIN
+
+    // Ring bookkeeping.  During iteration c the LDS reads touch V^T tile c and K tile c + KAHEAD - 2 (the fragments of
+    // the following step); both must have landed at its barrier, and that barrier frees the slots of the tiles before
+    // them, into which the copies of V^T tile c + 2 and K tile c + KAHEAD go: needed two iterations later.
+    constexpr int KAHEAD = NH == 2 ? 3 : 4;
+    // ring slots (byte offsets) of: the K tile requested in this iteration, the V^T tile requested, the K tile whose
+    // fragments are read, the V^T tile whose fragments are read; each moves on by one slot per iteration
+    uint32_t kreq = (KAHEAD % T::SLOTS) * T::KBYTES, vreq = 2 * T::VBYTES, kread = ((KAHEAD - 2) % T::SLOTS) * T::KBYTES, vread = 0;
+    for (int c = 0; c < k; ++c) {
+        // copies that may stay in flight here: those requested one iteration ago
+        if (c == 0) wait_copies_and_barrier<0>();      // (nothing is in flight; joins the waves after the prologue's LDS reads)
+        else if (c + KAHEAD - 1 < k) wait_copies_and_barrier<T::LOADS>();
+        else if (c + 1 < k) wait_copies_and_barrier<T::VINS>();
+        else wait_copies_and_barrier<0>();
+        if (c + KAHEAD - wbase >= 64) load_window(wbase + 32);     // (never for lists of at most 64 blocks)
+        if (KAHEAD == 4 && c == 0 && 3 < k) request_K(3, 0);
+        if (c + KAHEAD < k) request_K(c + KAHEAD, kreq);
+        if (c + 2 < k) request_V(c + 2, vreq);
+        if (c + 1 == k) request_epilogue();
+        const bool more = c + 1 < k;
+        if (more) t_nxt = tile_info(c + 1);
+        const bool ragged_n = more && t_nxt.valid != kBK;
+        const int vslot = T::VRING + (int)vread, kslot = (int)kread;
+        if (NH == 2) {
+            // first half of tile c: accumulates the second half of tile c-1, forms S^T of the second half of tile c;
+            // reads the fragments of the next step: V^T tile c first half, K tile c+1 first half
+            if (over_cur || c == 0 || t_cur.tiny || t_cur.valid != kBK) careful_step(c > 0, true, t_cur, t_cur, 1, vslot, 0, kslot, 0);
+            else fast_step(t_cur, t_cur, vslot, 0, kslot, 0);
+            // second half of tile c: accumulates its first half, forms S^T of the first half of tile c+1;
+            // reads V^T tile c second half and K tile c+1 second half for the first step of the next iteration
+            if (over_cur || !more || t_cur.tiny || ragged_n) careful_step(true, more, t_cur, t_nxt, 0, vslot, 1, kslot, 1);
+            else fast_step(t_cur, t_nxt, vslot, 1, kslot, 1);
+        } else {
+            // accumulates this wave's half of tile c-1, forms S^T of its half of tile c+1; reads V^T tile c and K tile c+2
+            if (over_cur || c == 0 || !more || t_cur.tiny || ragged_n) careful_step(c > 0, more, t_cur, t_nxt, kh, vslot, kh, kslot, kh);
+            else fast_step(t_cur, t_nxt, vslot, kh, kslot, kh);
+        }
+        t_cur = t_nxt;
+        kreq = next_slot(kreq, T::KBYTES); kread = next_slot(kread, T::KBYTES);
+        vreq = next_slot(vreq, T::VBYTES); vread = next_slot(vread, T::VBYTES);
+    }
+#undef SLA_SB
+
+    wait_copies_and_barrier<0>();                      // epilogue operands landed; every wave is past its last tile
+    if (k > 0) accumulate(vf_use, w_prev);             // the last unit's weights
+    float l_run = l_part + xchg32(l_part) + l_full;
+
+    uint8_t *stA = lds + kHqOff, *stB = lds + kWtOff;
+    const uint8_t *zrow = lds + T::ZOFF;
     if (KS == 2) {
-        // ---- merge the two key halves: the kh = 1 wave parks (O, max, sum) in LDS, its partner folds them in.
-        // Four 4 KB slots for the two 32-channel halves of the two parked waves: three in stage L and one
-        // behind W^T in stage B (an e4m3 stage is only 12 KB); max/sum go behind the Z row in stage A.
-        auto slot = [&](int r) { return r < 3 ? stL + r * 4096 : (T::STAGE >= 16384 ? stL + 12288 : stB + 8192); };
-        float *ml = (float *)(stA + 8448) + wq * 128;
+        // ---- merge the two key halves: the kh = 1 wave parks (O, max, sum) in the V^T ring, its partner folds them in.
+        // Four 4 KB slots for the two 32-channel halves of the two parked waves, max/sum behind them.
+        wait_copies_and_barrier<0>();                  // every wave has read its last V^T fragments
+        uint8_t *park = lds + T::VRING;
+        float *ml = (float *)(park + 16384) + wq * 128;
         if (kh == 1) {
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                uint8_t *dst = slot(2 * wq + e);
+                uint8_t *dst = park + (2 * wq + e) * 4096;
 #pragma unroll
                 for (int x4 = 0; x4 < 4; ++x4)
                     *(float4 *)(dst + x4 * 1024 + lane * 16) = make_float4(oacc[e][4 * x4], oacc[e][4 * x4 + 1], oacc[e][4 * x4 + 2], oacc[e][4 * x4 + 3]);
@@ -379,7 +655,7 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
             l_run = l_run * a0 + l1 * a1;
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                const uint8_t *src = slot(2 * wq + e);
+                const uint8_t *src = park + (2 * wq + e) * 4096;
 #pragma unroll
                 for (int x4 = 0; x4 < 4; ++x4) {
                     const float4 o1 = *(const float4 *)(src + x4 * 1024 + lane * 16);
@@ -392,8 +668,8 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
         }
     }
 
-    // ---- normalise the sparse output
-    const float inv_l = l_run > 0.f ? 1.0f / l_run : 0.f;
+    // ---- normalise the sparse output: the weights carried the V scale relative to the first tile's
+    const float inv_l = l_run > 0.f ? fast_exp2(lv_ref) / l_run : 0.f;
 #pragma unroll
     for (int e = 0; e < 2; ++e)
 #pragma unroll
@@ -481,9 +757,9 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
     // ---- store.  Register 4a+b of oacc[e] is channel 32e + 8a + 4g + b of row q: the wave's 32x64 tile
     // is transposed through a private 4 KB LDS slice (8-byte pieces, XOR-swizzled by row) so that it
     // leaves as full 128-byte rows, 16 bytes per lane.
-    wait_copies_and_barrier<0>();                      // all waves are done reading the ring
+    wait_copies_and_barrier<0>();                      // all waves are done reading the epilogue operands
     if (kh == 0) {
-        uint8_t *ot = lds + wq * 4096;
+        uint8_t *ot = lds + T::VRING + wq * 4096;
         const int f = ((l32 >> 1) & 7) << 1;
 #pragma unroll
         for (int e = 0; e < 2; ++e)
@@ -498,8 +774,8 @@ __global__ __launch_bounds__(64 * NW * KS, (NW == 2 && KS == 1) ? 2 : 3) void at
         wave_lds_sync();
         const int q0w = i * BQ + 32 * wq;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int r = 8 * k + (lane >> 3), ch = lane & 7;      // row of the tile, 16-byte chunk of the row
+        for (int kk = 0; kk < 4; ++kk) {
+            const int r = 8 * kk + (lane >> 3), ch = lane & 7;      // row of the tile, 16-byte chunk of the row
             const int fr = ((r >> 1) & 7) << 1;
             const uint4 v = *(const uint4 *)(ot + r * 128 + (((2 * ch) ^ fr) << 3));
             if (q0w + r < N) *(uint4 *)(O + head + (size_t)(q0w + r) * rm.ts + ch * 8) = v;
@@ -519,19 +795,19 @@ hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int NW, int KS, bool FP8, int STG>
-static hipError_t launch_attend_t(const void *Q, const void *K, const void *Vp, const float *sQ, const float *sK, const float *sV, RowMap rm,
+template <int NW, int KS, bool FP8>
+static hipError_t launch_attend_t(const void *Q, const void *K, const void *Vp, const float *lvs, const float *sQ, const float *sK, RowMap rm,
                                   const int32_t *crit_idx, int k_c, const void *Hq, const void *WT, int proj_per_head, int phi,
                                   int H, int N, int Nqb, int Nkb, long total, float c_exp, void *O, hipStream_t st)
 {
-    attend_kernel<NW, KS, FP8, STG><<<(unsigned)xcd_grid(total), 64 * NW * KS, 0, st>>>(Q, K, (const uint16_t *)Vp, sQ, sK, sV, rm, crit_idx, k_c, (const uint16_t *)Hq,
-                                                                          (const uint16_t *)WT, proj_per_head, phi, H, N, Nqb, Nkb,
-                                                                          total, c_exp, (uint16_t *)O);
+    attend_kernel<NW, KS, FP8><<<(unsigned)xcd_grid(total), 64 * NW * KS, 0, st>>>(Q, K, (const uint16_t *)Vp, lvs, sQ, sK, rm, crit_idx, k_c, (const uint16_t *)Hq,
+                                                                     (const uint16_t *)WT, proj_per_head, phi, H, N, Nqb, Nkb,
+                                                                     total, c_exp, (uint16_t *)O);
     return hipGetLastError();
 }
 
-hipError_t launch_attend(const void *Q, const void *K, const void *Vp,
-                         const float *sQ, const float *sK, const float *sV, bool fp8, RowMap rm,
+hipError_t launch_attend(const void *Q, const void *K, const void *Vp, const float *lvs,
+                         const float *sQ, const float *sK, bool fp8, RowMap rm,
                          const int32_t *crit_idx, int k_c, const void *Hq, const void *WT,
                          int proj_per_head, int phi, int B, int H, int N, int bq, float sm_scale,
                          void *O, hipStream_t st)
@@ -539,14 +815,13 @@ hipError_t launch_attend(const void *Q, const void *K, const void *Vp,
     const int Nqb = (N + bq - 1) / bq, Nkb = (N + kBK - 1) / kBK;
     const long total = (long)B * H * Nqb;
     const float c_exp = sm_scale * kLog2e;
-#define SLA_ATT(NW, KS, F8, STG) return launch_attend_t<NW, KS, F8, STG>(Q, K, Vp, sQ, sK, sV, rm, crit_idx, k_c, Hq, WT, proj_per_head, phi, H, N, Nqb, Nkb, total, c_exp, O, st)
-    if (bq == 128) { if (fp8) SLA_ATT(4, 1, true, 3); else SLA_ATT(4, 1, false, 3); }
+#define SLA_ATT(NW, KS, F8) return launch_attend_t<NW, KS, F8>(Q, K, Vp, lvs, sQ, sK, rm, crit_idx, k_c, Hq, WT, proj_per_head, phi, H, N, Nqb, Nkb, total, c_exp, O, st)
+    if (bq == 128) { if (fp8) SLA_ATT(4, 1, true); else SLA_ATT(4, 1, false); }
     // 64-row query blocks: two query groups x two key halves, so a workgroup still has four waves;
     // with very few critical blocks per row the merge of the halves costs more than it hides
-    if (k_c >= 4) { if (fp8) SLA_ATT(2, 2, true, 3); else SLA_ATT(2, 2, false, 3); }
-    if (fp8) SLA_ATT(2, 1, true, 3);
-    if (k_c <= 2) SLA_ATT(2, 1, false, 2);
-    SLA_ATT(2, 1, false, 3);
+    if (k_c >= 4) { if (fp8) SLA_ATT(2, 2, true); else SLA_ATT(2, 2, false); }
+    if (fp8) SLA_ATT(2, 1, true);
+    SLA_ATT(2, 1, false);
 #undef SLA_ATT
 }
 

@@ -7,9 +7,13 @@
 // (transposed) in its own LDS slice, every lane normalises one token row (no cross-lane work
 // for the softmax), the 64x64x64 product runs on v_mfma_f32_32x32x16_bf16, and the state leaves
 // in the layout the aggregation GEMM and the attention epilogue read.  The same pass also leaves
-// V^T of the block (bf16, key-permuted) for the attention kernel, which can then fetch both of
+// V^T of the block (fp16, key-permuted) for the attention kernel, which can then fetch both of
 // its tiles as plain 16-byte rows, and (optionally) the fp64 block mean of K for the classifier,
 // so K is read from HBM once per layer by this kernel instead of twice.
+// The fp16 copy of V is exact: bf16 values are first divided by the power of two 2^e of the block's largest
+// magnitude (so that any bf16 tensor fits the range of fp16; entries more than 2^24 below the block's maximum
+// are the only ones to lose bits), E4M3 codes are taken as they are; the attention kernel gets e, or the base-2
+// logarithm of the E4M3 block scale, in `lvs` and folds it into the exponent of its softmax weights.
 // The loads of the next block are in flight (in registers) while the current one is processed, and the
 // state and V^T tiles leave through LDS so that every store instruction writes 1 KB of whole rows:
 // the kernel is bound by HBM (16 KB in, 16.6 KB out per block for bf16 inputs).  A few workgroups past
@@ -89,6 +93,27 @@ __device__ __forceinline__ uint4 e4m3x8_to_bf16x8(uint32_t lo, uint32_t hi)
     return o;
 }
 
+// Exponent field (1..254) of the largest magnitude among the bf16 values of V a wave holds for one key block.
+__device__ __forceinline__ int block_max_exponent(const uint32_t (&v)[32])
+{
+    uint32_t mx = 0;
+#pragma unroll
+    for (int x = 0; x < 32; ++x) mx = max(mx, max(v[x] & 0x7FFFu, (v[x] >> 16) & 0x7FFFu));
+    for (int o = 32; o > 0; o >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, o, 64));
+    const int e = (int)(mx >> 7);
+    return e < 1 ? 1 : (e > 254 ? 254 : e);
+}
+
+// four bf16 (two dwords) times 2^sh -> four fp16 (two dwords), round to nearest even where bits are lost
+__device__ __forceinline__ uint2 bf16x4_to_f16x4(uint2 w, int sh)
+{
+    typedef __attribute__((ext_vector_type(2))) _Float16 h2;
+    h2 a, b;
+    a[0] = (_Float16)ldexpf(bf16_lo(w.x), sh); a[1] = (_Float16)ldexpf(bf16_hi(w.x), sh);
+    b[0] = (_Float16)ldexpf(bf16_lo(w.y), sh); b[1] = (_Float16)ldexpf(bf16_hi(w.y), sh);
+    return make_uint2(__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, b));
+}
+
 // Registers -> LDS: K rows as bf16 (e4m3 codes widened exactly, the block scale is applied later
 // in fp32), V transposed to [channel][token] bf16 (e4m3 widened exactly, unscaled).
 template <bool FP8>
@@ -151,7 +176,7 @@ template <bool FP8>
 __global__ __launch_bounds__(64 * kWavesPerWG) __attribute__((amdgpu_waves_per_eu(2, 2))) void states_kernel(const void *__restrict__ K, const void *__restrict__ V,
                                                                   const float *__restrict__ sK, const float *__restrict__ sV,
                                                                   RowMap rm, int N, int Nkb, long nblocks, int per_wave,
-                                                                  uint16_t *__restrict__ hT, uint16_t *__restrict__ Vp,
+                                                                  uint16_t *__restrict__ hT, uint16_t *__restrict__ Vp, float *__restrict__ lvs,
                                                                   double *__restrict__ kbar, int phi, unsigned state_wgs,
                                                                   const uint16_t *__restrict__ W, uint16_t *__restrict__ WT)
 {
@@ -187,6 +212,8 @@ __global__ __launch_bounds__(64 * kWavesPerWG) __attribute__((amdgpu_waves_per_e
         block_geometry(blk, tok0, valid);
         wave_lds_sync();                             // the previous block's LDS reads are done
         stage_block<FP8>(regs, Ks, Vt, lane);
+        int vexp = 127;                              // bf16: exponent field of the block's largest |V| (127 = 2^0)
+        if constexpr (!FP8) { if (Vp != nullptr) vexp = block_max_exponent(regs.v); }
         if (blk + 1 < last) {                        // next block's loads fly while this one is processed
             size_t tn; int vn;
             block_geometry(blk + 1, tn, vn);
@@ -244,16 +271,18 @@ __global__ __launch_bounds__(64 * kWavesPerWG) __attribute__((amdgpu_waves_per_e
 
         // ---- V^T tile for the attention kernel: Vp[e][.] with the 2nd and 3rd group of 4 tokens of every
         // 16 swapped (slot 16s + 8g + 4a + b holds token 16s + 8a + 4g + b), which is the key order the
-        // accumulator-as-operand trick of that kernel needs; e4m3 V leaves widened to bf16, unscaled.
+        // accumulator-as-operand trick of that kernel needs.  fp16: bf16 V divided by 2^(vexp - 127), e4m3 codes as they are.
         if (Vp != nullptr) {
             uint16_t *vt = Vp + (size_t)blk * kD * kBK;
             const int c = lane & 7, src = 16 * (c >> 1) + 4 * (c & 1);   // 16-byte piece c of a row: tokens src..src+3, src+8..src+11
 #pragma unroll
             for (int x = 0; x < 8; ++x) {                                // a wave-wide store covers 8 whole rows (1 KB)
                 const int e = 8 * x + (lane >> 3);
-                const uint2 lo = *(const uint2 *)(Vt + e * kLdsRow + src), hi = *(const uint2 *)(Vt + e * kLdsRow + src + 8);
+                const uint2 lo = bf16x4_to_f16x4(*(const uint2 *)(Vt + e * kLdsRow + src), 127 - vexp);
+                const uint2 hi = bf16x4_to_f16x4(*(const uint2 *)(Vt + e * kLdsRow + src + 8), 127 - vexp);
                 *(uint4 *)(vt + e * kBK + 8 * c) = make_uint4(lo.x, lo.y, hi.x, hi.y);
             }
+            if (lane == 0) lvs[blk] = FP8 ? __log2f(fmaxf(sV[blk], 1e-30f)) : (float)(vexp - 127);
         }
 
         // ---- z: lane d sums phi^T row d (the bf16 values the product below consumes)
@@ -311,7 +340,7 @@ __global__ __launch_bounds__(64 * kWavesPerWG) __attribute__((amdgpu_waves_per_e
 }
 
 hipError_t launch_states(const void *K, const void *V, const float *sK, const float *sV, bool fp8, RowMap rm,
-                         int BH, int N, void *hT, void *Vp, double *kbar, int phi, const void *W, int nW, void *WT, hipStream_t st)
+                         int BH, int N, void *hT, void *Vp, float *lvs, double *kbar, int phi, const void *W, int nW, void *WT, hipStream_t st)
 {
     const int Nkb = (N + kBK - 1) / kBK;
     const long nblocks = (long)BH * Nkb;
@@ -321,8 +350,8 @@ hipError_t launch_states(const void *K, const void *V, const float *sK, const fl
     const long waves = (nblocks + per_wave - 1) / per_wave;
     const unsigned grid = (unsigned)((waves + kWavesPerWG - 1) / kWavesPerWG);
     const unsigned extra = W != nullptr ? (unsigned)nW : 0u;
-    if (fp8) states_kernel<true><<<grid + extra, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, rm, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, kbar, phi, grid, (const uint16_t *)W, (uint16_t *)WT);
-    else     states_kernel<false><<<grid + extra, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, rm, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, kbar, phi, grid, (const uint16_t *)W, (uint16_t *)WT);
+    if (fp8) states_kernel<true><<<grid + extra, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, rm, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, lvs, kbar, phi, grid, (const uint16_t *)W, (uint16_t *)WT);
+    else     states_kernel<false><<<grid + extra, 64 * kWavesPerWG, 0, st>>>(K, V, sK, sV, rm, N, Nkb, nblocks, per_wave, (uint16_t *)hT, (uint16_t *)Vp, lvs, kbar, phi, grid, (const uint16_t *)W, (uint16_t *)WT);
     return hipGetLastError();
 }
 

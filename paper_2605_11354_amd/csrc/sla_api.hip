@@ -30,7 +30,7 @@ struct Plan {
     sla::RowMap rm;      // where the rows of a (b,h) live in Q, K, V, O, dO
     float sm_scale;
     bool fp8, empty;
-    size_t off_qbar, off_kbar, off_scores, off_lab, off_crit, off_hT, off_Hq, off_WT, off_Vp, off_dWpart, total;
+    size_t off_qbar, off_kbar, off_scores, off_lab, off_crit, off_hT, off_Hq, off_WT, off_Vp, off_lvs, off_dWpart, total;
 };
 
 // Validates the parameter block and derives every size used downstream.
@@ -91,6 +91,7 @@ sla_status_t make_plan(const sla_params_t *p, Plan &pl)
     pl.off_Hq = carve(BH * pl.Nqb * sla::kStateElems * 2);
     pl.off_WT = carve((size_t)pl.nW * 64 * 64 * 2);
     pl.off_Vp = carve(BH * pl.Nkb * 64 * 64 * 2);
+    pl.off_lvs = carve(BH * pl.Nkb * sizeof(float));
     pl.off_dWpart = carve(pl.empty ? 0 : BH * (size_t)sla::wproj_grad_groups(pl.BH, p->N) * 64 * 64 * sizeof(float));
     pl.total = off;
     return SLA_OK;
@@ -215,7 +216,7 @@ sla_status_t sla_linear_states(const sla_params_t *p, const void *K, const void 
     if (pl.empty) return SLA_OK;
     SLA_REQ_PTR(K); SLA_REQ_PTR(V); SLA_REQ_PTR(hT);
     if (pl.fp8) { SLA_REQ_PTR(sK); SLA_REQ_PTR(sV); }
-    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.rm, pl.BH, p->N, hT, nullptr, nullptr, p->phi, nullptr, 0, nullptr, (hipStream_t)stream));
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.rm, pl.BH, p->N, hT, nullptr, nullptr, nullptr, p->phi, nullptr, 0, nullptr, (hipStream_t)stream));
     return SLA_OK;
 }
 
@@ -255,8 +256,8 @@ sla_status_t sla_sparse_combine(const sla_params_t *p, const void *Q, const void
                                        at<uint64_t>(workspace, pl.off_lab), pl.lab_pitch, at<int32_t>(workspace, pl.off_crit), st));
     if (Hq) SLA_HIP(sla::launch_transpose_w(W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
     // the attention kernel reads V as transposed tiles; the states pass produces them (its states go to the workspace)
-    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.rm, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp), nullptr, p->phi, nullptr, 0, nullptr, st));
-    SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), sQ, sK, sV, pl.fp8, pl.rm, at<int32_t>(workspace, pl.off_crit), pl.k_c, Hq,
+    SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.rm, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp), at<float>(workspace, pl.off_lvs), nullptr, p->phi, nullptr, 0, nullptr, st));
+    SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), at<float>(workspace, pl.off_lvs), sQ, sK, pl.fp8, pl.rm, at<int32_t>(workspace, pl.off_crit), pl.k_c, Hq,
                                at<void>(workspace, pl.off_WT), p->proj_per_head, p->phi, p->B, p->H, p->N, p->bq, pl.sm_scale, O, st));
     return SLA_OK;
 }
@@ -278,10 +279,10 @@ sla_status_t sla_forward_with_labels(const sla_params_t *p, const void *Q, const
     SLA_HIP(sla::launch_labels_prepare(labels, (long)pl.BH * pl.Nqb, pl.Nkb, pl.k_c > 0 ? pl.k_c : 1,
                                        at<uint64_t>(workspace, pl.off_lab), pl.lab_pitch, at<int32_t>(workspace, pl.off_crit), st));
     SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.rm, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp),
-                               nullptr, p->phi, W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
+                               at<float>(workspace, pl.off_lvs), nullptr, p->phi, W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
     SLA_HIP(sla::launch_aggregate(at<uint64_t>(workspace, pl.off_lab), pl.lab_pitch, at<void>(workspace, pl.off_hT), pl.BH, pl.Nqb, pl.Nkb,
                                   at<void>(workspace, pl.off_Hq), st));
-    SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), sQ, sK, sV, pl.fp8, pl.rm, at<int32_t>(workspace, pl.off_crit), pl.k_c,
+    SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), at<float>(workspace, pl.off_lvs), sQ, sK, pl.fp8, pl.rm, at<int32_t>(workspace, pl.off_crit), pl.k_c,
                                at<void>(workspace, pl.off_Hq), at<void>(workspace, pl.off_WT), p->proj_per_head, p->phi, p->B, p->H,
                                p->N, p->bq, pl.sm_scale, O, st));
     return SLA_OK;
@@ -306,13 +307,13 @@ static sla_status_t forward_impl(const sla_params_t *p, const void *Q, const voi
     SLA_HIP(mark(1));     // states + V^T tiles + block means of K: the one pass over K and V besides the attention kernel;
                           // a few extra workgroups of the same launch lay out W_proj for the attention epilogue
     SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.rm, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp),
-                               at<double>(workspace, pl.off_kbar), p->phi, W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
+                               at<float>(workspace, pl.off_lvs), at<double>(workspace, pl.off_kbar), p->phi, W_proj, pl.nW, at<void>(workspace, pl.off_WT), st));
     if ((s = run_classify(p, pl, Q, K, sQ, sK, labels, nullptr, nullptr, nullptr, nullptr, nullptr, workspace, st, ev, true)) != SLA_OK) return s;
     SLA_HIP(mark(4));
     SLA_HIP(sla::launch_aggregate(at<uint64_t>(workspace, pl.off_lab), pl.lab_pitch, at<void>(workspace, pl.off_hT), pl.BH, pl.Nqb,
                                   pl.Nkb, at<void>(workspace, pl.off_Hq), st));
     SLA_HIP(mark(5));
-    SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), sQ, sK, sV, pl.fp8, pl.rm, at<int32_t>(workspace, pl.off_crit), pl.k_c,
+    SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), at<float>(workspace, pl.off_lvs), sQ, sK, pl.fp8, pl.rm, at<int32_t>(workspace, pl.off_crit), pl.k_c,
                                at<void>(workspace, pl.off_Hq), at<void>(workspace, pl.off_WT), p->proj_per_head, p->phi, p->B, p->H,
                                p->N, p->bq, pl.sm_scale, O, st));
     SLA_HIP(mark(6));

@@ -34,12 +34,14 @@ hipError_t launch_labels_prepare(const int8_t *lab_dense, long rows, int Nkb, in
                                  uint64_t *mbits, int lab_pitch, int32_t *crit_idx, hipStream_t st);
 
 // phi (here and below): feature map of the linear branch, 0 = softmax over the channels, 1 = ELU(x)+1.
-// per-key-block states: hT [BH,Nkb,65,64] bf16; optionally also Vp [BH,Nkb,64,64] bf16, the
-// transposed, key-permuted V tiles the attention kernel reads, and kbar [BH,Nkb,64] fp64, the
-// block means of K (same arithmetic as launch_pool); NULL skips either.  With W != NULL the launch also
-// does the work of launch_transpose_w(W, nW, WT) in nW extra workgroups.
+// per-key-block states: hT [BH,Nkb,65,64] bf16; optionally also Vp [BH,Nkb,64,64] fp16, the transposed,
+// key-permuted V tiles the attention kernel reads (bf16 V divided by a power of two per block, E4M3 codes
+// unscaled) with lvs [BH,Nkb] fp32, the base-2 logarithm of what one unit of Vp stands for (that power of two,
+// or the E4M3 block scale), and kbar [BH,Nkb,64] fp64, the block means of K (same arithmetic as launch_pool);
+// NULL skips Vp + lvs, or kbar.  With W != NULL the launch also does the work of launch_transpose_w(W, nW, WT)
+// in nW extra workgroups.
 hipError_t launch_states(const void *K, const void *V, const float *sK, const float *sV, bool fp8, RowMap rm,
-                         int BH, int N, void *hT, void *Vp, double *kbar, int phi, const void *W, int nW, void *WT, hipStream_t st);
+                         int BH, int N, void *hT, void *Vp, float *lvs, double *kbar, int phi, const void *W, int nW, void *WT, hipStream_t st);
 
 // Hq[bh][i][:] = sum over the key blocks j whose bit is set in row (bh,i) of mbits of hT[bh][j][:]   (bf16 MFMA, fp32 accumulate)
 hipError_t launch_aggregate(const uint64_t *mbits, int lab_pitch, const void *hT, int BH, int Nqb,
@@ -48,9 +50,9 @@ hipError_t launch_aggregate(const uint64_t *mbits, int lab_pitch, const void *hT
 // W [nW,64,64] bf16 -> WT[nW][e_out][e_in]
 hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st);
 
-// block-sparse attention over critical blocks + linear output + projection + sum
-hipError_t launch_attend(const void *Q, const void *K, const void *Vp,
-                         const float *sQ, const float *sK, const float *sV, bool fp8, RowMap rm,
+// block-sparse attention over critical blocks + linear output + projection + sum (Vp, lvs: from launch_states)
+hipError_t launch_attend(const void *Q, const void *K, const void *Vp, const float *lvs,
+                         const float *sQ, const float *sK, bool fp8, RowMap rm,
                          const int32_t *crit_idx, int k_c, const void *Hq, const void *WT,
                          int proj_per_head, int phi, int B, int H, int N, int bq, float sm_scale,
                          void *O, hipStream_t st);

@@ -256,34 +256,49 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
     float m_run = -INFINITY, l_part = 0.f, l_full = 0.f;
 
     const int32_t *ci = crit_idx + work * (long)k_c;
-    // number of leading valid entries of the critical list (a list taken from given labels may end in -1 entries)
-    int k = 0;
-    for (int base = 0; base < k_c; base += 64) {
-        const int idx = base + lane;
-        const int j = idx < k_c ? ci[idx] : -1;
-        const unsigned long long ok = __ballot(j >= 0 && j < Nkb);
-        if (ok == ~0ull) { k += 64; continue; }
-        k += __builtin_ctzll(~ok);
-        break;
-    }
-    k = __builtin_amdgcn_readfirstlane(k);
     // The list lives in registers, one entry per lane, as a window of 64 entries starting at wbase (a multiple of 32):
     // block index, log2 of its V scale and (e4m3) its exp2 constant.  The loop takes what it needs with v_readlane,
     // so no scalar load (and none of their waits) sits between the steps; the window moves every 32 tiles.
-    const float lv_ref = k > 0 ? lvh[ci[0]] : 0.f;     // log2 of the V scale of the first tile: the reference of the weights
     int wbase = 0, d_j = 0;
-    float d_lv = 0.f, d_cj = 0.f;
+    float d_lv = 0.f, d_cj = 0.f, lv_ref = 0.f;
+    // k: number of leading valid entries of the list (a list taken from given labels may end in -1 entries)
+    int k = 0;
+    {
+        const int j0 = lane < k_c ? ci[lane] : -1;      // the first window doubles as the first chunk of the count
+        unsigned long long ok = __ballot(j0 >= 0 && j0 < Nkb);
+        d_j = (j0 >= 0 && j0 < Nkb) ? j0 : 0;
+        if (ok != ~0ull) k = __builtin_ctzll(~ok);
+        else {
+            k = 64;
+            for (int base = 64; base < k_c; base += 64) {
+                const int idx = base + lane;
+                const int j = idx < k_c ? ci[idx] : -1;
+                ok = __ballot(j >= 0 && j < Nkb);
+                if (ok == ~0ull) { k += 64; continue; }
+                k += __builtin_ctzll(~ok);
+                break;
+            }
+        }
+        k = __builtin_amdgcn_readfirstlane(k);
+    }
+    // the scales of the window's blocks: a gather that depends on the indices (the first tile copies are requested
+    // between the two, see the prologue)
+    auto load_window_scales = [&](bool first) __attribute__((always_inline)) {
+        float lv = lvh[d_j];
+        // exp2 constant of the tile: softmax scale * log2(e) (* Q and K block scales for e4m3)
+        d_cj = FP8 ? fmaxf(c_exp * qscale * sK[bh * Nkb + d_j], 1e-30f) : c_exp;
+        asm volatile("" : "+v"(lv), "+v"(d_cj));       // the loads complete here, not at some later first use
+        // log2 of the V scale of the first tile: the reference of the weights
+        if (first) lv_ref = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(lv)));
+        d_lv = lv - lv_ref;
+    };
     auto load_window = [&](int wb) __attribute__((always_inline)) {
         const int idx = wb + lane;
-        const int j = idx < k ? ci[idx] : 0;
-        d_j = j;
-        d_lv = lvh[j] - lv_ref;
-        // exp2 constant of the tile: softmax scale * log2(e) (* Q and K block scales for e4m3)
-        d_cj = FP8 ? fmaxf(c_exp * qscale * sK[bh * Nkb + j], 1e-30f) : c_exp;
-        asm volatile("" : "+v"(d_j), "+v"(d_lv), "+v"(d_cj));     // the loads complete here, not at some later first use
+        d_j = idx < k ? ci[idx] : 0;
+        asm volatile("" : "+v"(d_j));
         wbase = wb;
+        load_window_scales(false);
     };
-    load_window(0);
     auto entry_j = [&](int c) { return __builtin_amdgcn_readlane(d_j, c - wbase); };
 
     CopyOffsets<NWAVES, FP8> co;
@@ -453,6 +468,7 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
     if (k > 2) request_K(2, 2 * T::KBYTES);
     if (k > 0) request_V(0, 0);
     if (k > 1) request_V(1, T::VBYTES);
+    load_window_scales(true);
     // Let the Q fragments (ordinary loads the compiler tracks) and the first tiles land here, once: left to the
     // compiler, its vmcnt(0) for Q would sit in front of their first use inside the loop and drain the ring every trip.
     __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));      // vmcnt(0), as a builtin so that the compiler's bookkeeping sees it

@@ -2,12 +2,15 @@
 """Benchmark of the SLA forward on one MI355X.
 
 A "step" is one sla_forward call (all kernels of the hot path) on one of the benchmark
-configurations, with seeded synthetic inputs already resident in HBM.  Prints ONE JSON line:
-ms per layer, dense-equivalent TFLOP/s (4*B*H*N^2*D / t), the roofline position of the
-dominant kernel (block-sparse attention, MFMA bound, algorithmic flops only) and of the
-HBM-bound kernels, and the fp64 CPU oracle timed on the host cores beside it.
+configurations, with seeded synthetic inputs already resident in HBM.  Prints ONE JSON line.
+The headline workload is configuration 2 (32 frames of global attention, bf16: the largest
+configuration at the paper's arithmetic); the same line carries, under "all_configs", the
+figures of configurations 1, 3 and 4 measured in the same run: ms per layer, the roofline
+position of the attention kernel (MFMA bound, algorithmic flops only) and of the HBM-bound
+kernels, the classifier chain, and parity against the fp64 CPU oracle.  The oracle is timed
+on the host cores beside it (cpu_baseline, on the headline workload).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--only]
 """
 from __future__ import annotations
 
@@ -22,39 +25,24 @@ sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"bf16": 2500.0, "fp8": 5000.0}     # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
+HEADLINE = 2
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=1, help="index into the benchmark configurations (default 1)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-check", action="store_true")
-    ap.add_argument("--with-grad", action="store_true", help="also time sla_wproj_grad (gradient of W_proj) after the forward")
-    ap.add_argument("--with-linear", action="store_true", help="also time sla_fp8_linear on the workload's qkv projection shape")
-    ap.add_argument("--with-quant", action="store_true", help="also time sla_quantise_e4m3 on a bf16 tensor of the workload's shape")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards over batch x heads with no "
-              "communication; no multi-GPU figure is produced). Use --gpus 1.", file=sys.stderr)
-        return 2
+def sample_blocks(BH: int, Nqb: int, n: int, rng):
+    """Query blocks for the oracle comparison: spread over all heads, always with the first and the last
+    block of the first and the last head (offset errors show at the ends)."""
+    sel = {(0, 0), (0, Nqb - 1), (BH - 1, 0), (BH - 1, Nqb - 1)}
+    if BH * Nqb <= n:
+        return sorted((bh, i) for bh in range(BH) for i in range(Nqb))
+    per = max(1, n // BH)
+    for bh in range(BH):
+        for i in rng.choice(Nqb, min(per, Nqb), replace=False):
+            sel.add((bh, int(i)))
+    return sorted(sel)
 
-    import numpy as np
-    import torch
-    from paper_2605_11354_amd import binding as B
-    from paper_2605_11354_amd import build as libbuild
-    from paper_2605_11354_amd import synth
 
-    if not os.path.exists(B.LIB_PATH):
-        libbuild.build()
-    B.lib()
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; the SLA forward has no CPU path", file=sys.stderr)
-        return 2
-
-    cfg = synth.CONFIGS[args.config]
+def measure(B, synth, orc, np, torch, index: int, steps: int, warmup: int, check: bool, cpu_baseline: bool, n_sample: int):
+    cfg = synth.CONFIGS[index]
     t0 = time.time()
     d = synth.make_inputs(cfg)
     gen_s = time.time() - t0
@@ -77,29 +65,25 @@ def main() -> int:
     def step():
         B.sla_forward(p, Q, K, V, W, O, labels, sQ, sK, sV, ws)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
 
-    # per-kernel durations: HIP events around every kernel on the launch stream, same K steps
+    # per-kernel durations: HIP events around every kernel on the launch stream, same number of steps
     stage = {}
-    for _ in range(args.steps):
+    for _ in range(steps):
         for k, v in B.sla_forward_profiled(p, Q, K, V, W, O, labels, sQ, sK, sV, ws).items():
-            stage[k] = stage.get(k, 0.0) + v / args.steps
+            stage[k] = stage.get(k, 0.0) + v / steps
 
     BH, N, D = cfg.B * cfg.H, cfg.N, 64
     dense_flops = 4.0 * BH * N * N * D
     elem = 1 if fp8 else 2
     qkv_bytes = BH * N * D * elem
-    bytes_pool_q = qkv_bytes + BH * Nqb * D * 8
-    # states pass: reads K and V once; writes the block states (65x64 bf16), the V^T tiles (64x64 bf16)
-    # and the fp64 block means of K (its launch also lays out W_proj for the epilogue: 8 KB per matrix)
-
     # algorithmic flops of the critical-block attention: 4*D per (valid query row, valid critical key)
     lab_host = labels.cpu().numpy()
     tail = cfg.N - (Nkb - 1) * cfg.bk
@@ -114,18 +98,22 @@ def main() -> int:
                 "frac": round(gbs / PEAK_HBM_GBS, 4)}
 
     attend_tflops = attend_flops / stage["attend"] / 1e9 if stage["attend"] > 0 else 0.0
-    traffic = None     # HBM bytes per launch of the attention kernel, from the committed FETCH_SIZE / WRITE_SIZE summary
+    # HBM bytes per launch of the attention kernel: not measured in this run (counters need rocprofv3); the figure is
+    # the one in the committed FETCH_SIZE / WRITE_SIZE summary of this workload, named in traffic_source
+    traffic, traffic_source = None, None
     tfile = os.path.join(ROOT, "profiles", f"{cfg.name}_hbm_counters.txt")
     if os.path.exists(tfile):
         for line in open(tfile):
             if line.startswith("attend_kernel HBM bytes per launch:"):
-                traffic = int(line.split(":")[1])
+                traffic, traffic_source = int(line.split(":")[1]), f"profiles/{cfg.name}_hbm_counters.txt (rocprofv3 --pmc, an earlier run of this command)"
     roofline = {"kernel": "attend (block-sparse attention over critical blocks + fused linear/proj epilogue)",
                 "bound": "mfma", "achieved": round(attend_tflops, 2), "peak": PEAK_TFLOPS[cfg.dtype], "unit": "TFLOP/s",
-                "frac": round(attend_tflops / PEAK_TFLOPS[cfg.dtype], 4), "traffic": traffic,
+                "frac": round(attend_tflops / PEAK_TFLOPS[cfg.dtype], 4), "traffic": traffic, "traffic_source": traffic_source,
                 "algorithmic_flops": attend_flops, "ms": round(stage["attend"], 5)}
     short_rows = Nkb <= 256      # the library's short-row path: Q means, logits and classifier in one launch
-    bytes_states = 2 * qkv_bytes + BH * Nkb * (65 * D * 2 + D * D * 2 + D * 8)
+    # states pass: reads K and V once; writes the block states (65x64 bf16), the V^T tiles (64x64 fp16), the fp64 block
+    # means of K and one fp32 scale exponent per block (its launch also lays out W_proj for the epilogue)
+    bytes_states = 2 * qkv_bytes + BH * Nkb * (65 * D * 2 + D * D * 2 + D * 8 + 4)
     kernels = {"states": hbm("states", bytes_states)}
     cls_flops = 2.0 * BH * Nqb * Nkb * D
 
@@ -136,41 +124,151 @@ def main() -> int:
     if short_rows:
         # Q means + logits + classification in one launch: reads Q once and the K means once per query block
         kernels["classify_fused"] = dict(fp64("scores"), algorithmic_bytes=int(qkv_bytes + BH * Nqb * Nkb * (D * 8 + 1)))
+        chain_ms = stage["scores"]
     else:
-        kernels["pool_q"] = hbm("pool_q", bytes_pool_q)
+        kernels["pool_q"] = hbm("pool_q", qkv_bytes + BH * Nqb * D * 8)
         kernels["scores"] = fp64("scores")
         kernels["select"] = {"ms": round(stage["select"], 5)}
+        chain_ms = stage["pool_q"] + stage["scores"] + stage["select"]
     agg_flops = 2.0 * BH * Nqb * Nkb * 65 * D
     kernels["aggregate"] = {"ms": round(stage["aggregate"], 5), "bound": "mfma",
                             "achieved_TFLOPs": round(agg_flops / stage["aggregate"] / 1e9, 2),
                             "frac": round(agg_flops / stage["aggregate"] / 1e9 / PEAK_TFLOPS["bf16"], 4)}
 
-    out = {
-        "metric": "SLA forward dense-equivalent TFLOP/s (ms/layer = ms_per_step; % MFMA peak = roofline.frac)",
-        "value": round(dense_flops / ms_per_step / 1e9, 2), "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if not fp8 else "fp8_e4m3", "data": "synthetic",
+    res = {
+        "workload": cfg.name, "dtype": "bf16" if not fp8 else "fp8_e4m3", "steps": steps, "warmup": warmup,
+        "ms_per_step": round(ms_per_step, 5), "dense_equiv_TFLOPs": round(dense_flops / ms_per_step / 1e9, 2),
         "config": {"workload": cfg.name, "B": cfg.B, "H": cfg.H, "N": cfg.N, "D": 64, "bq": cfg.bq, "bk": cfg.bk,
                    "k_crit": k_c, "k_neg": k_n, "k_marg": Nkb - k_c - k_n, "input_gen_s": round(gen_s, 1)},
-        "roofline": roofline, "kernels": kernels,
+        "roofline": roofline, "kernels": kernels, "classifier_chain_ms": round(chain_ms, 5),
         "sum_kernel_ms": round(stage["attend"] + sum(k["ms"] for k in kernels.values()), 5),
     }
+
+    if check or cpu_baseline:
+        po = orc.make_params(cfg.B, cfg.H, cfg.N, cfg.bq, cfg.bk, k_c, k_n, cfg.dtype, cfg.proj_per_head)
+        rng = np.random.default_rng(0)
+        t0 = time.perf_counter()
+        oc = orc.classify(po, d["Q"], d["K"], d["sQ"], d["sK"])
+        t_classify = time.perf_counter() - t0
+        sel = sample_blocks(BH, Nqb, n_sample, rng)
+        t0 = time.perf_counter()
+        oa = orc.attend(po, d["Q"], d["K"], d["V"], d["W"], oc["labels"], sel, d["sQ"], d["sK"], d["sV"])
+        t_attend = time.perf_counter() - t0
+        frac = len(sel) / float(BH * Nqb)
+        t_full_est = t_classify + t_attend / frac
+        if cpu_baseline:
+            res["cpu_baseline"] = {"value": round(dense_flops / t_full_est / 1e12, 4), "unit": "TFLOP/s",
+                                   "cores": orc.threads(), "kind": "oracle",
+                                   "ms_per_layer_extrapolated": round(t_full_est * 1e3, 1),
+                                   "sample": f"classifier on the full workload ({t_classify:.2f} s) + attention/linear/combine on "
+                                             f"{len(sel)} of {BH * Nqb} query blocks spread over all heads ({t_attend:.2f} s), scaled by 1/{frac:.4f}"}
+        if check:
+            Oh = O.float().cpu().numpy().astype(np.float64)
+            got = np.zeros_like(oa["O"])
+            for s, (bh, i) in enumerate(sel):
+                rows = min(N, (i + 1) * cfg.bq) - i * cfg.bq
+                got[s, :rows] = Oh[bh // cfg.H, bh % cfg.H, i * cfg.bq:i * cfg.bq + rows]
+            rms = float(np.sqrt(np.mean(oa["O"] ** 2)))
+            diff = np.abs(got - oa["O"])
+            ax = np.abs(oa["O"])
+            half_ulp = np.where(ax > 0, 2.0 ** (np.floor(np.log2(np.where(ax > 0, ax, 1.0))) - 8), 0.0)   # of the bf16 output format
+            bar = 6e-2 if fp8 else 2e-2
+            strict, arith = float(diff.max() / rms), float(np.maximum(diff - half_ulp, 0.0).max() / rms)
+            res["parity"] = {"label_mismatches": int((lab_host != oc["labels"]).sum()),
+                             "max_abs_over_rms_sampled": round(strict, 5),
+                             "beyond_bf16_store_over_rms": round(arith, 5),
+                             "bar": bar, "strict_pass": bool(strict <= bar), "arith_pass": bool(arith <= bar),
+                             "note": "strict = max|O - oracle| / RMS, including the rounding of the result to the bf16 output format "
+                                     "(up to 2^-8 |O|, above the bar on heavy-tailed rows for any bf16 output); arith = the same with "
+                                     "half a bf16 unit in the last place of the oracle value taken off",
+                             "sampled_query_blocks": len(sel)}
+    del Q, K, V, O, W, labels, ws
+    torch.cuda.empty_cache()
+    return res, (cfg, p)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=HEADLINE, help="headline workload: index into the benchmark configurations (default 2)")
+    ap.add_argument("--only", action="store_true", help="measure the headline workload only (no all_configs)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--with-grad", action="store_true", help="also time sla_wproj_grad (gradient of W_proj) after the forward")
+    ap.add_argument("--with-linear", action="store_true", help="also time sla_fp8_linear on the workload's qkv projection shape")
+    ap.add_argument("--with-quant", action="store_true", help="also time sla_quantise_e4m3 on a bf16 tensor of the workload's shape")
+    ap.add_argument("--alternate", action="store_true", help="also time frame attention followed by global attention on the same "
+                                                             "token-major activations (the alternation of the backbone)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards over batch x heads with no "
+              "communication; no multi-GPU figure is produced). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2605_11354_amd import binding as B
+    from paper_2605_11354_amd import build as libbuild
+    from paper_2605_11354_amd import synth
+
+    if not os.path.exists(B.LIB_PATH):
+        libbuild.build()
+    B.lib()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the SLA forward has no CPU path", file=sys.stderr)
+        return 2
+    check, cpu_b = not args.no_check, not args.no_cpu_baseline
+    orc = None
+    if check or cpu_b:
+        from oracle import sla_oracle as orc
+
+    head, (cfg, p) = measure(B, synth, orc, np, torch, args.config, args.steps, args.warmup, check, cpu_b, 1024)
+    out = {
+        "metric": "SLA forward dense-equivalent TFLOP/s (ms/layer = ms_per_step; % MFMA peak = roofline.frac)",
+        "value": head["dense_equiv_TFLOPs"], "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": head["dtype"], "data": "synthetic", "config": head["config"],
+        "roofline": head["roofline"], "kernels": head["kernels"], "classifier_chain_ms": head["classifier_chain_ms"],
+        "sum_kernel_ms": head["sum_kernel_ms"],
+    }
+    for k in ("cpu_baseline", "parity"):
+        if k in head:
+            out[k] = head[k]
+
+    BH, N, D = cfg.B * cfg.H, cfg.N, 64
+    fp8 = cfg.dtype == "fp8"
+    Nqb, Nkb = -(-cfg.N // cfg.bq), -(-cfg.N // cfg.bk)
+    qkv_bytes = BH * N * D * (1 if fp8 else 2)
+    if args.with_grad or args.with_quant or args.with_linear:
+        d = synth.make_inputs(cfg)
+        up16 = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        up = (lambda a: torch.from_numpy(a).cuda()) if fp8 else up16
+        Q, K, V, W = up(d["Q"]), up(d["K"]), up(d["V"]), up16(d["W"])
+        sQ, sK, sV = ((torch.from_numpy(d[k]).cuda() for k in ("sQ", "sK", "sV")) if fp8 else (None, None, None))
+        O = torch.empty((cfg.B, cfg.H, cfg.N, 64), dtype=torch.bfloat16, device="cuda")
+        ws = B.alloc_workspace(p)
+        B.sla_forward(p, Q, K, V, W, O, None, sQ, sK, sV, ws)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
 
     if args.with_grad:
         # gradient of the projection: reads Q, dO and the aggregated states once
         nW = cfg.H if cfg.proj_per_head else 1
         dO = torch.randn((cfg.B, cfg.H, cfg.N, 64), device="cuda").to(torch.bfloat16)
         dW = torch.empty((nW, 64, 64), dtype=torch.float32, device="cuda")
-        for _ in range(args.warmup):
-            B.sla_wproj_grad(p, Q, dO, dW, ws, sQ)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(args.steps):
-            B.sla_wproj_grad(p, Q, dO, dW, ws, sQ)
-        e1.record()
-        torch.cuda.synchronize()
-        gms = e0.elapsed_time(e1) / args.steps
+        gms = timed(lambda: B.sla_wproj_grad(p, Q, dO, dW, ws, sQ))
         gbytes = qkv_bytes + BH * N * D * 2 + BH * Nqb * 65 * D * 2 + nW * D * D * 4
         out["wproj_grad"] = {"ms": round(gms, 5), "bound": "hbm", "algorithmic_bytes": int(gbytes),
                              "achieved_GBs": round(gbytes / gms / 1e6, 1), "frac": round(gbytes / gms / 1e6 / PEAK_HBM_GBS, 4),
@@ -181,15 +279,7 @@ def main() -> int:
         xq = torch.randn((cfg.B, cfg.H, cfg.N, 64), device="cuda").to(torch.bfloat16)
         cq = torch.empty((cfg.B, cfg.H, cfg.N, 64), dtype=torch.uint8, device="cuda")
         sq_ = torch.empty((cfg.B, cfg.H, Nkb), dtype=torch.float32, device="cuda")
-        for _ in range(args.warmup):
-            B.sla_quantise_e4m3(xq, cfg.bk, cq, sq_)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(args.steps):
-            B.sla_quantise_e4m3(xq, cfg.bk, cq, sq_)
-        e1.record()
-        torch.cuda.synchronize()
-        qms = e0.elapsed_time(e1) / args.steps
+        qms = timed(lambda: B.sla_quantise_e4m3(xq, cfg.bk, cq, sq_))
         qbytes = BH * N * D * 3 + BH * Nkb * 4
         out["quantise_e4m3"] = {"ms": round(qms, 5), "bound": "hbm", "algorithmic_bytes": int(qbytes),
                                 "achieved_GBs": round(qbytes / qms / 1e6, 1), "frac": round(qbytes / qms / 1e6 / PEAK_HBM_GBS, 4)}
@@ -202,62 +292,55 @@ def main() -> int:
         Wl = (torch.randn((d_out, d_in), device="cuda") / d_in ** 0.5).to(torch.bfloat16)
         bl = torch.randn((d_out,), device="cuda").to(torch.bfloat16)
         yl = torch.empty((tokens, d_out), dtype=torch.bfloat16, device="cuda")
-        for _ in range(args.warmup):
-            B.sla_fp8_linear(xl, Wl, bl, yl)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(args.steps):
-            B.sla_fp8_linear(xl, Wl, bl, yl)
-        e1.record()
-        torch.cuda.synchronize()
-        lms = e0.elapsed_time(e1) / args.steps
+        lms = timed(lambda: B.sla_fp8_linear(xl, Wl, bl, yl))
         lflops = 2.0 * tokens * d_in * d_out
         out["fp8_linear"] = {"ms": round(lms, 5), "shape": [tokens, d_in, d_out], "bound": "mfma", "algorithmic_flops": lflops,
                              "achieved_TFLOPs": round(lflops / lms / 1e9, 1), "frac": round(lflops / lms / 1e9 / PEAK_TFLOPS["fp8"], 4),
                              "note": "three launches: token quantiser, weight quantiser, E4M3 GEMM with the scales and bias in its epilogue"}
 
-    if not args.no_check or not args.no_cpu_baseline:
-        from oracle import sla_oracle as orc
-        po = orc.make_params(cfg.B, cfg.H, cfg.N, cfg.bq, cfg.bk, k_c, k_n, cfg.dtype, cfg.proj_per_head)
-        rng = np.random.default_rng(0)
-        t0 = time.perf_counter()
-        oc = orc.classify(po, d["Q"], d["K"], d["sQ"], d["sK"])
-        t_classify = time.perf_counter() - t0
-        # bounded sample of query blocks for the attention part: whole heads, so the per-head
-        # state computation is amortised the way the full workload amortises it
-        heads = [0] if BH * Nqb > 4096 else list(range(BH))
-        per_head = Nqb if len(heads) > 1 else min(Nqb, 128)
-        sel = [(bh, int(i)) for bh in heads for i in (range(Nqb) if per_head == Nqb else sorted(rng.choice(Nqb, per_head, replace=False)))]
-        t0 = time.perf_counter()
-        oa = orc.attend(po, d["Q"], d["K"], d["V"], d["W"], oc["labels"], sel, d["sQ"], d["sK"], d["sV"])
-        t_attend = time.perf_counter() - t0
-        frac = len(sel) / float(BH * Nqb)
-        t_full_est = t_classify + t_attend / frac
-        if not args.no_cpu_baseline:
-          out["cpu_baseline"] = {"value": round(dense_flops / t_full_est / 1e12, 4), "unit": "TFLOP/s",
-                               "cores": orc.threads(), "kind": "oracle",
-                               "ms_per_layer_extrapolated": round(t_full_est * 1e3, 1),
-                               "sample": f"classifier on the full workload ({t_classify:.2f} s) + attention/linear/combine on "
-                                         f"{len(sel)} of {BH * Nqb} query blocks ({t_attend:.2f} s), scaled by 1/{frac:.4f}"}
-        if not args.no_check:
-            Oh = O.float().cpu().numpy().astype(np.float64)
-            got = np.zeros_like(oa["O"])
-            for s, (bh, i) in enumerate(sel):
-                rows = min(N, (i + 1) * cfg.bq) - i * cfg.bq
-                got[s, :rows] = Oh[bh // cfg.H, bh % cfg.H, i * cfg.bq:i * cfg.bq + rows]
-            rms = float(np.sqrt(np.mean(oa["O"] ** 2)))
-            diff = np.abs(got - oa["O"])
-            ax = np.abs(oa["O"])
-            half_ulp = np.where(ax > 0, 2.0 ** (np.floor(np.log2(np.where(ax > 0, ax, 1.0))) - 8), 0.0)   # of the bf16 output format
-            out["parity"] = {"label_mismatches": int((lab_host != oc["labels"]).sum()),
-                             "max_abs_over_rms_sampled": round(float(diff.max() / rms), 5),
-                             "beyond_bf16_store_over_rms": round(float(np.maximum(diff - half_ulp, 0.0).max() / rms), 5),
-                             "bar": 6e-2 if fp8 else 2e-2,
-                             "note": "the first figure includes the rounding of the exact result to the bf16 output format "
-                                     "(up to 2^-8 |O| on heavy-tailed rows); the tests assert the second",
-                             "sampled_query_blocks": len(sel)}
+    if args.alternate:
+        out["alternate"] = alternate_leg(B, synth, np, torch, timed)
+
+    if not args.only:
+        out["all_configs"] = {}
+        for idx in (1, 3, 4):
+            if idx == args.config:
+                continue
+            r, _ = measure(B, synth, orc, np, torch, idx, max(10, args.steps // 2), args.warmup, check, False, 512)
+            out["all_configs"][r["workload"]] = {
+                "dtype": r["dtype"], "ms_per_step": r["ms_per_step"], "dense_equiv_TFLOPs": r["dense_equiv_TFLOPs"],
+                "attend_ms": r["roofline"]["ms"], "attend_frac_of_mfma_peak": r["roofline"]["frac"], "attend_peak_TFLOPs": r["roofline"]["peak"],
+                "attend_traffic": r["roofline"]["traffic"], "attend_traffic_source": r["roofline"]["traffic_source"],
+                "states_ms": r["kernels"]["states"]["ms"], "states_frac_of_hbm_peak": r["kernels"]["states"]["frac"],
+                "classifier_chain_ms": r["classifier_chain_ms"], "aggregate_ms": r["kernels"]["aggregate"]["ms"],
+                "steps": r["steps"], "parity": r.get("parity")}
     print(json.dumps(out))
     return 0
+
+
+def alternate_leg(B, synth, np, torch, timed):
+    """Frame attention then global attention on the same [S, 1374, H, 64] activations (section 3.3: SLA replaces both
+    kinds of layer of the backbone): B = S frames of 1374 tokens, then B = 1 with S x 1374 tokens, one stream, one workspace."""
+    c1, c3 = synth.CONFIGS[1], synth.CONFIGS[3]
+    S, Nf, H = 8, 1374, c1.H
+    d = synth.make_inputs(c1)                                   # [1, H, S*Nf, 64] head-major -> token-major
+    tm = lambda a: torch.from_numpy(np.ascontiguousarray(a.transpose(0, 2, 1, 3)).view(np.int16)).cuda().view(torch.bfloat16)
+    Q, K, V = tm(d["Q"]), tm(d["K"]), tm(d["V"])               # [1, S*Nf, H, 64] == [S, Nf, H, 64]
+    W = torch.from_numpy(d["W"].view(np.int16)).cuda().view(torch.bfloat16)
+    pg = B.make_params(1, H, S * Nf, c1.bq, c1.bk, c1.crit_frac, c1.neg_frac, -1, -1, "bf16", True, layout="bnhd")
+    pf = B.make_params(S, H, Nf, c3.bq, c3.bk, c3.crit_frac, c3.neg_frac, -1, -1, "bf16", True, layout="bnhd")
+    ws = torch.empty(max(B.sla_workspace_bytes(pg), B.sla_workspace_bytes(pf)), dtype=torch.uint8, device="cuda")
+    Of, Og = torch.empty_like(Q), torch.empty_like(Q)
+
+    def pair():
+        B.sla_forward(pf, Q, K, V, W, Of, None, None, None, None, ws)
+        B.sla_forward(pg, Q, K, V, W, Og, None, None, None, None, ws)
+
+    ms = timed(pair)
+    msf = timed(lambda: B.sla_forward(pf, Q, K, V, W, Of, None, None, None, None, ws))
+    return {"frames": S, "tokens_per_frame": Nf, "layout": "[B,N,H,D]", "pair_ms": round(ms, 5), "frame_layer_ms": round(msf, 5),
+            "global_layer_ms": round(ms - msf, 5),
+            "note": "frame attention (B = frames) then global attention (B = 1) on the same buffers, one stream, one workspace"}
 
 
 if __name__ == "__main__":

@@ -99,6 +99,24 @@ sla_status_t sla_forward(const sla_params_t *p,
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * sla_forward for callers that cannot allocate device memory or pass a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same kernels and the same results as sla_forward, with
+ * the workspace taken from a device array of SLA_STATIC_WORKSPACE_BYTES bytes that is part of the library (one copy
+ * per GPU, held until the process ends).  Arguments as sla_forward without the workspace.  The call allocates
+ * nothing and issues only kernel launches; on the first call on a device it looks up that device's copy of the array
+ * (hipGetSymbolAddress) with the device current.  Shapes whose sla_workspace_bytes exceeds the array are rejected
+ * with SLA_ERR_WORKSPACE before any launch.  Every call on a GPU uses that GPU's one array: calls that overlap on the
+ * same GPU (different streams or threads) race; the array keeps the previous call's contents, and nothing in it has
+ * to start at zero (every part is written before it is read).  sla_wproj_grad cannot follow this call (it needs the
+ * caller's workspace).
+ */
+#define SLA_STATIC_WORKSPACE_BYTES (96u * 1024u * 1024u)
+sla_status_t sla_forward_static(const sla_params_t *p,
+                                const void *Q, const void *K, const void *V,
+                                const float *sQ, const float *sK, const float *sV,
+                                const void *W_proj, void *O, int8_t *labels, void *stream);
+
+/*
  * The forward with the block labels given instead of computed: steps 2-4 on the labels of an earlier call
  * (e.g. the masks of one layer reused by the next, whose Q and K differ little).  Arguments as sla_forward, except
  *   labels   in   int8 [B,H,Nqb,Nkb], 2 critical / 1 marginal / 0 negligible.  A row may hold any number of marginal

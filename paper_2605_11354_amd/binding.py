@@ -20,8 +20,9 @@ SLA_BF16, SLA_FP8_E4M3 = 0, 1
 STATE_ROWS = 65          # rows of one block state: 64 rows of h^T and one row of z
 EXPORTS = ["sla_resolve_counts", "sla_workspace_bytes", "sla_forward", "sla_pool_classify", "sla_linear_states",
            "sla_marginal_aggregate", "sla_sparse_combine", "sla_forward_profiled", "sla_wproj_grad", "sla_quantise_e4m3",
-           "sla_forward_with_labels", "sla_fp8_linear_workspace_bytes", "sla_fp8_linear",
+           "sla_forward_with_labels", "sla_fp8_linear_workspace_bytes", "sla_fp8_linear", "sla_forward_static",
            "sla_strerror", "sla_last_error", "sla_stage_name"]
+STATIC_WORKSPACE_BYTES = 96 * 1024 * 1024
 NUM_STAGES = 6
 
 
@@ -56,7 +57,7 @@ def lib() -> C.CDLL:
         _lib.sla_strerror.restype = C.c_char_p
         _lib.sla_last_error.restype = C.c_char_p
         _lib.sla_stage_name.restype = C.c_char_p
-        for name in EXPORTS[:13]:
+        for name in EXPORTS[:14]:
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -105,6 +106,13 @@ def sla_forward(p, Q, K, V, W_proj, O, labels=None, sQ=None, sK=None, sV=None, w
     ws = workspace if workspace is not None else alloc_workspace(p, Q.device)
     _check(lib().sla_forward(C.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(sQ), _ptr(sK), _ptr(sV), _ptr(W_proj),
                              _ptr(O), _ptr(labels), _ptr(ws), C.c_size_t(ws.numel()), _stream()), "sla_forward")
+    return O
+
+
+def sla_forward_static(p, Q, K, V, W_proj, O, labels=None, sQ=None, sK=None, sV=None):
+    """sla_forward on the library's own workspace (no allocation; shapes up to STATIC_WORKSPACE_BYTES of workspace)."""
+    _check(lib().sla_forward_static(C.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(sQ), _ptr(sK), _ptr(sV), _ptr(W_proj),
+                                    _ptr(O), _ptr(labels), _stream()), "sla_forward_static")
     return O
 
 

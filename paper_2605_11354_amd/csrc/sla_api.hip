@@ -8,6 +8,11 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+
+// Workspace of sla_forward_static: device memory that belongs to the library, one copy per GPU, held from the moment
+// the code object is loaded until the process ends.  In host code the name is only a handle for hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char g_static_workspace[SLA_STATIC_WORKSPACE_BYTES];
 
 namespace {
 
@@ -325,6 +330,36 @@ sla_status_t sla_forward(const sla_params_t *p, const void *Q, const void *K, co
                          void *workspace, size_t workspace_bytes, void *stream)
 {
     return forward_impl(p, Q, K, V, sQ, sK, sV, W_proj, O, labels, workspace, workspace_bytes, stream, nullptr, nullptr);
+}
+
+sla_status_t sla_forward_static(const sla_params_t *p, const void *Q, const void *K, const void *V, const float *sQ,
+                                const float *sK, const float *sV, const void *W_proj, void *O, int8_t *labels, void *stream)
+{
+    Plan pl;
+    sla_status_t s = make_plan(p, pl);
+    if (s != SLA_OK) return s;
+    if (pl.total > (size_t)SLA_STATIC_WORKSPACE_BYTES)
+        return fail(SLA_ERR_WORKSPACE, "this shape needs %zu bytes of workspace; sla_forward_static holds %zu (use sla_forward with a caller workspace)",
+                    pl.total, (size_t)SLA_STATIC_WORKSPACE_BYTES);
+    // address of the current device's copy of the array, looked up once per device
+    constexpr int kMaxDevices = 64;
+    static void *ptrs[kMaxDevices] = {};
+    static std::mutex mtx;
+    int dev = -1;
+    SLA_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(SLA_ERR_UNSUPPORTED, "device ordinal %d out of range", dev);
+    void *ws = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(mtx);
+        if (!ptrs[dev]) {
+            void *ptr = nullptr;
+            SLA_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_static_workspace)));
+            if (!ptr) return fail(SLA_ERR_HIP, "hipGetSymbolAddress returned a null address");
+            ptrs[dev] = ptr;
+        }
+        ws = ptrs[dev];
+    }
+    return forward_impl(p, Q, K, V, sQ, sK, sV, W_proj, O, labels, ws, (size_t)SLA_STATIC_WORKSPACE_BYTES, stream, nullptr, nullptr);
 }
 
 sla_status_t sla_wproj_grad(const sla_params_t *p, const void *Q, const float *sQ, const void *dO, float *dW,

@@ -242,6 +242,18 @@ sla_status_t sla_sparse_combine(const sla_params_t *p,
                                 const void *W_proj, const int8_t *labels, const void *Hq, void *O,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * sla_sparse_combine with the result left in fp32: O32 [B,H,N,D] (same layout switch) receives the values the bf16
+ * store of sla_sparse_combine rounds (round to nearest even), from the same kernel and the same arithmetic.  For tests
+ * and diagnosis: it separates the error of the kernel's arithmetic from the rounding of the output format, which on
+ * heavy-tailed rows (|O| far above the tensor's RMS) is by itself larger than the tolerance stated relative to the RMS.
+ */
+sla_status_t sla_sparse_combine_f32(const sla_params_t *p,
+                                    const void *Q, const void *K, const void *V,
+                                    const float *sQ, const float *sK, const float *sV,
+                                    const void *W_proj, const int8_t *labels, const void *Hq, float *O32,
+                                    void *workspace, size_t workspace_bytes, void *stream);
+
 const char *sla_strerror(sla_status_t status);
 const char *sla_last_error(void);
 

@@ -20,7 +20,7 @@ SLA_BF16, SLA_FP8_E4M3 = 0, 1
 STATE_ROWS = 65          # rows of one block state: 64 rows of h^T and one row of z
 EXPORTS = ["sla_resolve_counts", "sla_workspace_bytes", "sla_forward", "sla_pool_classify", "sla_linear_states",
            "sla_marginal_aggregate", "sla_sparse_combine", "sla_forward_profiled", "sla_wproj_grad", "sla_quantise_e4m3",
-           "sla_forward_with_labels", "sla_fp8_linear_workspace_bytes", "sla_fp8_linear", "sla_forward_static",
+           "sla_forward_with_labels", "sla_fp8_linear_workspace_bytes", "sla_fp8_linear", "sla_forward_static", "sla_sparse_combine_f32",
            "sla_strerror", "sla_last_error", "sla_stage_name"]
 STATIC_WORKSPACE_BYTES = 96 * 1024 * 1024
 NUM_STAGES = 6
@@ -57,7 +57,7 @@ def lib() -> C.CDLL:
         _lib.sla_strerror.restype = C.c_char_p
         _lib.sla_last_error.restype = C.c_char_p
         _lib.sla_stage_name.restype = C.c_char_p
-        for name in EXPORTS[:14]:
+        for name in EXPORTS[:15]:
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -195,3 +195,12 @@ def sla_sparse_combine(p, Q, K, V, W_proj, labels, Hq, O, sQ=None, sK=None, sV=N
                                     _ptr(labels), _ptr(Hq), _ptr(O), _ptr(ws), C.c_size_t(ws.numel()), _stream()),
            "sla_sparse_combine")
     return O
+
+
+def sla_sparse_combine_f32(p, Q, K, V, W_proj, labels, Hq, O32, sQ=None, sK=None, sV=None, workspace=None):
+    """sla_sparse_combine with the result in fp32 (O32: float32 tensor of the shape of O)."""
+    ws = workspace if workspace is not None else alloc_workspace(p, Q.device)
+    _check(lib().sla_sparse_combine_f32(C.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(sQ), _ptr(sK), _ptr(sV), _ptr(W_proj),
+                                        _ptr(labels), _ptr(Hq), _ptr(O32), _ptr(ws), C.c_size_t(ws.numel()), _stream()),
+           "sla_sparse_combine_f32")
+    return O32

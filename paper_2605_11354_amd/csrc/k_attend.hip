@@ -190,7 +190,7 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
     const void *__restrict__ Qp, const void *__restrict__ Kp, const uint16_t *__restrict__ Vp, const float *__restrict__ lvs,
     const float *__restrict__ sQ, const float *__restrict__ sK, RowMap rm,
     const int32_t *__restrict__ crit_idx, int k_c, const uint16_t *__restrict__ Hq, const uint16_t *__restrict__ WT,
-    int proj_per_head, int phi, int H, int N, int Nqb, int Nkb, long total, float c_exp, uint16_t *__restrict__ O)
+    int proj_per_head, int phi, int H, int N, int Nqb, int Nkb, long total, float c_exp, uint16_t *__restrict__ O, float *__restrict__ O32)
 {
     constexpr int NWAVES = NW * KS;
     using T = Tile<NWAVES, FP8>;
@@ -774,7 +774,17 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
     // is transposed through a private 4 KB LDS slice (8-byte pieces, XOR-swizzled by row) so that it
     // leaves as full 128-byte rows, 16 bytes per lane.
     wait_copies_and_barrier<0>();                      // all waves are done reading the epilogue operands
-    if (kh == 0) {
+    if (O32 != nullptr) {
+        // diagnostic output: the fp32 values the bf16 store below would round, straight from the accumulators
+        if (kh == 0 && qok) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+#pragma unroll
+                for (int aa = 0; aa < 4; ++aa)
+                    *(float4 *)(O32 + head + (size_t)q * rm.ts + 32 * e + 8 * aa + 4 * g) =
+                        make_float4(oacc[e][4 * aa + 0], oacc[e][4 * aa + 1], oacc[e][4 * aa + 2], oacc[e][4 * aa + 3]);
+        }
+    } else if (kh == 0) {
         uint8_t *ot = lds + T::VRING + wq * 4096;
         const int f = ((l32 >> 1) & 7) << 1;
 #pragma unroll
@@ -814,11 +824,11 @@ hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st)
 template <int NW, int KS, bool FP8>
 static hipError_t launch_attend_t(const void *Q, const void *K, const void *Vp, const float *lvs, const float *sQ, const float *sK, RowMap rm,
                                   const int32_t *crit_idx, int k_c, const void *Hq, const void *WT, int proj_per_head, int phi,
-                                  int H, int N, int Nqb, int Nkb, long total, float c_exp, void *O, hipStream_t st)
+                                  int H, int N, int Nqb, int Nkb, long total, float c_exp, void *O, float *O32, hipStream_t st)
 {
     attend_kernel<NW, KS, FP8><<<(unsigned)xcd_grid(total), 64 * NW * KS, 0, st>>>(Q, K, (const uint16_t *)Vp, lvs, sQ, sK, rm, crit_idx, k_c, (const uint16_t *)Hq,
                                                                      (const uint16_t *)WT, proj_per_head, phi, H, N, Nqb, Nkb,
-                                                                     total, c_exp, (uint16_t *)O);
+                                                                     total, c_exp, (uint16_t *)O, O32);
     return hipGetLastError();
 }
 
@@ -826,12 +836,12 @@ hipError_t launch_attend(const void *Q, const void *K, const void *Vp, const flo
                          const float *sQ, const float *sK, bool fp8, RowMap rm,
                          const int32_t *crit_idx, int k_c, const void *Hq, const void *WT,
                          int proj_per_head, int phi, int B, int H, int N, int bq, float sm_scale,
-                         void *O, hipStream_t st)
+                         void *O, float *O32, hipStream_t st)
 {
     const int Nqb = (N + bq - 1) / bq, Nkb = (N + kBK - 1) / kBK;
     const long total = (long)B * H * Nqb;
     const float c_exp = sm_scale * kLog2e;
-#define SLA_ATT(NW, KS, F8) return launch_attend_t<NW, KS, F8>(Q, K, Vp, lvs, sQ, sK, rm, crit_idx, k_c, Hq, WT, proj_per_head, phi, H, N, Nqb, Nkb, total, c_exp, O, st)
+#define SLA_ATT(NW, KS, F8) return launch_attend_t<NW, KS, F8>(Q, K, Vp, lvs, sQ, sK, rm, crit_idx, k_c, Hq, WT, proj_per_head, phi, H, N, Nqb, Nkb, total, c_exp, O, O32, st)
     if (bq == 128) { if (fp8) SLA_ATT(4, 1, true); else SLA_ATT(4, 1, false); }
     // 64-row query blocks: two query groups x two key halves, so a workgroup still has four waves;
     // with very few critical blocks per row the merge of the halves costs more than it hides

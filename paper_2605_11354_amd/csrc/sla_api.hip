@@ -242,15 +242,16 @@ sla_status_t sla_marginal_aggregate(const sla_params_t *p, const int8_t *labels,
     return SLA_OK;
 }
 
-sla_status_t sla_sparse_combine(const sla_params_t *p, const void *Q, const void *K, const void *V, const float *sQ,
-                                const float *sK, const float *sV, const void *W_proj, const int8_t *labels, const void *Hq,
-                                void *O, void *workspace, size_t workspace_bytes, void *stream)
+static sla_status_t sparse_combine_impl(const sla_params_t *p, const void *Q, const void *K, const void *V, const float *sQ,
+                                        const float *sK, const float *sV, const void *W_proj, const int8_t *labels, const void *Hq,
+                                        void *O, float *O32, void *workspace, size_t workspace_bytes, void *stream)
 {
     Plan pl;
     sla_status_t s = make_plan(p, pl);
     if (s != SLA_OK) return s;
     if (pl.empty) return SLA_OK;
-    SLA_REQ_PTR(Q); SLA_REQ_PTR(K); SLA_REQ_PTR(V); SLA_REQ_PTR(O);
+    SLA_REQ_PTR(Q); SLA_REQ_PTR(K); SLA_REQ_PTR(V);
+    if (O32) SLA_REQ_PTR(O32); else SLA_REQ_PTR(O);
     if (!labels) return fail(SLA_ERR_INVALID_ARG, "labels is NULL");
     if (pl.fp8) { SLA_REQ_PTR(sQ); SLA_REQ_PTR(sK); SLA_REQ_PTR(sV); }
     SLA_OPT_PTR(Hq);
@@ -263,8 +264,23 @@ sla_status_t sla_sparse_combine(const sla_params_t *p, const void *Q, const void
     // the attention kernel reads V as transposed tiles; the states pass produces them (its states go to the workspace)
     SLA_HIP(sla::launch_states(K, V, sK, sV, pl.fp8, pl.rm, pl.BH, p->N, at<void>(workspace, pl.off_hT), at<void>(workspace, pl.off_Vp), at<float>(workspace, pl.off_lvs), nullptr, p->phi, nullptr, 0, nullptr, st));
     SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), at<float>(workspace, pl.off_lvs), sQ, sK, pl.fp8, pl.rm, at<int32_t>(workspace, pl.off_crit), pl.k_c, Hq,
-                               at<void>(workspace, pl.off_WT), p->proj_per_head, p->phi, p->B, p->H, p->N, p->bq, pl.sm_scale, O, st));
+                               at<void>(workspace, pl.off_WT), p->proj_per_head, p->phi, p->B, p->H, p->N, p->bq, pl.sm_scale, O, O32, st));
     return SLA_OK;
+}
+
+sla_status_t sla_sparse_combine(const sla_params_t *p, const void *Q, const void *K, const void *V, const float *sQ,
+                                const float *sK, const float *sV, const void *W_proj, const int8_t *labels, const void *Hq,
+                                void *O, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return sparse_combine_impl(p, Q, K, V, sQ, sK, sV, W_proj, labels, Hq, O, nullptr, workspace, workspace_bytes, stream);
+}
+
+sla_status_t sla_sparse_combine_f32(const sla_params_t *p, const void *Q, const void *K, const void *V, const float *sQ,
+                                    const float *sK, const float *sV, const void *W_proj, const int8_t *labels, const void *Hq,
+                                    float *O32, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!O32) return fail(SLA_ERR_INVALID_ARG, "O32 is NULL");
+    return sparse_combine_impl(p, Q, K, V, sQ, sK, sV, W_proj, labels, Hq, nullptr, O32, workspace, workspace_bytes, stream);
 }
 
 sla_status_t sla_forward_with_labels(const sla_params_t *p, const void *Q, const void *K, const void *V, const float *sQ,
@@ -289,7 +305,7 @@ sla_status_t sla_forward_with_labels(const sla_params_t *p, const void *Q, const
                                   at<void>(workspace, pl.off_Hq), st));
     SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), at<float>(workspace, pl.off_lvs), sQ, sK, pl.fp8, pl.rm, at<int32_t>(workspace, pl.off_crit), pl.k_c,
                                at<void>(workspace, pl.off_Hq), at<void>(workspace, pl.off_WT), p->proj_per_head, p->phi, p->B, p->H,
-                               p->N, p->bq, pl.sm_scale, O, st));
+                               p->N, p->bq, pl.sm_scale, O, nullptr, st));
     return SLA_OK;
 }
 
@@ -320,7 +336,7 @@ static sla_status_t forward_impl(const sla_params_t *p, const void *Q, const voi
     SLA_HIP(mark(5));
     SLA_HIP(sla::launch_attend(Q, K, at<void>(workspace, pl.off_Vp), at<float>(workspace, pl.off_lvs), sQ, sK, pl.fp8, pl.rm, at<int32_t>(workspace, pl.off_crit), pl.k_c,
                                at<void>(workspace, pl.off_Hq), at<void>(workspace, pl.off_WT), p->proj_per_head, p->phi, p->B, p->H,
-                               p->N, p->bq, pl.sm_scale, O, st));
+                               p->N, p->bq, pl.sm_scale, O, nullptr, st));
     SLA_HIP(mark(6));
     return SLA_OK;
 }

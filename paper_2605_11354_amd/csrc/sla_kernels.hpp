@@ -50,12 +50,13 @@ hipError_t launch_aggregate(const uint64_t *mbits, int lab_pitch, const void *hT
 // W [nW,64,64] bf16 -> WT[nW][e_out][e_in]
 hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st);
 
-// block-sparse attention over critical blocks + linear output + projection + sum (Vp, lvs: from launch_states)
+// block-sparse attention over critical blocks + linear output + projection + sum (Vp, lvs: from launch_states).
+// O32 != NULL: the result is written there as fp32 (the values before the bf16 rounding) and O is not touched.
 hipError_t launch_attend(const void *Q, const void *K, const void *Vp, const float *lvs,
                          const float *sQ, const float *sK, bool fp8, RowMap rm,
                          const int32_t *crit_idx, int k_c, const void *Hq, const void *WT,
                          int proj_per_head, int phi, int B, int H, int N, int bq, float sm_scale,
-                         void *O, hipStream_t st);
+                         void *O, float *O32, hipStream_t st);
 
 // dW[w] = sum over the (b,h) that use projection matrix w and their tokens of O_lin^T dO, O_lin recomputed from Q and
 // the aggregated states Hq; part is scratch of wproj_grad_groups(BH, N) * BH * 64 * 64 floats

@@ -1,7 +1,12 @@
 """GPU parity: the HIP path (through the C ABI) against the fp64 oracle on the same seeded inputs.
 
-Bars: block labels, critical index lists, block means and pooled logits bit-exact; outputs
-within max-abs <= 2e-2 * RMS(oracle output) for bf16 inputs and 6e-2 for fp8 inputs.
+Bars: block labels, critical index lists, block means and pooled logits bit-exact.  Outputs: the
+stated bar is max-abs <= 2e-2 * RMS(oracle output) for bf16 inputs and 6e-2 for fp8 inputs; it is
+asserted as stated on the kernel's fp32 result (test_gpu_parity_more.py), together with "the bf16
+output is that result rounded to nearest even".  The comparisons of bf16 outputs in this file take
+half a bf16 unit in the last place of the oracle value off each element's error first
+(gpu_util.assert_output): rounding the exact result to bf16 alone exceeds the stated bar on
+heavy-tailed rows (|O| up to 40 x RMS), whatever computes it.  Both figures are printed.
 Intermediate bf16 tensors (block states, aggregated states) are compared with a tolerance
 of a few bf16 ulps of their largest entry (they are rounded once to bf16 on the device).
 """
@@ -304,8 +309,8 @@ def test_v_ones_closed_form_on_device():
 @pytest.mark.parametrize("name", ["c1_small", "c3_small", "c2_small"])
 def test_forward_back_to_back_and_profiled_variant(name):
     """Calls queued on one stream without host waits, sharing one workspace, must not disturb each
-    other (short rows fork onto the library's helper stream), and the measurement variant, which
-    runs the same kernels serially, must give the same bytes."""
+    other, and the measurement variant, which brackets the same kernels with events, must give the
+    same bytes."""
     from paper_2605_11354_amd import binding as B
     a = _case(name)
     d2 = dict(a.d)
@@ -522,18 +527,13 @@ def test_errors_are_reported_not_launched():
 # evaluate one by one (all of them for configuration 1, a seeded sample elsewhere that always
 # contains the first and the ragged last query block of some head).
 def _sample_blocks(case, n, seed=0):
-    rng = np.random.default_rng(seed)
-    BH = case.cfg.B * case.cfg.H
-    heads = sorted(rng.choice(BH, size=min(BH, max(3, 2 * n // case.Nqb + 1)), replace=False).tolist())
-    n = min(n, len(heads) * case.Nqb)
-    sel = {(heads[0], 0), (heads[0], case.Nqb - 1), (heads[-1], case.Nqb - 1)}
-    while len(sel) < n:
-        sel.add((int(rng.choice(heads)), int(rng.integers(case.Nqb))))
-    return sorted(sel)
+    """n query blocks spread over all heads, with both ends of the first and the last head."""
+    from bench import sample_blocks
+    return sample_blocks(case.cfg.B * case.cfg.H, case.Nqb, n, np.random.default_rng(seed))
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("idx,nsample", [(1, None), (2, 48), (3, 96), (4, 24)])
+@pytest.mark.parametrize("idx,nsample", [(1, None), (2, 256), (3, 1024), (4, 256)])
 def test_full_size_configuration(oracle, idx, nsample):
     cfg = synth.CONFIGS[idx]
     case = G.Case(cfg)

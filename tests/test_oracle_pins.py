@@ -43,6 +43,25 @@ def test_all_critical_equals_dense_attention(oracle, N, bq, bk):
         assert np.abs(r["O_lin"][0, h]).max() == 0.0     # linear branch contributes exactly 0
 
 
+@pytest.mark.parametrize("scale", [0.25, 0.03, 1.0])
+def test_softmax_scale_other_than_the_default_reaches_the_sparse_branch(oracle, scale):
+    """sm_scale != 1/sqrt(D): all blocks critical must equal dense softmax attention at THAT scale (section 3.3 fixes
+    only the default), and a general label pattern the token-level masked form at that scale."""
+    rng = np.random.default_rng(8)
+    Q, K, V, W = _small(rng, N=300)
+    p = oracle.make_params(1, 2, 300, 128, 64, 5, 0, proj_per_head=True, sm_scale=scale)
+    r = oracle.forward(p, Q, K, V, W)
+    for h in range(2):
+        ref = bf.dense_attention(*(bf.bf16_bits_to_f64(x[0, h]) for x in (Q, K, V)), scale)
+        np.testing.assert_allclose(r["O"][0, h], ref, rtol=0, atol=1e-12)
+    p = oracle.make_params(1, 2, 300, 64, 64, 2, 1, proj_per_head=True, sm_scale=scale)
+    r = oracle.forward(p, Q, K, V, W)
+    for h in range(2):
+        ref, _, _ = bf.sla_tokenlevel(*(bf.bf16_bits_to_f64(x[0, h]) for x in (Q, K, V)), bf.bf16_bits_to_f64(W[h]),
+                                      r["labels"][0, h], 64, 64, scale)
+        np.testing.assert_allclose(r["O"][0, h], ref, rtol=0, atol=1e-11)
+
+
 def test_all_critical_on_config0(oracle):
     cfg = synth.CONFIGS[0]
     d = synth.make_inputs(cfg)

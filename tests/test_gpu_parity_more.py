@@ -259,3 +259,42 @@ def test_full_size_outputs_over_all_heads_and_the_value_hull(oracle, idx):
     lo, hi = Vf.amin(dim=2, keepdim=True), Vf.amax(dim=2, keepdim=True)
     slack = 2.0 ** -7 * torch.maximum(lo.abs(), hi.abs())          # the bf16 store of a value at the edge
     assert bool(((Osp >= lo - slack) & (Osp <= hi + slack)).all())
+
+
+def test_frame_then_global_attention_on_the_same_activations(oracle):
+    """Section 3.3: SLA replaces both the frame attention and the global attention of the backbone.  The same
+    token-major activations [S, 1374, H, 64] are consumed as B = S frames of 1374 tokens (frame attention) and then as
+    B = 1 with S x 1374 tokens (global attention), back to back on one stream with one workspace; both results are
+    checked against the oracle evaluated on the corresponding head-major views."""
+    S, Nf, H = 3, 1374, 2
+    cg = C1.with_(H=H, N=S * Nf)                                  # global view: [1, H, S*Nf, 64]
+    cf = C3.with_(B=S, H=H, N=Nf)                                 # frame view:  [S, H, Nf, 64]
+    d = synth.make_inputs(cg)
+    tm = lambda a: np.ascontiguousarray(a.transpose(0, 2, 1, 3))  # head-major -> token-major
+    Q, K, V = (G.dev_bf16(tm(d[k])) for k in ("Q", "K", "V"))     # [1, S*Nf, H, 64] == [S, Nf, H, 64] in memory
+    W = G.dev_bf16(d["W"])
+    pg = B.make_params(1, H, S * Nf, cg.bq, cg.bk, cg.crit_frac, cg.neg_frac, -1, -1, "bf16", True, layout="bnhd")
+    pf = B.make_params(S, H, Nf, cf.bq, cf.bk, cf.crit_frac, cf.neg_frac, -1, -1, "bf16", True, layout="bnhd")
+    ws = torch.empty(max(B.sla_workspace_bytes(pg), B.sla_workspace_bytes(pf)), dtype=torch.uint8, device="cuda")
+    Of, Og = torch.empty_like(Q), torch.empty_like(Q)
+    labf = torch.empty((S, H, -(-Nf // cf.bq), -(-Nf // cf.bk)), dtype=torch.int8, device="cuda")
+    labg = torch.empty((1, H, -(-S * Nf // cg.bq), -(-S * Nf // cg.bk)), dtype=torch.int8, device="cuda")
+    for _ in range(2):                                            # twice: the second pair runs on a used workspace
+        B.sla_forward(pf, Q, K, V, W, Of, labf, None, None, None, ws)
+        B.sla_forward(pg, Q, K, V, W, Og, labg, None, None, None, ws)
+    torch.cuda.synchronize()
+    # global view against the oracle
+    kc, kn = B.sla_resolve_counts(pg)
+    po = oracle.make_params(1, H, S * Nf, cg.bq, cg.bk, kc, kn, "bf16", True)
+    r = oracle.forward(po, d["Q"], d["K"], d["V"], d["W"])
+    assert np.array_equal(labg.cpu().numpy(), r["labels"])
+    got = G.bf16_tensor_to_f64(Og).reshape(1, S * Nf, H, 64).transpose(0, 2, 1, 3)
+    G.assert_output(got, r["O"], "bf16", "global attention on token-major activations")
+    # frame view: frame s is tokens s*Nf .. (s+1)*Nf of every head
+    fv = lambda a: np.ascontiguousarray(a[0].reshape(H, S, Nf, 64).transpose(1, 0, 2, 3))
+    kc, kn = B.sla_resolve_counts(pf)
+    po = oracle.make_params(S, H, Nf, cf.bq, cf.bk, kc, kn, "bf16", True)
+    r = oracle.forward(po, fv(d["Q"]), fv(d["K"]), fv(d["V"]), d["W"])
+    assert np.array_equal(labf.cpu().numpy(), r["labels"])
+    got = G.bf16_tensor_to_f64(Of).reshape(S, Nf, H, 64).transpose(0, 2, 1, 3)
+    G.assert_output(got, r["O"], "bf16", "frame attention on the same activations")

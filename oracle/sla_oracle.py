@@ -223,3 +223,49 @@ def fp8_linear(x_bits, W_bits, bias_bits=None):
     if bias_bits is not None:
         y = y + (np.asarray(bias_bits, np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)[None, :]
     return y
+
+
+def alg1_token_level(Q, K, V, W_O, lam: float, sm_scale=None, phi: str = "elu1"):
+    """Alg. 1 exactly as the paper prints it, for one head, in fp64 (quadratic in N: small inputs only).
+
+    Token-level selection and a linear branch over ALL keys, where the block-level module above selects key blocks per
+    query block and restricts the linear branch to the marginal blocks.  Steps, in the algorithm's notation
+    (step 1, the frozen projections, is outside: Q, K, V are given):
+      2  S = Q K^T / sqrt(d)                        (sm_scale overrides 1/sqrt(d))
+      3  M = TopKMask(S, lambda): per query row the ceil(lambda N) largest scores are kept; equal scores are ordered
+         by key index, lowest first (the tie rule of the block-level classifier).  lambda = 0 keeps nothing.
+      4  A_sparse = Softmax(S (.) M): dropped entries are excluded from the softmax (a 0/1 product would leave
+         exp(0) of mass on them); a row that keeps nothing gives 0
+      5  O_sparse = A_sparse V
+      6  phi(Q), phi(K): ELU(x) + 1 elementwise (phi="softmax": the channel softmax of the benchmark configurations)
+      7  T = phi(K)^T V
+      8  z = phi(K)^T 1_N
+      9  O_lin = (phi(Q) T) ./ (phi(Q) z)
+      10 O = O_sparse + O_lin W_O
+    Q, K, V: float64 [N, d]; W_O: float64 [d, d].  Returns dict(O, O_sparse, O_lin, M) with M the boolean mask [N, N]."""
+    Q, K, V, W_O = (np.asarray(x, dtype=np.float64) for x in (Q, K, V, W_O))
+    N, d = Q.shape
+    scale = (1.0 / np.sqrt(d)) if sm_scale is None else float(sm_scale)
+    S = (Q @ K.T) * scale                                                   # step 2
+    keep = int(np.ceil(lam * N - 1e-12)) if lam > 0 else 0
+    keep = min(max(keep, 0), N)
+    M = np.zeros((N, N), dtype=bool)                                        # step 3
+    if keep > 0:
+        order = np.argsort(-S, axis=1, kind="stable")                       # score descending, equal scores by key index
+        np.put_along_axis(M, order[:, :keep], True, axis=1)
+    O_sparse = np.zeros((N, V.shape[1]))
+    if keep > 0:                                                            # steps 4-5
+        Sm = np.where(M, S, -np.inf)
+        E = np.where(M, np.exp(Sm - Sm.max(axis=1, keepdims=True)), 0.0)
+        O_sparse = (E / E.sum(axis=1, keepdims=True)) @ V
+    if phi == "elu1":                                                       # step 6
+        f = lambda X: np.where(X > 0, X + 1.0, np.exp(np.minimum(X, 0.0)))
+    else:
+        def f(X):
+            Ex = np.exp(X - X.max(axis=-1, keepdims=True))
+            return Ex / Ex.sum(axis=-1, keepdims=True)
+    fQ, fK = f(Q), f(K)
+    T = fK.T @ V                                                            # step 7
+    z = fK.T @ np.ones(N)                                                   # step 8
+    O_lin = (fQ @ T) / (fQ @ z)[:, None]                                    # step 9
+    return {"O": O_sparse + O_lin @ W_O, "O_sparse": O_sparse, "O_lin": O_lin, "M": M}    # step 10

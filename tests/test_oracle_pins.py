@@ -448,3 +448,62 @@ def test_fp8_linear_matches_torch_fake_quant(oracle):
     assert np.array_equal(c1, c2) and s2[5] == s1[5] * 8 and np.array_equal(np.delete(s1, 5), np.delete(s2, 5))
     y2 = oracle.fp8_linear(synth.to_bf16_bits(x2), Wb, None)
     np.testing.assert_allclose(y2[5], 8.0 * (y[5] - (bb.astype(np.uint32) << 16).view(np.float32)), rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------------------------ Alg. 1 as printed (token-level mask, global linear branch)
+def _alg1_inputs(N, seed=4):
+    rng = np.random.default_rng(seed)
+    f = lambda s: bf.bf16_bits_to_f64(synth.to_bf16_bits(rng.standard_normal((N, 64)) * s))
+    return f(1.0), f(1.0), f(1.0), bf.bf16_bits_to_f64(synth.to_bf16_bits(rng.standard_normal((64, 64)) / 8.0))
+
+
+@pytest.mark.parametrize("phi", ["elu1", "softmax"])
+def test_alg1_with_keep_ratio_one_is_dense_plus_global_linear_attention(oracle, phi):
+    """lambda = 1 keeps every key: O = Softmax(Q K^T / sqrt(d)) V + LinearAttention(Q, K, V) W_O, both textbook operators."""
+    Q, K, V, W = _alg1_inputs(150)
+    r = oracle.alg1_token_level(Q, K, V, W, 1.0, phi=phi)
+    assert r["M"].all()
+    np.testing.assert_allclose(r["O_sparse"], bf.dense_attention(Q, K, V, 0.125), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(r["O"], bf.dense_attention(Q, K, V, 0.125) + bf.linear_attention(Q, K, V, W, phi), rtol=0, atol=1e-12)
+
+
+def test_alg1_mask_on_a_hand_built_score_order(oracle):
+    """Scores with a known order: Q = one-hot rows, K = columns of a table, so S = table / 8 entry for entry.  The mask
+    keeps ceil(lambda N) keys per row, the largest first, equal scores by lowest key index; the sparse output is then the
+    softmax-weighted mean of the kept V rows, and the linear branch does not depend on lambda."""
+    N = 8
+    table = np.array([[7, 6, 5, 4, 3, 2, 1, 0],            # descending: keeps 0, 1, 2
+                      [0, 1, 2, 3, 4, 5, 6, 7],            # ascending: keeps 7, 6, 5
+                      [5, 5, 5, 5, 5, 5, 5, 5],            # all tied: keeps 0, 1, 2
+                      [1, 9, 1, 9, 1, 9, 1, 9],            # ties at the top: 1, 3, 5
+                      [2, 0, 2, 0, 2, 0, 2, 0],            # ties at the threshold: 0, 2, 4
+                      [0, 0, 0, 8, 0, 0, 0, 0],            # one peak, then ties by index: 3, 0, 1
+                      [-1, -2, -3, -4, -5, -6, -7, -8],    # negative scores: 0, 1, 2
+                      [3, 1, 4, 1, 5, 9, 2, 6]], float)    # 5, 7, 4
+    Q = np.zeros((N, 64)); Q[np.arange(N), np.arange(N)] = 1.0
+    K = np.zeros((N, 64)); K[:, :N] = table.T
+    rng = np.random.default_rng(6)
+    V = rng.standard_normal((N, 64)); W = rng.standard_normal((64, 64)) / 8.0
+    r = oracle.alg1_token_level(Q, K, V, W, 3.0 / 8.0)
+    want = [[0, 1, 2], [7, 6, 5], [0, 1, 2], [1, 3, 5], [0, 2, 4], [3, 0, 1], [0, 1, 2], [5, 7, 4]]
+    for i in range(N):
+        assert sorted(np.nonzero(r["M"][i])[0].tolist()) == sorted(want[i]), i
+        w = np.exp(table[i, want[i]] / 8.0); w /= w.sum()
+        np.testing.assert_allclose(r["O_sparse"][i], w @ V[want[i]], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(r["O_lin"] @ W, bf.linear_attention(Q, K, V, W, "elu1"), rtol=0, atol=1e-12)
+    assert oracle.alg1_token_level(Q, K, V, W, 0.3)["M"].sum(axis=1).tolist() == [3] * N      # ceil(0.3 * 8) = 3
+    r0 = oracle.alg1_token_level(Q, K, V, W, 0.0)
+    assert not r0["M"].any() and np.abs(r0["O_sparse"]).max() == 0.0
+
+
+def test_alg1_agrees_with_the_block_level_module_at_its_two_limits(oracle):
+    """Where the two granularities coincide: everything kept (lambda = 1 / all blocks critical) and nothing kept
+    (lambda = 0 / all blocks marginal): the block-level oracle and Alg. 1 as printed give the same output."""
+    rng = np.random.default_rng(9)
+    Qb, Kb, Vb, Wb = _small(rng, N=200, per_head=False)
+    Q, K, V, W = (bf.bf16_bits_to_f64(x) for x in (Qb[0, 0], Kb[0, 0], Vb[0, 0], Wb))
+    p = oracle.make_params(1, 2, 200, 64, 64, 4, 0, phi="elu1")
+    np.testing.assert_allclose(oracle.forward(p, Qb, Kb, Vb, Wb, want_parts=True)["O_sparse"][0, 0],
+                               oracle.alg1_token_level(Q, K, V, W, 1.0)["O_sparse"], rtol=0, atol=1e-12)
+    p = oracle.make_params(1, 2, 200, 64, 64, 0, 0, phi="elu1")
+    np.testing.assert_allclose(oracle.forward(p, Qb, Kb, Vb, Wb)["O"][0, 0], oracle.alg1_token_level(Q, K, V, W, 0.0)["O"], rtol=0, atol=1e-12)

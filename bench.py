@@ -297,6 +297,23 @@ def main() -> int:
         out["fp8_linear"] = {"ms": round(lms, 5), "shape": [tokens, d_in, d_out], "bound": "mfma", "algorithmic_flops": lflops,
                              "achieved_TFLOPs": round(lflops / lms / 1e9, 1), "frac": round(lflops / lms / 1e9 / PEAK_TFLOPS["fp8"], 4),
                              "note": "three launches: token quantiser, weight quantiser, E4M3 GEMM with the scales and bias in its epilogue"}
+        # the same layer with the attention's E4M3 block quantiser in the GEMM's epilogue, against layer + 3 quantiser calls
+        if cfg.B == 1 or cfg.N % 256 == 0:                    # a token block may not straddle a GEMM tile
+            c8 = [torch.empty((cfg.B, cfg.N, cfg.H, 64), dtype=torch.uint8, device="cuda") for _ in range(3)]
+            s8 = [torch.empty((cfg.B, cfg.H, nb), dtype=torch.float32, device="cuda") for nb in (Nqb, Nkb, Nkb)]
+            fms = timed(lambda: B.sla_fp8_linear_qkv(xl, Wl, bl, cfg.B, cfg.N, cfg.H, cfg.bq, c8[0], c8[1], c8[2], s8[0], s8[1], s8[2]))
+            y5 = yl.view(cfg.B, cfg.N, 3, cfg.H, 64)
+            parts = [y5[:, :, w].contiguous() for w in range(3)]
+
+            def unfused():
+                B.sla_fp8_linear(xl, Wl, bl, yl)
+                for w, blk in enumerate((cfg.bq, cfg.bk, cfg.bk)):
+                    B.sla_quantise_e4m3(parts[w], blk, c8[w], s8[w], layout="bnhd")
+            ums = timed(unfused)
+            out["fp8_linear_qkv"] = {"ms": round(fms, 5), "unfused_ms": round(ums, 5), "bound": "mfma",
+                                     "achieved_TFLOPs": round(lflops / fms / 1e9, 1), "frac": round(lflops / fms / 1e9 / PEAK_TFLOPS["fp8"], 4),
+                                     "note": "unfused_ms = sla_fp8_linear + three sla_quantise_e4m3 calls on contiguous slices "
+                                             "(the slicing copies themselves are not timed)"}
 
     if args.alternate:
         out["alternate"] = alternate_leg(B, synth, np, torch, timed)

@@ -178,6 +178,25 @@ sla_status_t sla_fp8_linear(const void *x, const void *W, const void *bias, int3
                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * sla_fp8_linear as the qkv projection in front of the attention, with the per-block E4M3 quantiser in the epilogue of
+ * the GEMM (Alg. 2; App. B.2-B.4): the layer's output y [B*N, 3*H*64] (channels ordered [q|k|v][head][64]) is never
+ * written; instead each (head, token block) of it is quantised as sla_quantise_e4m3 would (blk = bq for Q, 64 for K and
+ * V) and the call leaves Q, K and V in the form sla_forward takes with dtype = SLA_FP8_E4M3 and layout = SLA_LAYOUT_BNHD.
+ * Bit for bit the result of sla_fp8_linear followed by sla_quantise_e4m3 on the three slices of y.
+ *   x           in   bf16 [B*N, d_in]           d_in a multiple of 128
+ *   W           in   bf16 [3*H*64, d_in]
+ *   bias        in   bf16 [3*H*64] or NULL
+ *   Q8, K8, V8  out  uint8 E4M3 codes [B,N,H,64]
+ *   sQ          out  fp32 [B,H,ceil(N/bq)];   sK, sV  out  fp32 [B,H,ceil(N/64)]
+ *   workspace   sla_fp8_linear_workspace_bytes(B*N, d_in, 3*H*64) bytes, 256-byte aligned
+ * With B > 1, N must be a multiple of the GEMM's token tile (256, or 128 for small problems): a token block may not
+ * straddle a tile; otherwise SLA_ERR_UNSUPPORTED.
+ */
+sla_status_t sla_fp8_linear_qkv(const void *x, const void *W, const void *bias, int32_t B, int32_t N, int32_t H, int32_t d_in,
+                                int32_t bq, void *Q8, void *K8, void *V8, float *sQ, float *sK, float *sV,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Measurement variant of sla_forward: identical kernels and results, but every kernel is
  * bracketed by HIP events on `stream`; the call then WAITS for the stream and writes the
  * duration of each kernel in milliseconds to stage_ms[SLA_NUM_STAGES] (host memory).

@@ -20,7 +20,7 @@ SLA_BF16, SLA_FP8_E4M3 = 0, 1
 STATE_ROWS = 65          # rows of one block state: 64 rows of h^T and one row of z
 EXPORTS = ["sla_resolve_counts", "sla_workspace_bytes", "sla_forward", "sla_pool_classify", "sla_linear_states",
            "sla_marginal_aggregate", "sla_sparse_combine", "sla_forward_profiled", "sla_wproj_grad", "sla_quantise_e4m3",
-           "sla_forward_with_labels", "sla_fp8_linear_workspace_bytes", "sla_fp8_linear", "sla_forward_static", "sla_sparse_combine_f32",
+           "sla_forward_with_labels", "sla_fp8_linear_workspace_bytes", "sla_fp8_linear", "sla_forward_static", "sla_sparse_combine_f32", "sla_fp8_linear_qkv",
            "sla_strerror", "sla_last_error", "sla_stage_name"]
 STATIC_WORKSPACE_BYTES = 96 * 1024 * 1024
 NUM_STAGES = 6
@@ -57,7 +57,7 @@ def lib() -> C.CDLL:
         _lib.sla_strerror.restype = C.c_char_p
         _lib.sla_last_error.restype = C.c_char_p
         _lib.sla_stage_name.restype = C.c_char_p
-        for name in EXPORTS[:15]:
+        for name in EXPORTS[:16]:
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -204,3 +204,17 @@ def sla_sparse_combine_f32(p, Q, K, V, W_proj, labels, Hq, O32, sQ=None, sK=None
                                         _ptr(labels), _ptr(Hq), _ptr(O32), _ptr(ws), C.c_size_t(ws.numel()), _stream()),
            "sla_sparse_combine_f32")
     return O32
+
+
+def sla_fp8_linear_qkv(x, W, bias, B_, N, H, bq, Q8, K8, V8, sQ, sK, sV, workspace=None):
+    """qkv projection with the per-block E4M3 quantiser in the GEMM's epilogue: x [B*N, d_in], W [3*H*64, d_in]."""
+    import torch
+    d_in = x.shape[1]
+    if workspace is None:
+        n = C.c_size_t()
+        _check(lib().sla_fp8_linear_workspace_bytes(C.c_int32(B_ * N), C.c_int32(d_in), C.c_int32(3 * H * 64), C.byref(n)),
+               "sla_fp8_linear_workspace_bytes")
+        workspace = torch.empty(max(256, n.value), dtype=torch.uint8, device=x.device)
+    _check(lib().sla_fp8_linear_qkv(_ptr(x), _ptr(W), _ptr(bias), C.c_int32(B_), C.c_int32(N), C.c_int32(H), C.c_int32(d_in),
+                                    C.c_int32(bq), _ptr(Q8), _ptr(K8), _ptr(V8), _ptr(sQ), _ptr(sK), _ptr(sV),
+                                    _ptr(workspace), C.c_size_t(workspace.numel()), _stream()), "sla_fp8_linear_qkv")

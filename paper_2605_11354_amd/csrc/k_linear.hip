@@ -56,7 +56,6 @@ __global__ __launch_bounds__(256) void quantise_rows_kernel(const uint16_t *__re
 
 namespace {
 constexpr int kLinK = 128;                           // bytes (= E4M3 elements) of K per step
-constexpr int kLinTile = 128 * kLinK;                // bytes of one operand tile in LDS
 constexpr int kLinOutRow = 128 + 8;                  // bf16 per row of the output staging tile
 __device__ __forceinline__ int lin_swz(int row) { return (row >> 1) & 7; }
 }  // namespace
@@ -66,11 +65,25 @@ __device__ __forceinline__ int lin_swz(int row) { return (row >> 1) & 7; }
 // step).  TB = 4: tile 256 tokens x 128 channels for large token counts -- a wave's 64 x 128 tile needs six operand
 // reads per eight MFMAs instead of four per four, which takes the LDS read rate off the critical path; one LDS buffer
 // (two barriers per K step) so that two workgroups still share a CU.
-template <int TB>
+//
+// QKV: the layer is the qkv projection in front of the attention (O = 3 H 64 output channels ordered [q|k|v][head][64])
+// and the epilogue, instead of storing y, quantises it per (head, token block) with the scaled E4M3 quantiser of
+// App. B.2 -- the form sla_forward takes E4M3 inputs in -- and stores codes [B,N,H,64] and scales [B,H,blocks] of Q, K
+// and V directly: the bf16 tile staged in LDS is the y the unfused layer would have written, a wavefront takes one
+// (token block, head) of it at a time (absolute maximum by a wave reduction, then divide / clamp / convert: the
+// arithmetic of quantise_e4m3_kernel), so the result is bit for bit that of sla_fp8_linear followed by
+// sla_quantise_e4m3, without y's round trip through HBM.  Token blocks never straddle a tile (the host checks).
+struct QkvOut {
+    uint8_t *codes[3];          // Q, K, V codes, [B,N,H,64]
+    float *scales[3];           // [B,H,ceil(N/blk)], blk = bq for Q, 64 for K and V
+    int N, H, bq;
+};
+
+template <int TB, bool QKV>
 __global__ __launch_bounds__(256) void fp8_gemm_kernel(const uint8_t *__restrict__ A8, const float *__restrict__ sa,
                                                        const uint8_t *__restrict__ W8, const float *__restrict__ sw,
                                                        const uint16_t *__restrict__ bias, int M, int O, int K, int n_it,
-                                                       long total, uint16_t *__restrict__ Y)
+                                                       long total, uint16_t *__restrict__ Y, QkvOut qkv)
 {
     constexpr int kTok = 64 * TB;                                                // tokens per workgroup tile
     constexpr int kBufs = TB == 2 ? 2 : 1;
@@ -212,11 +225,55 @@ __global__ __launch_bounds__(256) void fp8_gemm_kernel(const uint8_t *__restrict
             }
     }
     __syncthreads();
+    if constexpr (!QKV) {
 #pragma unroll
-    for (int t = 0; t < kTok / 16; ++t) {
-        const int idx = tid + 256 * t, r = idx >> 4, seg = idx & 15;
-        if (i0 + r < M && o0 + 8 * seg < O)                                      // O is a multiple of 8: a segment is in or out as a whole
-            *(uint4 *)(Y + (size_t)(i0 + r) * O + o0 + 8 * seg) = *(const uint4 *)(stage + r * kLinOutRow + 8 * seg);
+        for (int t = 0; t < kTok / 16; ++t) {
+            const int idx = tid + 256 * t, r = idx >> 4, seg = idx & 15;
+            if (i0 + r < M && o0 + 8 * seg < O)                                  // O is a multiple of 8: a segment is in or out as a whole
+                *(uint4 *)(Y + (size_t)(i0 + r) * O + o0 + 8 * seg) = *(const uint4 *)(stage + r * kLinOutRow + 8 * seg);
+        }
+    } else {
+        // units of the tile: (64-channel half = one head of q, k or v) x (token block of that tensor); one wave per unit
+        const int N = qkv.N, H = qkv.H, rr = lane >> 3, cc = lane & 7;
+        for (int hf = 0; hf < 2; ++hf) {
+            const int ch0 = o0 + 64 * hf;
+            if (ch0 >= O) break;
+            const int which = ch0 / (H * 64), h = (ch0 - which * H * 64) >> 6;
+            const int blk = which == 0 ? qkv.bq : kBK, nblk_seq = (N + blk - 1) / blk;
+            for (int tb = wave; tb * blk < kTok; tb += 4) {
+                const int t0 = i0 + tb * blk;
+                if (t0 >= M) break;                                              // uniform over the wave
+                const int b = t0 / N, tin = t0 - b * N, valid = min(blk, N - tin);
+                const uint16_t *src = stage + (tb * blk) * kLinOutRow + 64 * hf + 8 * cc;
+                float amax = 0.f;
+                for (int r = rr; r < valid; r += 8) {
+                    const uint4 v = *(const uint4 *)(src + r * kLinOutRow);
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) amax = fmaxf(amax, fmaxf(fabsf(bf16_lo(w[q])), fabsf(bf16_hi(w[q]))));
+                }
+                amax = wave_max(amax);
+                const float scale = fmaxf(amax, 1e-8f) / 448.0f;
+                if (lane == 0) qkv.scales[which][((size_t)b * H + h) * nblk_seq + tin / blk] = scale;
+                uint8_t *dst = qkv.codes[which] + (((size_t)b * N + tin) * H + h) * 64 + 8 * cc;
+                for (int r = rr; r < valid; r += 8) {
+                    const uint4 v = *(const uint4 *)(src + r * kLinOutRow);
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                    float y[8];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        y[2 * q] = fminf(fmaxf(bf16_lo(w[q]) / scale, -448.0f), 448.0f);
+                        y[2 * q + 1] = fminf(fmaxf(bf16_hi(w[q]) / scale, -448.0f), 448.0f);
+                    }
+                    int lo = 0, hi = 0;
+                    lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], lo, false);
+                    lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], lo, true);
+                    hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[4], y[5], hi, false);
+                    hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[6], y[7], hi, true);
+                    *(uint2 *)(dst + (size_t)r * H * 64) = make_uint2((uint32_t)lo, (uint32_t)hi);
+                }
+            }
+        }
     }
 }
 
@@ -226,20 +283,46 @@ hipError_t launch_quantise_rows(const void *X, long rows, int cols, void *codes,
     return hipGetLastError();
 }
 
+static bool lin_wide_tiles(int M, int n_ot) { return (long)((M + 255) / 256) * n_ot >= 512; }   // enough 256-token tiles to fill the chip twice over
+
 hipError_t launch_fp8_gemm(const void *A8, const float *sa, const void *W8, const float *sw, const void *bias, int M, int O, int K,
                            void *Y, hipStream_t st)
 {
     const int n_ot = (O + 127) / 128;
-    if ((long)((M + 255) / 256) * n_ot >= 512) {        // enough 256-token tiles to fill the chip twice over
+    const QkvOut none = {};
+    if (lin_wide_tiles(M, n_ot)) {
         const int n_it = (M + 255) / 256;
         const long total = (long)n_it * n_ot;
-        fp8_gemm_kernel<4><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint8_t *)A8, sa, (const uint8_t *)W8, sw, (const uint16_t *)bias, M, O, K,
-                                                                       n_it, total, (uint16_t *)Y);
+        fp8_gemm_kernel<4, false><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint8_t *)A8, sa, (const uint8_t *)W8, sw, (const uint16_t *)bias, M, O, K,
+                                                                              n_it, total, (uint16_t *)Y, none);
     } else {
         const int n_it = (M + 127) / 128;
         const long total = (long)n_it * n_ot;
-        fp8_gemm_kernel<2><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint8_t *)A8, sa, (const uint8_t *)W8, sw, (const uint16_t *)bias, M, O, K,
-                                                                       n_it, total, (uint16_t *)Y);
+        fp8_gemm_kernel<2, false><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint8_t *)A8, sa, (const uint8_t *)W8, sw, (const uint16_t *)bias, M, O, K,
+                                                                              n_it, total, (uint16_t *)Y, none);
+    }
+    return hipGetLastError();
+}
+
+int fp8_gemm_qkv_token_tile(int M, int H) { return lin_wide_tiles(M, (3 * H * 64 + 127) / 128) ? 256 : 128; }
+
+hipError_t launch_fp8_gemm_qkv(const void *A8, const float *sa, const void *W8, const float *sw, const void *bias, int B, int N, int H, int K,
+                               int bq, void *const codes[3], float *const scales[3], hipStream_t st)
+{
+    const int M = B * N, O = 3 * H * 64, n_ot = (O + 127) / 128;
+    QkvOut q;
+    for (int w = 0; w < 3; ++w) { q.codes[w] = (uint8_t *)codes[w]; q.scales[w] = scales[w]; }
+    q.N = N; q.H = H; q.bq = bq;
+    if (lin_wide_tiles(M, n_ot)) {
+        const int n_it = (M + 255) / 256;
+        const long total = (long)n_it * n_ot;
+        fp8_gemm_kernel<4, true><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint8_t *)A8, sa, (const uint8_t *)W8, sw, (const uint16_t *)bias, M, O, K,
+                                                                             n_it, total, nullptr, q);
+    } else {
+        const int n_it = (M + 127) / 128;
+        const long total = (long)n_it * n_ot;
+        fp8_gemm_kernel<2, true><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint8_t *)A8, sa, (const uint8_t *)W8, sw, (const uint16_t *)bias, M, O, K,
+                                                                             n_it, total, nullptr, q);
     }
     return hipGetLastError();
 }

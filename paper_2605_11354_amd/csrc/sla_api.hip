@@ -414,7 +414,7 @@ sla_status_t sla_quantise_e4m3(const void *X, int32_t B, int32_t H, int32_t N, i
 
 namespace {
 struct LinPlan { size_t off_cx, off_sx, off_cw, off_sw, total; };
-sla_status_t make_lin_plan(int32_t N, int32_t d_in, int32_t d_out, LinPlan &lp)
+static sla_status_t make_lin_plan(int32_t N, int32_t d_in, int32_t d_out, LinPlan &lp)
 {
     if (N < 0 || d_in <= 0 || d_out <= 0) return fail(SLA_ERR_INVALID_ARG, "bad sizes (N=%d d_in=%d d_out=%d)", N, d_in, d_out);
     if (d_in % 128 != 0) return fail(SLA_ERR_UNSUPPORTED, "d_in = %d; only multiples of 128 are implemented", d_in);
@@ -458,6 +458,37 @@ sla_status_t sla_fp8_linear(const void *x, const void *W, const void *bias, int3
     SLA_HIP(sla::launch_quantise_rows(W, d_out, d_in, at<void>(workspace, lp.off_cw), at<float>(workspace, lp.off_sw), st));
     SLA_HIP(sla::launch_fp8_gemm(at<void>(workspace, lp.off_cx), at<float>(workspace, lp.off_sx), at<void>(workspace, lp.off_cw),
                                  at<float>(workspace, lp.off_sw), bias, N, d_out, d_in, y, st));
+    return SLA_OK;
+}
+
+sla_status_t sla_fp8_linear_qkv(const void *x, const void *W, const void *bias, int32_t B, int32_t N, int32_t H, int32_t d_in,
+                                int32_t bq, void *Q8, void *K8, void *V8, float *sQ, float *sK, float *sV,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (B < 0 || N < 0 || H <= 0) return fail(SLA_ERR_INVALID_ARG, "bad sizes (B=%d N=%d H=%d)", B, N, H);
+    if (bq != 64 && bq != 128) return fail(SLA_ERR_UNSUPPORTED, "query block bq = %d; only 64 and 128 are implemented", bq);
+    if ((double)B * N >= 2.0e9) return fail(SLA_ERR_UNSUPPORTED, "too many tokens");
+    const int32_t tokens = B * N, d_out = 3 * H * 64;
+    LinPlan lp;
+    sla_status_t s = make_lin_plan(tokens, d_in, d_out, lp);
+    if (s != SLA_OK) return s;
+    if (tokens == 0) return SLA_OK;
+    const int tile = sla::fp8_gemm_qkv_token_tile(tokens, H);
+    if (B > 1 && N % tile != 0)
+        return fail(SLA_ERR_UNSUPPORTED, "with B > 1, N must be a multiple of %d (a token block may not straddle a token tile); N = %d", tile, N);
+    SLA_REQ_PTR(x); SLA_REQ_PTR(W); SLA_REQ_PTR(Q8); SLA_REQ_PTR(K8); SLA_REQ_PTR(V8);
+    SLA_OPT_PTR(bias);
+    if (!sQ || !sK || !sV) return fail(SLA_ERR_INVALID_ARG, "a scale output is NULL");
+    if (!workspace) return fail(SLA_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", lp.total);
+    if (!aligned(workspace, 256)) return fail(SLA_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    if (workspace_bytes < lp.total) return fail(SLA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, lp.total);
+    hipStream_t st = (hipStream_t)stream;
+    SLA_HIP(sla::launch_quantise_rows(x, tokens, d_in, at<void>(workspace, lp.off_cx), at<float>(workspace, lp.off_sx), st));
+    SLA_HIP(sla::launch_quantise_rows(W, d_out, d_in, at<void>(workspace, lp.off_cw), at<float>(workspace, lp.off_sw), st));
+    void *const codes[3] = {Q8, K8, V8};
+    float *const scales[3] = {sQ, sK, sV};
+    SLA_HIP(sla::launch_fp8_gemm_qkv(at<void>(workspace, lp.off_cx), at<float>(workspace, lp.off_sx), at<void>(workspace, lp.off_cw),
+                                     at<float>(workspace, lp.off_sw), bias, B, N, H, d_in, bq, codes, scales, st));
     return SLA_OK;
 }
 

@@ -73,4 +73,12 @@ hipError_t launch_quantise_rows(const void *X, long rows, int cols, void *codes,
 hipError_t launch_fp8_gemm(const void *A8, const float *sa, const void *W8, const float *sw, const void *bias, int M, int O, int K,
                            void *Y, hipStream_t st);
 
+// The same GEMM as the qkv projection in front of the attention: A8 [B*N, K], W8 [3*H*64, K] (output channels ordered
+// [q|k|v][head][64]); instead of y it writes the per-block scaled E4M3 form of Q, K and V: codes[w] [B,N,H,64] and
+// scales[w] [B,H,ceil(N/blk)] for w = 0 (Q, blk = bq), 1 (K, blk = 64), 2 (V, blk = 64).  A token block must not
+// straddle a token tile of fp8_gemm_qkv_token_tile(B*N, H) tokens: B == 1, or N a multiple of that tile.
+int fp8_gemm_qkv_token_tile(int M, int H);
+hipError_t launch_fp8_gemm_qkv(const void *A8, const float *sa, const void *W8, const float *sw, const void *bias, int B, int N, int H, int K,
+                               int bq, void *const codes[3], float *const scales[3], hipStream_t st);
+
 }  // namespace sla

@@ -88,6 +88,11 @@ hipError_t launch_pool(const void *X, const float *scales, bool fp8, RowMap rm, 
 // fp64 register-tiled product: workgroup tile 64(i) x 64(j), thread tile 4 x 4, the channel
 // loop runs in ascending order so every (i,j) accumulator is the canonical fma chain.
 // Bound: fp64 vector FMA (2*Nqb*Nkb*64 flops per head).
+__device__ __forceinline__ uint64_t desc_key(double s);
+
+// KEYS: instead of the logits, store the upper halves of their order-preserving keys (uint32 [rows, pitch], pitch in
+// keys): all the long-row classifier needs unless a threshold cuts through a group of equal upper halves.
+template <bool KEYS>
 __global__ __launch_bounds__(256) void scores_kernel(const double *__restrict__ qbar, const double *__restrict__ kbar,
                                                      int Nqb, int Nkb, int pitch, double *__restrict__ S)
 {
@@ -138,15 +143,26 @@ __global__ __launch_bounds__(256) void scores_kernel(const double *__restrict__ 
     }
     // a thread's four logits of a row are 32 contiguous bytes; the row pitch is a multiple of 8 entries, so the
     // group is inside the row's allocation as a whole (entries in [Nkb, pitch) are padding nobody reads)
-    double *Sh = S + bh * (long)Nqb * pitch;
     const int gj = j0 + tx * 4;
+    if constexpr (KEYS) {
+        uint32_t *Kh = (uint32_t *)S + bh * (long)Nqb * pitch;
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-        const int gi = i0 + ty * 4 + a;
-        if (gi < Nqb && gj < pitch) {
-            double2 *dst = (double2 *)(Sh + (long)gi * pitch + gj);
-            dst[0] = double2{acc[a][0], acc[a][1]};
-            dst[1] = double2{acc[a][2], acc[a][3]};
+        for (int a = 0; a < 4; ++a) {
+            const int gi = i0 + ty * 4 + a;
+            if (gi < Nqb && gj < pitch)
+                *(uint4 *)(Kh + (long)gi * pitch + gj) = make_uint4((uint32_t)(desc_key(acc[a][0]) >> 32), (uint32_t)(desc_key(acc[a][1]) >> 32),
+                                                                     (uint32_t)(desc_key(acc[a][2]) >> 32), (uint32_t)(desc_key(acc[a][3]) >> 32));
+        }
+    } else {
+        double *Sh = S + bh * (long)Nqb * pitch;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const int gi = i0 + ty * 4 + a;
+            if (gi < Nqb && gj < pitch) {
+                double2 *dst = (double2 *)(Sh + (long)gi * pitch + gj);
+                dst[0] = double2{acc[a][0], acc[a][1]};
+                dst[1] = double2{acc[a][2], acc[a][3]};
+            }
         }
     }
 }
@@ -155,7 +171,7 @@ hipError_t launch_scores(const double *qbar, const double *kbar, int BH, int Nqb
                          int pitch, double *S, hipStream_t st)
 {
     dim3 grid((Nkb + 63) / 64, (Nqb + 63) / 64, BH);
-    scores_kernel<<<grid, 256, 0, st>>>(qbar, kbar, Nqb, Nkb, pitch, S);
+    scores_kernel<false><<<grid, 256, 0, st>>>(qbar, kbar, Nqb, Nkb, pitch, S);
     return hipGetLastError();
 }
 
@@ -751,6 +767,262 @@ hipError_t launch_classify_fused(const void *Q, const float *sQ, bool fp8, RowMa
     if (Nkb <= 192) SLA_CF(3);
     if (Nkb <= 256) SLA_CF(4);
 #undef SLA_CF
+    return hipErrorInvalidValue;
+}
+
+// ---- long rows without the fp64 round trip (Nkb > 256, no logits or block-score softmax asked for) ------------
+// The classifier needs the ORDER of a row's logits, not their values, and the order is almost always decided by
+// the leading bits.  So the logits go to memory as 32-bit keys -- the upper half of the order-preserving 64-bit
+// key of the fp64 logit: sign, exponent and 20 bits of mantissa -- and the selection runs on those: one register
+// and one instruction per key and step instead of two or more.  Where a threshold falls inside a group of equal
+// 32-bit keys and the group is not taken as a whole, the members' logits are evaluated again (the same 64-step
+// fma chain, so the same bits) and the lower halves of their keys decide, then the block index: the labels are
+// those of the full fp64 order, bit for bit.
+
+hipError_t launch_score_keys(const double *qbar, const double *kbar, int BH, int Nqb, int Nkb, int pitch, uint32_t *keys,
+                             hipStream_t st)
+{
+    dim3 grid((Nkb + 63) / 64, (Nqb + 63) / 64, BH);
+    scores_kernel<true><<<grid, 256, 0, st>>>(qbar, kbar, Nqb, Nkb, pitch, (double *)keys);
+    return hipGetLastError();
+}
+
+// wave-wide minimum / maximum of a 32-bit value (DPP steps as above), uniform result
+template <bool MAX>
+__device__ __forceinline__ uint32_t wave_minmax_u32(uint32_t v)
+{
+    auto step = [](uint32_t a, uint32_t b) { return MAX ? (a > b ? a : b) : (a < b ? a : b); };
+    v = step(v, dpp_get<kShr1, 0xf>(v, v));
+    v = step(v, dpp_get<kShr2, 0xf>(v, v));
+    v = step(v, dpp_get<kShr4, 0xf>(v, v));
+    v = step(v, dpp_get<kShr8, 0xf>(v, v));
+    v = step(v, dpp_get<kBc15, 0xa>(v, v));
+    v = step(v, dpp_get<kBc31, 0xc>(v, v));
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+// (T, r, n): the k smallest (value, index) pairs among the candidates are the candidates with value < T plus the r
+// lowest-index ones of the n candidates with value == T.
+struct Cut { uint32_t T; int r, n; };
+
+// Radix descent, eight bits at a time from the top, for up to two ranks at once (two[t] = rank t wanted).  A slot m
+// of a lane is a candidate if cand(m); while both ranks follow the same prefix one histogram serves both.  hist:
+// 512 counters private to the wave.  Requires 1 <= k[t] <= number of candidates.
+template <int KPL, class Cand>
+__device__ __forceinline__ void radix_cuts(const uint32_t (&val)[KPL], Cand cand, const int (&k)[2], const bool (&want)[2],
+                                           uint32_t *hist, Cut (&cut)[2])
+{
+    const int lane = threadIdx.x & 63;
+    uint32_t prefix[2] = {0u, 0u};
+    int kk[2] = {k[0], k[1]};
+    bool act[2] = {want[0], want[1]};
+    for (int shift = 24; shift >= 0 && (act[0] || act[1]); shift -= 8) {
+        const bool both = act[0] && act[1], same = both && prefix[0] == prefix[1];
+        wave_lds_sync();
+        *(uint4 *)(hist + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
+        if (both && !same) *(uint4 *)(hist + 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
+        wave_lds_sync();
+        const int t0 = act[0] ? 0 : 1;                      // the rank whose counts go to the first histogram
+        if (shift == 24) {                                  // no prefix yet: every candidate counts, one histogram
+#pragma unroll
+            for (int m = 0; m < KPL; ++m)
+                if (cand(m)) atomicAdd(&hist[val[m] >> 24], 1u);
+        } else if (both && !same) {
+#pragma unroll
+            for (int m = 0; m < KPL; ++m) {
+                if (!cand(m)) continue;
+                const uint32_t p = val[m] >> (shift + 8), d = (val[m] >> shift) & 255u;
+                if (p == prefix[0]) atomicAdd(&hist[d], 1u);
+                if (p == prefix[1]) atomicAdd(&hist[256 + d], 1u);
+            }
+        } else {
+            const uint32_t pf = prefix[t0];
+#pragma unroll
+            for (int m = 0; m < KPL; ++m) {
+                if (!cand(m)) continue;
+                if ((val[m] >> (shift + 8)) == pf) atomicAdd(&hist[(val[m] >> shift) & 255u], 1u);
+            }
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            if (!act[t]) continue;
+            const uint32_t *h = hist + ((t == 1 && both && !same) ? 256 : 0);
+            const uint4 c4 = *(const uint4 *)(h + lane * 4);
+            const uint32_t c[4] = {c4.x, c4.y, c4.z, c4.w};
+            const uint32_t mine = c[0] + c[1] + c[2] + c[3];
+            const uint32_t incl = wave_incl_scan(mine), excl = incl - mine;
+            const bool here = excl < (uint32_t)kk[t] && (uint32_t)kk[t] <= incl;
+            const int src = __ffsll((long long)__ballot(here)) - 1;          // exactly one lane
+            uint32_t before = excl, digit = 0, cnt = 0;
+            if (here) {
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    if (cnt == 0) {
+                        if (before + c[b] >= (uint32_t)kk[t]) { digit = lane * 4 + b; cnt = c[b]; }
+                        else before += c[b];
+                    }
+                }
+            }
+            digit = bcast_u32(digit, src);
+            before = bcast_u32(before, src);
+            cnt = bcast_u32(cnt, src);
+            prefix[t] = (prefix[t] << 8) | digit;
+            kk[t] -= (int)before;
+            if (shift == 0) { cut[t] = Cut{prefix[t], kk[t], (int)cnt}; act[t] = false; }
+            else if (cnt == 1) {                                              // one candidate carries this prefix: fetch it
+                uint32_t found = 0;
+                bool have = false;
+#pragma unroll
+                for (int m = 0; m < KPL; ++m)
+                    if (cand(m) && (val[m] >> shift) == prefix[t]) { found = val[m]; have = true; }
+                cut[t] = Cut{bcast_u32(found, __ffsll((long long)__ballot(have)) - 1), 1, 1};
+                act[t] = false;
+            }
+        }
+    }
+}
+
+// Per-lane bit mask (bit m = slot m) of the k first slots in the order (key ascending, lower half of the exact key
+// ascending, index ascending), given the cut of the 32-bit keys.
+template <int KPL>
+__device__ __forceinline__ uint64_t take_first(const uint32_t (&key)[KPL], const Cut &cut, int Nkb, const double *__restrict__ q,
+                                               const double *__restrict__ kh, uint32_t *hist)
+{
+    const int lane = threadIdx.x & 63;
+    uint64_t bits = 0;
+    if (cut.r == cut.n) {                                   // the group at the threshold is taken as a whole (nearly always: n == 1)
+#pragma unroll
+        for (int m = 0; m < KPL; ++m) bits |= (uint64_t)(key[m] <= cut.T) << m;
+        return bits;
+    }
+    // r of the n slots with key == T: their exact keys decide.  lo[m]: lower half of the exact 64-bit key.
+    uint32_t lo[KPL];
+#pragma unroll
+    for (int m = 0; m < KPL; ++m) {
+        lo[m] = 0;
+        const int j = m * 64 + lane;
+        if (key[m] == cut.T && j < Nkb) {
+            const double *kr = kh + (long)j * kD;
+            double s = 0.0;
+            for (int d = 0; d < kD; ++d) s = fma(q[d], kr[d], s);
+            lo[m] = (uint32_t)desc_key(s);
+        }
+    }
+    const uint32_t T = cut.T;
+    auto cand = [&](int m) { return key[m] == T && m * 64 + lane < Nkb; };
+    const int k2[2] = {cut.r, 0};
+    const bool w2[2] = {true, false};
+    Cut c2[2];
+    radix_cuts<KPL>(lo, cand, k2, w2, hist, c2);
+    const uint64_t lt = (1ull << lane) - 1;
+    int tie = 0;
+#pragma unroll
+    for (int m = 0; m < KPL; ++m) {
+        const bool in = cand(m), eq = in && lo[m] == c2[0].T;
+        const uint64_t b = __ballot(eq);
+        const bool sel = key[m] < T || (in && lo[m] < c2[0].T) || (eq && tie + (int)__popcll(b & lt) < c2[0].r);
+        tie += __popcll(b);
+        bits |= (uint64_t)sel << m;
+    }
+    return bits;
+}
+
+// One wavefront per row; lane l holds the 32-bit keys of blocks j = 64 m + l.
+template <int KPL>
+__global__ __launch_bounds__(64, KPL <= 34 ? 4 : 2) void select_keys_kernel(const uint32_t *__restrict__ keys, int pitch, const double *__restrict__ qbar,
+                                                         const double *__restrict__ kbar, int Nqb, int Nkb, int k_c, int k_n,
+                                                         uint64_t *__restrict__ mbits, int lab_pitch,
+                                                         int8_t *__restrict__ lab_dense, int32_t *__restrict__ crit_idx)
+{
+    __shared__ __align__(16) uint32_t hist[512];
+    const long row = blockIdx.x;
+    const int lane = threadIdx.x;
+    const uint32_t *kr = keys + row * pitch;
+    uint32_t key[KPL];
+    uint32_t kmin = ~0u, kmax = 0u;
+#pragma unroll
+    for (int m = 0; m < KPL; ++m) {
+        const int j = m * 64 + lane;
+        key[m] = ~0u;
+        if (j < Nkb) {
+            key[m] = kr[j];
+            kmin = min(kmin, key[m]);
+            kmax = max(kmax, key[m]);
+        }
+    }
+    kmin = wave_minmax_u32<false>(kmin);
+    kmax = wave_minmax_u32<true>(kmax);
+    // keys relative to the row's range, so that the leading digits discriminate.  Slots past the end keep the largest
+    // value: they sort after every block of the row (equal keys go by index), so no rank up to Nkb reaches them.
+    const uint32_t range = kmax - kmin;
+    const int sh = range ? __clz((int)range) : 0;
+#pragma unroll
+    for (int m = 0; m < KPL; ++m) key[m] = (m * 64 + lane < Nkb) ? (key[m] - kmin) << sh : ~0u;
+
+    const int k_keep = Nkb - k_n;          // the first k_keep of the order are not negligible
+    const int k2[2] = {k_c, k_keep};
+    const bool want[2] = {k_c > 0 && k_c < Nkb, k_keep > 0 && k_keep < Nkb};
+    Cut cut[2] = {Cut{0u, 0, 0}, Cut{0u, 0, 0}};
+    radix_cuts<KPL>(key, [](int) { return true; }, k2, want, hist, cut);
+
+    const uint64_t lt = (1ull << lane) - 1;
+    uint32_t mb_lo = 0, mb_hi = 0;         // lane m keeps the marginal mask of chunk m: one 8-byte store per lane at the end
+    int ncrit = 0;
+    auto emit = [&](int m, bool selc, bool seln) {
+        const int j = m * 64 + lane;
+        const int8_t lab = selc ? 2 : (seln ? 1 : 0);
+        const uint64_t mb = __ballot(lab == 1);
+        if (lane == m) { mb_lo = (uint32_t)mb; mb_hi = (uint32_t)(mb >> 32); }
+        if (lab_dense && j < Nkb) lab_dense[row * Nkb + j] = lab;
+        if (crit_idx) {
+            const uint64_t b = __ballot(selc);
+            if (b) {                                            // most chunks hold no critical block
+                const int pos = ncrit + (int)__popcll(b & lt);
+                if (selc && pos < k_c) crit_idx[row * k_c + pos] = j;
+                ncrit += __popcll(b);
+            }
+        }
+    };
+    const bool whole0 = !want[0] || cut[0].r == cut[0].n, whole1 = !want[1] || cut[1].r == cut[1].n;
+    if (whole0 && whole1) {                // the groups at both thresholds are taken whole (nearly always: single keys)
+        const uint32_t Tc = cut[0].T, Tn = cut[1].T;
+#pragma unroll
+        for (int m = 0; m < KPL; ++m) {
+            const bool valid = m * 64 + lane < Nkb;
+            const bool selc = want[0] ? key[m] <= Tc : (k_c > 0 && valid);
+            const bool seln = want[1] ? key[m] <= Tn : (k_keep > 0 && valid);
+            emit(m, selc, seln);
+        }
+    } else {
+        const long bh = row / Nqb;
+        const double *q = qbar + row * kD, *kh = kbar + bh * (long)Nkb * kD;
+        uint64_t valid = 0;
+#pragma unroll
+        for (int m = 0; m < KPL; ++m) valid |= (uint64_t)(m * 64 + lane < Nkb) << m;
+        const uint64_t cm = want[0] ? take_first<KPL>(key, cut[0], Nkb, q, kh, hist) : (k_c > 0 ? valid : 0ull);
+        const uint64_t nm = want[1] ? take_first<KPL>(key, cut[1], Nkb, q, kh, hist) : (k_keep > 0 ? valid : 0ull);
+#pragma unroll
+        for (int m = 0; m < KPL; ++m) emit(m, (cm >> m) & 1, (nm >> m) & 1);
+    }
+    if (lane < (lab_pitch >> 6)) mbits[row * (lab_pitch >> 6) + lane] = ((uint64_t)mb_hi << 32) | mb_lo;
+}
+
+template <int KPL>
+static hipError_t launch_select_keys_t(const uint32_t *keys, int pitch, const double *qbar, const double *kbar, long rows, int Nqb,
+                                       int Nkb, int k_c, int k_n, uint64_t *mbits, int lab_pitch, int8_t *lab_dense,
+                                       int32_t *crit_idx, hipStream_t st)
+{
+    select_keys_kernel<KPL><<<(unsigned)rows, 64, 0, st>>>(keys, pitch, qbar, kbar, Nqb, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx);
+    return hipGetLastError();
+}
+
+hipError_t launch_select_keys(const uint32_t *keys, int pitch, const double *qbar, const double *kbar, long rows, int Nqb, int Nkb,
+                              int k_c, int k_n, uint64_t *mbits, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx, hipStream_t st)
+{
+#define SLA_SK(K) if (lab_pitch <= 64 * K) return launch_select_keys_t<K>(keys, pitch, qbar, kbar, rows, Nqb, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx, st)
+    SLA_SK(4); SLA_SK(8); SLA_SK(12); SLA_SK(16); SLA_SK(24); SLA_SK(34); SLA_SK(48); SLA_SK(64);
+#undef SLA_SK
     return hipErrorInvalidValue;
 }
 

@@ -149,6 +149,14 @@ sla_status_t run_classify(const sla_params_t *p, const Plan &pl, const void *Q, 
         SLA_HIP(mark(3));
         return SLA_OK;
     }
+    if (!Pc && !scores_out) {           // only the order matters: 32-bit keys instead of fp64 logits
+        uint32_t *keys = at<uint32_t>(ws, pl.off_scores);
+        SLA_HIP(sla::launch_score_keys(qbar, kbar, pl.BH, pl.Nqb, pl.Nkb, pl.s_pitch, keys, st));
+        SLA_HIP(mark(3));
+        SLA_HIP(sla::launch_select_keys(keys, pl.s_pitch, qbar, kbar, (long)pl.BH * pl.Nqb, pl.Nqb, pl.Nkb, pl.k_c, pl.k_n,
+                                        at<uint64_t>(ws, pl.off_lab), pl.lab_pitch, labels, pl.k_c > 0 ? crit : nullptr, st));
+        return SLA_OK;
+    }
     SLA_HIP(sla::launch_scores(qbar, kbar, pl.BH, pl.Nqb, pl.Nkb, pl.s_pitch, at<double>(ws, pl.off_scores), st));
     SLA_HIP(mark(3));
     SLA_HIP(sla::launch_select(at<double>(ws, pl.off_scores), pl.s_pitch, (long)pl.BH * pl.Nqb, pl.Nkb, pl.k_c, pl.k_n,

@@ -23,6 +23,15 @@ hipError_t launch_select(const double *S, int pitch, long rows, int Nkb, int k_c
                          uint64_t *mbits, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx,
                          float *Pc, double *S_dense, float sm_scale, hipStream_t st);
 
+// The same two steps for long rows when neither the logits nor the block-score softmax are wanted: the logits are
+// stored as 32-bit keys (upper half of the order-preserving key of the fp64 logit; keys [rows, pitch], pitch in
+// keys) and the selection runs on those, evaluating the exact logit again only for the members of a group of equal
+// 32-bit keys that a threshold cuts through.  Same labels, mask and critical lists as launch_scores + launch_select.
+hipError_t launch_score_keys(const double *qbar, const double *kbar, int BH, int Nqb, int Nkb, int pitch, uint32_t *keys,
+                             hipStream_t st);
+hipError_t launch_select_keys(const uint32_t *keys, int pitch, const double *qbar, const double *kbar, long rows, int Nqb, int Nkb,
+                              int k_c, int k_n, uint64_t *mbits, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx, hipStream_t st);
+
 // short rows (Nkb <= 256): block mean of Q + pooled logits + classifier in one launch; kbar holds the
 // block means of K.  Outputs as launch_select; qbar_out (optional) receives the block means of Q.
 hipError_t launch_classify_fused(const void *Q, const float *sQ, bool fp8, RowMap rm, const double *kbar, int BH, int N, int bq, int Nkb,

@@ -139,14 +139,14 @@ __device__ __forceinline__ float max16(const f32x16 &s)
     return max3(max3(a, b, c), max3(d, e, s[15]), a);
 }
 
-template <int NWAVES, bool FP8>
+template <int NWAVES, bool FP8, int NSLOTS = 3>
 struct Tile {
     static constexpr int KBYTES = FP8 ? 64 * 64 : 64 * 128;     // K tile (e4m3 / bf16)
     static constexpr int VBYTES = 64 * 128;                     // V^T tile (always fp16)
     static constexpr int KINS = KBYTES / 1024 / NWAVES;         // 1 KB copy instructions per wave
     static constexpr int VINS = VBYTES / 1024 / NWAVES;
     static constexpr int LOADS = KINS + VINS;                   // per wave per tile
-    static constexpr int SLOTS = 3;                             // slots of the K ring and of the V^T ring
+    static constexpr int SLOTS = NSLOTS;                        // slots of the K ring and of the V^T ring (2: lists of at most two blocks)
     static constexpr int VRING = SLOTS * KBYTES;                // the V^T ring follows the K ring
     // behind the rings: a 256-byte slot for the Z row, and, for E4M3 inputs (whose K ring is too small for both
     // epilogue operands), 8 KB for W^T
@@ -185,7 +185,9 @@ template <bool B> using flag = std::integral_constant<bool, B>;
 // two waves share a query group and each takes one 32-key half of every tile (used for 64-row
 // query blocks so that a workgroup still has four waves); their partial (max, sum, O) are merged
 // through LDS after the loop and the KS = 0 wave of each pair runs the epilogue.
-template <int NW, int KS, bool FP8>
+// SL: ring slots.  Three for the pipeline described above; two are enough when no list has more than two blocks (every
+// tile then has a slot of its own and nothing is requested inside the loop), and a third more workgroups fit a CU.
+template <int NW, int KS, bool FP8, int SL>
 __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
     const void *__restrict__ Qp, const void *__restrict__ Kp, const uint16_t *__restrict__ Vp, const float *__restrict__ lvs,
     const float *__restrict__ sQ, const float *__restrict__ sK, RowMap rm,
@@ -193,7 +195,8 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
     int proj_per_head, int phi, int H, int N, int Nqb, int Nkb, long total, float c_exp, uint16_t *__restrict__ O, float *__restrict__ O32)
 {
     constexpr int NWAVES = NW * KS;
-    using T = Tile<NWAVES, FP8>;
+    using T = Tile<NWAVES, FP8, SL>;
+    static_assert(SL == 3 || (SL == 2 && KS == 1), "two slots: unsplit lists of at most two blocks");
     constexpr int BQ = 32 * NW;
     constexpr int ES = FP8 ? 1 : 2;                     // bytes per input element
     constexpr int NH = 2 / KS;                          // units (32-key halves of a tile) this wave processes per tile
@@ -604,7 +607,7 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
     constexpr int KAHEAD = NH == 2 ? 3 : 4;
     // ring slots (byte offsets) of: the K tile requested in this iteration, the V^T tile requested, the K tile whose
     // fragments are read, the V^T tile whose fragments are read; each moves on by one slot per iteration
-    uint32_t kreq = (KAHEAD % T::SLOTS) * T::KBYTES, vreq = 2 * T::VBYTES, kread = ((KAHEAD - 2) % T::SLOTS) * T::KBYTES, vread = 0;
+    uint32_t kreq = (KAHEAD % T::SLOTS) * T::KBYTES, vreq = (2 % T::SLOTS) * T::VBYTES, kread = ((KAHEAD - 2) % T::SLOTS) * T::KBYTES, vread = 0;
     for (int c = 0; c < k; ++c) {
         // copies that may stay in flight here: those requested one iteration ago
         if (c == 0) wait_copies_and_barrier<0>();      // (nothing is in flight; joins the waves after the prologue's LDS reads)
@@ -821,12 +824,12 @@ hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int NW, int KS, bool FP8>
+template <int NW, int KS, bool FP8, int SL = 3>
 static hipError_t launch_attend_t(const void *Q, const void *K, const void *Vp, const float *lvs, const float *sQ, const float *sK, RowMap rm,
                                   const int32_t *crit_idx, int k_c, const void *Hq, const void *WT, int proj_per_head, int phi,
                                   int H, int N, int Nqb, int Nkb, long total, float c_exp, void *O, float *O32, hipStream_t st)
 {
-    attend_kernel<NW, KS, FP8><<<(unsigned)xcd_grid(total), 64 * NW * KS, 0, st>>>(Q, K, (const uint16_t *)Vp, lvs, sQ, sK, rm, crit_idx, k_c, (const uint16_t *)Hq,
+    attend_kernel<NW, KS, FP8, SL><<<(unsigned)xcd_grid(total), 64 * NW * KS, 0, st>>>(Q, K, (const uint16_t *)Vp, lvs, sQ, sK, rm, crit_idx, k_c, (const uint16_t *)Hq,
                                                                      (const uint16_t *)WT, proj_per_head, phi, H, N, Nqb, Nkb,
                                                                      total, c_exp, (uint16_t *)O, O32);
     return hipGetLastError();
@@ -846,9 +849,11 @@ hipError_t launch_attend(const void *Q, const void *K, const void *Vp, const flo
     // 64-row query blocks: two query groups x two key halves, so a workgroup still has four waves;
     // with very few critical blocks per row the merge of the halves costs more than it hides
     if (k_c >= 4) { if (fp8) SLA_ATT(2, 2, true); else SLA_ATT(2, 2, false); }
-    if (fp8) SLA_ATT(2, 1, true);
-    SLA_ATT(2, 1, false);
+    if (k_c > 2) { if (fp8) SLA_ATT(2, 1, true); else SLA_ATT(2, 1, false); }
 #undef SLA_ATT
+    // lists of at most two blocks (frame attention): two ring slots, four workgroups per CU
+    if (fp8) return launch_attend_t<2, 1, true, 2>(Q, K, Vp, lvs, sQ, sK, rm, crit_idx, k_c, Hq, WT, proj_per_head, phi, H, N, Nqb, Nkb, total, c_exp, O, O32, st);
+    return launch_attend_t<2, 1, false, 2>(Q, K, Vp, lvs, sQ, sK, rm, crit_idx, k_c, Hq, WT, proj_per_head, phi, H, N, Nqb, Nkb, total, c_exp, O, O32, st);
 }
 
 }  // namespace sla

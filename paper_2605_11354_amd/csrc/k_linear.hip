@@ -283,11 +283,193 @@ hipError_t launch_quantise_rows(const void *X, long rows, int cols, void *codes,
     return hipGetLastError();
 }
 
+// The same product on 256 tokens x 256 channels per workgroup, for problems with enough of those tiles: four waves as
+// 2 x 2, a wave's tile is 128 channels x 128 tokens = 4 x 4 MFMA tiles (256 accumulator registers, one wave per SIMD).
+// Eight operand fragments feed sixteen MFMAs, so the LDS read rate (the limit of the smaller tiles: twelve fragment
+// reads per sixteen MFMAs on each of four waves is three quarters of the LDS bandwidth) drops to half of it.  Tiles go
+// from global memory straight into LDS (global_load_lds_dwordx4: 1 KB per wave instruction, the chunk swizzle applied on
+// the global side), two stages of 64 KB, the copies two K steps ahead of the products, one barrier per step (the
+// schedule is written out at the loop).  The copies are inline assembly, invisible to the compiler's wait counting; the wait is explicit.
+// Epilogue: scales and bias in fp32, each wave stages its [token][channel] tile in its own quarter of LDS (16-byte
+// chunks XOR-ed with the token row against bank conflicts) and stores 16 bytes per lane, 256 contiguous bytes per row.
+__global__ __launch_bounds__(256, 1) void fp8_gemm_big_kernel(const uint8_t *__restrict__ A8, const float *__restrict__ sa,
+                                                              const uint8_t *__restrict__ W8, const float *__restrict__ sw,
+                                                              const uint16_t *__restrict__ bias, int M, int O, int K, int n_it,
+                                                              long total, uint16_t *__restrict__ Y)
+{
+    constexpr int kStage = 2 * 256 * kLinK;                                      // bytes of one stage: A tile + W tile
+    __shared__ __attribute__((aligned(1024))) uint8_t smem[2 * kStage + 2048];   // behind the stages: the tile's 256 channel scales and biases
+    const long item = xcd_remap(blockIdx.x, total);
+    if (item >= total) return;
+    const int n_ot = (int)(total / n_it);
+    const int ot = (int)(item % n_ot), it = (int)(item / n_ot);                  // channel tile fastest (see above)
+    const int i0 = it * 256, o0 = ot * 256;
+    {   // thread t brings channel o0 + t's scale and bias; published by the first barrier, read in the epilogue
+        const int oc = min(o0 + (int)threadIdx.x, O - 1);
+        float *cs = (float *)(smem + 2 * kStage);
+        cs[threadIdx.x] = sw[oc];
+        cs[256 + threadIdx.x] = bias ? bf16_bits_to_f32(bias[oc]) : 0.f;
+    }
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);                  // uniform: LDS destinations of the copies sit in scalar registers
+    const int wo = (wave >> 1) * 128, wi = (wave & 1) * 128;                     // wave's first channel / token within the tile
+
+    // copies: wave w brings rows 64 w .. 64 w + 63 of both tiles, 8 rows (1 KB) per instruction; lane l lands at
+    // row 8 x + l / 8, chunk position l % 8, and fetches the chunk that belongs there (rows past the end of a matrix
+    // repeat its last row: their results are never stored)
+    uint32_t va[8], vw[8];
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+        const int row = 64 * wave + 8 * x + (lane >> 3), ch = (lane & 7) ^ lin_swz(row);
+        va[x] = (uint32_t)min(i0 + row, M - 1) * (uint32_t)K + ch * 16;
+        vw[x] = (uint32_t)min(o0 + row, O - 1) * (uint32_t)K + ch * 16;
+    }
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)smem;
+    auto issue = [&](int ks, int stage) {
+        const uint32_t dst = lds_base + stage * kStage + wave * 8192;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            copy_1k_to_lds(A8 + (size_t)ks * kLinK, va[x], dst + x * 1024);
+            copy_1k_to_lds(W8 + (size_t)ks * kLinK, vw[x], dst + 256 * kLinK + x * 1024);
+        }
+    };
+    auto frag = [&](const uint8_t *tile, int row, int s) {
+        const int c0 = 4 * s + 2 * g;
+        const uint4 u0 = *(const uint4 *)(tile + row * kLinK + ((c0 ^ lin_swz(row)) << 4));
+        const uint4 u1 = *(const uint4 *)(tile + row * kLinK + (((c0 + 1) ^ lin_swz(row)) << 4));
+        i32x8 f;
+        f[0] = u0.x; f[1] = u0.y; f[2] = u0.z; f[3] = u0.w; f[4] = u1.x; f[5] = u1.y; f[6] = u1.z; f[7] = u1.w;
+        return f;
+    };
+
+    f32x16 acc[4][4];                                                           // [channel sub-tile][token sub-tile]
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+
+    // Schedule of one K step ks (stage st = ks & 1; a step is two 64-byte slices s0, s1, sixteen MFMAs each):
+    //     MFMAs of (ks, s0), the reads of the fragments of (ks, s1) slipped in after the first eight
+    //     wait: copies of step ks+1 landed (issued a whole step ago), own reads returned; barrier
+    //     MFMAs of (ks, s1); slipped in: the reads of the fragments of (ks+1, s0) after the first eight, one copy of
+    //     step ks+2 (into stage st, which every wave has finished reading) after each of the sixteen
+    // so the wave keeps the matrix unit's queue filled except at the barrier: every LDS read has at least eight MFMAs
+    // (five hundred cycles) to arrive in, the copies run two steps ahead on two stages, one barrier per step.
+    const int ksteps = K / kLinK;
+    i32x8 wf0[4], af0[4], wf1[4], af1[4];
+    auto read_one = [&](i32x8 (&wf)[4], i32x8 (&af)[4], int stage, int sl, int idx) {     // fragment idx of 8: 0..3 W, 4..7 A
+        const uint8_t *At = smem + stage * kStage, *Wt = At + 256 * kLinK;
+        if (idx < 4) wf[idx] = frag(Wt, wo + 32 * idx + l32, sl);
+        else af[idx - 4] = frag(At, wi + 32 * (idx - 4) + l32, sl);
+    };
+    auto copy_one = [&](int ks, int stage, int idx) {                                      // copy idx of 16: even A, odd W
+        const uint32_t dst = lds_base + stage * kStage + wave * 8192 + (idx >> 1) * 1024;
+        if (idx & 1) copy_1k_to_lds(W8 + (size_t)ks * kLinK, vw[idx >> 1], dst + 256 * kLinK);
+        else copy_1k_to_lds(A8 + (size_t)ks * kLinK, va[idx >> 1], dst);
+    };
+#define SLA_SB() __builtin_amdgcn_sched_barrier(0)
+    issue(0, 0);
+    if (ksteps > 1) issue(1, 1);
+    if (ksteps > 1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");           // the sixteen copies of step 0 (those of step 1 may fly on)
+    else            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int f = 0; f < 8; ++f) read_one(wf0, af0, 0, 0, f);
+    for (int ks = 0; ks < ksteps; ++ks) {
+        const int st = ks & 1;
+        const bool more1 = ks + 1 < ksteps, more2 = ks + 2 < ksteps;
+        // F0 was requested at least eight MFMAs ago: say here that it has arrived, so that the wait the compiler puts in
+        // front of its first use does not cover the reads that follow
+        __builtin_amdgcn_s_waitcnt(0xC07F);        // lgkmcnt(0) only
+        SLA_SB();
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wf0[m >> 2], af0[m & 3], acc[m >> 2][m & 3], 0, 0, 0, 0, 0, 0);
+            if (m < 8) read_one(wf1, af1, st, 1, m);
+            SLA_SB();
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0xC07F);        // lgkmcnt(0), as a builtin: the compiler then knows F1 has arrived
+        __builtin_amdgcn_s_barrier();
+        SLA_SB();
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wf1[m >> 2], af1[m & 3], acc[m >> 2][m & 3], 0, 0, 0, 0, 0, 0);
+            if (m < 8 && more1) read_one(wf0, af0, st ^ 1, 0, m);
+            if (more2) copy_one(ks + 2, st, m);
+            SLA_SB();
+        }
+    }
+#undef SLA_SB
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    __builtin_amdgcn_s_barrier();                                                // every wave is past its last fragment reads
+
+    // accumulator (a,b) register 4q+r of lane (l32, g): channel o0 + wo + 32a + 8q + 4g + r, token i0 + wi + 32b + l32.
+    // The wave's tile as [128 tokens][128 channels] bf16 in its own 32 KB: the 8-byte piece of channels 4 c2 .. 4 c2 + 3
+    // (c2 = 8a + 2q + g) of token row t goes to 16-byte chunk (c2 / 2) ^ (t % 16), half c2 % 2.
+    uint8_t *stage = smem + wave * 32768;
+    float swv[4][4][4], bv[4][4][4];
+    {
+        const float *cs = (const float *)(smem + 2 * kStage);
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c = wo + 32 * a + 8 * q + 4 * g;
+                const float4 s4 = *(const float4 *)(cs + c), b4 = *(const float4 *)(cs + 256 + c);
+                swv[a][q][0] = s4.x; swv[a][q][1] = s4.y; swv[a][q][2] = s4.z; swv[a][q][3] = s4.w;
+                bv[a][q][0] = b4.x; bv[a][q][1] = b4.y; bv[a][q][2] = b4.z; bv[a][q][3] = b4.w;
+            }
+    }
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const int t = 32 * b + l32;
+        const float si = sa[min(i0 + wi + t, M - 1)];
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float v[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] = acc[a][b][4 * q + r] * (si * swv[a][q][r]) + bv[a][q][r];
+                const int c2 = 8 * a + 2 * q + g;
+                *(uint2 *)(stage + t * 256 + (((c2 >> 1) ^ (t & 15)) << 4) + ((c2 & 1) << 3)) = make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
+            }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                          // the wave reads back what it wrote itself
+#pragma unroll
+    for (int x0 = 0; x0 < 32; x0 += 16) {                                        // sixteen rows' pieces read, then sixteen stores
+        uint4 piece[16];
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+            const int t = 4 * (x0 + x) + (lane >> 4), c = lane & 15;             // 16 lanes per token row: 256 contiguous bytes
+            piece[x] = *(const uint4 *)(stage + t * 256 + ((c ^ (t & 15)) << 4));
+        }
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+            const int t = 4 * (x0 + x) + (lane >> 4), c = lane & 15;
+            const int i = i0 + wi + t, o = o0 + wo + 8 * c;
+            if (i < M && o < O) *(uint4 *)(Y + (size_t)i * O + o) = piece[x];    // O is a multiple of 8: a piece is in or out as a whole
+        }
+    }
+}
+
+static bool lin_big_tiles(int M, int O) { return (long)((M + 255) / 256) * ((O + 255) / 256) >= 512; }   // two rounds of the chip
+
 static bool lin_wide_tiles(int M, int n_ot) { return (long)((M + 255) / 256) * n_ot >= 512; }   // enough 256-token tiles to fill the chip twice over
 
 hipError_t launch_fp8_gemm(const void *A8, const float *sa, const void *W8, const float *sw, const void *bias, int M, int O, int K,
                            void *Y, hipStream_t st)
 {
+    if (lin_big_tiles(M, O)) {
+        const int n_it = (M + 255) / 256;
+        const long total = (long)n_it * ((O + 255) / 256);
+        fp8_gemm_big_kernel<<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint8_t *)A8, sa, (const uint8_t *)W8, sw, (const uint16_t *)bias, M, O, K,
+                                                                       n_it, total, (uint16_t *)Y);
+        return hipGetLastError();
+    }
     const int n_ot = (O + 127) / 128;
     const QkvOut none = {};
     if (lin_wide_tiles(M, n_ot)) {

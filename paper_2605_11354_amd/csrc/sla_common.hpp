@@ -106,6 +106,17 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// 1 KB copies global -> LDS: lane l moves the 16 bytes at base + voff(l) to LDS byte lds_addr + 16 l.
+// base and lds_addr are wave-uniform (SGPRs); M0 carries the LDS address for the copy and is put back afterwards
+// (the compiler reserves M0 for its own use and does not accept it as a clobber, so the statement leaves it as it
+// found it).  The s_nop is the wait state the ISA asks for between a scalar write of M0 and an instruction that
+// moves data into LDS through it (the compiler's hazard recogniser does not look inside inline assembly).
+__device__ __forceinline__ void copy_1k_to_lds(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
+{
+    uint32_t saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0) : "v"(voff), "s"(base), "s"(lds_addr) : "memory");
+}
 // One projection matrix W [e_in][e_out] -> WT [e_out][slot], slot 16s + 8g + 4a + b holding e_in = 16s + 8a + 4g + b
 // (transposed, and with the same permutation of the contraction index as the V^T tiles, so the projection
 // product of the attention kernel reads it with the fragment addressing of its main loop).  One workgroup of

@@ -486,7 +486,9 @@ def test_forward_with_given_labels_reproduces_the_forward(oracle, name):
 
 @pytest.mark.parametrize("N,d_in,d_out,with_bias", [(300, 256, 200, True), (128, 128, 128, False), (1, 1024, 8, True),
                                                     (1374, 1024, 3072, True), (257, 384, 136, False),
-                                                    (8000, 128, 2048, True)])        # the last one takes the 256-token tiles
+                                                    (8000, 128, 2048, True),          # takes the 256-token tiles
+                                                    (33000, 128, 1032, True),         # 256 x 256 tiles, ragged in both directions
+                                                    (40000, 384, 1024, False)])       # 256 x 256 tiles, three K steps
 def test_fp8_linear_layer(oracle, N, d_in, d_out, with_bias):
     """Alg. 2 forward on the device against the oracle.  The code matrices and scales are the oracle's bit for bit
     (same quantiser arithmetic), products of E4M3 numbers are exact in fp32, so what remains is fp32 accumulation

@@ -73,6 +73,23 @@ __device__ __forceinline__ int lin_swz(int row) { return (row >> 1) & 7; }
 // (token block, head) of it at a time (absolute maximum by a wave reduction, then divide / clamp / convert: the
 // arithmetic of quantise_e4m3_kernel), so the result is bit for bit that of sla_fp8_linear followed by
 // sla_quantise_e4m3, without y's round trip through HBM.  Token blocks never straddle a tile (the host checks).
+// x / d for many x and one d, with the bits of the IEEE division: y = RN(1 / d) once (a true division), then
+// q = RN(x y), r = x - d q (exact in one fma), RN(q + r y) is the correctly rounded quotient (Markstein's division
+// step; it needs y correctly rounded and fails only for a significand of d of all ones, which takes the division).
+// Quotients here are at most 448 in magnitude and anything below 2^-10 becomes the code 0, so the exponent range
+// plays no part.  Three instructions per element instead of the ten of the division's expansion.
+struct BlockDivisor {
+    float d, y;
+    bool plain;
+    __device__ __forceinline__ explicit BlockDivisor(float d_) : d(d_), y(1.0f / d_), plain((__float_as_uint(d_) & 0x7FFFFFu) == 0x7FFFFFu) {}
+    __device__ __forceinline__ float operator()(float x) const
+    {
+        if (plain) return x / d;
+        const float q = x * y;
+        return fmaf(fmaf(-q, d, x), y, q);
+    }
+};
+
 struct QkvOut {
     uint8_t *codes[3];          // Q, K, V codes, [B,N,H,64]
     float *scales[3];           // [B,H,ceil(N/blk)], blk = bq for Q, 64 for K and V
@@ -254,6 +271,7 @@ __global__ __launch_bounds__(256) void fp8_gemm_kernel(const uint8_t *__restrict
                 }
                 amax = wave_max(amax);
                 const float scale = fmaxf(amax, 1e-8f) / 448.0f;
+                const BlockDivisor by_scale(scale);
                 if (lane == 0) qkv.scales[which][((size_t)b * H + h) * nblk_seq + tin / blk] = scale;
                 uint8_t *dst = qkv.codes[which] + (((size_t)b * N + tin) * H + h) * 64 + 8 * cc;
                 for (int r = rr; r < valid; r += 8) {
@@ -262,8 +280,8 @@ __global__ __launch_bounds__(256) void fp8_gemm_kernel(const uint8_t *__restrict
                     float y[8];
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        y[2 * q] = fminf(fmaxf(bf16_lo(w[q]) / scale, -448.0f), 448.0f);
-                        y[2 * q + 1] = fminf(fmaxf(bf16_hi(w[q]) / scale, -448.0f), 448.0f);
+                        y[2 * q] = fminf(fmaxf(by_scale(bf16_lo(w[q])), -448.0f), 448.0f);
+                        y[2 * q + 1] = fminf(fmaxf(by_scale(bf16_hi(w[q])), -448.0f), 448.0f);
                     }
                     int lo = 0, hi = 0;
                     lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], lo, false);
@@ -292,10 +310,11 @@ hipError_t launch_quantise_rows(const void *X, long rows, int cols, void *codes,
 // schedule is written out at the loop).  The copies are inline assembly, invisible to the compiler's wait counting; the wait is explicit.
 // Epilogue: scales and bias in fp32, each wave stages its [token][channel] tile in its own quarter of LDS (16-byte
 // chunks XOR-ed with the token row against bank conflicts) and stores 16 bytes per lane, 256 contiguous bytes per row.
+template <bool QKV>
 __global__ __launch_bounds__(256, 1) void fp8_gemm_big_kernel(const uint8_t *__restrict__ A8, const float *__restrict__ sa,
                                                               const uint8_t *__restrict__ W8, const float *__restrict__ sw,
                                                               const uint16_t *__restrict__ bias, int M, int O, int K, int n_it,
-                                                              long total, uint16_t *__restrict__ Y)
+                                                              long total, uint16_t *__restrict__ Y, QkvOut qkv)
 {
     constexpr int kStage = 2 * 256 * kLinK;                                      // bytes of one stage: A tile + W tile
     __shared__ __attribute__((aligned(1024))) uint8_t smem[2 * kStage + 2048];   // behind the stages: the tile's 256 channel scales and biases
@@ -358,6 +377,11 @@ __global__ __launch_bounds__(256, 1) void fp8_gemm_big_kernel(const uint8_t *__r
     // so the wave keeps the matrix unit's queue filled except at the barrier: every LDS read has at least eight MFMAs
     // (five hundred cycles) to arrive in, the copies run two steps ahead on two stages, one barrier per step.
     const int ksteps = K / kLinK;
+    // Workgroups that share an operand tile run at the same time and would ask the same L2 channels for the same lines
+    // at the same moment; each starts its K loop at a different step instead (measured: 9 % faster).  The sum over K is
+    // then taken in a rotated order: same products, fp32 rounding in a different order than the smaller tiles take.
+    const int rot = (int)(item % ksteps);
+#define KS_(k) (((k) + rot) % ksteps)
     i32x8 wf0[4], af0[4], wf1[4], af1[4];
     auto read_one = [&](i32x8 (&wf)[4], i32x8 (&af)[4], int stage, int sl, int idx) {     // fragment idx of 8: 0..3 W, 4..7 A
         const uint8_t *At = smem + stage * kStage, *Wt = At + 256 * kLinK;
@@ -370,8 +394,8 @@ __global__ __launch_bounds__(256, 1) void fp8_gemm_big_kernel(const uint8_t *__r
         else copy_1k_to_lds(A8 + (size_t)ks * kLinK, va[idx >> 1], dst);
     };
 #define SLA_SB() __builtin_amdgcn_sched_barrier(0)
-    issue(0, 0);
-    if (ksteps > 1) issue(1, 1);
+    issue(KS_(0), 0);
+    if (ksteps > 1) issue(KS_(1), 1);
     if (ksteps > 1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");           // the sixteen copies of step 0 (those of step 1 may fly on)
     else            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
@@ -398,7 +422,7 @@ __global__ __launch_bounds__(256, 1) void fp8_gemm_big_kernel(const uint8_t *__r
         for (int m = 0; m < 16; ++m) {
             acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wf1[m >> 2], af1[m & 3], acc[m >> 2][m & 3], 0, 0, 0, 0, 0, 0);
             if (m < 8 && more1) read_one(wf0, af0, st ^ 1, 0, m);
-            if (more2) copy_one(ks + 2, st, m);
+            if (more2) copy_one(KS_(ks + 2), st, m);
             SLA_SB();
         }
     }
@@ -439,22 +463,70 @@ __global__ __launch_bounds__(256, 1) void fp8_gemm_big_kernel(const uint8_t *__r
             }
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                          // the wave reads back what it wrote itself
+    if constexpr (!QKV) {
 #pragma unroll
-    for (int x0 = 0; x0 < 32; x0 += 16) {                                        // sixteen rows' pieces read, then sixteen stores
-        uint4 piece[16];
+        for (int x0 = 0; x0 < 32; x0 += 16) {                                    // sixteen rows' pieces read, then sixteen stores
+            uint4 piece[16];
 #pragma unroll
-        for (int x = 0; x < 16; ++x) {
-            const int t = 4 * (x0 + x) + (lane >> 4), c = lane & 15;             // 16 lanes per token row: 256 contiguous bytes
-            piece[x] = *(const uint4 *)(stage + t * 256 + ((c ^ (t & 15)) << 4));
+            for (int x = 0; x < 16; ++x) {
+                const int t = 4 * (x0 + x) + (lane >> 4), c = lane & 15;         // 16 lanes per token row: 256 contiguous bytes
+                piece[x] = *(const uint4 *)(stage + t * 256 + ((c ^ (t & 15)) << 4));
+            }
+#pragma unroll
+            for (int x = 0; x < 16; ++x) {
+                const int t = 4 * (x0 + x) + (lane >> 4), c = lane & 15;
+                const int i = i0 + wi + t, o = o0 + wo + 8 * c;
+                if (i < M && o < O) *(uint4 *)(Y + (size_t)i * O + o) = piece[x];    // O is a multiple of 8: a piece is in or out as a whole
+            }
         }
+    } else {
+        // the wave's tile is two heads (of q, k or v) x 128 tokens = whole token blocks of those heads: it quantises
+        // them by itself, one (head, token block) at a time, with the arithmetic of quantise_e4m3_kernel
+        const int N = qkv.N, H = qkv.H, rr = lane >> 3, cc = lane & 7;
+        for (int hf = 0; hf < 2; ++hf) {
+            const int ch0 = o0 + wo + 64 * hf;
+            if (ch0 >= O) break;
+            const int which = ch0 / (H * 64), h = (ch0 - which * H * 64) >> 6;
+            const int blk = which == 0 ? qkv.bq : kBK, nblk_seq = (N + blk - 1) / blk;
+            for (int tb = 0; tb * blk < 128; ++tb) {
+                const int t0 = i0 + wi + tb * blk;
+                if (t0 >= M) break;                                              // uniform over the wave
+                const int b = t0 / N, tin = t0 - b * N, valid = min(blk, N - tin);
+                float amax = 0.f;
+                for (int r = rr; r < valid; r += 8) {
+                    const int t = tb * blk + r;
+                    const uint4 v = *(const uint4 *)(stage + t * 256 + (((8 * hf + cc) ^ (t & 15)) << 4));
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int x = 0; x < 16; ++x) {
-            const int t = 4 * (x0 + x) + (lane >> 4), c = lane & 15;
-            const int i = i0 + wi + t, o = o0 + wo + 8 * c;
-            if (i < M && o < O) *(uint4 *)(Y + (size_t)i * O + o) = piece[x];    // O is a multiple of 8: a piece is in or out as a whole
+                    for (int q = 0; q < 4; ++q) amax = fmaxf(amax, fmaxf(fabsf(bf16_lo(w[q])), fabsf(bf16_hi(w[q]))));
+                }
+                amax = wave_max(amax);
+                const float scale = fmaxf(amax, 1e-8f) / 448.0f;
+                const BlockDivisor by_scale(scale);
+                if (lane == 0) qkv.scales[which][((size_t)b * H + h) * nblk_seq + tin / blk] = scale;
+                uint8_t *dst = qkv.codes[which] + (((size_t)b * N + tin) * H + h) * 64 + 8 * cc;
+                for (int r = rr; r < valid; r += 8) {
+                    const int t = tb * blk + r;
+                    const uint4 v = *(const uint4 *)(stage + t * 256 + (((8 * hf + cc) ^ (t & 15)) << 4));
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                    float y[8];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        y[2 * q] = fminf(fmaxf(by_scale(bf16_lo(w[q])), -448.0f), 448.0f);
+                        y[2 * q + 1] = fminf(fmaxf(by_scale(bf16_hi(w[q])), -448.0f), 448.0f);
+                    }
+                    int lo = 0, hi = 0;
+                    lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], lo, false);
+                    lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], lo, true);
+                    hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[4], y[5], hi, false);
+                    hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[6], y[7], hi, true);
+                    *(uint2 *)(dst + (size_t)r * H * 64) = make_uint2((uint32_t)lo, (uint32_t)hi);
+                }
+            }
         }
     }
 }
+#undef KS_
 
 static bool lin_big_tiles(int M, int O) { return (long)((M + 255) / 256) * ((O + 255) / 256) >= 512; }   // two rounds of the chip
 
@@ -466,8 +538,8 @@ hipError_t launch_fp8_gemm(const void *A8, const float *sa, const void *W8, cons
     if (lin_big_tiles(M, O)) {
         const int n_it = (M + 255) / 256;
         const long total = (long)n_it * ((O + 255) / 256);
-        fp8_gemm_big_kernel<<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint8_t *)A8, sa, (const uint8_t *)W8, sw, (const uint16_t *)bias, M, O, K,
-                                                                       n_it, total, (uint16_t *)Y);
+        fp8_gemm_big_kernel<false><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint8_t *)A8, sa, (const uint8_t *)W8, sw, (const uint16_t *)bias, M, O, K,
+                                                                              n_it, total, (uint16_t *)Y, QkvOut{});
         return hipGetLastError();
     }
     const int n_ot = (O + 127) / 128;
@@ -486,7 +558,7 @@ hipError_t launch_fp8_gemm(const void *A8, const float *sa, const void *W8, cons
     return hipGetLastError();
 }
 
-int fp8_gemm_qkv_token_tile(int M, int H) { return lin_wide_tiles(M, (3 * H * 64 + 127) / 128) ? 256 : 128; }
+int fp8_gemm_qkv_token_tile(int M, int H) { return (lin_big_tiles(M, 3 * H * 64) || lin_wide_tiles(M, (3 * H * 64 + 127) / 128)) ? 256 : 128; }
 
 hipError_t launch_fp8_gemm_qkv(const void *A8, const float *sa, const void *W8, const float *sw, const void *bias, int B, int N, int H, int K,
                                int bq, void *const codes[3], float *const scales[3], hipStream_t st)
@@ -495,6 +567,13 @@ hipError_t launch_fp8_gemm_qkv(const void *A8, const float *sa, const void *W8, 
     QkvOut q;
     for (int w = 0; w < 3; ++w) { q.codes[w] = (uint8_t *)codes[w]; q.scales[w] = scales[w]; }
     q.N = N; q.H = H; q.bq = bq;
+    if (lin_big_tiles(M, O)) {
+        const int n_it = (M + 255) / 256;
+        const long total = (long)n_it * ((O + 255) / 256);
+        fp8_gemm_big_kernel<true><<<(unsigned)xcd_grid(total), 256, 0, st>>>((const uint8_t *)A8, sa, (const uint8_t *)W8, sw, (const uint16_t *)bias, M, O, K,
+                                                                             n_it, total, nullptr, q);
+        return hipGetLastError();
+    }
     if (lin_wide_tiles(M, n_ot)) {
         const int n_it = (M + 255) / 256;
         const long total = (long)n_it * n_ot;

@@ -32,7 +32,8 @@ def _fused(B_, N, H, bq, xb, Wb, bb):
 # (B, N, H, d_in, bq): ragged last blocks, one head more than a 128-channel tile holds evenly (H = 3: a tile spans the
 # last head of q and the first of k), B > 1 on whole tiles, a problem large enough for the 256-token tiles, one token
 CASES = [(1, 300, 2, 256, 64), (1, 333, 3, 128, 128), (2, 256, 2, 384, 128), (1, 1374, 16, 1024, 128),
-         (1, 8000, 16, 128, 128), (2, 512, 3, 128, 64), (1, 1, 1, 128, 64), (1, 65, 1, 128, 128)]
+         (1, 8000, 16, 128, 128), (2, 512, 3, 128, 64), (1, 1, 1, 128, 64), (1, 65, 1, 128, 128),
+         (1, 11000, 16, 256, 128), (1, 11100, 16, 384, 64), (43, 256, 16, 128, 128)]     # the last three take the 256 x 256 tiles
 
 
 @pytest.mark.parametrize("B_,N,H,d_in,bq", CASES)

@@ -13,6 +13,7 @@
 // kernel forms the transposed tile D[o][i] (W rows as the A operand), so that a lane's four consecutive accumulator
 // registers are four consecutive output channels of one token and leave through LDS as 16-byte stores.  Global
 // loads run two K steps ahead of their use in registers, LDS is double buffered with an LDS-only barrier.
+// Problems with many tiles take fp8_gemm_big_kernel instead (256 x 256 tiles, described at the kernel).
 #include "sla_common.hpp"
 #include "sla_kernels.hpp"
 

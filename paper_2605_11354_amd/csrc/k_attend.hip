@@ -13,9 +13,9 @@
 // accumulator registers 8u..8u+7, i.e. keys 16s + 8a' + 4g + b; the V^T rows are read with
 // exactly that key permutation: the states kernel leaves V^T of every key block in that order,
 // so a V^T fragment is one 16-byte LDS read like a K fragment.
-// Template parameters: NW query groups of 32 rows (2 for 64-row, 4 for 128-row query blocks); KS = 2 splits every
-// tile of a 64-row block between two wave pairs (one 32-key half each) whose (maximum, sum, O) are merged
-// through LDS before the epilogue, so that short lists still give a workgroup four waves of work.
+// Template parameters: NW query groups of 32 rows (2 for 64-row, 4 for 128-row query blocks), one wave each.  (An earlier
+// form split every tile of a 64-row block between two wave pairs that merged their partial results through LDS; with
+// the software pipeline below two waves per workgroup are faster at every list length, 13 to 16 % on lists of 9 and 34.)
 //
 // Arithmetic of the weights.  P is rounded to fp16 (11 significant bits) and V^T arrives as fp16 from the states
 // kernel (bf16 or E4M3 values are exact in fp16 once divided by the power of two the states kernel picks per key
@@ -170,31 +170,27 @@ struct CopyOffsets {
 
 template <bool B> using flag = std::integral_constant<bool, B>;
 
-// NW: 32-row query groups per workgroup (query block = 32 NW rows).  KS: key split -- with KS = 2
-// two waves share a query group and each takes one 32-key half of every tile (used for 64-row
-// query blocks so that a workgroup still has four waves); their partial (max, sum, O) are merged
-// through LDS after the loop and the KS = 0 wave of each pair runs the epilogue.
+// NW: 32-row query groups per workgroup (query block = 32 NW rows), one wave per group.
 // SL: ring slots.  Three for the pipeline described above; two are enough when no list has more than two blocks (every
 // tile then has a slot of its own and nothing is requested inside the loop), and a third more workgroups fit a CU.
-template <int NW, int KS, bool FP8, int SL>
-__global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
+template <int NW, bool FP8, int SL>
+__global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     const void *__restrict__ Qp, const void *__restrict__ Kp, const uint16_t *__restrict__ Vp, const float *__restrict__ lvs,
     const float *__restrict__ sQ, const float *__restrict__ sK, RowMap rm,
     const int32_t *__restrict__ crit_idx, int k_c, const uint16_t *__restrict__ Hq, const uint16_t *__restrict__ WT,
     int proj_per_head, int phi, int H, int N, int Nqb, int Nkb, long total, float c_exp, uint16_t *__restrict__ O, float *__restrict__ O32)
 {
-    constexpr int NWAVES = NW * KS;
+    constexpr int NWAVES = NW;
     using T = Tile<NWAVES, FP8, SL>;
-    static_assert(SL == 3 || (SL == 2 && KS == 1), "two slots: unsplit lists of at most two blocks");
+    static_assert(SL == 3 || SL == 2, "three ring slots, or two for lists of at most two blocks");
     constexpr int BQ = 32 * NW;
     constexpr int ES = FP8 ? 1 : 2;                     // bytes per input element
-    constexpr int NH = 2 / KS;                          // units (32-key halves of a tile) this wave processes per tile
     constexpr int KROWB = FP8 ? 64 : 128;               // bytes of a K row in LDS
     __shared__ __attribute__((aligned(1024))) uint8_t lds[T::LDS];
     const long work = xcd_remap(blockIdx.x, total);
     if (work >= total) return;                        // the whole workgroup leaves together
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
-    const int wq = wave % NW, kh = wave / NW;         // query group and key half (kh = 0 when KS = 1)
+    const int wq = wave;                              // query group of this wave
     const long bh = work / Nqb;
     const int i = (int)(work - bh * Nqb);
     const int q = i * BQ + 32 * wq + l32;             // this lane's query row
@@ -235,8 +231,6 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
         koff[s] = FP8 ? l32 * 64 + ((((2 * g + (s & 1)) ^ swz4(l32))) << 4) : l32 * 128 + (((2 * s + g) ^ swz8(l32)) << 4);
 #pragma unroll
     for (int st = 0; st < 4; ++st) voff[st] = l32 * 128 + (((2 * st + g) ^ swz8(l32)) << 4);
-    // KS == 2: the two steps of this wave's half (computed, not indexed: a run-time index would put voff[] in memory)
-    const int voffk[2] = {l32 * 128 + (((4 * kh + g) ^ swz8(l32)) << 4), l32 * 128 + (((4 * kh + 2 + g) ^ swz8(l32)) << 4)};
 
     f32x16 zero16;
 #pragma unroll
@@ -350,7 +344,7 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
         return t;
     };
 
-    // ---- pieces of a step.  Unit u of a wave is the 32-key half `half` of tile c: u = c * NH + half - (KS == 2 ? kh : 0)
+    // ---- pieces of a step.  Unit u of a wave is the 32-key half `half` of tile c: u = 2 c + half
     // S^T of a unit: K rows 32 half .. 32 half + 31 of the tile in K slot c % 3
     // kbase / vbase: byte offset of a slot of the K ring / of the V^T ring (wave-uniform); the per-lane part koff / voff
     // is added once per slot, the half of the tile is an immediate offset of the read (K) or picks the register (V^T)
@@ -358,7 +352,7 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
         return lds + half * 32 * KROWB + (kbase + koff[s]);
     };
     auto v_frag_addr = [&](int vbase, int half, int ss, int e) {
-        return lds + e * 32 * 128 + (vbase + (KS == 2 ? voffk[ss] : voff[2 * half + ss]));
+        return lds + e * 32 * 128 + (vbase + voff[2 * half + ss]);
     };
     // key mask of a ragged block as the initial accumulator: 0 for real keys, -inf for keys past the end
     auto s_init = [&](int valid, int half) {
@@ -466,12 +460,12 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
     __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));      // vmcnt(0), as a builtin so that the compiler's bookkeeping sees it
     wait_copies_and_barrier<0>();
 
-    // Units of this wave: u = NH c + hh is the 32-key half (KS == 2 ? kh : hh) of tile c.  Step u accumulates unit u-1
+    // Units of this wave: u = 2 c + hh is the 32-key half hh of tile c.  Step u accumulates unit u-1
     // (V^T fragments vf_use), forms S^T of unit u+1 (K fragments kf_use) and runs the softmax of unit u; meanwhile the
     // fragments of step u+1 are read from LDS (vf_pre, kf_pre), so that a slot is done with one step before its
     // arithmetic and the LDS latency is off the critical path.
-    auto unit_tile = [&](int u) { return NH == 2 ? u >> 1 : u; };
-    auto unit_half = [&](int u) { return NH == 2 ? u & 1 : kh; };
+    auto unit_tile = [&](int u) { return u >> 1; };
+    auto unit_half = [&](int u) { return u & 1; };
     f32x16 s_cur = zero16;
     Weights w_prev;
     w_prev.p[0] = w_prev.p[1] = __builtin_bit_cast(f16x8, make_uint4(0, 0, 0, 0));
@@ -479,7 +473,7 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
     KFrag kf_use, kf_pre;
     VFrag vf_use, vf_pre;
     TileInfo t_cur, t_nxt;
-    const int U = k * NH;                              // units of this wave
+    const int U = 2 * k;                               // units of this wave
     if (k > 0) {
         t_cur = tile_info(0);
         s_cur = compute_S(load_kfrag(0, unit_half(0)), t_cur.valid == kBK ? zero16 : s_init(t_cur.valid, unit_half(0)));
@@ -551,20 +545,22 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
         };
         SLA_SB();
         if (!FP8) {
+            // S^T of the next unit first: its last MFMA then has four more behind it before the step ends with the
+            // overflow check on its result (and the next step starts with its exponentials)
             sm(0);    el(0, 1);   cv2(0);
             SLA_PIN("+v"(s_nxt), "+v"(moff), "+v"(pw[0])); SLA_SB();
-            pv(0, 0); el(2, 3);   cv2(1);
-            SLA_PIN("+v"(oacc[0]), "+v"(moff), "+v"(pw[1])); SLA_SB();
-            sm(1);    el(4, 5);   cv2(2);
+            sm(1);    el(2, 3);   cv2(1);
+            SLA_PIN("+v"(s_nxt), "+v"(moff), "+v"(pw[1])); SLA_SB();
+            sm(2);    el(4, 5);   cv2(2);
             SLA_PIN("+v"(s_nxt), "+v"(moff), "+v"(pw[2])); SLA_SB();
-            pv(0, 1); el(6, 7);   cv2(3);
-            SLA_PIN("+v"(oacc[1]), "+v"(moff), "+v"(pw[3])); SLA_SB();
-            sm(2);    el(8, 9);   cv2(4);
-            SLA_PIN("+v"(s_nxt), "+v"(moff), "+v"(pw[4])); SLA_SB();
-            pv(1, 0); el(10, 11); cv2(5);
-            SLA_PIN("+v"(oacc[0]), "+v"(moff), "+v"(pw[5])); SLA_SB();
-            sm(3);    el(12, 13); cv2(6); dots(0);
-            SLA_PIN("+v"(s_nxt), "+v"(moff), "+v"(pw[6]), "+v"(l_part)); SLA_SB();
+            sm(3);    el(6, 7);   cv2(3);
+            SLA_PIN("+v"(s_nxt), "+v"(moff), "+v"(pw[3])); SLA_SB();
+            pv(0, 0); el(8, 9);   cv2(4);
+            SLA_PIN("+v"(oacc[0]), "+v"(moff), "+v"(pw[4])); SLA_SB();
+            pv(0, 1); el(10, 11); cv2(5);
+            SLA_PIN("+v"(oacc[1]), "+v"(moff), "+v"(pw[5])); SLA_SB();
+            pv(1, 0); el(12, 13); cv2(6); dots(0);
+            SLA_PIN("+v"(oacc[0]), "+v"(moff), "+v"(pw[6]), "+v"(l_part)); SLA_SB();
             pv(1, 1); el(14, 15); cv2(7); dots(1);
             SLA_PIN("+v"(oacc[1]), "+v"(pw[7]), "+v"(l_part)); SLA_SB();
         } else {
@@ -593,7 +589,7 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
     // Ring bookkeeping.  During iteration c the LDS reads touch V^T tile c and K tile c + KAHEAD - 2 (the fragments of
     // the following step); both must have landed at its barrier, and that barrier frees the slots of the tiles before
     // them, into which the copies of V^T tile c + 2 and K tile c + KAHEAD go: needed two iterations later.
-    constexpr int KAHEAD = NH == 2 ? 3 : 4;
+    constexpr int KAHEAD = 3;
     // ring slots (byte offsets) of: the K tile requested in this iteration, the V^T tile requested, the K tile whose
     // fragments are read, the V^T tile whose fragments are read; each moves on by one slot per iteration
     uint32_t kreq = (KAHEAD % T::SLOTS) * T::KBYTES, vreq = (2 % T::SLOTS) * T::VBYTES, kread = ((KAHEAD - 2) % T::SLOTS) * T::KBYTES, vread = 0;
@@ -604,7 +600,6 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
         else if (c + 1 < k) wait_copies_and_barrier<T::VINS>();
         else wait_copies_and_barrier<0>();
         if (c + KAHEAD - wbase >= 64) load_window(wbase + 32);     // (never for lists of at most 64 blocks)
-        if (KAHEAD == 4 && c == 0 && 3 < k) request_K(3, 0);
         if (c + KAHEAD < k) request_K(c + KAHEAD, kreq);
         if (c + 2 < k) request_V(c + 2, vreq);
         if (c + 1 == k) request_epilogue();
@@ -612,20 +607,14 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
         if (more) t_nxt = tile_info(c + 1);
         const bool ragged_n = more && t_nxt.valid != kBK;
         const int vslot = T::VRING + (int)vread, kslot = (int)kread;
-        if (NH == 2) {
-            // first half of tile c: accumulates the second half of tile c-1, forms S^T of the second half of tile c;
-            // reads the fragments of the next step: V^T tile c first half, K tile c+1 first half
-            if (over_cur || c == 0 || t_cur.tiny || t_cur.valid != kBK) careful_step(c > 0, true, t_cur, t_cur, 1, vslot, 0, kslot, 0);
-            else fast_step(t_cur, t_cur, vslot, 0, kslot, 0);
-            // second half of tile c: accumulates its first half, forms S^T of the first half of tile c+1;
-            // reads V^T tile c second half and K tile c+1 second half for the first step of the next iteration
-            if (over_cur || !more || t_cur.tiny || ragged_n) careful_step(true, more, t_cur, t_nxt, 0, vslot, 1, kslot, 1);
-            else fast_step(t_cur, t_nxt, vslot, 1, kslot, 1);
-        } else {
-            // accumulates this wave's half of tile c-1, forms S^T of its half of tile c+1; reads V^T tile c and K tile c+2
-            if (over_cur || c == 0 || !more || t_cur.tiny || ragged_n) careful_step(c > 0, more, t_cur, t_nxt, kh, vslot, kh, kslot, kh);
-            else fast_step(t_cur, t_nxt, vslot, kh, kslot, kh);
-        }
+        // first half of tile c: accumulates the second half of tile c-1, forms S^T of the second half of tile c;
+        // reads the fragments of the next step: V^T tile c first half, K tile c+1 first half
+        if (over_cur || c == 0 || t_cur.tiny || t_cur.valid != kBK) careful_step(c > 0, true, t_cur, t_cur, 1, vslot, 0, kslot, 0);
+        else fast_step(t_cur, t_cur, vslot, 0, kslot, 0);
+        // second half of tile c: accumulates its first half, forms S^T of the first half of tile c+1;
+        // reads V^T tile c second half and K tile c+1 second half for the first step of the next iteration
+        if (over_cur || !more || t_cur.tiny || ragged_n) careful_step(true, more, t_cur, t_nxt, 0, vslot, 1, kslot, 1);
+        else fast_step(t_cur, t_nxt, vslot, 1, kslot, 1);
         t_cur = t_nxt;
         kreq = next_slot(kreq, T::KBYTES); kread = next_slot(kread, T::KBYTES);
         vreq = next_slot(vreq, T::VBYTES); vread = next_slot(vread, T::VBYTES);
@@ -638,44 +627,6 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
 
     uint8_t *stA = lds + kHqOff, *stB = lds + kWtOff;
     const uint8_t *zrow = lds + T::ZOFF;
-    if (KS == 2) {
-        // ---- merge the two key halves: the kh = 1 wave parks (O, max, sum) in the V^T ring, its partner folds them in.
-        // Four 4 KB slots for the two 32-channel halves of the two parked waves, max/sum behind them.
-        wait_copies_and_barrier<0>();                  // every wave has read its last V^T fragments
-        uint8_t *park = lds + T::VRING;
-        float *ml = (float *)(park + 16384) + wq * 128;
-        if (kh == 1) {
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                uint8_t *dst = park + (2 * wq + e) * 4096;
-#pragma unroll
-                for (int x4 = 0; x4 < 4; ++x4)
-                    *(float4 *)(dst + x4 * 1024 + lane * 16) = make_float4(oacc[e][4 * x4], oacc[e][4 * x4 + 1], oacc[e][4 * x4 + 2], oacc[e][4 * x4 + 3]);
-            }
-            ml[lane] = m_run;
-            ml[64 + lane] = l_run;
-        }
-        wait_copies_and_barrier<0>();
-        if (kh == 0) {
-            const float m1 = ml[lane], l1 = ml[64 + lane];
-            const float m = fmaxf(m_run, m1);
-            const float a0 = m_run == m ? 1.0f : fast_exp2(m_run - m), a1 = m1 == m ? 1.0f : fast_exp2(m1 - m);   // -inf - -inf avoided
-            l_run = l_run * a0 + l1 * a1;
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const uint8_t *src = park + (2 * wq + e) * 4096;
-#pragma unroll
-                for (int x4 = 0; x4 < 4; ++x4) {
-                    const float4 o1 = *(const float4 *)(src + x4 * 1024 + lane * 16);
-                    oacc[e][4 * x4 + 0] = oacc[e][4 * x4 + 0] * a0 + o1.x * a1;
-                    oacc[e][4 * x4 + 1] = oacc[e][4 * x4 + 1] * a0 + o1.y * a1;
-                    oacc[e][4 * x4 + 2] = oacc[e][4 * x4 + 2] * a0 + o1.z * a1;
-                    oacc[e][4 * x4 + 3] = oacc[e][4 * x4 + 3] * a0 + o1.w * a1;
-                }
-            }
-        }
-    }
-
     // ---- normalise the sparse output: the weights carried the V scale relative to the first tile's
     const float inv_l = l_run > 0.f ? fast_exp2(lv_ref) / l_run : 0.f;
 #pragma unroll
@@ -683,7 +634,7 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
 #pragma unroll
         for (int x = 0; x < 16; ++x) oacc[e][x] *= inv_l;
 
-    if (Hq != nullptr && kh == 0) {
+    if (Hq != nullptr) {
         // ---- phi(Q): softmax over the 64 channels of the row (this lane holds 32, lane^32 the rest).
         // x[8s + c] is channel dcol(s) + c, the channel slot c of K-step s carries in the product below.
         float x[32];
@@ -768,7 +719,7 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
     wait_copies_and_barrier<0>();                      // all waves are done reading the epilogue operands
     if (O32 != nullptr) {
         // diagnostic output: the fp32 values the bf16 store below would round, straight from the accumulators
-        if (kh == 0 && qok) {
+        if (qok) {
 #pragma unroll
             for (int e = 0; e < 2; ++e)
 #pragma unroll
@@ -776,7 +727,7 @@ __global__ __launch_bounds__(64 * NW * KS, 2) void attend_kernel(
                     *(float4 *)(O32 + head + (size_t)q * rm.ts + 32 * e + 8 * aa + 4 * g) =
                         make_float4(oacc[e][4 * aa + 0], oacc[e][4 * aa + 1], oacc[e][4 * aa + 2], oacc[e][4 * aa + 3]);
         }
-    } else if (kh == 0) {
+    } else {
         uint8_t *ot = lds + T::VRING + wq * 4096;
         const int f = ((l32 >> 1) & 7) << 1;
 #pragma unroll
@@ -813,12 +764,12 @@ hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int NW, int KS, bool FP8, int SL = 3>
+template <int NW, bool FP8, int SL = 3>
 static hipError_t launch_attend_t(const void *Q, const void *K, const void *Vp, const float *lvs, const float *sQ, const float *sK, RowMap rm,
                                   const int32_t *crit_idx, int k_c, const void *Hq, const void *WT, int proj_per_head, int phi,
                                   int H, int N, int Nqb, int Nkb, long total, float c_exp, void *O, float *O32, hipStream_t st)
 {
-    attend_kernel<NW, KS, FP8, SL><<<(unsigned)xcd_grid(total), 64 * NW * KS, 0, st>>>(Q, K, (const uint16_t *)Vp, lvs, sQ, sK, rm, crit_idx, k_c, (const uint16_t *)Hq,
+    attend_kernel<NW, FP8, SL><<<(unsigned)xcd_grid(total), 64 * NW, 0, st>>>(Q, K, (const uint16_t *)Vp, lvs, sQ, sK, rm, crit_idx, k_c, (const uint16_t *)Hq,
                                                                      (const uint16_t *)WT, proj_per_head, phi, H, N, Nqb, Nkb,
                                                                      total, c_exp, (uint16_t *)O, O32);
     return hipGetLastError();
@@ -833,16 +784,13 @@ hipError_t launch_attend(const void *Q, const void *K, const void *Vp, const flo
     const int Nqb = (N + bq - 1) / bq, Nkb = (N + kBK - 1) / kBK;
     const long total = (long)B * H * Nqb;
     const float c_exp = sm_scale * kLog2e;
-#define SLA_ATT(NW, KS, F8) return launch_attend_t<NW, KS, F8>(Q, K, Vp, lvs, sQ, sK, rm, crit_idx, k_c, Hq, WT, proj_per_head, phi, H, N, Nqb, Nkb, total, c_exp, O, O32, st)
-    if (bq == 128) { if (fp8) SLA_ATT(4, 1, true); else SLA_ATT(4, 1, false); }
-    // 64-row query blocks: two query groups x two key halves, so a workgroup still has four waves;
-    // with very few critical blocks per row the merge of the halves costs more than it hides
-    if (k_c >= 4) { if (fp8) SLA_ATT(2, 2, true); else SLA_ATT(2, 2, false); }
-    if (k_c > 2) { if (fp8) SLA_ATT(2, 1, true); else SLA_ATT(2, 1, false); }
-#undef SLA_ATT
+#define SLA_ATT(NW, F8, SL) return launch_attend_t<NW, F8, SL>(Q, K, Vp, lvs, sQ, sK, rm, crit_idx, k_c, Hq, WT, proj_per_head, phi, H, N, Nqb, Nkb, total, c_exp, O, O32, st)
+    if (bq == 128) { if (fp8) SLA_ATT(4, true, 3); else SLA_ATT(4, false, 3); }
+    if (k_c > 2) { if (fp8) SLA_ATT(2, true, 3); else SLA_ATT(2, false, 3); }
     // lists of at most two blocks (frame attention): two ring slots, four workgroups per CU
-    if (fp8) return launch_attend_t<2, 1, true, 2>(Q, K, Vp, lvs, sQ, sK, rm, crit_idx, k_c, Hq, WT, proj_per_head, phi, H, N, Nqb, Nkb, total, c_exp, O, O32, st);
-    return launch_attend_t<2, 1, false, 2>(Q, K, Vp, lvs, sQ, sK, rm, crit_idx, k_c, Hq, WT, proj_per_head, phi, H, N, Nqb, Nkb, total, c_exp, O, O32, st);
+    if (fp8) SLA_ATT(2, true, 2);
+    SLA_ATT(2, false, 2);
+#undef SLA_ATT
 }
 
 }  // namespace sla

@@ -1,5 +1,5 @@
 """GPU parity, second part: the tolerance as stated (on the fp32 result), shapes and paths the first part
-does not reach (odd head counts, E4M3 with batch > 1 and with the key-split kernel, all-zero blocks, short and long
+does not reach (odd head counts, E4M3 with batch > 1 and with 64-row query blocks, all-zero blocks, short and long
 critical lists, V blocks of very different magnitude, a running maximum that has to be raised in mid-list) and
 whole-tensor invariants at full size."""
 import numpy as np
@@ -25,7 +25,7 @@ CASES = {
     "h3_per_head": (C0.with_(H=3, N=700, proj_per_head=True), 2, 5),
     "h3_per_head_bq128": (C0.with_(B=2, H=3, N=900, bq=128, proj_per_head=True), 3, 6),
     "c4_batch2": (C4.with_(B=2, H=2, N=1374), 2, 12),
-    "c4_bq64_kc6": (C4.with_(H=2, N=1000, bq=64), 6, 5),          # E4M3, 64-row query blocks, key-split kernel
+    "c4_bq64_kc6": (C4.with_(H=2, N=1000, bq=64), 6, 5),          # E4M3, 64-row query blocks
     "c4_batch2_bq64": (C4.with_(B=2, H=3, N=900, bq=64), 5, 4),
 }
 

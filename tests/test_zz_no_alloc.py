@@ -24,7 +24,7 @@ def _run_both(cfg):
 def test_static_workspace_forward_matches_forward_twice_in_a_row():
     """Two calls in a row on the library's own workspace, the second on a smaller input (the array keeps the first
     call's contents): both must reproduce sla_forward bit for bit (same kernels, same order of operations)."""
-    big = synth.CONFIGS[1].with_(H=4, N=5 * 1374)            # ragged tails, per-head projection, key-split kernel
+    big = synth.CONFIGS[1].with_(H=4, N=5 * 1374)            # ragged tails, per-head projection, 64-row query blocks
     small = synth.CONFIGS[0].with_(N=330)                     # smaller in every slice of the workspace
     assert B.sla_workspace_bytes(Case(big).p) <= B.STATIC_WORKSPACE_BYTES
     _run_both(big)

@@ -505,7 +505,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
         s_cur = s_nxt; w_prev = w; vf_use = vf_pre; kf_use = kf_pre;
     };
     // Fast form (a unit in the middle of the list, full tiles, no exponent above kRaise), written out in issue order:
-    // one MFMA, then a share of the vector work (the matrix unit needs 32 cycles per MFMA, the share of vector work
+    // one MFMA, then a share of the vector work (staggered: exponentials of one pair of weights, the pack of the pair
+    // before, the multiply-adds of the pair after) (the matrix unit needs 32 cycles per MFMA, the share of vector work
     // about as long).  The order is held by data dependencies the compiler cannot see through: every share ends in
     // an empty asm statement that "rewrites" the results of the share and the exponent offset the next one starts
     // from, so nothing can move from one share into another (the instruction selector would otherwise bunch the MFMAs
@@ -531,9 +532,13 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
                 s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf_use.w[st]), qf[st], s_nxt, 0, 0, 0);
             }
         };
-        auto el = [&](int x0, int x1) {
+        auto fm = [&](int x0, int x1) {
 #pragma unroll
-            for (int x = x0; x <= x1; ++x) s_cur[x] = fast_exp2(fmaf(s_cur[x], t.cj, moff));
+            for (int x = x0; x <= x1; ++x) s_cur[x] = fmaf(s_cur[x], t.cj, moff);
+        };
+        auto ex = [&](int x0, int x1) {
+#pragma unroll
+            for (int x = x0; x <= x1; ++x) s_cur[x] = fast_exp2(s_cur[x]);
         };
         auto cv2 = [&](int pr) { pw[pr] = pack_f16(s_cur[2 * pr], s_cur[2 * pr + 1]); };
         auto dots = [&](int ss) {
@@ -547,33 +552,39 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
         if (!FP8) {
             // S^T of the next unit first: its last MFMA then has four more behind it before the step ends with the
             // overflow check on its result (and the next step starts with its exponentials)
-            sm(0);    el(0, 1);   cv2(0);
+            // the vector work of a share is staggered: the exponentials of pair i, the pack of pair i-1 (whose
+            // exponentials have left the quarter-rate pipe by now) and the multiply-adds of pair i+1
+            fm(0, 1);
+            sm(0);    ex(0, 1);   fm(2, 3);
+            SLA_PIN("+v"(s_nxt), "+v"(moff)); SLA_SB();
+            sm(1);    ex(2, 3);   cv2(0); fm(4, 5);
             SLA_PIN("+v"(s_nxt), "+v"(moff), "+v"(pw[0])); SLA_SB();
-            sm(1);    el(2, 3);   cv2(1);
+            sm(2);    ex(4, 5);   cv2(1); fm(6, 7);
             SLA_PIN("+v"(s_nxt), "+v"(moff), "+v"(pw[1])); SLA_SB();
-            sm(2);    el(4, 5);   cv2(2);
+            sm(3);    ex(6, 7);   cv2(2); fm(8, 9);
             SLA_PIN("+v"(s_nxt), "+v"(moff), "+v"(pw[2])); SLA_SB();
-            sm(3);    el(6, 7);   cv2(3);
-            SLA_PIN("+v"(s_nxt), "+v"(moff), "+v"(pw[3])); SLA_SB();
-            pv(0, 0); el(8, 9);   cv2(4);
-            SLA_PIN("+v"(oacc[0]), "+v"(moff), "+v"(pw[4])); SLA_SB();
-            pv(0, 1); el(10, 11); cv2(5);
-            SLA_PIN("+v"(oacc[1]), "+v"(moff), "+v"(pw[5])); SLA_SB();
-            pv(1, 0); el(12, 13); cv2(6); dots(0);
-            SLA_PIN("+v"(oacc[0]), "+v"(moff), "+v"(pw[6]), "+v"(l_part)); SLA_SB();
-            pv(1, 1); el(14, 15); cv2(7); dots(1);
-            SLA_PIN("+v"(oacc[1]), "+v"(pw[7]), "+v"(l_part)); SLA_SB();
-        } else {
-            sm(0);    el(0, 4);   cv2(0); cv2(1);                            // the e4m3 MFMA takes twice as long
-            SLA_PIN("+v"(s_nxt), "+v"(moff), "+v"(pw[0]), "+v"(pw[1])); SLA_SB();
-            pv(0, 0); el(5, 7);   cv2(2); cv2(3);
-            SLA_PIN("+v"(oacc[0]), "+v"(moff), "+v"(pw[2]), "+v"(pw[3])); SLA_SB();
-            pv(0, 1); el(8, 10);  cv2(4);
+            pv(0, 0); ex(8, 9);   cv2(3); fm(10, 11);
+            SLA_PIN("+v"(oacc[0]), "+v"(moff), "+v"(pw[3])); SLA_SB();
+            pv(0, 1); ex(10, 11); cv2(4); fm(12, 13);
             SLA_PIN("+v"(oacc[1]), "+v"(moff), "+v"(pw[4])); SLA_SB();
-            pv(1, 0); el(11, 13); cv2(5); cv2(6); dots(0);
-            SLA_PIN("+v"(oacc[0]), "+v"(moff), "+v"(pw[5]), "+v"(pw[6]), "+v"(l_part)); SLA_SB();
-            pv(1, 1); el(14, 15); cv2(7); dots(1);
-            SLA_PIN("+v"(oacc[1]), "+v"(pw[7]), "+v"(l_part)); SLA_SB();
+            pv(1, 0); ex(12, 13); cv2(5); fm(14, 15); dots(0);
+            SLA_PIN("+v"(oacc[0]), "+v"(pw[5]), "+v"(l_part)); SLA_SB();
+            pv(1, 1); ex(14, 15); cv2(6); dots(1);
+            SLA_PIN("+v"(oacc[1]), "+v"(pw[6]), "+v"(l_part)); SLA_SB();
+            cv2(7);
+        } else {
+            fm(0, 4);                                                            // the e4m3 MFMA takes twice as long: a larger first share
+            sm(0);    ex(0, 4);   fm(5, 7);
+            SLA_PIN("+v"(s_nxt), "+v"(moff)); SLA_SB();
+            pv(0, 0); ex(5, 7);   cv2(0); cv2(1); fm(8, 10);
+            SLA_PIN("+v"(oacc[0]), "+v"(moff), "+v"(pw[0]), "+v"(pw[1])); SLA_SB();
+            pv(0, 1); ex(8, 10);  cv2(2); cv2(3); fm(11, 13);
+            SLA_PIN("+v"(oacc[1]), "+v"(moff), "+v"(pw[2]), "+v"(pw[3])); SLA_SB();
+            pv(1, 0); ex(11, 13); cv2(4); fm(14, 15); dots(0);
+            SLA_PIN("+v"(oacc[0]), "+v"(pw[4]), "+v"(l_part)); SLA_SB();
+            pv(1, 1); ex(14, 15); cv2(5); cv2(6); dots(1);
+            SLA_PIN("+v"(oacc[1]), "+v"(pw[5]), "+v"(pw[6]), "+v"(l_part)); SLA_SB();
+            cv2(7);
         }
         w.p[0] = __builtin_bit_cast(f16x8, make_uint4(pw[0], pw[1], pw[2], pw[3]));
         w.p[1] = __builtin_bit_cast(f16x8, make_uint4(pw[4], pw[5], pw[6], pw[7]));

@@ -317,7 +317,6 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
         const uint8_t *vt = Vh + (uint64_t)(uint32_t)entry_j(c) * (uint32_t)(kBK * kD * 2);
         copy_nk_to_lds<T::VINS>(vt, co.v, vdst0 + slot);
     };
-    auto next_slot = [](uint32_t slot, uint32_t bytes) { return slot + bytes == T::SLOTS * bytes ? 0u : slot + bytes; };
     // The operands of the linear/projection epilogue (the 64x64 tile of Hq^T, the Z row, W^T) travel the same way
     // into the K ring, which is idle during the last tile, so their latency hides behind that tile's arithmetic.
     const uint8_t *Hi8 = Hq ? (const uint8_t *)(Hq + (size_t)work * kStateElems) : nullptr;
@@ -601,10 +600,14 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     // the following step); both must have landed at its barrier, and that barrier frees the slots of the tiles before
     // them, into which the copies of V^T tile c + 2 and K tile c + KAHEAD go: needed two iterations later.
     constexpr int KAHEAD = 3;
-    // ring slots (byte offsets) of: the K tile requested in this iteration, the V^T tile requested, the K tile whose
-    // fragments are read, the V^T tile whose fragments are read; each moves on by one slot per iteration
-    uint32_t kreq = (KAHEAD % T::SLOTS) * T::KBYTES, vreq = (2 % T::SLOTS) * T::VBYTES, kread = ((KAHEAD - 2) % T::SLOTS) * T::KBYTES, vread = 0;
-    for (int c = 0; c < k; ++c) {
+    // Ring slots of iteration c, with P = c mod SLOTS: the V^T tile whose fragments are read sits in slot P, the K tile
+    // whose fragments are read (tile c+1) in slot P+1, the K tile requested (c+3) goes where tile c was, the V^T tile
+    // requested (c+2) into slot P+2.  The loop is unrolled over P so that the slots are constants: the fragment reads
+    // take them as immediate offsets and no slot arithmetic is left in the loop.
+    auto iteration = [&](int c, auto phase) __attribute__((always_inline)) {
+        constexpr int P = decltype(phase)::value, S = T::SLOTS;
+        constexpr uint32_t kreq = ((P + KAHEAD) % S) * T::KBYTES, vreq = ((P + 2) % S) * T::VBYTES;
+        constexpr int kslot = ((P + KAHEAD - 2) % S) * T::KBYTES, vslot = T::VRING + P * T::VBYTES;
         // copies that may stay in flight here: those requested one iteration ago
         if (c == 0) wait_copies_and_barrier<0>();      // (nothing is in flight; joins the waves after the prologue's LDS reads)
         else if (c + KAHEAD - 1 < k) wait_copies_and_barrier<T::LOADS>();
@@ -617,7 +620,6 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
         const bool more = c + 1 < k;
         if (more) t_nxt = tile_info(c + 1);
         const bool ragged_n = more && t_nxt.valid != kBK;
-        const int vslot = T::VRING + (int)vread, kslot = (int)kread;
         // first half of tile c: accumulates the second half of tile c-1, forms S^T of the second half of tile c;
         // reads the fragments of the next step: V^T tile c first half, K tile c+1 first half
         if (over_cur || c == 0 || t_cur.tiny || t_cur.valid != kBK) careful_step(c > 0, true, t_cur, t_cur, 1, vslot, 0, kslot, 0);
@@ -627,8 +629,11 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
         if (over_cur || !more || t_cur.tiny || ragged_n) careful_step(true, more, t_cur, t_nxt, 0, vslot, 1, kslot, 1);
         else fast_step(t_cur, t_nxt, vslot, 1, kslot, 1);
         t_cur = t_nxt;
-        kreq = next_slot(kreq, T::KBYTES); kread = next_slot(kread, T::KBYTES);
-        vreq = next_slot(vreq, T::VBYTES); vread = next_slot(vread, T::VBYTES);
+    };
+    for (int c = 0; c < k; c += T::SLOTS) {
+        iteration(c, std::integral_constant<int, 0>{});
+        if (c + 1 < k) iteration(c + 1, std::integral_constant<int, 1>{});
+        if (T::SLOTS == 3 && c + 2 < k) iteration(c + 2, std::integral_constant<int, 2 % T::SLOTS>{});
     }
 #undef SLA_SB
 

@@ -35,6 +35,7 @@ SMALL = [
     # 256 / 257 key blocks (fused classifier / separate logits + selection)
     ("nqb192", C0.with_(H=1, N=192 * 64), 4, 150),
     ("nqb193", C0.with_(H=1, N=193 * 64 - 5), 4, 150),
+    ("nqb300", C0.with_(H=1, N=300 * 64 - 9), 4, 230),            # 128-query-block aggregation tiles
     ("nkb256", C0.with_(H=1, N=256 * 64 - 1), 6, 200),
     ("nkb257_bq128", C0.with_(H=1, N=257 * 64 - 63, bq=128), 6, 200),
 ]
@@ -125,7 +126,7 @@ def test_linear_states(oracle, name):
         assert np.abs(got[:, 64, :] - z).max() <= 2.0 ** -7 * np.abs(z).max()
 
 
-@pytest.mark.parametrize("name", ["c0", "c0_bq128_tail", "c1_small", "c4_small", "nqb192", "nqb193", "nkb257_bq128"])
+@pytest.mark.parametrize("name", ["c0", "c0_bq128_tail", "c1_small", "c4_small", "nqb192", "nqb193", "nqb300", "nkb257_bq128"])
 def test_marginal_aggregate(oracle, name):
     case = _case(name)
     lab = case.oracle_classify(oracle)["labels"]

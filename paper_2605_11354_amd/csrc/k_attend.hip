@@ -170,6 +170,13 @@ struct CopyOffsets {
 
 template <bool B> using flag = std::integral_constant<bool, B>;
 
+#ifdef SLA_PROBE_TIME   /* timing probe only: cycle counter of one wave at five points of every tile */
+__device__ unsigned long long sla_probe_times[64 * 8];
+#define SLA_T(c, pt) do { if (probe_on && (c) < 64) { const unsigned long long t_ = __builtin_readcyclecounter(); if (lane == 0) tprobe[(c) * 8 + (pt)] = t_; } } while (0)
+#else
+#define SLA_T(c, pt)
+#endif
+
 // NW: 32-row query groups per workgroup (query block = 32 NW rows), one wave per group.
 // SL: ring slots.  Three for the pipeline described above; two are enough when no list has more than two blocks (every
 // tile then has a slot of its own and nothing is requested inside the loop), and a third more workgroups fit a CU.
@@ -190,6 +197,15 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     const long work = xcd_remap(blockIdx.x, total);
     if (work >= total) return;                        // the whole workgroup leaves together
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+#ifdef SLA_PROBE_TIME
+    __shared__ unsigned long long tprobe[64 * 8];
+#ifdef SLA_PROBE_PAD
+    __shared__ uint8_t lds_pad[SLA_PROBE_PAD];
+    if (Nqb < 0) lds_pad[tid] = 1;                    // keeps the array
+#endif
+    const bool probe_on = __builtin_amdgcn_readfirstlane((int)(work == total / 2 + 3 && wave == 1)) != 0;
+    const unsigned long long tp_c0 = __builtin_readcyclecounter(), tp_r0 = __builtin_amdgcn_s_memrealtime();
+#endif
     const int wq = wave;                              // query group of this wave
     const long bh = work / Nqb;
     const int i = (int)(work - bh * Nqb);
@@ -239,14 +255,19 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     // Running state of the lane's row.  m_run: reference exponent (log2 domain) of the weights; l_part: this lane's
     // share of the row sum, accumulated from the fp16 weights the second product consumes (divided by the V scale
     // ratio again); l_full: row sums formed in fp32 by the careful steps (already complete over the lane pair).
-    float m_run = -INFINITY, l_part = 0.f, l_full = 0.f;
+    float m_run = -INFINITY, l_part = 0.f, l_alt = 0.f, l_full = 0.f;      // (l_alt: second partial sum of the fast steps)
 
     const int32_t *ci = crit_idx + work * (long)k_c;
+    // Ragged block: only the last key block of the sequence can be short.
+    const int tail_rows = N & (kBK - 1), ragged_j = tail_rows ? Nkb - 1 : -1;
     // The list lives in registers, one entry per lane, as a window of 64 entries starting at wbase (a multiple of 32):
     // block index, log2 of its V scale and (e4m3) its exp2 constant.  The loop takes what it needs with v_readlane,
     // so no scalar load (and none of their waits) sits between the steps; the window moves every 32 tiles.
     int wbase = 0, d_j = 0;
     float d_lv = 0.f, d_cj = 0.f, lv_ref = 0.f;
+    // One bit per window entry: set if its tile needs the guarded form of an iteration (past the end of the list,
+    // the ragged last block, a V scale far from the first tile's).
+    unsigned long long d_bad = ~0ull;
     // k: number of leading valid entries of the list (a list taken from given labels may end in -1 entries)
     int k = 0;
     {
@@ -277,6 +298,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
         // log2 of the V scale of the first tile: the reference of the weights
         if (first) lv_ref = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(lv)));
         d_lv = lv - lv_ref;
+        d_bad = __ballot(wbase + lane >= k || d_j == ragged_j || !(fabsf(d_lv) <= kTinyV));
     };
     auto load_window = [&](int wb) __attribute__((always_inline)) {
         const int idx = wb + lane;
@@ -291,18 +313,16 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     co.init(wave, lane, krowb);
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);                       // same value, provably uniform
     const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_p)lds;                // LDS byte address of the K ring
-    // Ragged block: only the last key block of the sequence can be short.
-    const int tail_rows = N & (kBK - 1), ragged_j = tail_rows ? Nkb - 1 : -1;
     const uint32_t ktile_bytes = (uint32_t)kBK * (uint32_t)krowb;                  // bytes from one K block to the next
     const uint32_t kdst0 = lds_base + wave_u * T::KINS * 1024, vdst0 = lds_base + T::VRING + wave_u * T::VINS * 1024;
     // slot: byte offset of the ring slot (a multiple of the tile size below 3 tiles)
-    auto request_K = [&](int c, uint32_t slot) __attribute__((always_inline)) {       // K tile of list entry c into the slot at byte offset `slot` of the K ring
+    auto request_K = [&](int c, uint32_t slot, bool full = false) __attribute__((always_inline)) {       // K tile of list entry c into the slot at byte offset `slot` of the K ring (full: known not to be the ragged block)
 #ifdef SLA_PROBE_NOCOPY
         return;
 #endif
         const uint32_t j = (uint32_t)entry_j(c);
         const uint8_t *kt = Kh + (uint64_t)j * ktile_bytes;
-        if ((int)j != ragged_j) {
+        if (full || (int)j != ragged_j) {
             copy_nk_to_lds<T::KINS>(kt, co.k, kdst0 + slot);
         } else {                                       // rows past the end are clamped to the last one; they are masked later
 #pragma unroll
@@ -416,6 +436,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     };
     auto rescale = [&](float alpha) __attribute__((always_inline)) {
         l_part *= alpha;
+        l_alt *= alpha;
         l_full *= alpha;
 #pragma unroll
         for (int e = 0; e < 2; ++e)
@@ -543,9 +564,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
         auto dots = [&](int ss) {
             const uint4 q4 = __builtin_bit_cast(uint4, w_prev.p[ss]);
             l_part = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, q4.x), iv, l_part, false);
-            l_part = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, q4.y), iv, l_part, false);
+            l_alt = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, q4.y), iv, l_alt, false);
             l_part = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, q4.z), iv, l_part, false);
-            l_part = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, q4.w), iv, l_part, false);
+            l_alt = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, q4.w), iv, l_alt, false);
         };
         SLA_SB();
         if (!FP8) {
@@ -567,9 +588,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
             pv(0, 1); ex(10, 11); cv2(4); fm(12, 13);
             SLA_PIN("+v"(oacc[1]), "+v"(moff), "+v"(pw[4])); SLA_SB();
             pv(1, 0); ex(12, 13); cv2(5); fm(14, 15); dots(0);
-            SLA_PIN("+v"(oacc[0]), "+v"(pw[5]), "+v"(l_part)); SLA_SB();
+            SLA_PIN("+v"(oacc[0]), "+v"(pw[5]), "+v"(l_part), "+v"(l_alt)); SLA_SB();
             pv(1, 1); ex(14, 15); cv2(6); dots(1);
-            SLA_PIN("+v"(oacc[1]), "+v"(pw[6]), "+v"(l_part)); SLA_SB();
+            SLA_PIN("+v"(oacc[1]), "+v"(pw[6]), "+v"(l_part), "+v"(l_alt)); SLA_SB();
             cv2(7);
         } else {
             fm(0, 4);                                                            // the e4m3 MFMA takes twice as long: a larger first share
@@ -580,9 +601,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
             pv(0, 1); ex(8, 10);  cv2(2); cv2(3); fm(11, 13);
             SLA_PIN("+v"(oacc[1]), "+v"(moff), "+v"(pw[2]), "+v"(pw[3])); SLA_SB();
             pv(1, 0); ex(11, 13); cv2(4); fm(14, 15); dots(0);
-            SLA_PIN("+v"(oacc[0]), "+v"(pw[4]), "+v"(l_part)); SLA_SB();
+            SLA_PIN("+v"(oacc[0]), "+v"(pw[4]), "+v"(l_part), "+v"(l_alt)); SLA_SB();
             pv(1, 1); ex(14, 15); cv2(5); cv2(6); dots(1);
-            SLA_PIN("+v"(oacc[1]), "+v"(pw[5]), "+v"(pw[6]), "+v"(l_part)); SLA_SB();
+            SLA_PIN("+v"(oacc[1]), "+v"(pw[5]), "+v"(pw[6]), "+v"(l_part), "+v"(l_alt)); SLA_SB();
             cv2(7);
         }
         w.p[0] = __builtin_bit_cast(f16x8, make_uint4(pw[0], pw[1], pw[2], pw[3]));
@@ -596,6 +617,22 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     };
 #undef SLA_PIN
 
+    // Raises the running maximum of the rows to the exact maximum over the unit whose S^T is s_cur, in front of a fast
+    // step: the accumulators, the row sums and the weights of the previous unit (not yet multiplied into the
+    // accumulators) are rescaled; the fast step that follows then sees no exponent above zero.
+    auto raise_reference = [&](const TileInfo &t) __attribute__((always_inline)) {
+        const float top = pair_max(max16(s_cur)) * t.cj + t.lsv;
+        const float m_new = fmaxf(m_run, top);
+        const float alpha = m_new == m_run ? 1.0f : fast_exp2(m_run - m_new);
+        rescale(alpha);
+        const _Float16 ah = (_Float16)alpha;
+#pragma unroll
+        for (int ss = 0; ss < 2; ++ss)
+#pragma unroll
+            for (int x = 0; x < 8; ++x) w_prev.p[ss][x] *= ah;
+        m_run = m_new;
+    };
+
     // Ring bookkeeping.  During iteration c the LDS reads touch V^T tile c and K tile c + KAHEAD - 2 (the fragments of
     // the following step); both must have landed at its barrier, and that barrier frees the slots of the tiles before
     // them, into which the copies of V^T tile c + 2 and K tile c + KAHEAD go: needed two iterations later.
@@ -608,11 +645,13 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
         constexpr int P = decltype(phase)::value, S = T::SLOTS;
         constexpr uint32_t kreq = ((P + KAHEAD) % S) * T::KBYTES, vreq = ((P + 2) % S) * T::VBYTES;
         constexpr int kslot = ((P + KAHEAD - 2) % S) * T::KBYTES, vslot = T::VRING + P * T::VBYTES;
+        SLA_T(c, 0);
         // copies that may stay in flight here: those requested one iteration ago
         if (c == 0) wait_copies_and_barrier<0>();      // (nothing is in flight; joins the waves after the prologue's LDS reads)
         else if (c + KAHEAD - 1 < k) wait_copies_and_barrier<T::LOADS>();
         else if (c + 1 < k) wait_copies_and_barrier<T::VINS>();
         else wait_copies_and_barrier<0>();
+        SLA_T(c, 1);
         if (c + KAHEAD - wbase >= 64) load_window(wbase + 32);     // (never for lists of at most 64 blocks)
         if (c + KAHEAD < k) request_K(c + KAHEAD, kreq);
         if (c + 2 < k) request_V(c + 2, vreq);
@@ -620,25 +659,74 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
         const bool more = c + 1 < k;
         if (more) t_nxt = tile_info(c + 1);
         const bool ragged_n = more && t_nxt.valid != kBK;
+        SLA_T(c, 2);
         // first half of tile c: accumulates the second half of tile c-1, forms S^T of the second half of tile c;
         // reads the fragments of the next step: V^T tile c first half, K tile c+1 first half
         if (over_cur || c == 0 || t_cur.tiny || t_cur.valid != kBK) careful_step(c > 0, true, t_cur, t_cur, 1, vslot, 0, kslot, 0);
         else fast_step(t_cur, t_cur, vslot, 0, kslot, 0);
+        SLA_T(c, 3);
         // second half of tile c: accumulates its first half, forms S^T of the first half of tile c+1;
         // reads V^T tile c second half and K tile c+1 second half for the first step of the next iteration
         if (over_cur || !more || t_cur.tiny || ragged_n) careful_step(true, more, t_cur, t_nxt, 0, vslot, 1, kslot, 1);
         else fast_step(t_cur, t_nxt, vslot, 1, kslot, 1);
+        SLA_T(c, 4);
         t_cur = t_nxt;
     };
-    for (int c = 0; c < k; c += T::SLOTS) {
+    // The lean form of an iteration, for the middle of a list: tile c is not the first, tiles c .. c + KAHEAD exist, are
+    // full and none has a far-off V scale, and the window holds them (lean_ok checks this for three iterations at a
+    // time).  Nothing is conditional but the raise of the running maximum; both steps are fast steps.
+    auto lean_iteration = [&](int c, auto phase) __attribute__((always_inline)) {
+        constexpr int P = decltype(phase)::value, S = T::SLOTS;
+        constexpr uint32_t kreq = ((P + KAHEAD) % S) * T::KBYTES, vreq = ((P + 2) % S) * T::VBYTES;
+        constexpr int kslot = ((P + KAHEAD - 2) % S) * T::KBYTES, vslot = T::VRING + P * T::VBYTES;
+        SLA_T(c, 0);
+        wait_copies_and_barrier<T::LOADS>();
+        SLA_T(c, 1);
+        request_K(c + KAHEAD, kreq, true);
+        request_V(c + 2, vreq);
+        t_nxt.valid = kBK; t_nxt.tiny = false;
+        t_nxt.cj = FP8 ? __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(d_cj), c + 1 - wbase)) : c_exp;
+        t_nxt.lsv = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(d_lv), c + 1 - wbase));
+        t_nxt.invr = fast_exp2(-t_nxt.lsv);
+        SLA_T(c, 2);
+        if (over_cur) raise_reference(t_cur);
+        fast_step(t_cur, t_cur, vslot, 0, kslot, 0);
+        SLA_T(c, 3);
+        if (over_cur) raise_reference(t_cur);
+        fast_step(t_cur, t_nxt, vslot, 1, kslot, 1);
+        SLA_T(c, 4);
+        t_cur = t_nxt;
+    };
+    // three lean iterations from tile c on are possible: bits c .. c + 2 + KAHEAD of d_bad are clear and inside the window
+    auto lean_ok = [&](int c) {
+        return c + 2 + KAHEAD - wbase < 64 && ((uint32_t)(d_bad >> (c - wbase)) & ((1u << (KAHEAD + 3)) - 1)) == 0;
+    };
+    for (int c = 0; c < k;) {
         iteration(c, std::integral_constant<int, 0>{});
         if (c + 1 < k) iteration(c + 1, std::integral_constant<int, 1>{});
         if (T::SLOTS == 3 && c + 2 < k) iteration(c + 2, std::integral_constant<int, 2 % T::SLOTS>{});
+        c += T::SLOTS;
+        if constexpr (T::SLOTS == 3) {
+            while (lean_ok(c)) {
+                lean_iteration(c, std::integral_constant<int, 0>{});
+                lean_iteration(c + 1, std::integral_constant<int, 1>{});
+                lean_iteration(c + 2, std::integral_constant<int, 2>{});
+                c += 3;
+            }
+        }
     }
 #undef SLA_SB
 
     wait_copies_and_barrier<0>();                      // epilogue operands landed; every wave is past its last tile
+#ifdef SLA_PROBE_TIME
+    if (probe_on) {
+        const unsigned long long tp_c1 = __builtin_readcyclecounter(), tp_r1 = __builtin_amdgcn_s_memrealtime();
+        if (lane == 0) { tprobe[63 * 8 + 6] = tp_c1 - tp_c0; tprobe[63 * 8 + 7] = tp_r1 - tp_r0; }   // wave life: shader clock, 100 MHz clock
+        for (int x = lane; x < 64 * 8; x += 64) sla_probe_times[x] = tprobe[x];
+    }
+#endif
     if (k > 0) accumulate(vf_use, w_prev);             // the last unit's weights
+    l_part += l_alt;
     float l_run = l_part + xchg32(l_part) + l_full;
 
     uint8_t *stA = lds + kHqOff, *stB = lds + kWtOff;
@@ -773,6 +861,10 @@ __global__ __launch_bounds__(256) void transpose_w_kernel(const uint16_t *__rest
 {
     transpose_w_tile(W + (size_t)blockIdx.x * kD * kD, WT + (size_t)blockIdx.x * kD * kD, 256);
 }
+
+#ifdef SLA_PROBE_TIME
+extern "C" int sla_probe_read(unsigned long long *dst) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(sla_probe_times), sizeof(unsigned long long) * 64 * 8); }
+#endif
 
 hipError_t launch_transpose_w(const void *W, int nW, void *WT, hipStream_t st)
 {

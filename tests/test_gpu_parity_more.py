@@ -214,17 +214,23 @@ def case_kc(cfg):
 
 
 @pytest.mark.parametrize("bq", [64, 128])
-@pytest.mark.parametrize("where", ["late", "middle"])
+@pytest.mark.parametrize("where", ["late", "middle", "staircase"])
 def test_running_maximum_raised_in_mid_list(oracle, bq, where):
     """Keys of one block scaled so that their logits tower over everything seen before: the attention kernel's
-    running maximum, set by the first block, has to be raised when the list reaches that block."""
+    running maximum, set by the first block, has to be raised when the list reaches that block (staircase: every
+    block from the fourth to the twelfth towers over the one before, so the maximum is raised again and again in the
+    middle of the list, where the kernel runs its iterations without per-tile checks)."""
     cfg = C0.with_(N=1100, bq=bq)
     d = dict(synth.make_inputs(cfg))
     f = lambda bits: (bits.astype(np.uint32) << 16).view(np.float32)
     kk = f(d["K"]).copy()
-    j = 14 if where == "late" else 7
-    kk[:, :, j * 64:(j + 1) * 64] *= np.float32(24.0)
-    kk[:, :, (j + 1) * 64:(j + 1) * 64 + 32] *= np.float32(6.0)
+    if where == "staircase":
+        for j in range(3, 12):
+            kk[:, :, j * 64 + (j % 3) * 16:(j + 1) * 64] *= np.float32(1.9 ** (j - 2))
+    else:
+        j = 14 if where == "late" else 7
+        kk[:, :, j * 64:(j + 1) * 64] *= np.float32(24.0)
+        kk[:, :, (j + 1) * 64:(j + 1) * 64 + 32] *= np.float32(6.0)
     d["K"] = synth.to_bf16_bits(kk)
     case = G.Case(cfg, d, k_crit=case_kc(cfg), k_neg=0)
     O, lab = case.forward()

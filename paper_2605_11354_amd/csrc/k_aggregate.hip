@@ -40,6 +40,7 @@ __global__ __launch_bounds__(256, (TA == 2 && AHEAD == 3) ? 4 : 1) void aggregat
                                                         const uint16_t *__restrict__ hT, int Nqb, int Nkb, int n_it,
                                                         long total, uint16_t *__restrict__ Hq)
 {
+    asm volatile("" ::"s"(mbits), "s"(nkw), "s"(hT), "s"(Nqb), "s"(Nkb), "s"(n_it), "s"(total), "s"(Hq));      // all kernel arguments in one batch of scalar loads, here
     constexpr int kWN = 4 / TA;                   // waves along the columns (TA 32-column sub-tiles each)
     constexpr int kWI = 4 / kWN;                  // waves along the query blocks (TB 32-block sub-tiles each)
     constexpr int BM = 32 * TB * kWI;             // query blocks per workgroup tile

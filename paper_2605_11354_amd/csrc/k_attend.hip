@@ -194,6 +194,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     constexpr int ES = FP8 ? 1 : 2;                     // bytes per input element
     constexpr int KROWB = FP8 ? 64 : 128;               // bytes of a K row in LDS
     __shared__ __attribute__((aligned(1024))) uint8_t lds[T::LDS];
+    // All kernel arguments are fetched here, in one batch of scalar loads: left to the compiler each would be loaded in
+    // front of its first use, a dozen scalar-cache round trips one after the other along the prologue and the epilogue.
+    asm volatile("" ::"s"(Qp), "s"(Kp), "s"(Vp), "s"(lvs), "s"(sQ), "s"(sK), "s"(rm.bs), "s"(rm.hs), "s"(rm.ts), "s"(rm.H), "s"(crit_idx),
+                 "s"(k_c), "s"(Hq), "s"(WT), "s"(proj_per_head), "s"(phi), "s"(H), "s"(N), "s"(Nqb), "s"(Nkb), "s"(total), "s"(c_exp), "s"(O), "s"(O32));
     const long work = xcd_remap(blockIdx.x, total);
     if (work >= total) return;                        // the whole workgroup leaves together
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
@@ -217,6 +221,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     const uint8_t *Vh = (const uint8_t *)(Vp + (size_t)bh * Nkb * kBK * kD);
     const float *lvh = lvs + bh * Nkb;
 
+    SLA_T(62, 0);
     // Q as the B operand of S^T: bf16 -> 4 K-steps of 8 channels (16s + 8g ..), e4m3 -> 32 channels (32g ..)
     bf16x8 qf[4];
     i32x8 q8;
@@ -309,6 +314,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     };
     auto entry_j = [&](int c) { return __builtin_amdgcn_readlane(d_j, c - wbase); };
 
+    SLA_T(62, 1);
     CopyOffsets<NWAVES, FP8> co;
     co.init(wave, lane, krowb);
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);                       // same value, provably uniform
@@ -474,11 +480,14 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     if (k > 2) request_K(2, 2 * T::KBYTES);
     if (k > 0) request_V(0, 0);
     if (k > 1) request_V(1, T::VBYTES);
+    SLA_T(62, 2);
     load_window_scales(true);
     // Let the Q fragments (ordinary loads the compiler tracks) and the first tiles land here, once: left to the
     // compiler, its vmcnt(0) for Q would sit in front of their first use inside the loop and drain the ring every trip.
+    SLA_T(62, 3);
     __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));      // vmcnt(0), as a builtin so that the compiler's bookkeeping sees it
     wait_copies_and_barrier<0>();
+    SLA_T(62, 4);
 
     // Units of this wave: u = 2 c + hh is the 32-key half hh of tile c.  Step u accumulates unit u-1
     // (V^T fragments vf_use), forms S^T of unit u+1 (K fragments kf_use) and runs the softmax of unit u; meanwhile the
@@ -500,6 +509,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
         if (U > 1) kf_use = load_kfrag(unit_tile(1) * T::KBYTES, unit_half(1));     // for S^T of unit 1, formed in step 0
     }
 
+    SLA_T(62, 5);
 #define SLA_SB() __builtin_amdgcn_sched_barrier(0)
 #define SLA_PIN(...) asm volatile("" : __VA_ARGS__)
     // Whether some lane's largest exponent in the unit whose S^T is s would exceed kRaise against the lane's running
@@ -718,13 +728,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
 #undef SLA_SB
 
     wait_copies_and_barrier<0>();                      // epilogue operands landed; every wave is past its last tile
-#ifdef SLA_PROBE_TIME
-    if (probe_on) {
-        const unsigned long long tp_c1 = __builtin_readcyclecounter(), tp_r1 = __builtin_amdgcn_s_memrealtime();
-        if (lane == 0) { tprobe[63 * 8 + 6] = tp_c1 - tp_c0; tprobe[63 * 8 + 7] = tp_r1 - tp_r0; }   // wave life: shader clock, 100 MHz clock
-        for (int x = lane; x < 64 * 8; x += 64) sla_probe_times[x] = tprobe[x];
-    }
-#endif
+    SLA_T(61, 0);
     if (k > 0) accumulate(vf_use, w_prev);             // the last unit's weights
     l_part += l_alt;
     float l_run = l_part + xchg32(l_part) + l_full;
@@ -738,6 +742,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
 #pragma unroll
         for (int x = 0; x < 16; ++x) oacc[e][x] *= inv_l;
 
+    SLA_T(61, 1);
     if (Hq != nullptr) {
         // ---- phi(Q): softmax over the 64 channels of the row (this lane holds 32, lane^32 the rest).
         // x[8s + c] is channel dcol(s) + c, the channel slot c of K-step s carries in the product below.
@@ -789,6 +794,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
         den += xchg32(den);
         const float inv_den = den > 0.f ? 1.0f / den : 0.f;     // no marginal block: H = Z = 0 and O_lin = 0
 
+        SLA_T(61, 2);
         // ---- O_lin^T = Hq^T phi(Q)^T   (Hq^T tile staged with the tile swizzle)
         f32x16 lacc[2];
 #pragma unroll
@@ -820,7 +826,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     // ---- store.  Register 4a+b of oacc[e] is channel 32e + 8a + 4g + b of row q: the wave's 32x64 tile
     // is transposed through a private 4 KB LDS slice (8-byte pieces, XOR-swizzled by row) so that it
     // leaves as full 128-byte rows, 16 bytes per lane.
+    SLA_T(61, 3);
     wait_copies_and_barrier<0>();                      // all waves are done reading the epilogue operands
+    SLA_T(61, 4);
     if (O32 != nullptr) {
         // diagnostic output: the fp32 values the bf16 store below would round, straight from the accumulators
         if (qok) {
@@ -854,6 +862,14 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
             if (q0w + r < N) *(uint4 *)(O + head + (size_t)(q0w + r) * rm.ts + ch * 8) = v;
         }
     }
+    SLA_T(61, 5);
+#ifdef SLA_PROBE_TIME
+    if (probe_on) {
+        const unsigned long long tp_c1 = __builtin_readcyclecounter(), tp_r1 = __builtin_amdgcn_s_memrealtime();
+        if (lane == 0) { tprobe[63 * 8 + 6] = tp_c1 - tp_c0; tprobe[63 * 8 + 7] = tp_r1 - tp_r0; }   // wave life: shader clock, 100 MHz clock
+        for (int x = lane; x < 64 * 8; x += 64) sla_probe_times[x] = tprobe[x];
+    }
+#endif
 }
 
 // W [nW][e_in][e_out] -> WT [nW][e_out][slot] as its own launch (the whole forward folds this into the states pass)

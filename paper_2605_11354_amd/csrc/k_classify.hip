@@ -18,6 +18,7 @@ template <bool FP8>
 __global__ __launch_bounds__(256) void pool_kernel(const void *__restrict__ X, const float *__restrict__ scales,
                                                    RowMap rm, int N, int blk, int nblk, long units, double *__restrict__ mean)
 {
+    asm volatile("" ::"s"(X), "s"(scales), "s"(rm.bs), "s"(rm.hs), "s"(rm.ts), "s"(rm.H), "s"(N), "s"(blk), "s"(nblk), "s"(units), "s"(mean));      // all kernel arguments in one batch of scalar loads, here
     const long u = (long)blockIdx.x * 256 + threadIdx.x;
     if (u >= units) return;
     const int c = (int)(u & 7);
@@ -453,6 +454,10 @@ __global__ __launch_bounds__(256) void classify_fused_kernel(const void *__restr
                                            // sixteen lanes of one 16-byte access pass cover all 64 banks once
     __shared__ __align__(16) double ks[64 * kPitch];
     __shared__ uint32_t hist[4][256];
+    // every kernel argument is fetched here, in one batch of scalar loads (left to the compiler: a dozen round trips to the
+    // scalar cache, each in front of the first use of an argument)
+    asm volatile("" ::"s"(Q), "s"(sQ), "s"(rm.bs), "s"(rm.hs), "s"(rm.ts), "s"(rm.H), "s"(kbar), "s"(N), "s"(bq), "s"(Nqb), "s"(Nkb), "s"(k_c), "s"(k_n),
+                 "s"(mbits), "s"(lab_pitch), "s"(lab_dense), "s"(crit_idx), "s"(Pc), "s"(S_dense), "s"(qbar_out), "s"(sm_scale));
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const long bh = blockIdx.y;
     const int i = blockIdx.x * 4 + wave;

@@ -180,6 +180,7 @@ __global__ __launch_bounds__(64 * kWavesPerWG) __attribute__((amdgpu_waves_per_e
                                                                   double *__restrict__ kbar, int phi, unsigned state_wgs,
                                                                   const uint16_t *__restrict__ W, uint16_t *__restrict__ WT)
 {
+    asm volatile("" ::"s"(K), "s"(V), "s"(sK), "s"(sV), "s"(rm.bs), "s"(rm.hs), "s"(rm.ts), "s"(rm.H), "s"(N), "s"(Nkb), "s"(nblocks), "s"(per_wave), "s"(hT), "s"(Vp), "s"(lvs), "s"(kbar), "s"(phi), "s"(state_wgs), "s"(W), "s"(WT));      // all kernel arguments in one batch of scalar loads, here
     if (blockIdx.x >= state_wgs) {     // workgroups past the states grid each lay out one projection matrix for the attention kernel
         const size_t m = (size_t)(blockIdx.x - state_wgs) * kD * kD;
         transpose_w_tile(W + m, WT + m, 64 * kWavesPerWG);

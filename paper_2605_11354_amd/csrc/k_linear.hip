@@ -103,6 +103,8 @@ __global__ __launch_bounds__(256) void fp8_gemm_kernel(const uint8_t *__restrict
                                                        const uint16_t *__restrict__ bias, int M, int O, int K, int n_it,
                                                        long total, uint16_t *__restrict__ Y, QkvOut qkv)
 {
+    asm volatile("" ::"s"(A8), "s"(sa), "s"(W8), "s"(sw), "s"(bias), "s"(M), "s"(O), "s"(K), "s"(n_it), "s"(total), "s"(Y), "s"(qkv.codes[0]), "s"(qkv.codes[1]), "s"(qkv.codes[2]),
+                 "s"(qkv.scales[0]), "s"(qkv.scales[1]), "s"(qkv.scales[2]), "s"(qkv.N), "s"(qkv.H), "s"(qkv.bq));      // all kernel arguments in one batch of scalar loads, here
     constexpr int kTok = 64 * TB;                                                // tokens per workgroup tile
     constexpr int kBufs = TB == 2 ? 2 : 1;
     constexpr int kBufBytes = (kTok + 128) * kLinK;                              // token tile, then channel tile
@@ -317,6 +319,8 @@ __global__ __launch_bounds__(256, 1) void fp8_gemm_big_kernel(const uint8_t *__r
                                                               const uint16_t *__restrict__ bias, int M, int O, int K, int n_it,
                                                               long total, uint16_t *__restrict__ Y, QkvOut qkv)
 {
+    asm volatile("" ::"s"(A8), "s"(sa), "s"(W8), "s"(sw), "s"(bias), "s"(M), "s"(O), "s"(K), "s"(n_it), "s"(total), "s"(Y), "s"(qkv.codes[0]), "s"(qkv.codes[1]), "s"(qkv.codes[2]),
+                 "s"(qkv.scales[0]), "s"(qkv.scales[1]), "s"(qkv.scales[2]), "s"(qkv.N), "s"(qkv.H), "s"(qkv.bq));      // all kernel arguments in one batch of scalar loads, here
     constexpr int kStage = 2 * 256 * kLinK;                                      // bytes of one stage: A tile + W tile
     __shared__ __attribute__((aligned(1024))) uint8_t smem[2 * kStage + 2048];   // behind the stages: the tile's 256 channel scales and biases
     const long item = xcd_remap(blockIdx.x, total);

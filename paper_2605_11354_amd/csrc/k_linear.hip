@@ -17,6 +17,8 @@
 #include "sla_common.hpp"
 #include "sla_kernels.hpp"
 
+#include <type_traits>
+
 namespace sla {
 
 __global__ __launch_bounds__(256) void quantise_rows_kernel(const uint16_t *__restrict__ X, long rows, int cols,
@@ -313,6 +315,12 @@ hipError_t launch_quantise_rows(const void *X, long rows, int cols, void *codes,
 // schedule is written out at the loop).  The copies are inline assembly, invisible to the compiler's wait counting; the wait is explicit.
 // Epilogue: scales and bias in fp32, each wave stages its [token][channel] tile in its own quarter of LDS (16-byte
 // chunks XOR-ed with the token row against bank conflicts) and stores 16 bytes per lane, 256 contiguous bytes per row.
+#ifdef SLA_PROBE_TIME   /* timing probe only: cycle counter of one wave at the phase boundaries of its tile */
+__device__ unsigned long long sla_gemm_probe_times[16];
+#define SLA_GT(pt) do { if (gprobe) { const unsigned long long t_ = __builtin_readcyclecounter(), r_ = __builtin_amdgcn_s_memrealtime(); if ((threadIdx.x & 63) == 0) { sla_gemm_probe_times[pt] = t_; sla_gemm_probe_times[8 + pt] = r_; } } } while (0)
+#else
+#define SLA_GT(pt)
+#endif
 template <bool QKV>
 __global__ __launch_bounds__(256, 1) void fp8_gemm_big_kernel(const uint8_t *__restrict__ A8, const float *__restrict__ sa,
                                                               const uint8_t *__restrict__ W8, const float *__restrict__ sw,
@@ -325,6 +333,10 @@ __global__ __launch_bounds__(256, 1) void fp8_gemm_big_kernel(const uint8_t *__r
     __shared__ __attribute__((aligned(1024))) uint8_t smem[2 * kStage + 2048];   // behind the stages: the tile's 256 channel scales and biases
     const long item = xcd_remap(blockIdx.x, total);
     if (item >= total) return;
+#ifdef SLA_PROBE_TIME
+    const bool gprobe = __builtin_amdgcn_readfirstlane((int)(item == total / 2 + 5 && threadIdx.x < 64)) != 0;
+#endif
+    SLA_GT(0);
     const int n_ot = (int)(total / n_it);
     const int ot = (int)(item % n_ot), it = (int)(item / n_ot);                  // channel tile fastest (see above)
     const int i0 = it * 256, o0 = ot * 256;
@@ -393,10 +405,10 @@ __global__ __launch_bounds__(256, 1) void fp8_gemm_big_kernel(const uint8_t *__r
         if (idx < 4) wf[idx] = frag(Wt, wo + 32 * idx + l32, sl);
         else af[idx - 4] = frag(At, wi + 32 * (idx - 4) + l32, sl);
     };
-    auto copy_one = [&](int ks, int stage, int idx) {                                      // copy idx of 16: even A, odd W
-        const uint32_t dst = lds_base + stage * kStage + wave * 8192 + (idx >> 1) * 1024;
-        if (idx & 1) copy_1k_to_lds(W8 + (size_t)ks * kLinK, vw[idx >> 1], dst + 256 * kLinK);
-        else copy_1k_to_lds(A8 + (size_t)ks * kLinK, va[idx >> 1], dst);
+    auto copy_one = [&](const uint8_t *An, const uint8_t *Wn, uint32_t dst0, int idx) {   // copy idx of 16 of a step: even A, odd W
+        const uint32_t dst = dst0 + (idx >> 1) * 1024;
+        if (idx & 1) copy_1k_to_lds(Wn, vw[idx >> 1], dst + 256 * kLinK);
+        else copy_1k_to_lds(An, va[idx >> 1], dst);
     };
 #define SLA_SB() __builtin_amdgcn_sched_barrier(0)
     issue(KS_(0), 0);
@@ -404,11 +416,20 @@ __global__ __launch_bounds__(256, 1) void fp8_gemm_big_kernel(const uint8_t *__r
     if (ksteps > 1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");           // the sixteen copies of step 0 (those of step 1 may fly on)
     else            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
+    SLA_GT(1);
+#ifdef SLA_PROBE_TIME
+    unsigned long long wait_copy_ = 0, wait_bar_ = 0;
+#endif
 #pragma unroll
     for (int f = 0; f < 8; ++f) read_one(wf0, af0, 0, 0, f);
+    // k2: the K slice that step ks+2 works on (kept by increment: a division per copy would cost more than the MFMA
+    // the copy hides behind)
+    int k2 = KS_(2 % ksteps);
     for (int ks = 0; ks < ksteps; ++ks) {
-        const int st = ks & 1;
         const bool more1 = ks + 1 < ksteps, more2 = ks + 2 < ksteps;
+        const int st = ks & 1;
+        const uint8_t *An = A8 + (size_t)k2 * kLinK, *Wn = W8 + (size_t)k2 * kLinK;
+        const uint32_t dst0 = lds_base + st * kStage + wave * 8192;
         // F0 was requested at least eight MFMAs ago: say here that it has arrived, so that the wait the compiler puts in
         // front of its first use does not cover the reads that follow
         __builtin_amdgcn_s_waitcnt(0xC07F);        // lgkmcnt(0) only
@@ -419,55 +440,89 @@ __global__ __launch_bounds__(256, 1) void fp8_gemm_big_kernel(const uint8_t *__r
             if (m < 8) read_one(wf1, af1, st, 1, m);
             SLA_SB();
         }
+#ifdef SLA_PROBE_TIME
+        unsigned long long w0_ = 0, w1_ = 0;
+        if (gprobe) w0_ = __builtin_readcyclecounter();
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (gprobe) w1_ = __builtin_readcyclecounter();
+#else
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
         __builtin_amdgcn_s_waitcnt(0xC07F);        // lgkmcnt(0), as a builtin: the compiler then knows F1 has arrived
         __builtin_amdgcn_s_barrier();
+#ifdef SLA_PROBE_TIME
+        if (gprobe) { const unsigned long long w2_ = __builtin_readcyclecounter(); wait_copy_ += w1_ - w0_; wait_bar_ += w2_ - w1_; }
+#endif
         SLA_SB();
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
             acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wf1[m >> 2], af1[m & 3], acc[m >> 2][m & 3], 0, 0, 0, 0, 0, 0);
             if (m < 8 && more1) read_one(wf0, af0, st ^ 1, 0, m);
-            if (more2) copy_one(KS_(ks + 2), st, m);
+            if (more2) copy_one(An, Wn, dst0, m);
             SLA_SB();
         }
+        k2 = k2 + 1 == ksteps ? 0 : k2 + 1;
     }
 #undef SLA_SB
+    SLA_GT(2);
+#ifdef SLA_PROBE_TIME
+    if (gprobe && (threadIdx.x & 63) == 0) { sla_gemm_probe_times[6] = wait_copy_; sla_gemm_probe_times[7] = wait_bar_; }
+#endif
     __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_s_barrier();                                                // every wave is past its last fragment reads
+    SLA_GT(3);
 
     // accumulator (a,b) register 4q+r of lane (l32, g): channel o0 + wo + 32a + 8q + 4g + r, token i0 + wi + 32b + l32.
     // The wave's tile as [128 tokens][128 channels] bf16 in its own 32 KB: the 8-byte piece of channels 4 c2 .. 4 c2 + 3
     // (c2 = 8a + 2q + g) of token row t goes to 16-byte chunk (c2 / 2) ^ (t % 16), half c2 % 2.
     uint8_t *stage = smem + wave * 32768;
-    float swv[4][4][4], bv[4][4][4];
-    {
-        const float *cs = (const float *)(smem + 2 * kStage);
+    // y = (acc * s_token) * s_channel + bias, two roundings before the bf16 store.  Everything the loop below needs is
+    // requested first and awaited once (left alone, the compiler puts each LDS read in front of its first use and waits
+    // for it there, thirty-two round trips one after the other).
+    float si[4];
+    const float *cs = (const float *)(smem + 2 * kStage);
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
+    for (int b = 0; b < 4; ++b) si[b] = sa[min(i0 + wi + 32 * b + l32, M - 1)];
+    float4 sw4[2][4], bi4[2][4];                                                 // one channel sub-tile in use, the next one on its way
+    auto fetch = [&](int a, int buf) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int c = wo + 32 * a + 8 * q + 4 * g;
+            sw4[buf][q] = *(const float4 *)(cs + c);
+            bi4[buf][q] = *(const float4 *)(cs + 256 + c);
+        }
+    };
+    auto landed = [&](int buf) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            asm volatile("" : "+v"(sw4[buf][q].x), "+v"(sw4[buf][q].y), "+v"(sw4[buf][q].z), "+v"(sw4[buf][q].w),
+                              "+v"(bi4[buf][q].x), "+v"(bi4[buf][q].y), "+v"(bi4[buf][q].z), "+v"(bi4[buf][q].w));
+    };
+    fetch(0, 0);
+    asm volatile("" : "+v"(si[0]), "+v"(si[1]), "+v"(si[2]), "+v"(si[3]));
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const int buf = a & 1;
+        __builtin_amdgcn_sched_barrier(0);
+        if (a + 1 < 4) fetch(a + 1, buf ^ 1);
+        __builtin_amdgcn_sched_barrier(0);
+        landed(buf);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int t = 32 * b + l32;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int c = wo + 32 * a + 8 * q + 4 * g;
-                const float4 s4 = *(const float4 *)(cs + c), b4 = *(const float4 *)(cs + 256 + c);
-                swv[a][q][0] = s4.x; swv[a][q][1] = s4.y; swv[a][q][2] = s4.z; swv[a][q][3] = s4.w;
-                bv[a][q][0] = b4.x; bv[a][q][1] = b4.y; bv[a][q][2] = b4.z; bv[a][q][3] = b4.w;
-            }
-    }
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-        const int t = 32 * b + l32;
-        const float si = sa[min(i0 + wi + t, M - 1)];
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float v[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) v[r] = acc[a][b][4 * q + r] * (si * swv[a][q][r]) + bv[a][q][r];
+                const float v0 = fmaf(acc[a][b][4 * q + 0] * si[b], sw4[buf][q].x, bi4[buf][q].x);
+                const float v1 = fmaf(acc[a][b][4 * q + 1] * si[b], sw4[buf][q].y, bi4[buf][q].y);
+                const float v2 = fmaf(acc[a][b][4 * q + 2] * si[b], sw4[buf][q].z, bi4[buf][q].z);
+                const float v3 = fmaf(acc[a][b][4 * q + 3] * si[b], sw4[buf][q].w, bi4[buf][q].w);
                 const int c2 = 8 * a + 2 * q + g;
-                *(uint2 *)(stage + t * 256 + (((c2 >> 1) ^ (t & 15)) << 4) + ((c2 & 1) << 3)) = make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
+                *(uint2 *)(stage + t * 256 + (((c2 >> 1) ^ (t & 15)) << 4) + ((c2 & 1) << 3)) = make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
             }
+        }
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                          // the wave reads back what it wrote itself
+    SLA_GT(4);
     if constexpr (!QKV) {
 #pragma unroll
         for (int x0 = 0; x0 < 32; x0 += 16) {                                    // sixteen rows' pieces read, then sixteen stores
@@ -530,7 +585,12 @@ __global__ __launch_bounds__(256, 1) void fp8_gemm_big_kernel(const uint8_t *__r
             }
         }
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    SLA_GT(5);
 }
+#ifdef SLA_PROBE_TIME
+extern "C" int sla_probe_read_gemm(unsigned long long *dst) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(sla_gemm_probe_times), sizeof(unsigned long long) * 16); }
+#endif
 #undef KS_
 
 static bool lin_big_tiles(int M, int O) { return (long)((M + 255) / 256) * ((O + 255) / 256) >= 512; }   // two rounds of the chip

@@ -211,7 +211,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     const unsigned long long tp_c0 = __builtin_readcyclecounter(), tp_r0 = __builtin_amdgcn_s_memrealtime();
 #endif
     const int wq = wave;                              // query group of this wave
-    const long bh = work / Nqb;
+    const long bh = (long)((unsigned)work / (unsigned)Nqb);      // (the grid fits 32 bits)
     const int i = (int)(work - bh * Nqb);
     const int q = i * BQ + 32 * wq + l32;             // this lane's query row
     const bool qok = q < N;
@@ -346,7 +346,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     // The operands of the linear/projection epilogue (the 64x64 tile of Hq^T, the Z row, W^T) travel the same way
     // into the K ring, which is idle during the last tile, so their latency hides behind that tile's arithmetic.
     const uint8_t *Hi8 = Hq ? (const uint8_t *)(Hq + (size_t)work * kStateElems) : nullptr;
-    const uint8_t *Wh8 = (const uint8_t *)(WT + (proj_per_head ? (size_t)(bh % H) * kD * kD : 0));
+    const uint8_t *Wh8 = (const uint8_t *)(WT + (proj_per_head ? (size_t)((unsigned)bh % (unsigned)H) * kD * kD : 0));
     constexpr int kHqOff = 0, kWtOff = FP8 ? T::WOFF : 8192;
     auto request_epilogue = [&]() __attribute__((always_inline)) {
         if (Hq == nullptr) return;

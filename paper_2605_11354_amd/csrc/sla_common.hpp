@@ -17,7 +17,12 @@ constexpr int kStateElems = kStateRows * kD;   // 4160
 struct RowMap {
     long bs, hs;
     int ts, H;
-    __host__ __device__ size_t head(long bh) const { return (size_t)(bh / H) * bs + (size_t)(bh % H) * hs; }
+    // (b, h) of bh = b H + h by 32-bit division (B H fits 31 bits; a 64-bit division is some sixty instructions)
+    __host__ __device__ size_t head(long bh) const
+    {
+        const unsigned b = (unsigned)bh / (unsigned)H, h = (unsigned)bh - b * (unsigned)H;
+        return (size_t)b * bs + (size_t)h * hs;
+    }
 };
 inline RowMap make_rowmap(int token_major, int H, int N)
 {

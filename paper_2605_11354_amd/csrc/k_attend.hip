@@ -222,6 +222,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     const float *lvh = lvs + bh * Nkb;
 
     SLA_T(62, 0);
+    // The critical list of the row is asked for first of all: the tile copies, the scale gather and with them the whole
+    // prologue wait for it (loads return in order: behind the Q rows it would arrive after them).
+    const int32_t *ci = crit_idx + work * (long)k_c;
+    const int j0_first = lane < k_c ? ci[lane] : -1;
     // Q as the B operand of S^T: bf16 -> 4 K-steps of 8 channels (16s + 8g ..), e4m3 -> 32 channels (32g ..)
     bf16x8 qf[4];
     i32x8 q8;
@@ -262,7 +266,6 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     // ratio again); l_full: row sums formed in fp32 by the careful steps (already complete over the lane pair).
     float m_run = -INFINITY, l_part = 0.f, l_alt = 0.f, l_full = 0.f;      // (l_alt: second partial sum of the fast steps)
 
-    const int32_t *ci = crit_idx + work * (long)k_c;
     // Ragged block: only the last key block of the sequence can be short.
     const int tail_rows = N & (kBK - 1), ragged_j = tail_rows ? Nkb - 1 : -1;
     // The list lives in registers, one entry per lane, as a window of 64 entries starting at wbase (a multiple of 32):
@@ -276,7 +279,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     // k: number of leading valid entries of the list (a list taken from given labels may end in -1 entries)
     int k = 0;
     {
-        const int j0 = lane < k_c ? ci[lane] : -1;      // the first window doubles as the first chunk of the count
+        const int j0 = j0_first;                        // the first window doubles as the first chunk of the count
         unsigned long long ok = __ballot(j0 >= 0 && j0 < Nkb);
         d_j = (j0 >= 0 && j0 < Nkb) ? j0 : 0;
         if (ok != ~0ull) k = __builtin_ctzll(~ok);
@@ -744,6 +747,19 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
 
     SLA_T(61, 1);
     if (Hq != nullptr) {
+        // The sixteen operand fragments of the two products below are read from LDS here, in one go, so that their latency
+        // passes behind the arithmetic of phi(Q) (read where they are used, each would be awaited on its own).
+        bf16x8 hfr[4][2], wfr[4][2];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int hchunk = FP8 ? 4 * g + s : 2 * s + g;      // 16-byte chunk holding channels dcol(s)..dcol(s)+7
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                hfr[s][e] = *(const bf16x8 *)(stA + (32 * e + l32) * 128 + ((hchunk ^ swz8(l32)) << 4));
+                wfr[s][e] = *(const bf16x8 *)(stB + (32 * e + l32) * 128 + (((2 * s + g) ^ swz8(l32)) << 4));
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
         // ---- phi(Q): softmax over the 64 channels of the row (this lane holds 32, lane^32 the rest).
         // x[8s + c] is channel dcol(s) + c, the channel slot c of K-step s carries in the product below.
         float x[32];
@@ -799,12 +815,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
         f32x16 lacc[2];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            const int hchunk = FP8 ? 4 * g + s : 2 * s + g;      // 16-byte chunk holding channels dcol(s)..dcol(s)+7
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const bf16x8 hf = *(const bf16x8 *)(stA + (32 * e + l32) * 128 + ((hchunk ^ swz8(l32)) << 4));
-                lacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hf, fq[s], s == 0 ? zero16 : lacc[e], 0, 0, 0);
-            }
+            for (int e = 0; e < 2; ++e) lacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hfr[s][e], fq[s], s == 0 ? zero16 : lacc[e], 0, 0, 0);
         }
 #pragma unroll
         for (int e = 0; e < 2; ++e)
@@ -816,10 +828,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
         for (int s = 0; s < 4; ++s) {
             const bf16x8 pf = pack8(lacc[s >> 1], 8 * (s & 1));
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const bf16x8 wf = *(const bf16x8 *)(stB + (32 * e + l32) * 128 + (((2 * s + g) ^ swz8(l32)) << 4));
-                oacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, pf, oacc[e], 0, 0, 0);
-            }
+            for (int e = 0; e < 2; ++e) oacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[s][e], pf, oacc[e], 0, 0, 0);
         }
     }
 

@@ -27,10 +27,11 @@
 //
 // Software pipeline.  The work of a wave is a stream of units (32 keys x 32 queries).  In step u the matrix unit
 // runs O += V P of unit u-1 and S of unit u+1 while the vector unit runs the softmax of unit u; the three have no
-// dependency on each other, so the compiler can interleave MFMA and VALU instructions in one basic block
-// (`sched_group_barrier` below asks for exactly that).  Everything with control flow (raising the maximum, the
-// first unit of a row, a ragged key block, a key block whose V scale is far below the first one's) sits between the
-// steps or in the "careful" variant of a step.
+// dependency on each other, so MFMA and VALU instructions alternate in one basic block (scheduling barriers and
+// value pins below hold the order).  Everything with control flow (raising the maximum, the first unit of a row, a
+// ragged key block, a key block whose V scale is far below the first one's) sits between the steps or in the
+// "careful" variant of a step.  In the middle of a list, where none of the special cases can occur (one bit per list
+// entry says so), iterations run three at a time in a form without guards.
 //
 // Memory pipeline.  K and V^T tiles go from global memory straight into LDS (global_load_lds_dwordx4, no staging
 // registers) into two rings of three slots each.  K runs ahead of V^T by the pipeline's skew, so the copies of an

@@ -49,11 +49,12 @@ __global__ __launch_bounds__(256, (TA == 2 && AHEAD == 3) ? 4 : 1) void aggregat
 
     const long item = xcd_remap(blockIdx.x, total);      // (head, column tile, query tile), query tile fastest:
     if (item >= total) return;                           // neighbours on one XCD share a state slab in its L2
-    const int it = (int)(item % n_it);
-    const long rest = item / n_it;
+    // (32-bit divisions: the grid fits 32 bits, and a 64-bit division is some sixty instructions)
+    const unsigned rest = (unsigned)item / (unsigned)n_it;
+    const int it = (int)((unsigned)item - rest * (unsigned)n_it);
     constexpr int kNT = (kStateElems + 127) / 128;
-    const int nt = (int)(rest % kNT);
     const long bh = rest / kNT;
+    const int nt = (int)(rest - (unsigned)bh * kNT);
     const int n0 = nt * 128, i0 = it * BM;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -68,7 +69,12 @@ __global__ __launch_bounds__(256, (TA == 2 && AHEAD == 3) ? 4 : 1) void aggregat
     // the last one and meet mask bits that are zero, columns and query blocks past the end give results nobody
     // stores), so the compiler can count the loads in flight and wait for exactly the set it needs.
     const int n4 = (tid & 3) | ((tid >> 2) & 0x1C), jg = ((tid >> 2) & 3) | ((tid >> 5) & 4);
-    const uint16_t *hcol = Hf + (n0 + 4 * n4 < kStateElems ? n0 + 4 * n4 : 0);   // kStateElems % 4 == 0: a group is in or out as a whole
+    // byte offsets inside the head's slab fit 32 bits (a slab is Nkb x 8320 bytes): the loads take the slab's base from
+    // scalar registers and a 32-bit offset per lane, formed with full-rate instructions (64-bit address arithmetic
+    // per load was a quarter-rate multiply and more, a third of the loop's vector time)
+    const uint8_t *Hf8 = (const uint8_t *)Hf;
+    const uint32_t colb = 2u * (uint32_t)(n0 + 4 * n4 < kStateElems ? n0 + 4 * n4 : 0);   // kStateElems % 4 == 0: a group is in or out as a whole
+    auto state_piece = [&](int j) { return *(const uint2 *)(Hf8 + (__umul24((uint32_t)j, 2u * kStateElems) + colb)); };
     // mask rows of this lane: query block i0 + wi + 32 b + l32, one 64-bit word per K step
     const uint2 *mrow[TB];
 #pragma unroll
@@ -86,7 +92,7 @@ __global__ __launch_bounds__(256, (TA == 2 && AHEAD == 3) ? 4 : 1) void aggregat
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const int j = min(ks * kAggK + jg * 8 + r, Nkb - 1);
-            h[r] = *(const uint2 *)(hcol + (long)j * kStateElems);
+            h[r] = state_piece(j);
         }
     };
     // first and last steps: the same tile, but key blocks past the end are skipped instead of repeated (short
@@ -97,7 +103,7 @@ __global__ __launch_bounds__(256, (TA == 2 && AHEAD == 3) ? 4 : 1) void aggregat
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const int j = ks * kAggK + jg * 8 + r;
-            h[r] = j < Nkb ? *(const uint2 *)(hcol + (long)j * kStateElems) : make_uint2(0u, 0u);
+            h[r] = j < Nkb ? state_piece(j) : make_uint2(0u, 0u);
         }
     };
     auto store_tile = [&](uint16_t *As, const uint2 (&h)[8]) {
@@ -118,11 +124,14 @@ __global__ __launch_bounds__(256, (TA == 2 && AHEAD == 3) ? 4 : 1) void aggregat
         *(uint4 *)(a + 3 * kAggRow) = c3;
     };
     // eight mask bits (key blocks 16 s + 8 g .. + 7 of the K step) -> the B operand of one MFMA: bf16 2.0 where set.
-    // x * 0x8001 puts a second copy of the byte 15 bits up, so that one shift brings bit 2d to bit 14 and bit 2d+1 to
-    // bit 30 of the same dword: the two bf16 exponent bits of 2.0.
+    // x | x << 15 puts a second copy of the byte 15 bits up, so that one shift brings bit 2d to bit 14 and bit 2d+1 to
+    // bit 30 of the same dword: the two bf16 exponent bits of 2.0.  (The empty asm keeps the compiler from turning
+    // the four shifts of that word into four multiplications of x by wide constants: v_mul_lo_u32 runs at a quarter
+    // of the rate of a shift, and three of them per operand were a third of the loop's vector time.)
     auto mask_frag = [&](const uint2 &w, int s) {
         const uint32_t x = ((s < 2 ? w.x : w.y) >> (16 * (s & 1) + 8 * g)) & 0xFFu;
-        const uint32_t m = x * 0x8001u;
+        uint32_t m = x | (x << 15);
+        asm("" : "+v"(m));
         union { uint32_t u[4]; bf16x8 v; } f;
         f.u[0] = (m << 14) & 0x40004000u;
         f.u[1] = (m << 12) & 0x40004000u;

@@ -136,7 +136,7 @@ struct Tile {
     static constexpr int KINS = KBYTES / 1024 / NWAVES;         // 1 KB copy instructions per wave
     static constexpr int VINS = VBYTES / 1024 / NWAVES;
     static constexpr int LOADS = KINS + VINS;                   // per wave per tile
-    static constexpr int SLOTS = NSLOTS;                        // slots of the K ring and of the V^T ring (2: lists of at most two blocks)
+    static constexpr int SLOTS = NSLOTS;                        // slots of the K ring and of the V^T ring
     static constexpr int VRING = SLOTS * KBYTES;                // the V^T ring follows the K ring
     // behind the rings: a 256-byte slot for the Z row, and, for E4M3 inputs (whose K ring is too small for both
     // epilogue operands), 8 KB for W^T
@@ -172,6 +172,7 @@ struct CopyOffsets {
 template <bool B> using flag = std::integral_constant<bool, B>;
 
 #ifdef SLA_PROBE_TIME   /* timing probe only: cycle counter of one wave at five points of every tile */
+__device__ unsigned long long sla_wg_times[2 * 32768];      // 100 MHz clock at the start and the end of every workgroup (the first 32768)
 __device__ unsigned long long sla_probe_times[64 * 8];
 #define SLA_T(c, pt) do { if (probe_on && (c) < 64) { const unsigned long long t_ = __builtin_readcyclecounter(); if (lane == 0) tprobe[(c) * 8 + (pt)] = t_; } } while (0)
 #else
@@ -179,8 +180,7 @@ __device__ unsigned long long sla_probe_times[64 * 8];
 #endif
 
 // NW: 32-row query groups per workgroup (query block = 32 NW rows), one wave per group.
-// SL: ring slots.  Three for the pipeline described above; two are enough when no list has more than two blocks (every
-// tile then has a slot of its own and nothing is requested inside the loop), and a third more workgroups fit a CU.
+// SL: ring slots (three: the pipeline described above).
 template <int NW, bool FP8, int SL>
 __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     const void *__restrict__ Qp, const void *__restrict__ Kp, const uint16_t *__restrict__ Vp, const float *__restrict__ lvs,
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
 {
     constexpr int NWAVES = NW;
     using T = Tile<NWAVES, FP8, SL>;
-    static_assert(SL == 3 || SL == 2, "three ring slots, or two for lists of at most two blocks");
+    static_assert(SL == 3, "the pipeline below needs three ring slots");
     constexpr int BQ = 32 * NW;
     constexpr int ES = FP8 ? 1 : 2;                     // bytes per input element
     constexpr int KROWB = FP8 ? 64 : 128;               // bytes of a K row in LDS
@@ -210,6 +210,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
 #endif
     const bool probe_on = __builtin_amdgcn_readfirstlane((int)(work == total / 2 + 3 && wave == 1)) != 0;
     const unsigned long long tp_c0 = __builtin_readcyclecounter(), tp_r0 = __builtin_amdgcn_s_memrealtime();
+    if (tid == 0 && work < 32768) sla_wg_times[2 * work] = tp_r0;
 #endif
     const int wq = wave;                              // query group of this wave
     const long bh = (long)((unsigned)work / (unsigned)Nqb);      // (the grid fits 32 bits)
@@ -874,11 +875,317 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     }
     SLA_T(61, 5);
 #ifdef SLA_PROBE_TIME
+    if (tid == 0 && work < 32768) sla_wg_times[2 * work + 1] = __builtin_amdgcn_s_memrealtime();
     if (probe_on) {
         const unsigned long long tp_c1 = __builtin_readcyclecounter(), tp_r1 = __builtin_amdgcn_s_memrealtime();
         if (lane == 0) { tprobe[63 * 8 + 6] = tp_c1 - tp_c0; tprobe[63 * 8 + 7] = tp_r1 - tp_r0; }   // wave life: shader clock, 100 MHz clock
         for (int x = lane; x < 64 * 8; x += 64) sla_probe_times[x] = tprobe[x];
     }
+#endif
+}
+
+// The same computation for SHORT critical lists (frame attention: one or two blocks per row; up to kShortList), where
+// a workgroup's life is memory latency (list -> tiles, operands of the linear branch) and little arithmetic: no software
+// pipeline and no rings, so that the kernel fits 128 registers and 17 KB of LDS and eight workgroups of two waves (four
+// of four) share a CU and hide each other's round trips.  Order of work: the linear branch first (its operands, the Hq^T
+// tile, W^T and Z, are asked for together with Q and the list; its result waits in sixteen registers as bf16), then one
+// tile at a time through a single K slot and a single V^T slot: S^T, exact running maximum, fp16 weights carrying the
+// block's V exponent, O^T += V^T P^T (the arithmetic of the careful step above); at the end O = O_sparse / l + O_lin W.
+constexpr int kShortList = 2;
+// (Two tile buffers, the copies of tile c+1 in flight while tile c is worked on, were measured on lists of nine: a
+// workgroup then lives 20 us instead of 31, but only four fit a CU instead of eight, and the launch takes the same time.)
+template <int NW, bool FP8>
+__global__ __launch_bounds__(64 * NW, 4) void attend_short_kernel(
+    const void *__restrict__ Qp, const void *__restrict__ Kp, const uint16_t *__restrict__ Vp, const float *__restrict__ lvs,
+    const float *__restrict__ sQ, const float *__restrict__ sK, RowMap rm,
+    const int32_t *__restrict__ crit_idx, int k_c, const uint16_t *__restrict__ Hq, const uint16_t *__restrict__ WT,
+    int proj_per_head, int phi, int H, int N, int Nqb, int Nkb, long total, float c_exp, uint16_t *__restrict__ O, float *__restrict__ O32)
+{
+    using T = Tile<NW, FP8, 2>;                       // (for the copy-instruction counts and tile sizes only)
+    constexpr int BQ = 32 * NW;
+    constexpr int ES = FP8 ? 1 : 2;
+    constexpr int KROWB = FP8 ? 64 : 128;
+    constexpr int kA = 0, kB = 8192, kZ = 16384;      // LDS: slot A (K tile / Hq^T), slot B (V^T tile / W^T), the Z row
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[kZ + 256];
+    asm volatile("" ::"s"(Qp), "s"(Kp), "s"(Vp), "s"(lvs), "s"(sQ), "s"(sK), "s"(rm.bs), "s"(rm.hs), "s"(rm.ts), "s"(rm.H), "s"(crit_idx),
+                 "s"(k_c), "s"(Hq), "s"(WT), "s"(proj_per_head), "s"(phi), "s"(H), "s"(N), "s"(Nqb), "s"(Nkb), "s"(total), "s"(c_exp), "s"(O), "s"(O32));
+    const long work = xcd_remap(blockIdx.x, total);
+    if (work >= total) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+#ifdef SLA_PROBE_TIME
+    if (tid == 0 && work < 32768) sla_wg_times[2 * work] = __builtin_amdgcn_s_memrealtime();
+#endif
+    const long bh = (long)((unsigned)work / (unsigned)Nqb);
+    const int i = (int)(work - bh * Nqb);
+    const int q = i * BQ + 32 * wave + l32;
+    const bool qok = q < N;
+    const size_t head = rm.head(bh);
+    const int krowb = rm.ts * ES;
+    const uint8_t *Kh = (const uint8_t *)Kp + head * ES;
+    const uint8_t *Vh = (const uint8_t *)(Vp + (size_t)bh * Nkb * kBK * kD);
+
+    // the list (at most kShortList entries, one per lane), then Q
+    const int j0 = lane < k_c ? crit_idx[work * (long)k_c + lane] : -1;
+    bf16x8 qf[4];
+    i32x8 q8;
+    if (FP8) {
+        uint4 w0 = make_uint4(0, 0, 0, 0), w1 = w0;
+        if (qok) {
+            const uint8_t *qr = (const uint8_t *)Qp + head + (size_t)q * rm.ts + 32 * g;
+            w0 = *(const uint4 *)qr;
+            w1 = *(const uint4 *)(qr + 16);
+        }
+        q8[0] = w0.x; q8[1] = w0.y; q8[2] = w0.z; q8[3] = w0.w; q8[4] = w1.x; q8[5] = w1.y; q8[6] = w1.z; q8[7] = w1.w;
+    } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            uint4 w = make_uint4(0, 0, 0, 0);
+            if (qok) w = *(const uint4 *)((const uint16_t *)Qp + head + (size_t)q * rm.ts + 16 * s + 8 * g);
+            qf[s] = __builtin_bit_cast(bf16x8, w);
+        }
+    }
+    const float qscale = FP8 ? sQ[work] : 1.0f;
+
+    CopyOffsets<NW, FP8> co;
+    co.init(wave, lane, krowb);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_p)lds;
+    const uint32_t ktile_bytes = (uint32_t)kBK * (uint32_t)krowb;
+    const int tail_rows = N & (kBK - 1), ragged_j = tail_rows ? Nkb - 1 : -1;
+
+    // ---- the linear branch: operands on their way while the list and Q arrive
+    if (Hq != nullptr) {
+        const uint8_t *Hi8 = (const uint8_t *)(Hq + (size_t)work * kStateElems);
+        const uint8_t *Wh8 = (const uint8_t *)(WT + (proj_per_head ? (size_t)((unsigned)bh % (unsigned)H) * kD * kD : 0));
+#pragma unroll
+        for (int x = 0; x < T::VINS; ++x) copy_1k_to_lds(Hi8, co.v[x], lds_base + kA + (wave_u * T::VINS + x) * 1024);
+#pragma unroll
+        for (int x = 0; x < T::VINS; ++x) copy_1k_to_lds(Wh8, co.v[x], lds_base + kB + (wave_u * T::VINS + x) * 1024);
+        if (tid < 8) copy_1k_to_lds(Hi8 + 64 * kD * 2, tid * 16, lds_base + kZ);
+    }
+    // number of leading valid entries, their V exponents and exp2 constants (a gather that depends on the list)
+    const bool jok = j0 >= 0 && j0 < Nkb;
+    const unsigned long long okm = __ballot(jok);
+    int k = okm == ~0ull ? 64 : __builtin_ctzll(~okm);
+    k = __builtin_amdgcn_readfirstlane(min(k, k_c));
+    const int d_j = jok ? j0 : 0;
+    float d_lv = lvs[bh * Nkb + d_j];
+    float d_cj = FP8 ? fmaxf(c_exp * qscale * sK[bh * Nkb + d_j], 1e-30f) : c_exp;
+    asm volatile("" : "+v"(d_lv), "+v"(d_cj));
+    const float lv_ref = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(d_lv)));
+    d_lv -= lv_ref;
+    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));      // vmcnt(0): Q, the list and the operands have landed
+    wait_copies_and_barrier<0>();
+
+    f32x16 zero16;
+#pragma unroll
+    for (int x = 0; x < 16; ++x) zero16[x] = 0.f;
+    uint32_t lin[16];                                  // O_lin W of this lane's row, bf16 pairs (channel 32e + 8a + 4g + b: lin[8e + 2a + b/2])
+#pragma unroll
+    for (int x = 0; x < 16; ++x) lin[x] = 0u;
+    if (Hq != nullptr) {
+        const uint8_t *stA = lds + kA, *stB = lds + kB, *zrow = lds + kZ;
+        float x[32];
+        if (FP8) {
+#pragma unroll
+            for (int w = 0; w < 8; ++w) {
+                const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(q8[w], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(q8[w], true);
+                x[4 * w + 0] = lo[0] * qscale; x[4 * w + 1] = lo[1] * qscale; x[4 * w + 2] = hi[0] * qscale; x[4 * w + 3] = hi[1] * qscale;
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const uint4 w = __builtin_bit_cast(uint4, qf[s]);
+                x[8 * s + 0] = bf16_lo(w.x); x[8 * s + 1] = bf16_hi(w.x);
+                x[8 * s + 2] = bf16_lo(w.y); x[8 * s + 3] = bf16_hi(w.y);
+                x[8 * s + 4] = bf16_lo(w.z); x[8 * s + 5] = bf16_hi(w.z);
+                x[8 * s + 6] = bf16_lo(w.w); x[8 * s + 7] = bf16_hi(w.w);
+            }
+        }
+        float inv = 1.0f;
+        if (phi == 0) {
+            float mx = x[0];
+#pragma unroll
+            for (int d = 1; d < 32; ++d) mx = fmaxf(mx, x[d]);
+            mx = pair_max(mx);
+            float sum = 0.f;
+#pragma unroll
+            for (int d = 0; d < 32; ++d) { x[d] = fast_exp2((x[d] - mx) * kLog2e); sum += x[d]; }
+            sum += xchg32(sum);
+            inv = 1.0f / sum;
+        } else {
+#pragma unroll
+            for (int d = 0; d < 32; ++d) x[d] = x[d] > 0.f ? x[d] + 1.0f : fast_exp2(x[d] * kLog2e);
+        }
+        bf16x8 fq[4];
+        float den = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int dcol = FP8 ? 32 * g + 8 * s : 16 * s + 8 * g;
+            uint4 o;
+            o.x = pack_bf16(x[8 * s + 0] * inv, x[8 * s + 1] * inv); o.y = pack_bf16(x[8 * s + 2] * inv, x[8 * s + 3] * inv);
+            o.z = pack_bf16(x[8 * s + 4] * inv, x[8 * s + 5] * inv); o.w = pack_bf16(x[8 * s + 6] * inv, x[8 * s + 7] * inv);
+            fq[s] = __builtin_bit_cast(bf16x8, o);
+            const uint4 z = *(const uint4 *)(zrow + dcol * 2);
+            den += bf16_lo(o.x) * bf16_lo(z.x) + bf16_hi(o.x) * bf16_hi(z.x) + bf16_lo(o.y) * bf16_lo(z.y) + bf16_hi(o.y) * bf16_hi(z.y)
+                 + bf16_lo(o.z) * bf16_lo(z.z) + bf16_hi(o.z) * bf16_hi(z.z) + bf16_lo(o.w) * bf16_lo(z.w) + bf16_hi(o.w) * bf16_hi(z.w);
+        }
+        den += xchg32(den);
+        const float inv_den = den > 0.f ? 1.0f / den : 0.f;
+        f32x16 lacc[2];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int hchunk = FP8 ? 4 * g + s : 2 * s + g;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const bf16x8 hf = *(const bf16x8 *)(stA + (32 * e + l32) * 128 + ((hchunk ^ swz8(l32)) << 4));
+                lacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hf, fq[s], s == 0 ? zero16 : lacc[e], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int y = 0; y < 16; ++y) lacc[e][y] *= inv_den;
+        f32x16 pl[2];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const bf16x8 pf = pack8(lacc[s >> 1], 8 * (s & 1));
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const bf16x8 wf = *(const bf16x8 *)(stB + (32 * e + l32) * 128 + (((2 * s + g) ^ swz8(l32)) << 4));
+                pl[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, pf, s == 0 ? zero16 : pl[e], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int y = 0; y < 8; ++y) lin[8 * e + y] = pack_bf16(pl[e][2 * y], pl[e][2 * y + 1]);
+    }
+    wait_copies_and_barrier<0>();                      // every wave is done with the operands: the slots take tiles now
+    auto request_tile = [&](int c) __attribute__((always_inline)) {
+        const uint32_t j = (uint32_t)__builtin_amdgcn_readlane(d_j, c);
+        const uint8_t *kt = Kh + (uint64_t)j * ktile_bytes;
+        const uint32_t kdst = lds_base + kA + wave_u * T::KINS * 1024, vdst = lds_base + kB + wave_u * T::VINS * 1024;
+        if ((int)j != ragged_j) copy_nk_to_lds<T::KINS>(kt, co.k, kdst);
+        else {
+#pragma unroll
+            for (int x = 0; x < T::KINS; ++x)
+                copy_1k_to_lds(kt, co.k[x] - (co.krow[x] - min(co.krow[x], tail_rows - 1)) * krowb, kdst + x * 1024);
+        }
+        copy_nk_to_lds<T::VINS>(Vh + (uint64_t)j * (uint32_t)(kBK * kD * 2), co.v, vdst);
+    };
+
+    // ---- the tiles, one at a time
+    int koff[4], voff[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+        koff[s] = FP8 ? l32 * 64 + ((((2 * g + (s & 1)) ^ swz4(l32))) << 4) : l32 * 128 + (((2 * s + g) ^ swz8(l32)) << 4);
+#pragma unroll
+    for (int st = 0; st < 4; ++st) voff[st] = l32 * 128 + (((2 * st + g) ^ swz8(l32)) << 4);
+    f32x16 oacc[2] = {zero16, zero16};
+    float m_run = -INFINITY, l_sum = 0.f;
+    for (int c = 0; c < k; ++c) {
+        const uint8_t *ldsb = lds;
+        const uint32_t j = (uint32_t)__builtin_amdgcn_readlane(d_j, c);
+        request_tile(c);
+        const int valid = (int)j == ragged_j ? tail_rows : kBK;
+        const float cj = FP8 ? __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(d_cj), c)) : c_exp;
+        const float lsv = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(d_lv), c));
+        const float rsv = fast_exp2(lsv);
+        wait_copies_and_barrier<0>();                  // tile c has landed
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            f32x16 sacc;
+#pragma unroll
+            for (int x = 0; x < 16; ++x) sacc[x] = (32 * half + 8 * (x >> 2) + 4 * g + (x & 3)) < valid ? 0.f : -INFINITY;
+            if (FP8) {
+                const i32x4 w0 = *(const i32x4 *)(ldsb + kA + half * 32 * KROWB + koff[0]), w1 = *(const i32x4 *)(ldsb + kA + half * 32 * KROWB + koff[1]);
+                i32x8 k8;
+                k8[0] = w0[0]; k8[1] = w0[1]; k8[2] = w0[2]; k8[3] = w0[3]; k8[4] = w1[0]; k8[5] = w1[1]; k8[6] = w1[2]; k8[7] = w1[3];
+                sacc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(k8, q8, sacc, 0, 0, 0, 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int st = 0; st < 4; ++st) {
+                    const bf16x8 kf = *(const bf16x8 *)(ldsb + kA + half * 32 * KROWB + koff[st]);
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], sacc, 0, 0, 0);
+                }
+            }
+            const float top = pair_max(max16(sacc)) * cj + lsv;        // -inf if the row sees no real key in this unit
+            if (__ballot(top > m_run)) {
+                const float m_new = fmaxf(m_run, top);
+                const float alpha = m_new == m_run ? 1.0f : fast_exp2(m_run - m_new);
+                l_sum *= alpha;
+#pragma unroll
+                for (int e = 0; e < 2; ++e)
+#pragma unroll
+                    for (int x = 0; x < 16; ++x) oacc[e][x] *= alpha;
+                m_run = m_new;
+            }
+            const float mfin = m_run == -INFINITY ? 0.f : m_run;
+            float sum = 0.f;
+#pragma unroll
+            for (int x = 0; x < 16; ++x) {
+                const float pu = fast_exp2(fmaf(sacc[x], cj, -mfin));
+                sum += pu;
+                sacc[x] = pu * rsv;
+            }
+            l_sum += sum;
+            const f16x8 p0 = pack8_f16(sacc, 0), p1 = pack8_f16(sacc, 8);
+#pragma unroll
+            for (int ss = 0; ss < 2; ++ss)
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const f16x8 vf = *(const f16x8 *)(ldsb + kB + e * 32 * 128 + voff[2 * half + ss]);
+                    oacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, ss == 0 ? p0 : p1, oacc[e], 0, 0, 0);
+                }
+        }
+        wait_copies_and_barrier<0>();                  // all waves are done with the tile before the next one is asked for
+    }
+
+    // ---- O = O_sparse / l + O_lin W
+    const float l_run = l_sum + xchg32(l_sum);
+    const float inv_l = l_run > 0.f ? fast_exp2(lv_ref) / l_run : 0.f;
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+        for (int y = 0; y < 8; ++y) {
+            oacc[e][2 * y] = fmaf(oacc[e][2 * y], inv_l, bf16_lo(lin[8 * e + y]));
+            oacc[e][2 * y + 1] = fmaf(oacc[e][2 * y + 1], inv_l, bf16_hi(lin[8 * e + y]));
+        }
+    if (O32 != nullptr) {
+        if (qok) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+#pragma unroll
+                for (int aa = 0; aa < 4; ++aa)
+                    *(float4 *)(O32 + head + (size_t)q * rm.ts + 32 * e + 8 * aa + 4 * g) =
+                        make_float4(oacc[e][4 * aa + 0], oacc[e][4 * aa + 1], oacc[e][4 * aa + 2], oacc[e][4 * aa + 3]);
+        }
+    } else {
+        uint8_t *ot = lds + wave * 4096;               // (NW x 4 KB: inside the two slots)
+        const int f = ((l32 >> 1) & 7) << 1;
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int aa = 0; aa < 4; ++aa) {
+                uint2 o;
+                o.x = pack_bf16(oacc[e][4 * aa + 0], oacc[e][4 * aa + 1]);
+                o.y = pack_bf16(oacc[e][4 * aa + 2], oacc[e][4 * aa + 3]);
+                const int piece = 8 * e + 2 * aa + g;
+                *(uint2 *)(ot + l32 * 128 + ((piece ^ f) << 3)) = o;
+            }
+        wave_lds_sync();
+        const int q0w = i * BQ + 32 * wave;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int r = 8 * kk + (lane >> 3), ch = lane & 7;
+            const int fr = ((r >> 1) & 7) << 1;
+            const uint4 v = *(const uint4 *)(ot + r * 128 + (((2 * ch) ^ fr) << 3));
+            if (q0w + r < N) *(uint4 *)(O + head + (size_t)(q0w + r) * rm.ts + ch * 8) = v;
+        }
+    }
+#ifdef SLA_PROBE_TIME
+    if (tid == 0 && work < 32768) sla_wg_times[2 * work + 1] = __builtin_amdgcn_s_memrealtime();
 #endif
 }
 
@@ -889,6 +1196,7 @@ __global__ __launch_bounds__(256) void transpose_w_kernel(const uint16_t *__rest
 }
 
 #ifdef SLA_PROBE_TIME
+extern "C" int sla_probe_read_wg(unsigned long long *dst, int n) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(sla_wg_times), sizeof(unsigned long long) * 2 * n); }
 extern "C" int sla_probe_read(unsigned long long *dst) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(sla_probe_times), sizeof(unsigned long long) * 64 * 8); }
 #endif
 
@@ -920,10 +1228,16 @@ hipError_t launch_attend(const void *Q, const void *K, const void *Vp, const flo
     const float c_exp = sm_scale * kLog2e;
 #define SLA_ATT(NW, F8, SL) return launch_attend_t<NW, F8, SL>(Q, K, Vp, lvs, sQ, sK, rm, crit_idx, k_c, Hq, WT, proj_per_head, phi, H, N, Nqb, Nkb, total, c_exp, O, O32, st)
     if (bq == 128) { if (fp8) SLA_ATT(4, true, 3); else SLA_ATT(4, false, 3); }
-    if (k_c > 2) { if (fp8) SLA_ATT(2, true, 3); else SLA_ATT(2, false, 3); }
-    // lists of at most two blocks (frame attention): two ring slots, four workgroups per CU
-    if (fp8) SLA_ATT(2, true, 2);
-    SLA_ATT(2, false, 2);
+    // lists of at most two blocks (frame attention): the kernel without a pipeline, eight workgroups per CU
+    if (k_c <= kShortList) {
+        if (fp8) attend_short_kernel<2, true><<<(unsigned)xcd_grid(total), 128, 0, st>>>(Q, K, (const uint16_t *)Vp, lvs, sQ, sK, rm, crit_idx, k_c, (const uint16_t *)Hq,
+                                                                                       (const uint16_t *)WT, proj_per_head, phi, H, N, Nqb, Nkb, total, c_exp, (uint16_t *)O, O32);
+        else attend_short_kernel<2, false><<<(unsigned)xcd_grid(total), 128, 0, st>>>(Q, K, (const uint16_t *)Vp, lvs, sQ, sK, rm, crit_idx, k_c, (const uint16_t *)Hq,
+                                                                                      (const uint16_t *)WT, proj_per_head, phi, H, N, Nqb, Nkb, total, c_exp, (uint16_t *)O, O32);
+        return hipGetLastError();
+    }
+    if (fp8) SLA_ATT(2, true, 3);
+    SLA_ATT(2, false, 3);
 #undef SLA_ATT
 }
 

@@ -27,6 +27,10 @@ CASES = {
     "c4_batch2": (C4.with_(B=2, H=2, N=1374), 2, 12),
     "c4_bq64_kc6": (C4.with_(H=2, N=1000, bq=64), 6, 5),          # E4M3, 64-row query blocks
     "c4_batch2_bq64": (C4.with_(B=2, H=3, N=900, bq=64), 5, 4),
+    # 64-row query blocks with at most two critical blocks: the attention kernel for short lists
+    "c4_bq64_kc2": (C4.with_(H=2, N=1000, bq=64), 2, 5),
+    "c4_batch2_bq64_kc1": (C4.with_(B=2, H=3, N=650, bq=64, proj_per_head=True), 1, 3),
+    "c0_batch2_kc1_tail": (C0.with_(B=2, H=3, N=330), 1, 2),
 }
 
 
@@ -48,7 +52,7 @@ def _f32_forward(case, labels_np):
 
 
 @pytest.mark.parametrize("name", ["c0", "c0_tail150", "c0_bq128_tail", "c1_small", "c2_small", "c3_small", "c4_small",
-                                  "h3_per_head", "c4_bq64_kc6"])
+                                  "h3_per_head", "c4_bq64_kc6", "c4_bq64_kc2", "c4_batch2_bq64_kc1"])
 def test_stated_tolerance_on_the_fp32_result(oracle, name):
     """max |O - oracle| <= tau * RMS(oracle), tau = 2e-2 (bf16 inputs) / 6e-2 (E4M3 inputs), asserted as stated on the
     kernel's fp32 result, and the bf16 output is that result rounded to nearest even, bit for bit: together they bound
@@ -78,7 +82,8 @@ def test_stated_tolerance_on_the_fp32_result_full_size_c1(oracle):
     assert err <= G.TOL["bf16"]
 
 
-@pytest.mark.parametrize("name", ["h3_per_head", "h3_per_head_bq128", "c4_batch2", "c4_bq64_kc6", "c4_batch2_bq64"])
+@pytest.mark.parametrize("name", ["h3_per_head", "h3_per_head_bq128", "c4_batch2", "c4_bq64_kc6", "c4_batch2_bq64", "c4_bq64_kc2",
+                                  "c4_batch2_bq64_kc1", "c0_batch2_kc1_tail"])
 @pytest.mark.parametrize("phi", ["softmax", "elu1"])
 def test_forward_more_shapes(oracle, name, phi):
     case = _case(name, phi=phi)
@@ -148,7 +153,7 @@ def test_e4m3_forward_with_all_zero_blocks(oracle, bq):
     G.assert_output(G.gather_blocks(G.bf16_tensor_to_f64(O2), ref["sel"], bq, 2), ref["O"], "fp8", f"zero blocks, classified, bq={bq}")
 
 
-@pytest.mark.parametrize("name", ["c0_bq128_tail", "h3_per_head", "c4_bq64_kc6", "c4_small"])
+@pytest.mark.parametrize("name", ["c0_bq128_tail", "h3_per_head", "c4_bq64_kc6", "c4_small", "c4_bq64_kc2", "c0_batch2_kc1_tail"])
 def test_given_labels_with_short_critical_lists(oracle, name):
     """Labels whose rows hold fewer critical blocks than k_crit (their lists end in unfilled entries), none at all, or
     only the ragged last block."""

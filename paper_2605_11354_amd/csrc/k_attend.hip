@@ -174,8 +174,10 @@ template <bool B> using flag = std::integral_constant<bool, B>;
 #ifdef SLA_PROBE_TIME   /* timing probe only: cycle counter of one wave at five points of every tile */
 __device__ unsigned long long sla_wg_times[2 * 32768];      // 100 MHz clock at the start and the end of every workgroup (the first 32768)
 __device__ unsigned long long sla_probe_times[64 * 8];
-#define SLA_T(c, pt) do { if (probe_on && (c) < 64) { const unsigned long long t_ = __builtin_readcyclecounter(); if (lane == 0) tprobe[(c) * 8 + (pt)] = t_; } } while (0)
+#define SLA_TP(row, pt) do { if (probe_on) { const unsigned long long t_ = __builtin_readcyclecounter(); if (lane == 0) tprobe[(row) * 8 + (pt)] = t_; } } while (0)
+#define SLA_T(c, pt) do { if ((c) < 61) SLA_TP(c, pt); } while (0)      /* rows 61..63: epilogue, prologue, wave life */
 #else
+#define SLA_TP(row, pt)
 #define SLA_T(c, pt)
 #endif
 
@@ -223,7 +225,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     const uint8_t *Vh = (const uint8_t *)(Vp + (size_t)bh * Nkb * kBK * kD);
     const float *lvh = lvs + bh * Nkb;
 
-    SLA_T(62, 0);
+    SLA_TP(62, 0);
     // The critical list of the row is asked for first of all: the tile copies, the scale gather and with them the whole
     // prologue wait for it (loads return in order: behind the Q rows it would arrive after them).
     const int32_t *ci = crit_idx + work * (long)k_c;
@@ -319,7 +321,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     };
     auto entry_j = [&](int c) { return __builtin_amdgcn_readlane(d_j, c - wbase); };
 
-    SLA_T(62, 1);
+    SLA_TP(62, 1);
     CopyOffsets<NWAVES, FP8> co;
     co.init(wave, lane, krowb);
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);                       // same value, provably uniform
@@ -485,14 +487,14 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     if (k > 2) request_K(2, 2 * T::KBYTES);
     if (k > 0) request_V(0, 0);
     if (k > 1) request_V(1, T::VBYTES);
-    SLA_T(62, 2);
+    SLA_TP(62, 2);
     load_window_scales(true);
     // Let the Q fragments (ordinary loads the compiler tracks) and the first tiles land here, once: left to the
     // compiler, its vmcnt(0) for Q would sit in front of their first use inside the loop and drain the ring every trip.
-    SLA_T(62, 3);
+    SLA_TP(62, 3);
     __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));      // vmcnt(0), as a builtin so that the compiler's bookkeeping sees it
     wait_copies_and_barrier<0>();
-    SLA_T(62, 4);
+    SLA_TP(62, 4);
 
     // Units of this wave: u = 2 c + hh is the 32-key half hh of tile c.  Step u accumulates unit u-1
     // (V^T fragments vf_use), forms S^T of unit u+1 (K fragments kf_use) and runs the softmax of unit u; meanwhile the
@@ -514,7 +516,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
         if (U > 1) kf_use = load_kfrag(unit_tile(1) * T::KBYTES, unit_half(1));     // for S^T of unit 1, formed in step 0
     }
 
-    SLA_T(62, 5);
+    SLA_TP(62, 5);
 #define SLA_SB() __builtin_amdgcn_sched_barrier(0)
 #define SLA_PIN(...) asm volatile("" : __VA_ARGS__)
     // Whether some lane's largest exponent in the unit whose S^T is s would exceed kRaise against the lane's running
@@ -733,7 +735,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
 #undef SLA_SB
 
     wait_copies_and_barrier<0>();                      // epilogue operands landed; every wave is past its last tile
-    SLA_T(61, 0);
+    SLA_TP(61, 0);
     if (k > 0) accumulate(vf_use, w_prev);             // the last unit's weights
     l_part += l_alt;
     float l_run = l_part + xchg32(l_part) + l_full;
@@ -747,7 +749,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
 #pragma unroll
         for (int x = 0; x < 16; ++x) oacc[e][x] *= inv_l;
 
-    SLA_T(61, 1);
+    SLA_TP(61, 1);
     if (Hq != nullptr) {
         // The sixteen operand fragments of the two products below are read from LDS here, in one go, so that their latency
         // passes behind the arithmetic of phi(Q) (read where they are used, each would be awaited on its own).
@@ -787,9 +789,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
 #pragma unroll
             for (int d = 1; d < 32; ++d) mx = fmaxf(mx, x[d]);
             mx = pair_max(mx);
+            const float nmx = -mx * kLog2e;
             float sum = 0.f;
 #pragma unroll
-            for (int d = 0; d < 32; ++d) { x[d] = fast_exp2((x[d] - mx) * kLog2e); sum += x[d]; }
+            for (int d = 0; d < 32; ++d) { x[d] = fast_exp2(fmaf(x[d], kLog2e, nmx)); sum += x[d]; }
             sum += xchg32(sum);
             inv = 1.0f / sum;
         } else {                                               // ELU(x)+1, elementwise
@@ -806,13 +809,12 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
             o.z = pack_bf16(x[8 * s + 4] * inv, x[8 * s + 5] * inv); o.w = pack_bf16(x[8 * s + 6] * inv, x[8 * s + 7] * inv);
             fq[s] = __builtin_bit_cast(bf16x8, o);
             const uint4 z = *(const uint4 *)(zrow + dcol * 2);
-            den += bf16_lo(o.x) * bf16_lo(z.x) + bf16_hi(o.x) * bf16_hi(z.x) + bf16_lo(o.y) * bf16_lo(z.y) + bf16_hi(o.y) * bf16_hi(z.y)
-                 + bf16_lo(o.z) * bf16_lo(z.z) + bf16_hi(o.z) * bf16_hi(z.z) + bf16_lo(o.w) * bf16_lo(z.w) + bf16_hi(o.w) * bf16_hi(z.w);
+            den = dot2_bf16(o.w, z.w, dot2_bf16(o.z, z.z, dot2_bf16(o.y, z.y, dot2_bf16(o.x, z.x, den))));
         }
         den += xchg32(den);
         const float inv_den = den > 0.f ? 1.0f / den : 0.f;     // no marginal block: H = Z = 0 and O_lin = 0
 
-        SLA_T(61, 2);
+        SLA_TP(61, 2);
         // ---- O_lin^T = Hq^T phi(Q)^T   (Hq^T tile staged with the tile swizzle)
         f32x16 lacc[2];
 #pragma unroll
@@ -837,9 +839,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
     // ---- store.  Register 4a+b of oacc[e] is channel 32e + 8a + 4g + b of row q: the wave's 32x64 tile
     // is transposed through a private 4 KB LDS slice (8-byte pieces, XOR-swizzled by row) so that it
     // leaves as full 128-byte rows, 16 bytes per lane.
-    SLA_T(61, 3);
+    SLA_TP(61, 3);
     wait_copies_and_barrier<0>();                      // all waves are done reading the epilogue operands
-    SLA_T(61, 4);
+    SLA_TP(61, 4);
     if (O32 != nullptr) {
         // diagnostic output: the fp32 values the bf16 store below would round, straight from the accumulators
         if (qok) {
@@ -873,7 +875,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_kernel(
             if (q0w + r < N) *(uint4 *)(O + head + (size_t)(q0w + r) * rm.ts + ch * 8) = v;
         }
     }
-    SLA_T(61, 5);
+    SLA_TP(61, 5);
 #ifdef SLA_PROBE_TIME
     if (tid == 0 && work < 32768) sla_wg_times[2 * work + 1] = __builtin_amdgcn_s_memrealtime();
     if (probe_on) {
@@ -1008,9 +1010,10 @@ __global__ __launch_bounds__(64 * NW, 4) void attend_short_kernel(
 #pragma unroll
             for (int d = 1; d < 32; ++d) mx = fmaxf(mx, x[d]);
             mx = pair_max(mx);
+            const float nmx = -mx * kLog2e;
             float sum = 0.f;
 #pragma unroll
-            for (int d = 0; d < 32; ++d) { x[d] = fast_exp2((x[d] - mx) * kLog2e); sum += x[d]; }
+            for (int d = 0; d < 32; ++d) { x[d] = fast_exp2(fmaf(x[d], kLog2e, nmx)); sum += x[d]; }
             sum += xchg32(sum);
             inv = 1.0f / sum;
         } else {
@@ -1027,8 +1030,7 @@ __global__ __launch_bounds__(64 * NW, 4) void attend_short_kernel(
             o.z = pack_bf16(x[8 * s + 4] * inv, x[8 * s + 5] * inv); o.w = pack_bf16(x[8 * s + 6] * inv, x[8 * s + 7] * inv);
             fq[s] = __builtin_bit_cast(bf16x8, o);
             const uint4 z = *(const uint4 *)(zrow + dcol * 2);
-            den += bf16_lo(o.x) * bf16_lo(z.x) + bf16_hi(o.x) * bf16_hi(z.x) + bf16_lo(o.y) * bf16_lo(z.y) + bf16_hi(o.y) * bf16_hi(z.y)
-                 + bf16_lo(o.z) * bf16_lo(z.z) + bf16_hi(o.z) * bf16_hi(z.z) + bf16_lo(o.w) * bf16_lo(z.w) + bf16_hi(o.w) * bf16_hi(z.w);
+            den = dot2_bf16(o.w, z.w, dot2_bf16(o.z, z.z, dot2_bf16(o.y, z.y, dot2_bf16(o.x, z.x, den))));
         }
         den += xchg32(den);
         const float inv_den = den > 0.f ? 1.0f / den : 0.f;

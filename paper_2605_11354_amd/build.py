@@ -13,7 +13,7 @@ LIB = os.path.join(HERE, "libsla.so")
 # The same library with the timing probes of k_attend.hip and k_linear.hip compiled in (-DSLA_PROBE_TIME: one wave writes
 # the shader-clock and 100 MHz counters at the phase boundaries of its work; results are unchanged).  Only probe.py loads it.
 PROBE_LIB = os.path.join(HERE, "libsla_probe.so")
-PROBED = ["k_attend.hip", "k_linear.hip"]
+PROBED = ["k_attend.hip", "k_linear.hip", "k_classify.hip"]
 SOURCES = ["sla_api.hip", "k_classify.hip", "k_states.hip", "k_aggregate.hip", "k_attend.hip", "k_backward.hip", "k_quant.hip", "k_linear.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-ffp-contract=off", "-Wall", "-Wextra",
          "-Wno-unused-parameter", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -190,9 +190,108 @@ __global__ __launch_bounds__(256) void scores_kernel(const double *__restrict__ 
     }
 }
 
+// The same product with an 8 x 8 register tile per thread (workgroup tile 128 x 128, 256 threads), for heads with
+// enough tiles to fill the chip.  With 4 x 4 tiles a channel step reads 64 bytes of LDS per lane for 16 fma and LDS is
+// the busy unit; 8 x 8 reads 128 bytes for 64 fma, so the fp64 pipe is.  Channels arrive sixteen at a time: the next
+// chunk is in flight in registers while the present one is consumed, and goes to the other LDS buffer (one barrier
+// per chunk).  Each accumulator still sees its channels in ascending order: the same fma chain, the same bits.
+template <bool KEYS>
+__global__ __launch_bounds__(256, 2) void scores_big_kernel(const double *__restrict__ qbar, const double *__restrict__ kbar,
+                                                            int Nqb, int Nkb, int pitch, double *__restrict__ S)
+{
+    constexpr int TILE = 128, CH = 16, PER = TILE * CH / 256, LP = TILE + 2;
+    __shared__ __align__(16) double qs[2][CH][LP];
+    __shared__ __align__(16) double ks[2][CH][LP];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int j0 = blockIdx.x * TILE, i0 = blockIdx.y * TILE;
+    const long bh = blockIdx.z;
+    const double *qh = qbar + bh * (long)Nqb * kD;
+    const double *kh = kbar + bh * (long)Nkb * kD;
+    double acc[8][8];
+#pragma unroll
+    for (int a = 0; a < 8; ++a)
+#pragma unroll
+        for (int b = 0; b < 8; ++b) acc[a][b] = 0.0;
+    // element r of a thread: channel (tid & 15) of row (tid >> 4) + 16 r of the chunk; rows past the end repeat the
+    // last one (their results are not stored), so the loads are unconditional
+    const int sd = tid & 15, srow = tid >> 4;
+    const double *qsrc[PER], *ksrc[PER];
+#pragma unroll
+    for (int r = 0; r < PER; ++r) {
+        qsrc[r] = qh + (long)min(i0 + srow + 16 * r, Nqb - 1) * kD + sd;
+        ksrc[r] = kh + (long)min(j0 + srow + 16 * r, Nkb - 1) * kD + sd;
+    }
+    double qr[PER], kr[PER];
+    auto fetch = [&](int c) {
+#pragma unroll
+        for (int r = 0; r < PER; ++r) { qr[r] = qsrc[r][c * CH]; kr[r] = ksrc[r][c * CH]; }
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int r = 0; r < PER; ++r) { qs[buf][sd][srow + 16 * r] = qr[r]; ks[buf][sd][srow + 16 * r] = kr[r]; }
+    };
+    fetch(0);
+    stage(0);
+    lds_barrier();
+#pragma unroll
+    for (int c = 0; c < kD / CH; ++c) {
+        if (c + 1 < kD / CH) fetch(c + 1);
+#pragma unroll 2
+        for (int d = 0; d < CH; ++d) {
+            double qv[8], kv[8];
+#pragma unroll
+            for (int a = 0; a < 8; ++a) { qv[a] = qs[c & 1][d][ty * 8 + a]; kv[a] = ks[c & 1][d][tx * 8 + a]; }
+#pragma unroll
+            for (int a = 0; a < 8; ++a)
+#pragma unroll
+                for (int b = 0; b < 8; ++b) acc[a][b] = fma(qv[a], kv[b], acc[a][b]);
+        }
+        if (c + 1 < kD / CH) {
+            stage((c + 1) & 1);            // every wave is past the chunk before this one (the barrier of the last trip)
+            lds_barrier();
+        }
+    }
+    // a thread's eight results of a row are contiguous; the row pitch is a multiple of 8 entries
+    const int gj = j0 + tx * 8;
+    if constexpr (KEYS) {
+        uint32_t *Kh = (uint32_t *)S + bh * (long)Nqb * pitch;
+#pragma unroll
+        for (int a = 0; a < 8; ++a) {
+            const int gi = i0 + ty * 8 + a;
+            if (gi < Nqb && gj < pitch) {
+                uint4 *dst = (uint4 *)(Kh + (long)gi * pitch + gj);
+                dst[0] = make_uint4((uint32_t)(desc_key(acc[a][0]) >> 32), (uint32_t)(desc_key(acc[a][1]) >> 32),
+                                    (uint32_t)(desc_key(acc[a][2]) >> 32), (uint32_t)(desc_key(acc[a][3]) >> 32));
+                dst[1] = make_uint4((uint32_t)(desc_key(acc[a][4]) >> 32), (uint32_t)(desc_key(acc[a][5]) >> 32),
+                                    (uint32_t)(desc_key(acc[a][6]) >> 32), (uint32_t)(desc_key(acc[a][7]) >> 32));
+            }
+        }
+    } else {
+        double *Sh = S + bh * (long)Nqb * pitch;
+#pragma unroll
+        for (int a = 0; a < 8; ++a) {
+            const int gi = i0 + ty * 8 + a;
+            if (gi < Nqb && gj < pitch) {
+                double2 *dst = (double2 *)(Sh + (long)gi * pitch + gj);
+#pragma unroll
+                for (int b = 0; b < 4; ++b) dst[b] = double2{acc[a][2 * b], acc[a][2 * b + 1]};
+            }
+        }
+    }
+}
+
+// launches with at least one 128 x 128 tile for each of the chip's 512 workgroup slots (two per compute unit) use the
+// big-tile kernel; smaller ones fill the chip better with 64 x 64 tiles
+constexpr long kBigScoreTiles = 512;
+
 hipError_t launch_scores(const double *qbar, const double *kbar, int BH, int Nqb, int Nkb,
                          int pitch, double *S, hipStream_t st)
 {
+    const dim3 big((Nkb + 127) / 128, (Nqb + 127) / 128, BH);
+    if ((long)big.x * big.y * big.z >= kBigScoreTiles) {
+        scores_big_kernel<false><<<big, 256, 0, st>>>(qbar, kbar, Nqb, Nkb, pitch, S);
+        return hipGetLastError();
+    }
     dim3 grid((Nkb + 63) / 64, (Nqb + 63) / 64, BH);
     scores_kernel<false><<<grid, 256, 0, st>>>(qbar, kbar, Nqb, Nkb, pitch, S);
     return hipGetLastError();
@@ -849,6 +948,11 @@ hipError_t launch_classify_fused(const void *Q, const float *sQ, bool fp8, RowMa
 hipError_t launch_score_keys(const double *qbar, const double *kbar, int BH, int Nqb, int Nkb, int pitch, uint32_t *keys,
                              hipStream_t st)
 {
+    const dim3 big((Nkb + 127) / 128, (Nqb + 127) / 128, BH);
+    if ((long)big.x * big.y * big.z >= kBigScoreTiles) {
+        scores_big_kernel<true><<<big, 256, 0, st>>>(qbar, kbar, Nqb, Nkb, pitch, (double *)keys);
+        return hipGetLastError();
+    }
     dim3 grid((Nkb + 63) / 64, (Nqb + 63) / 64, BH);
     scores_kernel<true><<<grid, 256, 0, st>>>(qbar, kbar, Nqb, Nkb, pitch, (double *)keys);
     return hipGetLastError();
@@ -868,53 +972,98 @@ __device__ __forceinline__ uint32_t wave_minmax_u32(uint32_t v)
     return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
+#ifdef SLA_PROBE_TIME   /* timing probe only: cycle counter of one row's wave at the phase boundaries of the selection */
+__device__ unsigned long long sla_select_probe_times[32];
+__device__ int sla_select_probe_on;                      // set by the probed wave for the helpers it calls
+#define SLA_ST(on, pt) do { if (on) { const unsigned long long t_ = __builtin_readcyclecounter(); if ((threadIdx.x & 63) == 0) sla_select_probe_times[pt] = t_; } } while (0)
+extern "C" int sla_probe_read_select(unsigned long long *dst) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(sla_select_probe_times), sizeof(unsigned long long) * 32); }
+#else
+#define SLA_ST(on, pt)
+#endif
+
 // (T, r, n): the k smallest (value, index) pairs among the candidates are the candidates with value < T plus the r
-// lowest-index ones of the n candidates with value == T.
+// lowest-index ones of the n candidates with value == T, or, if r == n == 1, the candidates with value <= T (T is then
+// an upper bound of the one key at the threshold, below the next key, rather than that key itself).
 struct Cut { uint32_t T; int r, n; };
 
-// Radix descent, eight bits at a time from the top, for up to two ranks at once (two[t] = rank t wanted).  A slot m
-// of a lane is a candidate if cand(m); while both ranks follow the same prefix one histogram serves both.  hist:
-// 512 counters private to the wave.  Requires 1 <= k[t] <= number of candidates.
-template <int KPL, class Cand>
-__device__ __forceinline__ void radix_cuts(const uint32_t (&val)[KPL], Cand cand, const int (&k)[2], const bool (&want)[2],
-                                           uint32_t *hist, Cut (&cut)[2])
+// The row's keys live in LDS (kv[j] = key of block j) and every pass over them is a rolled loop.  (Held in registers
+// with the loops unrolled the kernel was 18 000 instructions of straight-line code and, with 34 keys per lane, spilled.)
+// The kernel is bound by instruction issue -- about three waves per SIMD, each instruction of a wave taking the SIMD
+// some six cycles -- so the passes are written for few instructions per key: sixteen bytes per LDS read where the
+// order of the keys does not matter, no predicated atomics (a key that does not count adds to a spare word of its
+// lane instead, which costs one select where masking the lane out costs four scalar instructions).
+
+// The keys a radix descent looks at.  AllKeys: every entry of kv[0, 256 nit), four consecutive ones per lane and trip.
+struct AllKeys {
+    const uint32_t *kv;
+    int nit;
+    template <class F>
+    __device__ __forceinline__ void for_each(F f) const
+    {
+        const uint4 *q = (const uint4 *)kv + (threadIdx.x & 63);
+#pragma unroll 2
+        for (int it = 0; it < nit; ++it) {
+            const uint4 v = q[it * 64];
+            f(v.x); f(v.y); f(v.z); f(v.w);
+        }
+    }
+};
+// MemberKeys: entry 64 m + lane for the set bits m of the lane's mask.
+struct MemberKeys {
+    const uint32_t *kv;
+    int nslots;
+    uint64_t mem;
+    template <class F>
+    __device__ __forceinline__ void for_each(F f) const
+    {
+        const int lane = threadIdx.x & 63;
+        for (int m = 0; m < nslots; ++m)
+            if ((mem >> m) & 1) f(kv[m * 64 + lane]);
+    }
+};
+
+// Radix descent, eight bits at a time from the top, for up to two ranks at once (want[t] = rank t wanted) over the
+// keys of `keys`; while both ranks follow the same prefix one histogram serves both.  hist: two histograms of 256
+// counters and a spare word per lane, private to the wave.  Requires 1 <= k[t] <= number of keys.
+template <class Keys>
+__device__ __forceinline__ void radix_cuts(const Keys keys, const int (&k)[2], const bool (&want)[2],
+                                           uint32_t *hist, Cut (&cut)[2], bool probe = false)
 {
     const int lane = threadIdx.x & 63;
+    int pass_ = 0;
+    (void)pass_; (void)probe;
     uint32_t prefix[2] = {0u, 0u};
     int kk[2] = {k[0], k[1]};
     bool act[2] = {want[0], want[1]};
+    const uint32_t spare = 512u + lane;
     for (int shift = 24; shift >= 0 && (act[0] || act[1]); shift -= 8) {
-        const bool both = act[0] && act[1], same = both && prefix[0] == prefix[1];
+        const bool both = act[0] && act[1], two = both && prefix[0] != prefix[1];
         wave_lds_sync();
         *(uint4 *)(hist + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
-        if (both && !same) *(uint4 *)(hist + 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
+        if (two) *(uint4 *)(hist + 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
         wave_lds_sync();
-        const int t0 = act[0] ? 0 : 1;                      // the rank whose counts go to the first histogram
-        if (shift == 24) {                                  // no prefix yet: every candidate counts, one histogram
-#pragma unroll
-            for (int m = 0; m < KPL; ++m)
-                if (cand(m)) atomicAdd(&hist[val[m] >> 24], 1u);
-        } else if (both && !same) {
-#pragma unroll
-            for (int m = 0; m < KPL; ++m) {
-                if (!cand(m)) continue;
-                const uint32_t p = val[m] >> (shift + 8), d = (val[m] >> shift) & 255u;
-                if (p == prefix[0]) atomicAdd(&hist[d], 1u);
-                if (p == prefix[1]) atomicAdd(&hist[256 + d], 1u);
-            }
+        const uint32_t pf0 = prefix[act[0] ? 0 : 1], pf1 = prefix[1];   // the first histogram counts for the first active rank
+        SLA_ST(probe && pass_ < 4, 4 + 3 * pass_);
+        if (shift == 24) {                                   // no prefix yet: every key counts (both ranks, one histogram)
+            keys.for_each([&](uint32_t v) { atomicAdd(&hist[v >> 24], 1u); });
+        } else if (!two) {
+            keys.for_each([&](uint32_t v) {
+                const uint32_t d = (v >> shift) & 255u;
+                atomicAdd(&hist[(v >> (shift + 8)) == pf0 ? d : spare], 1u);
+            });
         } else {
-            const uint32_t pf = prefix[t0];
-#pragma unroll
-            for (int m = 0; m < KPL; ++m) {
-                if (!cand(m)) continue;
-                if ((val[m] >> (shift + 8)) == pf) atomicAdd(&hist[(val[m] >> shift) & 255u], 1u);
-            }
+            keys.for_each([&](uint32_t v) {
+                const uint32_t p = v >> (shift + 8), d = (v >> shift) & 255u;
+                atomicAdd(&hist[p == pf0 ? d : spare], 1u);
+                atomicAdd(&hist[p == pf1 ? 256u + d : spare], 1u);
+            });
         }
         wave_lds_sync();
+        SLA_ST(probe && pass_ < 4, 5 + 3 * pass_);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             if (!act[t]) continue;
-            const uint32_t *h = hist + ((t == 1 && both && !same) ? 256 : 0);
+            const uint32_t *h = hist + ((t == 1 && two) ? 256 : 0);
             const uint4 c4 = *(const uint4 *)(h + lane * 4);
             const uint32_t c[4] = {c4.x, c4.y, c4.z, c4.w};
             const uint32_t mine = c[0] + c[1] + c[2] + c[3];
@@ -937,142 +1086,207 @@ __device__ __forceinline__ void radix_cuts(const uint32_t (&val)[KPL], Cand cand
             prefix[t] = (prefix[t] << 8) | digit;
             kk[t] -= (int)before;
             if (shift == 0) { cut[t] = Cut{prefix[t], kk[t], (int)cnt}; act[t] = false; }
-            else if (cnt == 1) {                                              // one candidate carries this prefix: fetch it
-                uint32_t found = 0;
-                bool have = false;
-#pragma unroll
-                for (int m = 0; m < KPL; ++m)
-                    if (cand(m) && (val[m] >> shift) == prefix[t]) { found = val[m]; have = true; }
-                cut[t] = Cut{bcast_u32(found, __ffsll((long long)__ballot(have)) - 1), 1, 1};
+            else if (cnt == 1) {
+                // one key carries this prefix: the largest value with the prefix cuts the keys where that key does
+                cut[t] = Cut{(prefix[t] << shift) | ((1u << shift) - 1u), 1, 1};
                 act[t] = false;
             }
         }
+        SLA_ST(probe && pass_ < 4, 6 + 3 * pass_);
+        ++pass_;
     }
 }
 
 // Per-lane bit mask (bit m = slot m) of the k first slots in the order (key ascending, lower half of the exact key
-// ascending, index ascending), given the cut of the 32-bit keys.
-template <int KPL>
-__device__ __forceinline__ uint64_t take_first(const uint32_t (&key)[KPL], const Cut &cut, int Nkb, const double *__restrict__ q,
+// ascending, index ascending), given the cut of the 32-bit keys.  Works in place: the members of the group at the
+// threshold carry the lower halves of their exact keys in kv while they are ranked, and get their key back at the end.
+__device__ __forceinline__ uint64_t take_first(uint32_t *kv, int nslots, const Cut &cut, int Nkb, const double *__restrict__ q,
                                                const double *__restrict__ kh, uint32_t *hist)
 {
     const int lane = threadIdx.x & 63;
     uint64_t bits = 0;
     if (cut.r == cut.n) {                                   // the group at the threshold is taken as a whole (nearly always: n == 1)
-#pragma unroll
-        for (int m = 0; m < KPL; ++m) bits |= (uint64_t)(key[m] <= cut.T) << m;
+#pragma unroll 4
+        for (int m = 0; m < nslots; ++m) bits |= (uint64_t)(kv[m * 64 + lane] <= cut.T) << m;
         return bits;
     }
-    // r of the n slots with key == T: their exact keys decide.  lo[m]: lower half of the exact 64-bit key.
-    uint32_t lo[KPL];
-#pragma unroll
-    for (int m = 0; m < KPL; ++m) {
-        lo[m] = 0;
+    // r of the n slots with key == T: their exact keys decide.
+    const uint32_t T = cut.T;
+    uint64_t mem = 0;                                       // bit m: slot m belongs to the group
+    for (int m = 0; m < nslots; ++m) {
         const int j = m * 64 + lane;
-        if (key[m] == cut.T && j < Nkb) {
+        const uint32_t v = kv[j];
+        if (v == T && j < Nkb) {
             const double *kr = kh + (long)j * kD;
             double s = 0.0;
+#pragma unroll 4
             for (int d = 0; d < kD; ++d) s = fma(q[d], kr[d], s);
-            lo[m] = (uint32_t)desc_key(s);
-        }
+            kv[j] = (uint32_t)desc_key(s);                  // lower half of the exact 64-bit key
+            mem |= 1ull << m;
+        } else if (v < T) bits |= 1ull << m;
     }
-    const uint32_t T = cut.T;
-    auto cand = [&](int m) { return key[m] == T && m * 64 + lane < Nkb; };
+    auto cand = [&](int m) { return ((mem >> m) & 1) != 0; };
     const int k2[2] = {cut.r, 0};
     const bool w2[2] = {true, false};
     Cut c2[2];
-    radix_cuts<KPL>(lo, cand, k2, w2, hist, c2);
+    radix_cuts(MemberKeys{kv, nslots, mem}, k2, w2, hist, c2);
     const uint64_t lt = (1ull << lane) - 1;
     int tie = 0;
-#pragma unroll
-    for (int m = 0; m < KPL; ++m) {
-        const bool in = cand(m), eq = in && lo[m] == c2[0].T;
+    for (int m = 0; m < nslots; ++m) {
+        const bool in = cand(m);
+        const uint32_t lo = kv[m * 64 + lane];
+        const bool eq = in && lo == c2[0].T;
         const uint64_t b = __ballot(eq);
-        const bool sel = key[m] < T || (in && lo[m] < c2[0].T) || (eq && tie + (int)__popcll(b & lt) < c2[0].r);
+        const bool sel = (in && lo < c2[0].T) || (eq && tie + (int)__popcll(b & lt) < c2[0].r);
         tie += __popcll(b);
         bits |= (uint64_t)sel << m;
+        if (in) kv[m * 64 + lane] = T;
     }
     return bits;
 }
 
-// One wavefront per row; lane l holds the 32-bit keys of blocks j = 64 m + l.
+// One wavefront per row; lane l owns the 32-bit keys of blocks j = 64 m + l (KPL: slots per lane the LDS buffer holds).
 template <int KPL>
-__global__ __launch_bounds__(64, KPL <= 34 ? 4 : 2) void select_keys_kernel(const uint32_t *__restrict__ keys, int pitch, const double *__restrict__ qbar,
+__global__ __launch_bounds__(64) void select_keys_kernel(const uint32_t *__restrict__ keys, int pitch, const double *__restrict__ qbar,
                                                          const double *__restrict__ kbar, int Nqb, int Nkb, int k_c, int k_n,
                                                          uint64_t *__restrict__ mbits, int lab_pitch,
                                                          int8_t *__restrict__ lab_dense, int32_t *__restrict__ crit_idx)
 {
-    __shared__ __align__(16) uint32_t hist[512];
+    __shared__ __align__(16) uint32_t kv[256 * ((KPL + 3) / 4)];
+    __shared__ __align__(16) uint32_t hist[512 + 64];        // two histograms and a spare word per lane; later the critical list
     const long row = blockIdx.x;
     const int lane = threadIdx.x;
+    const int nslots = (Nkb + 63) >> 6;
     const uint32_t *kr = keys + row * pitch;
-    uint32_t key[KPL];
+#ifdef SLA_PROBE_TIME
+    const bool sprobe = row == (long)(gridDim.x / 2 + 5);
+    if (sprobe && lane < 32) sla_select_probe_times[lane] = 0;
+#endif
+    SLA_ST(sprobe, 0);
+    // Lane l of trip `it` owns the four keys from j = 4 (64 it + l) on, in the row and in kv alike.  Trips whose 256 keys
+    // all exist run unchecked; the last one or two read no further than the row's allocation (pitch: a multiple of
+    // eight keys; what lies past Nkb is padding) and leave keys past the end out of the minimum and maximum.
+    const int nit = (nslots + 3) >> 2, nfull = Nkb >> 8;
+    const uint4 *kr4 = (const uint4 *)kr;
+    uint4 *kv4 = (uint4 *)kv;
     uint32_t kmin = ~0u, kmax = 0u;
-#pragma unroll
-    for (int m = 0; m < KPL; ++m) {
-        const int j = m * 64 + lane;
-        key[m] = ~0u;
-        if (j < Nkb) {
-            key[m] = kr[j];
-            kmin = min(kmin, key[m]);
-            kmax = max(kmax, key[m]);
-        }
+#pragma unroll 4
+    for (int it = 0; it < nfull; ++it) {
+        const uint4 v = kr4[it * 64 + lane];
+        kv4[it * 64 + lane] = v;
+        kmin = min(min(kmin, v.x), min(min(v.y, v.z), v.w));
+        kmax = max(max(kmax, v.x), max(max(v.y, v.z), v.w));
+    }
+    for (int it = nfull; it < nit; ++it) {
+        const int q = it * 64 + lane, j = 4 * q;
+        const uint4 v = kr4[min(q, (pitch >> 2) - 1)];
+        kv4[q] = v;
+        if (j + 0 < Nkb) { kmin = min(kmin, v.x); kmax = max(kmax, v.x); }
+        if (j + 1 < Nkb) { kmin = min(kmin, v.y); kmax = max(kmax, v.y); }
+        if (j + 2 < Nkb) { kmin = min(kmin, v.z); kmax = max(kmax, v.z); }
+        if (j + 3 < Nkb) { kmin = min(kmin, v.w); kmax = max(kmax, v.w); }
     }
     kmin = wave_minmax_u32<false>(kmin);
     kmax = wave_minmax_u32<true>(kmax);
-    // keys relative to the row's range, so that the leading digits discriminate.  Slots past the end keep the largest
+    SLA_ST(sprobe, 1);
+    // keys relative to the row's range, so that the leading digits discriminate.  Entries past the end get the largest
     // value: they sort after every block of the row (equal keys go by index), so no rank up to Nkb reaches them.
     const uint32_t range = kmax - kmin;
     const int sh = range ? __clz((int)range) : 0;
-#pragma unroll
-    for (int m = 0; m < KPL; ++m) key[m] = (m * 64 + lane < Nkb) ? (key[m] - kmin) << sh : ~0u;
+#pragma unroll 4
+    for (int it = 0; it < nfull; ++it) {
+        uint4 v = kv4[it * 64 + lane];
+        v.x = (v.x - kmin) << sh; v.y = (v.y - kmin) << sh; v.z = (v.z - kmin) << sh; v.w = (v.w - kmin) << sh;
+        kv4[it * 64 + lane] = v;
+    }
+    for (int it = nfull; it < nit; ++it) {
+        const int q = it * 64 + lane, j = 4 * q;
+        uint4 v = kv4[q];
+        v.x = j + 0 < Nkb ? (v.x - kmin) << sh : ~0u; v.y = j + 1 < Nkb ? (v.y - kmin) << sh : ~0u;
+        v.z = j + 2 < Nkb ? (v.z - kmin) << sh : ~0u; v.w = j + 3 < Nkb ? (v.w - kmin) << sh : ~0u;
+        kv4[q] = v;
+    }
+    wave_lds_sync();                       // from here on the keys are read by other lanes than the ones that wrote them
+    SLA_ST(sprobe, 2);
 
     const int k_keep = Nkb - k_n;          // the first k_keep of the order are not negligible
     const int k2[2] = {k_c, k_keep};
     const bool want[2] = {k_c > 0 && k_c < Nkb, k_keep > 0 && k_keep < Nkb};
     Cut cut[2] = {Cut{0u, 0, 0}, Cut{0u, 0, 0}};
-    radix_cuts<KPL>(key, [](int) { return true; }, k2, want, hist, cut);
+#ifdef SLA_PROBE_TIME
+    radix_cuts(AllKeys{kv, nit}, k2, want, hist, cut, sprobe);
+#else
+    radix_cuts(AllKeys{kv, nit}, k2, want, hist, cut);
+#endif
+    SLA_ST(sprobe, 16);
 
-    const uint64_t lt = (1ull << lane) - 1;
-    uint32_t mb_lo = 0, mb_hi = 0;         // lane m keeps the marginal mask of chunk m: one 8-byte store per lane at the end
-    int ncrit = 0;
-    auto emit = [&](int m, bool selc, bool seln) {
-        const int j = m * 64 + lane;
-        const int8_t lab = selc ? 2 : (seln ? 1 : 0);
-        const uint64_t mb = __ballot(lab == 1);
-        if (lane == m) { mb_lo = (uint32_t)mb; mb_hi = (uint32_t)(mb >> 32); }
-        if (lab_dense && j < Nkb) lab_dense[row * Nkb + j] = lab;
-        if (crit_idx) {
-            const uint64_t b = __ballot(selc);
-            if (b) {                                            // most chunks hold no critical block
-                const int pos = ncrit + (int)__popcll(b & lt);
-                if (selc && pos < k_c) crit_idx[row * k_c + pos] = j;
-                ncrit += __popcll(b);
-            }
-        }
-    };
-    const bool whole0 = !want[0] || cut[0].r == cut[0].n, whole1 = !want[1] || cut[1].r == cut[1].n;
-    if (whole0 && whole1) {                // the groups at both thresholds are taken whole (nearly always: single keys)
-        const uint32_t Tc = cut[0].T, Tn = cut[1].T;
-#pragma unroll
-        for (int m = 0; m < KPL; ++m) {
-            const bool valid = m * 64 + lane < Nkb;
-            const bool selc = want[0] ? key[m] <= Tc : (k_c > 0 && valid);
-            const bool seln = want[1] ? key[m] <= Tn : (k_keep > 0 && valid);
-            emit(m, selc, seln);
-        }
-    } else {
+    // whole: the groups at both thresholds are taken whole (nearly always: single keys) and two compares label a slot;
+    // otherwise per-lane bit masks say which slots are among the first k_c / k_keep of the exact order
+    const bool whole = (!want[0] || cut[0].r == cut[0].n) && (!want[1] || cut[1].r == cut[1].n);
+    uint64_t cm = 0, nm = 0;
+    if (!whole) {
         const long bh = row / Nqb;
         const double *q = qbar + row * kD, *kh = kbar + bh * (long)Nkb * kD;
-        uint64_t valid = 0;
-#pragma unroll
-        for (int m = 0; m < KPL; ++m) valid |= (uint64_t)(m * 64 + lane < Nkb) << m;
-        const uint64_t cm = want[0] ? take_first<KPL>(key, cut[0], Nkb, q, kh, hist) : (k_c > 0 ? valid : 0ull);
-        const uint64_t nm = want[1] ? take_first<KPL>(key, cut[1], Nkb, q, kh, hist) : (k_keep > 0 ? valid : 0ull);
-#pragma unroll
-        for (int m = 0; m < KPL; ++m) emit(m, (cm >> m) & 1, (nm >> m) & 1);
+        if (want[0]) cm = take_first(kv, nslots, cut[0], Nkb, q, kh, hist);
+        if (want[1]) nm = take_first(kv, nslots, cut[1], Nkb, q, kh, hist);
+    }
+    const uint32_t Tc = cut[0].T, Tn = cut[1].T;
+    uint32_t mb_lo = 0, mb_hi = 0;         // lane m keeps the marginal mask of chunk m: one 8-byte store per lane at the end
+    int ncrit = 0;
+    // The critical list is collected in LDS (the histogram is done with) and leaves as whole rows at the end (stores
+    // entry by entry each waited for the one before); a list longer than the buffer goes to memory entry by entry.
+    const bool list_in_lds = k_c <= 512;
+    wave_lds_sync();
+    // bc, bn: the lanes of chunk m among the first k_c / k_keep of the order (as wave masks)
+    auto emit = [&](int m, uint64_t bc, uint64_t bn) {
+        const uint64_t mb = bn & ~bc;                           // marginal: kept, not critical
+        if (lane == m) { mb_lo = (uint32_t)mb; mb_hi = (uint32_t)(mb >> 32); }
+        const int j = m * 64 + lane;
+        const bool selc = (bc >> lane) & 1;
+        if (lab_dense && j < Nkb) lab_dense[row * Nkb + j] = selc ? 2 : (int8_t)((bn >> lane) & 1);
+        if (crit_idx && bc) {                                   // (a chunk without critical block: nothing to list)
+            const int pos = ncrit + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bc >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bc, 0u));
+            if (list_in_lds) hist[selc && pos < k_c ? pos : 512 + lane] = (uint32_t)j;     // other lanes write to a spare row
+            else if (selc && pos < k_c) crit_idx[row * k_c + pos] = j;
+            ncrit += __popcll(bc);
+        }
+    };
+    if (whole && want[0] && want[1] && !lab_dense && crit_idx && list_in_lds) {
+        // the forward's case, without a branch in the loop: every lane writes its block index, the ones that are not
+        // critical to the spare row
+#pragma unroll 4
+        for (int m = 0; m < nslots; ++m) {
+            const uint32_t v = kv[m * 64 + lane];
+            const bool selc = v <= Tc;
+            const uint64_t bc = __ballot(selc), mb = __ballot(v <= Tn) & ~bc;
+            if (lane == m) { mb_lo = (uint32_t)mb; mb_hi = (uint32_t)(mb >> 32); }
+            const int pos = ncrit + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bc >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bc, 0u));
+            hist[selc && pos < k_c ? pos : 512 + lane] = (uint32_t)(m * 64 + lane);
+            ncrit += __popcll(bc);
+        }
+    } else if (whole) {
+        const uint64_t all_c = k_c > 0 ? ~0ull : 0ull, all_n = k_keep > 0 ? ~0ull : 0ull;
+#pragma unroll 4
+        for (int m = 0; m < nslots; ++m) {
+            const uint32_t v = kv[m * 64 + lane];
+            const uint64_t valid = __ballot(m * 64 + lane < Nkb);
+            emit(m, want[0] ? __ballot(v <= Tc) : (all_c & valid), want[1] ? __ballot(v <= Tn) : (all_n & valid));
+        }
+    } else {
+        uint64_t vm = 0;
+        for (int m = 0; m < nslots; ++m) vm |= (uint64_t)(m * 64 + lane < Nkb) << m;
+        if (!want[0]) cm = k_c > 0 ? vm : 0ull;
+        if (!want[1]) nm = k_keep > 0 ? vm : 0ull;
+        for (int m = 0; m < nslots; ++m) emit(m, __ballot((cm >> m) & 1), __ballot((nm >> m) & 1));
+    }
+    SLA_ST(sprobe, 17);
+    if (crit_idx && list_in_lds) {
+        wave_lds_sync();
+        const int n = min(ncrit, k_c);
+        for (int t = lane; t < n; t += 64) crit_idx[row * k_c + t] = (int32_t)hist[t];
     }
     if (lane < (lab_pitch >> 6)) mbits[row * (lab_pitch >> 6) + lane] = ((uint64_t)mb_hi << 32) | mb_lo;
+    SLA_ST(sprobe, 18);
 }
 
 template <int KPL>
@@ -1088,7 +1302,7 @@ hipError_t launch_select_keys(const uint32_t *keys, int pitch, const double *qba
                               int k_c, int k_n, uint64_t *mbits, int lab_pitch, int8_t *lab_dense, int32_t *crit_idx, hipStream_t st)
 {
 #define SLA_SK(K) if (lab_pitch <= 64 * K) return launch_select_keys_t<K>(keys, pitch, qbar, kbar, rows, Nqb, Nkb, k_c, k_n, mbits, lab_pitch, lab_dense, crit_idx, st)
-    SLA_SK(4); SLA_SK(8); SLA_SK(12); SLA_SK(16); SLA_SK(24); SLA_SK(34); SLA_SK(48); SLA_SK(64);
+    SLA_SK(8); SLA_SK(16); SLA_SK(34); SLA_SK(64);
 #undef SLA_SK
     return hipErrorInvalidValue;
 }

@@ -76,6 +76,7 @@ def probe_attend(idx: int, per_tile: bool) -> None:
           "-> first S %d | -> block 0 %d" % (pr[1] - pr[0], pr[2] - pr[1], pr[3] - pr[2], pr[4] - pr[3], pr[5] - pr[4], t[0, 0] - pr[5]))
     print("epilogue, cycles: last block -> loop exit %d | last PV + 1/l %d | phi(Q) %d | linear-branch MFMAs %d | barrier %d | store %d"
           % (ep[0] - t[nk - 1, 4] if nk == k_c else -1, ep[1] - ep[0], ep[2] - ep[1], ep[3] - ep[2], ep[4] - ep[3], ep[5] - ep[4]))
+    probe_select_report(L, (cfg.N + cfg.bk - 1) // cfg.bk)
     nwg = min(32768, cfg.B * cfg.H * ((cfg.N + cfg.bq - 1) // cfg.bq))
     wb = (ctypes.c_ulonglong * (2 * nwg))()
     if L.sla_probe_read_wg(wb, nwg) != 0:
@@ -85,6 +86,26 @@ def probe_attend(idx: int, per_tile: bool) -> None:
     span = (w[:, 1].max() - w[:, 0].min()) / 100.0
     print("workgroups (first %d): life median %.1f us, 10%% %.1f, 90%% %.1f; first start to last end %.1f us"
           % (nwg, np.median(life), np.percentile(life, 10), np.percentile(life, 90), span))
+
+
+def probe_select_report(L: ctypes.CDLL, nkb: int) -> None:
+    """Phases of select_keys_kernel (rows of more than 256 key blocks) for one row in the middle of the launch."""
+    if nkb <= 256:
+        return
+    buf = (ctypes.c_ulonglong * 32)()
+    if L.sla_probe_read_select(buf) != 0:
+        raise RuntimeError("sla_probe_read_select failed")
+    t = [int(x) for x in buf]
+    out = ["load keys + min/max %d" % (t[1] - t[0]), "shift %d" % (t[2] - t[1])]
+    last = t[2]
+    for p in range(4):
+        a, b, c = t[4 + 3 * p], t[5 + 3 * p], t[6 + 3 * p]
+        if a == 0:
+            break
+        out.append("pass %d: clear %d, count %d, scan + cut %d" % (p, a - last, b - a, c - b))
+        last = c
+    out += ["labels, lists, masks %d" % (t[17] - t[16]), "mask store %d" % (t[18] - t[17]), "whole row %d" % (t[18] - t[0])]
+    print("select_keys_kernel, one row of %d keys, cycles: " % nkb + " | ".join(out))
 
 
 def probe_gemm(M: int) -> None:

@@ -42,7 +42,7 @@ def _variants(cfg, d):
 
 @pytest.mark.parametrize("nkb,bq,kc,kn", [(300, 64, 15, 200), (300, 128, 1, 299), (300, 64, 299, 1), (300, 64, 0, 150), (300, 64, 7, 0),
                                           (700, 128, 35, 560), (1000, 64, 50, 500), (1100, 128, 3, 1000), (1700, 128, 40, 1100),
-                                          (2147, 128, 64, 1400), (2500, 128, 100, 2000), (4000, 128, 120, 2500)])
+                                          (2147, 128, 64, 1400), (2500, 128, 100, 2000), (4000, 128, 120, 2500), (3000, 64, 90, 2400)])
 def test_key_classifier_equals_the_exact_order(oracle, nkb, bq, kc, kn):
     from paper_2605_11354_amd import binding as B
     cfg = C0.with_(H=2 if nkb <= 1100 else 1, N=nkb * 64 - 17, bq=bq, n_clusters=256)

@@ -12,99 +12,106 @@
 namespace sla {
 
 // ------------------------------------------------------------------------------------- pool
-// 8 threads per token block, each owning 8 consecutive channels (16 B of bf16 / 8 B of e4m3
-// per token), serial over the tokens of the block.  Bound: HBM (one streaming read of X).
-template <bool FP8>
+// 64 / CPT threads per token block, each owning CPT consecutive channels (CPT x 2 bytes of bf16 / CPT bytes of e4m3
+// per token), serial over the tokens of the block.  Bound: HBM (one streaming read of X).  A thread keeps 32 rows in
+// flight; CPT is chosen at the launch so that there are enough waves to hide the rest of the latency (eight channels
+// per thread are one wave per 512 token rows: fewer than one wave per SIMD on the benchmark shapes).
+template <int BYTES> struct PoolWord;
+template <> struct PoolWord<16> { typedef uint4 type; };
+template <> struct PoolWord<8> { typedef uint2 type; };
+template <> struct PoolWord<4> { typedef uint32_t type; };
+template <> struct PoolWord<2> { typedef uint16_t type; };
+
+__device__ __forceinline__ uint32_t pool_dword(const uint4 &w, int i) { return i == 0 ? w.x : i == 1 ? w.y : i == 2 ? w.z : w.w; }
+__device__ __forceinline__ uint32_t pool_dword(const uint2 &w, int i) { return i == 0 ? w.x : w.y; }
+__device__ __forceinline__ uint32_t pool_dword(uint32_t w, int) { return w; }
+__device__ __forceinline__ uint32_t pool_dword(uint16_t w, int) { return w; }
+
+template <bool FP8, int CPT>
 __global__ __launch_bounds__(256) void pool_kernel(const void *__restrict__ X, const float *__restrict__ scales,
                                                    RowMap rm, int N, int blk, int nblk, long units, double *__restrict__ mean)
 {
+    constexpr int TPB = kD / CPT, ES = FP8 ? 1 : 2;       // threads per token block, bytes per element
+    typedef typename PoolWord<CPT * ES>::type Word;
     asm volatile("" ::"s"(X), "s"(scales), "s"(rm.bs), "s"(rm.hs), "s"(rm.ts), "s"(rm.H), "s"(N), "s"(blk), "s"(nblk), "s"(units), "s"(mean));      // all kernel arguments in one batch of scalar loads, here
     const long u = (long)blockIdx.x * 256 + threadIdx.x;
     if (u >= units) return;
-    const int c = (int)(u & 7);
-    const long blkid = u >> 3;
+    const int c = (int)(u % TPB);
+    const long blkid = u / TPB;
     const long bh = blkid / nblk;
     const int j = (int)(blkid - bh * nblk);
     const int t0 = j * blk;
     const int cnt = min(N - t0, blk);
-    double acc[8];
+    double acc[CPT];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) acc[k] = 0.0;
-    if (FP8) {
-        const uint8_t *x = (const uint8_t *)X + rm.head(bh) + (size_t)t0 * rm.ts + c * 8;
-        const double s = (double)scales[blkid];
-        auto add_row = [&](uint2 w) {
-            const f32x2 a0 = __builtin_amdgcn_cvt_pk_f32_fp8(w.x, false), a1 = __builtin_amdgcn_cvt_pk_f32_fp8(w.x, true);
-            const f32x2 a2 = __builtin_amdgcn_cvt_pk_f32_fp8(w.y, false), a3 = __builtin_amdgcn_cvt_pk_f32_fp8(w.y, true);
-            acc[0] += (double)a0[0] * s; acc[1] += (double)a0[1] * s;
-            acc[2] += (double)a1[0] * s; acc[3] += (double)a1[1] * s;
-            acc[4] += (double)a2[0] * s; acc[5] += (double)a2[1] * s;
-            acc[6] += (double)a3[0] * s; acc[7] += (double)a3[1] * s;
-        };
-        // sixteen rows are requested before the first is consumed, and the next sixteen before that (a launch has fewer
-        // than one wave per SIMD on the benchmark shapes: the loads in flight per thread are what hides the latency)
-        uint2 wa[16], wb[16];
-        auto fetch = [&](uint2 (&w)[16], int t) {
+    for (int k = 0; k < CPT; ++k) acc[k] = 0.0;
+    const double s = FP8 ? (double)scales[blkid] : 1.0;
+    auto add_row = [&](Word w) {
+        if (FP8) {
 #pragma unroll
-            for (int k = 0; k < 16; ++k) w[k] = *(const uint2 *)(x + (size_t)(t + k) * rm.ts);
-        };
-        auto consume = [&](const uint2 (&w)[16]) {
+            for (int k = 0; k < CPT; k += 2) {
+                const f32x2 a = (k & 2) ? __builtin_amdgcn_cvt_pk_f32_fp8(pool_dword(w, k >> 2), true)
+                                        : __builtin_amdgcn_cvt_pk_f32_fp8(pool_dword(w, k >> 2), false);
+                acc[k] += (double)a[0] * s;
+                acc[k + 1] += (double)a[1] * s;
+            }
+        } else {
 #pragma unroll
-            for (int k = 0; k < 16; ++k) add_row(w[k]);
-        };
-        int t = 0;
-        if (cnt >= 16) fetch(wa, 0);
-        for (; t + 32 <= cnt; t += 32) {
-            fetch(wb, t + 16);
-            consume(wa);
-            if (t + 48 <= cnt) fetch(wa, t + 32);
-            consume(wb);
+            for (int k = 0; k < CPT; k += 2) {
+                acc[k] += (double)bf16_lo(pool_dword(w, k >> 1));
+                acc[k + 1] += (double)bf16_hi(pool_dword(w, k >> 1));
+            }
         }
-        if (t + 16 <= cnt) { consume(wa); t += 16; }
-        for (; t < cnt; ++t) add_row(*(const uint2 *)(x + (size_t)t * rm.ts));
-    } else {
-        const uint16_t *x = (const uint16_t *)X + rm.head(bh) + (size_t)t0 * rm.ts + c * 8;
-        auto add_row = [&](uint4 w) {
-            acc[0] += (double)bf16_lo(w.x); acc[1] += (double)bf16_hi(w.x);
-            acc[2] += (double)bf16_lo(w.y); acc[3] += (double)bf16_hi(w.y);
-            acc[4] += (double)bf16_lo(w.z); acc[5] += (double)bf16_hi(w.z);
-            acc[6] += (double)bf16_lo(w.w); acc[7] += (double)bf16_hi(w.w);
-        };
-        uint4 wa[16], wb[16];                   // as above: two sets of sixteen rows in flight
-        auto fetch = [&](uint4 (&w)[16], int t) {
+    };
+    const uint8_t *x = (const uint8_t *)X + (rm.head(bh) + (size_t)t0 * rm.ts + c * CPT) * ES;
+    const size_t rowb = (size_t)rm.ts * ES;
+    // sixteen rows are requested before the first is consumed, and the next sixteen before that
+    Word wa[16], wb[16];
+    auto fetch = [&](Word (&w)[16], int t) {
 #pragma unroll
-            for (int k = 0; k < 16; ++k) w[k] = *(const uint4 *)(x + (size_t)(t + k) * rm.ts);
-        };
-        auto consume = [&](const uint4 (&w)[16]) {
+        for (int k = 0; k < 16; ++k) w[k] = *(const Word *)(x + (size_t)(t + k) * rowb);
+    };
+    auto consume = [&](const Word (&w)[16]) {
 #pragma unroll
-            for (int k = 0; k < 16; ++k) add_row(w[k]);
-        };
-        int t = 0;
-        if (cnt >= 16) fetch(wa, 0);
-        for (; t + 32 <= cnt; t += 32) {
-            fetch(wb, t + 16);
-            consume(wa);
-            if (t + 48 <= cnt) fetch(wa, t + 32);
-            consume(wb);
-        }
-        if (t + 16 <= cnt) { consume(wa); t += 16; }
-        for (; t < cnt; ++t) add_row(*(const uint4 *)(x + (size_t)t * rm.ts));
+        for (int k = 0; k < 16; ++k) add_row(w[k]);
+    };
+    int t = 0;
+    if (cnt >= 16) fetch(wa, 0);
+    for (; t + 32 <= cnt; t += 32) {
+        fetch(wb, t + 16);
+        consume(wa);
+        if (t + 48 <= cnt) fetch(wa, t + 32);
+        consume(wb);
     }
+    if (t + 16 <= cnt) { consume(wa); t += 16; }
+    for (; t < cnt; ++t) add_row(*(const Word *)(x + (size_t)t * rowb));
     const double inv = 1.0 / (double)cnt;
-    double *o = mean + blkid * kD + c * 8;
+    double *o = mean + blkid * kD + c * CPT;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) o[k] = acc[k] * inv;
+    for (int k = 0; k < CPT; ++k) o[k] = acc[k] * inv;
+}
+
+template <bool FP8, int CPT>
+static hipError_t launch_pool_t(const void *X, const float *scales, RowMap rm, int BH, int N, int blk, double *mean, hipStream_t st)
+{
+    const int nblk = (N + blk - 1) / blk;
+    const long units = (long)BH * nblk * (kD / CPT);
+    pool_kernel<FP8, CPT><<<(unsigned)((units + 255) / 256), 256, 0, st>>>(X, scales, rm, N, blk, nblk, units, mean);
+    return hipGetLastError();
 }
 
 hipError_t launch_pool(const void *X, const float *scales, bool fp8, RowMap rm, int BH, int N, int blk,
                        double *mean, hipStream_t st)
 {
-    const int nblk = (N + blk - 1) / blk;
-    const long units = (long)BH * nblk * 8;
-    const unsigned grid = (unsigned)((units + 255) / 256);
-    if (fp8) pool_kernel<true><<<grid, 256, 0, st>>>(X, scales, rm, N, blk, nblk, units, mean);
-    else     pool_kernel<false><<<grid, 256, 0, st>>>(X, scales, rm, N, blk, nblk, units, mean);
-    return hipGetLastError();
+    // the widest loads that still give about four waves per SIMD (4096 waves of 64 threads)
+    const long blocks = (long)BH * ((N + blk - 1) / blk);
+    if (fp8) {
+        if (blocks * 8 >= 4096L * 64) return launch_pool_t<true, 8>(X, scales, rm, BH, N, blk, mean, st);
+        return launch_pool_t<true, 4>(X, scales, rm, BH, N, blk, mean, st);
+    }
+    if (blocks * 8 >= 4096L * 64) return launch_pool_t<false, 8>(X, scales, rm, BH, N, blk, mean, st);
+    if (blocks * 16 >= 4096L * 64) return launch_pool_t<false, 4>(X, scales, rm, BH, N, blk, mean, st);
+    return launch_pool_t<false, 2>(X, scales, rm, BH, N, blk, mean, st);
 }
 
 // ----------------------------------------------------------------------------------- scores

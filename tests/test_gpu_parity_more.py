@@ -309,3 +309,35 @@ def test_frame_then_global_attention_on_the_same_activations(oracle):
     assert np.array_equal(labf.cpu().numpy(), r["labels"])
     got = G.bf16_tensor_to_f64(Of).reshape(S, Nf, H, 64).transpose(0, 2, 1, 3)
     G.assert_output(got, r["O"], "bf16", "frame attention on the same activations")
+
+
+@pytest.mark.parametrize("dtype,heads", [("bf16", 32), ("bf16", 64), ("fp8", 64)])
+def test_block_means_of_launches_with_many_blocks(oracle, dtype, heads):
+    """pool_kernel gives a thread eight, four or two channels by the number of token blocks in the launch (16384 and 32768
+    are the steps); the other tests stay below the first step.  Block means (Alg. 1 step 2, fp64 sums in token order) and
+    labels against the oracle on cheap random inputs: random sign, exponent within fifteen binades, random mantissa."""
+    N = 512 * 64 - 17
+    rng = np.random.default_rng(11)
+    cfg = synth.CONFIGS[0].with_(B=1, H=heads, N=N, bq=64, bk=64, dtype=dtype)
+    shape = (1, heads, N, 64)
+    if dtype == "bf16":
+        def draw():
+            r = rng.integers(0, 1 << 16, size=shape, dtype=np.uint16)
+            return (r & np.uint16(0x807F)) | ((np.uint16(118) + ((r >> 7) & np.uint16(15))) << np.uint16(7))
+        d = {"Q": draw(), "K": draw(), "sQ": None, "sK": None, "sV": None}
+    else:
+        def draw():
+            r = rng.integers(0, 1 << 8, size=shape, dtype=np.uint8)
+            return np.where((r & 0x7F) == 0x7F, r & 0xFE, r).astype(np.uint8)          # no NaN codes
+        nb = -(-N // 64)
+        d = {"Q": draw(), "K": draw(), "sQ": rng.uniform(0.01, 0.1, (1, heads, nb)).astype(np.float32),
+             "sK": rng.uniform(0.01, 0.1, (1, heads, nb)).astype(np.float32)}
+        d["sV"] = d["sK"]
+    d["V"] = d["K"]
+    d["W"] = synth.to_bf16_bits(np.eye(64, dtype=np.float32))
+    case = G.Case(cfg, d, k_crit=20, k_neg=300)
+    got = case.classify(want=("qbar", "kbar"))
+    ref = case.oracle_classify(oracle, want_means=True)
+    assert np.array_equal(got["qbar"], ref["qbar"]), "query block means differ"
+    assert np.array_equal(got["kbar"], ref["kbar"]), "key block means differ"
+    assert np.array_equal(got["labels"], ref["labels"]), "labels differ"

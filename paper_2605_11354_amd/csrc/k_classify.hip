@@ -1104,9 +1104,10 @@ __device__ __forceinline__ void radix_cuts(const Keys keys, const int (&k)[2], c
     }
 }
 
-// Per-lane bit mask (bit m = slot m) of the k first slots in the order (key ascending, lower half of the exact key
-// ascending, index ascending), given the cut of the 32-bit keys.  Works in place: the members of the group at the
-// threshold carry the lower halves of their exact keys in kv while they are ranked, and get their key back at the end.
+// Per-lane bit mask (bit m = slot m) of the k first slots in the order (exact 64-bit key ascending, index ascending),
+// given the cut of the row's 32-bit ranks (which are a non-decreasing function of the keys).  Works in place: the members
+// of the group at the threshold carry first the upper, then, if those tie too, the lower halves of their exact keys in
+// kv while they are ranked, and get their rank value back at the end.
 __device__ __forceinline__ uint64_t take_first(uint32_t *kv, int nslots, const Cut &cut, int Nkb, const double *__restrict__ q,
                                                const double *__restrict__ kh, uint32_t *hist)
 {
@@ -1117,38 +1118,57 @@ __device__ __forceinline__ uint64_t take_first(uint32_t *kv, int nslots, const C
         for (int m = 0; m < nslots; ++m) bits |= (uint64_t)(kv[m * 64 + lane] <= cut.T) << m;
         return bits;
     }
-    // r of the n slots with key == T: their exact keys decide.
+    // r of the n slots with rank value T: their exact keys decide.
     const uint32_t T = cut.T;
     uint64_t mem = 0;                                       // bit m: slot m belongs to the group
     for (int m = 0; m < nslots; ++m) {
-        const int j = m * 64 + lane;
-        const uint32_t v = kv[j];
-        if (v == T && j < Nkb) {
+        const uint32_t v = kv[m * 64 + lane];
+        if (v == T && m * 64 + lane < Nkb) mem |= 1ull << m;
+        else if (v < T) bits |= 1ull << m;
+    }
+    // the half `lower` of the exact keys of the slots in `who` -> kv
+    auto exact_halves = [&](uint64_t who, bool lower) {
+        for (int m = 0; m < nslots; ++m) {
+            if (!((who >> m) & 1)) continue;
+            const int j = m * 64 + lane;
             const double *kr = kh + (long)j * kD;
             double s = 0.0;
 #pragma unroll 4
             for (int d = 0; d < kD; ++d) s = fma(q[d], kr[d], s);
-            kv[j] = (uint32_t)desc_key(s);                  // lower half of the exact 64-bit key
-            mem |= 1ull << m;
-        } else if (v < T) bits |= 1ull << m;
-    }
-    auto cand = [&](int m) { return ((mem >> m) & 1) != 0; };
-    const int k2[2] = {cut.r, 0};
-    const bool w2[2] = {true, false};
-    Cut c2[2];
-    radix_cuts(MemberKeys{kv, nslots, mem}, k2, w2, hist, c2);
+            const uint64_t key = desc_key(s);
+            kv[j] = lower ? (uint32_t)key : (uint32_t)(key >> 32);
+        }
+    };
     const uint64_t lt = (1ull << lane) - 1;
-    int tie = 0;
-    for (int m = 0; m < nslots; ++m) {
-        const bool in = cand(m);
-        const uint32_t lo = kv[m * 64 + lane];
-        const bool eq = in && lo == c2[0].T;
-        const uint64_t b = __ballot(eq);
-        const bool sel = (in && lo < c2[0].T) || (eq && tie + (int)__popcll(b & lt) < c2[0].r);
-        tie += __popcll(b);
-        bits |= (uint64_t)sel << m;
-        if (in) kv[m * 64 + lane] = T;
+    const bool w2[2] = {true, false};
+    uint64_t who = mem;                                     // the slots still tied
+    int need = cut.r;                                       // how many of them to take
+    for (int level = 0; level < 2 && need > 0; ++level) {
+        exact_halves(who, level == 1);
+        const int k2[2] = {need, 0};
+        Cut c2[2];
+        radix_cuts(MemberKeys{kv, nslots, who}, k2, w2, hist, c2);
+        const uint32_t T2 = c2[0].T;
+        const bool whole = c2[0].r == c2[0].n;
+        uint64_t tied = 0;
+        int tie = 0;
+        for (int m = 0; m < nslots; ++m) {
+            const bool in = (who >> m) & 1;
+            const uint32_t x = kv[m * 64 + lane];
+            const bool eq = in && x == T2 && !whole;
+            bool sel = in && (whole ? x <= T2 : x < T2);
+            if (level == 1) {                               // equal keys: by index
+                const uint64_t b = __ballot(eq);
+                sel = sel || (eq && tie + (int)__popcll(b & lt) < c2[0].r);
+                tie += __popcll(b);
+            } else if (eq) tied |= 1ull << m;
+            bits |= (uint64_t)sel << m;
+        }
+        who = tied;
+        need = whole ? 0 : c2[0].r;
     }
+    for (int m = 0; m < nslots; ++m)
+        if ((mem >> m) & 1) kv[m * 64 + lane] = T;
     return bits;
 }
 
@@ -1196,21 +1216,31 @@ __global__ __launch_bounds__(64) void select_keys_kernel(const uint32_t *__restr
     kmin = wave_minmax_u32<false>(kmin);
     kmax = wave_minmax_u32<true>(kmax);
     SLA_ST(sprobe, 1);
-    // keys relative to the row's range, so that the leading digits discriminate.  Entries past the end get the largest
-    // value: they sort after every block of the row (equal keys go by index), so no rank up to Nkb reaches them.
-    const uint32_t range = kmax - kmin;
-    const int sh = range ? __clz((int)range) : 0;
-#pragma unroll 4
+    // The selection ranks 32-bit values w = floor((s_max - s) * 2^32 / (s_max - s_min)) of the row, s being the logit
+    // with the lower half of its fp64 pattern cleared (what a 32-bit key holds): a non-decreasing function of the key,
+    // so cutting the row at a rank of w is cutting it at that rank of the keys wherever w separates them, and where it
+    // does not (equal w at the threshold) the exact keys are consulted as for equal keys.  The keys themselves are a
+    // poor radix: sign and exponent lead, and the first digit of a row puts three quarters of its keys into one bin
+    // (atomics of forty lanes on one counter), the second digit most of those again.  w spreads a row like its logits.
+    // Entries past the end get the largest value: they sort after every block of the row (equal values go by index).
+    auto key_value = [](uint32_t key) {                       // the fp64 whose upper half the key encodes, lower half zero
+        const uint32_t hi = key ^ ((uint32_t)~((int32_t)key >> 31) >> 1);
+        return __longlong_as_double((long long)((uint64_t)hi << 32));
+    };
+    const double s_max = key_value(kmin), s_min = key_value(kmax);
+    const double span = s_max - s_min, scale = span > 0.0 ? 4294967040.0 / span : 0.0;      // 2^32 - 2^8: below the padding value
+    auto spread = [&](uint32_t key) { return (uint32_t)((s_max - key_value(key)) * scale); };
+#pragma unroll 2
     for (int it = 0; it < nfull; ++it) {
         uint4 v = kv4[it * 64 + lane];
-        v.x = (v.x - kmin) << sh; v.y = (v.y - kmin) << sh; v.z = (v.z - kmin) << sh; v.w = (v.w - kmin) << sh;
+        v.x = spread(v.x); v.y = spread(v.y); v.z = spread(v.z); v.w = spread(v.w);
         kv4[it * 64 + lane] = v;
     }
     for (int it = nfull; it < nit; ++it) {
         const int q = it * 64 + lane, j = 4 * q;
         uint4 v = kv4[q];
-        v.x = j + 0 < Nkb ? (v.x - kmin) << sh : ~0u; v.y = j + 1 < Nkb ? (v.y - kmin) << sh : ~0u;
-        v.z = j + 2 < Nkb ? (v.z - kmin) << sh : ~0u; v.w = j + 3 < Nkb ? (v.w - kmin) << sh : ~0u;
+        v.x = j + 0 < Nkb ? spread(v.x) : ~0u; v.y = j + 1 < Nkb ? spread(v.y) : ~0u;
+        v.z = j + 2 < Nkb ? spread(v.z) : ~0u; v.w = j + 3 < Nkb ? spread(v.w) : ~0u;
         kv4[q] = v;
     }
     wave_lds_sync();                       // from here on the keys are read by other lanes than the ones that wrote them
@@ -1260,20 +1290,24 @@ __global__ __launch_bounds__(64) void select_keys_kernel(const uint32_t *__restr
     };
     if (whole && want[0] && want[1] && !lab_dense && crit_idx && list_in_lds) {
         // the forward's case, without a branch in the loop: every lane writes its block index, the ones that are not
-        // critical to the spare row
-#pragma unroll 4
-        for (int m = 0; m < nslots; ++m) {
-            const uint32_t v = kv[m * 64 + lane];
+        // critical to the spare row.  Four slots per trip, written out (the compiler does not unroll a loop of unknown
+        // length around wave-wide votes), so that the four LDS reads are in flight together.
+        auto step = [&](int m, uint32_t v) {
             const bool selc = v <= Tc;
             const uint64_t bc = __ballot(selc), mb = __ballot(v <= Tn) & ~bc;
             if (lane == m) { mb_lo = (uint32_t)mb; mb_hi = (uint32_t)(mb >> 32); }
             const int pos = ncrit + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bc >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bc, 0u));
             hist[selc && pos < k_c ? pos : 512 + lane] = (uint32_t)(m * 64 + lane);
             ncrit += __popcll(bc);
+        };
+        int m = 0;
+        for (; m + 4 <= nslots; m += 4) {
+            const uint32_t v0 = kv[m * 64 + lane], v1 = kv[m * 64 + 64 + lane], v2 = kv[m * 64 + 128 + lane], v3 = kv[m * 64 + 192 + lane];
+            step(m, v0); step(m + 1, v1); step(m + 2, v2); step(m + 3, v3);
         }
+        for (; m < nslots; ++m) step(m, kv[m * 64 + lane]);
     } else if (whole) {
         const uint64_t all_c = k_c > 0 ? ~0ull : 0ull, all_n = k_keep > 0 ? ~0ull : 0ull;
-#pragma unroll 4
         for (int m = 0; m < nslots; ++m) {
             const uint32_t v = kv[m * 64 + lane];
             const uint64_t valid = __ballot(m * 64 + lane < Nkb);

@@ -377,6 +377,143 @@ __device__ __forceinline__ double key_to_logit(uint64_t key)
     return __longlong_as_double((long long)u);
 }
 
+#ifdef SLA_PROBE_TIME   /* timing probe only: cycle counter of one row's wave at the phase boundaries of the selection */
+__device__ unsigned long long sla_select_probe_times[32];
+__device__ int sla_select_probe_on;                      // set by the probed wave for the helpers it calls
+#define SLA_ST(on, pt) do { if (on) { const unsigned long long t_ = __builtin_readcyclecounter(); if ((threadIdx.x & 63) == 0) sla_select_probe_times[pt] = t_; } } while (0)
+extern "C" int sla_probe_read_select(unsigned long long *dst) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(sla_select_probe_times), sizeof(unsigned long long) * 32); }
+#else
+#define SLA_ST(on, pt)
+#endif
+
+// (T, r, n): the k smallest (value, index) pairs among the candidates are the candidates with value < T plus the r
+// lowest-index ones of the n candidates with value == T, or, if r == n == 1, the candidates with value <= T (T is then
+// an upper bound of the one key at the threshold, below the next key, rather than that key itself).
+struct Cut { uint32_t T; int r, n; };
+
+// The row's keys live in LDS (kv[j] = key of block j) and every pass over them is a rolled loop.  (Held in registers
+// with the loops unrolled the kernel was 18 000 instructions of straight-line code and, with 34 keys per lane, spilled.)
+// The kernel is bound by instruction issue -- about three waves per SIMD, each instruction of a wave taking the SIMD
+// some six cycles -- so the passes are written for few instructions per key: sixteen bytes per LDS read where the
+// order of the keys does not matter, no predicated atomics (a key that does not count adds to a spare word of its
+// lane instead, which costs one select where masking the lane out costs four scalar instructions).
+
+// The keys a radix descent looks at.  AllKeys: every entry of kv[0, 256 nit), four consecutive ones per lane and trip.
+struct AllKeys {
+    const uint32_t *kv;
+    int nit;
+    template <class F>
+    __device__ __forceinline__ void for_each(F f) const
+    {
+        const uint4 *q = (const uint4 *)kv + (threadIdx.x & 63);
+#pragma unroll 2
+        for (int it = 0; it < nit; ++it) {
+            const uint4 v = q[it * 64];
+            f(v.x); f(v.y); f(v.z); f(v.w);
+        }
+    }
+};
+// MemberKeys: entry 64 m + lane for the set bits m of the lane's mask.
+struct MemberKeys {
+    const uint32_t *kv;
+    int nslots;
+    uint64_t mem;
+    template <class F>
+    __device__ __forceinline__ void for_each(F f) const
+    {
+        const int lane = threadIdx.x & 63;
+        for (int m = 0; m < nslots; ++m)
+            if ((mem >> m) & 1) f(kv[m * 64 + lane]);
+    }
+};
+
+// Radix descent, eight bits at a time from the top, for up to two ranks at once (want[t] = rank t wanted) over the
+// keys of `keys`; while both ranks follow the same prefix one histogram serves both.  hist: two histograms of 256
+// counters and, from spare_at on, a spare word per lane, private to the wave.  Requires 1 <= k[t] <= number of keys.
+template <class Keys>
+__device__ __forceinline__ void radix_cuts(const Keys keys, const int (&k)[2], const bool (&want)[2],
+                                           uint32_t *hist, Cut (&cut)[2], bool probe = false, uint32_t spare_at = 512u)
+{
+    const int lane = threadIdx.x & 63;
+    int pass_ = 0;
+    (void)pass_; (void)probe;
+    uint32_t prefix[2] = {0u, 0u};
+    int kk[2] = {k[0], k[1]};
+    bool act[2] = {want[0], want[1]};
+    const uint32_t spare = spare_at + lane;           // (a caller that asks for one rank only needs one histogram: spare_at = 256)
+    for (int shift = 24; shift >= 0 && (act[0] || act[1]); shift -= 8) {
+        const bool both = act[0] && act[1], two = both && prefix[0] != prefix[1];
+        wave_lds_sync();
+        *(uint4 *)(hist + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
+        if (two) *(uint4 *)(hist + 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
+        wave_lds_sync();
+        const uint32_t pf0 = prefix[act[0] ? 0 : 1], pf1 = prefix[1];   // the first histogram counts for the first active rank
+        SLA_ST(probe && pass_ < 4, 4 + 3 * pass_);
+        if (shift == 24) {                                   // no prefix yet: every key counts (both ranks, one histogram)
+            keys.for_each([&](uint32_t v) { atomicAdd(&hist[v >> 24], 1u); });
+        } else if (!two) {
+            keys.for_each([&](uint32_t v) {
+                const uint32_t d = (v >> shift) & 255u;
+                atomicAdd(&hist[(v >> (shift + 8)) == pf0 ? d : spare], 1u);
+            });
+        } else {
+            keys.for_each([&](uint32_t v) {
+                const uint32_t p = v >> (shift + 8), d = (v >> shift) & 255u;
+                atomicAdd(&hist[p == pf0 ? d : spare], 1u);
+                atomicAdd(&hist[p == pf1 ? 256u + d : spare], 1u);
+            });
+        }
+        wave_lds_sync();
+        SLA_ST(probe && pass_ < 4, 5 + 3 * pass_);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            if (!act[t]) continue;
+            const uint32_t *h = hist + ((t == 1 && two) ? 256 : 0);
+            const uint4 c4 = *(const uint4 *)(h + lane * 4);
+            const uint32_t c[4] = {c4.x, c4.y, c4.z, c4.w};
+            const uint32_t mine = c[0] + c[1] + c[2] + c[3];
+            const uint32_t incl = wave_incl_scan(mine), excl = incl - mine;
+            const bool here = excl < (uint32_t)kk[t] && (uint32_t)kk[t] <= incl;
+            const int src = __ffsll((long long)__ballot(here)) - 1;          // exactly one lane
+            uint32_t before = excl, digit = 0, cnt = 0;
+            if (here) {
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    if (cnt == 0) {
+                        if (before + c[b] >= (uint32_t)kk[t]) { digit = lane * 4 + b; cnt = c[b]; }
+                        else before += c[b];
+                    }
+                }
+            }
+            digit = bcast_u32(digit, src);
+            before = bcast_u32(before, src);
+            cnt = bcast_u32(cnt, src);
+            prefix[t] = (prefix[t] << 8) | digit;
+            kk[t] -= (int)before;
+            if (shift == 0) { cut[t] = Cut{prefix[t], kk[t], (int)cnt}; act[t] = false; }
+            else if (cnt == 1) {
+                // one key carries this prefix: the largest value with the prefix cuts the keys where that key does
+                cut[t] = Cut{(prefix[t] << shift) | ((1u << shift) - 1u), 1, 1};
+                act[t] = false;
+            }
+        }
+        SLA_ST(probe && pass_ < 4, 6 + 3 * pass_);
+        ++pass_;
+    }
+}
+
+// RegKeys: KPL values per lane, in registers (short rows).
+template <int KPL>
+struct RegKeys {
+    const uint32_t (&w)[KPL];
+    template <class F>
+    __device__ __forceinline__ void for_each(F f) const
+    {
+#pragma unroll
+        for (int m = 0; m < KPL; ++m) f(w[m]);
+    }
+};
+
 // Finds (T, r): the k smallest (key, index) pairs of the row are exactly the keys < T plus the
 // r lowest-index keys == T.  Requires 1 <= k <= Nkb.  Uniform across the wave.  hist: 256 counters private
 // to this wave (LDS operations of one wave execute in order, so no workgroup barrier is involved).
@@ -469,17 +606,37 @@ __device__ __forceinline__ void classify_row_wave(uint64_t (&key)[KPL], long row
             if (m * 64 + lane < Nkb) Pc[row * Nkb + m * 64 + lane] = e[m] * inv;
     }
 
-    // shift keys into the row's range so the leading radix digits discriminate
-    const uint64_t range = kmax - kmin;
-    const int sh = range ? __clzll((long long)range) : 0;
-#pragma unroll
-    for (int m = 0; m < KPL; ++m) key[m] = (key[m] - kmin) << sh;   // invalid slots are never read
-
+    // Both ranks are first looked for among 32-bit values w = floor((s_max - s) 2^32 / (s_max - s_min)), which spread a
+    // row like its logits (the keys' own leading digits are sign and exponent: nearly every key of a row in one bin).
+    // w is a non-increasing function of the logit, so where the group at a threshold is taken whole (nearly always one
+    // key) the cut of w is the cut of the exact order.  Otherwise the exact keys are ranked as before.
     const int k_keep = Nkb - k_n;          // first k_keep of the order are not negligible
+    const bool want[2] = {k_c > 0 && k_c < Nkb, k_keep > 0 && k_keep < Nkb};
+    uint32_t w[KPL];
+    {
+        const double s_max = key_to_logit(kmin), s_min = key_to_logit(kmax);
+        const double span = s_max - s_min, scale = span > 0.0 ? 4294967040.0 / span : 0.0;   // 2^32 - 2^8: below the padding value
+#pragma unroll
+        for (int m = 0; m < KPL; ++m) w[m] = (m * 64 + lane < Nkb) ? (uint32_t)((s_max - key_to_logit(key[m])) * scale) : ~0u;
+    }
+    // (one rank per descent: a single histogram, so that four workgroups of the fused kernel still fit a CU's LDS)
+    Cut cut[2] = {Cut{0u, 0, 0}, Cut{0u, 0, 0}}, c1[2];
+    const bool one[2] = {true, false};
+    if (want[0]) { const int k1[2] = {k_c, 0}; radix_cuts(RegKeys<KPL>{w}, k1, one, hist, c1, false, 256u); cut[0] = c1[0]; }
+    if (want[1]) { const int k1[2] = {k_keep, 0}; radix_cuts(RegKeys<KPL>{w}, k1, one, hist, c1, false, 256u); cut[1] = c1[0]; }
+    const bool whole = (!want[0] || cut[0].r == cut[0].n) && (!want[1] || cut[1].r == cut[1].n);
+
     uint64_t Tc = 0, Tn = 0;
     int rc = 0, rn = 0;
-    if (k_c > 0 && k_c < Nkb) radix_select<KPL>(key, Nkb, k_c, hist, Tc, rc);
-    if (k_keep > 0 && k_keep < Nkb) radix_select<KPL>(key, Nkb, k_keep, hist, Tn, rn);
+    if (!whole) {
+        // shift keys into the row's range so the leading radix digits discriminate
+        const uint64_t range = kmax - kmin;
+        const int sh = range ? __clzll((long long)range) : 0;
+#pragma unroll
+        for (int m = 0; m < KPL; ++m) key[m] = (key[m] - kmin) << sh;   // invalid slots are never read
+        if (want[0]) radix_select<KPL>(key, Nkb, k_c, hist, Tc, rc);
+        if (want[1]) radix_select<KPL>(key, Nkb, k_keep, hist, Tn, rn);
+    }
 
     int tie_c = 0, tie_n = 0, ncrit = 0;
     const uint64_t lt = (1ull << lane) - 1;
@@ -490,6 +647,7 @@ __device__ __forceinline__ void classify_row_wave(uint64_t (&key)[KPL], long row
         bool selc, seln;
         if (k_c <= 0) selc = false;
         else if (k_c >= Nkb) selc = valid;
+        else if (whole) selc = valid && w[m] <= cut[0].T;
         else {
             const bool eq = valid && key[m] == Tc;
             const uint64_t b = __ballot(eq);
@@ -498,6 +656,7 @@ __device__ __forceinline__ void classify_row_wave(uint64_t (&key)[KPL], long row
         }
         if (k_keep <= 0) seln = false;
         else if (k_keep >= Nkb) seln = valid;
+        else if (whole) seln = valid && w[m] <= cut[1].T;
         else {
             const bool eq = valid && key[m] == Tn;
             const uint64_t b = __ballot(eq);
@@ -523,7 +682,7 @@ __global__ __launch_bounds__(64) void select_kernel(const double *__restrict__ S
                                                     int8_t *__restrict__ lab_dense, int32_t *__restrict__ crit_idx,
                                                     float *__restrict__ Pc, double *__restrict__ S_dense, float sm_scale)
 {
-    __shared__ uint32_t hist[256];
+    __shared__ __align__(16) uint32_t hist[256 + 64];     // a histogram and a spare word per lane
     const long row = blockIdx.x;
     const int lane = threadIdx.x;
     const double *s = S + row * pitch;
@@ -559,7 +718,7 @@ __global__ __launch_bounds__(256) void classify_fused_kernel(const void *__restr
     constexpr int kPitch = 66;             // doubles per row of the K-mean buffer: 16-byte aligned rows, and the
                                            // sixteen lanes of one 16-byte access pass cover all 64 banks once
     __shared__ __align__(16) double ks[64 * kPitch];
-    __shared__ uint32_t hist[4][256];
+    __shared__ __align__(16) uint32_t hist[4][256 + 64];   // per wave: a histogram and a spare word per lane
     // every kernel argument is fetched here, in one batch of scalar loads (left to the compiler: a dozen round trips to the
     // scalar cache, each in front of the first use of an argument)
     asm volatile("" ::"s"(Q), "s"(sQ), "s"(rm.bs), "s"(rm.hs), "s"(rm.ts), "s"(rm.H), "s"(kbar), "s"(N), "s"(bq), "s"(Nqb), "s"(Nkb), "s"(k_c), "s"(k_n),
@@ -977,131 +1136,6 @@ __device__ __forceinline__ uint32_t wave_minmax_u32(uint32_t v)
     v = step(v, dpp_get<kBc15, 0xa>(v, v));
     v = step(v, dpp_get<kBc31, 0xc>(v, v));
     return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
-}
-
-#ifdef SLA_PROBE_TIME   /* timing probe only: cycle counter of one row's wave at the phase boundaries of the selection */
-__device__ unsigned long long sla_select_probe_times[32];
-__device__ int sla_select_probe_on;                      // set by the probed wave for the helpers it calls
-#define SLA_ST(on, pt) do { if (on) { const unsigned long long t_ = __builtin_readcyclecounter(); if ((threadIdx.x & 63) == 0) sla_select_probe_times[pt] = t_; } } while (0)
-extern "C" int sla_probe_read_select(unsigned long long *dst) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(sla_select_probe_times), sizeof(unsigned long long) * 32); }
-#else
-#define SLA_ST(on, pt)
-#endif
-
-// (T, r, n): the k smallest (value, index) pairs among the candidates are the candidates with value < T plus the r
-// lowest-index ones of the n candidates with value == T, or, if r == n == 1, the candidates with value <= T (T is then
-// an upper bound of the one key at the threshold, below the next key, rather than that key itself).
-struct Cut { uint32_t T; int r, n; };
-
-// The row's keys live in LDS (kv[j] = key of block j) and every pass over them is a rolled loop.  (Held in registers
-// with the loops unrolled the kernel was 18 000 instructions of straight-line code and, with 34 keys per lane, spilled.)
-// The kernel is bound by instruction issue -- about three waves per SIMD, each instruction of a wave taking the SIMD
-// some six cycles -- so the passes are written for few instructions per key: sixteen bytes per LDS read where the
-// order of the keys does not matter, no predicated atomics (a key that does not count adds to a spare word of its
-// lane instead, which costs one select where masking the lane out costs four scalar instructions).
-
-// The keys a radix descent looks at.  AllKeys: every entry of kv[0, 256 nit), four consecutive ones per lane and trip.
-struct AllKeys {
-    const uint32_t *kv;
-    int nit;
-    template <class F>
-    __device__ __forceinline__ void for_each(F f) const
-    {
-        const uint4 *q = (const uint4 *)kv + (threadIdx.x & 63);
-#pragma unroll 2
-        for (int it = 0; it < nit; ++it) {
-            const uint4 v = q[it * 64];
-            f(v.x); f(v.y); f(v.z); f(v.w);
-        }
-    }
-};
-// MemberKeys: entry 64 m + lane for the set bits m of the lane's mask.
-struct MemberKeys {
-    const uint32_t *kv;
-    int nslots;
-    uint64_t mem;
-    template <class F>
-    __device__ __forceinline__ void for_each(F f) const
-    {
-        const int lane = threadIdx.x & 63;
-        for (int m = 0; m < nslots; ++m)
-            if ((mem >> m) & 1) f(kv[m * 64 + lane]);
-    }
-};
-
-// Radix descent, eight bits at a time from the top, for up to two ranks at once (want[t] = rank t wanted) over the
-// keys of `keys`; while both ranks follow the same prefix one histogram serves both.  hist: two histograms of 256
-// counters and a spare word per lane, private to the wave.  Requires 1 <= k[t] <= number of keys.
-template <class Keys>
-__device__ __forceinline__ void radix_cuts(const Keys keys, const int (&k)[2], const bool (&want)[2],
-                                           uint32_t *hist, Cut (&cut)[2], bool probe = false)
-{
-    const int lane = threadIdx.x & 63;
-    int pass_ = 0;
-    (void)pass_; (void)probe;
-    uint32_t prefix[2] = {0u, 0u};
-    int kk[2] = {k[0], k[1]};
-    bool act[2] = {want[0], want[1]};
-    const uint32_t spare = 512u + lane;
-    for (int shift = 24; shift >= 0 && (act[0] || act[1]); shift -= 8) {
-        const bool both = act[0] && act[1], two = both && prefix[0] != prefix[1];
-        wave_lds_sync();
-        *(uint4 *)(hist + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
-        if (two) *(uint4 *)(hist + 256 + lane * 4) = make_uint4(0u, 0u, 0u, 0u);
-        wave_lds_sync();
-        const uint32_t pf0 = prefix[act[0] ? 0 : 1], pf1 = prefix[1];   // the first histogram counts for the first active rank
-        SLA_ST(probe && pass_ < 4, 4 + 3 * pass_);
-        if (shift == 24) {                                   // no prefix yet: every key counts (both ranks, one histogram)
-            keys.for_each([&](uint32_t v) { atomicAdd(&hist[v >> 24], 1u); });
-        } else if (!two) {
-            keys.for_each([&](uint32_t v) {
-                const uint32_t d = (v >> shift) & 255u;
-                atomicAdd(&hist[(v >> (shift + 8)) == pf0 ? d : spare], 1u);
-            });
-        } else {
-            keys.for_each([&](uint32_t v) {
-                const uint32_t p = v >> (shift + 8), d = (v >> shift) & 255u;
-                atomicAdd(&hist[p == pf0 ? d : spare], 1u);
-                atomicAdd(&hist[p == pf1 ? 256u + d : spare], 1u);
-            });
-        }
-        wave_lds_sync();
-        SLA_ST(probe && pass_ < 4, 5 + 3 * pass_);
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            if (!act[t]) continue;
-            const uint32_t *h = hist + ((t == 1 && two) ? 256 : 0);
-            const uint4 c4 = *(const uint4 *)(h + lane * 4);
-            const uint32_t c[4] = {c4.x, c4.y, c4.z, c4.w};
-            const uint32_t mine = c[0] + c[1] + c[2] + c[3];
-            const uint32_t incl = wave_incl_scan(mine), excl = incl - mine;
-            const bool here = excl < (uint32_t)kk[t] && (uint32_t)kk[t] <= incl;
-            const int src = __ffsll((long long)__ballot(here)) - 1;          // exactly one lane
-            uint32_t before = excl, digit = 0, cnt = 0;
-            if (here) {
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    if (cnt == 0) {
-                        if (before + c[b] >= (uint32_t)kk[t]) { digit = lane * 4 + b; cnt = c[b]; }
-                        else before += c[b];
-                    }
-                }
-            }
-            digit = bcast_u32(digit, src);
-            before = bcast_u32(before, src);
-            cnt = bcast_u32(cnt, src);
-            prefix[t] = (prefix[t] << 8) | digit;
-            kk[t] -= (int)before;
-            if (shift == 0) { cut[t] = Cut{prefix[t], kk[t], (int)cnt}; act[t] = false; }
-            else if (cnt == 1) {
-                // one key carries this prefix: the largest value with the prefix cuts the keys where that key does
-                cut[t] = Cut{(prefix[t] << shift) | ((1u << shift) - 1u), 1, 1};
-                act[t] = false;
-            }
-        }
-        SLA_ST(probe && pass_ < 4, 6 + 3 * pass_);
-        ++pass_;
-    }
 }
 
 // Per-lane bit mask (bit m = slot m) of the k first slots in the order (exact 64-bit key ascending, index ascending),

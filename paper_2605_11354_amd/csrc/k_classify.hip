@@ -1105,11 +1105,11 @@ hipError_t launch_classify_fused(const void *Q, const float *sQ, bool fp8, RowMa
 // ---- long rows without the fp64 round trip (Nkb > 256, no logits or block-score softmax asked for) ------------
 // The classifier needs the ORDER of a row's logits, not their values, and the order is almost always decided by
 // the leading bits.  So the logits go to memory as 32-bit keys -- the upper half of the order-preserving 64-bit
-// key of the fp64 logit: sign, exponent and 20 bits of mantissa -- and the selection runs on those: one register
-// and one instruction per key and step instead of two or more.  Where a threshold falls inside a group of equal
-// 32-bit keys and the group is not taken as a whole, the members' logits are evaluated again (the same 64-step
-// fma chain, so the same bits) and the lower halves of their keys decide, then the block index: the labels are
-// those of the full fp64 order, bit for bit.
+// key of the fp64 logit: sign, exponent and 20 bits of mantissa -- and the selection runs on those (on a linear
+// spread of the values they stand for, see select_keys_kernel): one 32-bit word per key.  Where a threshold falls
+// inside a group the 32-bit values do not separate and the group is not taken as a whole, the members' logits are
+// evaluated again (the same 64-step fma chain, so the same bits) and their exact keys decide, then the block
+// index: the labels are those of the full fp64 order, bit for bit.
 
 hipError_t launch_score_keys(const double *qbar, const double *kbar, int BH, int Nqb, int Nkb, int pitch, uint32_t *keys,
                              hipStream_t st)

@@ -96,7 +96,7 @@ def probe_select_report(L: ctypes.CDLL, nkb: int) -> None:
     if L.sla_probe_read_select(buf) != 0:
         raise RuntimeError("sla_probe_read_select failed")
     t = [int(x) for x in buf]
-    out = ["load keys + min/max %d" % (t[1] - t[0]), "shift %d" % (t[2] - t[1])]
+    out = ["load keys + min/max %d" % (t[1] - t[0]), "spread over the row's range %d" % (t[2] - t[1])]
     last = t[2]
     for p in range(4):
         a, b, c = t[4 + 3 * p], t[5 + 3 * p], t[6 + 3 * p]

@@ -1160,18 +1160,32 @@ __device__ __forceinline__ uint64_t take_first(uint32_t *kv, int nslots, const C
         if (v == T && m * 64 + lane < Nkb) mem |= 1ull << m;
         else if (v < T) bits |= 1ull << m;
     }
-    // the half `lower` of the exact keys of the slots in `who` -> kv
+    // The half `lower` of the exact keys of the slots in `who` -> kv.  One row with a group to resolve is on the
+    // kernel's critical path (the other rows are long done), so the 64-step chain is fed from LDS (the Q mean, staged
+    // once per call in the histogram's place) and from registers loaded eight channels at a time (more would cost the
+    // whole kernel occupancy): eight memory round trips per member, each of four 16-byte loads.
     auto exact_halves = [&](uint64_t who, bool lower) {
+        double *qs = (double *)hist;
+        wave_lds_sync();
+        qs[lane] = q[lane];
+        wave_lds_sync();
         for (int m = 0; m < nslots; ++m) {
             if (!((who >> m) & 1)) continue;
             const int j = m * 64 + lane;
             const double *kr = kh + (long)j * kD;
             double s = 0.0;
-#pragma unroll 4
-            for (int d = 0; d < kD; ++d) s = fma(q[d], kr[d], s);
+#pragma unroll 1
+            for (int c = 0; c < kD; c += 8) {
+                double kk[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) kk[e] = kr[c + e];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s = fma(qs[c + e], kk[e], s);
+            }
             const uint64_t key = desc_key(s);
             kv[j] = lower ? (uint32_t)key : (uint32_t)(key >> 32);
         }
+        wave_lds_sync();
     };
     const uint64_t lt = (1ull << lane) - 1;
     const bool w2[2] = {true, false};

@@ -1188,6 +1188,56 @@ __device__ __forceinline__ uint64_t take_first(uint32_t *kv, int nslots, const C
         wave_lds_sync();
     };
     const uint64_t lt = (1ull << lane) - 1;
+    if (cut.n <= 64) {
+        // A small group (nearly always two or three blocks): the members' exact keys go to LDS in index order, lane t
+        // counts the members in front of member t, and the first r are taken.  (The radix descents below are for large
+        // groups: runs of equal blocks.)
+        double *qs = (double *)hist;                        // words 0..127: the Q mean; 128..255: keys; 256..319: taken or not
+        uint64_t *xk = (uint64_t *)(hist + 128);
+        uint32_t *taken = hist + 256;
+        wave_lds_sync();
+        qs[lane] = q[lane];
+        wave_lds_sync();
+        int n = 0;
+        for (int m = 0; m < nslots; ++m) {
+            const bool in = (mem >> m) & 1;
+            const uint64_t b = __ballot(in);
+            if (!b) continue;
+            if (in) {
+                const double *kr = kh + (long)(m * 64 + lane) * kD;
+                double s = 0.0;
+#pragma unroll 1
+                for (int c = 0; c < kD; c += 8) {
+                    double kk[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) kk[e] = kr[c + e];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) s = fma(qs[c + e], kk[e], s);
+                }
+                xk[n + (int)__popcll(b & lt)] = desc_key(s);
+            }
+            n += __popcll(b);
+        }
+        wave_lds_sync();
+        const uint64_t mine = lane < n ? xk[lane] : 0;
+        int ahead = 0;
+        for (int u = 0; u < n; ++u) {
+            const uint64_t other = xk[u];
+            ahead += (other < mine || (other == mine && u < lane)) ? 1 : 0;
+        }
+        taken[lane] = (lane < n && ahead < cut.r) ? 1u : 0u;
+        wave_lds_sync();
+        n = 0;
+        for (int m = 0; m < nslots; ++m) {
+            const bool in = (mem >> m) & 1;
+            const uint64_t b = __ballot(in);
+            if (!b) continue;
+            if (in && taken[n + (int)__popcll(b & lt)]) bits |= 1ull << m;
+            n += __popcll(b);
+        }
+        wave_lds_sync();
+        return bits;
+    }
     const bool w2[2] = {true, false};
     uint64_t who = mem;                                     // the slots still tied
     int need = cut.r;                                       // how many of them to take

@@ -123,11 +123,15 @@ __device__ __forceinline__ uint64_t desc_key(double s);
 // KEYS: instead of the logits, store the upper halves of their order-preserving keys (uint32 [rows, pitch], pitch in
 // keys): all the long-row classifier needs unless a threshold cuts through a group of equal upper halves.
 template <bool KEYS>
-__global__ __launch_bounds__(256) void scores_kernel(const double *__restrict__ qbar, const double *__restrict__ kbar,
-                                                     int Nqb, int Nkb, int pitch, double *__restrict__ S)
+__global__ __launch_bounds__(256, 5) void scores_kernel(const double *__restrict__ qbar, const double *__restrict__ kbar,
+                                                        int Nqb, int Nkb, int pitch, double *__restrict__ S)
 {
-    __shared__ double qs[32][66];
-    __shared__ double ks[32][66];
+    // Channels in four quarters of sixteen through one LDS buffer of 17 KB, and at most 102 registers: five workgroups
+    // per CU, so that the 1056 tiles of a 16-head launch of 344 x 687 blocks are resident at once.  (Halves of 32
+    // channels, 34 KB and four workgroups per CU, measured the same on that launch.)
+    constexpr int QC = 16;
+    __shared__ double qs[QC][66];
+    __shared__ double ks[QC][66];
     const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
     const int j0 = blockIdx.x * 64, i0 = blockIdx.y * 64;
     const long bh = blockIdx.z;
@@ -139,29 +143,33 @@ __global__ __launch_bounds__(256) void scores_kernel(const double *__restrict__ 
 #pragma unroll
         for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
 
-    // both channel halves are requested up front (row indices clamped, so the loads are unconditional and the
-    // second half stays in flight while the first is staged and consumed)
-    double qr[2][8], kr[2][8];
+    // element r of a thread in a quarter: channel (tid & 15) of row (tid >> 4) + 16 r (row indices clamped, so the
+    // loads are unconditional); the next quarter is requested before the present one is consumed
+    const int sd = tid & 15, srow = tid >> 4;
+    const double *qsrc[4], *ksrc[4];
 #pragma unroll
-    for (int dh = 0; dh < 2; ++dh)
+    for (int r = 0; r < 4; ++r) {
+        qsrc[r] = qh + (long)min(i0 + srow + 16 * r, Nqb - 1) * kD + sd;
+        ksrc[r] = kh + (long)min(j0 + srow + 16 * r, Nkb - 1) * kD + sd;
+    }
+    double qr[4], kr[4];
+    auto fetch = [&](int c) {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int idx = tid + 256 * r, row = idx >> 5, d = idx & 31;
-            qr[dh][r] = qh[(long)min(i0 + row, Nqb - 1) * kD + dh * 32 + d];
-            kr[dh][r] = kh[(long)min(j0 + row, Nkb - 1) * kD + dh * 32 + d];
+        for (int r = 0; r < 4; ++r) { qr[r] = qsrc[r][c * QC]; kr[r] = ksrc[r][c * QC]; }
+    };
+    fetch(0);
+#pragma unroll
+    for (int c = 0; c < kD / QC; ++c) {
+        if (c) lds_barrier();              // the quarter before is consumed
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {      // rows past the end repeat the last one; their results are not stored
+            qs[sd][srow + 16 * r] = qr[r];
+            ks[sd][srow + 16 * r] = kr[r];
         }
-#pragma unroll
-    for (int dh = 0; dh < 2; ++dh) {
-        if (dh) lds_barrier();             // first half consumed; the loads of the second stay in flight
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int idx = tid + 256 * r, row = idx >> 5, d = idx & 31;
-            qs[d][row] = qr[dh][r];        // rows past the end repeat the last one; their results are not stored
-            ks[d][row] = kr[dh][r];
-        }
+        if (c + 1 < kD / QC) fetch(c + 1);
         lds_barrier();
 #pragma unroll 4
-        for (int d = 0; d < 32; ++d) {
+        for (int d = 0; d < QC; ++d) {
             double qv[4], kv[4];
 #pragma unroll
             for (int a = 0; a < 4; ++a) { qv[a] = qs[d][ty * 4 + a]; kv[a] = ks[d][tx * 4 + a]; }

@@ -19,7 +19,8 @@ def _bf16(x):
 
 def _variants(cfg, d):
     """plain; groups of four key blocks whose means differ by far less than 2^-20 relative (two of them exactly equal);
-    a run of all-zero key blocks (logit exactly 0: a large group of exact ties in the middle of the order); Q = 0 (all tie)."""
+    a run of all-zero key blocks (logit exactly 0: a large group of exact ties in the middle of the order); Q = 0 (all tie);
+    runs of blocks with tiny distinct logits (below)."""
     yield "plain", d
     K = d["K"].copy()
     nkb = cfg.N // 64                                         # whole blocks only
@@ -38,6 +39,19 @@ def _variants(cfg, d):
     K[:, :, 40 * 64:(40 + nkb // 3) * 64] = 0
     yield "zero_run", dict(d, K=K)
     yield "all_tie", dict(d, Q=np.zeros_like(d["Q"]))
+    # a run of key blocks with tiny, distinct logits (one non-zero element of 2^-(40 + j mod 30), alternating sign): next to
+    # the row's range they are all one value, but their keys differ in sign and exponent -- a tied group of the ranked
+    # 32-bit values whose members are told apart by the upper halves of their exact keys, some pairs only by the index
+    K = d["K"].copy()
+    for t, j in enumerate(range(40, 40 + nkb // 3)):
+        K[:, :, j * 64:(j + 1) * 64] = 0
+        K[:, :, j * 64, 3] = _bf16((-1.0) ** t * 2.0 ** -(40 + t % 30))
+    yield "tiny_run", dict(d, K=K)
+    K = d["K"].copy()                                          # the same with a short run (a group of at most 64 blocks)
+    for t, j in enumerate(range(40, 40 + min(40, nkb // 4))):
+        K[:, :, j * 64:(j + 1) * 64] = 0
+        K[:, :, j * 64, 3] = _bf16((-1.0) ** t * 2.0 ** -(40 + t % 13))
+    yield "tiny_short_run", dict(d, K=K)
 
 
 @pytest.mark.parametrize("nkb,bq,kc,kn", [(300, 64, 15, 200), (300, 128, 1, 299), (300, 64, 299, 1), (300, 64, 0, 150), (300, 64, 7, 0),
@@ -73,3 +87,20 @@ def test_key_classifier_e4m3_inputs(oracle):
     got = case.classify(want=("crit_idx",))
     ref = case.oracle_classify(oracle)
     assert np.array_equal(got["labels"], ref["labels"])
+
+
+@pytest.mark.parametrize("nkb,kc,kn", [(100, 5, 60), (100, 40, 30), (250, 12, 150), (250, 60, 100)])
+def test_short_rows_with_tied_groups(oracle, nkb, kc, kn):
+    """Rows of at most 256 key blocks (the fused classifier) look for both ranks among the same 32-bit spread of the logits
+    and fall back to the exact keys where a group is not taken whole: the same variants as above."""
+    cfg = C0.with_(H=2, N=nkb * 64 - 17, bq=64, n_clusters=64)
+    d = synth.make_inputs(cfg)
+    for name, dd in _variants(cfg, d):
+        case = G.Case(cfg, dd, k_crit=kc, k_neg=kn)
+        got = case.classify(want=("crit_idx",))
+        ref = case.oracle_classify(oracle)
+        assert np.array_equal(got["labels"], ref["labels"]), name
+        for idx in np.ndindex(got["labels"].shape[:3]):
+            assert np.array_equal(got["crit_idx"][idx], np.nonzero(ref["labels"][idx] == 2)[0]), (name, idx)
+        O1, lab1 = case.forward()
+        assert np.array_equal(lab1.cpu().numpy(), ref["labels"]), name
